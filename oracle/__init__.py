@@ -1,0 +1,133 @@
+"""CPU fp64 oracle for the transpose convolution of arxiv 2209.03704.
+
+TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the CPU-baseline
+leg of the benchmark may import this package; the product never does.  The
+arithmetic lives in ``kst_oracle.c`` (plain C, literal zero-embedding of
+Section 1 followed by the correlation of Eq. 1); this module only compiles it
+with gcc, loads it with ctypes and marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kst_oracle.c")
+_LIB = os.path.join(_HERE, "libkst_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            dp = ctypes.POINTER(ctypes.c_double)
+            ip = ctypes.POINTER(ctypes.c_int32)
+            lib.kst_oracle_out_size.argtypes = [ctypes.c_int] * 3
+            lib.kst_oracle_out_size.restype = ctypes.c_int
+            lib.kst_oracle_threads.argtypes = []
+            lib.kst_oracle_threads.restype = ctypes.c_int
+            lib.kst_oracle_forward.argtypes = [dp, dp, dp] + [ctypes.c_int] * 6
+            lib.kst_oracle_forward.restype = ctypes.c_int
+            lib.kst_oracle_forward_planes.argtypes = (
+                [dp, dp, dp, ip, ip, ctypes.c_int] + [ctypes.c_int] * 6)
+            lib.kst_oracle_forward_planes.restype = ctypes.c_int
+            lib.kst_oracle_conventional_ops.argtypes = (
+                [ctypes.c_int] * 5 + [ctypes.POINTER(ctypes.c_int64)] * 2)
+            lib.kst_oracle_conventional_ops.restype = None
+            _lib = lib
+    return _lib
+
+
+def _f64(a, shape_len):
+    a = np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+    if a.ndim != shape_len:
+        raise ValueError("expected %d dimensions, got %r" % (shape_len, a.shape))
+    return a
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def out_size(N: int, n: int, P: int = 0) -> int:
+    """Output edge (2N-1) + 2P - n + 1 (Section 1: 2N-n without padding)."""
+    return _load().kst_oracle_out_size(N, n, P)
+
+
+def threads() -> int:
+    return _load().kst_oracle_threads()
+
+
+def _dims(x, w):
+    B, Cin, N, N2 = x.shape
+    Cout, Cin2, n, n2 = w.shape
+    if N != N2 or n != n2 or Cin != Cin2:
+        raise ValueError("need square maps/kernels with matching Cin: %r %r" % (x.shape, w.shape))
+    return B, Cin, Cout, N, n
+
+
+def forward(x, w, P: int = 0) -> np.ndarray:
+    """out[B][Cout][M][M] in fp64 for x[B][Cin][N][N], w[Cout][Cin][n][n]."""
+    x = _f64(x, 4)
+    w = _f64(w, 4)
+    B, Cin, Cout, N, n = _dims(x, w)
+    lib = _load()
+    M = lib.kst_oracle_out_size(N, n, P)
+    if M < 1:
+        raise ValueError("kernel larger than the up-sampled map")
+    out = np.empty((B, Cout, M, M), dtype=np.float64)
+    rc = lib.kst_oracle_forward(_dptr(x), _dptr(w), _dptr(out), B, Cin, Cout, N, n, P)
+    if rc != 0:
+        raise RuntimeError("kst_oracle_forward failed (%d)" % rc)
+    return out
+
+
+def forward_planes(x, w, b_idx, co_idx, P: int = 0) -> np.ndarray:
+    """Complete output planes (b_idx[k], co_idx[k]) -> [K][M][M], same definition."""
+    x = _f64(x, 4)
+    w = _f64(w, 4)
+    B, Cin, Cout, N, n = _dims(x, w)
+    b_idx = np.ascontiguousarray(np.asarray(b_idx, dtype=np.int32))
+    co_idx = np.ascontiguousarray(np.asarray(co_idx, dtype=np.int32))
+    if b_idx.shape != co_idx.shape or b_idx.ndim != 1:
+        raise ValueError("b_idx and co_idx must be equal-length vectors")
+    lib = _load()
+    M = lib.kst_oracle_out_size(N, n, P)
+    if M < 1:
+        raise ValueError("kernel larger than the up-sampled map")
+    out = np.empty((b_idx.size, M, M), dtype=np.float64)
+    ip = ctypes.POINTER(ctypes.c_int32)
+    rc = lib.kst_oracle_forward_planes(
+        _dptr(x), _dptr(w), _dptr(out), b_idx.ctypes.data_as(ip), co_idx.ctypes.data_as(ip),
+        int(b_idx.size), B, Cin, Cout, N, n, P)
+    if rc != 0:
+        raise RuntimeError("kst_oracle_forward_planes failed (%d)" % rc)
+    return out
+
+
+def conventional_ops(Cin: int, Cout: int, N: int, n: int, P: int = 0):
+    """(multiplications, additions) of the conventional method, as Table 4 counts them."""
+    m = ctypes.c_int64()
+    a = ctypes.c_int64()
+    _load().kst_oracle_conventional_ops(Cin, Cout, N, n, P, ctypes.byref(m), ctypes.byref(a))
+    return m.value, a.value

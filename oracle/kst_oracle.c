@@ -1,0 +1,154 @@
+/*
+ * Oracle for the transpose convolution of arxiv 2209.03704 -- TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition that every GPU result is checked
+ * against.  It is not part of the product: only the test-suite, the smoke
+ * check and the CPU-baseline leg of the benchmark may call it.  It shares no
+ * code with the HIP library.
+ *
+ * What it computes (Section 1, second paragraph, and Eq. 1 of Section 2):
+ *
+ *   1. Up-sampling.  An N x N map becomes S x S with S = 2N-1 by embedding a
+ *      zero after every row and every column:
+ *          U[p][q] = in[p/2][q/2]  if p and q are both even, else 0.
+ *      With a padding factor P (Section 3.3 applies P = 2 in its figures; the
+ *      benchmark shapes use P = 0) a frame of P zeros is put around U, giving
+ *      Sp = S + 2P.
+ *   2. Stride-1 correlation with the n x n kernel (Eq. 1, read with 0-based
+ *      offsets u,v = 0..n-1, no kernel flip), summed over input channels:
+ *          out[b][co][y][x] = sum_ci sum_u sum_v  Upad[b][ci][y+u][x+v] * w[co][ci][u][v]
+ *      for 0 <= y,x < M,  M = Sp - n + 1  (= 2N - n when P = 0).
+ *
+ * U is really built and the zeros are really multiplied: there is no parity
+ * shortcut anywhere in this file.  All arithmetic is fp64.  Layouts are dense
+ * row-major: in[B][Cin][N][N], w[Cout][Cin][n][n], out[B][Cout][M][M].
+ *
+ * Parity pins (tests/test_oracle_pins.py): hand-worked 4x4 / 3x3 example of
+ * Fig. 2's shapes, all-ones and unit-impulse closed forms, n = 1 and n = 2
+ * degenerate cases, agreement with separately coded forms of Eqs. 7-10 and of
+ * the scatter (adjoint) form, linearity, the adjoint identity with a strided
+ * correlation, library conv routines on fp64, and the operation counts of
+ * Table 4.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Output edge length for input edge N, kernel edge n, padding factor P. */
+int kst_oracle_out_size(int N, int n, int P)
+{
+    return (2 * N - 1) + 2 * P - n + 1;
+}
+
+int kst_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Build the zero-embedded, zero-framed maps of one batch item: Upad[Cin][Sp][Sp]. */
+static void upsample_item(const double *in_b, double *Upad, int Cin, int N, int P)
+{
+    const int S = 2 * N - 1;
+    const int Sp = S + 2 * P;
+    memset(Upad, 0, (size_t)Cin * Sp * Sp * sizeof(double));
+    for (int ci = 0; ci < Cin; ++ci)
+        for (int a = 0; a < N; ++a)
+            for (int b = 0; b < N; ++b)
+                Upad[((size_t)ci * Sp + (P + 2 * a)) * Sp + (P + 2 * b)] =
+                    in_b[((size_t)ci * N + a) * N + b];
+}
+
+/* Eq. 1 on the up-sampled maps, one output plane (one batch item, one co). */
+static void correlate_plane(const double *Upad, const double *w_co, double *out_plane,
+                            int Cin, int Sp, int n, int M)
+{
+    for (int y = 0; y < M; ++y)
+        for (int x = 0; x < M; ++x) {
+            double acc = 0.0;
+            for (int ci = 0; ci < Cin; ++ci)
+                for (int u = 0; u < n; ++u)
+                    for (int v = 0; v < n; ++v)
+                        acc += Upad[((size_t)ci * Sp + (y + u)) * Sp + (x + v)] *
+                               w_co[((size_t)ci * n + u) * n + v];
+            out_plane[(size_t)y * M + x] = acc;
+        }
+}
+
+/*
+ * Full forward.  Returns 0, or 1 for an illegal shape / failed allocation.
+ * out must hold B*Cout*M*M doubles.
+ */
+int kst_oracle_forward(const double *in, const double *w, double *out,
+                       int B, int Cin, int Cout, int N, int n, int P)
+{
+    if (B < 1 || Cin < 1 || Cout < 1 || N < 1 || n < 1 || P < 0) return 1;
+    const int M = kst_oracle_out_size(N, n, P);
+    if (M < 1) return 1;
+    const int Sp = 2 * N - 1 + 2 * P;
+    double *Upad = (double *)malloc((size_t)Cin * Sp * Sp * sizeof(double));
+    if (!Upad) return 1;
+    for (int b = 0; b < B; ++b) {
+        upsample_item(in + (size_t)b * Cin * N * N, Upad, Cin, N, P);
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int co = 0; co < Cout; ++co)
+            correlate_plane(Upad, w + (size_t)co * Cin * n * n,
+                            out + ((size_t)b * Cout + co) * M * M, Cin, Sp, n, M);
+    }
+    free(Upad);
+    return 0;
+}
+
+/*
+ * The same definition restricted to chosen output planes, for sizes where
+ * the whole tensor would take too long: plane k is (b_idx[k], co_idx[k]) and
+ * is written, complete, to out_planes[k][M][M].
+ */
+int kst_oracle_forward_planes(const double *in, const double *w, double *out_planes,
+                              const int32_t *b_idx, const int32_t *co_idx, int n_planes,
+                              int B, int Cin, int Cout, int N, int n, int P)
+{
+    if (B < 1 || Cin < 1 || Cout < 1 || N < 1 || n < 1 || P < 0 || n_planes < 0) return 1;
+    const int M = kst_oracle_out_size(N, n, P);
+    if (M < 1) return 1;
+    for (int k = 0; k < n_planes; ++k)
+        if (b_idx[k] < 0 || b_idx[k] >= B || co_idx[k] < 0 || co_idx[k] >= Cout) return 1;
+    const int Sp = 2 * N - 1 + 2 * P;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *Upad = (double *)malloc((size_t)Cin * Sp * Sp * sizeof(double));
+        if (!Upad) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int k = 0; k < n_planes; ++k) {
+            if (!Upad) continue;
+            upsample_item(in + (size_t)b_idx[k] * Cin * N * N, Upad, Cin, N, P);
+            correlate_plane(Upad, w + (size_t)co_idx[k] * Cin * n * n,
+                            out_planes + (size_t)k * M * M, Cin, Sp, n, M);
+        }
+        free(Upad);
+    }
+    return fail;
+}
+
+/*
+ * Operation counts of the conventional method as Table 4 counts them: one
+ * multiplication per (output element, kernel element, ci, co), and one
+ * addition fewer than that per output element of each output channel.
+ */
+void kst_oracle_conventional_ops(int Cin, int Cout, int N, int n, int P,
+                                 int64_t *mults, int64_t *adds)
+{
+    const int64_t M = kst_oracle_out_size(N, n, P);
+    *mults = M * M * (int64_t)n * n * Cin * Cout;
+    *adds = *mults - M * M * Cout;
+}

@@ -1,0 +1,108 @@
+"""Seeded synthetic workloads: shapes and value distributions only.
+
+This module holds none of the method's arithmetic.  It is the one piece that
+both the HIP path's callers and the oracle's callers use, so that the two are
+fed identical bits.  The five named layers stand in for the workloads the
+paper measures (single- and three-channel image maps of Tables 1-2, GAN
+generator layers of Table 3) whose images and trained weights are not
+available; timing does not depend on the values.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+SEED_BASE = 220903704
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    B: int
+    Cin: int
+    Cout: int
+    N: int          # input map edge
+    n: int          # kernel edge
+    dtype: str      # "f32" | "bf16" (bf16 operands, fp32 accumulate and output)
+    in_dist: str    # "uniform" | "normal" | "relu_normal"
+    w_std: float = 0.02
+    P: int = 0      # padding factor on the up-sampled map
+
+    @property
+    def M(self) -> int:
+        """Output edge: (2N-1) + 2P - n + 1 (Section 1)."""
+        return 2 * self.N - 1 + 2 * self.P - self.n + 1
+
+    @property
+    def in_shape(self):
+        return (self.B, self.Cin, self.N, self.N)
+
+    @property
+    def w_shape(self):
+        return (self.Cout, self.Cin, self.n, self.n)
+
+    @property
+    def out_shape(self):
+        return (self.B, self.Cout, self.M, self.M)
+
+
+# The five benchmark layers, in the order the baseline lists them.
+LAYERS = (
+    Layer("cfg1_tiny_1ch", 1, 1, 1, 32, 3, "f32", "uniform"),
+    Layer("cfg2_1ch_bandwidth", 64, 1, 1, 512, 5, "f32", "normal"),
+    Layer("cfg3_gan_n4", 128, 512, 256, 16, 4, "f32", "relu_normal"),
+    Layer("cfg4_deep_n5", 64, 1024, 512, 8, 5, "f32", "relu_normal"),
+    Layer("cfg5_late_bf16", 32, 256, 128, 64, 3, "bf16", "relu_normal"),
+)
+
+
+def layer_by_name(name: str) -> Layer:
+    for i, l in enumerate(LAYERS):
+        if l.name == name or name in ("cfg%d" % (i + 1), str(i + 1)):
+            return l
+    raise KeyError(name)
+
+
+def layer_seed(layer: Layer) -> int:
+    for i, l in enumerate(LAYERS):
+        if l is layer or l == layer:
+            return SEED_BASE + i
+    return SEED_BASE + 1000
+
+
+def make_tensors(layer: Layer, seed: int | None = None):
+    """(x, w) as CPU torch tensors in the layer's operand dtype.
+
+    The input is drawn first, then the weights, from one seeded CPU generator.
+    For "bf16" the fp32 draws are rounded once, to nearest even, to bfloat16:
+    both the HIP path and the oracle consume those rounded bits.
+    """
+    g = torch.Generator(device="cpu")
+    g.manual_seed(layer_seed(layer) if seed is None else seed)
+    if layer.in_dist == "uniform":
+        x = torch.rand(layer.in_shape, generator=g, dtype=torch.float32) * 2.0 - 1.0
+    elif layer.in_dist == "normal":
+        x = torch.randn(layer.in_shape, generator=g, dtype=torch.float32)
+    elif layer.in_dist == "relu_normal":
+        x = torch.randn(layer.in_shape, generator=g, dtype=torch.float32).clamp_(min=0.0)
+    elif layer.in_dist == "integer":
+        x = torch.randint(-4, 5, layer.in_shape, generator=g).to(torch.float32)
+    else:
+        raise ValueError(layer.in_dist)
+    if layer.in_dist == "integer":
+        w = torch.randint(-3, 4, layer.w_shape, generator=g).to(torch.float32)
+    else:
+        w = torch.randn(layer.w_shape, generator=g, dtype=torch.float32) * layer.w_std
+    if layer.dtype == "bf16":
+        x = x.to(torch.bfloat16)
+        w = w.to(torch.bfloat16)
+    elif layer.dtype != "f32":
+        raise ValueError(layer.dtype)
+    return x.contiguous(), w.contiguous()
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of an fp32 / bf16 CPU tensor to a float64 numpy array."""
+    return t.detach().cpu().to(torch.float64).numpy()

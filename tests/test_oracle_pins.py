@@ -1,0 +1,328 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle (oracle/kst_oracle.c) is the literal definition: zero-embed, then
+Eq. 1.  It is pinned against things that are not itself: a hand-worked
+example, closed forms, separately coded forms of the same map (Eqs. 7-10 of
+Section 3.3, the scatter form), linear-algebra invariants, library
+convolutions in fp64, and the operation counts of Table 4.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_4x4.txt")
+
+
+# ----------------------------------------------------------------------------
+# Separately coded forms of the same linear map (test-local, pure Python/numpy)
+# ----------------------------------------------------------------------------
+def segregated_form(x, w):
+    """Eqs. 7-10 with the sub-kernels of Section 3.2, P = 0, written as loops.
+
+    K1..K4 take alternate rows/columns of K starting at (0,0), (0,1), (1,0),
+    (1,1); quad (i, j) produces out[2i+r][2j+s] from the un-upsampled input
+    shifted by (r, s).  Members of the last quad row/column that fall outside
+    the M x M output are discarded (Section 3.3, odd output sizes).
+    """
+    B, Cin, N, _ = x.shape
+    Cout, _, n, _ = w.shape
+    M = 2 * N - n
+    out = np.zeros((B, Cout, M, M))
+    sub = {(r, s): w[:, :, r::2, s::2] for r in (0, 1) for s in (0, 1)}
+    Q = (M + 1) // 2
+    for b in range(B):
+        for co in range(Cout):
+            for i in range(Q):
+                for j in range(Q):
+                    for (r, s), K in sub.items():
+                        y, xx = 2 * i + r, 2 * j + s
+                        if y >= M or xx >= M:
+                            continue
+                        acc = 0.0
+                        for ci in range(Cin):
+                            for u in range(K.shape[2]):
+                                for v in range(K.shape[3]):
+                                    acc += x[b, ci, i + r + u, j + s + v] * K[co, ci, u, v]
+                        out[b, co, y, xx] = acc
+    return out
+
+
+def scatter_form(x, w, P=0):
+    """Each input pixel (a, b) sits at (P+2a, P+2b) of the padded up-sampled map
+    and is seen by output (y, x) through kernel element (P+2a-y, P+2b-x)."""
+    B, Cin, N, _ = x.shape
+    Cout, _, n, _ = w.shape
+    M = 2 * N - 1 + 2 * P - n + 1
+    out = np.zeros((B, Cout, M, M))
+    for a in range(N):
+        for b in range(N):
+            for u in range(n):
+                for v in range(n):
+                    y, xx = P + 2 * a - u, P + 2 * b - v
+                    if 0 <= y < M and 0 <= xx < M:
+                        out[:, :, y, xx] += np.einsum("bi,oi->bo", x[:, :, a, b], w[:, :, u, v])
+    return out
+
+
+def rand_case(rng, B, Cin, Cout, N, n, integer=False):
+    if integer:
+        x = rng.integers(-5, 6, size=(B, Cin, N, N)).astype(np.float64)
+        w = rng.integers(-4, 5, size=(Cout, Cin, n, n)).astype(np.float64)
+    else:
+        x = rng.standard_normal((B, Cin, N, N))
+        w = rng.standard_normal((Cout, Cin, n, n))
+    return x, w
+
+
+def legal_small_shapes():
+    for n in range(1, 8):
+        nmin = n // 2 + 1          # smallest N with 2N - n >= 1
+        for N in (nmin, nmin + 1, nmin + 2, 6, 9):
+            if 2 * N - n >= 1:
+                yield N, n
+
+
+# ----------------------------------------------------------------------------
+# 1. Hand-worked example (shapes of Fig. 2 and Figs. 5-6)
+# ----------------------------------------------------------------------------
+def read_golden():
+    cases = {}
+    with open(GOLDEN) as f:
+        lines = [l.strip() for l in f if l.strip() and not l.startswith("#")]
+    k = 0
+    while k < len(lines):
+        tag, n, M = lines[k].split()
+        assert tag == "case"
+        n, M = int(n), int(M)
+        rows = [[int(t) for t in lines[k + 1 + r].split()] for r in range(M)]
+        cases[n] = np.array(rows, dtype=np.float64)
+        k += 1 + M
+    return cases
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5])
+def test_hand_example(n):
+    want = read_golden()[n]
+    x = np.arange(1, 17, dtype=np.float64).reshape(1, 1, 4, 4)
+    w = np.arange(1, n * n + 1, dtype=np.float64).reshape(1, 1, n, n)
+    got = oracle.forward(x, w)
+    assert got.shape == (1, 1, 8 - n, 8 - n)
+    assert np.array_equal(got[0, 0], want)
+
+
+# ----------------------------------------------------------------------------
+# 2. Closed forms
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N,n", [(5, 3), (6, 4), (7, 5), (4, 2), (9, 7)])
+def test_all_ones_gives_parity_sums(N, n):
+    """Fig. 3's four cases: with in == 1 an output at (y, x) adds exactly the
+    kernel elements whose row/column parity equals (y mod 2, x mod 2)."""
+    rng = np.random.default_rng(n)
+    w = rng.integers(-9, 10, size=(2, 3, n, n)).astype(np.float64)
+    x = np.ones((2, 3, N, N))
+    out = oracle.forward(x, w)
+    M = 2 * N - n
+    for r in (0, 1):
+        for s in (0, 1):
+            want = w[:, :, r::2, s::2].sum(axis=(1, 2, 3))     # per co
+            blk = out[:, :, r::2, s::2]
+            if blk.size:
+                assert np.array_equal(blk, np.broadcast_to(want[None, :, None, None], blk.shape))
+    assert out.shape == (2, 2, M, M)
+
+
+def test_unit_impulse_places_reversed_kernel():
+    """A single 1 at (a, b): out[y][x] = k[2a-y][2b-x] where that index exists."""
+    N, n, a, b = 6, 5, 3, 2
+    w = np.arange(1, n * n + 1, dtype=np.float64).reshape(1, 1, n, n)
+    x = np.zeros((1, 1, N, N))
+    x[0, 0, a, b] = 1.0
+    out = oracle.forward(x, w)[0, 0]
+    M = 2 * N - n
+    want = np.zeros((M, M))
+    for y in range(M):
+        for xx in range(M):
+            u, v = 2 * a - y, 2 * b - xx
+            if 0 <= u < n and 0 <= v < n:
+                want[y, xx] = w[0, 0, u, v]
+    assert np.array_equal(out, want)
+
+
+def test_n1_is_scaled_upsampling():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((2, 1, 5, 5))
+    w = np.array([[[[2.5]]]])
+    out = oracle.forward(x, w)
+    assert out.shape == (2, 1, 9, 9)
+    assert np.array_equal(out[:, :, ::2, ::2], 2.5 * x)
+    assert not out[:, :, 1::2, :].any() and not out[:, :, :, 1::2].any()
+
+
+def test_n2_is_outer_product_with_kernel():
+    """n = 2: every output quad is in[i][j] times the 2x2 kernel (Kronecker)."""
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((1, 1, 4, 4))
+    w = rng.standard_normal((1, 1, 2, 2))
+    out = oracle.forward(x, w)[0, 0]
+    # out[2i+r][2j+s] uses U[2i+r+u][2j+s+v] with only (u, v) = (r, s) hitting data
+    # at in[i+r][j+s]: a Kronecker product of the shifted input with the kernel.
+    for r in (0, 1):
+        for s in (0, 1):
+            blk = out[r::2, s::2]
+            assert np.allclose(blk, w[0, 0, r, s] * x[0, 0, r:r + blk.shape[0], s:s + blk.shape[1]],
+                               rtol=0, atol=0)
+
+
+# ----------------------------------------------------------------------------
+# 3./4. Separately coded forms: Eqs. 7-10 and the scatter form
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N,n", sorted(set(legal_small_shapes())))
+def test_matches_segregated_equations_exactly_on_integers(N, n):
+    rng = np.random.default_rng(100 * N + n)
+    x, w = rand_case(rng, 2, 3, 2, N, n, integer=True)
+    assert np.array_equal(oracle.forward(x, w), segregated_form(x, w))
+
+
+@pytest.mark.parametrize("N,n", [(4, 3), (5, 4), (6, 5), (3, 2), (8, 7), (2, 1)])
+def test_matches_segregated_equations_in_fp64(N, n):
+    rng = np.random.default_rng(7 * N + n)
+    x, w = rand_case(rng, 1, 2, 3, N, n)
+    got, want = oracle.forward(x, w), segregated_form(x, w)
+    assert np.abs(got - want).max() <= 1e-12 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("N,n,P", [(4, 3, 0), (5, 4, 0), (6, 5, 0), (4, 5, 2), (4, 5, 3),
+                                   (4, 4, 2), (3, 3, 1), (2, 7, 3)])
+def test_matches_scatter_form(N, n, P):
+    rng = np.random.default_rng(31 * N + 5 * n + P)
+    x, w = rand_case(rng, 2, 2, 3, N, n, integer=True)
+    assert np.array_equal(oracle.forward(x, w, P), scatter_form(x, w, P))
+
+
+# ----------------------------------------------------------------------------
+# 5. Linearity and the two-pixel shift
+# ----------------------------------------------------------------------------
+def test_linearity_in_input_and_kernel():
+    rng = np.random.default_rng(5)
+    x1, w1 = rand_case(rng, 2, 3, 2, 6, 5)
+    x2, w2 = rand_case(rng, 2, 3, 2, 6, 5)
+    a, b = 0.75, -1.25
+    lhs = oracle.forward(a * x1 + b * x2, w1)
+    rhs = a * oracle.forward(x1, w1) + b * oracle.forward(x2, w1)
+    assert np.abs(lhs - rhs).max() <= 1e-13 * np.abs(rhs).max()
+    lhs = oracle.forward(x1, a * w1 + b * w2)
+    rhs = a * oracle.forward(x1, w1) + b * oracle.forward(x1, w2)
+    assert np.abs(lhs - rhs).max() <= 1e-13 * np.abs(rhs).max()
+
+
+def test_one_pixel_input_shift_moves_output_by_two():
+    rng = np.random.default_rng(6)
+    N, n = 8, 3
+    x, w = rand_case(rng, 1, 2, 2, N, n)
+    xs = np.zeros_like(x)
+    xs[:, :, 1:, 1:] = x[:, :, :-1, :-1]
+    o, os_ = oracle.forward(x, w), oracle.forward(xs, w)
+    # Interior only: rows/cols that see neither the vacated nor the dropped pixels.
+    assert np.allclose(os_[:, :, 2:, 2:][:, :, :-n, :-n], o[:, :, :-2, :-2][:, :, :-n, :-n],
+                       rtol=0, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# 6. Adjoint identity with the matching stride-2 correlation
+# ----------------------------------------------------------------------------
+def strided_adjoint(g, w, N):
+    """T*(g)[b][ci][a][c] = sum_co sum_{u,v} g[b][co][2a-u][2c-v] w[co][ci][u][v]."""
+    B, Cout, M, _ = g.shape
+    _, Cin, n, _ = w.shape
+    out = np.zeros((B, Cin, N, N))
+    for a in range(N):
+        for c in range(N):
+            for u in range(n):
+                for v in range(n):
+                    y, xx = 2 * a - u, 2 * c - v
+                    if 0 <= y < M and 0 <= xx < M:
+                        out[:, :, a, c] += np.einsum("bo,oi->bi", g[:, :, y, xx], w[:, :, u, v])
+    return out
+
+
+@pytest.mark.parametrize("N,n", [(5, 3), (5, 4), (6, 5), (3, 1), (4, 2)])
+def test_adjoint_identity(N, n):
+    rng = np.random.default_rng(40 + n)
+    x, w = rand_case(rng, 2, 3, 2, N, n)
+    M = 2 * N - n
+    g = rng.standard_normal((2, 2, M, M))
+    lhs = np.vdot(oracle.forward(x, w), g)
+    rhs = np.vdot(x, strided_adjoint(g, w, N))
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), 1.0)
+
+
+# ----------------------------------------------------------------------------
+# 7. Library routines in fp64 (cross-check only)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N,n,P", [(6, 3, 0), (7, 4, 0), (8, 5, 0), (4, 4, 2), (4, 5, 2), (4, 5, 3),
+                                   (5, 1, 0), (5, 2, 0)])
+def test_library_convolutions(N, n, P):
+    rng = np.random.default_rng(70 + N + n + P)
+    x, w = rand_case(rng, 2, 3, 4, N, n)
+    got = oracle.forward(x, w, P)
+    xt, wt = torch.from_numpy(x), torch.from_numpy(w)
+    # (i) conv2d (a correlation in torch) on an explicitly zero-embedded tensor
+    S = 2 * N - 1
+    U = torch.zeros(2, 3, S, S, dtype=torch.float64)
+    U[:, :, ::2, ::2] = xt
+    ref1 = torch.nn.functional.conv2d(U, wt, padding=P).numpy()
+    assert np.abs(got - ref1).max() <= 1e-12 * np.abs(ref1).max()
+    # (ii) conv_transpose2d, stride 2, with the kernel rotated by 180 degrees and its
+    # channel axes swapped; padding n-1-P crops the full scatter output to M.
+    if n - 1 - P >= 0:
+        w_t = torch.flip(wt, dims=(2, 3)).permute(1, 0, 2, 3).contiguous()
+        ref2 = torch.nn.functional.conv_transpose2d(xt, w_t, stride=2, padding=n - 1 - P).numpy()
+        assert ref2.shape == got.shape
+        assert np.abs(got - ref2).max() <= 1e-12 * np.abs(ref2).max()
+
+
+# ----------------------------------------------------------------------------
+# 8. Shapes and counts
+# ----------------------------------------------------------------------------
+def test_output_size_law():
+    assert oracle.out_size(4, 3) == 5          # Fig. 2: 4x4 input, 3x3 kernel
+    # Table 1 shapes with padding factor 2: 224 -> 451 padded up-sampled; the odd kernels give
+    # odd outputs (447, 449), one row/column short of what the quad sweep produces.
+    assert oracle.out_size(224, 5, 2) == 447
+    assert oracle.out_size(224, 4, 2) == 448
+    assert oracle.out_size(224, 3, 2) == 449
+    assert oracle.out_size(4, 4, 2) == 8       # Table 3, DCGAN layer 2: 4x4 -> 8x8
+    for N, n in [(32, 3), (512, 5), (16, 4), (8, 5), (64, 3)]:
+        assert oracle.out_size(N, n) == 2 * N - n
+
+
+def test_table4_conventional_counts():
+    # DCGAN layer 2 (4x4x1024 in, 4x4x1024x512 kernel, padding factor 2 -> 8x8 out)
+    assert oracle.conventional_ops(1024, 512, 4, 4, 2) == (536_870_912, 536_838_144)
+    # DCGAN layer 3 (8x8x512 -> 16x16x256) and layer 5 (32x32x128 -> 64x64x3)
+    assert oracle.conventional_ops(512, 256, 8, 4, 2) == (536_870_912, 536_805_376)
+    assert oracle.conventional_ops(128, 3, 32, 4, 2) == (25_165_824, 25_153_536)
+    # EB-GAN layer 7 (128x128x64 in, 4x4x64x64)
+    assert oracle.conventional_ops(64, 64, 128, 4, 2) == (4_294_967_296, 4_290_772_992)
+
+
+def test_forward_planes_equals_forward():
+    rng = np.random.default_rng(9)
+    x, w = rand_case(rng, 3, 2, 4, 6, 5)
+    full = oracle.forward(x, w)
+    b = [2, 0, 1, 2]
+    co = [3, 0, 2, 1]
+    pl = oracle.forward_planes(x, w, b, co)
+    for k in range(4):
+        assert np.array_equal(pl[k], full[b[k], co[k]])
+
+
+def test_rejects_illegal_shapes():
+    with pytest.raises(ValueError):
+        oracle.forward(np.zeros((1, 1, 2, 2)), np.zeros((1, 1, 5, 5)))   # 2N - n < 1
+    with pytest.raises(ValueError):
+        oracle.forward(np.zeros((1, 2, 4, 4)), np.zeros((1, 3, 3, 3)))   # Cin mismatch
