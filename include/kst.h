@@ -1,0 +1,154 @@
+/*
+ * kst -- kernel-segregated transpose convolution (arxiv 2209.03704) for
+ * AMD MI355X (gfx950).  C ABI of libkst.so.
+ *
+ * The operation (Section 1 and Eq. 1 of Section 2 of the paper): an N x N map
+ * is up-sampled to (2N-1) x (2N-1) by embedding a zero after every row and
+ * column, then correlated (no kernel flip, stride 1) with an n x n kernel,
+ * summed over input channels, giving an M x M map with M = 2N - n.  The
+ * library never builds the up-sampled map: it splits each kernel into four
+ * sub-kernels by (row, column) parity (Section 3.2) and applies them to the
+ * original input, four outputs per step (Section 3.3, Eqs. 7-10).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer to memory the caller owns
+ *     (hipMalloc or a PyTorch tensor).  The library keeps none of them.
+ *   - Dense row-major layouts: in[B][Cin][N][N], w[Cout][Cin][n][n],
+ *     out[B][Cout][M][M].  out is always fp32 and is completely overwritten
+ *     (no bias, no activation, no accumulation).  Buffers must not alias.
+ *   - dtype describes in and w: KST_F32 (fp32 operands, fp32 arithmetic) or
+ *     KST_BF16 (bfloat16 operands, fp32 accumulation, fp32 out).
+ *   - Work is enqueued on `stream` and the call returns without waiting for
+ *     it.  Arguments are validated on the host before anything is launched;
+ *     errors come back as a kst_status, nothing throws or aborts.
+ *   - Every data pointer must be 16-byte aligned.
+ *   - Legal shapes: B, Cin, Cout, N, n >= 1 and 2N - n >= 1, with every tensor
+ *     below 2^31 elements.
+ *   - Calls on different streams may run concurrently.
+ */
+#ifndef KST_H
+#define KST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same definition as the HIP runtime's, so that no HIP header is needed here. */
+typedef struct ihipStream_t *hipStream_t;
+
+typedef enum {
+    KST_F32 = 0,
+    KST_BF16 = 1
+} kst_dtype;
+
+typedef enum {
+    KST_OK = 0,
+    KST_ERR_NULL = 1,       /* a required pointer is NULL                              */
+    KST_ERR_SHAPE = 2,      /* a size < 1, 2N - n < 1, or a tensor of 2^31+ elements   */
+    KST_ERR_DTYPE = 3,      /* dtype is neither KST_F32 nor KST_BF16                   */
+    KST_ERR_WORKSPACE = 4,  /* workspace missing or smaller than kst_workspace_bytes  */
+    KST_ERR_HIP = 5,        /* the HIP runtime refused an allocation or a launch      */
+    KST_ERR_PATH = 6,       /* unknown kst_path, or a path that cannot run this shape */
+    KST_ERR_ALIGN = 7       /* a data pointer is not 16-byte aligned                  */
+} kst_status;
+
+/* Which kernel family kst_forward_seg uses.  AUTO picks DIRECT for small
+ * channel counts (bandwidth-bound) and IGEMM (matrix cores) otherwise. */
+typedef enum {
+    KST_PATH_AUTO = 0,
+    KST_PATH_DIRECT = 1,
+    KST_PATH_IGEMM = 2
+} kst_path;
+
+int kst_version(void);
+const char *kst_status_string(int status);
+
+/* M = 2N - n, the output edge (Section 1).  May be < 1 for illegal shapes. */
+int kst_out_size(int N, int n);
+
+/*
+ * Shape of sub-kernel p of an n x n kernel (Section 3.2).  p = 2r + s selects
+ * the rows of parity r and the columns of parity s: p = 0..3 are the paper's
+ * K1 (K00), K2 (K01), K3 (K10), K4 (K11).  Writes Ta = ceil((n-r)/2) rows and
+ * Tb = ceil((n-s)/2) columns (either may be 0 for n = 1).  Returns KST_OK, or
+ * KST_ERR_SHAPE for n < 1 or p outside 0..3.  Host pointers.
+ */
+kst_status kst_subkernel_shape(int n, int p, int *Ta, int *Tb);
+
+/*
+ * Segregated-weight buffer (the output of kst_segregate_weights).
+ *
+ * The buffer is the four per-parity tensors W_0..W_3, each contiguous, one
+ * after the other; W_p starts kst_segregated_offset(...) elements into it.
+ * With t = a*Tb + b the tap index inside sub-kernel p, and
+ * W_p(co, ci, a, b) = w[co][ci][2a + r][2b + s]:
+ *
+ *   KST_F32 :  W_p laid out as [Cin][Ta*Tb][Cout]            (co fastest)
+ *   KST_BF16:  W_p laid out as [ceil(Cin/8)][Ta*Tb][Cout][8] (ci mod 8 fastest),
+ *              input channels padded with zeros to a multiple of 8.
+ *
+ * Both put the reduction index next to the output channel the way the matrix
+ * cores read it.  kst_segregated_elems is the total element count (of 4 or 2
+ * bytes); for KST_F32 it equals Cout*Cin*n*n: segregation is a permutation.
+ * Both return 0 for illegal arguments.
+ */
+size_t kst_segregated_elems(int Cin, int Cout, int n, kst_dtype dtype);
+size_t kst_segregated_offset(int Cin, int Cout, int n, int p, kst_dtype dtype);
+
+/*
+ * Weight pre-segregation (Section 3.2, the sub-kernel matrices K00..K11).
+ * Reads w[Cout][Cin][n][n], writes every element of w_seg in the layout above.
+ * Done once per weight tensor.  One kernel launch on `stream`.
+ */
+kst_status kst_segregate_weights(const void *w, void *w_seg, int Cin, int Cout, int n,
+                                 kst_dtype dtype, hipStream_t stream);
+
+/*
+ * Bytes of scratch kst_forward_seg needs for this shape and path (0 when it
+ * needs none).  The matrix-core path uses it for partial sums when it splits
+ * the input-channel reduction across workgroups.
+ */
+size_t kst_workspace_bytes(int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path);
+
+/*
+ * Segregated forward pass (Section 3.3, Eqs. 7-10), weights already
+ * segregated:
+ *   out[b][co][2i+r][2j+s] = sum_ci sum_a sum_b' in[b][ci][i+r+a][j+s+b'] * W_p(co,ci,a,b')
+ * for every (i, j, r, s) with 2i+r < M and 2j+s < M; the extra row and column
+ * the quad sweep would produce for odd M are never written.  ws/ws_bytes:
+ * scratch of at least kst_workspace_bytes(...) bytes, 256-byte aligned (may
+ * be NULL/0 when that is 0).  Its contents are undefined afterwards.
+ */
+kst_status kst_forward_seg(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
+                           int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path,
+                           hipStream_t stream);
+
+/*
+ * Whole path from un-segregated weights: segregates w into scratch, then runs
+ * the segregated forward pass with path AUTO.  Same result as
+ * kst_segregate_weights + kst_forward_seg.  The scratch (segregated weights
+ * and workspace) is taken from and returned to the device's stream-ordered
+ * memory pool on `stream` (hipMallocAsync / hipFreeAsync): no host
+ * synchronisation, but not usable under stream capture.
+ */
+kst_status kst_forward(const void *in, const void *w, void *out,
+                       int B, int Cin, int Cout, int N, int n, kst_dtype dtype, hipStream_t stream);
+
+/*
+ * The conventional method the paper compares against (Section 1; Eq. 1 on the
+ * up-sampled map), kept as the speed-up reference and never tuned: one kernel
+ * writes U[B][Cin][2N-1][2N-1] (same dtype as in) including all its zeros,
+ * a second computes every output with the full n x n x Cin loop over U.
+ * U must hold B*Cin*(2N-1)^2 elements.
+ */
+kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void *out,
+                                   int B, int Cin, int Cout, int N, int n, kst_dtype dtype,
+                                   hipStream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KST_H */

@@ -1,0 +1,189 @@
+// C ABI of libkst.so: argument validation, path choice, launches.
+#include "kst_internal.h"
+
+using namespace kst;
+
+namespace {
+
+constexpr size_t kMaxElems = (size_t)1 << 31;
+
+bool dtype_ok(int dt) { return dt == KST_F32 || dt == KST_BF16; }
+size_t elt_bytes(kst_dtype dt) { return dt == KST_BF16 ? 2 : 4; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+kst_status check_weight_shape(int Cin, int Cout, int n)
+{
+    if (Cin < 1 || Cout < 1 || n < 1) return KST_ERR_SHAPE;
+    const size_t pad = ((size_t)Cin + 7) / 8 * 8;
+    if (n > 46340 || pad * (size_t)Cout >= kMaxElems / ((size_t)n * n)) return KST_ERR_SHAPE;
+    return KST_OK;
+}
+
+kst_status check_shape(int B, int Cin, int Cout, int N, int n)
+{
+    if (B < 1 || N < 1) return KST_ERR_SHAPE;
+    kst_status st = check_weight_shape(Cin, Cout, n);
+    if (st != KST_OK) return st;
+    if (N > 32768) return KST_ERR_SHAPE;
+    const long long M = 2LL * N - n;
+    if (M < 1) return KST_ERR_SHAPE;
+    const size_t S = 2 * (size_t)N - 1;
+    if ((size_t)B * Cin >= kMaxElems / (S * S)) return KST_ERR_SHAPE;            // up-sampled map (and in)
+    if ((size_t)B * Cout >= kMaxElems / ((size_t)(M + 1) * (M + 1))) return KST_ERR_SHAPE;   // out, quad grid
+    return KST_OK;
+}
+
+// AUTO: the matrix cores pay off once both channel counts can fill MFMA blocks.
+kst_path choose_path(const Shape &s, kst_dtype dt)
+{
+    const bool ok = dt == KST_BF16 ? igemm_bf16_supported(s) : igemm_f32_supported(s);
+    if (ok && s.Cout >= 16 && s.Cin >= 8) return KST_PATH_IGEMM;
+    return KST_PATH_DIRECT;
+}
+
+kst_status resolve_path(const Shape &s, kst_dtype dt, int path, kst_path *out)
+{
+    if (path == KST_PATH_AUTO) { *out = choose_path(s, dt); return KST_OK; }
+    if (path == KST_PATH_DIRECT) { *out = KST_PATH_DIRECT; return KST_OK; }
+    if (path == KST_PATH_IGEMM) {
+        const bool ok = dt == KST_BF16 ? igemm_bf16_supported(s) : igemm_f32_supported(s);
+        if (!ok) return KST_ERR_PATH;
+        *out = KST_PATH_IGEMM;
+        return KST_OK;
+    }
+    return KST_ERR_PATH;
+}
+
+size_t workspace_for(const Shape &s, kst_dtype dt, kst_path path)
+{
+    if (path != KST_PATH_IGEMM) return 0;
+    return dt == KST_BF16 ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int kst_version(void) { return 100; }
+
+const char *kst_status_string(int status)
+{
+    switch (status) {
+        case KST_OK: return "ok";
+        case KST_ERR_NULL: return "null pointer";
+        case KST_ERR_SHAPE: return "illegal shape";
+        case KST_ERR_DTYPE: return "unknown dtype";
+        case KST_ERR_WORKSPACE: return "workspace missing or too small";
+        case KST_ERR_HIP: return "HIP runtime error";
+        case KST_ERR_PATH: return "unknown or unsupported path";
+        case KST_ERR_ALIGN: return "pointer not 16-byte aligned";
+        default: return "unknown status";
+    }
+}
+
+int kst_out_size(int N, int n) { return 2 * N - n; }
+
+kst_status kst_subkernel_shape(int n, int p, int *Ta, int *Tb)
+{
+    if (!Ta || !Tb) return KST_ERR_NULL;
+    if (n < 1 || p < 0 || p > 3) return KST_ERR_SHAPE;
+    *Ta = taps_for_parity(n, p >> 1);
+    *Tb = taps_for_parity(n, p & 1);
+    return KST_OK;
+}
+
+size_t kst_segregated_elems(int Cin, int Cout, int n, kst_dtype dtype)
+{
+    if (!dtype_ok(dtype) || check_weight_shape(Cin, Cout, n) != KST_OK) return 0;
+    return seg_elems(Cin, Cout, n, dtype);
+}
+
+size_t kst_segregated_offset(int Cin, int Cout, int n, int p, kst_dtype dtype)
+{
+    if (!dtype_ok(dtype) || check_weight_shape(Cin, Cout, n) != KST_OK || p < 0 || p > 3) return 0;
+    return seg_offset(Cin, Cout, n, p, dtype);
+}
+
+kst_status kst_segregate_weights(const void *w, void *w_seg, int Cin, int Cout, int n, kst_dtype dtype,
+                                 hipStream_t stream)
+{
+    if (!w || !w_seg) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    kst_status st = check_weight_shape(Cin, Cout, n);
+    if (st != KST_OK) return st;
+    if (!aligned16(w) || !aligned16(w_seg)) return KST_ERR_ALIGN;
+    return launch_segregate(w, w_seg, Cin, Cout, n, dtype, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
+size_t kst_workspace_bytes(int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path)
+{
+    if (!dtype_ok(dtype) || check_shape(B, Cin, Cout, N, n) != KST_OK) return 0;
+    const Shape s = make_shape(B, Cin, Cout, N, n);
+    kst_path chosen;
+    if (resolve_path(s, dtype, path, &chosen) != KST_OK) return 0;
+    return workspace_for(s, dtype, chosen);
+}
+
+kst_status kst_forward_seg(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
+                           int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path,
+                           hipStream_t stream)
+{
+    if (!in || !w_seg || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    kst_status st = check_shape(B, Cin, Cout, N, n);
+    if (st != KST_OK) return st;
+    const Shape s = make_shape(B, Cin, Cout, N, n);
+    kst_path chosen;
+    st = resolve_path(s, dtype, path, &chosen);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
+    const size_t need = workspace_for(s, dtype, chosen);
+    if (need > 0) {
+        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return KST_ERR_ALIGN;
+    }
+    hipError_t e;
+    if (chosen == KST_PATH_DIRECT)
+        e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
+    else if (dtype == KST_BF16)
+        e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, stream);
+    else
+        e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s, stream);
+    return e == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
+kst_status kst_forward(const void *in, const void *w, void *out, int B, int Cin, int Cout, int N, int n,
+                       kst_dtype dtype, hipStream_t stream)
+{
+    if (!in || !w || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    kst_status st = check_shape(B, Cin, Cout, N, n);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w) || !aligned16(out)) return KST_ERR_ALIGN;
+    const Shape s = make_shape(B, Cin, Cout, N, n);
+    const kst_path chosen = choose_path(s, dtype);
+    const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;
+    const size_t ws_bytes = workspace_for(s, dtype, chosen);
+    void *scratch = nullptr;
+    if (hipMallocAsync(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
+    void *ws = ws_bytes ? (void *)((char *)scratch + seg_bytes) : nullptr;
+    st = kst_segregate_weights(w, scratch, Cin, Cout, n, dtype, stream);
+    if (st == KST_OK)
+        st = kst_forward_seg(in, scratch, out, ws, ws_bytes, B, Cin, Cout, N, n, dtype, chosen, stream);
+    if (hipFreeAsync(scratch, stream) != hipSuccess && st == KST_OK) st = KST_ERR_HIP;
+    return st;
+}
+
+kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void *out, int B, int Cin, int Cout,
+                                   int N, int n, kst_dtype dtype, hipStream_t stream)
+{
+    if (!in || !w || !U || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    kst_status st = check_shape(B, Cin, Cout, N, n);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w) || !aligned16(U) || !aligned16(out)) return KST_ERR_ALIGN;
+    const Shape s = make_shape(B, Cin, Cout, N, n);
+    return launch_zero_insert(in, w, U, (float *)out, s, dtype, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
+}  // extern "C"

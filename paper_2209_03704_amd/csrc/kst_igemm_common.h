@@ -1,0 +1,91 @@
+// Pieces shared by the fp32 and bf16 matrix-core kernels: the tile plan, the
+// class-interleaving epilogue and the split-reduction pass.
+#pragma once
+#include "kst_internal.h"
+
+namespace kst {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int G_TM = 128;        // positions per workgroup (4 MFMA column blocks)
+constexpr int G_TCO = 128;       // output channels per workgroup (4 MFMA row blocks)
+constexpr int G_THREADS = 512;   // 8 waves: 2 (channel halves) x 4 (position blocks)
+
+struct IgemmParams {
+    int B, Cin, Cout, N, M, E, EE;
+    int Mtot;              // B * E * E
+    int tiles_m, tiles_co, splits;
+    int ci_per_split;      // multiple of the kernel's channel step
+    int lrows;             // input rows (stacked over batch items) held per channel
+    unsigned off[4];       // element offset of W_p
+    size_t out_elems;
+};
+
+// kc: input channels staged per step.
+inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
+{
+    IgemmParams p;
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.E = s.E;
+    p.EE = s.E * s.E;
+    p.Mtot = s.B * p.EE;
+    p.tiles_m = (p.Mtot + G_TM - 1) / G_TM;
+    p.tiles_co = (s.Cout + G_TCO - 1) / G_TCO;
+    // Rows of one channel that G_TM consecutive positions can touch: the quad rows
+    // spanned, the rows skipped at each batch-item boundary, and the window halo.
+    const int dg = (G_TM - 2) / s.E + 1;
+    const int crossings = (dg + s.E - 1) / s.E;
+    p.lrows = dg + crossings * (s.N - s.E) + s.fl + 1;
+    // Split the channel reduction when the tile grid alone cannot fill the chip.
+    const int tiles = p.tiles_m * p.tiles_co;
+    const int chunks = (s.Cin + kc - 1) / kc;
+    int splits = 1;
+    if (tiles <= 128) {
+        splits = 256 / tiles;
+        if (splits > chunks) splits = chunks;
+        if (splits > 16) splits = 16;
+    }
+    const int cps = (chunks + splits - 1) / splits;
+    p.ci_per_split = cps * kc;
+    p.splits = (chunks + cps - 1) / cps;
+    for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
+    p.out_elems = (size_t)s.B * s.Cout * s.M * s.M;
+    return p;
+}
+
+// Store one wave's accumulators.  acc[cls][h] is the 32 x 32 block of class cls
+// (rows: output channels co_base + 32h + 8(v/4) + 4kk + v%4; column: this lane's
+// quad).  The s = 0 / s = 1 classes of a row parity sit side by side in memory.
+__device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][2], const IgemmParams &p,
+                                            int co_base, int kk, int mb, int mi, int mj)
+{
+    const bool x1_ok = 2 * mj + 1 < p.M;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co_base + h * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            if (co >= p.Cout) continue;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int y = 2 * mi + r;
+                if (y >= p.M) continue;
+                float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
+                const float v0 = acc[2 * r][h][v], v1 = acc[2 * r + 1][h][v];
+                if (x1_ok) {
+                    if ((reinterpret_cast<uintptr_t>(q) & 7u) == 0) {
+                        *reinterpret_cast<float2 *>(q) = make_float2(v0, v1);
+                    } else {
+                        q[0] = v0;
+                        q[1] = v1;
+                    }
+                } else {
+                    q[0] = v0;
+                }
+            }
+        }
+}
+
+// out[e] = sum over splits of ws[split][e], in split order (deterministic).
+hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream);
+
+}  // namespace kst

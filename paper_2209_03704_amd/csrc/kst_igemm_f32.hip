@@ -1,0 +1,212 @@
+// Matrix-core (MFMA) segregated forward pass, fp32 operands and arithmetic.
+//
+// Section 3.3, Eqs. 7-10, as four implicit GEMMs that share one input tile:
+// for parity class p = (r, s)
+//     C_p[co][m] = sum_k  W_p[co][k] * X_p[k][m],   k = (ci, a, b'),  m = (b, i, j)
+// with X_p[k][m] = in[b][ci][i + r + a][j + s + b'] gathered on the fly from an
+// LDS copy of the input rows the tile touches (never materialised), and the
+// four C_p interleaved into out[b][co][2i + r][2j + s] on the way out.
+//
+// Output channels run down the MFMA rows and quad positions run across its
+// columns, so that for one accumulator register the 32 lanes of a half-wave
+// hold 32 consecutive quads of one output row: the s = 0 / s = 1 accumulators
+// pair up into 8-byte stores that tile a contiguous row segment.
+//
+// Positions are numbered m = (b*E + i)*E + j over the E x E quad grid
+// (E = ceil(M/2)); a workgroup owns TM consecutive positions for TCO output
+// channels and all four classes.  Odd M: the phantom last row/column members
+// are computed (their reads stay inside the map) and not stored.
+#include "kst_igemm_common.h"
+
+namespace kst {
+
+constexpr int G_KC = 4;          // input channels staged per step (even)
+
+template <int n>
+__global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__restrict__ in,
+                                                                const float *__restrict__ w_seg,
+                                                                float *__restrict__ dst, IgemmParams p)
+{
+    constexpr int fl = n / 2;
+    constexpr int NN = n * n;
+    extern __shared__ float lds[];
+    const int xplane = p.lrows * p.N;            // floats per staged channel
+    float *Xs = lds;                             // [G_KC][lrows*N]
+    float *Ws = lds + G_KC * xplane;             // [G_KC][NN][G_TCO]
+
+    unsigned id = blockIdx.x;
+    const int tile_m = (int)(id % (unsigned)p.tiles_m);
+    id /= (unsigned)p.tiles_m;
+    const int tile_co = (int)(id % (unsigned)p.tiles_co);
+    const int split = (int)(id / (unsigned)p.tiles_co);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wco = wave & 1, wpos = wave >> 1;
+
+    const int m0 = tile_m * G_TM;
+    const int co0 = tile_co * G_TCO;
+    const int b0 = m0 / p.EE;
+    const int i0 = (m0 - b0 * p.EE) / p.E;
+    const int R0 = b0 * p.N + i0;                // first stacked input row of the tile
+
+    // This lane's quad position (clamped so that every LDS read stays inside the tile).
+    int m = m0 + wpos * 32 + l32;
+    const bool m_valid = m < p.Mtot;
+    if (!m_valid) m = p.Mtot - 1;
+    const int mb = m / p.EE;
+    const int mrem = m - mb * p.EE;
+    const int mi = mrem / p.E, mj = mrem - mi * p.E;
+    const int xbase = ((mb * p.N + mi) - R0) * p.N + mj + kk * xplane;
+    const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
+
+    const int ci_begin = split * p.ci_per_split;
+    const int ci_end = min(p.Cin, ci_begin + p.ci_per_split);
+
+    for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
+        if (ci0 != ci_begin) __syncthreads();
+        // Stage the input rows [R0, R0 + lrows) of channels ci0 .. ci0+KC-1.
+        for (int e = tid; e < G_KC * xplane; e += G_THREADS) {
+            const int c = e / xplane;
+            const int rem = e - c * xplane;
+            const int lr = rem / p.N, x = rem - lr * p.N;
+            const int R = R0 + lr;
+            const int bb = R / p.N, y = R - bb * p.N;
+            float v = 0.0f;
+            if (bb < p.B && ci0 + c < ci_end)
+                v = in[(((size_t)bb * p.Cin + ci0 + c) * p.N + y) * p.N + x];
+            Xs[e] = v;
+        }
+        // Stage the weights of those channels: all taps of all classes, TCO channels.
+        for (int e = tid; e < G_KC * NN * G_TCO; e += G_THREADS) {
+            const int tco = e % G_TCO;
+            const int rest = e / G_TCO;
+            const int T = rest % NN, c = rest / NN;
+            int cls = 0;
+#pragma unroll
+            for (int q = 1; q < 4; ++q)
+                if (T >= class_tap_base(n, q)) cls = q;
+            const int Tp = class_taps(n, cls);
+            const int t = T - class_tap_base(n, cls);
+            float v = 0.0f;
+            if (co0 + tco < p.Cout && ci0 + c < ci_end)
+                v = w_seg[p.off[cls] + ((size_t)(ci0 + c) * Tp + t) * p.Cout + co0 + tco];
+            Ws[e] = v;
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int c2 = 0; c2 < G_KC; c2 += 2) {
+            // Input fragments for every window offset (dy, dx): shared by all classes.
+            float xf[fl + 1][fl + 1];
+#pragma unroll
+            for (int dy = 0; dy <= fl; ++dy)
+#pragma unroll
+                for (int dx = 0; dx <= fl; ++dx)
+                    xf[dy][dx] = Xs[c2 * xplane + xbase + dy * p.N + dx];
+#pragma unroll
+            for (int cls = 0; cls < 4; ++cls) {
+                const int r = cls >> 1, s = cls & 1;
+                const int Ta = taps_for_parity(n, r), Tb = taps_for_parity(n, s);
+#pragma unroll
+                for (int a = 0; a < Ta; ++a)
+#pragma unroll
+                    for (int bq = 0; bq < Tb; ++bq) {
+                        const int T = class_tap_base(n, cls) + a * Tb + bq;
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const float wf = Ws[(c2 * NN + T) * G_TCO + wbase + h * 32];
+                            acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, xf[r + a][s + bq], acc[cls][h], 0, 0, 0);
+                        }
+                    }
+            }
+        }
+    }
+
+    // Epilogue: interleave the four classes; lanes l32 = consecutive quads of a row.
+    if (!m_valid) return;
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
+}
+
+// Sum the per-split partial outputs (fixed order: deterministic).
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ ws, float *__restrict__ out,
+                                                              size_t elems, int splits)
+{
+    const size_t e = (size_t)blockIdx.x * 256u + threadIdx.x;
+    if (e >= elems) return;
+    float a = ws[e];
+    for (int s = 1; s < splits; ++s) a += ws[(size_t)s * elems + e];
+    out[e] = a;
+}
+
+static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_F32, G_KC); }
+
+static size_t lds_bytes(const IgemmParams &p, int n)
+{
+    return (size_t)G_KC * ((size_t)p.lrows * p.N + (size_t)n * n * G_TCO) * sizeof(float);
+}
+
+bool igemm_f32_supported(const Shape &s)
+{
+    if (s.n > 7) return false;
+    return lds_bytes(plan(s), s.n) <= 160 * 1024;
+}
+
+size_t igemm_f32_workspace_bytes(const Shape &s)
+{
+    const IgemmParams p = plan(s);
+    return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+}
+
+template <int n>
+static hipError_t launch_n(const float *in, const float *w_seg, float *dst, const IgemmParams &p, hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p, n);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_kernel<n>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned blocks = (unsigned)p.tiles_m * p.tiles_co * p.splits;
+    hipLaunchKernelGGL(igemm_f32_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
+                            hipStream_t stream)
+{
+    const IgemmParams p = plan(s);
+    float *dst = p.splits > 1 ? (float *)ws : out;
+    hipError_t e;
+    switch (s.n) {
+        case 1: e = launch_n<1>(in, w_seg, dst, p, stream); break;
+        case 2: e = launch_n<2>(in, w_seg, dst, p, stream); break;
+        case 3: e = launch_n<3>(in, w_seg, dst, p, stream); break;
+        case 4: e = launch_n<4>(in, w_seg, dst, p, stream); break;
+        case 5: e = launch_n<5>(in, w_seg, dst, p, stream); break;
+        case 6: e = launch_n<6>(in, w_seg, dst, p, stream); break;
+        case 7: e = launch_n<7>(in, w_seg, dst, p, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream);
+    return e;
+}
+
+hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream)
+{
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
+                       ws, out, elems, splits);
+    return hipGetLastError();
+}
+
+}  // namespace kst

@@ -1,0 +1,72 @@
+// Internal declarations shared by the translation units of libkst.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "kst.h"
+
+namespace kst {
+
+// Sub-kernel geometry of Section 3.2: parity r keeps rows r, r+2, ... of an n-row kernel.
+__host__ __device__ constexpr int taps_for_parity(int n, int r) { return (n - r + 1) / 2; }
+__host__ __device__ constexpr int class_taps(int n, int p)
+{
+    return taps_for_parity(n, p >> 1) * taps_for_parity(n, p & 1);
+}
+// Taps of all classes before class p (class-major tap numbering 0..n*n-1).
+__host__ __device__ constexpr int class_tap_base(int n, int p)
+{
+    int s = 0;
+    for (int q = 0; q < p; ++q) s += class_taps(n, q);
+    return s;
+}
+
+// Operand element -> fp32.  bfloat16 operands travel as raw 16-bit patterns.
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(uint16_t v) { return __uint_as_float((unsigned)v << 16); }
+
+struct Shape {
+    int B, Cin, Cout, N, n;
+    int M;    // output edge 2N - n
+    int E;    // quad rows/columns: ceil(M / 2)
+    int fl;   // floor(n / 2): halo of the input window of one quad
+};
+
+inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
+{
+    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2};
+    return s;
+}
+
+// Element offset of W_p inside the segregated buffer, and the total size.
+inline size_t seg_cin_padded(int Cin, kst_dtype dt) { return dt == KST_BF16 ? (size_t)((Cin + 7) / 8) * 8 : (size_t)Cin; }
+inline size_t seg_offset(int Cin, int Cout, int n, int p, kst_dtype dt)
+{
+    return seg_cin_padded(Cin, dt) * (size_t)Cout * (size_t)class_tap_base(n, p);
+}
+inline size_t seg_elems(int Cin, int Cout, int n, kst_dtype dt)
+{
+    return seg_cin_padded(Cin, dt) * (size_t)Cout * (size_t)n * (size_t)n;
+}
+
+// Launchers (each enqueues on `stream` and returns the launch status).
+hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n, kst_dtype dt,
+                            hipStream_t stream);
+hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out, const Shape &s,
+                              kst_dtype dt, hipStream_t stream);
+// Direct path: any shape.
+hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
+                         hipStream_t stream);
+// Matrix-core path: whether the kernels can run the shape, scratch they need, launch.
+bool igemm_f32_supported(const Shape &s);
+bool igemm_bf16_supported(const Shape &s);
+size_t igemm_f32_workspace_bytes(const Shape &s);
+size_t igemm_bf16_workspace_bytes(const Shape &s);
+hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
+                            hipStream_t stream);
+hipError_t launch_igemm_bf16(const void *in, const void *w_seg, float *out, void *ws, const Shape &s,
+                             hipStream_t stream);
+
+}  // namespace kst

@@ -1,0 +1,99 @@
+"""Host-side checks of libkst.so that need no GPU: the library loads, exports
+every symbol include/kst.h declares, and rejects bad arguments before any
+launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2209_03704_amd import binding as kst
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kst.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kst_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    names = declared_symbols()
+    assert "kst_forward" in names and "kst_segregate_weights" in names
+    l = kst.lib()
+    for name in names:
+        assert hasattr(l, name), name
+        assert name in kst.SIGNATURES, "binding lacks " + name
+        assert hasattr(kst, name), "binding lacks a wrapper for " + name
+    assert sorted(kst.SIGNATURES) == names
+
+
+def test_version_and_strings():
+    assert kst.kst_version() >= 100
+    assert kst.kst_status_string(0) == "ok"
+    assert all(kst.kst_status_string(s) for s in range(0, 9))
+
+
+@pytest.mark.parametrize("N,n", [(4, 3), (32, 3), (512, 5), (16, 4), (8, 5), (64, 3)])
+def test_out_size(N, n):
+    assert kst.kst_out_size(N, n) == 2 * N - n          # Section 1
+
+
+@pytest.mark.parametrize("n", range(1, 10))
+def test_subkernel_shapes_partition_the_kernel(n):
+    """Section 3.2: sizes ceil x ceil, ceil x floor, floor x ceil, floor x floor."""
+    ce, fl = (n + 1) // 2, n // 2
+    shapes = [kst.kst_subkernel_shape(n, p) for p in range(4)]
+    assert shapes == [(ce, ce), (ce, fl), (fl, ce), (fl, fl)]
+    assert sum(a * b for a, b in shapes) == n * n
+    # fp32 segregation is a permutation: same element count, class offsets are prefix sums
+    Cin, Cout = 5, 7
+    assert kst.kst_segregated_elems(Cin, Cout, n, kst.KST_F32) == Cin * Cout * n * n
+    run = 0
+    for p, (a, b) in enumerate(shapes):
+        assert kst.kst_segregated_offset(Cin, Cout, n, p, kst.KST_F32) == run * Cin * Cout
+        assert kst.kst_segregated_offset(Cin, Cout, n, p, kst.KST_BF16) == run * 8 * Cout
+        run += a * b
+    assert kst.kst_segregated_elems(Cin, Cout, n, kst.KST_BF16) == 8 * Cout * n * n
+
+
+def test_subkernel_shape_errors():
+    with pytest.raises(kst.KstError):
+        kst.kst_subkernel_shape(0, 0)
+    with pytest.raises(kst.KstError):
+        kst.kst_subkernel_shape(3, 4)
+
+
+def test_argument_errors_are_statuses_not_crashes():
+    l = kst.lib()
+    one = ctypes.c_void_p(16)          # non-null, aligned, never dereferenced: checks fail first
+    # null pointers
+    assert l.kst_forward(None, one, one, 1, 1, 1, 4, 3, 0, None) == 1
+    assert l.kst_forward_seg(one, None, one, None, 0, 1, 1, 1, 4, 3, 0, 0, None) == 1
+    assert l.kst_segregate_weights(None, one, 1, 1, 3, 0, None) == 1
+    assert l.kst_forward_zero_insert(one, one, None, one, 1, 1, 1, 4, 3, 0, None) == 1
+    # dtype
+    assert l.kst_forward(one, one, one, 1, 1, 1, 4, 3, 7, None) == 3
+    assert l.kst_segregate_weights(one, one, 1, 1, 3, 2, None) == 3
+    # shapes: a size < 1, kernel larger than the up-sampled map, tensors of 2^31 elements
+    assert l.kst_forward(one, one, one, 0, 1, 1, 4, 3, 0, None) == 2
+    assert l.kst_forward(one, one, one, 1, 1, 1, 2, 5, 0, None) == 2
+    assert l.kst_forward(one, one, one, 1, 1, 1, 4, 0, 0, None) == 2
+    assert l.kst_forward(one, one, one, 4096, 64, 64, 512, 3, 0, None) == 2
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 1, 1, 4, 9, 0, 0, None) == 2
+    # unknown path; matrix-core path asked for a kernel size it does not cover
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 3, 0, 9, None) == 6
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 9, 0, 2, None) == 6
+    # alignment
+    odd = ctypes.c_void_p(20)
+    assert l.kst_forward(odd, one, one, 1, 1, 1, 4, 3, 0, None) == 7
+    # workspace: the split matrix-core plan needs scratch
+    need = kst.kst_workspace_bytes(64, 1024, 512, 8, 5, kst.KST_F32, kst.KST_PATH_IGEMM)
+    assert need > 0
+    assert l.kst_forward_seg(one, one, one, None, 0, 64, 1024, 512, 8, 5, 0, 2, None) == 4
+    assert l.kst_forward_seg(one, one, one, one, need - 1, 64, 1024, 512, 8, 5, 0, 2, None) == 4
+    # sizes helpers return 0 on illegal input
+    assert kst.kst_segregated_elems(0, 1, 3, 0) == 0
+    assert kst.kst_workspace_bytes(1, 1, 1, 2, 5, 0, 0) == 0
+    assert kst.kst_workspace_bytes(1, 1, 1, 32, 3, kst.KST_F32, kst.KST_PATH_DIRECT) == 0
