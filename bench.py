@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the kernel-segregated transpose convolution on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers all|none] [--no-cpu]
+
+One step = one pass of the whole hot path on the headline workload (the
+single-channel bandwidth-bound layer): weight pre-segregation, then the
+segregated forward pass with its edge masking, through the C ABI, inputs
+resident in HBM.  Prints ONE JSON line: whole-job useful GMAC/s, the roofline
+of the dominant kernel (measured live with events on the launch stream), the
+CPU oracle as a baseline, and a per-layer table for the five benchmark layers
+(time, useful GMAC/s, roofline fraction, speed-up over the zero-insert path).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
+# profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", default="all", choices=["all", "none"],
+                    help="also time each of the five benchmark layers")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default=None, help="time just this layer's kernel (profiling aid), e.g. cfg3")
+    return ap.parse_args()
+
+
+class Resident:
+    """A layer's operands in HBM, with `sets` rotating input/output buffers so that
+    successive launches cannot be served from the last-level cache."""
+
+    def __init__(self, layer, sets, torch, kst, wl):
+        self.layer = layer
+        x, w = wl.make_tensors(layer)
+        self.host = (x, w)
+        self.w = w.cuda()
+        self.x = [x.cuda() if i == 0 else x.cuda().clone() for i in range(sets)]
+        self.out = [torch.empty(layer.out_shape, dtype=torch.float32, device="cuda") for _ in range(sets)]
+        dt = kst.KST_BF16 if layer.dtype == "bf16" else kst.KST_F32
+        self.w_seg = torch.empty(kst.kst_segregated_elems(layer.Cin, layer.Cout, layer.n, dt),
+                                 dtype=w.dtype, device="cuda")
+        need = kst.kst_workspace_bytes(layer.B, layer.Cin, layer.Cout, layer.N, layer.n, dt, kst.KST_PATH_AUTO)
+        self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda") if need else None
+        self.sets = sets
+
+
+def time_launches(torch, fn, iters, warmup):
+    """Average milliseconds per call of fn(i), by events on the current stream."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(iters):
+        fn(i)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def roofline_for(layer, ms, metrics):
+    """Roofline entry of the forward kernel of `layer` given its launch time."""
+    direct = layer.Cout < 16 or layer.Cin < 8
+    if direct:
+        a = metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(a, 1), "peak": metrics.HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(a / metrics.HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name)}
+    peak = metrics.MFMA_PEAK_TFLOPS[layer.dtype]
+    a = 2.0 * metrics.useful_macs(layer) / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(a, 2), "peak": peak, "unit": "TFLOP/s",
+            "frac": round(a / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name)}
+
+
+def cpu_baseline(layer, host, metrics, wl, budget_s=12.0):
+    """The fp64 zero-insert oracle on the host cores, on a bounded sample of batch items."""
+    import oracle
+    x, w = host
+    x64, w64 = wl.to_f64(x), wl.to_f64(w)
+    per_item = metrics.useful_macs(layer) / layer.B
+    t0 = time.perf_counter()
+    oracle.forward(x64[:1], w64)
+    t1 = time.perf_counter() - t0
+    items = int(max(1, min(layer.B, budget_s / max(t1, 1e-6))))
+    t0 = time.perf_counter()
+    oracle.forward(x64[:items], w64)
+    dt = time.perf_counter() - t0
+    return {"value": round(per_item * items / dt / 1e9, 4), "unit": "GMAC/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": "%d of %d batch items of %s, fp64 zero-insert + Eq. 1, %.1f s" % (items, layer.B, layer.name, dt)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus 1 only)")
+    import torch
+
+    from paper_2209_03704_amd import binding as kst
+    from paper_2209_03704_amd import metrics
+    from paper_2209_03704_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    kst.lib()   # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    def fwd_seg(r):
+        L = r.layer
+        return lambda i: kst.kst_forward_seg(r.x[i % r.sets], r.w_seg, L.Cout, L.n, out=r.out[i % r.sets], ws=r.ws)
+
+    def whole_path(r):
+        L = r.layer
+
+        def step(i):
+            kst.kst_segregate_weights(r.w, r.w_seg)
+            kst.kst_forward_seg(r.x[i % r.sets], r.w_seg, L.Cout, L.n, out=r.out[i % r.sets], ws=r.ws)
+        return step
+
+    if args.only == "copy":
+        # A plain device copy of known size (256 MiB read + 256 MiB written per launch): the
+        # yardstick the HBM counters and the achievable bandwidth are scaled by.
+        n = 64 * 1024 * 1024
+        bufs = [(torch.empty(n, dtype=torch.float32, device="cuda").normal_(),
+                 torch.empty(n, dtype=torch.float32, device="cuda")) for _ in range(3)]
+        ms = time_launches(torch, lambda i: bufs[i % 3][1].copy_(bufs[i % 3][0]), args.steps, args.warmup)
+        print(json.dumps({"kernel": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n, "kernel_ms": ms,
+                          "GB_per_s": round(8 * n / (ms * 1e-3) / 1e9, 1)}))
+        return
+    if args.only:
+        layer = wl.layer_by_name(args.only)
+        r = Resident(layer, 3, torch, kst, wl)
+        kst.kst_segregate_weights(r.w, r.w_seg)
+        ms = time_launches(torch, fwd_seg(r), args.steps, args.warmup)
+        print(json.dumps({"layer": layer.name, "kernel_ms": ms, "roofline": roofline_for(layer, ms, metrics)}))
+        return
+
+    # ---- headline: whole path on the bandwidth-bound single-channel layer ----------------
+    head = wl.LAYERS[1]
+    r = Resident(head, 3, torch, kst, wl)
+    step = whole_path(r)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = time_launches(torch, fwd_seg(r), args.steps, args.warmup)
+    value = metrics.useful_macs(head) / (ms_per_step * 1e-3) / 1e9
+    roof = roofline_for(head, kernel_ms, metrics)
+    roof["kernel"] = "direct forward (kst_forward_seg)"
+    roof["kernel_us"] = round(kernel_ms * 1e3, 2)
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(head, r.host, metrics, wl)
+    del r
+    torch.cuda.empty_cache()
+
+    # ---- per-layer table ---------------------------------------------------------------------
+    table = []
+    if args.layers == "all":
+        for layer in wl.LAYERS:
+            r = Resident(layer, 3, torch, kst, wl)
+            kst.kst_segregate_weights(r.w, r.w_seg)
+            iters = max(5, min(args.steps, 30))
+            ms = time_launches(torch, fwd_seg(r), iters, 3)
+            seg_ms = time_launches(torch, lambda i: kst.kst_segregate_weights(r.w, r.w_seg), 10, 2)
+            U = torch.empty((layer.B, layer.Cin, 2 * layer.N - 1, 2 * layer.N - 1), dtype=r.w.dtype, device="cuda")
+            zi_ms = time_launches(
+                torch, lambda i: kst.kst_forward_zero_insert(r.x[0], r.w, U=U, out=r.out[0]), 2, 1)
+            roof_l = roofline_for(layer, ms, metrics)
+            table.append({
+                "layer": layer.name,
+                "shape": {"B": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n,
+                          "dtype": layer.dtype},
+                "forward_us": round(ms * 1e3, 2),
+                "segregate_us": round(seg_ms * 1e3, 2),
+                "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
+                "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
+                "hbm_frac": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),
+                "roofline": roof_l,
+                "zero_insert_us": round(zi_ms * 1e3, 1),
+                "speedup_vs_zero_insert": round(zi_ms / ms, 2),
+                "algorithmic_mac_ratio": round(metrics.conventional_macs(layer) / metrics.useful_macs(layer), 3),
+            })
+            del r, U
+            torch.cuda.empty_cache()
+
+    line = {
+        "metric": "useful GMAC/s (segregated transpose convolution, whole path)",
+        "value": round(value, 1),
+        "unit": "GMAC/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": head.name, "B": head.B, "Cin": head.Cin, "Cout": head.Cout, "N": head.N,
+                   "n": head.n, "out": list(head.out_shape),
+                   "step": "kst_segregate_weights + kst_forward_seg, inputs resident in HBM, 3 rotating buffer sets"},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "layers": table,
+        "paper_context": "paper reports 3.7x (Xeon CPU) / 3.4x (RTX 2070) average speed-up over zero-insert; ideal 4x",
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -115,7 +115,7 @@ def tiny_shapes():
 def test_tiny_grid(N, n, dtype):
     for (B, Cin, Cout) in [(1, 1, 1), (2, 3, 5), (3, 5, 2)]:
         layer = wl.Layer("tiny", B, Cin, Cout, N, n, dtype, "normal", w_std=0.5)
-        check_layer(layer, seed=1000 * N + 10 * n + B, skip_unsupported_igemm=(n >= 6 and N <= 6))
+        check_layer(layer, seed=1000 * N + 10 * n + B, skip_unsupported_igemm=(n >= 6))
 
 
 def test_integer_inputs_are_exact_in_fp32():
