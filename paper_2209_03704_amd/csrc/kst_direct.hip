@@ -9,6 +9,9 @@
 // row and column): those stores are suppressed, and the input indices a
 // phantom member would read still lie inside the map, so loads need no mask
 // beyond the tile edge.
+#include <cstdlib>
+
+#include "kst_direct_flat.h"
 #include "kst_internal.h"
 
 namespace kst {
@@ -128,6 +131,340 @@ __global__ void __launch_bounds__(256) direct_kernel(const T *__restrict__ in, c
         }
 }
 
+// ---------------------------------------------------------------------------
+// Row-strip variant: the fast path whenever a strip of full input rows fits in LDS.
+//
+// On this chip a store that is not 16-byte aligned costs about a third of the
+// write bandwidth, and with an odd M every other output row starts misaligned,
+// so the per-quad stores of the tile kernel cannot reach the HBM roofline.
+// Here the roles are turned round: a lane owns one 16-byte ALIGNED group of
+// four consecutive outputs of one row.  Within a row the parity pattern of the
+// group (s = 0,1,0,1 or 1,0,1,0) and the row parity r are the same for every
+// lane, so the four sub-kernels still apply with wave-uniform control flow:
+// the group needs Ta(r) input rows x (fl + 2) columns of the original input and
+// produces two outputs of each column parity (Eqs. 7-10, two quad halves at a
+// time).  Only the first and last group of a row can be partial; those use
+// masked scalar stores.  A workgroup owns R consecutive output rows of one
+// plane; their R/2 + fl input rows are one contiguous run of the input and are
+// staged in LDS (with 4 floats of slack on both sides of each row so that
+// partial groups read inside the buffer).  Accumulators stay in registers
+// across input channels.
+// ---------------------------------------------------------------------------
+struct RowsParams {
+    int B, Cin, Cout, N, M;
+    int R;                    // output rows per workgroup (even)
+    int chunks_per_plane;     // ceil(M / R)
+    unsigned nchunks;         // planes * chunks_per_plane
+    unsigned xcd_slots;       // ceil(nchunks / 8)
+    int xcd_remap;
+    int prefetch;             // single-channel kernel: next strip's loads fly during compute
+    int xs_buf;               // floats per LDS input buffer
+    int mode;   // TEMP ablation: 1 skip staging, 2 skip compute, 4 skip stores
+    int xs_stride;            // floats per staged row: N rounded up to 4, plus 8
+    unsigned off[4];
+};
+
+constexpr int R_ITEMS = 8;    // (row, group) pairs per lane
+constexpr int R_PAD = 4;      // slack floats left of each staged row (and at least as many right)
+
+// One aligned group of row parity r whose first output has column parity `par`.
+// rowp: staged input row i + r of this output row, at column 0.  cbase: first window column.
+template <int n, int r, int par>
+__device__ __forceinline__ void rows_group(float4 &acc, const float *__restrict__ rowp, int xs_stride, int cbase,
+                                           const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
+{
+    constexpr int fl = n / 2;
+    constexpr int Ta = r ? n / 2 : (n + 1) / 2;
+    constexpr int Tb0 = (n + 1) / 2, Tb1 = n / 2;
+    float win[Ta > 0 ? Ta : 1][fl + 2];
+#pragma unroll
+    for (int a = 0; a < Ta; ++a)
+#pragma unroll
+        for (int c = 0; c < fl + 2; ++c) win[a][c] = rowp[a * xs_stride + cbase + c];
+    // Output k of the group has column parity s_k and starts its taps at window column c_k.
+    constexpr int s_k[4] = {par, 1 - par, par, 1 - par};
+    constexpr int c_k[4] = {0, par ? 0 : 1, 1, par ? 1 : 2};
+    float o[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int Tb = s_k[k] ? Tb1 : Tb0;
+#pragma unroll
+        for (int a = 0; a < Ta; ++a)
+#pragma unroll
+            for (int bq = 0; bq < Tb; ++bq) o[k] = fmaf(win[a][c_k[k] + bq], wk[r][s_k[k]][a * Tb + bq], o[k]);
+    }
+    acc = make_float4(o[0], o[1], o[2], o[3]);
+}
+
+// Shared prologue of the two row-strip kernels: strip geometry and input staging.
+struct RowsGeom {
+    int plane, b, co, y0, i0, rows_out, rows_in;
+    size_t plane_base;
+};
+
+__device__ __forceinline__ void rows_geometry(const RowsParams &p, int fl, unsigned logical, RowsGeom &g)
+{
+    g.plane = (int)(logical / (unsigned)p.chunks_per_plane);
+    const int chunk = (int)(logical - (unsigned)g.plane * p.chunks_per_plane);
+    g.b = g.plane / p.Cout;
+    g.co = g.plane - g.b * p.Cout;
+    g.y0 = chunk * p.R;
+    g.i0 = g.y0 >> 1;
+    g.rows_out = min(p.R, p.M - g.y0);
+    g.rows_in = min(p.R / 2 + fl, p.N - g.i0);
+    g.plane_base = (size_t)g.plane * p.M * p.M;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs.  With xcd_remap each XCD gets one
+// contiguous eighth of the strips, so that neighbouring strips share halo rows in its L2.
+__device__ __forceinline__ unsigned rows_logical_chunk(const RowsParams &p)
+{
+    return p.xcd_remap ? (blockIdx.x & 7u) * p.xcd_slots + (blockIdx.x >> 3) : blockIdx.x;
+}
+
+// Stage input rows i0 .. i0+rows_in-1 of (b, ci): one contiguous run of the input.
+template <typename T>
+__device__ __forceinline__ void rows_stage(float *__restrict__ Xs, const T *__restrict__ in, const RowsParams &p,
+                                           const RowsGeom &g, int ci)
+{
+    const int tid = threadIdx.x;
+    const T *src = in + (((size_t)g.b * p.Cin + ci) * p.N + g.i0) * p.N;
+    if (sizeof(T) == 4 && (p.N & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+        // All loads of a batch are issued before the first LDS write waits for any of them.
+        const float4 *s4 = reinterpret_cast<const float4 *>(src);
+        const int n4 = p.N >> 2, count4 = g.rows_in * n4;
+        for (int base = 0; base < count4; base += 4 * 256) {
+            float4 tmp[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                tmp[k] = s4[min(base + k * 256 + tid, count4 - 1)];   // clamped: always a valid load
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int v = base + k * 256 + tid;
+                if (v < count4) {
+                    const int rr = v / n4, x4 = v - rr * n4;
+                    *reinterpret_cast<float4 *>(Xs + rr * p.xs_stride + R_PAD + 4 * x4) = tmp[k];
+                }
+            }
+        }
+    } else {
+        const int count = g.rows_in * p.N;
+        for (int base = 0; base < count; base += 4 * 256) {
+            T tmp[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                tmp[k] = src[min(base + k * 256 + tid, count - 1)];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = base + k * 256 + tid;
+                if (e < count) {
+                    const int rr = e / p.N, x = e - rr * p.N;
+                    Xs[rr * p.xs_stride + R_PAD + x] = to_f32(tmp[k]);
+                }
+            }
+        }
+    }
+}
+
+template <int n, typename T>
+__device__ __forceinline__ void rows_weights(float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)],
+                                             const T *__restrict__ w_seg, const RowsParams &p, int ci, int co)
+{
+    constexpr int Ta0 = (n + 1) / 2, Ta1 = n / 2;
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int Ta = r ? Ta1 : Ta0, Tb = s ? Ta1 : Ta0;
+#pragma unroll
+            for (int t = 0; t < Ta * Tb; ++t)
+                wk[r][s][t] = to_f32(w_seg[wseg_index<T>(p.off[2 * r + s], Ta * Tb, p.Cout, ci, t, co)]);
+        }
+}
+
+__device__ __forceinline__ void rows_store(float *__restrict__ o, const float4 &v4, int x0, int M)
+{
+    if (x0 >= 0 && x0 + 3 < M) {
+        *reinterpret_cast<float4 *>(o) = v4;                     // 16-byte aligned by construction
+    } else {
+        const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (x0 + k >= 0 && x0 + k < M) o[k] = v[k];
+    }
+}
+
+// One output row of parity r for a single input channel: compute and store at once.
+template <int n, int r>
+__device__ __forceinline__ void rows_emit(float *__restrict__ out, const float *__restrict__ Xs, const RowsParams &p,
+                                          const RowsGeom &g, int row, int shift,
+                                          const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
+{
+    const int y = g.y0 + row;
+    const float *rowp = Xs + ((row >> 1) + r) * p.xs_stride + R_PAD;
+    float *orow = out + g.plane_base + (size_t)y * p.M;
+    for (int t = threadIdx.x; 4 * t - shift < p.M; t += 256) {
+        const int x0 = 4 * t - shift;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!(p.mode & 2)) {
+        if (shift & 1) rows_group<n, r, 1>(acc, rowp, p.xs_stride, ((x0 - 1) >> 1) + 1, wk);
+        else rows_group<n, r, 0>(acc, rowp, p.xs_stride, x0 >> 1, wk);
+        } else acc.x = wk[0][0][0] * t;
+        if (!(p.mode & 4) || acc.x == 1234.5f) rows_store(orow + x0, acc, x0, p.M);
+    }
+}
+
+// Single input channel (the bandwidth-bound case).  Nothing has to be accumulated, so
+// each row is computed and stored straight away and a lane keeps almost no state.
+// The kernel is persistent: a workgroup walks over many strips, and while it computes
+// and stores strip k from one LDS buffer the 16-byte loads of strip k+1 are already in
+// flight into registers (written to the other buffer afterwards, one barrier per
+// strip).  Without that overlap all workgroups of a launch load, compute and store in
+// lock-step and the read and write phases of the whole chip add up instead of overlapping.
+constexpr int R_NLD = 4;      // float4 loads in flight per lane (pre0..pre3): strips of at most 256 * 4 * 4 floats
+
+template <int n, typename T>
+__global__ void __launch_bounds__(256) direct_rows1_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
+                                                             float *__restrict__ out, RowsParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 x [R/2 + fl][xs_stride]
+    const int tid = threadIdx.x;
+    // Strip schedule: with xcd_remap, XCD x owns strips [x * xcd_slots, (x+1) * xcd_slots) and
+    // its workgroups interleave over them; otherwise all workgroups interleave over everything.
+    unsigned c, c_end, stride;
+    if (p.xcd_remap) {
+        const unsigned xcd = blockIdx.x & 7u;
+        c = xcd * p.xcd_slots + (blockIdx.x >> 3);
+        c_end = min((xcd + 1) * p.xcd_slots, p.nchunks);
+        stride = gridDim.x >> 3;
+    } else {
+        c = blockIdx.x;
+        c_end = p.nchunks;
+        stride = gridDim.x;
+    }
+    if (c >= c_end) return;
+
+    RowsGeom g;
+    rows_geometry(p, n / 2, c, g);
+    const int n4 = p.N >> 2;
+    rows_stage<T>(lds, in, p, g, 0);                      // first strip: plain staging
+    __syncthreads();
+
+    float wk[2][2][((n + 1) / 2) * ((n + 1) / 2)];
+    int cur_co = -1;
+    const int mstep = p.M & 3;
+    int buf = 0;
+    while (true) {
+        const unsigned cn = c + stride;
+        const bool more = cn < c_end;
+        // Geometry of the next strip (of this one again after the last: the loads below are
+        // then redundant but still valid, which keeps them unconditional and in registers).
+        RowsGeom gn;
+        rows_geometry(p, n / 2, more ? cn : c, gn);
+        float4 pre0, pre1, pre2, pre3;
+        const int count4 = gn.rows_in * n4;
+        if (p.prefetch) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(in + (((size_t)gn.b * p.Cin) * p.N + gn.i0) * p.N);
+            pre0 = s4[min(tid, count4 - 1)];
+            pre1 = s4[min(256 + tid, count4 - 1)];
+            pre2 = s4[min(512 + tid, count4 - 1)];
+            pre3 = s4[min(768 + tid, count4 - 1)];
+        }
+        if (g.co != cur_co) {
+            rows_weights<n, T>(wk, w_seg, p, 0, g.co);
+            cur_co = g.co;
+        }
+        const float *Xs = lds + buf * p.xs_buf;
+        int shift = (int)((g.plane_base + (size_t)g.y0 * p.M) & 3);
+#pragma unroll 1
+        for (int row = 0; row < g.rows_out; row += 2) {
+            rows_emit<n, 0>(out, Xs, p, g, row, shift, wk);
+            shift = (shift + mstep) & 3;
+            if (row + 1 < g.rows_out) rows_emit<n, 1>(out, Xs, p, g, row + 1, shift, wk);
+            shift = (shift + mstep) & 3;
+        }
+        if (!more) break;
+        float *Xn = lds + (buf ^ 1) * p.xs_buf;
+        if (p.prefetch) {
+            const float4 pre[4] = {pre0, pre1, pre2, pre3};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int v = k * 256 + tid;
+                if (v < count4) {
+                    const int rr = v / n4, x4 = v - rr * n4;
+                    *reinterpret_cast<float4 *>(Xn + rr * p.xs_stride + R_PAD + 4 * x4) = pre[k];
+                }
+            }
+        } else {
+            rows_stage<T>(Xn, in, p, gn, 0);
+        }
+        __syncthreads();
+        g = gn;
+        c = cn;
+        buf ^= 1;
+    }
+}
+
+// Several input channels: per-lane accumulators for R_ITEMS (row, group) pairs persist
+// across the channel loop.  GL = log2(groups per lane per row); R = R_ITEMS >> GL rows.
+template <int n, typename T, int GL>
+__global__ void __launch_bounds__(256) direct_rows_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
+                                                            float *__restrict__ out, RowsParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) float Xs[];   // [R/2 + fl][xs_stride]
+    RowsGeom g;
+    const unsigned logical = rows_logical_chunk(p);
+    if (logical >= p.nchunks) return;
+    rows_geometry(p, n / 2, logical, g);
+    const int tid = threadIdx.x;
+    const int shift0 = (int)((g.plane_base + (size_t)g.y0 * p.M) & 3);
+    const int mstep = p.M & 3;
+
+    float4 acc[R_ITEMS];
+#pragma unroll
+    for (int it = 0; it < R_ITEMS; ++it) acc[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    for (int ci = 0; ci < p.Cin; ++ci) {
+        if (ci) __syncthreads();
+        rows_stage<T>(Xs, in, p, g, ci);
+        float wk[2][2][((n + 1) / 2) * ((n + 1) / 2)];
+        rows_weights<n, T>(wk, w_seg, p, ci, g.co);
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < R_ITEMS; ++it) {
+            constexpr int gmask = (1 << GL) - 1;
+            const int row = it >> GL;
+            if (row >= g.rows_out) continue;                     // uniform
+            const int shift = (shift0 + row * mstep) & 3;
+            const int x0 = 4 * (((it & gmask) << 8) + tid) - shift;
+            if (x0 >= p.M) continue;
+            const float *rowp = Xs + ((row >> 1) + (row & 1)) * p.xs_stride + R_PAD;
+            if (shift & 1) {
+                const int cbase = ((x0 - 1) >> 1) + 1;
+                if (row & 1) rows_group<n, 1, 1>(acc[it], rowp, p.xs_stride, cbase, wk);
+                else rows_group<n, 0, 1>(acc[it], rowp, p.xs_stride, cbase, wk);
+            } else {
+                const int cbase = x0 >> 1;
+                if (row & 1) rows_group<n, 1, 0>(acc[it], rowp, p.xs_stride, cbase, wk);
+                else rows_group<n, 0, 0>(acc[it], rowp, p.xs_stride, cbase, wk);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int it = 0; it < R_ITEMS; ++it) {
+        constexpr int gmask = (1 << GL) - 1;
+        const int row = it >> GL;
+        if (row >= g.rows_out) continue;
+        const int shift = (shift0 + row * mstep) & 3;
+        const int x0 = 4 * (((it & gmask) << 8) + tid) - shift;
+        if (x0 >= p.M) continue;
+        rows_store(out + g.plane_base + (size_t)(g.y0 + row) * p.M + x0, acc[it], x0, p.M);
+    }
+}
+
 // Any kernel size: one lane per quad, operands read straight from global memory.
 template <typename T>
 __global__ void __launch_bounds__(256) direct_generic_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
@@ -165,9 +502,92 @@ static void launch_tiled(const T *in, const T *w_seg, float *out, const DirectPa
     hipLaunchKernelGGL((direct_kernel<n, T>), dim3(blocks), dim3(256), 0, stream, in, w_seg, out, p);
 }
 
+constexpr size_t kRowsLdsLimit = 64 * 1024;
+
+// Strip plan: R output rows per workgroup and 2^gl groups per lane per row with
+// R << gl == R_ITEMS, so that 256 lanes x 2^gl aligned groups cover a row of M (+3) floats.
+template <int n, typename T>
+static bool try_rows(const T *in, const T *w_seg, float *out, const Shape &s, kst_dtype dt, hipStream_t stream)
+{
+    RowsParams p;
+    const int groups = (s.M + 3 + 3) / 4;                      // aligned groups that can touch one row
+    int gl = 0;
+    while ((256 << gl) < groups) ++gl;
+    p.xs_stride = ((s.N + 3) & ~3) + 2 * R_PAD;
+    p.prefetch = 0;
+    size_t lds;
+    unsigned grid;
+    if (s.Cin == 1) {
+        // Tallest strip (up to 16 rows) whose input fits the prefetch registers and 20 KB of LDS.
+        static const int tune = getenv("KST_ROWS_R") ? atoi(getenv("KST_ROWS_R")) : 8;
+        int R = tune;
+        const bool vec = sizeof(T) == 4 && (s.N & 3) == 0;
+        while (R > 2 && ((size_t)(R / 2 + s.fl) * p.xs_stride * sizeof(float) > 20 * 1024 ||
+                         (vec && (size_t)(R / 2 + s.fl) * s.N > (size_t)256 * R_NLD * 4)))
+            R -= 2;
+        p.R = R;
+        p.xs_buf = (R / 2 + s.fl) * p.xs_stride;
+        p.prefetch = vec && (size_t)(R / 2 + s.fl) * s.N <= (size_t)256 * R_NLD * 4;
+        lds = (size_t)2 * p.xs_buf * sizeof(float);
+        if (lds > kRowsLdsLimit) return false;
+    } else {
+        if ((R_ITEMS >> gl) < 2) return false;                 // rows wider than 4 * 256 * 4 floats
+        p.R = R_ITEMS >> gl;
+        p.xs_buf = (p.R / 2 + s.fl) * p.xs_stride;
+        lds = (size_t)p.xs_buf * sizeof(float);
+        if (lds > kRowsLdsLimit) return false;
+    }
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M;
+    p.chunks_per_plane = (s.M + p.R - 1) / p.R;
+    const size_t nchunks = (size_t)s.B * s.Cout * p.chunks_per_plane;
+    if (nchunks >= 0x7ffffff0u) return false;
+    p.nchunks = (unsigned)nchunks;
+    p.xcd_slots = (p.nchunks + 7) / 8;
+    static const int xr = getenv("KST_XCD") ? atoi(getenv("KST_XCD")) : 1;
+    p.xcd_remap = xr;
+    static const int md = getenv("KST_MODE") ? atoi(getenv("KST_MODE")) : 0;
+    p.mode = md;
+    for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
+    const dim3 block(256);
+    if (s.Cin == 1) {
+        // Persistent: a few workgroups per CU, each walking over its share of the strips.
+        static const int wgs = getenv("KST_WGS") ? atoi(getenv("KST_WGS")) : 2048;
+        grid = (unsigned)wgs;
+        if (grid > p.xcd_slots * 8) grid = p.xcd_slots * 8;
+        grid = grid < 8 ? 8 : (grid & ~7u);                    // whole multiples of the 8 XCDs
+        hipLaunchKernelGGL((direct_rows1_kernel<n, T>), dim3(grid), block, lds, stream, in, w_seg, out, p);
+        return true;
+    }
+    grid = p.xcd_slots * 8;
+    if (gl == 0)
+        hipLaunchKernelGGL((direct_rows_kernel<n, T, 0>), dim3(grid), block, lds, stream, in, w_seg, out, p);
+    else if (gl == 1)
+        hipLaunchKernelGGL((direct_rows_kernel<n, T, 1>), dim3(grid), block, lds, stream, in, w_seg, out, p);
+    else
+        hipLaunchKernelGGL((direct_rows_kernel<n, T, 2>), dim3(grid), block, lds, stream, in, w_seg, out, p);
+    return true;
+}
+
+template <typename T>
+static bool run_rows(const T *in, const T *w_seg, float *out, const Shape &s, kst_dtype dt, hipStream_t stream)
+{
+    switch (s.n) {
+        case 1: return try_rows<1, T>(in, w_seg, out, s, dt, stream);
+        case 2: return try_rows<2, T>(in, w_seg, out, s, dt, stream);
+        case 3: return try_rows<3, T>(in, w_seg, out, s, dt, stream);
+        case 4: return try_rows<4, T>(in, w_seg, out, s, dt, stream);
+        case 5: return try_rows<5, T>(in, w_seg, out, s, dt, stream);
+        case 6: return try_rows<6, T>(in, w_seg, out, s, dt, stream);
+        case 7: return try_rows<7, T>(in, w_seg, out, s, dt, stream);
+        default: return false;
+    }
+}
+
 template <typename T>
 static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, kst_dtype dt, hipStream_t stream)
 {
+    static const int no_rows = getenv("KST_NO_ROWS") ? 1 : 0;
+    if (!no_rows && run_rows<T>(in, w_seg, out, s, dt, stream)) return hipGetLastError();
     DirectParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.E = s.E;
     p.tiles_x = (s.E + D_TJ - 1) / D_TJ;
@@ -196,6 +616,12 @@ static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, k
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream)
 {
+    FlatParams fp;
+    unsigned grid;
+    size_t lds;
+    static const int no_flat = getenv("KST_NO_FLAT") ? 1 : 0;
+    if (!no_flat && direct_flat_plan(s, dt, fp, grid, lds))
+        return launch_direct_flat((const float *)in, (const float *)w_seg, out, s, fp, grid, lds, stream);
     if (dt == KST_BF16) return run<uint16_t>((const uint16_t *)in, (const uint16_t *)w_seg, out, s, dt, stream);
     return run<float>((const float *)in, (const float *)w_seg, out, s, dt, stream);
 }

@@ -151,6 +151,26 @@ def test_direct_multi_tile(B, Cin, Cout, N, n, dtype):
     check_layer(layer, paths=("direct", "forward"), seed=N + n)
 
 
+@pytest.mark.parametrize("B,Cout,N,n", [
+    (2, 3, 100, 5),     # M = 195: planes end off 16-byte boundaries, several output channels
+    (3, 2, 64, 4),      # even kernel
+    (5, 1, 48, 3),      # M*M just above one block: most blocks touch two planes
+    (1, 2, 200, 7),
+    (2, 2, 52, 1),      # n = 1: three empty sub-kernels, zeros must still be written
+    (3, 1, 60, 2),
+    (1, 3, 96, 6),
+    (2, 1, 512, 5),     # the headline layer's map size
+])
+def test_direct_single_channel_flat_kernel(B, Cout, N, n):
+    """fp32, one input channel, N a multiple of 4: the persistent flat-output kernel."""
+    layer = wl.Layer("flat", B, 1, Cout, N, n, "f32", "normal", w_std=0.3)
+    check_layer(layer, paths=("direct", "forward"), seed=N * 3 + n)
+    layer = wl.Layer("flat_int", B, 1, Cout, N, n, "f32", "integer")
+    x, w, res = run_paths(layer, ("direct",), seed=N + n)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w))
+    assert np.array_equal(res["direct"].astype(np.float64), want)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Cin,Cout,N,n", [
     (5, 20, 150, 12, 4),    # 2 channel tiles (ragged), tiles straddle batch items
