@@ -137,6 +137,184 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__res
     igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
 }
 
+// ---------------------------------------------------------------------------
+// Pipelined variant (N and Cout multiples of 4): the same tile and MFMA loop,
+// but operands are staged with 16-byte loads whose addresses are worked out
+// once per lane before the channel loop, and the loads of chunk k+1 are in
+// flight (into registers) while chunk k is multiplied out of LDS.
+// ---------------------------------------------------------------------------
+constexpr int P_NX4 = 2;         // input float4 per lane per chunk at most
+
+template <int n>
+__global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *__restrict__ in,
+                                                                     const float *__restrict__ w_seg,
+                                                                     float *__restrict__ dst, IgemmParams p)
+{
+    constexpr int fl = n / 2;
+    constexpr int NN = n * n;
+    constexpr int W4 = G_KC * NN * (G_TCO / 4);                  // weight float4 per chunk
+    constexpr int NW4 = (W4 + G_THREADS - 1) / G_THREADS;        // ... per lane
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int xplane = p.lrows * p.N;                            // floats per staged channel (multiple of 4)
+    float *Xs = lds;                                             // [G_KC][xplane]
+    float *Ws = lds + G_KC * xplane;                             // [G_KC][NN][G_TCO]
+
+    unsigned id = blockIdx.x;
+    const int tile_m = (int)(id % (unsigned)p.tiles_m);
+    id /= (unsigned)p.tiles_m;
+    const int tile_co = (int)(id % (unsigned)p.tiles_co);
+    const int split = (int)(id / (unsigned)p.tiles_co);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wco = wave & 1, wpos = wave >> 1;
+
+    const int m0 = tile_m * G_TM;
+    const int co0 = tile_co * G_TCO;
+    const int b0 = m0 / p.EE;
+    const int i0 = (m0 - b0 * p.EE) / p.E;
+    const int R0 = b0 * p.N + i0;
+
+    int m = m0 + wpos * 32 + l32;
+    const bool m_valid = m < p.Mtot;
+    if (!m_valid) m = p.Mtot - 1;
+    const int mb = m / p.EE;
+    const int mrem = m - mb * p.EE;
+    const int mi = mrem / p.E, mj = mrem - mi * p.E;
+    const int xbase = ((mb * p.N + mi) - R0) * p.N + mj + kk * xplane;
+    const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
+
+    const int ci_begin = split * p.ci_per_split;
+    const int ci_end = min(p.Cin, ci_begin + p.ci_per_split);
+
+    // ---- staging plan: where each of this lane's float4 comes from and goes to -------------
+    unsigned w_off[NW4], w_inc[NW4];
+    int w_c[NW4];                                   // channel within the chunk, or 1 << 20 when unused
+#pragma unroll
+    for (int k = 0; k < NW4; ++k) {
+        const int e4 = tid + k * G_THREADS;
+        const int tco4 = e4 & (G_TCO / 4 - 1);
+        const int rest = e4 / (G_TCO / 4);
+        const int T = rest % NN, c = rest / NN;
+        int cls = 0;
+#pragma unroll
+        for (int q = 1; q < 4; ++q)
+            if (T >= class_tap_base(n, q)) cls = q;
+        const int Tp = cls == 0 ? class_taps(n, 0) : cls == 1 ? class_taps(n, 1) : cls == 2 ? class_taps(n, 2) : class_taps(n, 3);
+        const int tb = cls == 0 ? 0 : cls == 1 ? class_tap_base(n, 1) : cls == 2 ? class_tap_base(n, 2) : class_tap_base(n, 3);
+        const bool ok = e4 < W4 && co0 + 4 * tco4 < p.Cout;
+        w_off[k] = p.off[cls] + ((unsigned)(ci_begin + c) * Tp + (T - tb)) * p.Cout + co0 + 4 * tco4;
+        w_inc[k] = (unsigned)G_KC * Tp * p.Cout;
+        w_c[k] = ok ? c : (1 << 20);
+    }
+    const int xp4 = xplane >> 2, n4 = p.N >> 2;
+    unsigned x_off[P_NX4];
+    int x_c[P_NX4];
+#pragma unroll
+    for (int k = 0; k < P_NX4; ++k) {
+        const int e4 = tid + k * G_THREADS;
+        const int c = e4 / xp4;
+        const int rem = e4 - c * xp4;
+        const int lr = rem / n4, x4 = rem - lr * n4;
+        const int R = R0 + lr;
+        const int bb = R / p.N, y = R - bb * p.N;
+        const bool ok = e4 < G_KC * xp4 && bb < p.B;
+        x_off[k] = (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.N + 4 * x4;
+        x_c[k] = ok ? c : (1 << 20);
+    }
+    const unsigned x_inc = (unsigned)G_KC * p.N * p.N;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
+
+    float4 w_reg[NW4], x_reg[P_NX4];
+    // Chunk at ci_begin -> registers -> LDS.
+#pragma unroll
+    for (int k = 0; k < NW4; ++k)
+    {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ci_begin + w_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(w_seg + w_off[k]);
+        w_reg[k] = v;
+    }
+#pragma unroll
+    for (int k = 0; k < P_NX4; ++k)
+    {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ci_begin + x_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(in + x_off[k]);
+        x_reg[k] = v;
+    }
+#pragma unroll
+    for (int k = 0; k < NW4; ++k)
+        if (tid + k * G_THREADS < W4) reinterpret_cast<float4 *>(Ws)[tid + k * G_THREADS] = w_reg[k];
+#pragma unroll
+    for (int k = 0; k < P_NX4; ++k)
+        if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = x_reg[k];
+    __syncthreads();
+
+    for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
+        // Next chunk's loads (all-zero past the end of this split's channels).
+        const int cn = ci0 + G_KC;
+#pragma unroll
+        for (int k = 0; k < NW4; ++k) {
+            w_off[k] += w_inc[k];
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (cn + w_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(w_seg + w_off[k]);
+            w_reg[k] = v;
+        }
+#pragma unroll
+        for (int k = 0; k < P_NX4; ++k) {
+            x_off[k] += x_inc;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (cn + x_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(in + x_off[k]);
+            x_reg[k] = v;
+        }
+
+#pragma unroll
+        for (int c2 = 0; c2 < G_KC; c2 += 2) {
+            float xf[fl + 1][fl + 1];
+#pragma unroll
+            for (int dy = 0; dy <= fl; ++dy)
+#pragma unroll
+                for (int dx = 0; dx <= fl; ++dx)
+                    xf[dy][dx] = Xs[c2 * xplane + xbase + dy * p.N + dx];
+#pragma unroll
+            for (int cls = 0; cls < 4; ++cls) {
+                const int r = cls >> 1, s = cls & 1;
+                const int Ta = taps_for_parity(n, r), Tb = taps_for_parity(n, s);
+#pragma unroll
+                for (int a = 0; a < Ta; ++a)
+#pragma unroll
+                    for (int bq = 0; bq < Tb; ++bq) {
+                        const int T = class_tap_base(n, cls) + a * Tb + bq;
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const float wf = Ws[(c2 * NN + T) * G_TCO + wbase + h * 32];
+                            acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, xf[r + a][s + bq], acc[cls][h], 0, 0, 0);
+                        }
+                    }
+            }
+        }
+        if (cn >= ci_end) break;
+        __syncthreads();                                         // every wave is done reading this chunk
+#pragma unroll
+        for (int k = 0; k < NW4; ++k)
+            if (tid + k * G_THREADS < W4) reinterpret_cast<float4 *>(Ws)[tid + k * G_THREADS] = w_reg[k];
+#pragma unroll
+        for (int k = 0; k < P_NX4; ++k)
+            if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = x_reg[k];
+        __syncthreads();
+    }
+
+    if (!m_valid) return;
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
+}
+
 // Sum the per-split partial outputs (fixed order: deterministic).
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ ws, float *__restrict__ out,
                                                               size_t elems, int splits)
@@ -177,7 +355,19 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)p.tiles_m * p.tiles_co * p.splits;
-    hipLaunchKernelGGL(igemm_f32_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    // The pipelined kernel wants 16-byte rows and fits its input chunk in P_NX4 loads per lane.
+    const bool pipe = (p.N & 3) == 0 && (p.Cout & 3) == 0 &&
+                      (size_t)G_KC * p.lrows * p.N / 4 <= (size_t)P_NX4 * G_THREADS;
+    if (pipe) {
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(igemm_f32_pipe_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    } else {
+        hipLaunchKernelGGL(igemm_f32_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    }
     return hipGetLastError();
 }
 
