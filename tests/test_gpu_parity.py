@@ -187,6 +187,19 @@ def test_igemm_multi_tile(B, Cin, Cout, N, n, dtype):
                 skip_unsupported_igemm=(n == 7 and dtype == "bf16"))
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (3, 40, 130, 34, 4),    # E = 32: four quad rows per strip, ragged channel tile
+    (2, 24, 40, 64, 2),     # E = 63 with an even kernel (M = 126)
+    (1, 17, 33, 50, 1),     # n = 1, Cin not a multiple of 8 or 16
+    (2, 9, 16, 128, 3),     # E = 127: one quad row per strip
+    (2, 48, 32, 22, 3),     # E = 20: six quad rows per strip, last strip short
+])
+def test_igemm_bf16_row_strip_kernel(B, Cin, Cout, N, n):
+    """bf16 maps whose quad rows hold 16..128 quads take the row-strip matrix-core kernel."""
+    layer = wl.Layer("strip", B, Cin, Cout, N, n, "bf16", "relu_normal", w_std=0.1)
+    check_layer(layer, paths=("igemm", "forward", "direct"), seed=N * 5 + n)
+
+
 # ----------------------------------------------------------------------------
 # Boundary behaviour: nothing outside `out` is written; results are reproducible
 # ----------------------------------------------------------------------------
