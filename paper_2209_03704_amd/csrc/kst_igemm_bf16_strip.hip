@@ -4,15 +4,18 @@
 // GEMMs on v_mfma_f32_32x32x16_bf16, fp32 accumulation), organised for maps whose
 // quad rows are at most 128 quads wide:
 //   * a workgroup owns TI whole quad rows of one batch item (TI * E <= 128 quad
-//     positions) for 128 output channels, so its input is TI + fl full rows (one
+//     positions) for 64 output channels, so its input is TI + fl full rows (one
 //     contiguous run per channel) and its output is 2*TI full rows per channel;
-//   * 8 waves, each 32 channels x 64 positions x 4 parity classes (128 fp32
+//   * 4 waves, each 32 channels x 64 positions x 4 parity classes (128 fp32
 //     accumulators): one weight fragment feeds two position blocks, which keeps
-//     the LDS read traffic per MFMA low enough for the bf16 MFMA rate;
+//     the LDS read traffic per MFMA low enough for the bf16 MFMA rate; two such
+//     workgroups share a CU, so one's epilogue overlaps the other's MFMA loop;
 //   * operands of chunk k+1 travel from HBM into registers while chunk k is
 //     multiplied out of LDS; the input is transposed from NCHW to [pixel][ci]
 //     on the way (eight 4-byte loads of one pixel pair, eight channels -> two
 //     16-byte LDS writes).
+#include <cstdlib>
+
 #include "kst_igemm_common.h"
 
 namespace kst {
@@ -21,11 +24,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
-constexpr int S_THREADS = 512;
-constexpr int S_TCO = 128;
+constexpr int S_THREADS = 256;
+constexpr int S_TCO = 64;
 constexpr int S_KC = 16;               // channels per chunk = one MFMA reduction step
 constexpr int S_XS = S_KC + 8;         // LDS pixel stride in bf16 (48 bytes)
-constexpr int S_NXU = 1;               // (pixel pair, channel octet) units per lane per chunk at most
+constexpr int S_NXU = 2;               // (pixel pair, channel octet) units per lane per chunk at most
 
 struct StripParams {
     int B, Cin, Cout, N, M, E;
@@ -33,10 +36,11 @@ struct StripParams {
     int lrows, npix;
     int cin_oct;
     unsigned off[4];
+    int mode;   // TEMP ablation
 };
 
 template <int n>
-__global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint16_t *__restrict__ in,
+__global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const uint16_t *__restrict__ in,
                                                                        const uint16_t *__restrict__ w_seg,
                                                                        float *__restrict__ out, StripParams p)
 {
@@ -59,7 +63,7 @@ __global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint1
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, kk = lane >> 5;
-    const int wco = wave & 3, wpos = wave >> 2;
+    const int wco = wave & 1, wpos = wave >> 1;
 
     // This lane's two quad positions (clamped: every LDS read stays inside the staged rows).
     int ti[2], tj[2], xbase[2];
@@ -76,14 +80,14 @@ __global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint1
     const int wbase = kk * S_TCO + wco * 32 + l32;
 
     // ---- staging plan ------------------------------------------------------------------------
-    // Weights: lane -> (tap parity, octet, channel), unit k -> tap 2k + (tid >> 8): one 16-byte group each.
+    // Weights: lane -> (tap parity, octet, channel), unit k -> tap 2k + (tid >> 7): one 16-byte group each.
     constexpr int NWU = (NN + 1) / 2;
-    const int w_oc = (tid >> 7) & 1, w_co = tid & 127;
+    const int w_oc = (tid >> 6) & 1, w_co = tid & 63;
     unsigned w_off[NWU], w_inc[NWU];
     bool w_ok[NWU];
 #pragma unroll
     for (int k = 0; k < NWU; ++k) {
-        const int T = 2 * k + (tid >> 8);
+        const int T = 2 * k + (tid >> 7);
         int cls = 0;
 #pragma unroll
         for (int q = 1; q < 4; ++q)
@@ -147,7 +151,7 @@ __global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint1
     auto store_chunk = [&]() {
 #pragma unroll
         for (int k = 0; k < NWU; ++k)
-            if (2 * k + (tid >> 8) < NN) Ws[k * S_THREADS + tid] = w_reg[k];
+            if (2 * k + (tid >> 7) < NN) Ws[k * S_THREADS + tid] = w_reg[k];
 #pragma unroll
         for (int k = 0; k < S_NXU; ++k) {
             if (tid + k * S_THREADS < 2 * npairs) {
@@ -166,7 +170,7 @@ __global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint1
     store_chunk();
     __syncthreads();
 
-    for (int ci0 = 0; ci0 < p.Cin; ci0 += S_KC) {
+    for (int ci0 = 0; ci0 < ((p.mode & 2) ? S_KC : p.Cin); ci0 += S_KC) {
         const int cn = ci0 + S_KC;
         if (cn < p.Cin) load_chunk(cn);
 
@@ -204,7 +208,7 @@ __global__ void __launch_bounds__(S_THREADS) igemm_bf16_strip_kernel(const uint1
     typedef float float2u __attribute__((ext_vector_type(2), aligned(4)));
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb) {
-        if (!pos_ok[pb]) continue;
+        if (!pos_ok[pb] || ((p.mode & 4) && acc[0][0][0] != 1234.5f)) continue;
         const int gi = i0 + ti[pb], gj = tj[pb];
         const bool x1_ok = 2 * gj + 1 < p.M;
 #pragma unroll
@@ -240,6 +244,8 @@ bool strip_plan(const Shape &s, StripParams &p, size_t &lds)
     if (p.npix > S_NXU * S_THREADS) return false;             // (npix / 2 pairs) * 2 octets units
     p.cin_oct = (s.Cin + 7) / 8;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
+    static const int md = getenv("KST_MODE") ? atoi(getenv("KST_MODE")) : 0;
+    p.mode = md;
     lds = (size_t)p.npix * S_XS * 2 + (size_t)s.n * s.n * 2 * S_TCO * 16;
     return lds <= 160 * 1024 && (size_t)s.B * p.tiles_co * p.strips < 0x7fffffffu;
 }
