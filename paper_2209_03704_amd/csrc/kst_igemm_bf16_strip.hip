@@ -14,8 +14,6 @@
 //     multiplied out of LDS; the input is transposed from NCHW to [pixel][ci]
 //     on the way (eight 4-byte loads of one pixel pair, eight channels -> two
 //     16-byte LDS writes).
-#include <cstdlib>
-
 #include "kst_igemm_common.h"
 
 namespace kst {
@@ -35,8 +33,9 @@ struct StripParams {
     int TI, strips, tiles_co;
     int lrows, npix;
     int cin_oct;
+    int estride;            // floats per channel in the epilogue's LDS image (multiple of 4)
+    int tg;                 // 16-byte groups per channel run, upper bound
     unsigned off[4];
-    int mode;   // TEMP ablation
 };
 
 template <int n>
@@ -94,12 +93,12 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
             if (T >= class_tap_base(n, q)) cls = q;
         const int Tp = class_taps(n, cls), t = T - class_tap_base(n, cls);
         w_ok[k] = T < NN && co0 + w_co < p.Cout;
-        w_off[k] = p.off[cls] + (((unsigned)w_oc * Tp + t) * p.Cout + co0 + w_co) * 8u;
-        w_inc[k] = 2u * Tp * p.Cout * 8u;
+        w_off[k] = w_ok[k] ? p.off[cls] + (((unsigned)w_oc * Tp + t) * p.Cout + co0 + w_co) * 8u : 0u;
+        w_inc[k] = w_ok[k] ? 2u * Tp * p.Cout * 8u : 0u;
     }
     // Input: unit -> (pixel pair, octet); eight channels of the pair are loaded as 4-byte words.
     const int npairs = p.npix >> 1;
-    unsigned x_off[S_NXU];
+    unsigned x_off[S_NXU], x_incv[S_NXU];
     int x_dst[S_NXU], x_oc[S_NXU];
     bool x_ok[S_NXU];
 #pragma unroll
@@ -110,10 +109,10 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
         const int lr = pix / p.N, x = pix - lr * p.N;
         x_ok[k] = e < 2 * npairs && i0 + lr < p.N;
         x_oc[k] = oc;
-        x_off[k] = ((((unsigned)b * p.Cin + oc * 8) * p.N + i0 + lr) * p.N + x);
+        x_off[k] = x_ok[k] ? ((((unsigned)b * p.Cin + oc * 8) * p.N + i0 + lr) * p.N + x) : 0u;
+        x_incv[k] = x_ok[k] ? (unsigned)S_KC * p.N * p.N : 0u;
         x_dst[k] = pix * S_XS + oc * 8;
     }
-    const unsigned x_inc = (unsigned)S_KC * p.N * p.N;
     const unsigned plane = (unsigned)p.N * p.N;
 
     floatx16 acc[4][2];
@@ -145,7 +144,7 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
                     v = *reinterpret_cast<const unsigned *>(in + x_off[k] + c * plane);
                 x_reg[k][c] = v;
             }
-            x_off[k] += x_inc;
+            x_off[k] += x_incv[k];
         }
     };
     auto store_chunk = [&]() {
@@ -170,7 +169,7 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
     store_chunk();
     __syncthreads();
 
-    for (int ci0 = 0; ci0 < ((p.mode & 2) ? S_KC : p.Cin); ci0 += S_KC) {
+    for (int ci0 = 0; ci0 < p.Cin; ci0 += S_KC) {
         const int cn = ci0 + S_KC;
         if (cn < p.Cin) load_chunk(cn);
 
@@ -204,31 +203,62 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
         __syncthreads();
     }
 
-    // ---- epilogue: the four classes of a quad sit side by side; lanes run along a row --------
-    typedef float float2u __attribute__((ext_vector_type(2), aligned(4)));
+    // ---- epilogue -----------------------------------------------------------------------------
+    // Per output channel the strip is one contiguous run of rows_out * M floats.  The four
+    // classes are interleaved into that run in LDS, 32 channels per pass, and streamed out
+    // with 16-byte stores whose lane quads sit in one 64-byte segment (lane t of a channel
+    // owns floats [base64 + 4t, +4), base64 = run start rounded down to 64 bytes); only the
+    // groups cut by the ends of a run use scalar stores.
+    float *Es = reinterpret_cast<float *>(lds_raw);                 // [32][estride]
+    const int rows_out = min(2 * rows_q, p.M - 2 * i0);
+    const int L = rows_out * p.M;
+    const unsigned MM = (unsigned)p.M * p.M;
+    const unsigned g_first = (((unsigned)b * p.Cout + co0) * p.M + 2 * i0) * p.M;   // run start of channel co0
+    for (int pass = 0; pass < 2; ++pass) {
+        __syncthreads();                                             // LDS is free: K loop / previous pass read it
+        const int nco = min(32, p.Cout - (co0 + pass * 32));
+        if (nco <= 0) break;                                         // uniform
+        if (wco == pass) {
 #pragma unroll
-    for (int pb = 0; pb < 2; ++pb) {
-        if (!pos_ok[pb] || ((p.mode & 4) && acc[0][0][0] != 1234.5f)) continue;
-        const int gi = i0 + ti[pb], gj = tj[pb];
-        const bool x1_ok = 2 * gj + 1 < p.M;
+            for (int pb = 0; pb < 2; ++pb) {
+                if (!pos_ok[pb]) continue;
+                const bool x1_ok = 2 * tj[pb] + 1 < p.M;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int co = co0 + wco * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
-                if (co >= p.Cout) continue;
+                for (int v = 0; v < 16; ++v) {
+                    const int cl = 8 * (v >> 2) + 4 * kk + (v & 3);
+                    if (cl >= nco) continue;
+                    const unsigned g_co = g_first + (unsigned)(pass * 32 + cl) * MM;
+                    float *e = Es + cl * p.estride + (g_co & 3u) + 2 * ti[pb] * p.M + 2 * tj[pb];
 #pragma unroll
-                for (int r = 0; r < 2; ++r) {
-                    const int y = 2 * gi + r;
-                    if (y >= p.M) continue;
-                    float *q = out + (((size_t)b * p.Cout + co) * p.M + y) * p.M + 2 * gj;
-                    const float v0 = acc[2 * r][pb][v], v1 = acc[2 * r + 1][pb][v];
-                    if (x1_ok) {
-                        float2u pair = {v0, v1};
-                        *reinterpret_cast<float2u *>(q) = pair;
-                    } else {
-                        q[0] = v0;
+                    for (int r = 0; r < 2; ++r) {
+                        if (2 * ti[pb] + r >= rows_out) continue;
+                        e[r * p.M] = acc[2 * r][pb][v];
+                        if (x1_ok) e[r * p.M + 1] = acc[2 * r + 1][pb][v];
                     }
                 }
             }
+        }
+        __syncthreads();
+        // Wave w streams channels w, w + 4, ...; its lanes walk the channel's 16-byte groups.
+        for (int cl = wave; cl < nco; cl += S_THREADS / 64) {
+            const unsigned g_co = g_first + (unsigned)(pass * 32 + cl) * MM;
+            const unsigned base64 = g_co & ~15u;
+            const float *erow = Es + cl * p.estride + (int)(g_co & 3u);
+            for (int t = lane; t < p.tg; t += 64) {
+                const unsigned f0 = base64 + 4u * t;
+                const int rel = (int)(f0 - g_co);
+                if (rel + 3 < 0 || rel >= L) continue;
+                const float *src = erow + rel;                       // 16-byte aligned
+                float *dst = out + f0;
+                if (rel >= 0 && rel + 3 < L) {
+                    *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (rel + k >= 0 && rel + k < L) dst[k] = src[k];
+                }
+            }
+        }
     }
 }
 
@@ -244,9 +274,12 @@ bool strip_plan(const Shape &s, StripParams &p, size_t &lds)
     if (p.npix > S_NXU * S_THREADS) return false;             // (npix / 2 pairs) * 2 octets units
     p.cin_oct = (s.Cin + 7) / 8;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
-    static const int md = getenv("KST_MODE") ? atoi(getenv("KST_MODE")) : 0;
-    p.mode = md;
+    const int Lmax = 2 * p.TI * s.M;
+    p.estride = (Lmax + 3 + 3) & ~3;
+    p.tg = (15 + Lmax - 1) / 4 + 1;
     lds = (size_t)p.npix * S_XS * 2 + (size_t)s.n * s.n * 2 * S_TCO * 16;
+    const size_t lds_epi = (size_t)32 * p.estride * sizeof(float);
+    if (lds_epi > lds) lds = lds_epi;
     return lds <= 160 * 1024 && (size_t)s.B * p.tiles_co * p.strips < 0x7fffffffu;
 }
 
