@@ -10,13 +10,14 @@ struct FlatParams {
     unsigned MM;            // M * M
     unsigned total;         // B * Cout * M * M (below 2^31)
     unsigned nblocks;       // ceil(total / CH)
-    unsigned vblocks;       // nblocks rounded up to whole XCD runs
-    unsigned run;           // consecutive blocks handed to one XCD
-    int dx, dy;             // step = dy * M + dx: how (row, column) move per workgroup iteration
+    // How (plane, row, column) move when the flat index advances by ...
+    int g_plane, g_y, g_x;  // ... gridDim.x * CH floats (a workgroup's next block)
+    int s_y, s_x;           // ... one workgroup iteration (4 * threads floats)
+    int c_y, c_x;           // ... CH - 1 floats (first to last float of a full block)
+    int fast;               // M >= 256: a wave's 256 floats cross at most one row end
     int max_rows;           // input rows one piece can need
     int xs_stride, xs_buf;  // floats per staged row / per LDS buffer
     unsigned off[4];        // element offset of W_p in the segregated weights
-    int mode;               // TEMP ablation
 };
 
 // False when the shape is outside what the kernel covers (then the caller uses another path).

@@ -27,6 +27,13 @@
 // other buffer afterwards, one barrier per piece.  Without this all
 // workgroups of a launch load, compute and store in lock-step and the read
 // and write phases of the whole chip add up instead of overlapping.
+//
+// Measured on this chip the kernel is bound by instruction issue (about one
+// instruction per SIMD every four cycles, scalar ones included), so all
+// bookkeeping is incremental: block, row and column positions advance by
+// host-computed steps with carries instead of divisions, and a wave whose 256
+// floats lie in one row, or cross exactly one row end, runs code specialised
+// by scalar (r, par) with LDS addresses of the form scalar base + 2 * lane.
 #include <cstdlib>
 
 #include "kst_direct_flat.h"
@@ -47,46 +54,50 @@ static_assert(F_THREADS == 256 || F_THREADS == 512, "two or four float4 per lane
 
 // Flat output indices fit 32 bits: the ABI keeps every tensor below 2^31 elements.
 struct Piece {
+    unsigned j;               // block the piece belongs to
     unsigned fa, fb;          // flat output range of this piece, inside one plane
     unsigned p0;              // flat index of the plane's first element
-    int co;                   // output channel of the plane
-    int ya, yb;               // first / last output row touched
+    int plane;
+    int ya, xa;               // row / column of fa inside the plane
+    int yb;                   // last output row touched
     int ia;                   // first input row staged
     int rows_in;              // input rows staged
+    int full;                 // covers its whole block: fa = j*CH, fb = fa + CH
     const float *src;         // in + first staged row
 };
 
-// Work-unit walk: block j covers flat [j*CH, (j+1)*CH) and is cut at plane ends.
-struct Cursor {
-    unsigned j;               // block
-    unsigned f;               // next flat index to process within block j
+// Position (plane, row, column) of the first float of block j.
+struct BlockPos {
+    unsigned j;
+    int plane, y, x;
 };
 
-__device__ __forceinline__ void piece_at(const FlatParams &p, const float *__restrict__ in, const Cursor &c, Piece &pc)
+__device__ __forceinline__ void finish_piece(const FlatParams &p, const float *__restrict__ in, Piece &pc)
 {
-    const unsigned block_end = min((c.j + 1) * p.CH, p.total);
-    const unsigned plane = c.f / p.MM;
-    pc.p0 = plane * p.MM;
-    pc.fa = c.f;
+    const unsigned block_end = min((pc.j + 1) * p.CH, p.total);
+    pc.p0 = pc.fa - (unsigned)(pc.ya * p.M + pc.xa);
     pc.fb = min(block_end, pc.p0 + p.MM);
-    const int b = (int)(plane / (unsigned)p.Cout);
-    pc.co = (int)(plane - (unsigned)b * p.Cout);
-    pc.ya = (int)((pc.fa - pc.p0) / (unsigned)p.M);
-    pc.yb = (int)((pc.fb - 1 - pc.p0) / (unsigned)p.M);
+    pc.full = pc.fa == pc.j * p.CH && pc.fb - pc.fa == p.CH;
+    if (pc.full) {
+        pc.yb = pc.ya + p.c_y + (pc.xa + p.c_x >= p.M ? 1 : 0);
+    } else {
+        pc.yb = (int)((pc.fb - 1 - pc.p0) / (unsigned)p.M);          // rare: blocks at a plane end
+    }
     pc.ia = pc.ya >> 1;
     const int ib = min(p.N - 1, (pc.yb >> 1) + p.fl);
     pc.rows_in = ib - pc.ia + 1;
-    pc.src = in + ((size_t)b * p.N + pc.ia) * p.N;          // Cin == 1
+    const int b = pc.plane / p.Cout;                                 // Cin == 1: plane -> batch item
+    pc.src = in + ((size_t)b * p.N + pc.ia) * p.N;
 }
 
-// Block schedule.  Workgroups are dealt round-robin to the 8 XCDs; runs of `run`
-// consecutive blocks go to the same XCD so that neighbouring blocks find their
-// shared input rows in that XCD's L2, while the chip as a whole still sweeps the
-// tensor front to back.
-__device__ __forceinline__ unsigned block_of(const FlatParams &p, unsigned v)
+__device__ __forceinline__ void first_piece(const FlatParams &p, const float *__restrict__ in, const BlockPos &bp, Piece &pc)
 {
-    const unsigned xcd = v & 7u, w = v >> 3;
-    return ((w / p.run) * 8u + xcd) * p.run + (w % p.run);
+    pc.j = bp.j;
+    pc.fa = bp.j * p.CH;
+    pc.plane = bp.plane;
+    pc.ya = bp.y;
+    pc.xa = bp.x;
+    finish_piece(p, in, pc);
 }
 
 // One aligned group in output row parity r whose first column has parity par.
@@ -135,6 +146,47 @@ __device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__res
     }
 }
 
+// Segment = the 256 consecutive floats one wave covers in one iteration; it starts at
+// (row y, column xs) and crosses exactly one row end.  Lanes left of the row end compute
+// their group in row y, lanes right of it in row y + 1, the lane on it both.
+template <int n>
+__device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int ia,
+                                              int y, int xs, int lane,
+                                              const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
+{
+    const int x0 = xs + 4 * lane;
+    float oa[4] = {0.f, 0.f, 0.f, 0.f}, ob[4] = {0.f, 0.f, 0.f, 0.f};
+    if (x0 < p.M) {
+        const int r = y & 1;
+        const float *rowp = Xs + ((y >> 1) - ia + r) * p.xs_stride + F_PAD + 2 * lane;
+        if (xs & 1) {
+            const int cbase = ((xs - 1) >> 1) + 1;
+            if (r) flat_group<n, 1, 1>(oa, rowp, p.xs_stride, cbase, wk);
+            else flat_group<n, 0, 1>(oa, rowp, p.xs_stride, cbase, wk);
+        } else {
+            const int cbase = xs >> 1;
+            if (r) flat_group<n, 1, 0>(oa, rowp, p.xs_stride, cbase, wk);
+            else flat_group<n, 0, 0>(oa, rowp, p.xs_stride, cbase, wk);
+        }
+    }
+    if (x0 + 3 >= p.M) {
+        const int y1 = y + 1, xs1 = xs - p.M;                        // negative column: head of the next row
+        const int r = y1 & 1;
+        const float *rowp = Xs + ((y1 >> 1) - ia + r) * p.xs_stride + F_PAD + 2 * lane;
+        if (xs1 & 1) {
+            const int cbase = ((xs1 - 1) >> 1) + 1;
+            if (r) flat_group<n, 1, 1>(ob, rowp, p.xs_stride, cbase, wk);
+            else flat_group<n, 0, 1>(ob, rowp, p.xs_stride, cbase, wk);
+        } else {
+            const int cbase = xs1 >> 1;
+            if (r) flat_group<n, 1, 0>(ob, rowp, p.xs_stride, cbase, wk);
+            else flat_group<n, 0, 0>(ob, rowp, p.xs_stride, cbase, wk);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = x0 + k < p.M ? oa[k] : ob[k];
+}
+
 template <int n>
 __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ w_seg,
@@ -147,17 +199,23 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n4 = p.N >> 2;
 
-    // This workgroup's blocks: v, v + gridDim.x, ... mapped through block_of().
-    unsigned v = blockIdx.x;
-    const unsigned v_end = p.vblocks;
-    Cursor cur;
-    // Skip virtual slots that map past the last block (the run layout rounds up).
-    while (v < v_end && block_of(p, v) >= p.nblocks) v += gridDim.x;
-    if (v >= v_end) return;
-    cur.j = block_of(p, v);
-    cur.f = cur.j * p.CH;
+    // This workgroup's blocks: blockIdx.x, + gridDim.x, ...  The position of the first one costs
+    // the only divisions of the common path; later ones are reached by adding the grid step.
+    BlockPos bp;
+    bp.j = blockIdx.x;
+    if (bp.j >= p.nblocks) return;
+    {
+        const unsigned f = bp.j * p.CH;
+        const unsigned plane = f / p.MM;
+        const unsigned rel = f - plane * p.MM;
+        bp.plane = (int)plane;
+        bp.y = (int)(rel / (unsigned)p.M);
+        bp.x = (int)(rel - (unsigned)bp.y * (unsigned)p.M);
+    }
+    // Row / column offset of this wave's 256 floats inside an iteration.
+    const int w_y = (wave * 256) / p.M, w_x = wave * 256 - w_y * p.M;
 
-    // Where float4 number k*256 + tid of a staged run lands in an LDS buffer (the same for every piece).
+    // Where float4 number k * threads + tid of a staged run lands in an LDS buffer (same for every piece).
     int lds_off[F_NPRE];
 #pragma unroll
     for (int k = 0; k < F_NPRE; ++k) {
@@ -167,7 +225,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     }
 
     Piece pc;
-    piece_at(p, in, cur, pc);
+    first_piece(p, in, bp, pc);
     // First piece: plain staging (all loads issued before the first LDS write).
     {
         const float4 *s4 = reinterpret_cast<const float4 *>(pc.src);
@@ -187,22 +245,40 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     int cur_co = -1;
     int buf = 0;
     while (true) {
-        // ---- where the next piece is, and its loads ------------------------------------------
-        Cursor nxt = cur;
+        // ---- the next piece and its loads --------------------------------------------------------
+        Piece pn;
+        bool more;
         {
-            const unsigned block_end = min((cur.j + 1) * p.CH, p.total);
-            if (pc.fb < block_end) {
-                nxt.f = pc.fb;
+            const unsigned block_end = min((pc.j + 1) * p.CH, p.total);
+            if (pc.fb < block_end) {                              // the plane ended inside the block
+                pn.j = pc.j;
+                pn.fa = pc.fb;
+                pn.plane = pc.plane + 1;
+                pn.ya = 0;
+                pn.xa = 0;
+                more = true;
             } else {
-                v += gridDim.x;
-                while (v < v_end && block_of(p, v) >= p.nblocks) v += gridDim.x;
-                nxt.j = v < v_end ? block_of(p, v) : 0xffffffffu;
-                nxt.f = nxt.j * p.CH;
+                bp.j += gridDim.x;
+                bp.plane += p.g_plane;
+                bp.y += p.g_y;
+                bp.x += p.g_x;
+                if (bp.x >= p.M) { bp.x -= p.M; ++bp.y; }
+                if (bp.y >= p.M) { bp.y -= p.M; ++bp.plane; }
+                more = bp.j < p.nblocks;
+                pn.j = more ? bp.j : pc.j;                        // after the last: reload this block (valid, unused)
+                pn.fa = pn.j * p.CH;
+                pn.plane = more ? bp.plane : pc.plane;
+                pn.ya = more ? bp.y : pc.ya;
+                pn.xa = more ? bp.x : pc.xa;
+                if (!more && pc.fa != pc.j * p.CH) {              // this was a second piece: its block's first
+                    pn.plane = pc.plane - 1;                      // piece started in the previous plane
+                    const unsigned rel = pn.fa - (pc.p0 - p.MM);
+                    pn.ya = (int)(rel / (unsigned)p.M);
+                    pn.xa = (int)(rel - (unsigned)pn.ya * (unsigned)p.M);
+                }
             }
         }
-        const bool more = nxt.j != 0xffffffffu;
-        Piece pn;
-        piece_at(p, in, more ? nxt : cur, pn);      // after the last piece: reload it (valid, unused)
+        finish_piece(p, in, pn);
         const int count4n = pn.rows_in * n4;
         const float4 *s4 = reinterpret_cast<const float4 *>(pn.src);
         const float4 pre0 = s4[min(tid, count4n - 1)];
@@ -211,7 +287,8 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
         const float4 pre3 = F_NPRE > 2 ? s4[min(3 * F_THREADS + tid, count4n - 1)] : pre0;
 
         // ---- weights of this plane's output channel (scalar registers) ----------------------
-        if (pc.co != cur_co) {
+        const int co = pc.plane % p.Cout;
+        if (co != cur_co) {
 #pragma unroll
             for (int r = 0; r < 2; ++r)
 #pragma unroll
@@ -219,66 +296,71 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     const int Ta = r ? Ta1 : Ta0, Tb = s ? Ta1 : Ta0;
 #pragma unroll
                     for (int t = 0; t < Ta * Tb; ++t)
-                        wk[r][s][t] = w_seg[p.off[2 * r + s] + (size_t)t * p.Cout + pc.co];   // Cin == 1
+                        wk[r][s][t] = w_seg[p.off[2 * r + s] + (size_t)t * p.Cout + co];   // Cin == 1
                 }
-            cur_co = pc.co;
+            cur_co = co;
         }
 
         // ---- compute and store this piece -------------------------------------------------------
-        // Wave-level bookkeeping lives in scalar registers: fw is the flat index of the wave's
-        // first float this iteration and (ys, xs) its row and column in floor-division form
-        // (ys < 0 while the wave still starts before the plane).
         const float *Xs = lds + buf * p.xs_buf;
-        const unsigned block_start = cur.j * p.CH;
-        const int it0 = (int)((pc.fa - block_start) >> F_STEP_LOG2), it1 = (int)((pc.fb - 1 - block_start) >> F_STEP_LOG2);
-        unsigned fw = block_start + ((unsigned)it0 << F_STEP_LOG2) + 256u * (unsigned)wave;
-        int ys, xs;
-        {
-            const int K = p.dy + 1;                             // K * M > F_STEP > distance to the plane start
-            const unsigned relp = (unsigned)((int)(fw - pc.p0) + K * p.M);
-            const unsigned q = relp / (unsigned)p.M;
-            ys = (int)q - K;
-            xs = (int)(relp - q * (unsigned)p.M);
-        }
-        for (int it = it0; it <= it1; ++it) {
-            if (fw >= pc.fa && fw + 255 < pc.fb && ys >= 0 && xs + 255 < p.M) {
-                // The whole wave lies in one row and inside the piece: (r, par) are uniform, the
-                // LDS window is a scalar base plus 2 * lane, the store is one full aligned float4.
-                const int r = ys & 1;
-                const float *rowp = Xs + ((ys >> 1) - pc.ia + r) * p.xs_stride + F_PAD + 2 * lane;
+        if (pc.full && p.fast) {
+            // Every wave segment lies inside the piece and the plane.  (y, xs): row and column of
+            // the wave's first float, advanced by one workgroup iteration at a time.
+            int y = pc.ya + w_y, xs = pc.xa + w_x;
+            if (xs >= p.M) { xs -= p.M; ++y; }
+            unsigned fw = pc.fa + 256u * (unsigned)wave;
+#pragma unroll 1
+            for (int it = 0; it < (int)(p.CH / F_STEP); ++it) {
                 float o[4];
-                if (xs & 1) {
-                    const int cbase = ((xs - 1) >> 1) + 1;
-                    if (r) flat_group<n, 1, 1>(o, rowp, p.xs_stride, cbase, wk);
-                    else flat_group<n, 0, 1>(o, rowp, p.xs_stride, cbase, wk);
+                if (xs + 255 < p.M) {
+                    const int r = y & 1;
+                    const float *rowp = Xs + ((y >> 1) - pc.ia + r) * p.xs_stride + F_PAD + 2 * lane;
+                    if (xs & 1) {
+                        const int cbase = ((xs - 1) >> 1) + 1;
+                        if (r) flat_group<n, 1, 1>(o, rowp, p.xs_stride, cbase, wk);
+                        else flat_group<n, 0, 1>(o, rowp, p.xs_stride, cbase, wk);
+                    } else {
+                        const int cbase = xs >> 1;
+                        if (r) flat_group<n, 1, 0>(o, rowp, p.xs_stride, cbase, wk);
+                        else flat_group<n, 0, 0>(o, rowp, p.xs_stride, cbase, wk);
+                    }
                 } else {
-                    const int cbase = xs >> 1;
-                    if (r) flat_group<n, 1, 0>(o, rowp, p.xs_stride, cbase, wk);
-                    else flat_group<n, 0, 0>(o, rowp, p.xs_stride, cbase, wk);
+                    cross_segment<n>(o, Xs, p, pc.ia, y, xs, lane, wk);
                 }
                 *reinterpret_cast<float4 *>(out + fw + 4 * lane) = make_float4(o[0], o[1], o[2], o[3]);
-            } else if (fw + 255 >= pc.fa && fw < pc.fb) {
-                // General path: the wave meets a row end, a plane end or a block edge.
-                const unsigned f0 = fw + 4 * lane;
+                fw += F_STEP;
+                xs += p.s_x;
+                y += p.s_y;
+                if (xs >= p.M) { xs -= p.M; ++y; }
+            }
+        } else {
+            // General path: pieces cut by a plane end, and maps narrower than a wave segment.
+            const unsigned block_start = pc.j * p.CH;
+            const int it0 = (int)((pc.fa - block_start) >> F_STEP_LOG2);
+            const int it1 = (int)((pc.fb - 1 - block_start) >> F_STEP_LOG2);
+            unsigned f0 = block_start + ((unsigned)it0 << F_STEP_LOG2) + 4 * tid;
+            int y, x0;                                           // floor-division form, y may start negative
+            {
+                const int K = p.s_y + 1;                         // K * M > F_STEP > distance to the plane start
+                const unsigned relp = (unsigned)((int)(f0 - pc.p0) + K * p.M);
+                const unsigned q = relp / (unsigned)p.M;
+                y = (int)q - K;
+                x0 = (int)(relp - q * (unsigned)p.M);
+            }
+            for (int it = it0; it <= it1; ++it) {
                 if (f0 + 3 >= pc.fa && f0 < pc.fb) {
-                    int y = ys, x0 = xs + 4 * lane;
-                    if (x0 >= p.M) {
-                        const int qq = x0 / p.M;
-                        y += qq;
-                        x0 -= qq * p.M;
-                    }
                     // A group hanging over the start of the plane is the head of row 0 (negative column).
                     const int yy = y < 0 ? 0 : y, xx = y < 0 ? x0 - p.M : x0;
                     float o[4];
                     flat_row_group<n>(o, Xs, p, pc.ia, yy, xx, wk);
-                    if (xx + 3 >= p.M && yy + 1 <= pc.yb) {     // straddles a row end: head of the next row
+                    if (xx + 3 >= p.M && yy + 1 <= pc.yb) {      // straddles a row end: head of the next row
                         float o2[4];
                         flat_row_group<n>(o2, Xs, p, pc.ia, yy + 1, xx - p.M, wk);
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             if (xx + k >= p.M) o[k] = o2[k];
                     }
-                    float *dst = out + f0;                      // 16-byte aligned
+                    float *dst = out + f0;                       // 16-byte aligned
                     if (f0 >= pc.fa && f0 + 3 < pc.fb) {
                         *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
                     } else {
@@ -287,11 +369,11 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                             if (f0 + k >= pc.fa && f0 + k < pc.fb) dst[k] = o[k];
                     }
                 }
+                f0 += F_STEP;
+                x0 += p.s_x;
+                y += p.s_y;
+                if (x0 >= p.M) { x0 -= p.M; ++y; }
             }
-            fw += F_STEP;
-            xs += p.dx;
-            ys += p.dy;
-            if (xs >= p.M) { xs -= p.M; ++ys; }
         }
         if (!more) break;
 
@@ -303,7 +385,6 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
             if (k * F_THREADS + tid < count4n) *reinterpret_cast<float4 *>(Xn + lds_off[k]) = pre[k];
         __syncthreads();
         pc = pn;
-        cur = nxt;
         buf ^= 1;
     }
 }
@@ -329,10 +410,7 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     p.MM = (unsigned)MM;
     p.total = (unsigned)((long long)s.B * s.Cout * MM);
     p.nblocks = (p.total + CH - 1) / CH;
-    p.run = 8;
-    p.vblocks = ((p.nblocks + 8 * p.run - 1) / (8 * p.run)) * (8 * p.run);
-    p.dy = F_STEP / s.M;
-    p.dx = F_STEP % s.M;
+    p.fast = s.M >= 256;
     // Input rows one piece can need: the rows its output span maps to, plus halo.
     const int span = (int)((CH - 1 + s.M - 1) / s.M);           // yb - ya at most
     p.max_rows = span / 2 + 1 + s.fl + 1;
@@ -343,14 +421,19 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     lds = (size_t)2 * p.xs_buf * sizeof(float);
     if (lds > 64 * 1024) return false;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(1, s.Cout, s.n, c, KST_F32);
+    // One resident round: three 512-lane workgroups per CU on 256 CUs.
     static const int wgs = getenv("KST_WGS") ? atoi(getenv("KST_WGS")) : 768;
     grid = (unsigned)wgs;
-    static const int md = getenv("KST_MODE") ? atoi(getenv("KST_MODE")) : 0;
-    p.mode = md;
-    static const int rn = getenv("KST_RUN") ? atoi(getenv("KST_RUN")) : 8;
-    p.run = rn;
-    p.vblocks = ((p.nblocks + 8 * p.run - 1) / (8 * p.run)) * (8 * p.run);
-    if (grid > p.vblocks) grid = p.vblocks;
+    if (grid > p.nblocks) grid = p.nblocks;
+    const unsigned long long gstep = (unsigned long long)grid * CH;
+    p.g_plane = (int)(gstep / (unsigned long long)MM);
+    const unsigned grem = (unsigned)(gstep % (unsigned long long)MM);
+    p.g_y = (int)(grem / (unsigned)s.M);
+    p.g_x = (int)(grem % (unsigned)s.M);
+    p.s_y = F_STEP / s.M;
+    p.s_x = F_STEP % s.M;
+    p.c_y = (int)((CH - 1) / (unsigned)s.M);
+    p.c_x = (int)((CH - 1) % (unsigned)s.M);
     return true;
 }
 
