@@ -86,8 +86,9 @@ __device__ __forceinline__ void finish_piece(const FlatParams &p, const float *_
     pc.ia = pc.ya >> 1;
     const int ib = min(p.N - 1, (pc.yb >> 1) + p.fl);
     pc.rows_in = ib - pc.ia + 1;
-    const int b = pc.plane / p.Cout;                                 // Cin == 1: plane -> batch item
-    pc.src = in + ((size_t)b * p.N + pc.ia) * p.N;
+    // Cin == 1: plane -> batch item.  32-bit offsets: the input has fewer than 2^31 elements.
+    const unsigned b = p.Cout == 1 ? (unsigned)pc.plane : (unsigned)pc.plane / (unsigned)p.Cout;
+    pc.src = in + (b * (unsigned)p.N + (unsigned)pc.ia) * (unsigned)p.N;
 }
 
 __device__ __forceinline__ void first_piece(const FlatParams &p, const float *__restrict__ in, const BlockPos &bp, Piece &pc)
@@ -246,39 +247,25 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     int buf = 0;
     while (true) {
         // ---- the next piece and its loads --------------------------------------------------------
-        Piece pn;
-        bool more;
-        {
-            const unsigned block_end = min((pc.j + 1) * p.CH, p.total);
-            if (pc.fb < block_end) {                              // the plane ended inside the block
-                pn.j = pc.j;
-                pn.fa = pc.fb;
-                pn.plane = pc.plane + 1;
-                pn.ya = 0;
-                pn.xa = 0;
-                more = true;
-            } else {
-                bp.j += gridDim.x;
-                bp.plane += p.g_plane;
-                bp.y += p.g_y;
-                bp.x += p.g_x;
-                if (bp.x >= p.M) { bp.x -= p.M; ++bp.y; }
-                if (bp.y >= p.M) { bp.y -= p.M; ++bp.plane; }
-                more = bp.j < p.nblocks;
-                pn.j = more ? bp.j : pc.j;                        // after the last: reload this block (valid, unused)
-                pn.fa = pn.j * p.CH;
-                pn.plane = more ? bp.plane : pc.plane;
-                pn.ya = more ? bp.y : pc.ya;
-                pn.xa = more ? bp.x : pc.xa;
-                if (!more && pc.fa != pc.j * p.CH) {              // this was a second piece: its block's first
-                    pn.plane = pc.plane - 1;                      // piece started in the previous plane
-                    const unsigned rel = pn.fa - (pc.p0 - p.MM);
-                    pn.ya = (int)(rel / (unsigned)p.M);
-                    pn.xa = (int)(rel - (unsigned)pn.ya * (unsigned)p.M);
-                }
-            }
+        // (After the last piece the loads below simply fetch this piece's rows again: valid, unused.)
+        Piece pn = pc;
+        bool more = true;
+        if (pc.fb < min((pc.j + 1) * p.CH, p.total)) {           // the plane ended inside the block
+            pn.fa = pc.fb;
+            pn.plane = pc.plane + 1;
+            pn.ya = 0;
+            pn.xa = 0;
+            finish_piece(p, in, pn);
+        } else {
+            bp.j += gridDim.x;
+            bp.plane += p.g_plane;
+            bp.y += p.g_y;
+            bp.x += p.g_x;
+            if (bp.x >= p.M) { bp.x -= p.M; ++bp.y; }
+            if (bp.y >= p.M) { bp.y -= p.M; ++bp.plane; }
+            if (bp.j < p.nblocks) first_piece(p, in, bp, pn);
+            else more = false;
         }
-        finish_piece(p, in, pn);
         const int count4n = pn.rows_in * n4;
         const float4 *s4 = reinterpret_cast<const float4 *>(pn.src);
         const float4 pre0 = s4[min(tid, count4n - 1)];
@@ -287,7 +274,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
         const float4 pre3 = F_NPRE > 2 ? s4[min(3 * F_THREADS + tid, count4n - 1)] : pre0;
 
         // ---- weights of this plane's output channel (scalar registers) ----------------------
-        const int co = pc.plane % p.Cout;
+        const int co = p.Cout == 1 ? 0 : (int)((unsigned)pc.plane % (unsigned)p.Cout);
         if (co != cur_co) {
 #pragma unroll
             for (int r = 0; r < 2; ++r)
@@ -296,7 +283,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     const int Ta = r ? Ta1 : Ta0, Tb = s ? Ta1 : Ta0;
 #pragma unroll
                     for (int t = 0; t < Ta * Tb; ++t)
-                        wk[r][s][t] = w_seg[p.off[2 * r + s] + (size_t)t * p.Cout + co];   // Cin == 1
+                        wk[r][s][t] = w_seg[p.off[2 * r + s] + (unsigned)(t * p.Cout + co)];   // Cin == 1
                 }
             cur_co = co;
         }
