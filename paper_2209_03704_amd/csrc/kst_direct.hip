@@ -9,8 +9,6 @@
 // row and column): those stores are suppressed, and the input indices a
 // phantom member would read still lie inside the map, so loads need no mask
 // beyond the tile edge.
-#include <cstdlib>
-
 #include "kst_direct_flat.h"
 #include "kst_internal.h"
 
@@ -159,7 +157,6 @@ struct RowsParams {
     int xcd_remap;
     int prefetch;             // single-channel kernel: next strip's loads fly during compute
     int xs_buf;               // floats per LDS input buffer
-    int mode;   // TEMP ablation: 1 skip staging, 2 skip compute, 4 skip stores
     int xs_stride;            // floats per staged row: N rounded up to 4, plus 8
     unsigned off[4];
 };
@@ -308,11 +305,9 @@ __device__ __forceinline__ void rows_emit(float *__restrict__ out, const float *
     for (int t = threadIdx.x; 4 * t - shift < p.M; t += 256) {
         const int x0 = 4 * t - shift;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!(p.mode & 2)) {
         if (shift & 1) rows_group<n, r, 1>(acc, rowp, p.xs_stride, ((x0 - 1) >> 1) + 1, wk);
         else rows_group<n, r, 0>(acc, rowp, p.xs_stride, x0 >> 1, wk);
-        } else acc.x = wk[0][0][0] * t;
-        if (!(p.mode & 4) || acc.x == 1234.5f) rows_store(orow + x0, acc, x0, p.M);
+        rows_store(orow + x0, acc, x0, p.M);
     }
 }
 
@@ -519,8 +514,7 @@ static bool try_rows(const T *in, const T *w_seg, float *out, const Shape &s, ks
     unsigned grid;
     if (s.Cin == 1) {
         // Tallest strip (up to 16 rows) whose input fits the prefetch registers and 20 KB of LDS.
-        static const int tune = getenv("KST_ROWS_R") ? atoi(getenv("KST_ROWS_R")) : 8;
-        int R = tune;
+        int R = 8;
         const bool vec = sizeof(T) == 4 && (s.N & 3) == 0;
         while (R > 2 && ((size_t)(R / 2 + s.fl) * p.xs_stride * sizeof(float) > 20 * 1024 ||
                          (vec && (size_t)(R / 2 + s.fl) * s.N > (size_t)256 * R_NLD * 4)))
@@ -543,16 +537,14 @@ static bool try_rows(const T *in, const T *w_seg, float *out, const Shape &s, ks
     if (nchunks >= 0x7ffffff0u) return false;
     p.nchunks = (unsigned)nchunks;
     p.xcd_slots = (p.nchunks + 7) / 8;
-    static const int xr = getenv("KST_XCD") ? atoi(getenv("KST_XCD")) : 1;
-    p.xcd_remap = xr;
-    static const int md = getenv("KST_MODE") ? atoi(getenv("KST_MODE")) : 0;
-    p.mode = md;
+    // Single channel: plain interleaving measured faster than XCD-contiguous ranges (one stream
+    // over the chip keeps HBM pages hot); several channels: neighbours share halo rows in L2.
+    p.xcd_remap = s.Cin == 1 ? 0 : 1;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
     const dim3 block(256);
     if (s.Cin == 1) {
         // Persistent: a few workgroups per CU, each walking over its share of the strips.
-        static const int wgs = getenv("KST_WGS") ? atoi(getenv("KST_WGS")) : 2048;
-        grid = (unsigned)wgs;
+        grid = 1024;
         if (grid > p.xcd_slots * 8) grid = p.xcd_slots * 8;
         grid = grid < 8 ? 8 : (grid & ~7u);                    // whole multiples of the 8 XCDs
         hipLaunchKernelGGL((direct_rows1_kernel<n, T>), dim3(grid), block, lds, stream, in, w_seg, out, p);
@@ -586,8 +578,7 @@ static bool run_rows(const T *in, const T *w_seg, float *out, const Shape &s, ks
 template <typename T>
 static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, kst_dtype dt, hipStream_t stream)
 {
-    static const int no_rows = getenv("KST_NO_ROWS") ? 1 : 0;
-    if (!no_rows && run_rows<T>(in, w_seg, out, s, dt, stream)) return hipGetLastError();
+    if (run_rows<T>(in, w_seg, out, s, dt, stream)) return hipGetLastError();
     DirectParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.E = s.E;
     p.tiles_x = (s.E + D_TJ - 1) / D_TJ;
@@ -619,8 +610,7 @@ hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Sh
     FlatParams fp;
     unsigned grid;
     size_t lds;
-    static const int no_flat = getenv("KST_NO_FLAT") ? 1 : 0;
-    if (!no_flat && direct_flat_plan(s, dt, fp, grid, lds))
+    if (direct_flat_plan(s, dt, fp, grid, lds))
         return launch_direct_flat((const float *)in, (const float *)w_seg, out, s, fp, grid, lds, stream);
     if (dt == KST_BF16) return run<uint16_t>((const uint16_t *)in, (const uint16_t *)w_seg, out, s, dt, stream);
     return run<float>((const float *)in, (const float *)w_seg, out, s, dt, stream);

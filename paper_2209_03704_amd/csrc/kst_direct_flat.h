@@ -14,6 +14,7 @@ struct FlatParams {
     int g_plane, g_y, g_x;  // ... gridDim.x * CH floats (a workgroup's next block)
     int s_y, s_x;           // ... one workgroup iteration (4 * threads floats)
     int c_y, c_x;           // ... CH - 1 floats (first to last float of a full block)
+    unsigned run;           // consecutive blocks handed to one XCD (1: plain blockIdx order)
     int fast;               // M >= 256: a wave's 256 floats cross at most one row end
     int max_rows;           // input rows one piece can need
     int xs_stride, xs_buf;  // floats per staged row / per LDS buffer

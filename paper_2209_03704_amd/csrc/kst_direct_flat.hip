@@ -34,8 +34,6 @@
 // host-computed steps with carries instead of divisions, and a wave whose 256
 // floats lie in one row, or cross exactly one row end, runs code specialised
 // by scalar (r, par) with LDS addresses of the form scalar base + 2 * lane.
-#include <cstdlib>
-
 #include "kst_direct_flat.h"
 
 namespace kst {
@@ -202,8 +200,16 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
 
     // This workgroup's blocks: blockIdx.x, + gridDim.x, ...  The position of the first one costs
     // the only divisions of the common path; later ones are reached by adding the grid step.
+    // Workgroups are dealt round-robin to the 8 XCDs: runs of `run` consecutive blocks go to the
+    // same XCD, so that neighbouring blocks find their shared input rows in that XCD's L2, while
+    // the chip as a whole still sweeps the tensor front to back.  (The grid is a multiple of
+    // 8 * run, which keeps a workgroup's stride at gridDim.x blocks.)
     BlockPos bp;
     bp.j = blockIdx.x;
+    if (p.run > 1) {
+        const unsigned xcd = blockIdx.x & 7u, w = blockIdx.x >> 3;
+        bp.j = ((w / p.run) * 8u + xcd) * p.run + (w % p.run);
+    }
     if (bp.j >= p.nblocks) return;
     {
         const unsigned f = bp.j * p.CH;
@@ -409,9 +415,10 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     if (lds > 64 * 1024) return false;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(1, s.Cout, s.n, c, KST_F32);
     // One resident round: three 512-lane workgroups per CU on 256 CUs.
-    static const int wgs = getenv("KST_WGS") ? atoi(getenv("KST_WGS")) : 768;
+    const int wgs = 768;
     grid = (unsigned)wgs;
     if (grid > p.nblocks) grid = p.nblocks;
+    p.run = grid % 64 == 0 ? 8 : 1;                             // 1: plain blockIdx order
     const unsigned long long gstep = (unsigned long long)grid * CH;
     p.g_plane = (int)(gstep / (unsigned long long)MM);
     const unsigned grem = (unsigned)(gstep % (unsigned long long)MM);
