@@ -23,10 +23,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of each layer's forward kernel, measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE in separate runs, each scaled by what the same counter reads
+# for `--only copy`, a plain copy of known size: 2.0 and 1.0).  Figures and commands:
+# profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
+# kernels, quoted next to the live timing; None for a layer that was not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_1ch_bandwidth": 341986090,
+    "cfg3_gan_n4": 411748879,
+    "cfg4_deep_n5": 553743090 + 63439916,   # matrix-core kernel + split-reduction pass
+    "cfg5_late_bf16": 378411013,
+}
 
 
 def parse_args():
