@@ -139,14 +139,14 @@ static size_t lds_bytes(const IgemmParams &p, int n)
 
 bool igemm_bf16_supported(const Shape &s)
 {
-    if (igemm_bf16_strip_supported(s)) return true;
+    if (igemm_bf16_ring_supported(s) || igemm_bf16_strip_supported(s)) return true;
     if (s.n > 7) return false;
     return lds_bytes(plan(s), s.n) <= 160 * 1024;
 }
 
 size_t igemm_bf16_workspace_bytes(const Shape &s)
 {
-    if (igemm_bf16_strip_supported(s)) return 0;
+    if (igemm_bf16_ring_supported(s) || igemm_bf16_strip_supported(s)) return 0;
     const IgemmParams p = plan(s);
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
 }
@@ -169,6 +169,7 @@ static hipError_t launch_n(const uint16_t *in, const uint16_t *w_seg, float *dst
 hipError_t launch_igemm_bf16(const void *in_v, const void *w_seg_v, float *out, void *ws, const Shape &s,
                              hipStream_t stream)
 {
+    if (igemm_bf16_ring_supported(s)) return launch_igemm_bf16_ring(in_v, w_seg_v, out, s, stream);
     if (igemm_bf16_strip_supported(s)) return launch_igemm_bf16_strip(in_v, w_seg_v, out, s, stream);
     const uint16_t *in = (const uint16_t *)in_v, *w_seg = (const uint16_t *)w_seg_v;
     const IgemmParams p = plan(s);

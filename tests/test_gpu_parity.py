@@ -200,6 +200,40 @@ def test_igemm_bf16_row_strip_kernel(B, Cin, Cout, N, n):
     check_layer(layer, paths=("igemm", "forward", "direct"), seed=N * 5 + n)
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (2, 32, 64, 32, 3),     # E = 31: one column block, four quad rows per tile, last tile short
+    (2, 48, 64, 32, 2),     # even kernel, three chunks
+    (3, 16, 64, 64, 3),     # E = 63: two column blocks, a single chunk
+    (1, 32, 128, 64, 2),    # two channel tiles
+    (1, 16, 64, 128, 3),    # E = 127: four column blocks, one quad row per tile
+    (1, 32, 64, 128, 2),
+])
+def test_igemm_bf16_lds_ring_kernel(B, Cin, Cout, N, n):
+    """bf16 maps of 32, 64 or 128 pixels a side with whole channel tiles take the kernel that
+    fills an LDS ring with LDS-direct loads and fetches operands with transposing reads."""
+    layer = wl.Layer("ring", B, Cin, Cout, N, n, "bf16", "relu_normal", w_std=0.1)
+    check_layer(layer, paths=("igemm", "forward", "direct"), seed=N * 3 + n)
+
+
+def test_igemm_bf16_lds_ring_kernel_is_exact_on_integers_and_stays_inside_out():
+    """Small integers are exact in bf16 and in the fp32 accumulators, so the result must equal
+    the oracle bit for bit; guard words around `out` must survive."""
+    layer = wl.Layer("ring_int", 2, 32, 64, 64, 3, "bf16", "integer")
+    x, w = wl.make_tensors(layer, 11)
+    xd, wd = x.to(DEV), w.to(DEV)
+    ws = kst.kst_segregate_weights(wd)
+    numel = int(np.prod(layer.out_shape))
+    guard = 4096
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    out = buf[guard:guard + numel].view(layer.out_shape)
+    kst.kst_forward_seg(xd, ws, layer.Cout, layer.n, out=out, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    host = buf.cpu()
+    assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w))
+    assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
+
+
 # ----------------------------------------------------------------------------
 # Boundary behaviour: nothing outside `out` is written; results are reproducible
 # ----------------------------------------------------------------------------
