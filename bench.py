@@ -39,8 +39,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--layers", default="all", choices=["all", "none"],
                     help="also time each of the five benchmark layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")

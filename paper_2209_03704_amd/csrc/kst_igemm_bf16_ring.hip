@@ -10,13 +10,16 @@
 //     fragment an MFMA wants is produced by ds_read_b64_tr_b16, which transposes
 //     4 x 4 blocks of 16-bit elements across lanes on the way out of LDS;
 //   * a transposing read returns four CONSECUTIVE pixels from an 8-byte aligned
-//     address, so the window column dx = 1 of Eqs. 7-10 cannot be read from the same
-//     image; a second image shifted left by one pixel is staged through registers
-//     (one 16-byte load + one 4-byte load, four funnel shifts, one LDS write);
+//     address, so the window column dx = 1 of Eqs. 7-10 cannot be read the same way;
+//     it is the dx = 0 fragment moved down one lane (DPP wave shift), with the two
+//     lanes at the block edge patched from the neighbouring block's fragment;
 //   * the segregated weights already sit in fragment order in HBM and are copied by
 //     LDS-direct loads as well;
-//   * two stages form a ring: chunk k+1 lands in one stage while chunk k is
-//     multiplied out of the other, with one workgroup barrier per chunk.
+//   * three stages form a ring: chunks k+1 and k+2 are in flight while chunk k is
+//     multiplied, with one workgroup barrier per chunk.  The compiler would make
+//     every LDS read wait for all LDS-direct loads in flight, so inside the
+//     reduction loop the LDS reads, the counter waits and the barrier are written
+//     as inline assembly and the loop keeps the counts itself.
 // Tile: TI quad rows x 64 output channels per 256-thread workgroup, positions in
 // blocks of 32 consecutive quad columns of one quad row (the transposing read needs
 // consecutive pixels), 4 waves of 32 channels x 64 positions x 4 parity classes,
@@ -28,8 +31,8 @@
 namespace kst {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -40,7 +43,7 @@ constexpr int R_KC = 16;               // channels per chunk = one MFMA reductio
 template <int n, int N>
 struct RingGeom {
     static_assert(n == 2 || n == 3, "window columns 0 and 1 only");
-    static_assert(N == 32 || N == 64 || N == 128, "row of whole 32-column blocks");
+    static_assert(N == 32 || N == 64, "a quad row is one or two 32-column blocks held by one wave");
     static constexpr int fl = n / 2;
     static constexpr int NN = n * n;
     static constexpr int M = 2 * N - n;
@@ -57,19 +60,18 @@ struct RingGeom {
     static constexpr int UPC = CS / 16;                  // units per channel, padding included
     static constexpr int COPY_B = R_KC * CS;             // bytes per image
     static constexpr int W_B = NN * 2 * R_TCO * 16;      // weights per stage: [tap][octet][channel] x 16 bytes
-    static constexpr int STAGE_B = W_B + 2 * COPY_B;
+    static constexpr int STAGE_B = W_B + COPY_B;
+    static constexpr int STAGES = 3;
     static constexpr int W_SLABS = NN * 2;               // 1 KiB slabs (one wave-wide LDS-direct load each)
     static constexpr int X_SLABS = COPY_B / 1024;
     static_assert(COPY_B % 1024 == 0, "image is a whole number of slabs");
     static constexpr int SLABS = W_SLABS + X_SLABS;
     static constexpr int KMAX = (SLABS + 3) / 4;         // slabs per wave
-    static constexpr int RU = R_KC * ROWS * UPR;         // real units of the shifted image
-    static constexpr int NU = (RU + R_THREADS - 1) / R_THREADS;
     static constexpr int LMAX = 2 * TI * M;              // floats per channel run of a tile
     static constexpr int ESTRIDE = (LMAX + 3 + 3) & ~3;  // floats per channel in the epilogue image
     static constexpr int TG = (15 + LMAX - 1) / 4 + 1;   // 16-byte groups per channel run, upper bound
     static constexpr int EPI_B = 32 * ESTRIDE * 4;
-    static constexpr int LDS_B = 2 * STAGE_B > EPI_B ? 2 * STAGE_B : EPI_B;
+    static constexpr int LDS_B = STAGES * STAGE_B > EPI_B ? STAGES * STAGE_B : EPI_B;
 };
 
 struct RingParams {
@@ -159,25 +161,10 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
             g_inc[k] = (unsigned)R_KC * N * N;
         }
     }
-    // ---- shifted image: unit -> (channel, row, 8 pixels), through registers -------------------
-    unsigned b_off[G::NU], b_xoff[G::NU];
-    int b_dst[G::NU];
-    bool b_ok[G::NU];
+    int my_slabs = 0;                                           // LDS-direct loads this wave issues per chunk
 #pragma unroll
-    for (int j = 0; j < G::NU; ++j) {
-        const int u = tid + j * R_THREADS;
-        b_ok[j] = u < G::RU;
-        const int uu = b_ok[j] ? u : 0;
-        const int ci = uu / (G::ROWS * G::UPR);
-        const int rem = uu - ci * (G::ROWS * G::UPR);
-        const int row = rem / G::UPR, x8 = rem - row * G::UPR;
-        const int grow = min(i0 + row, N - 1);
-        b_off[j] = (((unsigned)b * p.Cin + ci) * N + grow) * N + x8 * 8;
-        // The pixel after the unit; for the last unit of a row it only feeds a column no
-        // valid position reads, so that lane re-reads its own first word.
-        b_xoff[j] = x8 + 1 < G::UPR ? b_off[j] + 8 : b_off[j];
-        b_dst[j] = G::W_B + G::COPY_B + ci * G::CS + row * G::ROW_B + x8 * 16;
-    }
+    for (int k = 0; k < G::KMAX; ++k)
+        if (wave + 4 * k < G::SLABS) ++my_slabs;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -187,31 +174,6 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[c][pb][v] = 0.0f;
 
-    uint4 b_reg[G::NU];
-    unsigned b_ext[G::NU];
-
-    auto load_shifted = [&]() {
-#pragma unroll
-        for (int j = 0; j < G::NU; ++j) {
-            if (b_ok[j]) {
-                b_reg[j] = *reinterpret_cast<const uint4 *>(in + b_off[j]);
-                b_ext[j] = *reinterpret_cast<const unsigned *>(in + b_xoff[j]);
-            }
-            b_off[j] += (unsigned)R_KC * N * N;
-            b_xoff[j] += (unsigned)R_KC * N * N;
-        }
-    };
-    auto store_shifted = [&](int stage) {
-#pragma unroll
-        for (int j = 0; j < G::NU; ++j) {
-            if (b_ok[j]) {
-                const uint4 d = b_reg[j];
-                const uint4 o = make_uint4(__builtin_amdgcn_alignbit(d.y, d.x, 16), __builtin_amdgcn_alignbit(d.z, d.y, 16),
-                                           __builtin_amdgcn_alignbit(d.w, d.z, 16), __builtin_amdgcn_alignbit(b_ext[j], d.w, 16));
-                *reinterpret_cast<uint4 *>(lds_raw + stage * G::STAGE_B + b_dst[j]) = o;
-            }
-        }
-    };
     auto issue_direct = [&](int stage) {
 #pragma unroll
         for (int k = 0; k < G::KMAX; ++k) {
@@ -224,28 +186,100 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
             }
         }
     };
-    // The window fragments of a chunk: (position block, window row, window column) -> eight
-    // channels of one pixel per lane.  They are fetched before the next chunk's LDS-direct
-    // loads are issued: the compiler makes a transposing read wait for every LDS-direct load
-    // in flight, and at that point there is none.
-    bf16x8 xf[2][2][2];
-    auto fetch_windows = [&](int stage) {
-        const unsigned char *sb = lds_raw + stage * G::STAGE_B;
+    // Wait until at most `allowed` of this wave's vector-memory loads are outstanding (they
+    // complete in issue order), then meet the other waves.  allowed is 0 or my_slabs.
+    auto wait_loads_and_meet = [&](int allowed) {
+        if (allowed == 0)
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        else if (allowed == G::KMAX)
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(G::KMAX) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(G::KMAX - 1) : "memory");
+    };
+    static_assert(G::KMAX * 4 - G::SLABS < 4 && G::KMAX >= 2 && G::KMAX < 64, "a wave issues KMAX or KMAX - 1 loads per chunk");
+
+    const unsigned lds_base = (unsigned)(size_t)(KST_LDS(unsigned char) *)lds_raw;
+    // One chunk: every LDS read of the wave in one block that ends with the wait for them,
+    // window column 1 by lane shift, then the MFMAs.
+    auto multiply = [&](int stage) {
+        const unsigned xa0 = lds_base + stage * G::STAGE_B + xrd[0];
+        const unsigned xa1 = lds_base + stage * G::STAGE_B + xrd[1];
+        const unsigned wa = lds_base + stage * G::STAGE_B + wrd;
+        uintx2 t[2][2][2];                                       // [position block][window row][channel half]
+        uintx4 wv[G::NN];
+        if constexpr (n == 3) {
+            asm volatile(
+                "ds_read_b64_tr_b16 %0, %17\n\t"
+                "ds_read_b64_tr_b16 %1, %17 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %2, %17 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %3, %17 offset:%22\n\t"
+                "ds_read_b64_tr_b16 %4, %18\n\t"
+                "ds_read_b64_tr_b16 %5, %18 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %6, %18 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %7, %18 offset:%22\n\t"
+                "ds_read_b128 %8, %19\n\t"
+                "ds_read_b128 %9, %19 offset:2048\n\t"
+                "ds_read_b128 %10, %19 offset:4096\n\t"
+                "ds_read_b128 %11, %19 offset:6144\n\t"
+                "ds_read_b128 %12, %19 offset:8192\n\t"
+                "ds_read_b128 %13, %19 offset:10240\n\t"
+                "ds_read_b128 %14, %19 offset:12288\n\t"
+                "ds_read_b128 %15, %19 offset:14336\n\t"
+                "ds_read_b128 %16, %19 offset:16384\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&v"(t[0][0][0]), "=&v"(t[0][0][1]), "=&v"(t[0][1][0]), "=&v"(t[0][1][1]), "=&v"(t[1][0][0]),
+                  "=&v"(t[1][0][1]), "=&v"(t[1][1][0]), "=&v"(t[1][1][1]), "=&v"(wv[0]), "=&v"(wv[1]), "=&v"(wv[2]),
+                  "=&v"(wv[3]), "=&v"(wv[4]), "=&v"(wv[5]), "=&v"(wv[6]), "=&v"(wv[7]), "=&v"(wv[8])
+                : "v"(xa0), "v"(xa1), "v"(wa), "n"(G::ROW_B), "n"(4 * G::CS), "n"(G::ROW_B + 4 * G::CS)
+                : "memory");
+        } else {
+            asm volatile(
+                "ds_read_b64_tr_b16 %0, %12\n\t"
+                "ds_read_b64_tr_b16 %1, %12 offset:%16\n\t"
+                "ds_read_b64_tr_b16 %2, %12 offset:%15\n\t"
+                "ds_read_b64_tr_b16 %3, %12 offset:%17\n\t"
+                "ds_read_b64_tr_b16 %4, %13\n\t"
+                "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
+                "ds_read_b64_tr_b16 %6, %13 offset:%15\n\t"
+                "ds_read_b64_tr_b16 %7, %13 offset:%17\n\t"
+                "ds_read_b128 %8, %14\n\t"
+                "ds_read_b128 %9, %14 offset:2048\n\t"
+                "ds_read_b128 %10, %14 offset:4096\n\t"
+                "ds_read_b128 %11, %14 offset:6144\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&v"(t[0][0][0]), "=&v"(t[0][0][1]), "=&v"(t[0][1][0]), "=&v"(t[0][1][1]), "=&v"(t[1][0][0]),
+                  "=&v"(t[1][0][1]), "=&v"(t[1][1][0]), "=&v"(t[1][1][1]), "=&v"(wv[0]), "=&v"(wv[1]), "=&v"(wv[2]),
+                  "=&v"(wv[3])
+                : "v"(xa0), "v"(xa1), "v"(wa), "n"(G::ROW_B), "n"(4 * G::CS), "n"(G::ROW_B + 4 * G::CS)
+                : "memory");
+        }
+        // Window fragments [block][row][column]: column 0 as read; column 1 = column 0 of the
+        // next quad, i.e. the next lane's value (lanes 0..31 and 32..63 hold the two channel
+        // halves of columns 0..31).  Lanes 31 and 63 take theirs from the block to the right
+        // when the wave holds it; otherwise they belong to a quad column past the row's last
+        // valid one and may hold anything.
+        bf16x8 xf[2][2][2];
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
-            for (int dy = 0; dy < 2; ++dy)
+            for (int dy = 0; dy < 2; ++dy) {
+                const uintx4 x0 = __builtin_shufflevector(t[pb][dy][0], t[pb][dy][1], 0, 1, 2, 3);
+                uintx4 x1;
 #pragma unroll
-                for (int dx = 0; dx < 2; ++dx) {
-                    const unsigned char *a = sb + xrd[pb] + dx * G::COPY_B + dy * G::ROW_B;
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KST_LDS(shortx4) *)a);
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KST_LDS(shortx4) *)(a + 4 * G::CS));
-                    const shortx8 t = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    xf[pb][dy][dx] = __builtin_bit_cast(bf16x8, t);
+                for (int i = 0; i < 4; ++i) {
+                    unsigned v = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0[i], 0x130, 0xf, 0xf, false);   // lane l <- lane l + 1
+                    if (G::CB == 2 && pb == 0) {
+                        const unsigned nb = i < 2 ? t[1][dy][0][i] : t[1][dy][1][i - 2];
+                        const unsigned e0 = (unsigned)__builtin_amdgcn_readlane((int)nb, 0);
+                        const unsigned e1 = (unsigned)__builtin_amdgcn_readlane((int)nb, 32);
+                        v = lane == 31 ? e0 : v;
+                        v = lane == 63 ? e1 : v;
+                    }
+                    x1[i] = v;
                 }
-    };
-    auto multiply = [&](int stage) {
-        const unsigned char *sb = lds_raw + stage * G::STAGE_B;
+                xf[pb][dy][0] = __builtin_bit_cast(bf16x8, x0);
+                xf[pb][dy][1] = __builtin_bit_cast(bf16x8, x1);
+            }
 #pragma unroll
         for (int cls = 0; cls < 4; ++cls) {
             const int r = cls >> 1, s = cls & 1;
@@ -255,7 +289,7 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
 #pragma unroll
                 for (int bq = 0; bq < Tb; ++bq) {
                     const int T = class_tap_base(n, cls) + a * Tb + bq;
-                    const bf16x8 wf = *reinterpret_cast<const bf16x8 *>(sb + T * (2 * R_TCO * 16) + wrd);
+                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[T]);
 #pragma unroll
                     for (int pb = 0; pb < 2; ++pb)
                         acc[cls][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[pb][r + a][s + bq],
@@ -265,21 +299,19 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     };
 
     // ---- reduction over the input channels ------------------------------------------------------
+    // Chunk c lives in stage c % 3.  At the top of iteration c the wave has issued the loads of
+    // chunks <= c + 1; it waits for its share of chunk c, meets the others (so chunk c is whole
+    // and nobody still reads chunk c - 1), refills the stage of chunk c - 1 with chunk c + 2,
+    // and multiplies chunk c.
     const int nchunks = p.Cin / R_KC;
-    load_shifted();
     issue_direct(0);
-    store_shifted(0);
+    if (nchunks > 1) issue_direct(1);
+    int cur = 0;
     for (int c = 0; c < nchunks; ++c) {
-        lds_barrier();                       // stage c & 1 is complete; the other stage is free
-        const int cur = c & 1;
-        const bool more = c + 1 < nchunks;   // uniform
-        fetch_windows(cur);
-        if (more) {
-            load_shifted();
-            issue_direct(cur ^ 1);
-        }
+        wait_loads_and_meet(c + 1 < nchunks ? my_slabs : 0);
+        if (c + 2 < nchunks) issue_direct(cur == 0 ? 2 : cur - 1);
         multiply(cur);
-        if (more) store_shifted(cur ^ 1);
+        cur = cur == 2 ? 0 : cur + 1;
     }
 
     // ---- epilogue -----------------------------------------------------------------------------
@@ -359,7 +391,7 @@ hipError_t launch_ring(const uint16_t *in, const uint16_t *w_seg, float *out, co
 bool igemm_bf16_ring_supported(const Shape &s)
 {
     if (s.n != 2 && s.n != 3) return false;
-    if (s.N != 32 && s.N != 64 && s.N != 128) return false;
+    if (s.N != 32 && s.N != 64) return false;
     if (s.Cin % R_KC != 0 || s.Cout % R_TCO != 0) return false;
     const size_t strips = (size_t)(s.E + (4 / ((s.E + 31) / 32)) - 1) / (4 / ((s.E + 31) / 32));
     return (size_t)s.B * (s.Cout / R_TCO) * strips < 0x7fffffffu;
@@ -375,10 +407,8 @@ hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out,
     switch (s.n * 1000 + s.N) {
         case 2032: return launch_ring<2, 32>(i16, w16, out, p, stream);
         case 2064: return launch_ring<2, 64>(i16, w16, out, p, stream);
-        case 2128: return launch_ring<2, 128>(i16, w16, out, p, stream);
         case 3032: return launch_ring<3, 32>(i16, w16, out, p, stream);
         case 3064: return launch_ring<3, 64>(i16, w16, out, p, stream);
-        case 3128: return launch_ring<3, 128>(i16, w16, out, p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -205,11 +205,11 @@ def test_igemm_bf16_row_strip_kernel(B, Cin, Cout, N, n):
     (2, 48, 64, 32, 2),     # even kernel, three chunks
     (3, 16, 64, 64, 3),     # E = 63: two column blocks, a single chunk
     (1, 32, 128, 64, 2),    # two channel tiles
-    (1, 16, 64, 128, 3),    # E = 127: four column blocks, one quad row per tile
-    (1, 32, 64, 128, 2),
+    (2, 16, 64, 32, 3),     # a single chunk
+    (1, 64, 64, 64, 3),     # four chunks: the three-stage ring wraps
 ])
 def test_igemm_bf16_lds_ring_kernel(B, Cin, Cout, N, n):
-    """bf16 maps of 32, 64 or 128 pixels a side with whole channel tiles take the kernel that
+    """bf16 maps of 32 or 64 pixels a side with whole channel tiles take the kernel that
     fills an LDS ring with LDS-direct loads and fetches operands with transposing reads."""
     layer = wl.Layer("ring", B, Cin, Cout, N, n, "bf16", "relu_normal", w_std=0.1)
     check_layer(layer, paths=("igemm", "forward", "direct"), seed=N * 3 + n)
