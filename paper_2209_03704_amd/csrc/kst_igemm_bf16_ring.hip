@@ -131,13 +131,18 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     }
     const int wrd = (kk * R_TCO + wco * 32 + l32) * 16;
 
-    // ---- LDS-direct plan: wave w copies slabs w, w + 4, ... of every stage -------------------
-    unsigned g_off[G::KMAX], g_inc[G::KMAX];
+    // ---- LDS-direct plan ----------------------------------------------------------------------
+    // Wave w copies slabs w, w + 4, ... of every stage: exactly KMAX loads per wave and chunk
+    // (the few slots past the last slab repeat slabs 0, 1, ...: the same bytes to the same
+    // place).  A load's address is a wave-uniform base that advances once per chunk plus a
+    // per-lane byte offset that never changes.
+    const unsigned char *g_base[G::KMAX];
+    unsigned g_inc[G::KMAX], g_lane[G::KMAX], g_dst[G::KMAX];
 #pragma unroll
     for (int k = 0; k < G::KMAX; ++k) {
-        const int q = wave + 4 * k;
-        g_off[k] = 0;
-        g_inc[k] = 0;
+        int q = wave + 4 * k;
+        if (q >= G::SLABS) q -= G::SLABS;
+        g_dst[k] = (unsigned)q * 1024u;
         if (q < G::W_SLABS) {
             const int T = q >> 1, oct = q & 1;
             int cls = 0;
@@ -148,23 +153,22 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
 #pragma unroll
             for (int c = 1; c < 4; ++c)
                 if (cls == c) { Tp = class_taps(n, c); tb = class_tap_base(n, c); }
-            g_off[k] = p.off[cls] + (((unsigned)oct * Tp + (T - tb)) * p.Cout + co0 + lane) * 8u;
-            g_inc[k] = 2u * Tp * p.Cout * 8u;
-        } else if (q < G::SLABS) {
+            g_base[k] = reinterpret_cast<const unsigned char *>(
+                w_seg + p.off[cls] + (((size_t)oct * Tp + (T - tb)) * p.Cout + co0) * 8u);
+            g_inc[k] = 2u * Tp * p.Cout * 16u;
+            g_lane[k] = (unsigned)lane * 16u;
+        } else {
             const int u = (q - G::W_SLABS) * 64 + lane;
             const int ci = u / G::UPC;
             int rem = u - ci * G::UPC;
             if (rem >= G::ROWS * G::UPR) rem = 0;                  // padding unit: any valid address
             const int row = rem / G::UPR, x8 = rem - row * G::UPR;
             const int grow = min(i0 + row, N - 1);
-            g_off[k] = (((unsigned)b * p.Cin + ci) * N + grow) * N + x8 * 8;
-            g_inc[k] = (unsigned)R_KC * N * N;
+            g_base[k] = reinterpret_cast<const unsigned char *>(in + (size_t)b * p.Cin * N * N);
+            g_inc[k] = (unsigned)R_KC * N * N * 2u;
+            g_lane[k] = (unsigned)(((ci * N + grow) * N + x8 * 8) * 2);
         }
     }
-    int my_slabs = 0;                                           // LDS-direct loads this wave issues per chunk
-#pragma unroll
-    for (int k = 0; k < G::KMAX; ++k)
-        if (wave + 4 * k < G::SLABS) ++my_slabs;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -177,125 +181,121 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     auto issue_direct = [&](int stage) {
 #pragma unroll
         for (int k = 0; k < G::KMAX; ++k) {
-            const int q = wave + 4 * k;
-            if (q < G::SLABS) {
-                const uint16_t *src = (q < G::W_SLABS ? w_seg : in) + g_off[k];
-                __builtin_amdgcn_global_load_lds((const KST_GLB(void) *)src,
-                                                 (KST_LDS(void) *)(lds_raw + stage * G::STAGE_B + q * 1024), 16, 0, 0);
-                g_off[k] += g_inc[k];
+            __builtin_amdgcn_global_load_lds((const KST_GLB(void) *)(g_base[k] + g_lane[k]),
+                                             (KST_LDS(void) *)(lds_raw + stage * G::STAGE_B + g_dst[k]), 16, 0, 0);
+            g_base[k] += g_inc[k];
+        }
+    };
+    // Wait until at most `allowed` (0 or KMAX) of this wave's vector-memory loads are
+    // outstanding (they complete in issue order), then meet the other waves.
+    auto wait_loads_and_meet = [&](bool last) {
+        if (last)
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(G::KMAX) : "memory");
+    };
+    static_assert(G::KMAX * 4 - G::SLABS < G::W_SLABS && G::KMAX < 64, "repeated slabs are weight slabs");
+
+    // Taps in the order they are multiplied: first those that read window column 0, then those
+    // that read column 1 (by then the window registers have been shifted in place).
+    struct TapOrder {
+        int T[G::NN], cls[G::NN], dy[G::NN], dx[G::NN], n0;
+        constexpr TapOrder() : T(), cls(), dy(), dx(), n0(0)
+        {
+            int m = 0;
+            for (int want = 0; want < 2; ++want) {
+                for (int c = 0; c < 4; ++c) {
+                    const int r = c >> 1, s2 = c & 1;
+                    const int Ta = taps_for_parity(n, r), Tb = taps_for_parity(n, s2);
+                    for (int a2 = 0; a2 < Ta; ++a2)
+                        for (int bq = 0; bq < Tb; ++bq)
+                            if (s2 + bq == want) {
+                                T[m] = class_tap_base(n, c) + a2 * Tb + bq;
+                                cls[m] = c; dy[m] = r + a2; dx[m] = want;
+                                ++m;
+                            }
+                }
+                if (want == 0) n0 = m;
             }
         }
     };
-    // Wait until at most `allowed` of this wave's vector-memory loads are outstanding (they
-    // complete in issue order), then meet the other waves.  allowed is 0 or my_slabs.
-    auto wait_loads_and_meet = [&](int allowed) {
-        if (allowed == 0)
-            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        else if (allowed == G::KMAX)
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(G::KMAX) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(G::KMAX - 1) : "memory");
-    };
-    static_assert(G::KMAX * 4 - G::SLABS < 4 && G::KMAX >= 2 && G::KMAX < 64, "a wave issues KMAX or KMAX - 1 loads per chunk");
+    constexpr TapOrder ord;
 
     const unsigned lds_base = (unsigned)(size_t)(KST_LDS(unsigned char) *)lds_raw;
-    // One chunk: every LDS read of the wave in one block that ends with the wait for them,
-    // window column 1 by lane shift, then the MFMAs.
-    auto multiply = [&](int stage) {
+    // One chunk: the transposing window reads and the first weight fragment in one block that
+    // ends with the wait for them; the other weight fragments are ordinary LDS loads issued
+    // before the first MFMAs and waited for one by one by the compiler.  The LDS-direct loads
+    // of a later chunk are issued behind the first MFMAs, whose execution hides them.
+    auto multiply = [&](int stage, bool refill, int refill_stage) {
         const unsigned xa0 = lds_base + stage * G::STAGE_B + xrd[0];
         const unsigned xa1 = lds_base + stage * G::STAGE_B + xrd[1];
         const unsigned wa = lds_base + stage * G::STAGE_B + wrd;
+        const unsigned char *sb = lds_raw + stage * G::STAGE_B;
         uintx2 t[2][2][2];                                       // [position block][window row][channel half]
-        uintx4 wv[G::NN];
-        if constexpr (n == 3) {
-            asm volatile(
-                "ds_read_b64_tr_b16 %0, %17\n\t"
-                "ds_read_b64_tr_b16 %1, %17 offset:%21\n\t"
-                "ds_read_b64_tr_b16 %2, %17 offset:%20\n\t"
-                "ds_read_b64_tr_b16 %3, %17 offset:%22\n\t"
-                "ds_read_b64_tr_b16 %4, %18\n\t"
-                "ds_read_b64_tr_b16 %5, %18 offset:%21\n\t"
-                "ds_read_b64_tr_b16 %6, %18 offset:%20\n\t"
-                "ds_read_b64_tr_b16 %7, %18 offset:%22\n\t"
-                "ds_read_b128 %8, %19\n\t"
-                "ds_read_b128 %9, %19 offset:2048\n\t"
-                "ds_read_b128 %10, %19 offset:4096\n\t"
-                "ds_read_b128 %11, %19 offset:6144\n\t"
-                "ds_read_b128 %12, %19 offset:8192\n\t"
-                "ds_read_b128 %13, %19 offset:10240\n\t"
-                "ds_read_b128 %14, %19 offset:12288\n\t"
-                "ds_read_b128 %15, %19 offset:14336\n\t"
-                "ds_read_b128 %16, %19 offset:16384\n\t"
-                "s_waitcnt lgkmcnt(0)"
-                : "=&v"(t[0][0][0]), "=&v"(t[0][0][1]), "=&v"(t[0][1][0]), "=&v"(t[0][1][1]), "=&v"(t[1][0][0]),
-                  "=&v"(t[1][0][1]), "=&v"(t[1][1][0]), "=&v"(t[1][1][1]), "=&v"(wv[0]), "=&v"(wv[1]), "=&v"(wv[2]),
-                  "=&v"(wv[3]), "=&v"(wv[4]), "=&v"(wv[5]), "=&v"(wv[6]), "=&v"(wv[7]), "=&v"(wv[8])
-                : "v"(xa0), "v"(xa1), "v"(wa), "n"(G::ROW_B), "n"(4 * G::CS), "n"(G::ROW_B + 4 * G::CS)
-                : "memory");
-        } else {
-            asm volatile(
-                "ds_read_b64_tr_b16 %0, %12\n\t"
-                "ds_read_b64_tr_b16 %1, %12 offset:%16\n\t"
-                "ds_read_b64_tr_b16 %2, %12 offset:%15\n\t"
-                "ds_read_b64_tr_b16 %3, %12 offset:%17\n\t"
-                "ds_read_b64_tr_b16 %4, %13\n\t"
-                "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
-                "ds_read_b64_tr_b16 %6, %13 offset:%15\n\t"
-                "ds_read_b64_tr_b16 %7, %13 offset:%17\n\t"
-                "ds_read_b128 %8, %14\n\t"
-                "ds_read_b128 %9, %14 offset:2048\n\t"
-                "ds_read_b128 %10, %14 offset:4096\n\t"
-                "ds_read_b128 %11, %14 offset:6144\n\t"
-                "s_waitcnt lgkmcnt(0)"
-                : "=&v"(t[0][0][0]), "=&v"(t[0][0][1]), "=&v"(t[0][1][0]), "=&v"(t[0][1][1]), "=&v"(t[1][0][0]),
-                  "=&v"(t[1][0][1]), "=&v"(t[1][1][0]), "=&v"(t[1][1][1]), "=&v"(wv[0]), "=&v"(wv[1]), "=&v"(wv[2]),
-                  "=&v"(wv[3])
-                : "v"(xa0), "v"(xa1), "v"(wa), "n"(G::ROW_B), "n"(4 * G::CS), "n"(G::ROW_B + 4 * G::CS)
-                : "memory");
-        }
-        // Window fragments [block][row][column]: column 0 as read; column 1 = column 0 of the
-        // next quad, i.e. the next lane's value (lanes 0..31 and 32..63 hold the two channel
-        // halves of columns 0..31).  Lanes 31 and 63 take theirs from the block to the right
-        // when the wave holds it; otherwise they belong to a quad column past the row's last
-        // valid one and may hold anything.
-        bf16x8 xf[2][2][2];
+        uintx4 w0;
+        bf16x8 wv[G::NN];                                        // in multiplication order
+        asm volatile(
+            "ds_read_b64_tr_b16 %0, %9\n\t"
+            "ds_read_b64_tr_b16 %1, %9 offset:%13\n\t"
+            "ds_read_b64_tr_b16 %2, %9 offset:%12\n\t"
+            "ds_read_b64_tr_b16 %3, %9 offset:%14\n\t"
+            "ds_read_b64_tr_b16 %4, %10\n\t"
+            "ds_read_b64_tr_b16 %5, %10 offset:%13\n\t"
+            "ds_read_b64_tr_b16 %6, %10 offset:%12\n\t"
+            "ds_read_b64_tr_b16 %7, %10 offset:%14\n\t"
+            "ds_read_b128 %8, %11 offset:%15\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(t[0][0][0]), "=&v"(t[0][0][1]), "=&v"(t[0][1][0]), "=&v"(t[0][1][1]), "=&v"(t[1][0][0]),
+              "=&v"(t[1][0][1]), "=&v"(t[1][1][0]), "=&v"(t[1][1][1]), "=&v"(w0)
+            : "v"(xa0), "v"(xa1), "v"(wa), "n"(G::ROW_B), "n"(4 * G::CS), "n"(G::ROW_B + 4 * G::CS), "n"(ord.T[0] * 2048)
+            : "memory");
+        wv[0] = __builtin_bit_cast(bf16x8, w0);
+#pragma unroll
+        for (int m = 1; m < G::NN; ++m)
+            wv[m] = *reinterpret_cast<const bf16x8 *>(sb + ord.T[m] * (2 * R_TCO * 16) + wrd);
+        __builtin_amdgcn_sched_barrier(0);                       // the rest of the weights fly during the first MFMAs
+
+        // Window fragments [block][row]: lanes 0..31 and 32..63 hold the two channel halves of
+        // quad columns 0..31 of the block.
+        uintx4 x[2][2];
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
-            for (int dy = 0; dy < 2; ++dy) {
-                const uintx4 x0 = __builtin_shufflevector(t[pb][dy][0], t[pb][dy][1], 0, 1, 2, 3);
-                uintx4 x1;
+            for (int dy = 0; dy < 2; ++dy) x[pb][dy] = __builtin_shufflevector(t[pb][dy][0], t[pb][dy][1], 0, 1, 2, 3);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    unsigned v = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x0[i], 0x130, 0xf, 0xf, false);   // lane l <- lane l + 1
-                    if (G::CB == 2 && pb == 0) {
-                        const unsigned nb = i < 2 ? t[1][dy][0][i] : t[1][dy][1][i - 2];
-                        const unsigned e0 = (unsigned)__builtin_amdgcn_readlane((int)nb, 0);
-                        const unsigned e1 = (unsigned)__builtin_amdgcn_readlane((int)nb, 32);
-                        v = lane == 31 ? e0 : v;
-                        v = lane == 63 ? e1 : v;
-                    }
-                    x1[i] = v;
+        for (int m = 0; m < ord.n0; ++m)
+#pragma unroll
+            for (int pb = 0; pb < 2; ++pb)
+                acc[ord.cls[m]][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (refill) issue_direct(refill_stage);
+        // Window column 1 = column 0 of the next quad = the next lane's value.  With both blocks
+        // of a quad row in the wave, the halves are regrouped so that one register holds all 64
+        // columns of a channel half, shifted down a lane, and regrouped back; a lone block is
+        // shifted as it is (its last column lies past the row's last valid quad).
+#pragma unroll
+        for (int dy = 0; dy < 2; ++dy)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (G::CB == 2) {
+                    const auto g = __builtin_amdgcn_permlane32_swap(x[0][dy][i], x[1][dy][i], false, false);
+                    const unsigned lo = (unsigned)__builtin_amdgcn_mov_dpp((int)g[0], 0x130, 0xf, 0xf, true);
+                    const unsigned hi = (unsigned)__builtin_amdgcn_mov_dpp((int)g[1], 0x130, 0xf, 0xf, true);
+                    const auto h = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+                    x[0][dy][i] = h[0];
+                    x[1][dy][i] = h[1];
+                } else {
+                    x[0][dy][i] = (unsigned)__builtin_amdgcn_mov_dpp((int)x[0][dy][i], 0x130, 0xf, 0xf, true);
+                    x[1][dy][i] = (unsigned)__builtin_amdgcn_mov_dpp((int)x[1][dy][i], 0x130, 0xf, 0xf, true);
                 }
-                xf[pb][dy][0] = __builtin_bit_cast(bf16x8, x0);
-                xf[pb][dy][1] = __builtin_bit_cast(bf16x8, x1);
             }
 #pragma unroll
-        for (int cls = 0; cls < 4; ++cls) {
-            const int r = cls >> 1, s = cls & 1;
-            const int Ta = taps_for_parity(n, r), Tb = taps_for_parity(n, s);
+        for (int m = ord.n0; m < G::NN; ++m)
 #pragma unroll
-            for (int a = 0; a < Ta; ++a)
-#pragma unroll
-                for (int bq = 0; bq < Tb; ++bq) {
-                    const int T = class_tap_base(n, cls) + a * Tb + bq;
-                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[T]);
-#pragma unroll
-                    for (int pb = 0; pb < 2; ++pb)
-                        acc[cls][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[pb][r + a][s + bq],
-                                                                                acc[cls][pb], 0, 0, 0);
-                }
-        }
+            for (int pb = 0; pb < 2; ++pb)
+                acc[ord.cls[m]][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb], 0, 0, 0);
     };
 
     // ---- reduction over the input channels ------------------------------------------------------
@@ -308,9 +308,8 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     if (nchunks > 1) issue_direct(1);
     int cur = 0;
     for (int c = 0; c < nchunks; ++c) {
-        wait_loads_and_meet(c + 1 < nchunks ? my_slabs : 0);
-        if (c + 2 < nchunks) issue_direct(cur == 0 ? 2 : cur - 1);
-        multiply(cur);
+        wait_loads_and_meet(c + 1 >= nchunks);
+        multiply(cur, c + 2 < nchunks, cur == 0 ? 2 : cur - 1);
         cur = cur == 2 ? 0 : cur + 1;
     }
 
@@ -320,6 +319,9 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     // with 16-byte stores whose lane quads sit in one 64-byte segment (lane t of a channel
     // owns floats [base64 + 4t, +4), base64 = run start rounded down to 64 bytes); only the
     // groups cut by the ends of a run use scalar stores.
+    // Channel cl of a pass keeps its run at Es[cl][(run start & 3) + ...], so that 16-byte
+    // groups of the run are 16-byte aligned in LDS too.  M * M is 0 or 1 (mod 4), so among
+    // the channels 8q + 4kk + j a lane holds, that shift depends on j alone.
     float *Es = reinterpret_cast<float *>(lds_raw);                 // [32][ESTRIDE]
     const int rows_out = min(2 * rows_q, G::M - 2 * i0);
     const int L = rows_out * G::M;
@@ -333,38 +335,44 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
             for (int pb = 0; pb < 2; ++pb) {
                 if (!pos_ok[pb]) continue;
                 const bool x1_ok = 2 * tj[pb] + 1 < G::M;
+                const bool r1_ok = 2 * ti[pb] + 1 < rows_out;
+                float *eq = Es + 4 * kk * G::ESTRIDE + 2 * ti[pb] * G::M + 2 * tj[pb];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int cl = 8 * (v >> 2) + 4 * kk + (v & 3);
-                    const unsigned g_co = g_first + (unsigned)(pass * 32 + cl) * MM;
-                    float *e = Es + cl * G::ESTRIDE + (g_co & 3u) + 2 * ti[pb] * G::M + 2 * tj[pb];
+                for (int j = 0; j < 4; ++j) {
+                    float *ej = eq + j * G::ESTRIDE + ((g_first + j * (MM & 3u)) & 3u);
 #pragma unroll
-                    for (int r = 0; r < 2; ++r) {
-                        if (2 * ti[pb] + r >= rows_out) continue;
-                        e[r * G::M] = acc[2 * r][pb][v];
-                        if (x1_ok) e[r * G::M + 1] = acc[2 * r + 1][pb][v];
+                    for (int q = 0; q < 4; ++q) {
+                        float *e = ej + 8 * q * G::ESTRIDE;
+                        const int v = 4 * q + j;
+                        e[0] = acc[0][pb][v];
+                        if (x1_ok) e[1] = acc[1][pb][v];
+                        if (r1_ok) {
+                            e[G::M] = acc[2][pb][v];
+                            if (x1_ok) e[G::M + 1] = acc[3][pb][v];
+                        }
                     }
                 }
             }
         }
         lds_barrier();
-        // Wave w streams channels w, w + 4, ...; its lanes walk the channel's 16-byte groups.
+        // Wave w streams channels w, w + 4, ...; lane t of a channel owns the 16-byte group
+        // [base64 + 4t, +4) of the output, base64 = run start rounded down to 64 bytes.
+#pragma unroll 2
         for (int cl = wave; cl < 32; cl += R_THREADS / 64) {
             const unsigned g_co = g_first + (unsigned)(pass * 32 + cl) * MM;
-            const unsigned base64 = g_co & ~15u;
-            const float *erow = Es + cl * G::ESTRIDE + (int)(g_co & 3u);
-            for (int t = lane; t < G::TG; t += 64) {
-                const unsigned f0 = base64 + 4u * t;
-                const int rel = (int)(f0 - g_co);
-                if (rel + 3 < 0 || rel >= L) continue;
-                const float *src = erow + rel;                       // 16-byte aligned
-                float *dst = out + f0;
+            const int a16 = (int)(g_co & 15u);                          // run start inside its 64-byte segment
+            const float *erun = Es + cl * G::ESTRIDE - (int)(g_co & 12u);   // group t of the run is at erun + 4t
+            float *orun = out + (g_co & ~15u);
+#pragma unroll
+            for (int it = 0; it < (G::TG + 63) / 64; ++it) {
+                const int t = lane + 64 * it;
+                const int rel = 4 * t - a16;                           // first float of the group, relative to the run
                 if (rel >= 0 && rel + 3 < L) {
-                    *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
-                } else {
+                    *reinterpret_cast<float4 *>(orun + 4 * t) = *reinterpret_cast<const float4 *>(erun + 4 * t);
+                } else if (rel + 3 >= 0 && rel < L) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        if (rel + k >= 0 && rel + k < L) dst[k] = src[k];
+                        if (rel + k >= 0 && rel + k < L) orun[4 * t + k] = erun[4 * t + k];
                 }
             }
         }
