@@ -138,6 +138,29 @@ kst_status kst_forward(const void *in, const void *w, void *out,
                        int B, int Cin, int Cout, int N, int n, kst_dtype dtype, hipStream_t stream);
 
 /*
+ * Padding factor P (Section 3.3, Figs. 5-7): the up-sampled (2N-1) x (2N-1)
+ * map is framed by P >= 0 zeros on every side before the n x n correlation, so
+ * the output edge is kst_out_size_padded(N, n, P) = 2N + 2P - n (it must be
+ * >= 1; P = 0 is the unframed operation above).  The segregated method moves the
+ * frame to the ORIGINAL input with the reduced factor floor(P / 2); for odd P the
+ * four sub-kernels swap roles (K4, K3, K2, K1).  Here: the input is copied into
+ * the workspace framed by ceil(P / 2) zeros and the unframed kernels run on the
+ * copy; for odd P they run into a second workspace buffer one pixel wider on
+ * every side, whose interior is then copied to `out` (one extra pass over the
+ * output).  Layouts, dtypes, alignment, stream and error behaviour are those of
+ * kst_forward_seg / kst_forward; `out` is [B][Cout][2N+2P-n][2N+2P-n] fp32.
+ * kst_workspace_bytes_padded returns 0 for an illegal shape or unsupported path
+ * (a legal call always needs a workspace when P > 0).
+ */
+int kst_out_size_padded(int N, int n, int P);
+size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path);
+kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
+                                  int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path,
+                                  hipStream_t stream);
+kst_status kst_forward_padded(const void *in, const void *w, void *out,
+                              int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream);
+
+/*
  * The conventional method the paper compares against (Section 1; Eq. 1 on the
  * up-sampled map), kept as the speed-up reference and never tuned: one kernel
  * writes U[B][Cin][2N-1][2N-1] (same dtype as in) including all its zeros,

@@ -35,6 +35,10 @@ SIGNATURES = {
     "kst_forward_seg": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
     "kst_forward": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 6 + [_c_void_p]),
     "kst_forward_zero_insert": (_c_int, [_c_void_p] * 4 + [_c_int] * 6 + [_c_void_p]),
+    "kst_out_size_padded": (_c_int, [_c_int] * 3),
+    "kst_workspace_bytes_padded": (_c_size_t, [_c_int] * 8),
+    "kst_forward_seg_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 8 + [_c_void_p]),
+    "kst_forward_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 7 + [_c_void_p]),
 }
 
 
@@ -192,4 +196,51 @@ def kst_forward_zero_insert(x: torch.Tensor, w: torch.Tensor, U: torch.Tensor | 
                                        B, Cin, Cout, N, n, _dtype_code(x), _stream())
     if st != KST_OK:
         raise KstError(st, "kst_forward_zero_insert")
+    return out
+
+
+def kst_out_size_padded(N: int, n: int, P: int) -> int:
+    return lib().kst_out_size_padded(N, n, P)
+
+
+def kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dtype: int, path: int = KST_PATH_AUTO) -> int:
+    return lib().kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dtype, path)
+
+
+def kst_forward_seg_padded(x: torch.Tensor, w_seg: torch.Tensor, Cout: int, n: int, P: int,
+                           out: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                           path: int = KST_PATH_AUTO) -> torch.Tensor:
+    B, Cin, Cout, N, n = _dims(x, n, Cout)
+    dt = _dtype_code(x)
+    if w_seg.dtype != x.dtype:
+        raise TypeError("x and w_seg must share a dtype")
+    M = 2 * N + 2 * P - n
+    if out is None:
+        out = torch.empty((B, Cout, max(M, 0), max(M, 0)), dtype=torch.float32, device=x.device)
+    elif out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    need = kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dt, path)
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_ptr = _dev(ws, "ws") if ws is not None else None
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    st = lib().kst_forward_seg_padded(_dev(x, "x"), _dev(w_seg, "w_seg"), _dev(out, "out"), ws_ptr, ws_bytes,
+                                      B, Cin, Cout, N, n, P, dt, path, _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_forward_seg_padded")
+    return out
+
+
+def kst_forward_padded(x: torch.Tensor, w: torch.Tensor, P: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    Cout, Cin_w, n, _ = w.shape
+    B, Cin, Cout, N, n = _dims(x, n, Cout)
+    if Cin_w != Cin or w.dtype != x.dtype:
+        raise ValueError("x and w disagree on Cin or dtype")
+    M = 2 * N + 2 * P - n
+    if out is None:
+        out = torch.empty((B, Cout, max(M, 0), max(M, 0)), dtype=torch.float32, device=x.device)
+    st = lib().kst_forward_padded(_dev(x, "x"), _dev(w, "w"), _dev(out, "out"), B, Cin, Cout, N, n, P,
+                                  _dtype_code(x), _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_forward_padded")
     return out

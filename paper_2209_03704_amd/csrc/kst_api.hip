@@ -174,6 +174,98 @@ kst_status kst_forward(const void *in, const void *w, void *out, int B, int Cin,
     return st;
 }
 
+// ---- padding factor P -------------------------------------------------------------------------
+namespace {
+
+struct Framed {
+    int q, Nq, M, Mq;                 // frame on the input, framed input edge, output edge, inner output edge
+    size_t in_bytes, wide_bytes;      // workspace parts before the inner kernels' own scratch (256-byte multiples)
+};
+
+kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, Framed *f)
+{
+    if (P < 0 || P > 32768 || B < 1 || N < 1 || N > 32768) return KST_ERR_SHAPE;
+    f->q = (P + 1) / 2;
+    f->Nq = N + 2 * f->q;
+    kst_status st = check_shape(B, Cin, Cout, f->Nq, n);        // also bounds the element counts
+    if (st != KST_OK) return st;
+    f->M = 2 * N + 2 * P - n;
+    f->Mq = 2 * f->Nq - n;
+    if (f->M < 1) return KST_ERR_SHAPE;
+    f->in_bytes = ((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255;
+    f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
+    return KST_OK;
+}
+
+}  // namespace
+
+int kst_out_size_padded(int N, int n, int P) { return 2 * N + 2 * P - n; }
+
+size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path)
+{
+    if (!dtype_ok(dtype)) return 0;
+    if (P == 0) return kst_workspace_bytes(B, Cin, Cout, N, n, dtype, path);
+    Framed f;
+    if (framed_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
+    const Shape s = make_shape(B, Cin, Cout, f.Nq, n);
+    kst_path chosen;
+    if (resolve_path(s, dtype, path, &chosen) != KST_OK) return 0;
+    return f.in_bytes + f.wide_bytes + workspace_for(s, dtype, chosen);
+}
+
+kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
+                                  int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path,
+                                  hipStream_t stream)
+{
+    if (P == 0) return kst_forward_seg(in, w_seg, out, ws, ws_bytes, B, Cin, Cout, N, n, dtype, path, stream);
+    if (!in || !w_seg || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    Framed f;
+    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, &f);
+    if (st != KST_OK) return st;
+    const Shape s = make_shape(B, Cin, Cout, f.Nq, n);
+    kst_path chosen;
+    st = resolve_path(s, dtype, path, &chosen);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
+    const size_t inner = workspace_for(s, dtype, chosen);
+    if (!ws || ws_bytes < f.in_bytes + f.wide_bytes + inner) return KST_ERR_WORKSPACE;
+    if (!aligned16(ws)) return KST_ERR_ALIGN;
+    char *base = (char *)ws;
+    void *in_framed = base;
+    float *wide = f.wide_bytes ? (float *)(base + f.in_bytes) : nullptr;
+    void *inner_ws = inner ? (void *)(base + f.in_bytes + f.wide_bytes) : nullptr;
+    if (launch_frame_input(in, in_framed, B, Cin, N, f.q, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    st = kst_forward_seg(in_framed, w_seg, wide ? (void *)wide : out, inner_ws, inner, B, Cin, Cout, f.Nq, n, dtype,
+                         chosen, stream);
+    if (st != KST_OK) return st;
+    if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, stream) != hipSuccess) return KST_ERR_HIP;
+    return KST_OK;
+}
+
+kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, int Cin, int Cout, int N, int n, int P,
+                              kst_dtype dtype, hipStream_t stream)
+{
+    if (P == 0) return kst_forward(in, w, out, B, Cin, Cout, N, n, dtype, stream);
+    if (!in || !w || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    Framed f;
+    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, &f);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w) || !aligned16(out)) return KST_ERR_ALIGN;
+    const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;
+    const size_t ws_bytes = kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dtype, KST_PATH_AUTO);
+    if (ws_bytes == 0) return KST_ERR_SHAPE;
+    void *scratch = nullptr;
+    if (hipMallocAsync(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
+    st = kst_segregate_weights(w, scratch, Cin, Cout, n, dtype, stream);
+    if (st == KST_OK)
+        st = kst_forward_seg_padded(in, scratch, out, (char *)scratch + seg_bytes, ws_bytes, B, Cin, Cout, N, n, P,
+                                    dtype, KST_PATH_AUTO, stream);
+    if (hipFreeAsync(scratch, stream) != hipSuccess && st == KST_OK) st = KST_ERR_HIP;
+    return st;
+}
+
 kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void *out, int B, int Cin, int Cout,
                                    int N, int n, kst_dtype dtype, hipStream_t stream)
 {

@@ -56,6 +56,10 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
                             hipStream_t stream);
 hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out, const Shape &s,
                               kst_dtype dt, hipStream_t stream);
+// Frame the input by q zeros on every side / drop the outermost rows and columns of an output.
+hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, kst_dtype dt,
+                              hipStream_t stream);
+hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, hipStream_t stream);
 // Direct path: any shape.
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream);

@@ -1,0 +1,79 @@
+// Padding factor P of Section 3.3 (Figs. 5-7): the up-sampled map is framed by P zeros,
+// which the segregated method turns into a frame on the ORIGINAL input.
+//
+// For even P the framed operation is exactly the unframed one on the input framed by P / 2
+// zeros (the paper's reduced padding factor).  For odd P the up-sampled frame is one zero
+// short of that of P + 1 on every side, so its output is the output for P + 1 without its
+// outermost rows and columns; the one-pixel shift is what swaps the roles of the four
+// sub-kernels (the paper's reversed order K4, K3, K2, K1).  Both cases therefore run the
+// unframed kernels on a framed copy of the input; odd P adds a crop.
+#include "kst_internal.h"
+
+namespace kst {
+
+namespace {
+
+// dst[b*c][Nq][Nq] = src[b*c][N][N] framed by q zeros; one thread per 8 bytes of a dst row.
+template <typename T>
+__global__ void __launch_bounds__(256) frame_input_kernel(const T *__restrict__ src, T *__restrict__ dst, unsigned planes,
+                                                          int N, int q)
+{
+    const int Nq = N + 2 * q;
+    const size_t total = (size_t)planes * Nq * Nq;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t row = i / (unsigned)Nq;
+        const int x = (int)(i - row * (unsigned)Nq) - q;
+        const size_t plane = row / (unsigned)Nq;
+        const int y = (int)(row - plane * (unsigned)Nq) - q;
+        T v = (T)0;
+        if (x >= 0 && x < N && y >= 0 && y < N) v = src[(plane * N + y) * N + x];
+        dst[i] = v;
+    }
+}
+
+// dst[plane][M][M] = src[plane][M + 2][M + 2] without its outermost rows and columns.
+__global__ void __launch_bounds__(256) crop_kernel(const float *__restrict__ src, float *__restrict__ dst, unsigned planes,
+                                                   int M)
+{
+    const int Ms = M + 2;
+    const size_t total = (size_t)planes * M * M;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t row = i / (unsigned)M;
+        const int x = (int)(i - row * (unsigned)M);
+        const size_t plane = row / (unsigned)M;
+        const int y = (int)(row - plane * (unsigned)M);
+        dst[i] = src[(plane * Ms + y + 1) * Ms + x + 1];
+    }
+}
+
+unsigned grid_for(size_t total)
+{
+    const size_t blocks = (total + 255) / 256;
+    return (unsigned)(blocks < 8192 ? (blocks ? blocks : 1) : 8192);
+}
+
+}  // namespace
+
+hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, kst_dtype dt,
+                              hipStream_t stream)
+{
+    const unsigned planes = (unsigned)B * (unsigned)Cin;
+    const size_t total = (size_t)planes * (N + 2 * q) * (N + 2 * q);
+    if (dt == KST_BF16)
+        hipLaunchKernelGGL(frame_input_kernel<uint16_t>, dim3(grid_for(total)), dim3(256), 0, stream,
+                           (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q);
+    else
+        hipLaunchKernelGGL(frame_input_kernel<float>, dim3(grid_for(total)), dim3(256), 0, stream, (const float *)in,
+                           (float *)in_framed, planes, N, q);
+    return hipGetLastError();
+}
+
+hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, hipStream_t stream)
+{
+    const unsigned planes = (unsigned)B * (unsigned)Cout;
+    const size_t total = (size_t)planes * M * M;
+    hipLaunchKernelGGL(crop_kernel, dim3(grid_for(total)), dim3(256), 0, stream, wide, out, planes, M);
+    return hipGetLastError();
+}
+
+}  // namespace kst

@@ -314,3 +314,90 @@ def test_benchmark_layers_sampled_planes(idx):
 def test_zero_insert_reference_on_a_benchmark_layer():
     layer = wl.LAYERS[0]
     check_layer(layer, paths=("zero_insert",))
+
+
+# ----------------------------------------------------------------------------
+# Padding factor P (Section 3.3, Figs. 5-7)
+# ----------------------------------------------------------------------------
+def padded_outputs(layer, P, seed, paths):
+    x, w = wl.make_tensors(layer, seed)
+    xd, wd = x.to(DEV), w.to(DEV)
+    res = {}
+    for name in paths:
+        if name == "forward":
+            o = kst.kst_forward_padded(xd, wd, P)
+        else:
+            code = {"direct": kst.KST_PATH_DIRECT, "igemm": kst.KST_PATH_IGEMM, "auto": kst.KST_PATH_AUTO}[name]
+            o = kst.kst_forward_seg_padded(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, P, path=code)
+        torch.cuda.synchronize()
+        res[name] = o.cpu().numpy()
+    return x, w, res
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,paths", [
+    (1, 1, 1, 4, 5, 2, ("direct", "auto", "forward")),            # Figs. 5-6: 4 x 4 input, 5 x 5 kernel, P = 2
+    (1, 1, 1, 4, 5, 3, ("direct", "auto", "forward")),            # Fig. 7: the same with P = 3
+    (2, 3, 4, 7, 3, 1, ("direct", "forward")),
+    (2, 3, 4, 7, 3, 2, ("direct", "forward")),
+    (1, 2, 3, 6, 4, 3, ("direct", "forward")),
+    (2, 1, 1, 9, 5, 4, ("direct", "forward")),
+    (1, 1, 2, 1, 5, 2, ("direct", "forward")),                    # a map the kernel only covers thanks to the frame
+    (2, 16, 32, 16, 4, 2, ("igemm", "auto", "direct", "forward")),   # a GAN layer shape: 16 -> 32
+    (2, 16, 32, 14, 4, 1, ("igemm", "direct")),
+    (1, 24, 40, 12, 3, 4, ("igemm", "direct")),
+    (1, 8, 16, 10, 5, 3, ("igemm", "direct", "forward")),
+])
+def test_padded_forward(B, Cin, Cout, N, n, P, paths, dtype):
+    layer = wl.Layer("padded", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2)
+    x, w, res = padded_outputs(layer, P, 1000 + 13 * N + 7 * n + P, paths)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    M = kst.kst_out_size_padded(N, n, P)
+    assert want.shape == (B, Cout, M, M)
+    for name, got in res.items():
+        assert got.shape == want.shape, name
+        e = rel_err(got, want)
+        assert e <= TOL[dtype], "%s: rel err %.3e" % (name, e)
+
+
+def test_padded_forward_is_exact_on_integers_and_stays_inside_out():
+    layer = wl.Layer("padded_int", 2, 3, 5, 9, 5, "f32", "integer")
+    x, w = wl.make_tensors(layer, 77)
+    xd, wd = x.to(DEV), w.to(DEV)
+    for P in (1, 2, 3):
+        M = kst.kst_out_size_padded(layer.N, layer.n, P)
+        numel = layer.B * layer.Cout * M * M
+        guard = 1024
+        buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+        out = buf[guard:guard + numel].view(layer.B, layer.Cout, M, M)
+        kst.kst_forward_seg_padded(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, P, out=out)
+        torch.cuda.synchronize()
+        host = buf.cpu()
+        assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+        want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+        assert np.array_equal(host[guard:guard + numel].view(out.shape).numpy().astype(np.float64), want)
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", [
+    (64, 512, 256, 16, 4, 2, "f32"),     # Table 3's 16 -> 32 generator layer at a benchmark batch size
+    (4, 64, 128, 60, 3, 4, "bf16"),      # framed to 64 x 64: takes the LDS-ring kernel
+    (16, 3, 1, 224, 5, 2, "f32"),        # Table 1's shape: 224 x 224 x 3 -> 447 x 447 x 1
+    (8, 3, 1, 224, 4, 3, "f32"),         # the same with an odd padding factor
+])
+def test_padded_forward_full_size_sampled_planes(B, Cin, Cout, N, n, P, dtype):
+    layer = wl.Layer("padded_full", B, Cin, Cout, N, n, dtype, "relu_normal")
+    x, w = wl.make_tensors(layer, 4242 + N + P)
+    xd, wd = x.to(DEV), w.to(DEV)
+    out = kst.kst_forward_padded(xd, wd, P)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    rng = np.random.default_rng(N * 10 + P)
+    pairs = set()
+    while len(pairs) < min(32, B * Cout):
+        pairs.add((int(rng.integers(B)), int(rng.integers(Cout))))
+    b_idx, co_idx = [p[0] for p in sorted(pairs)], [p[1] for p in sorted(pairs)]
+    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx, P)
+    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
+    assert got.shape == want.shape
+    e = rel_err(got, want)
+    assert e <= TOL[dtype], "rel err %.3e" % e

@@ -38,6 +38,15 @@ def test_version_and_strings():
 @pytest.mark.parametrize("N,n", [(4, 3), (32, 3), (512, 5), (16, 4), (8, 5), (64, 3)])
 def test_out_size(N, n):
     assert kst.kst_out_size(N, n) == 2 * N - n          # Section 1
+    assert kst.kst_out_size_padded(N, n, 0) == 2 * N - n
+
+
+def test_out_size_padded():
+    # Table 1 shapes (224 x 224 inputs, padding factor 2) and DCGAN's 4 -> 8 layer of Table 3
+    assert kst.kst_out_size_padded(224, 5, 2) == 447
+    assert kst.kst_out_size_padded(224, 4, 2) == 448
+    assert kst.kst_out_size_padded(224, 3, 2) == 449
+    assert kst.kst_out_size_padded(4, 4, 2) == 8
 
 
 @pytest.mark.parametrize("n", range(1, 10))
@@ -97,3 +106,15 @@ def test_argument_errors_are_statuses_not_crashes():
     assert kst.kst_segregated_elems(0, 1, 3, 0) == 0
     assert kst.kst_workspace_bytes(1, 1, 1, 2, 5, 0, 0) == 0
     assert kst.kst_workspace_bytes(1, 1, 1, 32, 3, kst.KST_F32, kst.KST_PATH_DIRECT) == 0
+    # padding factor: negative P, an output edge below 1, a missing or short workspace
+    assert l.kst_forward_seg_padded(one, one, one, one, 1 << 20, 1, 1, 1, 4, 3, -1, 0, 0, None) == 2
+    assert l.kst_forward_seg_padded(one, one, one, one, 1 << 20, 1, 1, 1, 1, 9, 2, 0, 0, None) == 2
+    assert l.kst_forward_padded(one, one, one, 1, 1, 1, 1, 9, 2, 0, None) == 2
+    assert l.kst_forward_seg_padded(one, None, one, one, 1 << 20, 1, 1, 1, 4, 3, 2, 0, 0, None) == 1
+    need = kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 2, kst.KST_F32)
+    assert need >= 2 * 3 * 10 * 10 * 4
+    assert l.kst_forward_seg_padded(one, one, one, None, 0, 2, 3, 4, 8, 3, 2, 0, 0, None) == 4
+    assert l.kst_forward_seg_padded(one, one, one, one, need - 1, 2, 3, 4, 8, 3, 2, 0, 0, None) == 4
+    assert kst.kst_workspace_bytes_padded(1, 1, 1, 1, 9, 2, 0) == 0
+    # odd P also holds the wider output
+    assert kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 3, kst.KST_F32) >= 2 * 3 * 12 * 12 * 4 + 2 * 4 * 21 * 21 * 4

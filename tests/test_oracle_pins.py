@@ -286,6 +286,61 @@ def test_library_convolutions(N, n, P):
 
 
 # ----------------------------------------------------------------------------
+# 7b. Padding factor (Section 3.3, Figs. 5-7): the frame moves to the original input
+# ----------------------------------------------------------------------------
+def segregated_form_padded(x, w, P):
+    """Eqs. 7-10 read for any padding factor, as loops over the ORIGINAL input: output row
+    y = 2i + ry takes the sub-kernel rows of parity r = (ry + P) mod 2 (for odd P the four
+    sub-kernels swap roles: K4, K3, K2, K1) from input rows i + (ry + r - P)/2 + a, and
+    whatever falls outside the map is the frame's zero."""
+    B, Cin, N, _ = x.shape
+    Cout, _, n, _ = w.shape
+    M = 2 * N + 2 * P - n
+    out = np.zeros((B, Cout, M, M))
+    for y in range(M):
+        for xx in range(M):
+            ry, rx, i, j = y & 1, xx & 1, y >> 1, xx >> 1
+            r, s = (ry + P) & 1, (rx + P) & 1
+            br, bc = i + (ry + r - P) // 2, j + (rx + s - P) // 2
+            for a in range((n - r + 1) // 2):
+                for b in range((n - s + 1) // 2):
+                    rr, cc = br + a, bc + b
+                    if 0 <= rr < N and 0 <= cc < N:
+                        out[:, :, y, xx] += np.einsum("bi,oi->bo", x[:, :, rr, cc], w[:, :, 2 * a + r, 2 * b + s])
+    return out
+
+
+@pytest.mark.parametrize("N,n,P", [(4, 5, 2), (4, 5, 3), (4, 5, 1), (5, 4, 1), (5, 4, 2), (3, 3, 4), (4, 3, 3),
+                                   (2, 5, 2), (3, 2, 1), (4, 1, 1), (1, 5, 2)])
+def test_padded_segregated_form_with_reduced_factor_and_swapped_subkernels(N, n, P):
+    """Figs. 5-7 use a 4 x 4 input, a 5 x 5 kernel and P = 2 (reduced factor 1) and P = 3
+    (reduced factor 1, sub-kernels in the order K4..K1)."""
+    rng = np.random.default_rng(900 + 31 * N + 7 * n + P)
+    x = rng.integers(-4, 5, (2, 3, N, N)).astype(np.float64)
+    w = rng.integers(-3, 4, (2, 3, n, n)).astype(np.float64)
+    assert np.array_equal(oracle.forward(x, w, P), segregated_form_padded(x, w, P))
+
+
+@pytest.mark.parametrize("N,n,P", [(4, 5, 2), (4, 5, 4), (5, 3, 2), (6, 4, 2), (3, 1, 2), (4, 5, 3), (4, 4, 1),
+                                   (5, 3, 1), (3, 2, 3)])
+def test_padding_factor_is_a_frame_on_the_original_input(N, n, P):
+    """Even P: the result is that of the unframed operation on the input framed by P/2 zeros
+    (the paper's reduced padding factor).  Odd P: it is the result for P + 1 without its
+    outermost rows and columns."""
+    rng = np.random.default_rng(950 + 31 * N + 7 * n + P)
+    x, w = rand_case(rng, 2, 2, 3, N, n)
+    got = oracle.forward(x, w, P)
+    q = (P + 1) // 2
+    xq = np.zeros((2, 2, N + 2 * q, N + 2 * q))
+    xq[:, :, q:q + N, q:q + N] = x
+    wide = oracle.forward(xq, w, 0)
+    if P % 2 == 0:
+        assert np.array_equal(got, wide)
+    else:
+        assert np.array_equal(got, wide[:, :, 1:-1, 1:-1])
+
+
+# ----------------------------------------------------------------------------
 # 8. Shapes and counts
 # ----------------------------------------------------------------------------
 def test_output_size_law():
