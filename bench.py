@@ -8,8 +8,9 @@ single-channel bandwidth-bound layer): weight pre-segregation, then the
 segregated forward pass with its edge masking, through the C ABI, inputs
 resident in HBM.  Prints ONE JSON line: whole-job useful GMAC/s, the roofline
 of the dominant kernel (measured live with events on the launch stream), the
-CPU oracle as a baseline, and a per-layer table for the five benchmark layers
-(time, useful GMAC/s, roofline fraction, speed-up over the zero-insert path).
+CPU oracle as a baseline, a per-layer table for the five benchmark layers (time, useful
+GMAC/s, roofline fraction, speed-up over the zero-insert path), and a table for the paper's
+own shapes with padding factor 2 (Tables 1 and 3).
 """
 from __future__ import annotations
 
@@ -212,6 +213,32 @@ def main():
             del r, U
             torch.cuda.empty_cache()
 
+    # ---- the paper's own shapes (padding factor 2), framed-input entry point -------------------
+    paper_table = []
+    if args.layers == "all":
+        for layer in wl.PAPER_LAYERS:
+            x, w = wl.make_tensors(layer)
+            xd = [x.cuda().clone() for _ in range(3)]
+            outs = [torch.empty(layer.out_shape, dtype=torch.float32, device="cuda") for _ in range(3)]
+            w_seg = kst.kst_segregate_weights(w.cuda())
+            need = kst.kst_workspace_bytes_padded(layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, kst.KST_F32)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            ms = time_launches(
+                torch, lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P,
+                                                            out=outs[i % 3], ws=ws), 30, 5)
+            paper_table.append({
+                "layer": layer.name,
+                "shape": {"B": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n,
+                          "P": layer.P, "M": layer.M, "dtype": layer.dtype},
+                "forward_us": round(ms * 1e3, 2),
+                "us_per_image": round(ms * 1e3 / layer.B, 3),
+                "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
+                "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
+                "algorithmic_mac_ratio": round(metrics.conventional_macs(layer) / metrics.useful_macs(layer), 3),
+            })
+            del xd, outs, ws
+            torch.cuda.empty_cache()
+
     line = {
         "metric": "useful GMAC/s (segregated transpose convolution, whole path)",
         "value": round(value, 1),
@@ -231,6 +258,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "layers": table,
+        "paper_shaped_layers": paper_table,
         "paper_context": "paper reports 3.7x (Xeon CPU) / 3.4x (RTX 2070) average speed-up over zero-insert; ideal 4x",
     }
     print(json.dumps(line))

@@ -60,6 +60,32 @@ size_t workspace_for(const Shape &s, kst_dtype dt, kst_path path)
     return dt == KST_BF16 ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s);
 }
 
+// The segregated forward pass on a validated shape (s.Ns may exceed s.N only where
+// igemm_f32_takes_row_stride says the kernel that will run reads it).
+kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes, const Shape &s,
+                           kst_dtype dtype, int path, hipStream_t stream)
+{
+    kst_path chosen;
+    kst_status st = resolve_path(s, dtype, path, &chosen);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
+    const size_t need = workspace_for(s, dtype, chosen);
+    if (need > 0) {
+        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return KST_ERR_ALIGN;
+    }
+    if (s.Ns != s.N && !(chosen == KST_PATH_IGEMM && dtype == KST_F32 && igemm_f32_takes_row_stride(s)))
+        return KST_ERR_SHAPE;
+    hipError_t e;
+    if (chosen == KST_PATH_DIRECT)
+        e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
+    else if (dtype == KST_BF16)
+        e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, stream);
+    else
+        e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s, stream);
+    return e == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -132,24 +158,7 @@ kst_status kst_forward_seg(const void *in, const void *w_seg, void *out, void *w
     if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
     kst_status st = check_shape(B, Cin, Cout, N, n);
     if (st != KST_OK) return st;
-    const Shape s = make_shape(B, Cin, Cout, N, n);
-    kst_path chosen;
-    st = resolve_path(s, dtype, path, &chosen);
-    if (st != KST_OK) return st;
-    if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
-    const size_t need = workspace_for(s, dtype, chosen);
-    if (need > 0) {
-        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
-        if (!aligned16(ws)) return KST_ERR_ALIGN;
-    }
-    hipError_t e;
-    if (chosen == KST_PATH_DIRECT)
-        e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
-    else if (dtype == KST_BF16)
-        e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, stream);
-    else
-        e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s, stream);
-    return e == hipSuccess ? KST_OK : KST_ERR_HIP;
+    return run_forward_seg(in, w_seg, out, ws, ws_bytes, make_shape(B, Cin, Cout, N, n), dtype, path, stream);
 }
 
 kst_status kst_forward(const void *in, const void *w, void *out, int B, int Cin, int Cout, int N, int n,
@@ -179,10 +188,12 @@ namespace {
 
 struct Framed {
     int q, Nq, M, Mq;                 // frame on the input, framed input edge, output edge, inner output edge
+    Shape s;                          // the inner, unframed problem (s.Ns: row stride of the framed copy)
+    kst_path chosen;
     size_t in_bytes, wide_bytes;      // workspace parts before the inner kernels' own scratch (256-byte multiples)
 };
 
-kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, Framed *f)
+kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, int path, Framed *f)
 {
     if (P < 0 || P > 32768 || B < 1 || N < 1 || N > 32768) return KST_ERR_SHAPE;
     f->q = (P + 1) / 2;
@@ -192,7 +203,18 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     f->M = 2 * N + 2 * P - n;
     f->Mq = 2 * f->Nq - n;
     if (f->M < 1) return KST_ERR_SHAPE;
-    f->in_bytes = ((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255;
+    f->s = make_shape(B, Cin, Cout, f->Nq, n);
+    st = resolve_path(f->s, dt, path, &f->chosen);
+    if (st != KST_OK) return st;
+    // The pipelined fp32 matrix-core kernel wants rows of whole 16-byte groups: give the framed
+    // copy a row stride rounded up to 4 elements when that is the kernel that will run.
+    if (f->chosen == KST_PATH_IGEMM && dt == KST_F32 && (f->Nq & 3) != 0) {
+        Shape wide = f->s;
+        wide.Ns = (f->Nq + 3) & ~3;
+        if (igemm_f32_takes_row_stride(wide) && workspace_for(wide, dt, f->chosen) == workspace_for(f->s, dt, f->chosen))
+            f->s = wide;
+    }
+    f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
     f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
     return KST_OK;
 }
@@ -206,11 +228,8 @@ size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P,
     if (!dtype_ok(dtype)) return 0;
     if (P == 0) return kst_workspace_bytes(B, Cin, Cout, N, n, dtype, path);
     Framed f;
-    if (framed_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    const Shape s = make_shape(B, Cin, Cout, f.Nq, n);
-    kst_path chosen;
-    if (resolve_path(s, dtype, path, &chosen) != KST_OK) return 0;
-    return f.in_bytes + f.wide_bytes + workspace_for(s, dtype, chosen);
+    if (framed_plan(B, Cin, Cout, N, n, P, dtype, path, &f) != KST_OK) return 0;
+    return f.in_bytes + f.wide_bytes + workspace_for(f.s, dtype, f.chosen);
 }
 
 kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
@@ -221,23 +240,18 @@ kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, 
     if (!in || !w_seg || !out) return KST_ERR_NULL;
     if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
     Framed f;
-    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, &f);
-    if (st != KST_OK) return st;
-    const Shape s = make_shape(B, Cin, Cout, f.Nq, n);
-    kst_path chosen;
-    st = resolve_path(s, dtype, path, &chosen);
+    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, path, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
-    const size_t inner = workspace_for(s, dtype, chosen);
+    const size_t inner = workspace_for(f.s, dtype, f.chosen);
     if (!ws || ws_bytes < f.in_bytes + f.wide_bytes + inner) return KST_ERR_WORKSPACE;
     if (!aligned16(ws)) return KST_ERR_ALIGN;
     char *base = (char *)ws;
     void *in_framed = base;
     float *wide = f.wide_bytes ? (float *)(base + f.in_bytes) : nullptr;
     void *inner_ws = inner ? (void *)(base + f.in_bytes + f.wide_bytes) : nullptr;
-    if (launch_frame_input(in, in_framed, B, Cin, N, f.q, dtype, stream) != hipSuccess) return KST_ERR_HIP;
-    st = kst_forward_seg(in_framed, w_seg, wide ? (void *)wide : out, inner_ws, inner, B, Cin, Cout, f.Nq, n, dtype,
-                         chosen, stream);
+    if (launch_frame_input(in, in_framed, B, Cin, N, f.q, f.s.Ns, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    st = run_forward_seg(in_framed, w_seg, wide ? (void *)wide : out, inner_ws, inner, f.s, dtype, f.chosen, stream);
     if (st != KST_OK) return st;
     if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, stream) != hipSuccess) return KST_ERR_HIP;
     return KST_OK;
@@ -250,7 +264,7 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, i
     if (!in || !w || !out) return KST_ERR_NULL;
     if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
     Framed f;
-    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, &f);
+    kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, KST_PATH_AUTO, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(w) || !aligned16(out)) return KST_ERR_ALIGN;
     const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;

@@ -13,6 +13,7 @@ constexpr int G_THREADS = 512;   // 8 waves: 2 (channel halves) x 4 (position bl
 
 struct IgemmParams {
     int B, Cin, Cout, N, M, E, EE;
+    int Ns;                // row stride of the input in elements (>= N)
     int Mtot;              // B * E * E
     int tiles_m, tiles_co, splits;
     int ci_per_split;      // multiple of the kernel's channel step
@@ -26,6 +27,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
 {
     IgemmParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.E = s.E;
+    p.Ns = s.Ns;
     p.EE = s.E * s.E;
     p.Mtot = s.B * p.EE;
     p.tiles_m = (p.Mtot + G_TM - 1) / G_TM;

@@ -155,7 +155,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     constexpr int W4 = G_KC * NN * (G_TCO / 4);                  // weight float4 per chunk
     constexpr int NW4 = (W4 + G_THREADS - 1) / G_THREADS;        // ... per lane
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int xplane = p.lrows * p.N;                            // floats per staged channel (multiple of 4)
+    const int xplane = p.lrows * p.Ns;                           // floats per staged channel (multiple of 4)
     float *Xs = lds;                                             // [G_KC][xplane]
     float *Ws = lds + G_KC * xplane;                             // [G_KC][NN][G_TCO]
 
@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     const int mb = m / p.EE;
     const int mrem = m - mb * p.EE;
     const int mi = mrem / p.E, mj = mrem - mi * p.E;
-    const int xbase = ((mb * p.N + mi) - R0) * p.N + mj + kk * xplane;
+    const int xbase = ((mb * p.N + mi) - R0) * p.Ns + mj + kk * xplane;
     const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
 
     const int ci_begin = split * p.ci_per_split;
@@ -208,7 +208,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
         w_inc[k] = (unsigned)G_KC * Tp * p.Cout;
         w_c[k] = ok ? c : (1 << 20);
     }
-    const int xp4 = xplane >> 2, n4 = p.N >> 2;
+    const int xp4 = xplane >> 2, n4 = p.Ns >> 2;
     unsigned x_off[P_NX4];
     int x_c[P_NX4];
 #pragma unroll
@@ -220,10 +220,10 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
         const int R = R0 + lr;
         const int bb = R / p.N, y = R - bb * p.N;
         const bool ok = e4 < G_KC * xp4 && bb < p.B;
-        x_off[k] = (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.N + 4 * x4;
+        x_off[k] = (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.Ns + 4 * x4;
         x_c[k] = ok ? c : (1 << 20);
     }
-    const unsigned x_inc = (unsigned)G_KC * p.N * p.N;
+    const unsigned x_inc = (unsigned)G_KC * p.N * p.Ns;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -282,7 +282,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
             for (int dy = 0; dy <= fl; ++dy)
 #pragma unroll
                 for (int dx = 0; dx <= fl; ++dx)
-                    xf[dy][dx] = Xs[c2 * xplane + xbase + dy * p.N + dx];
+                    xf[dy][dx] = Xs[c2 * xplane + xbase + dy * p.Ns + dx];
 #pragma unroll
             for (int cls = 0; cls < 4; ++cls) {
                 const int r = cls >> 1, s = cls & 1;
@@ -328,15 +328,26 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
 
 static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_F32, G_KC); }
 
+// The pipelined kernel wants 16-byte rows and fits its input chunk in P_NX4 loads per lane.
+static bool pipe_ok(const IgemmParams &p)
+{
+    return (p.Ns & 3) == 0 && (p.Cout & 3) == 0 && (size_t)G_KC * p.lrows * p.Ns / 4 <= (size_t)P_NX4 * G_THREADS;
+}
+
 static size_t lds_bytes(const IgemmParams &p, int n)
 {
-    return (size_t)G_KC * ((size_t)p.lrows * p.N + (size_t)n * n * G_TCO) * sizeof(float);
+    return (size_t)G_KC * ((size_t)p.lrows * p.Ns + (size_t)n * n * G_TCO) * sizeof(float);
 }
 
 bool igemm_f32_supported(const Shape &s)
 {
     if (s.n > 7) return false;
     return lds_bytes(plan(s), s.n) <= 160 * 1024;
+}
+
+bool igemm_f32_takes_row_stride(const Shape &s)
+{
+    return igemm_f32_supported(s) && pipe_ok(plan(s));
 }
 
 size_t igemm_f32_workspace_bytes(const Shape &s)
@@ -355,9 +366,8 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)p.tiles_m * p.tiles_co * p.splits;
-    // The pipelined kernel wants 16-byte rows and fits its input chunk in P_NX4 loads per lane.
-    const bool pipe = (p.N & 3) == 0 && (p.Cout & 3) == 0 &&
-                      (size_t)G_KC * p.lrows * p.N / 4 <= (size_t)P_NX4 * G_THREADS;
+    const bool pipe = pipe_ok(p);
+    if (!pipe && p.Ns != p.N) return hipErrorInvalidValue;
     if (pipe) {
         if (lds > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n>),

@@ -32,11 +32,12 @@ struct Shape {
     int M;    // output edge 2N - n
     int E;    // quad rows/columns: ceil(M / 2)
     int fl;   // floor(n / 2): halo of the input window of one quad
+    int Ns;   // elements between consecutive rows of `in` (N unless the caller framed it with a wider stride)
 };
 
 inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
 {
-    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2};
+    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N};
     return s;
 }
 
@@ -57,7 +58,7 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
 hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out, const Shape &s,
                               kst_dtype dt, hipStream_t stream);
 // Frame the input by q zeros on every side / drop the outermost rows and columns of an output.
-hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, kst_dtype dt,
+hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, int Ns, kst_dtype dt,
                               hipStream_t stream);
 hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, hipStream_t stream);
 // Direct path: any shape.
@@ -65,6 +66,7 @@ hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Sh
                          hipStream_t stream);
 // Matrix-core path: whether the kernels can run the shape, scratch they need, launch.
 bool igemm_f32_supported(const Shape &s);
+bool igemm_f32_takes_row_stride(const Shape &s);   // s.Ns != s.N is only read by the pipelined fp32 kernel
 bool igemm_bf16_supported(const Shape &s);
 bool igemm_bf16_strip_supported(const Shape &s);   // row-strip variant (quad rows of at most 128 quads)
 hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);

@@ -13,16 +13,17 @@ namespace kst {
 
 namespace {
 
-// dst[b*c][Nq][Nq] = src[b*c][N][N] framed by q zeros; one thread per 8 bytes of a dst row.
+// dst[b*c][Nq][Ns] = src[b*c][N][N] framed by q zeros, rows Ns >= Nq = N + 2q elements apart
+// (the elements past Nq are zeros too); one thread per element.
 template <typename T>
 __global__ void __launch_bounds__(256) frame_input_kernel(const T *__restrict__ src, T *__restrict__ dst, unsigned planes,
-                                                          int N, int q)
+                                                          int N, int q, int Ns)
 {
     const int Nq = N + 2 * q;
-    const size_t total = (size_t)planes * Nq * Nq;
+    const size_t total = (size_t)planes * Nq * Ns;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const size_t row = i / (unsigned)Nq;
-        const int x = (int)(i - row * (unsigned)Nq) - q;
+        const size_t row = i / (unsigned)Ns;
+        const int x = (int)(i - row * (unsigned)Ns) - q;
         const size_t plane = row / (unsigned)Nq;
         const int y = (int)(row - plane * (unsigned)Nq) - q;
         T v = (T)0;
@@ -54,17 +55,17 @@ unsigned grid_for(size_t total)
 
 }  // namespace
 
-hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, kst_dtype dt,
+hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, int Ns, kst_dtype dt,
                               hipStream_t stream)
 {
     const unsigned planes = (unsigned)B * (unsigned)Cin;
-    const size_t total = (size_t)planes * (N + 2 * q) * (N + 2 * q);
+    const size_t total = (size_t)planes * (N + 2 * q) * Ns;
     if (dt == KST_BF16)
         hipLaunchKernelGGL(frame_input_kernel<uint16_t>, dim3(grid_for(total)), dim3(256), 0, stream,
-                           (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q);
+                           (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q, Ns);
     else
         hipLaunchKernelGGL(frame_input_kernel<float>, dim3(grid_for(total)), dim3(256), 0, stream, (const float *)in,
-                           (float *)in_framed, planes, N, q);
+                           (float *)in_framed, planes, N, q, Ns);
     return hipGetLastError();
 }
 

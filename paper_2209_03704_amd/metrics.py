@@ -3,7 +3,7 @@
 "Useful" multiply-accumulates are the ones the segregated method of Section
 3.3 performs: output (y, x) of parity (r, s) costs Ta(r) * Tb(s) taps per
 (ci, co), with Ta(0) = ceil(n/2) and Ta(1) = floor(n/2) (the sub-kernel sizes
-of Section 3.2).  With E = ceil(M/2) even and O = floor(M/2) odd output
+of Section 3.2; with an odd padding factor the two swap).  With E = ceil(M/2) even and O = floor(M/2) odd output
 rows, the total is (E*ceil(n/2) + O*floor(n/2))^2 per (b, ci, co).  For even n
 that is exactly a quarter of the conventional M^2 n^2 (Table 4); for odd n a
 little less than a quarter.
@@ -23,6 +23,8 @@ def useful_macs(layer: Layer) -> int:
     M, n = layer.M, layer.n
     E, O = (M + 1) // 2, M // 2
     ce, fl = (n + 1) // 2, n // 2
+    if layer.P & 1:          # odd padding factor: even output rows take the odd sub-kernel rows
+        ce, fl = fl, ce
     return (E * ce + O * fl) ** 2 * layer.B * layer.Cin * layer.Cout
 
 

@@ -58,15 +58,32 @@ LAYERS = (
 )
 
 
+# Shapes the paper itself measures, all with padding factor 2: the 224 x 224 x 3 image maps of
+# Tables 1-2 reduced to one output channel with 3 x 3, 4 x 4 and 5 x 5 kernels, and the
+# DCGAN / DiscoGAN generator layers 2-5 of Table 3 (4 x 4 kernels), here at a batch of 64.
+PAPER_LAYERS = (
+    Layer("table1_224x224x3_n3_p2", 16, 3, 1, 224, 3, "f32", "uniform", P=2),
+    Layer("table1_224x224x3_n4_p2", 16, 3, 1, 224, 4, "f32", "uniform", P=2),
+    Layer("table1_224x224x3_n5_p2", 16, 3, 1, 224, 5, "f32", "uniform", P=2),
+    Layer("table3_dcgan_l2_4to8", 64, 1024, 512, 4, 4, "f32", "relu_normal", P=2),
+    Layer("table3_dcgan_l3_8to16", 64, 512, 256, 8, 4, "f32", "relu_normal", P=2),
+    Layer("table3_dcgan_l4_16to32", 64, 256, 128, 16, 4, "f32", "relu_normal", P=2),
+    Layer("table3_dcgan_l5_32to64", 64, 128, 3, 32, 4, "f32", "relu_normal", P=2),
+)
+
+
 def layer_by_name(name: str) -> Layer:
     for i, l in enumerate(LAYERS):
         if l.name == name or name in ("cfg%d" % (i + 1), str(i + 1)):
+            return l
+    for l in PAPER_LAYERS:
+        if l.name == name:
             return l
     raise KeyError(name)
 
 
 def layer_seed(layer: Layer) -> int:
-    for i, l in enumerate(LAYERS):
+    for i, l in enumerate(LAYERS + PAPER_LAYERS):
         if l is layer or l == layer:
             return SEED_BASE + i
     return SEED_BASE + 1000
