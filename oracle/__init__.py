@@ -48,6 +48,9 @@ def _load():
             lib.kst_oracle_threads.restype = ctypes.c_int
             lib.kst_oracle_forward.argtypes = [dp, dp, dp] + [ctypes.c_int] * 6
             lib.kst_oracle_forward.restype = ctypes.c_int
+            for fn in (lib.kst_oracle_backward_input, lib.kst_oracle_backward_weight):
+                fn.argtypes = [dp, dp, dp] + [ctypes.c_int] * 6
+                fn.restype = ctypes.c_int
             lib.kst_oracle_forward_planes.argtypes = (
                 [dp, dp, dp, ip, ip, ctypes.c_int] + [ctypes.c_int] * 6)
             lib.kst_oracle_forward_planes.restype = ctypes.c_int
@@ -131,3 +134,35 @@ def conventional_ops(Cin: int, Cout: int, N: int, n: int, P: int = 0):
     a = ctypes.c_int64()
     _load().kst_oracle_conventional_ops(Cin, Cout, N, n, P, ctypes.byref(m), ctypes.byref(a))
     return m.value, a.value
+
+
+def backward_input(g, w, N: int, P: int = 0) -> np.ndarray:
+    """d(loss)/d(in) [B][Cin][N][N] in fp64 from g = d(loss)/d(out) [B][Cout][M][M] and w."""
+    g = _f64(g, 4)
+    w = _f64(w, 4)
+    B, Cout, M, M2 = g.shape
+    Cout2, Cin, n, n2 = w.shape
+    lib = _load()
+    if M != M2 or n != n2 or Cout != Cout2 or M != lib.kst_oracle_out_size(N, n, P):
+        raise ValueError("shapes of g %r and w %r do not fit N=%d, P=%d" % (g.shape, w.shape, N, P))
+    din = np.empty((B, Cin, N, N), dtype=np.float64)
+    rc = lib.kst_oracle_backward_input(_dptr(g), _dptr(w), _dptr(din), B, Cin, Cout, N, n, P)
+    if rc != 0:
+        raise RuntimeError("kst_oracle_backward_input failed (%d)" % rc)
+    return din
+
+
+def backward_weight(x, g, n: int, P: int = 0) -> np.ndarray:
+    """d(loss)/d(w) [Cout][Cin][n][n] in fp64 from x [B][Cin][N][N] and g [B][Cout][M][M]."""
+    x = _f64(x, 4)
+    g = _f64(g, 4)
+    B, Cin, N, N2 = x.shape
+    B2, Cout, M, M2 = g.shape
+    lib = _load()
+    if N != N2 or M != M2 or B != B2 or M != lib.kst_oracle_out_size(N, n, P):
+        raise ValueError("shapes of x %r and g %r do not fit n=%d, P=%d" % (x.shape, g.shape, n, P))
+    dw = np.empty((Cout, Cin, n, n), dtype=np.float64)
+    rc = lib.kst_oracle_backward_weight(_dptr(x), _dptr(g), _dptr(dw), B, Cin, Cout, N, n, P)
+    if rc != 0:
+        raise RuntimeError("kst_oracle_backward_weight failed (%d)" % rc)
+    return dw

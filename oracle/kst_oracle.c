@@ -28,7 +28,8 @@
  * degenerate cases, agreement with separately coded forms of Eqs. 7-10 and of
  * the scatter (adjoint) form, linearity, the adjoint identity with a strided
  * correlation, library conv routines on fp64, and the operation counts of
- * Table 4.
+ * Table 4; the gradients by the inner-product identities that define an adjoint and
+ * by a library autograd of the forward in fp64.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -100,6 +101,83 @@ int kst_oracle_forward(const double *in, const double *w, double *out,
         for (int co = 0; co < Cout; ++co)
             correlate_plane(Upad, w + (size_t)co * Cin * n * n,
                             out + ((size_t)b * Cout + co) * M * M, Cin, Sp, n, M);
+    }
+    free(Upad);
+    return 0;
+}
+
+/*
+ * Gradients of the forward definition (the paper states, at the end of Section 3.3, that the
+ * method also serves the input and kernel gradients of back-propagation, without giving
+ * formulas; these are the plain adjoints of the two steps above).  With g = d(loss)/d(out):
+ *
+ *   input gradient:   every product Upad[y+u][x+v] * w[u][v] of Eq. 1 sends g[y][x] * w[u][v]
+ *                     back to Upad[y+u][x+v]; the gradient of zero-embedding is sampling the
+ *                     even rows and columns inside the frame:
+ *                         dUpad[b][ci][y+u][x+v] += g[b][co][y][x] * w[co][ci][u][v]
+ *                         din[b][ci][a][c] = dUpad[b][ci][P+2a][P+2c]
+ *   kernel gradient:  dw[co][ci][u][v] = sum_b sum_y sum_x Upad[b][ci][y+u][x+v] * g[b][co][y][x]
+ *
+ * dUpad and Upad are really built, zeros included.  Return 0, or 1 for an illegal shape or a
+ * failed allocation.
+ */
+int kst_oracle_backward_input(const double *g, const double *w, double *din,
+                              int B, int Cin, int Cout, int N, int n, int P)
+{
+    if (B < 1 || Cin < 1 || Cout < 1 || N < 1 || n < 1 || P < 0) return 1;
+    const int M = kst_oracle_out_size(N, n, P);
+    if (M < 1) return 1;
+    const int Sp = 2 * N - 1 + 2 * P;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int ci = 0; ci < Cin; ++ci) {
+            double *dU = (double *)calloc((size_t)Sp * Sp, sizeof(double));
+            if (!dU) { fail = 1; continue; }
+            for (int co = 0; co < Cout; ++co) {
+                const double *gp = g + ((size_t)b * Cout + co) * M * M;
+                const double *wk = w + ((size_t)co * Cin + ci) * n * n;
+                for (int y = 0; y < M; ++y)
+                    for (int x = 0; x < M; ++x)
+                        for (int u = 0; u < n; ++u)
+                            for (int v = 0; v < n; ++v)
+                                dU[(size_t)(y + u) * Sp + (x + v)] += gp[(size_t)y * M + x] * wk[u * n + v];
+            }
+            double *d = din + ((size_t)b * Cin + ci) * N * N;
+            for (int a = 0; a < N; ++a)
+                for (int c = 0; c < N; ++c) d[(size_t)a * N + c] = dU[(size_t)(P + 2 * a) * Sp + (P + 2 * c)];
+            free(dU);
+        }
+    return fail;
+}
+
+int kst_oracle_backward_weight(const double *in, const double *g, double *dw,
+                               int B, int Cin, int Cout, int N, int n, int P)
+{
+    if (B < 1 || Cin < 1 || Cout < 1 || N < 1 || n < 1 || P < 0) return 1;
+    const int M = kst_oracle_out_size(N, n, P);
+    if (M < 1) return 1;
+    const int Sp = 2 * N - 1 + 2 * P;
+    double *Upad = (double *)malloc((size_t)Cin * Sp * Sp * sizeof(double));
+    if (!Upad) return 1;
+    memset(dw, 0, (size_t)Cout * Cin * n * n * sizeof(double));
+    for (int b = 0; b < B; ++b) {
+        upsample_item(in + (size_t)b * Cin * N * N, Upad, Cin, N, P);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+        for (int co = 0; co < Cout; ++co)
+            for (int ci = 0; ci < Cin; ++ci) {
+                const double *gp = g + ((size_t)b * Cout + co) * M * M;
+                const double *Up = Upad + (size_t)ci * Sp * Sp;
+                double *d = dw + ((size_t)co * Cin + ci) * n * n;
+                for (int u = 0; u < n; ++u)
+                    for (int v = 0; v < n; ++v) {
+                        double acc = 0.0;
+                        for (int y = 0; y < M; ++y)
+                            for (int x = 0; x < M; ++x)
+                                acc += Up[(size_t)(y + u) * Sp + (x + v)] * gp[(size_t)y * M + x];
+                        d[u * n + v] += acc;
+                    }
+            }
     }
     free(Upad);
     return 0;

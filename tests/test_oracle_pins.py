@@ -381,3 +381,71 @@ def test_rejects_illegal_shapes():
         oracle.forward(np.zeros((1, 1, 2, 2)), np.zeros((1, 1, 5, 5)))   # 2N - n < 1
     with pytest.raises(ValueError):
         oracle.forward(np.zeros((1, 2, 4, 4)), np.zeros((1, 3, 3, 3)))   # Cin mismatch
+
+
+# ----------------------------------------------------------------------------
+# 9. Gradients (end of Section 3.3: the method also serves back-propagation)
+# ----------------------------------------------------------------------------
+GRAD_CASES = [(4, 3, 0), (5, 4, 0), (4, 5, 2), (4, 5, 3), (3, 2, 1), (6, 1, 0), (2, 5, 2), (5, 3, 4)]
+
+
+@pytest.mark.parametrize("N,n,P", GRAD_CASES)
+def test_gradients_are_the_adjoints_of_the_pinned_forward(N, n, P):
+    """<T(x; w), g> = <x, T_x*(g; w)> = <w, T_w*(x, g)> for the forward oracle pinned above.
+    Checked against every unit vector of x and of w, the identities fix both gradients
+    completely (the forward is linear in each)."""
+    rng = np.random.default_rng(1200 + 31 * N + 7 * n + P)
+    B, Cin, Cout = 2, 2, 3
+    x = rng.integers(-4, 5, (B, Cin, N, N)).astype(np.float64)
+    w = rng.integers(-3, 4, (Cout, Cin, n, n)).astype(np.float64)
+    M = oracle.out_size(N, n, P)
+    g = rng.integers(-3, 4, (B, Cout, M, M)).astype(np.float64)
+    din = oracle.backward_input(g, w, N, P)
+    dw = oracle.backward_weight(x, g, n, P)
+    for idx in np.ndindex(x.shape):
+        e = np.zeros_like(x)
+        e[idx] = 1.0
+        assert np.vdot(oracle.forward(e, w, P), g) == din[idx]
+    for idx in np.ndindex(w.shape):
+        e = np.zeros_like(w)
+        e[idx] = 1.0
+        assert np.vdot(oracle.forward(x, e, P), g) == dw[idx]
+
+
+@pytest.mark.parametrize("N,n,P", [(6, 3, 0), (5, 4, 2), (4, 5, 3), (7, 5, 0)])
+def test_gradients_match_library_autograd(N, n, P):
+    """Cross-check with a library: autograd of conv2d on an explicitly zero-embedded fp64 tensor."""
+    rng = np.random.default_rng(1300 + N + n + P)
+    x, w = rand_case(rng, 2, 3, 4, N, n)
+    M = oracle.out_size(N, n, P)
+    g = rng.standard_normal((2, 4, M, M))
+    xt = torch.from_numpy(x).requires_grad_(True)
+    wt = torch.from_numpy(w).requires_grad_(True)
+    S = 2 * N - 1
+    U = torch.zeros(2, 3, S, S, dtype=torch.float64)
+    U[:, :, ::2, ::2] = xt
+    out = torch.nn.functional.conv2d(U, wt, padding=P)
+    out.backward(torch.from_numpy(g))
+    din = oracle.backward_input(g, w, N, P)
+    dw = oracle.backward_weight(x, g, n, P)
+    assert np.abs(din - xt.grad.numpy()).max() <= 1e-12 * np.abs(din).max()
+    assert np.abs(dw - wt.grad.numpy()).max() <= 1e-12 * np.abs(dw).max()
+
+
+def test_input_gradient_is_a_stride_two_correlation_with_the_rotated_kernel():
+    """The form a kernel would compute: din[a][c] = sum g[2a-u][2c-v] w[u][v] (P = 0)."""
+    rng = np.random.default_rng(1400)
+    N, n = 5, 4
+    x, w = rand_case(rng, 1, 2, 3, N, n)
+    M = 2 * N - n
+    g = rng.integers(-3, 4, (1, 3, M, M)).astype(np.float64)
+    w = np.rint(4 * w)
+    want = np.zeros((1, 2, N, N))
+    for a in range(N):
+        for c in range(N):
+            for u in range(n):
+                for v in range(n):
+                    y, xx = 2 * a - u, 2 * c - v
+                    if 0 <= y < M and 0 <= xx < M:
+                        want[0, :, a, c] += np.einsum("o,oi->i", g[0, :, y, xx], w[:, :, u, v])
+    assert np.array_equal(oracle.backward_input(g, w, N, 0), want)
