@@ -161,6 +161,26 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
                               int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream);
 
 /*
+ * Gradients (end of Section 3.3: the segregated method also gives the input and
+ * kernel gradients of back-propagation).  g = d(loss)/d(out) is fp32,
+ * [B][Cout][M][M] with M = kst_out_size_padded(N, n, P); the results are fp32:
+ *   din[b][ci][a][c]  = sum_co sum_u sum_v g[b][co][P+2a-u][P+2c-v] * w[co][ci][u][v]
+ *   dw[co][ci][u][v]  = sum_b sum_a sum_c in[b][ci][a][c] * g[b][co][P+2a-u][P+2c-v]
+ * over the terms whose g index lies inside the map: exactly the products of the
+ * forward pass that involve an original input pixel.  w (un-segregated,
+ * [Cout][Cin][n][n]) and in are of type `dtype`.  din [B][Cin][N][N] and dw
+ * [Cout][Cin][n][n] are fully overwritten.  ws / ws_bytes: scratch of at least
+ * kst_backward_*_workspace_bytes(...) (0 when P = 0), used for framed copies as in
+ * kst_forward_seg_padded.  Pointers, alignment, stream and statuses as above.
+ */
+size_t kst_backward_input_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype);
+size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype);
+kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
+                              int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream);
+kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws, size_t ws_bytes,
+                               int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream);
+
+/*
  * The conventional method the paper compares against (Section 1; Eq. 1 on the
  * up-sampled map), kept as the speed-up reference and never tuned: one kernel
  * writes U[B][Cin][2N-1][2N-1] (same dtype as in) including all its zeros,

@@ -39,6 +39,10 @@ SIGNATURES = {
     "kst_workspace_bytes_padded": (_c_size_t, [_c_int] * 8),
     "kst_forward_seg_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 8 + [_c_void_p]),
     "kst_forward_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 7 + [_c_void_p]),
+    "kst_backward_input_workspace_bytes": (_c_size_t, [_c_int] * 7),
+    "kst_backward_weight_workspace_bytes": (_c_size_t, [_c_int] * 7),
+    "kst_backward_input": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
+    "kst_backward_weight": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
 }
 
 
@@ -244,3 +248,61 @@ def kst_forward_padded(x: torch.Tensor, w: torch.Tensor, P: int, out: torch.Tens
     if st != KST_OK:
         raise KstError(st, "kst_forward_padded")
     return out
+
+
+def _ws(need: int, ws, device):
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    ptr = _dev(ws, "ws") if ws is not None else None
+    size = ws.numel() * ws.element_size() if ws is not None else 0
+    return ws, ptr, size
+
+
+def kst_backward_input(g: torch.Tensor, w: torch.Tensor, N: int, P: int = 0, din: torch.Tensor | None = None,
+                       ws: torch.Tensor | None = None) -> torch.Tensor:
+    """d(loss)/d(in) [B][Cin][N][N] (fp32) from g = d(loss)/d(out) (fp32) and the un-segregated w."""
+    Cout, Cin, n, n2 = w.shape
+    B, Cout_g, M, M2 = g.shape
+    if n != n2 or M != M2 or Cout_g != Cout or g.dtype != torch.float32:
+        raise ValueError("g must be float32 [B][Cout][M][M] matching w")
+    if M != 2 * N + 2 * P - n:
+        raise ValueError("g's edge %d is not 2N + 2P - n" % M)
+    dt = _dtype_code(w)
+    if din is None:
+        din = torch.empty((B, Cin, N, N), dtype=torch.float32, device=g.device)
+    need = lib().kst_backward_input_workspace_bytes(B, Cin, Cout, N, n, P, dt)
+    ws, ws_ptr, ws_bytes = _ws(need, ws, g.device)
+    st = lib().kst_backward_input(_dev(g, "g"), _dev(w, "w"), _dev(din, "din"), ws_ptr, ws_bytes,
+                                  B, Cin, Cout, N, n, P, dt, _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_backward_input")
+    return din
+
+
+def kst_backward_weight(x: torch.Tensor, g: torch.Tensor, n: int, P: int = 0, dw: torch.Tensor | None = None,
+                        ws: torch.Tensor | None = None) -> torch.Tensor:
+    """d(loss)/d(w) [Cout][Cin][n][n] (fp32) from x and g = d(loss)/d(out) (fp32)."""
+    B, Cin, N, N2 = x.shape
+    B2, Cout, M, M2 = g.shape
+    if N != N2 or M != M2 or B != B2 or g.dtype != torch.float32:
+        raise ValueError("g must be float32 [B][Cout][M][M] matching x")
+    if M != 2 * N + 2 * P - n:
+        raise ValueError("g's edge %d is not 2N + 2P - n" % M)
+    dt = _dtype_code(x)
+    if dw is None:
+        dw = torch.empty((Cout, Cin, n, n), dtype=torch.float32, device=x.device)
+    need = lib().kst_backward_weight_workspace_bytes(B, Cin, Cout, N, n, P, dt)
+    ws, ws_ptr, ws_bytes = _ws(need, ws, x.device)
+    st = lib().kst_backward_weight(_dev(x, "x"), _dev(g, "g"), _dev(dw, "dw"), ws_ptr, ws_bytes,
+                                   B, Cin, Cout, N, n, P, dt, _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_backward_weight")
+    return dw
+
+
+def kst_backward_input_workspace_bytes(B, Cin, Cout, N, n, P, dtype: int) -> int:
+    return lib().kst_backward_input_workspace_bytes(B, Cin, Cout, N, n, P, dtype)
+
+
+def kst_backward_weight_workspace_bytes(B, Cin, Cout, N, n, P, dtype: int) -> int:
+    return lib().kst_backward_weight_workspace_bytes(B, Cin, Cout, N, n, P, dtype)

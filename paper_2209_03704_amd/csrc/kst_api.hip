@@ -253,7 +253,7 @@ kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, 
     if (launch_frame_input(in, in_framed, B, Cin, N, f.q, f.s.Ns, dtype, stream) != hipSuccess) return KST_ERR_HIP;
     st = run_forward_seg(in_framed, w_seg, wide ? (void *)wide : out, inner_ws, inner, f.s, dtype, f.chosen, stream);
     if (st != KST_OK) return st;
-    if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, stream) != hipSuccess) return KST_ERR_HIP;
+    if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, 1, stream) != hipSuccess) return KST_ERR_HIP;
     return KST_OK;
 }
 
@@ -278,6 +278,106 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, i
                                     dtype, KST_PATH_AUTO, stream);
     if (hipFreeAsync(scratch, stream) != hipSuccess && st == KST_OK) st = KST_ERR_HIP;
     return st;
+}
+
+// ---- gradients --------------------------------------------------------------------------------
+namespace {
+
+// Workspace of the gradient entry points: for P > 0 the unframed kernels run on framed copies.
+//   input gradient:  [g framed by one zero (odd P)] [din of the framed input]
+//   kernel gradient: [input framed by q] [g framed by one zero (odd P)]
+struct GradPlan {
+    int q, Nq, M, Mq;
+    Shape s;                          // the unframed problem the kernels see
+    size_t g_bytes, din_bytes, in_bytes;
+};
+
+kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
+{
+    if (P < 0 || P > 32768 || B < 1 || N < 1 || N > 32768) return KST_ERR_SHAPE;
+    f->q = (P + 1) / 2;
+    f->Nq = N + 2 * f->q;
+    kst_status st = check_shape(B, Cin, Cout, f->Nq, n);
+    if (st != KST_OK) return st;
+    f->M = 2 * N + 2 * P - n;
+    f->Mq = 2 * f->Nq - n;
+    if (f->M < 1) return KST_ERR_SHAPE;
+    f->s = make_shape(B, Cin, Cout, f->Nq, n);
+    f->g_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
+    f->din_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * sizeof(float) + 255) & ~(size_t)255) : 0;
+    f->in_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255) : 0;
+    return KST_OK;
+}
+
+}  // namespace
+
+size_t kst_backward_input_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype)
+{
+    GradPlan f;
+    if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
+    return f.g_bytes + f.din_bytes;
+}
+
+size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype)
+{
+    GradPlan f;
+    if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
+    return f.in_bytes + f.g_bytes;
+}
+
+kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
+                              int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream)
+{
+    if (!g || !w || !din) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    GradPlan f;
+    kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
+    if (st != KST_OK) return st;
+    if (!aligned16(g) || !aligned16(w) || !aligned16(din)) return KST_ERR_ALIGN;
+    const size_t need = f.g_bytes + f.din_bytes;
+    if (need) {
+        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return KST_ERR_ALIGN;
+    }
+    const float *g_in = (const float *)g;
+    float *d_out = (float *)din;
+    if (f.g_bytes) {          // odd P: the forward dropped the outermost ring of the wider output
+        if (launch_frame_input(g, ws, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
+        g_in = (const float *)ws;
+    }
+    if (P) d_out = (float *)((char *)ws + f.g_bytes);
+    if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    if (P && launch_crop(d_out, (float *)din, B, Cin, N, f.q, stream) != hipSuccess) return KST_ERR_HIP;
+    return KST_OK;
+}
+
+kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws, size_t ws_bytes,
+                               int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream)
+{
+    if (!in || !g || !dw) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    GradPlan f;
+    kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
+    if (st != KST_OK) return st;
+    if (!aligned16(in) || !aligned16(g) || !aligned16(dw)) return KST_ERR_ALIGN;
+    const size_t need = f.in_bytes + f.g_bytes;
+    if (need) {
+        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return KST_ERR_ALIGN;
+    }
+    const void *x_in = in;
+    const float *g_in = (const float *)g;
+    if (P) {
+        if (launch_frame_input(in, ws, B, Cin, N, f.q, f.Nq, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+        x_in = ws;
+    }
+    if (f.g_bytes) {
+        void *gw = (char *)ws + f.in_bytes;
+        if (launch_frame_input(g, gw, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
+        g_in = (const float *)gw;
+    }
+    return launch_backward_weight_generic(x_in, g_in, (float *)dw, f.s, dtype, stream) == hipSuccess ? KST_OK
+                                                                                                      : KST_ERR_HIP;
 }
 
 kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void *out, int B, int Cin, int Cout,

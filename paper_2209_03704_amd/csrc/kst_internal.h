@@ -60,7 +60,12 @@ hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out
 // Frame the input by q zeros on every side / drop the outermost rows and columns of an output.
 hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, int Ns, kst_dtype dt,
                               hipStream_t stream);
-hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, hipStream_t stream);
+hipError_t launch_crop(const float *wide, float *out, int planes_b, int planes_c, int M, int q, hipStream_t stream);
+// Gradients, P = 0, any shape (plain ALU kernels).  g, din and dw are fp32; w and in are of type dt.
+hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
+                                         hipStream_t stream);
+hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, const Shape &s, kst_dtype dt,
+                                          hipStream_t stream);
 // Direct path: any shape.
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream);

@@ -32,18 +32,18 @@ __global__ void __launch_bounds__(256) frame_input_kernel(const T *__restrict__ 
     }
 }
 
-// dst[plane][M][M] = src[plane][M + 2][M + 2] without its outermost rows and columns.
+// dst[plane][M][M] = src[plane][M + 2q][M + 2q] without its q outermost rows and columns.
 __global__ void __launch_bounds__(256) crop_kernel(const float *__restrict__ src, float *__restrict__ dst, unsigned planes,
-                                                   int M)
+                                                   int M, int q)
 {
-    const int Ms = M + 2;
+    const int Ms = M + 2 * q;
     const size_t total = (size_t)planes * M * M;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const size_t row = i / (unsigned)M;
         const int x = (int)(i - row * (unsigned)M);
         const size_t plane = row / (unsigned)M;
         const int y = (int)(row - plane * (unsigned)M);
-        dst[i] = src[(plane * Ms + y + 1) * Ms + x + 1];
+        dst[i] = src[(plane * Ms + y + q) * Ms + x + q];
     }
 }
 
@@ -69,11 +69,11 @@ hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, i
     return hipGetLastError();
 }
 
-hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, hipStream_t stream)
+hipError_t launch_crop(const float *wide, float *out, int B, int Cout, int M, int q, hipStream_t stream)
 {
     const unsigned planes = (unsigned)B * (unsigned)Cout;
     const size_t total = (size_t)planes * M * M;
-    hipLaunchKernelGGL(crop_kernel, dim3(grid_for(total)), dim3(256), 0, stream, wide, out, planes, M);
+    hipLaunchKernelGGL(crop_kernel, dim3(grid_for(total)), dim3(256), 0, stream, wide, out, planes, M, q);
     return hipGetLastError();
 }
 

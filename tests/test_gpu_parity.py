@@ -401,3 +401,51 @@ def test_padded_forward_full_size_sampled_planes(B, Cin, Cout, N, n, P, dtype):
     assert got.shape == want.shape
     e = rel_err(got, want)
     assert e <= TOL[dtype], "rel err %.3e" % e
+
+
+# ----------------------------------------------------------------------------
+# Gradients (end of Section 3.3)
+# ----------------------------------------------------------------------------
+GRAD_TOL = {"f32": 2e-5, "bf16": 2e-5}     # operands are exact in both cases; the sums are fp32
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (1, 1, 1, 4, 5, 2),      # Figs. 5-6 shape
+    (1, 1, 1, 4, 5, 3),      # Fig. 7 shape
+    (2, 3, 4, 7, 3, 0),
+    (2, 3, 4, 6, 4, 0),
+    (2, 5, 2, 9, 5, 0),
+    (1, 2, 3, 8, 1, 0),
+    (2, 3, 2, 5, 2, 1),
+    (2, 16, 32, 16, 4, 2),   # a generator layer shape
+    (3, 8, 24, 12, 3, 4),
+    (1, 40, 72, 10, 5, 0),
+    (1, 2, 2, 1, 5, 2),
+])
+def test_gradients(B, Cin, Cout, N, n, P, dtype):
+    layer = wl.Layer("grad", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 3000 + 13 * N + 7 * n + P)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(17 * N + n + P)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    torch.cuda.synchronize()
+    want_din = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert din.shape == want_din.shape and dw.shape == want_dw.shape
+    assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL[dtype]
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
+
+
+def test_gradients_are_exact_on_integers():
+    layer = wl.Layer("grad_int", 2, 3, 4, 9, 5, "f32", "integer", P=2)
+    x, w = wl.make_tensors(layer, 99)
+    M = kst.kst_out_size_padded(layer.N, layer.n, layer.P)
+    gen = torch.Generator().manual_seed(5)
+    g = torch.randint(-3, 4, (2, 4, M, M), generator=gen).to(torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P).cpu().numpy().astype(np.float64)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), layer.n, layer.P).cpu().numpy().astype(np.float64)
+    assert np.array_equal(din, oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P))
+    assert np.array_equal(dw, oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P))
