@@ -169,6 +169,7 @@ static hipError_t launch_n(const uint16_t *in, const uint16_t *w_seg, float *dst
 hipError_t launch_igemm_bf16(const void *in_v, const void *w_seg_v, float *out, void *ws, const Shape &s,
                              hipStream_t stream)
 {
+    if (igemm_bf16_wide_supported(s)) return launch_igemm_bf16_wide(in_v, w_seg_v, out, s, stream);
     if (igemm_bf16_ring_supported(s)) return launch_igemm_bf16_ring(in_v, w_seg_v, out, s, stream);
     if (igemm_bf16_strip_supported(s)) return launch_igemm_bf16_strip(in_v, w_seg_v, out, s, stream);
     const uint16_t *in = (const uint16_t *)in_v, *w_seg = (const uint16_t *)w_seg_v;

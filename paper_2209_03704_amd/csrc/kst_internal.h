@@ -77,6 +77,8 @@ bool igemm_bf16_strip_supported(const Shape &s);   // row-strip variant (quad ro
 hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
 bool igemm_bf16_ring_supported(const Shape &s);    // LDS-ring variant (n = 2, 3; N = 32, 64, 128; whole channel tiles)
 hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
+bool igemm_bf16_wide_supported(const Shape &s);    // persistent wide-tile variant (same shapes, at least ~one tile per CU)
+hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
 size_t igemm_f32_workspace_bytes(const Shape &s);
 size_t igemm_bf16_workspace_bytes(const Shape &s);
 hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,

@@ -234,6 +234,40 @@ def test_igemm_bf16_lds_ring_kernel_is_exact_on_integers_and_stays_inside_out():
     assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (4, 32, 256, 64, 3),     # 256 tiles of four quad rows x 64 channels, two chunks, last strip short
+    (8, 96, 128, 64, 2),     # even kernel, six chunks: the five-stage ring wraps
+    (32, 48, 128, 32, 3),    # one column block: a wave holds four quad rows
+    (29, 112, 128, 32, 2),   # seven chunks, 232 tiles on 256 CUs
+    (5, 16, 256, 64, 3),     # 320 tiles: some workgroups walk over two tiles; a single chunk
+])
+def test_igemm_bf16_wide_kernel(B, Cin, Cout, N, n):
+    """Layers with at least about one tile per CU take the persistent wide-tile kernel
+    (one wave per SIMD, 256 accumulators, fragments refreshed in place)."""
+    layer = wl.Layer("wide", B, Cin, Cout, N, n, "bf16", "relu_normal", w_std=0.1)
+    check_layer(layer, paths=("igemm", "forward"), seed=N * 7 + n)
+
+
+def test_igemm_bf16_wide_kernel_is_exact_on_integers_and_stays_inside_out():
+    """Small integers are exact in bf16 and in the fp32 accumulators, so the result must equal
+    the oracle bit for bit, tile after tile of a persistent workgroup; guard words around
+    `out` must survive."""
+    layer = wl.Layer("wide_int", 5, 32, 256, 64, 3, "bf16", "integer")
+    x, w = wl.make_tensors(layer, 13)
+    xd, wd = x.to(DEV), w.to(DEV)
+    ws = kst.kst_segregate_weights(wd)
+    numel = int(np.prod(layer.out_shape))
+    guard = 4096
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    out = buf[guard:guard + numel].view(layer.out_shape)
+    kst.kst_forward_seg(xd, ws, layer.Cout, layer.n, out=out, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    host = buf.cpu()
+    assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w))
+    assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
+
+
 # ----------------------------------------------------------------------------
 # Boundary behaviour: nothing outside `out` is written; results are reproducible
 # ----------------------------------------------------------------------------
