@@ -14,8 +14,8 @@
 //     registers, re-read for chunk c + 1 while the MFMAs of chunk c run (each register
 //     right after its last use); the chunk is laid out as a sequence of slots, one MFMA
 //     each, over which the lane shifts, the LDS reads, the LDS-direct loads (three
-//     instructions apiece) and the one barrier are dealt; the ring is five stages deep
-//     (four chunks of global latency in flight);
+//     instructions apiece) and the one barrier are dealt; the ring is three stages deep
+//     (two chunks of global latency in flight; deeper rings measured slower);
 //   * one workgroup per CU (4 waves, tile = 64 channels x 8 / CB quad rows, CB = 32-column
 //     blocks per quad row) walks over tiles: tile t + grid follows tile t.
 // The epilogue interleaves the classes into an LDS image of 32 channels per pass (all
@@ -61,7 +61,7 @@ struct WideGeom {
     static constexpr int COPY_B = W_KC * CS;             // bytes per image
     static constexpr int W_B = NN * 2 * W_TCO * 16;      // weights per stage: [tap][octet][channel] x 16 bytes
     static constexpr int STAGE_B = W_B + COPY_B;
-    static constexpr int STAGES = 5;
+    static constexpr int STAGES = 3;
     static constexpr int W_SLABS = NN * 2;               // 1 KiB slabs (one wave-wide LDS-direct load each)
     static constexpr int X_SLABS = COPY_B / 1024;
     static_assert(COPY_B % 1024 == 0, "image is a whole number of slabs");
