@@ -40,6 +40,16 @@ namespace kst {
 
 namespace {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// 16-byte aligned streaming store of four outputs: the output is written once and never
+// read back by this kernel, so its lines need not stay in L2.
+__device__ __forceinline__ void store_streaming(float *dst, const float (&o)[4])
+{
+    const floatx4 v = {o[0], o[1], o[2], o[3]};
+    __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(dst));
+}
+
 constexpr int F_PAD = 4;      // slack floats left and right of each staged input row
 #ifndef KST_FLAT_THREADS
 #define KST_FLAT_THREADS 512
@@ -320,7 +330,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                 } else {
                     cross_segment<n>(o, Xs, p, pc.ia, y, xs, lane, wk);
                 }
-                *reinterpret_cast<float4 *>(out + fw + 4 * lane) = make_float4(o[0], o[1], o[2], o[3]);
+                store_streaming(out + fw + 4 * lane, o);
                 fw += F_STEP;
                 xs += p.s_x;
                 y += p.s_y;
@@ -355,7 +365,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     }
                     float *dst = out + f0;                       // 16-byte aligned
                     if (f0 >= pc.fa && f0 + 3 < pc.fb) {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+                        store_streaming(dst, o);
                     } else {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
