@@ -284,7 +284,7 @@ __device__ __forceinline__ void rows_weights(float (&wk)[2][2][((n + 1) / 2) * (
 __device__ __forceinline__ void rows_store(float *__restrict__ o, const float4 &v4, int x0, int M)
 {
     if (x0 >= 0 && x0 + 3 < M) {
-        *reinterpret_cast<float4 *>(o) = v4;                     // 16-byte aligned by construction
+        store_streaming4(o, v4.x, v4.y, v4.z, v4.w);            // 16-byte aligned by construction
     } else {
         const float v[4] = {v4.x, v4.y, v4.z, v4.w};
 #pragma unroll

@@ -40,15 +40,8 @@ namespace kst {
 
 namespace {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-// 16-byte aligned streaming store of four outputs: the output is written once and never
-// read back by this kernel, so its lines need not stay in L2.
-__device__ __forceinline__ void store_streaming(float *dst, const float (&o)[4])
-{
-    const floatx4 v = {o[0], o[1], o[2], o[3]};
-    __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(dst));
-}
+// 16-byte aligned streaming store of four outputs.
+__device__ __forceinline__ void store_streaming(float *dst, const float (&o)[4]) { store_streaming4(dst, o[0], o[1], o[2], o[3]); }
 
 constexpr int F_PAD = 4;      // slack floats left and right of each staged input row
 #ifndef KST_FLAT_THREADS

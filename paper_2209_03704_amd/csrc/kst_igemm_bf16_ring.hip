@@ -368,7 +368,8 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
                 const int t = lane + 64 * it;
                 const int rel = 4 * t - a16;                           // first float of the group, relative to the run
                 if (rel >= 0 && rel + 3 < L) {
-                    *reinterpret_cast<float4 *>(orun + 4 * t) = *reinterpret_cast<const float4 *>(erun + 4 * t);
+                    const float4 v4 = *reinterpret_cast<const float4 *>(erun + 4 * t);
+                    store_streaming4(orun + 4 * t, v4.x, v4.y, v4.z, v4.w);
                 } else if (rel + 3 >= 0 && rel < L) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)

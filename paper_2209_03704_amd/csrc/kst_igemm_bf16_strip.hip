@@ -251,7 +251,8 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
                 const float *src = erow + rel;                       // 16-byte aligned
                 float *dst = out + f0;
                 if (rel >= 0 && rel + 3 < L) {
-                    *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+                    const float4 v4 = *reinterpret_cast<const float4 *>(src);
+                    store_streaming4(dst, v4.x, v4.y, v4.z, v4.w);
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)

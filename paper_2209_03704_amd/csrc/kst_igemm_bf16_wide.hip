@@ -31,7 +31,6 @@ namespace kst {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -547,8 +546,7 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
                     if (rel >= 0 && rel + 3 < L) {
                         // streaming store: the line is written back soon instead of sitting in L2
                         // until the whole chip's next burst of stores pushes it out
-                        const floatx4 vv = {v[it].x, v[it].y, v[it].z, v[it].w};
-                        __builtin_nontemporal_store(vv, reinterpret_cast<floatx4 *>(orun + 4 * tt));
+                        store_streaming4(orun + 4 * tt, v[it].x, v[it].y, v[it].z, v[it].w);
                     } else if (rel + 3 >= 0 && rel < L) {
                         const float f[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
 #pragma unroll
