@@ -30,10 +30,10 @@ if ROOT not in sys.path:
 # profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
 # kernels, quoted next to the live timing; None for a layer that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_1ch_bandwidth": 342048966,
-    "cfg3_gan_n4": 411743453,
-    "cfg4_deep_n5": 553744163 + 63440018,   # matrix-core kernel + split-reduction pass
-    "cfg5_late_bf16": 378526925,
+    "cfg2_1ch_bandwidth": 339383144,
+    "cfg3_gan_n4": 467693704,
+    "cfg4_deep_n5": 553773629 + 63439972,   # matrix-core kernel + split-reduction pass
+    "cfg5_late_bf16": 352754770,
 }
 
 
