@@ -235,6 +235,19 @@ def main():
             ms = time_launches(
                 torch, lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P,
                                                             out=outs[i % 3], ws=ws), 30, 5)
+            # gradients of the same layer (plain ALU kernels, not tuned): g = d(loss)/d(out)
+            g = torch.randn(layer.out_shape, dtype=torch.float32, device="cuda")
+            wd = w.cuda()
+            din = torch.empty((layer.B, layer.Cin, layer.N, layer.N), dtype=torch.float32, device="cuda")
+            dw = torch.empty_like(wd)
+            dt_code = kst.KST_F32
+            ws_bi = torch.empty(max(kst.kst_backward_input_workspace_bytes(
+                layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
+            ws_bw = torch.empty(max(kst.kst_backward_weight_workspace_bytes(
+                layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
+            bi_ms = time_launches(torch, lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws_bi), 2, 1)
+            bw_ms = time_launches(torch, lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws_bw), 2, 1)
+            del g, din, dw, ws_bi, ws_bw
             paper_table.append({
                 "layer": layer.name,
                 "shape": {"B": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n,
@@ -244,6 +257,8 @@ def main():
                 "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
                 "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
                 "algorithmic_mac_ratio": round(metrics.conventional_macs(layer) / metrics.useful_macs(layer), 3),
+                "backward_input_us": round(bi_ms * 1e3, 1),
+                "backward_weight_us": round(bw_ms * 1e3, 1),
             })
             del xd, outs, ws
             torch.cuda.empty_cache()

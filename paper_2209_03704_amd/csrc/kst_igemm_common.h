@@ -40,11 +40,20 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     // Split the channel reduction when the tile grid alone cannot fill the chip.
     const int tiles = p.tiles_m * p.tiles_co;
     const int chunks = (s.Cin + kc - 1) / kc;
+    // Candidates: split counts up to 16.  Cost of one: launch rounds on 256 CUs times the time
+    // of a tile's share of the reduction, plus the pass that sums the partial outputs (it reads
+    // `splits` copies and writes one).  A split has to beat the unsplit launch by a tenth to be
+    // worth its workspace.
     int splits = 1;
-    if (tiles <= 128) {
-        splits = 256 / tiles;
-        if (splits > chunks) splits = chunks;
-        if (splits > 16) splits = 16;
+    {
+        const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt == KST_BF16 ? 1.0e12 : 2.0e11);
+        const double out_b = (double)s.B * s.Cout * s.M * s.M * 4.0;
+        double best = (double)((tiles + 255) / 256) * tile_s;
+        const double unsplit = best;
+        for (int c = 2; c <= 16 && c <= chunks; ++c) {
+            const double t = (double)(((size_t)tiles * c + 255) / 256) * tile_s / c + (c + 1) * out_b / 4.0e12;
+            if (t < best && t < 0.9 * unsplit) { best = t; splits = c; }
+        }
     }
     const int cps = (chunks + splits - 1) / splits;
     p.ci_per_split = cps * kc;
