@@ -87,7 +87,6 @@ struct WideParams {
 };
 
 #define KST_LDS(T) T __attribute__((address_space(3)))
-#define KST_GLB(T) T __attribute__((address_space(1)))
 
 // Workgroup barrier behind this wave's LDS traffic.  Vector-memory operations (global
 // stores of an earlier pass, LDS-direct loads the caller has accounted for) stay in flight.
