@@ -170,7 +170,11 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
  * forward pass that involve an original input pixel.  w (un-segregated,
  * [Cout][Cin][n][n]) and in are of type `dtype`.  din [B][Cin][N][N] and dw
  * [Cout][Cin][n][n] are fully overwritten.  ws / ws_bytes: scratch of at least
- * kst_backward_*_workspace_bytes(...) (0 when P = 0), used for framed copies as in
+ * kst_backward_*_workspace_bytes(...), used for framed copies as in
+ * kst_forward_seg_padded and, by the matrix-core input-gradient kernel (fp32
+ * weights, n <= 5, at least 8 channels on either side), for the partial sums of
+ * a split reduction; it may be 0 (then ws may be NULL).  The byte count depends
+ * on the shape only, never on the pointers, as in
  * kst_forward_seg_padded.  Pointers, alignment, stream and statuses as above.
  */
 size_t kst_backward_input_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype);

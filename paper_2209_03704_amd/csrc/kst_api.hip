@@ -284,12 +284,14 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, i
 namespace {
 
 // Workspace of the gradient entry points: for P > 0 the unframed kernels run on framed copies.
-//   input gradient:  [g framed by one zero (odd P)] [din of the framed input]
+//   input gradient:  [g framed by one zero (odd P)] [din of the framed input] [partial sums of the
+//                    matrix-core kernel's split reduction]
 //   kernel gradient: [input framed by q] [g framed by one zero (odd P)]
 struct GradPlan {
     int q, Nq, M, Mq;
     Shape s;                          // the unframed problem the kernels see
     size_t g_bytes, din_bytes, in_bytes;
+    size_t split_bytes;               // input gradient on the matrix cores: partial sums
 };
 
 kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
@@ -306,6 +308,7 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->g_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->din_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->in_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255) : 0;
+    f->split_bytes = backward_input_igemm_supported(f->s, dt) ? backward_input_igemm_workspace_bytes(f->s) : 0;
     return KST_OK;
 }
 
@@ -315,7 +318,7 @@ size_t kst_backward_input_workspace_bytes(int B, int Cin, int Cout, int N, int n
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return f.g_bytes + f.din_bytes;
+    return f.g_bytes + f.din_bytes + f.split_bytes;
 }
 
 size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype)
@@ -334,7 +337,7 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(g) || !aligned16(w) || !aligned16(din)) return KST_ERR_ALIGN;
-    const size_t need = f.g_bytes + f.din_bytes;
+    const size_t need = f.g_bytes + f.din_bytes + f.split_bytes;
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
@@ -346,7 +349,13 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
         g_in = (const float *)ws;
     }
     if (P) d_out = (float *)((char *)ws + f.g_bytes);
-    if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    if (backward_input_igemm_supported(f.s, dtype)) {
+        void *split_ws = f.split_bytes ? (char *)ws + f.g_bytes + f.din_bytes : nullptr;
+        if (launch_backward_input_igemm(g_in, (const float *)w, d_out, split_ws, f.s, stream) != hipSuccess)
+            return KST_ERR_HIP;
+    } else if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) {
+        return KST_ERR_HIP;
+    }
     if (P && launch_crop(d_out, (float *)din, B, Cin, N, f.q, stream) != hipSuccess) return KST_ERR_HIP;
     return KST_OK;
 }

@@ -1,0 +1,289 @@
+// Input gradient of the transpose convolution on the matrix cores (fp32).
+//
+// End of Section 3.3: the segregated method also serves back-propagation.  With
+// g = d(loss)/d(out) and no padding factor,
+//
+//   din[b][ci][a][c] = sum_co sum_u sum_v g[b][co][2a-u][2c-v] * w[co][ci][u][v]
+//
+// over the (u, v) whose g index lies inside the M x M map: the forward's products read
+// backwards, one for every original input pixel and kernel element, none for an embedded
+// zero.  As a GEMM: rows = input channels ci, columns = positions (b, a, c), reduction over
+// (co, u, v); the B operand is gathered from g at stride 2.
+//
+// Tile: 128 positions x 128 input channels per 512-thread workgroup, 8 waves of 64 channels
+// x 32 positions (v_mfma_f32_32x32x2f32, 32 accumulators per lane); the reduction walks the
+// output channels in chunks of 4.  Per chunk the workgroup stages
+//   * the rows of g the tile's positions touch, into a zero-framed LDS image: "virtual"
+//     row VR = b * Hv + (y + n - 1), Hv = 2N + n - 2, and column x + n - 1, so that every tap
+//     of every position reads inside the image and finds a zero where g has no element;
+//   * the chunk's weights w[co][ci][u][v], read as they lie in memory (ci-major runs of n * n
+//     floats) and written to LDS as [co][u v][ci] with an odd row stride.
+// Both are loaded into registers one chunk ahead of the MFMAs that consume the previous
+// chunk from LDS.  Few tiles: the reduction is split over launches' z-range into a workspace
+// and summed by the forward path's reduction pass (fixed order).
+#include "kst_igemm_common.h"
+
+namespace kst {
+
+namespace {
+
+constexpr int B_TM = 128;        // positions per workgroup
+constexpr int B_TCI = 128;       // input channels per workgroup
+constexpr int B_THREADS = 512;
+constexpr int B_KC = 4;          // output channels per chunk (two MFMA reduction steps)
+constexpr int B_WST = B_TCI + 1; // LDS row stride of the staged weights (odd: the transposing writes spread over the banks)
+constexpr int B_PX = 16;         // g elements a lane stages per chunk at most
+
+struct BwdParams {
+    int B, Cin, Cout, N, M, n;
+    int Hv, Wl;            // virtual rows per batch item, LDS columns per row
+    int lrows;             // virtual rows staged per channel
+    int Mtot;              // B * N * N positions
+    int tiles_m, tiles_ci, splits, co_per_split;
+    size_t out_elems;
+};
+
+template <int n>
+__global__ void __launch_bounds__(B_THREADS) backward_input_f32_kernel(const float *__restrict__ g,
+                                                                        const float *__restrict__ w,
+                                                                        float *__restrict__ dst, BwdParams p)
+{
+    constexpr int NN = n * n;
+    constexpr int WE = B_KC * NN * B_TCI;                        // weight floats per chunk
+    constexpr int NWE = WE / B_THREADS;                          // ... per lane
+    static_assert(WE % B_THREADS == 0, "whole number of weight elements per lane");
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int xplane = p.lrows * p.Wl;                           // floats per staged channel
+    float *Xs = lds;                                             // [B_KC][lrows][Wl]
+    float *Ws = lds + B_KC * xplane;                             // [B_KC][NN][B_WST]
+
+    unsigned id = blockIdx.x;
+    const int tile_m = (int)(id % (unsigned)p.tiles_m);
+    id /= (unsigned)p.tiles_m;
+    const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
+    const int split = (int)(id / (unsigned)p.tiles_ci);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wci = wave & 1, wpos = wave >> 1;
+
+    const int NNp = p.N * p.N;
+    const int m0 = tile_m * B_TM;
+    const int ci0 = tile_ci * B_TCI;
+    // first virtual row the tile can touch: position m0's taps u = n - 1 .. 0 read rows 2a .. 2a + n - 1
+    const int b0 = m0 / NNp;
+    const int a0 = (m0 - b0 * NNp) / p.N;
+    const int VR0 = b0 * p.Hv + 2 * a0;
+
+    int m = m0 + wpos * 32 + l32;
+    const bool m_valid = m < p.Mtot;
+    if (!m_valid) m = p.Mtot - 1;
+    const int mb = m / NNp;
+    const int mrem = m - mb * NNp;
+    const int ma = mrem / p.N, mc = mrem - ma * p.N;
+    // LDS offset of this lane's tap (u, v) = (0, 0): row 2a + n - 1, column 2c + n - 1
+    const int xbase = (mb * p.Hv + 2 * ma + (n - 1) - VR0) * p.Wl + 2 * mc + (n - 1) + kk * xplane;
+    const int wbase = kk * (NN * B_WST) + wci * 64 + l32;
+
+    const int co_begin = split * p.co_per_split;
+    const int co_end = min(p.Cout, co_begin + p.co_per_split);
+
+    // ---- staging plan -------------------------------------------------------------------------
+    // weights: element e of the chunk = (c, ci, uv) as it lies in memory for a fixed output
+    // channel: w[co][ci0 + ci][uv], uv fastest
+    unsigned w_off[NWE];
+    int w_lds[NWE], w_c[NWE];                      // LDS float index; channel within the chunk, or 1 << 20 when unused
+#pragma unroll
+    for (int k = 0; k < NWE; ++k) {
+        const int e = tid + k * B_THREADS;
+        const int c = e / (NN * B_TCI);
+        const int rem = e - c * (NN * B_TCI);
+        const int ci = rem / NN, uv = rem - ci * NN;
+        const bool ok = ci0 + ci < p.Cin;
+        w_off[k] = (((unsigned)(co_begin + c) * p.Cin + ci0 + (ok ? ci : 0)) * NN) + uv;
+        w_lds[k] = (c * NN + uv) * B_WST + ci;
+        w_c[k] = ok ? c : (1 << 20);
+    }
+    const unsigned w_inc = (unsigned)B_KC * p.Cin * NN;
+    // g: element e of the chunk = (c, virtual row, LDS column)
+    unsigned x_off[B_PX];
+    int x_c[B_PX];
+#pragma unroll
+    for (int k = 0; k < B_PX; ++k) {
+        const int e = tid + k * B_THREADS;
+        const int c = e / xplane;
+        const int rem = e - c * xplane;
+        const int lr = rem / p.Wl, lc = rem - lr * p.Wl;
+        const int VR = VR0 + lr;
+        const int bb = VR / p.Hv;
+        const int y = VR - bb * p.Hv - (n - 1), x = lc - (n - 1);
+        const bool ok = e < B_KC * xplane && bb < p.B && y >= 0 && y < p.M && x >= 0 && x < p.M;
+        x_off[k] = ok ? ((((unsigned)bb * p.Cout + co_begin + c) * p.M + y) * p.M + x) : 0u;
+        x_c[k] = ok ? c : (1 << 20);
+    }
+    const unsigned x_inc = (unsigned)B_KC * p.M * p.M;
+
+    floatx16 acc[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[h][v] = 0.0f;
+
+    float w_reg[NWE], x_reg[B_PX];
+    auto load_chunk = [&](int co_first) {
+#pragma unroll
+        for (int k = 0; k < NWE; ++k) w_reg[k] = co_first + w_c[k] < co_end ? w[w_off[k]] : 0.0f;
+#pragma unroll
+        for (int k = 0; k < B_PX; ++k) x_reg[k] = co_first + x_c[k] < co_end ? g[x_off[k]] : 0.0f;
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int k = 0; k < NWE; ++k) Ws[w_lds[k]] = w_reg[k];
+#pragma unroll
+        for (int k = 0; k < B_PX; ++k)
+            if (tid + k * B_THREADS < B_KC * xplane) Xs[tid + k * B_THREADS] = x_reg[k];
+    };
+
+    load_chunk(co_begin);
+    store_chunk();
+    __syncthreads();
+
+    for (int co0 = co_begin; co0 < co_end; co0 += B_KC) {
+        // Next chunk's loads (all-zero past the end of this split's channels).
+        const int cn = co0 + B_KC;
+#pragma unroll
+        for (int k = 0; k < NWE; ++k) w_off[k] += w_inc;
+#pragma unroll
+        for (int k = 0; k < B_PX; ++k) x_off[k] += x_c[k] < B_KC ? x_inc : 0u;
+        load_chunk(cn);
+
+#pragma unroll
+        for (int c2 = 0; c2 < B_KC; c2 += 2) {
+#pragma unroll
+            for (int u = 0; u < n; ++u)
+#pragma unroll
+                for (int v = 0; v < n; ++v) {
+                    const float xf = Xs[c2 * xplane + xbase - u * p.Wl - v];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const float wf = Ws[(c2 * NN + u * n + v) * B_WST + wbase + h * 32];
+                        acc[h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, xf, acc[h], 0, 0, 0);
+                    }
+                }
+        }
+        if (cn >= co_end) break;
+        __syncthreads();                                         // every wave is done reading this chunk
+        store_chunk();
+        __syncthreads();
+    }
+
+    if (!m_valid) return;
+    // acc[h][v]: input channel ci0 + 64 wci + 32 h + 8 (v / 4) + 4 kk + v % 4 at this lane's position
+    float *o = dst + (size_t)split * p.out_elems;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int ci = ci0 + wci * 64 + h * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            if (ci < p.Cin) o[(((size_t)mb * p.Cin + ci) * p.N + ma) * p.N + mc] = acc[h][v];
+        }
+}
+
+BwdParams plan(const Shape &s)
+{
+    BwdParams p;
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.n = s.n;
+    p.Hv = 2 * s.N + s.n - 2;
+    p.Wl = 2 * s.N + s.n - 2;
+    // Virtual rows 128 consecutive positions can touch: two per row of positions, n across a
+    // batch-item boundary, and the n rows of the last position's taps.
+    const int dr = (B_TM - 2) / s.N + 1;
+    p.lrows = dr * (s.n > 2 ? s.n : 2) + s.n;
+    p.Mtot = s.B * s.N * s.N;
+    p.tiles_m = (p.Mtot + B_TM - 1) / B_TM;
+    p.tiles_ci = (s.Cin + B_TCI - 1) / B_TCI;
+    const int tiles = p.tiles_m * p.tiles_ci;
+    const int chunks = (s.Cout + B_KC - 1) / B_KC;
+    p.out_elems = (size_t)s.B * s.Cin * s.N * s.N;
+    // Split count: launch rounds on 256 CUs times a tile's share of the reduction, plus the
+    // summing pass; a split has to beat the unsplit launch by a tenth to be worth its workspace.
+    int splits = 1;
+    {
+        const double tile_s = (double)B_TM * B_TCI * s.Cout * s.n * s.n / 2.0e11;
+        const double out_b = (double)p.out_elems * 4.0;
+        double best = (double)((tiles + 255) / 256) * tile_s;
+        const double unsplit = best;
+        for (int c = 2; c <= 16 && c <= chunks; ++c) {
+            const double t = (double)(((size_t)tiles * c + 255) / 256) * tile_s / c + (c + 1) * out_b / 4.0e12;
+            if (t < best && t < 0.9 * unsplit) { best = t; splits = c; }
+        }
+    }
+    const int cps = (chunks + splits - 1) / splits;
+    p.co_per_split = cps * B_KC;
+    p.splits = (chunks + cps - 1) / cps;
+    return p;
+}
+
+size_t lds_bytes(const BwdParams &p)
+{
+    return ((size_t)B_KC * p.lrows * p.Wl + (size_t)B_KC * p.n * p.n * B_WST) * sizeof(float);
+}
+
+template <int n>
+hipError_t launch_n(const float *g, const float *w, float *dst, const BwdParams &p, hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_input_f32_kernel<n>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned blocks = (unsigned)p.tiles_m * p.tiles_ci * p.splits;
+    hipLaunchKernelGGL(backward_input_f32_kernel<n>, dim3(blocks), dim3(B_THREADS), lds, stream, g, w, dst, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// fp32 weights, kernels up to 5 x 5, a chunk of g that 16 elements per lane can stage, all
+// element counts inside 32 bits (the boundary checks the tensors; the virtual image is larger).
+bool backward_input_igemm_supported(const Shape &s, kst_dtype dt)
+{
+    if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
+    if (s.Cin < 8 || s.Cout < 8) return false;
+    const BwdParams p = plan(s);
+    if ((size_t)B_KC * p.lrows * p.Wl > (size_t)B_THREADS * B_PX) return false;
+    if (lds_bytes(p) > 160 * 1024) return false;
+    if ((size_t)s.B * p.Hv >= 0x7fffffffu / (size_t)p.Wl) return false;
+    if ((size_t)p.tiles_m * p.tiles_ci * p.splits >= 0x7fffffffu) return false;
+    return true;
+}
+
+size_t backward_input_igemm_workspace_bytes(const Shape &s)
+{
+    const BwdParams p = plan(s);
+    return p.splits > 1 ? (((size_t)p.splits * p.out_elems * sizeof(float) + 255) & ~(size_t)255) : 0;
+}
+
+hipError_t launch_backward_input_igemm(const float *g, const float *w, float *din, void *ws, const Shape &s,
+                                       hipStream_t stream)
+{
+    if (!backward_input_igemm_supported(s, KST_F32)) return hipErrorInvalidValue;
+    const BwdParams p = plan(s);
+    float *dst = p.splits > 1 ? (float *)ws : din;
+    hipError_t e;
+    switch (s.n) {
+        case 1: e = launch_n<1>(g, w, dst, p, stream); break;
+        case 2: e = launch_n<2>(g, w, dst, p, stream); break;
+        case 3: e = launch_n<3>(g, w, dst, p, stream); break;
+        case 4: e = launch_n<4>(g, w, dst, p, stream); break;
+        case 5: e = launch_n<5>(g, w, dst, p, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, din, p.out_elems, p.splits, stream);
+    return e;
+}
+
+}  // namespace kst

@@ -473,6 +473,47 @@ def test_gradients(B, Cin, Cout, N, n, P, dtype):
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (4, 136, 72, 16, 4, 2),    # two channel tiles, the second ragged; eleven position tiles
+    (64, 32, 16, 8, 4, 2),     # tiles that span several batch items
+    (2, 16, 264, 6, 5, 1),     # odd padding factor, long reduction: split over launches
+    (3, 24, 40, 33, 3, 0),     # odd map, position tiles cut rows
+    (2, 8, 8, 20, 2, 0),
+    (2, 9, 11, 12, 1, 0),
+    (1, 128, 128, 64, 4, 2),   # one row pair per tile
+])
+def test_input_gradient_on_the_matrix_cores(B, Cin, Cout, N, n, P):
+    """fp32 layers with at least 8 channels on either side take the MFMA input-gradient kernel."""
+    layer = wl.Layer("grad_mfma", B, Cin, Cout, N, n, "f32", "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 4000 + 13 * N + 7 * n + P)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(19 * N + n + P)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    torch.cuda.synchronize()
+    want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    assert din.shape == want.shape
+    assert rel_err(din.cpu().numpy(), want) <= GRAD_TOL["f32"]
+
+
+def test_input_gradient_on_the_matrix_cores_is_exact_on_integers_and_stays_inside_din():
+    layer = wl.Layer("grad_mfma_int", 3, 24, 16, 10, 5, "f32", "integer", P=2)
+    x, w = wl.make_tensors(layer, 98)
+    M = kst.kst_out_size_padded(layer.N, layer.n, layer.P)
+    gen = torch.Generator().manual_seed(6)
+    g = torch.randint(-3, 4, (3, 16, M, M), generator=gen).to(torch.float32)
+    numel = 3 * 24 * 10 * 10
+    guard = 1024
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    din = buf[guard:guard + numel].view(3, 24, 10, 10)
+    kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P, din=din)
+    torch.cuda.synchronize()
+    host = buf.cpu()
+    assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+    want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P)
+    assert np.array_equal(host[guard:guard + numel].view(3, 24, 10, 10).numpy().astype(np.float64), want)
+
+
 def test_gradients_are_exact_on_integers():
     layer = wl.Layer("grad_int", 2, 3, 4, 9, 5, "f32", "integer", P=2)
     x, w = wl.make_tensors(layer, 99)
