@@ -286,12 +286,12 @@ namespace {
 // Workspace of the gradient entry points: for P > 0 the unframed kernels run on framed copies.
 //   input gradient:  [g framed by one zero (odd P)] [din of the framed input] [partial sums of the
 //                    matrix-core kernel's split reduction]
-//   kernel gradient: [input framed by q] [g framed by one zero (odd P)]
+//   kernel gradient: [input framed by q] [g framed by one zero (odd P)] [partial sums, as above]
 struct GradPlan {
     int q, Nq, M, Mq;
     Shape s;                          // the unframed problem the kernels see
     size_t g_bytes, din_bytes, in_bytes;
-    size_t split_bytes;               // input gradient on the matrix cores: partial sums
+    size_t split_bytes, wsplit_bytes; // input / kernel gradient on the matrix cores: partial sums
 };
 
 kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
@@ -309,6 +309,7 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->din_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->in_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255) : 0;
     f->split_bytes = backward_input_igemm_supported(f->s, dt) ? backward_input_igemm_workspace_bytes(f->s) : 0;
+    f->wsplit_bytes = backward_weight_igemm_supported(f->s, dt) ? backward_weight_igemm_workspace_bytes(f->s) : 0;
     return KST_OK;
 }
 
@@ -325,7 +326,7 @@ size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int 
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return f.in_bytes + f.g_bytes;
+    return f.in_bytes + f.g_bytes + f.wsplit_bytes;
 }
 
 kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
@@ -369,7 +370,7 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(g) || !aligned16(dw)) return KST_ERR_ALIGN;
-    const size_t need = f.in_bytes + f.g_bytes;
+    const size_t need = f.in_bytes + f.g_bytes + f.wsplit_bytes;
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
@@ -384,6 +385,12 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
         void *gw = (char *)ws + f.in_bytes;
         if (launch_frame_input(g, gw, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
         g_in = (const float *)gw;
+    }
+    if (backward_weight_igemm_supported(f.s, dtype)) {
+        void *split_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + f.g_bytes : nullptr;
+        return launch_backward_weight_igemm((const float *)x_in, g_in, (float *)dw, split_ws, f.s, stream) == hipSuccess
+                   ? KST_OK
+                   : KST_ERR_HIP;
     }
     return launch_backward_weight_generic(x_in, g_in, (float *)dw, f.s, dtype, stream) == hipSuccess ? KST_OK
                                                                                                       : KST_ERR_HIP;

@@ -1,4 +1,5 @@
-// Input gradient of the transpose convolution on the matrix cores (fp32).
+// Gradients of the transpose convolution on the matrix cores (fp32): input gradient first,
+// kernel gradient below.
 //
 // End of Section 3.3: the segregated method also serves back-propagation.  With
 // g = d(loss)/d(out) and no padding factor,
@@ -283,6 +284,230 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
     }
     if (e != hipSuccess) return e;
     if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, din, p.out_elems, p.splits, stream);
+    return e;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel gradient on the matrix cores (fp32):
+//
+//   dw[co][ci][u][v] = sum_b sum_a sum_c in[b][ci][a][c] * g[b][co][2a-u][2c-v]
+//
+// over the terms whose g index lies inside the map.  As n * n GEMMs that share their B
+// operand: rows = output channels co (A gathered from g at stride 2, shifted by the tap),
+// columns = input channels ci, reduction over the positions (b, a, c).
+//
+// Tile: 32 co x 32 ci x all n * n taps per 256-thread workgroup; the taps are dealt over the
+// four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4) accumulators.
+// The reduction walks chunks of up to 16 consecutive positions of one input row; per chunk
+// the workgroup stages the 32 x CW inputs and, zero-framed so that every tap reads inside the
+// image, the n rows x (2 CW + n - 2) columns of g the chunk's taps touch for its 32 output
+// channels.  The position range is split over workgroups; the partial sums are added by the
+// forward path's reduction pass (fixed order).
+namespace {
+
+constexpr int W_T = 32;          // output channels = input channels per workgroup
+constexpr int W_THREADS = 256;
+constexpr int W_CW = 16;         // positions per chunk at most
+constexpr int W_PE = 26;         // elements a lane stages per chunk at most
+
+struct BwdWParams {
+    int B, Cin, Cout, N, M, n;
+    int cw;                // positions per chunk (even), column chunks per row
+    int ccs;
+    int is, gl, gs;        // LDS: floats per staged input channel, columns and floats per staged g channel
+    int nchunks, chunks_per_split, splits;
+    int tiles_co, tiles_ci;
+    size_t out_elems;
+};
+
+template <int n>
+__global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const float *__restrict__ in,
+                                                                         const float *__restrict__ g,
+                                                                         float *__restrict__ dst, BwdWParams p)
+{
+    constexpr int NN = n * n;
+    constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float *Is = lds;                                             // [W_T][is]
+    float *Gs = lds + W_T * p.is;                                // [W_T][n][gl] (channel stride gs)
+
+    unsigned id = blockIdx.x;
+    const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
+    id /= (unsigned)p.tiles_ci;
+    const int tile_co = (int)(id % (unsigned)p.tiles_co);
+    const int split = (int)(id / (unsigned)p.tiles_co);
+    const int co0 = tile_co * W_T, ci0 = tile_ci * W_T;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kk = lane >> 5;
+
+    // ---- staging plan: element e of a chunk, the same for every chunk --------------------------
+    // e < W_T * cw: input (ci, cc).  Then g: (co, lr, lc) with row y = 2a - (n - 1) + lr and column
+    // x = 2 c0 - (n - 1) + lc.
+    const int n_in = W_T * p.cw, n_all = n_in + W_T * n * p.gl;
+    int e_lds[W_PE], e_y[W_PE], e_x[W_PE];         // LDS float index; row / column offset; e_y = -1: input element
+    unsigned e_ch[W_PE];                           // channel's element offset in its tensor
+#pragma unroll
+    for (int k = 0; k < W_PE; ++k) {
+        const int e = tid + k * W_THREADS;
+        if (e < n_in) {
+            const int ci = e / p.cw, cc = e - ci * p.cw;
+            e_lds[k] = ci * p.is + cc;
+            e_y[k] = -1;
+            e_x[k] = cc;
+            e_ch[k] = ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0xffffffffu;
+        } else if (e < n_all) {
+            const int r = e - n_in;
+            const int co = r / (n * p.gl);
+            const int rem = r - co * (n * p.gl);
+            const int lr = rem / p.gl, lc = rem - lr * p.gl;
+            e_lds[k] = W_T * p.is + co * p.gs + lr * p.gl + lc;
+            e_y[k] = lr;
+            e_x[k] = lc;
+            e_ch[k] = co0 + co < p.Cout ? (unsigned)(co0 + co) * p.M * p.M : 0xffffffffu;
+        } else {
+            e_lds[k] = -1;
+            e_y[k] = 0; e_x[k] = 0; e_ch[k] = 0xffffffffu;
+        }
+    }
+
+    floatx16 acc[TW];
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    const int chunk_begin = split * p.chunks_per_split;
+    const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
+    const int ibase = l32 * p.is + kk;                           // B operand: input channel l32, position 2 k2 + kk
+    const int gbase = W_T * p.is + l32 * p.gs + 2 * kk + (n - 1);   // A operand: output channel l32, tap (0, 0)
+
+    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
+        const int row = ch / p.ccs, cchunk = ch - row * p.ccs;
+        const int b = row / p.N, a = row - b * p.N;
+        const int c0 = cchunk * p.cw;
+        const unsigned in_row = ((unsigned)b * p.Cin * p.N + a) * p.N + c0;       // + channel * N * N + cc
+        const int y0 = 2 * a - (n - 1), x0 = 2 * c0 - (n - 1);
+        const unsigned g_img = (unsigned)b * p.Cout * p.M * p.M;
+        __syncthreads();                                         // every wave is done with the previous chunk
+#pragma unroll
+        for (int k = 0; k < W_PE; ++k) {
+            if (e_lds[k] < 0) continue;
+            float v = 0.0f;
+            if (e_ch[k] != 0xffffffffu) {
+                if (e_y[k] < 0) {
+                    if (c0 + e_x[k] < p.N) v = in[in_row + e_ch[k] + e_x[k]];
+                } else {
+                    const int y = y0 + e_y[k], x = x0 + e_x[k];
+                    if (y >= 0 && y < p.M && x >= 0 && x < p.M) v = g[g_img + e_ch[k] + (unsigned)y * p.M + x];
+                }
+            }
+            lds[e_lds[k]] = v;
+        }
+        __syncthreads();
+        for (int k2 = 0; k2 < p.cw; k2 += 2) {
+            const float bf = Is[ibase + k2];
+#pragma unroll
+            for (int t = 0; t < TW; ++t) {
+                const int uv = wave + 4 * t;                     // wave-uniform
+                if (uv < NN) {
+                    const int u = uv / n, v = uv - u * n;
+                    const float af = Gs[gbase - W_T * p.is + (n - 1 - u) * p.gl + 2 * k2 - v];
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc[t], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // acc[t][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + l32, tap wave + 4 t
+    float *o = dst + (size_t)split * p.out_elems;
+    const int ci = ci0 + l32;
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const int uv = wave + 4 * t;
+        if (uv >= NN || ci >= p.Cin) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][v];
+        }
+    }
+}
+
+BwdWParams plan_w(const Shape &s)
+{
+    BwdWParams p;
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.n = s.n;
+    const int npad = (s.N + 1) & ~1;
+    p.cw = npad < W_CW ? npad : W_CW;
+    p.ccs = (s.N + p.cw - 1) / p.cw;
+    p.is = p.cw + 1;                                   // odd strides: lanes of different channels hit different banks
+    p.gl = 2 * p.cw + s.n - 2;
+    p.gs = s.n * p.gl + ((s.n * p.gl) % 2 == 0 ? 1 : 0);
+    p.nchunks = s.B * s.N * p.ccs;
+    p.tiles_co = (s.Cout + W_T - 1) / W_T;
+    p.tiles_ci = (s.Cin + W_T - 1) / W_T;
+    p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
+    // About four workgroups per CU, as long as every split keeps a few chunks.
+    const int tiles = p.tiles_co * p.tiles_ci;
+    int splits = (1024 + tiles - 1) / tiles;
+    if (splits > p.nchunks / 4) splits = p.nchunks / 4;
+    if (splits > 64) splits = 64;
+    if (splits < 1) splits = 1;
+    p.chunks_per_split = (p.nchunks + splits - 1) / splits;
+    p.splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    return p;
+}
+
+size_t lds_bytes_w(const BwdWParams &p) { return ((size_t)W_T * p.is + (size_t)W_T * p.gs) * sizeof(float); }
+
+template <int n>
+hipError_t launch_w(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
+    hipLaunchKernelGGL(backward_weight_f32_kernel<n>, dim3(blocks), dim3(W_THREADS), lds_bytes_w(p), stream, in, g, dst, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// fp32 operands, kernels up to 5 x 5, at least 8 channels on either side; element counts
+// inside 32 bits are the boundary's business.
+bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt)
+{
+    if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
+    if (s.Cin < 8 || s.Cout < 8) return false;
+    const BwdWParams p = plan_w(s);
+    if (W_T * p.cw + W_T * s.n * p.gl > W_THREADS * W_PE) return false;
+    if (lds_bytes_w(p) > 64 * 1024) return false;
+    if ((size_t)p.tiles_ci * p.tiles_co * p.splits >= 0x7fffffffu) return false;
+    return true;
+}
+
+size_t backward_weight_igemm_workspace_bytes(const Shape &s)
+{
+    const BwdWParams p = plan_w(s);
+    return p.splits > 1 ? (((size_t)p.splits * p.out_elems * sizeof(float) + 255) & ~(size_t)255) : 0;
+}
+
+hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *dw, void *ws, const Shape &s,
+                                        hipStream_t stream)
+{
+    if (!backward_weight_igemm_supported(s, KST_F32)) return hipErrorInvalidValue;
+    const BwdWParams p = plan_w(s);
+    float *dst = p.splits > 1 ? (float *)ws : dw;
+    hipError_t e;
+    switch (s.n) {
+        case 1: e = launch_w<1>(in, g, dst, p, stream); break;
+        case 2: e = launch_w<2>(in, g, dst, p, stream); break;
+        case 3: e = launch_w<3>(in, g, dst, p, stream); break;
+        case 4: e = launch_w<4>(in, g, dst, p, stream); break;
+        case 5: e = launch_w<5>(in, g, dst, p, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, dw, p.out_elems, p.splits, stream);
     return e;
 }
 

@@ -76,12 +76,16 @@ hipError_t launch_backward_input_generic(const float *g, const void *w, float *d
                                          hipStream_t stream);
 hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, const Shape &s, kst_dtype dt,
                                           hipStream_t stream);
-// Input gradient on the matrix cores (fp32 weights, kernels up to 5 x 5): whether it takes the
-// shape, the scratch of its split reduction, launch.
+// Input and kernel gradient on the matrix cores (fp32 operands, kernels up to 5 x 5): whether
+// they take the shape, the scratch of their split reductions, launch.
 bool backward_input_igemm_supported(const Shape &s, kst_dtype dt);
 size_t backward_input_igemm_workspace_bytes(const Shape &s);
 hipError_t launch_backward_input_igemm(const float *g, const float *w, float *din, void *ws, const Shape &s,
                                        hipStream_t stream);
+bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt);
+size_t backward_weight_igemm_workspace_bytes(const Shape &s);
+hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *dw, void *ws, const Shape &s,
+                                        hipStream_t stream);
 // Direct path: any shape.
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream);

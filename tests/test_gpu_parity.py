@@ -482,21 +482,25 @@ def test_gradients(B, Cin, Cout, N, n, P, dtype):
     (2, 9, 11, 12, 1, 0),
     (1, 128, 128, 64, 4, 2),   # one row pair per tile
 ])
-def test_input_gradient_on_the_matrix_cores(B, Cin, Cout, N, n, P):
-    """fp32 layers with at least 8 channels on either side take the MFMA input-gradient kernel."""
+def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
+    """fp32 layers with at least 8 channels on either side take the MFMA gradient kernels."""
     layer = wl.Layer("grad_mfma", B, Cin, Cout, N, n, "f32", "normal", w_std=0.2, P=P)
     x, w = wl.make_tensors(layer, 4000 + 13 * N + 7 * n + P)
     M = kst.kst_out_size_padded(N, n, P)
     gen = torch.Generator().manual_seed(19 * N + n + P)
     g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
     din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
     torch.cuda.synchronize()
     want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
     assert din.shape == want.shape
     assert rel_err(din.cpu().numpy(), want) <= GRAD_TOL["f32"]
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert dw.shape == want_dw.shape
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL["f32"]
 
 
-def test_input_gradient_on_the_matrix_cores_is_exact_on_integers_and_stays_inside_din():
+def test_gradients_on_the_matrix_cores_are_exact_on_integers_and_stay_inside_their_outputs():
     layer = wl.Layer("grad_mfma_int", 3, 24, 16, 10, 5, "f32", "integer", P=2)
     x, w = wl.make_tensors(layer, 98)
     M = kst.kst_out_size_padded(layer.N, layer.n, layer.P)
@@ -507,11 +511,19 @@ def test_input_gradient_on_the_matrix_cores_is_exact_on_integers_and_stays_insid
     buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
     din = buf[guard:guard + numel].view(3, 24, 10, 10)
     kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P, din=din)
+    wn = 16 * 24 * 25
+    wbuf = torch.full((wn + 2 * guard,), float("nan"), device=DEV)
+    dw = wbuf[guard:guard + wn].view(16, 24, 5, 5)
+    kst.kst_backward_weight(x.to(DEV), g.to(DEV), layer.n, layer.P, dw=dw)
     torch.cuda.synchronize()
     host = buf.cpu()
     assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
     want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P)
     assert np.array_equal(host[guard:guard + numel].view(3, 24, 10, 10).numpy().astype(np.float64), want)
+    whost = wbuf.cpu()
+    assert torch.isnan(whost[:guard]).all() and torch.isnan(whost[guard + wn:]).all()
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P)
+    assert np.array_equal(whost[guard:guard + wn].view(16, 24, 5, 5).numpy().astype(np.float64), want_dw)
 
 
 def test_gradients_are_exact_on_integers():
