@@ -301,7 +301,8 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 // The reduction walks chunks of up to 16 consecutive positions of one input row; per chunk
 // the workgroup stages the 32 x CW inputs and, zero-framed so that every tap reads inside the
 // image, the n rows x (2 CW + n - 2) columns of g the chunk's taps touch for its 32 output
-// channels.  The position range is split over workgroups; the partial sums are added by the
+// channels, fetched into registers while the previous chunk is multiplied.  The position
+// range is split over workgroups; the partial sums are added by the
 // forward path's reduction pass (fixed order).
 namespace {
 
@@ -383,19 +384,19 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
     const int ibase = l32 * p.is + kk;                           // B operand: input channel l32, position 2 k2 + kk
     const int gbase = W_T * p.is + l32 * p.gs + 2 * kk + (n - 1);   // A operand: output channel l32, tap (0, 0)
 
-    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
+    // The elements of chunk ch + 1 are fetched into registers while chunk ch is multiplied.
+    float e_reg[W_PE];
+    auto fetch = [&](int ch) {
         const int row = ch / p.ccs, cchunk = ch - row * p.ccs;
         const int b = row / p.N, a = row - b * p.N;
         const int c0 = cchunk * p.cw;
         const unsigned in_row = ((unsigned)b * p.Cin * p.N + a) * p.N + c0;       // + channel * N * N + cc
         const int y0 = 2 * a - (n - 1), x0 = 2 * c0 - (n - 1);
         const unsigned g_img = (unsigned)b * p.Cout * p.M * p.M;
-        __syncthreads();                                         // every wave is done with the previous chunk
 #pragma unroll
         for (int k = 0; k < W_PE; ++k) {
-            if (e_lds[k] < 0) continue;
             float v = 0.0f;
-            if (e_ch[k] != 0xffffffffu) {
+            if (e_lds[k] >= 0 && e_ch[k] != 0xffffffffu) {
                 if (e_y[k] < 0) {
                     if (c0 + e_x[k] < p.N) v = in[in_row + e_ch[k] + e_x[k]];
                 } else {
@@ -403,9 +404,17 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
                     if (y >= 0 && y < p.M && x >= 0 && x < p.M) v = g[g_img + e_ch[k] + (unsigned)y * p.M + x];
                 }
             }
-            lds[e_lds[k]] = v;
+            e_reg[k] = v;
         }
+    };
+    if (chunk_begin < chunk_end) fetch(chunk_begin);
+    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
+        __syncthreads();                                         // every wave is done with the previous chunk
+#pragma unroll
+        for (int k = 0; k < W_PE; ++k)
+            if (e_lds[k] >= 0) lds[e_lds[k]] = e_reg[k];
         __syncthreads();
+        if (ch + 1 < chunk_end) fetch(ch + 1);
         for (int k2 = 0; k2 < p.cw; k2 += 2) {
             const float bf = Is[ibase + k2];
 #pragma unroll
