@@ -309,7 +309,8 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->din_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->in_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255) : 0;
     f->split_bytes = backward_input_igemm_supported(f->s, dt) ? backward_input_igemm_workspace_bytes(f->s) : 0;
-    f->wsplit_bytes = backward_weight_igemm_supported(f->s, dt) ? backward_weight_igemm_workspace_bytes(f->s) : 0;
+    f->wsplit_bytes = backward_weight_igemm_supported(f->s, dt) ? backward_weight_igemm_workspace_bytes(f->s)
+                                                               : backward_weight_generic_workspace_bytes(f->s);
     return KST_OK;
 }
 
@@ -392,8 +393,10 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
                    ? KST_OK
                    : KST_ERR_HIP;
     }
-    return launch_backward_weight_generic(x_in, g_in, (float *)dw, f.s, dtype, stream) == hipSuccess ? KST_OK
-                                                                                                      : KST_ERR_HIP;
+    void *slice_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + f.g_bytes : nullptr;
+    return launch_backward_weight_generic(x_in, g_in, (float *)dw, slice_ws, f.s, dtype, stream) == hipSuccess
+               ? KST_OK
+               : KST_ERR_HIP;
 }
 
 kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void *out, int B, int Cin, int Cout,

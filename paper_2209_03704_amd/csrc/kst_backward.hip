@@ -11,7 +11,7 @@
 // output rows of parity r only: g[2a-u] = g[2(a-r-al)+r].
 //
 // This file: the kernels that take any shape and either operand type (plain ALU work).
-#include "kst_internal.h"
+#include "kst_igemm_common.h"
 
 namespace kst {
 
@@ -46,22 +46,27 @@ __global__ void __launch_bounds__(256) backward_input_generic_kernel(const float
     din[e] = acc;
 }
 
-// One workgroup per (co, ci): each thread sums its share of (b, a, c) for all n * n kernel
-// elements (n <= 7 kept in registers, else a loop over elements), then a tree in LDS.
+// One workgroup per (co, ci) and slice of the positions: each thread sums its share of the
+// slice's (b, a, c) for one kernel element at a time, then a tree in LDS.  With more than one
+// slice the workgroups write partial sums [slice][co][ci][u][v] that a second pass adds up.
 template <typename T>
 __global__ void __launch_bounds__(256) backward_weight_generic_kernel(const T *__restrict__ in, const float *__restrict__ g,
-                                                                       float *__restrict__ dw, int B, int Cin, int Cout,
-                                                                       int N, int M, int n)
+                                                                       float *__restrict__ dst, int B, int Cin, int Cout,
+                                                                       int N, int M, int n, int per_slice)
 {
     __shared__ float red[256];
-    const int co = blockIdx.x / Cin, ci = blockIdx.x - co * Cin;
+    const int pairs = Cout * Cin;
+    const int slice = blockIdx.x / pairs, pair = blockIdx.x - slice * pairs;
+    const int co = pair / Cin, ci = pair - co * Cin;
     const int tid = threadIdx.x;
     const int per_item = N * N;
     const int total = B * per_item;
+    const int e_begin = slice * per_slice, e_end = min(total, e_begin + per_slice);
+    float *o = dst + (size_t)slice * pairs * n * n;
     for (int uv = 0; uv < n * n; ++uv) {
         const int u = uv / n, v = uv - u * n;
         float acc = 0.0f;
-        for (int e = tid; e < total; e += 256) {
+        for (int e = e_begin + tid; e < e_end; e += 256) {
             const int b = e / per_item, rem = e - b * per_item;
             const int a = rem / N, c = rem - a * N;
             const int y = 2 * a - u, x = 2 * c - v;
@@ -75,9 +80,20 @@ __global__ void __launch_bounds__(256) backward_weight_generic_kernel(const T *_
             if (tid < s) red[tid] += red[tid + s];
             __syncthreads();
         }
-        if (tid == 0) dw[((size_t)co * Cin + ci) * n * n + uv] = red[0];
+        if (tid == 0) o[((size_t)co * Cin + ci) * n * n + uv] = red[0];
         __syncthreads();
     }
+}
+
+// Slices of the position range: few (co, ci) pairs alone cannot fill the chip.
+int weight_slices(const Shape &s)
+{
+    const long long pairs = (long long)s.Cout * s.Cin;
+    const long long total = (long long)s.B * s.N * s.N;
+    long long slices = (1024 + pairs - 1) / pairs;
+    if (slices > 256) slices = 256;
+    if (slices > (total + 1023) / 1024) slices = (total + 1023) / 1024;   // at least 1024 positions per slice
+    return slices < 1 ? 1 : (int)slices;
 }
 
 }  // namespace
@@ -96,17 +112,29 @@ hipError_t launch_backward_input_generic(const float *g, const void *w, float *d
     return hipGetLastError();
 }
 
-hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, const Shape &s, kst_dtype dt,
-                                          hipStream_t stream)
+size_t backward_weight_generic_workspace_bytes(const Shape &s)
 {
-    const unsigned blocks = (unsigned)s.Cout * (unsigned)s.Cin;
+    const int slices = weight_slices(s);
+    return slices > 1 ? (((size_t)slices * s.Cout * s.Cin * s.n * s.n * sizeof(float) + 255) & ~(size_t)255) : 0;
+}
+
+hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, void *ws, const Shape &s,
+                                          kst_dtype dt, hipStream_t stream)
+{
+    const int slices = weight_slices(s);
+    const int total = s.B * s.N * s.N;
+    const int per_slice = (total + slices - 1) / slices;
+    const unsigned blocks = (unsigned)s.Cout * (unsigned)s.Cin * (unsigned)slices;
+    float *dst = slices > 1 ? (float *)ws : dw;
     if (dt == KST_BF16)
         hipLaunchKernelGGL(backward_weight_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
-                           (const uint16_t *)in, g, dw, s.B, s.Cin, s.Cout, s.N, s.M, s.n);
+                           (const uint16_t *)in, g, dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
     else
         hipLaunchKernelGGL(backward_weight_generic_kernel<float>, dim3(blocks), dim3(256), 0, stream, (const float *)in, g,
-                           dw, s.B, s.Cin, s.Cout, s.N, s.M, s.n);
-    return hipGetLastError();
+                           dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || slices == 1) return e;
+    return launch_splitk_reduce((const float *)ws, dw, (size_t)s.Cout * s.Cin * s.n * s.n, slices, stream);
 }
 
 }  // namespace kst

@@ -74,8 +74,9 @@ hipError_t launch_crop(const float *wide, float *out, int planes_b, int planes_c
 // Gradients, P = 0, any shape (plain ALU kernels).  g, din and dw are fp32; w and in are of type dt.
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream);
-hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, const Shape &s, kst_dtype dt,
-                                          hipStream_t stream);
+size_t backward_weight_generic_workspace_bytes(const Shape &s);    // partial sums when the positions are sliced
+hipError_t launch_backward_weight_generic(const void *in, const float *g, float *dw, void *ws, const Shape &s,
+                                          kst_dtype dt, hipStream_t stream);
 // Input and kernel gradient on the matrix cores (fp32 operands, kernels up to 5 x 5): whether
 // they take the shape, the scratch of their split reductions, launch.
 bool backward_input_igemm_supported(const Shape &s, kst_dtype dt);

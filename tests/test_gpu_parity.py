@@ -500,6 +500,27 @@ def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL["f32"]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (4, 3, 1, 40, 5, 2),       # few channels, many positions: the kernel gradient slices the positions
+    (2, 3, 2, 63, 3, 0),
+    (16, 1, 1, 33, 4, 1),
+])
+def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
+    layer = wl.Layer("grad_few", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 5000 + 13 * N + 7 * n + P)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(23 * N + n + P)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    torch.cuda.synchronize()
+    want_din = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL[dtype]
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
+
+
 def test_gradients_on_the_matrix_cores_are_exact_on_integers_and_stay_inside_their_outputs():
     layer = wl.Layer("grad_mfma_int", 3, 24, 16, 10, 5, "f32", "integer", P=2)
     x, w = wl.make_tensors(layer, 98)
