@@ -192,6 +192,36 @@ def main():
     del r
     torch.cuda.empty_cache()
 
+    # ---- yardsticks: what the chip sustains with nothing in the way --------------------------
+    yard = None
+    if args.layers == "all":
+        n = 64 * 1024 * 1024
+        cb = [(torch.empty(n, dtype=torch.float32, device="cuda").normal_(),
+               torch.empty(n, dtype=torch.float32, device="cuda")) for _ in range(3)]
+        copy_ms = time_launches(torch, lambda i: kst.kst_yardstick_copy(cb[i % 3][0], cb[i % 3][1]), 30, 5)
+        del cb
+        torch.cuda.empty_cache()
+        sink = torch.empty(kst.kst_yardstick_mfma_sink_elems(), dtype=torch.float32, device="cuda")
+        f32_it, bf16_it = 2048, 4096
+        f32_ms = time_launches(torch, lambda i: kst.kst_yardstick_mfma(kst.KST_F32, f32_it, sink), 30, 10)
+        bf16_ms = time_launches(torch, lambda i: kst.kst_yardstick_mfma(kst.KST_BF16, bf16_it, sink), 30, 10)
+        yard = {
+            "copy_GB_per_s": round(8 * n / (copy_ms * 1e-3) / 1e9, 1),
+            "mfma_TFLOP_per_s": {
+                "f32": round(kst.kst_yardstick_mfma_flops(kst.KST_F32, f32_it) / (f32_ms * 1e-3) / 1e12, 1),
+                "bf16": round(kst.kst_yardstick_mfma_flops(kst.KST_BF16, bf16_it) / (bf16_ms * 1e-3) / 1e12, 1)},
+            "what": "256 MiB streaming copy (bytes read + written); loops of matrix-core instructions only, "
+                    "two waves per SIMD on all CUs",
+        }
+        del sink
+
+    def of_measured(layer, roof_l):
+        if yard is None:
+            return None
+        if roof_l["bound"] == "hbm":
+            return round(roof_l["achieved"] / yard["copy_GB_per_s"], 4)
+        return round(roof_l["achieved"] / yard["mfma_TFLOP_per_s"][layer.dtype], 4)
+
     # ---- per-layer table ---------------------------------------------------------------------
     table = []
     if args.layers == "all":
@@ -204,13 +234,17 @@ def main():
             U = torch.empty((layer.B, layer.Cin, 2 * layer.N - 1, 2 * layer.N - 1), dtype=r.w.dtype, device="cuda")
             zi_ms = time_launches(
                 torch, lambda i: kst.kst_forward_zero_insert(r.x[0], r.w, U=U, out=r.out[0]), 2, 1)
+            unseg_ms = time_launches(torch, lambda i: kst.kst_forward(r.x[i % r.sets], r.w, out=r.out[i % r.sets]),
+                                     min(iters, 10), 2)
             roof_l = roofline_for(layer, ms, metrics)
+            roof_l["frac_of_measured_yardstick"] = of_measured(layer, roof_l)
             table.append({
                 "layer": layer.name,
                 "shape": {"B": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n,
                           "dtype": layer.dtype},
                 "forward_us": round(ms * 1e3, 2),
                 "segregate_us": round(seg_ms * 1e3, 2),
+                "forward_unsegregated_w_us": round(unseg_ms * 1e3, 2),
                 "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
                 "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
                 "hbm_frac": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),
@@ -235,7 +269,7 @@ def main():
             ms = time_launches(
                 torch, lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P,
                                                             out=outs[i % 3], ws=ws), 30, 5)
-            # gradients of the same layer (plain ALU kernels, not tuned): g = d(loss)/d(out)
+            # gradients of the same layer: g = d(loss)/d(out)
             g = torch.randn(layer.out_shape, dtype=torch.float32, device="cuda")
             wd = w.cuda()
             din = torch.empty((layer.B, layer.Cin, layer.N, layer.N), dtype=torch.float32, device="cuda")
@@ -245,8 +279,8 @@ def main():
                 layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
             ws_bw = torch.empty(max(kst.kst_backward_weight_workspace_bytes(
                 layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
-            bi_ms = time_launches(torch, lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws_bi), 2, 1)
-            bw_ms = time_launches(torch, lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws_bw), 2, 1)
+            bi_ms = time_launches(torch, lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws_bi), 10, 2)
+            bw_ms = time_launches(torch, lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws_bw), 10, 2)
             del g, din, dw, ws_bi, ws_bw
             paper_table.append({
                 "layer": layer.name,
@@ -281,6 +315,7 @@ def main():
                    "step": "kst_segregate_weights + kst_forward_seg, inputs resident in HBM, 3 rotating buffer sets"},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "yardsticks": yard,
         "layers": table,
         "paper_shaped_layers": paper_table,
         "paper_context": "paper reports 3.7x (Xeon CPU) / 3.4x (RTX 2070) average speed-up over zero-insert; ideal 4x",

@@ -43,6 +43,10 @@ SIGNATURES = {
     "kst_backward_weight_workspace_bytes": (_c_size_t, [_c_int] * 7),
     "kst_backward_input": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
     "kst_backward_weight": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
+    "kst_yardstick_mfma_sink_elems": (_c_size_t, []),
+    "kst_yardstick_mfma_flops": (ctypes.c_double, [_c_int, _c_int]),
+    "kst_yardstick_mfma": (_c_int, [_c_int, _c_int, _c_void_p, _c_size_t, _c_void_p]),
+    "kst_yardstick_copy": (_c_int, [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
 }
 
 
@@ -306,3 +310,34 @@ def kst_backward_input_workspace_bytes(B, Cin, Cout, N, n, P, dtype: int) -> int
 
 def kst_backward_weight_workspace_bytes(B, Cin, Cout, N, n, P, dtype: int) -> int:
     return lib().kst_backward_weight_workspace_bytes(B, Cin, Cout, N, n, P, dtype)
+
+
+def kst_yardstick_mfma_sink_elems() -> int:
+    return lib().kst_yardstick_mfma_sink_elems()
+
+
+def kst_yardstick_mfma_flops(dtype: int, iters: int) -> float:
+    return lib().kst_yardstick_mfma_flops(dtype, iters)
+
+
+def kst_yardstick_mfma(dtype: int, iters: int, sink: torch.Tensor | None = None) -> torch.Tensor:
+    """One launch of the matrix-core-only loop; returns the sink tensor (values carry no meaning)."""
+    need = lib().kst_yardstick_mfma_sink_elems()
+    if sink is None:
+        sink = torch.empty(need, dtype=torch.float32, device="cuda")
+    if sink.dtype != torch.float32:
+        raise ValueError("sink must be float32")
+    st = lib().kst_yardstick_mfma(dtype, iters, _dev(sink, "sink"), sink.numel(), _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_yardstick_mfma")
+    return sink
+
+
+def kst_yardstick_copy(src: torch.Tensor, dst: torch.Tensor) -> torch.Tensor:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    st = lib().kst_yardstick_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_yardstick_copy")
+    return dst

@@ -411,4 +411,29 @@ kst_status kst_forward_zero_insert(const void *in, const void *w, void *U, void 
     return launch_zero_insert(in, w, U, (float *)out, s, dtype, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
 }
 
+size_t kst_yardstick_mfma_sink_elems(void) { return yardstick_mfma_sink_elems(); }
+
+double kst_yardstick_mfma_flops(kst_dtype dtype, int iters)
+{
+    if (!dtype_ok(dtype) || iters < 1) return 0.0;
+    return yardstick_mfma_flops(dtype, iters);
+}
+
+kst_status kst_yardstick_mfma(kst_dtype dtype, int iters, float *sink, size_t sink_elems, hipStream_t stream)
+{
+    if (!sink) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    if (iters < 1 || iters > (1 << 22)) return KST_ERR_SHAPE;
+    if (sink_elems < yardstick_mfma_sink_elems()) return KST_ERR_WORKSPACE;
+    return launch_yardstick_mfma(dtype, iters, sink, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
+kst_status kst_yardstick_copy(const void *src, void *dst, size_t bytes, hipStream_t stream)
+{
+    if (!src || !dst) return KST_ERR_NULL;
+    if (bytes % 16 != 0) return KST_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return KST_ERR_ALIGN;
+    return launch_yardstick_copy(src, dst, bytes, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
+}
+
 }  // extern "C"

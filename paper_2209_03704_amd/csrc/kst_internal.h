@@ -67,6 +67,11 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
                             hipStream_t stream);
 hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out, const Shape &s,
                               kst_dtype dt, hipStream_t stream);
+// Measurement yardsticks: a loop of matrix-core instructions only, and a streaming copy.
+size_t yardstick_mfma_sink_elems();
+double yardstick_mfma_flops(kst_dtype dt, int iters);
+hipError_t launch_yardstick_mfma(kst_dtype dt, int iters, float *sink, hipStream_t stream);
+hipError_t launch_yardstick_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 // Frame the input by q zeros on every side / drop the outermost rows and columns of an output.
 hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, int Ns, kst_dtype dt,
                               hipStream_t stream);
