@@ -211,8 +211,7 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     if (f->chosen == KST_PATH_IGEMM && dt == KST_F32 && (f->Nq & 3) != 0) {
         Shape wide = f->s;
         wide.Ns = (f->Nq + 3) & ~3;
-        if (igemm_f32_takes_row_stride(wide) && workspace_for(wide, dt, f->chosen) == workspace_for(f->s, dt, f->chosen))
-            f->s = wide;
+        if (igemm_f32_takes_row_stride(wide)) f->s = wide;
     }
     f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
     f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;

@@ -20,6 +20,7 @@ struct IgemmParams {
     int lrows;             // input rows (stacked over batch items) held per channel
     unsigned off[4];       // element offset of W_p
     size_t out_elems;
+    double est_s;          // the cost model's time for the launch chosen here (seconds)
 };
 
 // kc: input channels staged per step.
@@ -45,6 +46,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     // `splits` copies and writes one).  A split has to beat the unsplit launch by a tenth to be
     // worth its workspace.
     int splits = 1;
+    double est;
     {
         const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt == KST_BF16 ? 1.0e12 : 2.0e11);
         const double out_b = (double)s.B * s.Cout * s.M * s.M * 4.0;
@@ -54,7 +56,9 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
             const double t = (double)(((size_t)tiles * c + 255) / 256) * tile_s / c + (c + 1) * out_b / 4.0e12;
             if (t < best && t < 0.9 * unsplit) { best = t; splits = c; }
         }
+        est = best;
     }
+    p.est_s = est;
     const int cps = (chunks + splits - 1) / splits;
     p.ci_per_split = cps * kc;
     p.splits = (chunks + cps - 1) / cps;

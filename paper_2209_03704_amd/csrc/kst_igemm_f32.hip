@@ -145,30 +145,46 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__res
 // ---------------------------------------------------------------------------
 constexpr int P_NX4 = 2;         // input float4 per lane per chunk at most
 
+// What a lane needs to know about its column of the tile when the accumulators are stored.
+struct PipeLane {
+    int mb, mi, mj;      // batch item and quad of this lane's position
+    bool m_valid;        // false for lanes past the last position (they computed a clamped copy)
+};
+
+// Geometry of lane `tid` in position tile `tile_m` (no memory access).
+__device__ __forceinline__ PipeLane pipe_lane(const IgemmParams &p, int tile_m, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    int m = tile_m * G_TM + (wave >> 1) * 32 + (lane & 31);
+    PipeLane L;
+    L.m_valid = m < p.Mtot;
+    if (!L.m_valid) m = p.Mtot - 1;
+    L.mb = m / p.EE;
+    const int mrem = m - L.mb * p.EE;
+    L.mi = mrem / p.E;
+    L.mj = mrem - L.mi * p.E;
+    return L;
+}
+
+// acc = the tile's sums over input channels [ci_begin, ci_end).  Every thread of the workgroup
+// calls it; LDS is free to be overwritten once all of them have passed a barrier afterwards.
 template <int n>
-__global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *__restrict__ in,
-                                                                     const float *__restrict__ w_seg,
-                                                                     float *__restrict__ dst, IgemmParams p)
+__device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, const float *__restrict__ w_seg,
+                                                const IgemmParams &p, float *lds, int tile_m, int tile_co,
+                                                int ci_begin, int ci_end, const PipeLane &L, int tid,
+                                                floatx16 (&acc)[4][2])
 {
     constexpr int fl = n / 2;
     constexpr int NN = n * n;
     constexpr int W4 = G_KC * NN * (G_TCO / 4);                  // weight float4 per chunk
     constexpr int NW4 = (W4 + G_THREADS - 1) / G_THREADS;        // ... per lane
-    extern __shared__ __attribute__((aligned(16))) float lds[];
     const int xplane = p.lrows * p.Ns;                           // floats per staged channel (multiple of 4)
     float *Xs = lds;                                             // [G_KC][xplane]
     float *Ws = lds + G_KC * xplane;                             // [G_KC][NN][G_TCO]
 
-    unsigned id = blockIdx.x;
-    const int tile_m = (int)(id % (unsigned)p.tiles_m);
-    id /= (unsigned)p.tiles_m;
-    const int tile_co = (int)(id % (unsigned)p.tiles_co);
-    const int split = (int)(id / (unsigned)p.tiles_co);
-
-    const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, kk = lane >> 5;
-    const int wco = wave & 1, wpos = wave >> 1;
+    const int wco = wave & 1;
 
     const int m0 = tile_m * G_TM;
     const int co0 = tile_co * G_TCO;
@@ -176,17 +192,8 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     const int i0 = (m0 - b0 * p.EE) / p.E;
     const int R0 = b0 * p.N + i0;
 
-    int m = m0 + wpos * 32 + l32;
-    const bool m_valid = m < p.Mtot;
-    if (!m_valid) m = p.Mtot - 1;
-    const int mb = m / p.EE;
-    const int mrem = m - mb * p.EE;
-    const int mi = mrem / p.E, mj = mrem - mi * p.E;
-    const int xbase = ((mb * p.N + mi) - R0) * p.Ns + mj + kk * xplane;
+    const int xbase = ((L.mb * p.N + L.mi) - R0) * p.Ns + L.mj + kk * xplane;
     const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
-
-    const int ci_begin = split * p.ci_per_split;
-    const int ci_end = min(p.Cin, ci_begin + p.ci_per_split);
 
     // ---- staging plan: where each of this lane's float4 comes from and goes to -------------
     unsigned w_off[NW4], w_inc[NW4];
@@ -225,7 +232,6 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     }
     const unsigned x_inc = (unsigned)G_KC * p.N * p.Ns;
 
-    floatx16 acc[4][2];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -258,7 +264,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     __syncthreads();
 
     for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
-        // Next chunk's loads (all-zero past the end of this split's channels).
+        // Next chunk's loads (all-zero past the end of this range of channels).
         const int cn = ci0 + G_KC;
 #pragma unroll
         for (int k = 0; k < NW4; ++k) {
@@ -310,9 +316,144 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
             if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = x_reg[k];
         __syncthreads();
     }
+}
 
-    if (!m_valid) return;
-    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
+template <int n>
+__global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *__restrict__ in,
+                                                                     const float *__restrict__ w_seg,
+                                                                     float *__restrict__ dst, IgemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    unsigned id = blockIdx.x;
+    const int tile_m = (int)(id % (unsigned)p.tiles_m);
+    id /= (unsigned)p.tiles_m;
+    const int tile_co = (int)(id % (unsigned)p.tiles_co);
+    const int split = (int)(id / (unsigned)p.tiles_co);
+    const int ci_begin = split * p.ci_per_split;
+    const int ci_end = min(p.Cin, ci_begin + p.ci_per_split);
+
+    const PipeLane L = pipe_lane(p, tile_m, threadIdx.x);
+    floatx16 acc[4][2];
+    pipe_accumulate<n>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
+    if (!L.m_valid) return;
+    const int wave = threadIdx.x >> 6, kk = (threadIdx.x & 63) >> 5;
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
+}
+
+// ---------------------------------------------------------------------------
+// Even shares ("stream-K"): the (tile, channel chunk) pairs of the whole layer, tile-major, are
+// one list cut into SK_GRID equal ranges, one per persistent workgroup (one workgroup fits a
+// CU), so every CU multiplies for the same time whatever the tile count.  A range is a run of
+// pieces, each a span of chunks of one tile.  A piece that covers its tile's whole reduction is
+// stored straight to the output; any other is written raw (the accumulator registers, lane by
+// lane) to one of the workgroup's two slots: slot 2g for the first piece of workgroup g's range,
+// 2g + 1 for a later one (only the last can be partial then).  A second kernel adds the slots of
+// every tile that has more than one contributor in workgroup order (deterministic) and stores.
+// ---------------------------------------------------------------------------
+constexpr int SK_GRID = 256;                                  // CUs of the chip
+constexpr size_t SK_SLOT_FLOATS = (size_t)G_TM * G_TCO * 4;   // one tile's accumulators
+
+struct StreamK {
+    int chunks;                // channel chunks per tile
+    int grid;                  // workgroups (<= SK_GRID, <= units)
+    unsigned long long units;  // tiles * chunks
+};
+
+__device__ __forceinline__ unsigned long long sk_begin(const StreamK &k, int g)
+{
+    return (unsigned long long)g * k.units / (unsigned)k.grid;
+}
+
+template <int n>
+__global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const float *__restrict__ in,
+                                                                        const float *__restrict__ w_seg,
+                                                                        float *__restrict__ out, float *__restrict__ ws,
+                                                                        IgemmParams p, StreamK k)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x;
+    unsigned long long u = sk_begin(k, g);
+    const unsigned long long u_end = sk_begin(k, g + 1);
+    bool first = true;
+    while (u < u_end) {
+        const int tile = (int)(u / (unsigned)k.chunks);
+        const int c0 = (int)(u - (unsigned long long)tile * k.chunks);
+        const unsigned long long left = u_end - u;
+        const int c1 = left < (unsigned long long)(k.chunks - c0) ? c0 + (int)left : k.chunks;
+        const int tile_m = tile % p.tiles_m, tile_co = tile / p.tiles_m;
+        if (!first) __syncthreads();                 // the previous piece's last LDS reads are done
+        // A fresh copy of the lane number the compiler cannot see through: the staging plan is then
+        // worked out anew for every piece instead of being kept in registers across the pieces.
+        int tid_p = tid;
+        asm volatile("" : "+v"(tid_p));
+        const PipeLane L = pipe_lane(p, tile_m, tid_p);
+        floatx16 acc[4][2];
+        pipe_accumulate<n>(in, w_seg, p, lds, tile_m, tile_co, c0 * G_KC, min(p.Cin, c1 * G_KC), L, tid_p, acc);
+        if (c0 == 0 && c1 == k.chunks) {
+            if (L.m_valid) {
+                const int wave = tid >> 6, kk = (tid & 63) >> 5;
+                igemm_store(out, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
+            }
+        } else {
+            float4 *d = reinterpret_cast<float4 *>(ws + (size_t)(2 * g + (first ? 0 : 1)) * SK_SLOT_FLOATS);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        d[((c * 2 + h) * 4 + q) * G_THREADS + tid] =
+                            make_float4(acc[c][h][4 * q], acc[c][h][4 * q + 1], acc[c][h][4 * q + 2], acc[c][h][4 * q + 3]);
+        }
+        first = false;
+        u += (unsigned)(c1 - c0);
+    }
+}
+
+// One workgroup per tile: nothing to do when a single workgroup produced it; otherwise the sum of
+// its contributors' slots, in workgroup order, goes to the output.
+__global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const float *__restrict__ ws,
+                                                                            float *__restrict__ out, IgemmParams p, StreamK k)
+{
+    const int tile = blockIdx.x, tid = threadIdx.x;
+    const unsigned long long u0 = (unsigned long long)tile * k.chunks, u1 = u0 + k.chunks - 1;
+    auto owner = [&](unsigned long long unit) {
+        int g = (int)(unit * (unsigned)k.grid / k.units);
+        while (g + 1 < k.grid && sk_begin(k, g + 1) <= unit) ++g;
+        while (g > 0 && sk_begin(k, g) > unit) --g;
+        return g;
+    };
+    const int g0 = owner(u0), g1 = owner(u1);
+    if (g0 == g1) return;
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
+    for (int g = g0; g <= g1; ++g) {
+        const int slot = 2 * g + (sk_begin(k, g) < u0 ? 1 : 0);
+        const float4 *d = reinterpret_cast<const float4 *>(ws + (size_t)slot * SK_SLOT_FLOATS);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = d[((c * 2 + h) * 4 + q) * G_THREADS + tid];
+                    acc[c][h][4 * q] += v.x;
+                    acc[c][h][4 * q + 1] += v.y;
+                    acc[c][h][4 * q + 2] += v.z;
+                    acc[c][h][4 * q + 3] += v.w;
+                }
+    }
+    const int tile_m = tile % p.tiles_m, tile_co = tile / p.tiles_m;
+    const PipeLane L = pipe_lane(p, tile_m, tid);
+    if (!L.m_valid) return;
+    const int wave = tid >> 6, kk = (tid & 63) >> 5;
+    igemm_store(out, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
 }
 
 // Sum the per-split partial outputs (fixed order: deterministic).
@@ -350,10 +491,68 @@ bool igemm_f32_takes_row_stride(const Shape &s)
     return igemm_f32_supported(s) && pipe_ok(plan(s));
 }
 
+// Even shares or whole tiles?  Even shares when the pipelined kernel applies and the model says
+// they beat the best launch of whole (or split) tiles by 7 %: the longest range's multiply time
+// plus writing and reading every partial slot.
+struct SkPlan {
+    bool use;
+    StreamK k;
+};
+
+static SkPlan streamk_plan(const Shape &s, const IgemmParams &p)
+{
+    SkPlan r;
+    r.use = false;
+    r.k.chunks = (s.Cin + G_KC - 1) / G_KC;
+    const unsigned long long tiles = (unsigned long long)p.tiles_m * p.tiles_co;
+    r.k.units = tiles * (unsigned)r.k.chunks;
+    r.k.grid = r.k.units < (unsigned long long)SK_GRID ? (int)r.k.units : SK_GRID;
+    // Beyond 16 rounds of whole tiles the last, part-filled round costs less than the threshold.
+    if (!pipe_ok(p) || tiles % SK_GRID == 0 || tiles > 16u * SK_GRID) return r;
+    unsigned long long partial = 0;                       // pieces that go through a slot
+    for (int g = 0; g < r.k.grid; ++g) {
+        unsigned long long u = (unsigned long long)g * r.k.units / (unsigned)r.k.grid;
+        const unsigned long long u_end = (unsigned long long)(g + 1) * r.k.units / (unsigned)r.k.grid;
+        while (u < u_end) {                               // the pieces, as the kernel walks them
+            const unsigned long long c0 = u % (unsigned)r.k.chunks;
+            const unsigned long long room = (unsigned)r.k.chunks - c0, left = u_end - u;
+            const unsigned long long len = left < room ? left : room;
+            if (len != (unsigned)r.k.chunks) ++partial;
+            u += len;
+        }
+    }
+    const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / 2.0e11;
+    const double longest = (double)((r.k.units + r.k.grid - 1) / r.k.grid);
+    const double t = longest * tile_s / r.k.chunks + (double)partial * SK_SLOT_FLOATS * 4.0 * 2.0 / 4.0e12 + 5.0e-6;
+    r.use = t < 0.93 * p.est_s;
+    return r;
+}
+
 size_t igemm_f32_workspace_bytes(const Shape &s)
 {
     const IgemmParams p = plan(s);
+    const SkPlan sk = streamk_plan(s, p);
+    if (sk.use) return (size_t)2 * sk.k.grid * SK_SLOT_FLOATS * sizeof(float);
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+}
+
+template <int n>
+static hipError_t launch_streamk_n(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
+                                   const StreamK &k, hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p, n);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_streamk_kernel<n>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(igemm_f32_streamk_kernel<n>, dim3((unsigned)k.grid), dim3(G_THREADS), lds, stream, in, w_seg,
+                       out, ws, p, k);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3((unsigned)(p.tiles_m * p.tiles_co)), dim3(G_THREADS), 0,
+                       stream, ws, out, p, k);
+    return hipGetLastError();
 }
 
 template <int n>
@@ -385,6 +584,20 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
                             hipStream_t stream)
 {
     const IgemmParams p = plan(s);
+    const SkPlan sk = streamk_plan(s, p);
+    if (sk.use) {
+        float *slots = (float *)ws;
+        switch (s.n) {
+            case 1: return launch_streamk_n<1>(in, w_seg, out, slots, p, sk.k, stream);
+            case 2: return launch_streamk_n<2>(in, w_seg, out, slots, p, sk.k, stream);
+            case 3: return launch_streamk_n<3>(in, w_seg, out, slots, p, sk.k, stream);
+            case 4: return launch_streamk_n<4>(in, w_seg, out, slots, p, sk.k, stream);
+            case 5: return launch_streamk_n<5>(in, w_seg, out, slots, p, sk.k, stream);
+            case 6: return launch_streamk_n<6>(in, w_seg, out, slots, p, sk.k, stream);
+            case 7: return launch_streamk_n<7>(in, w_seg, out, slots, p, sk.k, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
     float *dst = p.splits > 1 ? (float *)ws : out;
     hipError_t e;
     switch (s.n) {
