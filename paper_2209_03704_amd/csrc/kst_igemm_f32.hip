@@ -18,6 +18,8 @@
 // are computed (their reads stay inside the map) and not stored.
 #include "kst_igemm_common.h"
 
+#include <utility>
+
 namespace kst {
 
 constexpr int G_KC = 4;          // input channels staged per step (even)
@@ -145,6 +147,19 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__res
 // ---------------------------------------------------------------------------
 constexpr int P_NX4 = 2;         // input float4 per lane per chunk at most
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
+// constant expression inside the body, so register arrays are only ever indexed by constants.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_each(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_each(f, std::make_integer_sequence<int, N>{});
+}
+
 // What a lane needs to know about its column of the tile when the accumulators are stored.
 struct PipeLane {
     int mb, mi, mj;      // batch item and quad of this lane's position
@@ -168,7 +183,7 @@ __device__ __forceinline__ PipeLane pipe_lane(const IgemmParams &p, int tile_m, 
 
 // acc = the tile's sums over input channels [ci_begin, ci_end).  Every thread of the workgroup
 // calls it; LDS is free to be overwritten once all of them have passed a barrier afterwards.
-template <int n>
+template <int n, bool DB>
 __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, const float *__restrict__ w_seg,
                                                 const IgemmParams &p, float *lds, int tile_m, int tile_co,
                                                 int ci_begin, int ci_end, const PipeLane &L, int tid,
@@ -196,8 +211,12 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
 
     // ---- staging plan: where each of this lane's float4 comes from and goes to -------------
+    // Cin is a multiple of G_KC here, so a chunk is either whole or past the end.  A lane with
+    // nothing to stage (past the chunk, past Cout, past the last batch item) loads the first
+    // element of the tensor over and over: whatever it brings only reaches output channels or
+    // positions that are never stored (an MFMA row depends on its own weight row only, a column
+    // on its own input column only).
     unsigned w_off[NW4], w_inc[NW4];
-    int w_c[NW4];                                   // channel within the chunk, or 1 << 20 when unused
 #pragma unroll
     for (int k = 0; k < NW4; ++k) {
         const int e4 = tid + k * G_THREADS;
@@ -211,13 +230,11 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
         const int Tp = cls == 0 ? class_taps(n, 0) : cls == 1 ? class_taps(n, 1) : cls == 2 ? class_taps(n, 2) : class_taps(n, 3);
         const int tb = cls == 0 ? 0 : cls == 1 ? class_tap_base(n, 1) : cls == 2 ? class_tap_base(n, 2) : class_tap_base(n, 3);
         const bool ok = e4 < W4 && co0 + 4 * tco4 < p.Cout;
-        w_off[k] = p.off[cls] + ((unsigned)(ci_begin + c) * Tp + (T - tb)) * p.Cout + co0 + 4 * tco4;
-        w_inc[k] = (unsigned)G_KC * Tp * p.Cout;
-        w_c[k] = ok ? c : (1 << 20);
+        w_off[k] = ok ? p.off[cls] + ((unsigned)(ci_begin + c) * Tp + (T - tb)) * p.Cout + co0 + 4 * tco4 : 0u;
+        w_inc[k] = ok ? (unsigned)G_KC * Tp * p.Cout : 0u;
     }
     const int xp4 = xplane >> 2, n4 = p.Ns >> 2;
-    unsigned x_off[P_NX4];
-    int x_c[P_NX4];
+    unsigned x_off[P_NX4], x_inc[P_NX4];
 #pragma unroll
     for (int k = 0; k < P_NX4; ++k) {
         const int e4 = tid + k * G_THREADS;
@@ -227,10 +244,9 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
         const int R = R0 + lr;
         const int bb = R / p.N, y = R - bb * p.N;
         const bool ok = e4 < G_KC * xp4 && bb < p.B;
-        x_off[k] = (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.Ns + 4 * x4;
-        x_c[k] = ok ? c : (1 << 20);
+        x_off[k] = ok ? (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.Ns + 4 * x4 : 0u;
+        x_inc[k] = ok ? (unsigned)G_KC * p.N * p.Ns : 0u;
     }
-    const unsigned x_inc = (unsigned)G_KC * p.N * p.Ns;
 
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -239,86 +255,124 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
 
+    // With two LDS stages (DB) chunk k + 1 is written into the other stage while chunk k is
+    // multiplied, and one barrier per chunk is enough; with one stage the writes wait between
+    // two barriers at the end of the chunk.
+    const int stage_floats = DB ? G_KC * (xplane + NN * G_TCO) : 0;
+    int cur = 0;                                    // float offset of the stage being multiplied
+    // A lane stages NW4 + P_NX4 float4 per chunk ("items": weights first, then input), each
+    // through a register of its own: item -> LDS at float offset `at`, and item <- global memory
+    // for the chunk at channel c0 (all-zero past the end of this range of channels; the item's
+    // offset moves on by one chunk afterwards).
+    constexpr int ITEMS = NW4 + P_NX4;
     float4 w_reg[NW4], x_reg[P_NX4];
-    // Chunk at ci_begin -> registers -> LDS.
-#pragma unroll
-    for (int k = 0; k < NW4; ++k)
-    {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ci_begin + w_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(w_seg + w_off[k]);
-        w_reg[k] = v;
-    }
-#pragma unroll
-    for (int k = 0; k < P_NX4; ++k)
-    {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ci_begin + x_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(in + x_off[k]);
-        x_reg[k] = v;
-    }
-#pragma unroll
-    for (int k = 0; k < NW4; ++k)
-        if (tid + k * G_THREADS < W4) reinterpret_cast<float4 *>(Ws)[tid + k * G_THREADS] = w_reg[k];
-#pragma unroll
-    for (int k = 0; k < P_NX4; ++k)
-        if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = x_reg[k];
+    // Loads carry no branch (a chunk past the end re-reads the first element): straight-line code
+    // lets the compiler count how many newer loads may be in flight when an item is needed,
+    // instead of waiting for all of them.
+    auto write_item = [&](auto jc, int at) {
+        constexpr int j = decltype(jc)::value;
+        // (copied member by member: a whole-struct copy from the register array into LDS makes
+        // the compiler keep the array in scratch memory)
+        if constexpr (j < NW4) {
+            const float4 v = make_float4(w_reg[j].x, w_reg[j].y, w_reg[j].z, w_reg[j].w);
+            if ((j + 1) * G_THREADS <= W4 || tid + j * G_THREADS < W4)
+                reinterpret_cast<float4 *>(Ws + at)[tid + j * G_THREADS] = v;
+        } else {
+            constexpr int k = j - NW4;
+            const float4 v = make_float4(x_reg[k].x, x_reg[k].y, x_reg[k].z, x_reg[k].w);
+            if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs + at)[tid + k * G_THREADS] = v;
+        }
+    };
+    auto fetch_item = [&](auto jc, int c0) {
+        constexpr int j = decltype(jc)::value;
+        const bool live = c0 < ci_end;                  // wave-uniform
+        if constexpr (j < NW4) {
+            w_reg[j] = *reinterpret_cast<const float4 *>(w_seg + (live ? w_off[j] : 0u));
+            w_off[j] += w_inc[j];
+        } else {
+            constexpr int k = j - NW4;
+            x_reg[k] = *reinterpret_cast<const float4 *>(in + (live ? x_off[k] : 0u));
+            x_off[k] += x_inc[k];
+        }
+    };
+    // First chunk -> LDS; the second is on its way into the registers while the first is
+    // multiplied.  From then on an item is written to LDS late in a chunk and its register
+    // refilled at once with the chunk after the next, so a load has a whole chunk's MFMAs to arrive.
+    static_for<ITEMS>([&](auto jc) { fetch_item(jc, ci_begin); });
+    static_for<ITEMS>([&](auto jc) {
+        write_item(jc, 0);
+        fetch_item(jc, ci_begin + G_KC);
+    });
     __syncthreads();
 
-    for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
-        // Next chunk's loads (all-zero past the end of this range of channels).
-        const int cn = ci0 + G_KC;
+    constexpr int STEPS = G_KC / 2;                 // channel pairs per chunk (an MFMA takes two channels)
+    // DB: item j goes to LDS (and is refilled) behind tap Q_WRITE + j, so that the staging
+    // instructions are spread over the MFMAs instead of holding them up in one block.
+    constexpr int Q_WRITE = STEPS * NN > ITEMS + 1 ? STEPS * NN - ITEMS - 1 : 0;
+    float xf[2][fl + 1][fl + 1], wf[2][2];
+    auto read_x = [&](auto stc) {
+        constexpr int st = decltype(stc)::value;
 #pragma unroll
-        for (int k = 0; k < NW4; ++k) {
-            w_off[k] += w_inc[k];
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (cn + w_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(w_seg + w_off[k]);
-            w_reg[k] = v;
-        }
+        for (int dy = 0; dy <= fl; ++dy)
 #pragma unroll
-        for (int k = 0; k < P_NX4; ++k) {
-            x_off[k] += x_inc;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (cn + x_c[k] < ci_end) v = *reinterpret_cast<const float4 *>(in + x_off[k]);
-            x_reg[k] = v;
-        }
+            for (int dx = 0; dx <= fl; ++dx)
+                xf[st & 1][dy][dx] = Xs[cur + 2 * st * xplane + xbase + dy * p.Ns + dx];
+    };
+    auto read_w = [&](auto qc) {                    // the two weight values of tap q of the chunk
+        constexpr int q = decltype(qc)::value;
+        wf[q & 1][0] = Ws[cur + (2 * (q / NN) * NN + q % NN) * G_TCO + wbase];
+        wf[q & 1][1] = Ws[cur + (2 * (q / NN) * NN + q % NN) * G_TCO + wbase + 32];
+    };
 
+    for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
+        const int cn = ci0 + G_KC;
+        // The MFMAs of this chunk, one tap after the other (class-major order); the two weight
+        // values of tap q + 1 are read from LDS before the MFMAs of tap q are issued, and the
+        // window of the next channel pair half-way through the current one, so that no MFMA waits
+        // for an LDS read issued right in front of it.
+        read_x(std::integral_constant<int, 0>{});
+        read_w(std::integral_constant<int, 0>{});
+        static_for<STEPS * NN>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            constexpr int st = q / NN, T = q % NN;
+            if constexpr (q + 1 < STEPS * NN) read_w(std::integral_constant<int, q + 1>{});
+            if constexpr (T == NN / 2 && st + 1 < STEPS) read_x(std::integral_constant<int, st + 1>{});
+            constexpr int cls = tap_class(n, T);
+            constexpr int r = cls >> 1, sp = cls & 1;
+            constexpr int local = T - class_tap_base(n, cls);
+            constexpr int Tb = taps_for_parity(n, sp);
+            constexpr int a = local / Tb, bq = local - a * Tb;
 #pragma unroll
-        for (int c2 = 0; c2 < G_KC; c2 += 2) {
-            float xf[fl + 1][fl + 1];
-#pragma unroll
-            for (int dy = 0; dy <= fl; ++dy)
-#pragma unroll
-                for (int dx = 0; dx <= fl; ++dx)
-                    xf[dy][dx] = Xs[c2 * xplane + xbase + dy * p.Ns + dx];
-#pragma unroll
-            for (int cls = 0; cls < 4; ++cls) {
-                const int r = cls >> 1, s = cls & 1;
-                const int Ta = taps_for_parity(n, r), Tb = taps_for_parity(n, s);
-#pragma unroll
-                for (int a = 0; a < Ta; ++a)
-#pragma unroll
-                    for (int bq = 0; bq < Tb; ++bq) {
-                        const int T = class_tap_base(n, cls) + a * Tb + bq;
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            const float wf = Ws[(c2 * NN + T) * G_TCO + wbase + h * 32];
-                            acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, xf[r + a][s + bq], acc[cls][h], 0, 0, 0);
-                        }
+            for (int h = 0; h < 2; ++h)
+                acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[q & 1][h], xf[st & 1][r + a][sp + bq],
+                                                                   acc[cls][h], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (DB && q >= Q_WRITE) {
+                static_for<ITEMS>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    if constexpr (q - Q_WRITE == j || (q == STEPS * NN - 1 && j > q - Q_WRITE)) {
+                        write_item(jc, stage_floats - cur);             // past the end: nobody reads it
+                        fetch_item(jc, cn + G_KC);
                     }
+                });
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        });
         if (cn >= ci_end) break;
-        __syncthreads();                                         // every wave is done reading this chunk
-#pragma unroll
-        for (int k = 0; k < NW4; ++k)
-            if (tid + k * G_THREADS < W4) reinterpret_cast<float4 *>(Ws)[tid + k * G_THREADS] = w_reg[k];
-#pragma unroll
-        for (int k = 0; k < P_NX4; ++k)
-            if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = x_reg[k];
-        __syncthreads();
+        __syncthreads();                            // every wave is done reading this chunk
+        if constexpr (DB) {
+            cur = stage_floats - cur;
+        } else {
+            static_for<ITEMS>([&](auto jc) {
+                write_item(jc, 0);
+                fetch_item(jc, cn + G_KC);
+            });
+            __syncthreads();
+        }
     }
 }
 
-template <int n>
+template <int n, bool DB>
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *__restrict__ in,
                                                                      const float *__restrict__ w_seg,
                                                                      float *__restrict__ dst, IgemmParams p)
@@ -334,7 +388,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
 
     const PipeLane L = pipe_lane(p, tile_m, threadIdx.x);
     floatx16 acc[4][2];
-    pipe_accumulate<n>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
+    pipe_accumulate<n, DB>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
     if (!L.m_valid) return;
     const int wave = threadIdx.x >> 6, kk = (threadIdx.x & 63) >> 5;
     igemm_store(dst + (size_t)split * p.out_elems, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
@@ -364,7 +418,7 @@ __device__ __forceinline__ unsigned long long sk_begin(const StreamK &k, int g)
     return (unsigned long long)g * k.units / (unsigned)k.grid;
 }
 
-template <int n>
+template <int n, bool DB>
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const float *__restrict__ in,
                                                                         const float *__restrict__ w_seg,
                                                                         float *__restrict__ out, float *__restrict__ ws,
@@ -389,7 +443,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
         asm volatile("" : "+v"(tid_p));
         const PipeLane L = pipe_lane(p, tile_m, tid_p);
         floatx16 acc[4][2];
-        pipe_accumulate<n>(in, w_seg, p, lds, tile_m, tile_co, c0 * G_KC, min(p.Cin, c1 * G_KC), L, tid_p, acc);
+        pipe_accumulate<n, DB>(in, w_seg, p, lds, tile_m, tile_co, c0 * G_KC, min(p.Cin, c1 * G_KC), L, tid_p, acc);
         if (c0 == 0 && c1 == k.chunks) {
             if (L.m_valid) {
                 const int wave = tid >> 6, kk = (tid & 63) >> 5;
@@ -469,15 +523,24 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
 
 static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_F32, G_KC); }
 
-// The pipelined kernel wants 16-byte rows and fits its input chunk in P_NX4 loads per lane.
+// The pipelined kernels want 16-byte rows, whole channel chunks, and an input chunk that fits
+// P_NX4 loads per lane.
 static bool pipe_ok(const IgemmParams &p)
 {
-    return (p.Ns & 3) == 0 && (p.Cout & 3) == 0 && (size_t)G_KC * p.lrows * p.Ns / 4 <= (size_t)P_NX4 * G_THREADS;
+    return (p.Ns & 3) == 0 && (p.Cout & 3) == 0 && p.Cin % G_KC == 0 &&
+           (size_t)G_KC * p.lrows * p.Ns / 4 <= (size_t)P_NX4 * G_THREADS;
 }
 
 static size_t lds_bytes(const IgemmParams &p, int n)
 {
     return (size_t)G_KC * ((size_t)p.lrows * p.Ns + (size_t)n * n * G_TCO) * sizeof(float);
+}
+
+// The pipelined kernels keep two stages in LDS when they fit (n <= 5: the larger kernels have no
+// registers to spare for it).
+static bool two_stages(const IgemmParams &p, int n)
+{
+    return n <= 5 && 2 * lds_bytes(p, n) <= 160 * 1024;
 }
 
 bool igemm_f32_supported(const Shape &s)
@@ -536,22 +599,45 @@ size_t igemm_f32_workspace_bytes(const Shape &s)
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
 }
 
-template <int n>
-static hipError_t launch_streamk_n(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
-                                   const StreamK &k, hipStream_t stream)
+template <int n, bool DB>
+static hipError_t launch_streamk_db(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
+                                    const StreamK &k, hipStream_t stream)
 {
-    const size_t lds = lds_bytes(p, n);
+    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_streamk_kernel<n>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_streamk_kernel<n, DB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(igemm_f32_streamk_kernel<n>, dim3((unsigned)k.grid), dim3(G_THREADS), lds, stream, in, w_seg,
-                       out, ws, p, k);
+    hipLaunchKernelGGL((igemm_f32_streamk_kernel<n, DB>), dim3((unsigned)k.grid), dim3(G_THREADS), lds, stream, in,
+                       w_seg, out, ws, p, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3((unsigned)(p.tiles_m * p.tiles_co)), dim3(G_THREADS), 0,
                        stream, ws, out, p, k);
+    return hipGetLastError();
+}
+
+template <int n>
+static hipError_t launch_streamk_n(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
+                                   const StreamK &k, hipStream_t stream)
+{
+    if constexpr (n <= 5)
+        if (two_stages(p, n)) return launch_streamk_db<n, true>(in, w_seg, out, ws, p, k, stream);
+    return launch_streamk_db<n, false>(in, w_seg, out, ws, p, k, stream);
+}
+
+template <int n, bool DB>
+static hipError_t launch_pipe_db(const float *in, const float *w_seg, float *dst, const IgemmParams &p, unsigned blocks,
+                                 hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n, DB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((igemm_f32_pipe_kernel<n, DB>), dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
     return hipGetLastError();
 }
 
@@ -568,12 +654,9 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
     const bool pipe = pipe_ok(p);
     if (!pipe && p.Ns != p.N) return hipErrorInvalidValue;
     if (pipe) {
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        hipLaunchKernelGGL(igemm_f32_pipe_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+        if constexpr (n <= 5)
+            if (two_stages(p, n)) return launch_pipe_db<n, true>(in, w_seg, dst, p, blocks, stream);
+        return launch_pipe_db<n, false>(in, w_seg, dst, p, blocks, stream);
     } else {
         hipLaunchKernelGGL(igemm_f32_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
     }

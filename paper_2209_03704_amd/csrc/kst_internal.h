@@ -23,6 +23,15 @@ __host__ __device__ constexpr int class_tap_base(int n, int p)
     return s;
 }
 
+// Class of tap T in that numbering.
+__host__ __device__ constexpr int tap_class(int n, int T)
+{
+    int c = 0;
+    for (int q = 1; q < 4; ++q)
+        if (T >= class_tap_base(n, q) && class_taps(n, q) > 0) c = q;
+    return c;
+}
+
 // Operand element -> fp32.  bfloat16 operands travel as raw 16-bit patterns.
 __device__ inline float to_f32(float v) { return v; }
 __device__ inline float to_f32(uint16_t v) { return __uint_as_float((unsigned)v << 16); }
