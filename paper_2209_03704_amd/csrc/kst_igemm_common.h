@@ -67,37 +67,45 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     return p;
 }
 
-// Store one wave's accumulators.  acc[cls][h] is the 32 x 32 block of class cls
-// (rows: output channels co_base + 32h + 8(v/4) + 4kk + v%4; column: this lane's
-// quad).  The s = 0 / s = 1 classes of a row parity sit side by side in memory.
-__device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][2], const IgemmParams &p,
-                                            int co_base, int kk, int mb, int mi, int mj)
+// Store 32 output channels of one wave's accumulators.  acc[cls] is the 32 x 32 block of class
+// cls (rows: output channels co_base + 8(v/4) + 4kk + v%4; column: this lane's quad).  The
+// s = 0 / s = 1 classes of a row parity sit side by side in memory.
+__device__ __forceinline__ void igemm_store_block(float *__restrict__ o, const floatx16 &a0, const floatx16 &a1,
+                                                  const floatx16 &a2, const floatx16 &a3, const IgemmParams &p,
+                                                  int co_base, int kk, int mb, int mi, int mj)
 {
     const bool x1_ok = 2 * mj + 1 < p.M;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int v = 0; v < 16; ++v) {
+        const int co = co_base + 8 * (v >> 2) + 4 * kk + (v & 3);
+        if (co >= p.Cout) continue;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int co = co_base + h * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
-            if (co >= p.Cout) continue;
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int y = 2 * mi + r;
-                if (y >= p.M) continue;
-                float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
-                const float v0 = acc[2 * r][h][v], v1 = acc[2 * r + 1][h][v];
-                if (x1_ok) {
-                    if ((reinterpret_cast<uintptr_t>(q) & 7u) == 0) {
-                        *reinterpret_cast<float2 *>(q) = make_float2(v0, v1);
-                    } else {
-                        q[0] = v0;
-                        q[1] = v1;
-                    }
+        for (int r = 0; r < 2; ++r) {
+            const int y = 2 * mi + r;
+            if (y >= p.M) continue;
+            float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
+            const float v0 = r ? a2[v] : a0[v], v1 = r ? a3[v] : a1[v];
+            if (x1_ok) {
+                if ((reinterpret_cast<uintptr_t>(q) & 7u) == 0) {
+                    *reinterpret_cast<float2 *>(q) = make_float2(v0, v1);
                 } else {
                     q[0] = v0;
+                    q[1] = v1;
                 }
+            } else {
+                q[0] = v0;
             }
         }
+    }
+}
+
+// Store one wave's accumulators: acc[cls][h] covers output channels co_base + 32h .. + 31.
+__device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][2], const IgemmParams &p,
+                                            int co_base, int kk, int mb, int mi, int mj)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        igemm_store_block(o, acc[0][h], acc[1][h], acc[2][h], acc[3][h], p, co_base + h * 32, kk, mb, mi, mj);
 }
 
 // out[e] = sum over splits of ws[split][e], in split order (deterministic).

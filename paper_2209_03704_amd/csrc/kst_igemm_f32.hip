@@ -465,12 +465,13 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
     }
 }
 
-// One workgroup per tile: nothing to do when a single workgroup produced it; otherwise the sum of
-// its contributors' slots, in workgroup order, goes to the output.
+// Two workgroups per tile (one per 32-channel half of every wave's block): nothing to do when a
+// single workgroup produced the tile; otherwise the sum of its contributors' slots, in workgroup
+// order, goes to the output.
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const float *__restrict__ ws,
                                                                             float *__restrict__ out, IgemmParams p, StreamK k)
 {
-    const int tile = blockIdx.x, tid = threadIdx.x;
+    const int tile = blockIdx.x >> 1, h = blockIdx.x & 1, tid = threadIdx.x;
     const unsigned long long u0 = (unsigned long long)tile * k.chunks, u1 = u0 + k.chunks - 1;
     auto owner = [&](unsigned long long unit) {
         int g = (int)(unit * (unsigned)k.grid / k.units);
@@ -480,34 +481,45 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const 
     };
     const int g0 = owner(u0), g1 = owner(u1);
     if (g0 == g1) return;
-    floatx16 acc[4][2];
+    float4 a[4][4];                                   // [class][four registers each]
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
+        for (int q = 0; q < 4; ++q) a[c][q] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int g = g0; g <= g1; ++g) {
         const int slot = 2 * g + (sk_begin(k, g) < u0 ? 1 : 0);
         const float4 *d = reinterpret_cast<const float4 *>(ws + (size_t)slot * SK_SLOT_FLOATS);
+        float4 v[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int q = 0; q < 4; ++q) v[c][q] = d[((c * 2 + h) * 4 + q) * G_THREADS + tid];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = d[((c * 2 + h) * 4 + q) * G_THREADS + tid];
-                    acc[c][h][4 * q] += v.x;
-                    acc[c][h][4 * q + 1] += v.y;
-                    acc[c][h][4 * q + 2] += v.z;
-                    acc[c][h][4 * q + 3] += v.w;
-                }
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a[c][q].x += v[c][q].x;
+                a[c][q].y += v[c][q].y;
+                a[c][q].z += v[c][q].z;
+                a[c][q].w += v[c][q].w;
+            }
     }
     const int tile_m = tile % p.tiles_m, tile_co = tile / p.tiles_m;
     const PipeLane L = pipe_lane(p, tile_m, tid);
     if (!L.m_valid) return;
+    floatx16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            acc[c][4 * q] = a[c][q].x;
+            acc[c][4 * q + 1] = a[c][q].y;
+            acc[c][4 * q + 2] = a[c][q].z;
+            acc[c][4 * q + 3] = a[c][q].w;
+        }
     const int wave = tid >> 6, kk = (tid & 63) >> 5;
-    igemm_store(out, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
+    igemm_store_block(out, acc[0], acc[1], acc[2], acc[3], p, tile_co * G_TCO + (wave & 1) * 64 + h * 32, kk,
+                      L.mb, L.mi, L.mj);
 }
 
 // Sum the per-split partial outputs (fixed order: deterministic).
@@ -613,7 +625,7 @@ static hipError_t launch_streamk_db(const float *in, const float *w_seg, float *
                        w_seg, out, ws, p, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3((unsigned)(p.tiles_m * p.tiles_co)), dim3(G_THREADS), 0,
+    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3(2u * (unsigned)(p.tiles_m * p.tiles_co)), dim3(G_THREADS), 0,
                        stream, ws, out, p, k);
     return hipGetLastError();
 }
