@@ -214,6 +214,11 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
         if (igemm_f32_takes_row_stride(wide)) f->s = wide;
     }
     f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
+    // The multi-channel direct kernel supplies the zero frame itself: no framed copy at all.
+    if (f->chosen == KST_PATH_DIRECT && direct_takes_virtual_frame(f->s, dt)) {
+        f->s.frame = f->q;
+        f->in_bytes = 0;
+    }
     f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
     return KST_OK;
 }
@@ -243,13 +248,20 @@ kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, 
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
     const size_t inner = workspace_for(f.s, dtype, f.chosen);
-    if (!ws || ws_bytes < f.in_bytes + f.wide_bytes + inner) return KST_ERR_WORKSPACE;
-    if (!aligned16(ws)) return KST_ERR_ALIGN;
+    const size_t need = f.in_bytes + f.wide_bytes + inner;
+    if (need > 0) {
+        if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return KST_ERR_ALIGN;
+    }
     char *base = (char *)ws;
     void *in_framed = base;
     float *wide = f.wide_bytes ? (float *)(base + f.in_bytes) : nullptr;
     void *inner_ws = inner ? (void *)(base + f.in_bytes + f.wide_bytes) : nullptr;
-    if (launch_frame_input(in, in_framed, B, Cin, N, f.q, f.s.Ns, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    if (f.s.frame == 0) {
+        if (launch_frame_input(in, in_framed, B, Cin, N, f.q, f.s.Ns, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+    } else {
+        in_framed = const_cast<void *>(in);
+    }
     st = run_forward_seg(in_framed, w_seg, wide ? (void *)wide : out, inner_ws, inner, f.s, dtype, f.chosen, stream);
     if (st != KST_OK) return st;
     if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, 1, stream) != hipSuccess) return KST_ERR_HIP;
@@ -267,14 +279,13 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, i
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(w) || !aligned16(out)) return KST_ERR_ALIGN;
     const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;
-    const size_t ws_bytes = kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dtype, KST_PATH_AUTO);
-    if (ws_bytes == 0) return KST_ERR_SHAPE;
+    const size_t ws_bytes = f.in_bytes + f.wide_bytes + workspace_for(f.s, dtype, f.chosen);   // may be 0
     void *scratch = nullptr;
     if (hipMallocAsync(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
     st = kst_segregate_weights(w, scratch, Cin, Cout, n, dtype, stream);
     if (st == KST_OK)
-        st = kst_forward_seg_padded(in, scratch, out, (char *)scratch + seg_bytes, ws_bytes, B, Cin, Cout, N, n, P,
-                                    dtype, KST_PATH_AUTO, stream);
+        st = kst_forward_seg_padded(in, scratch, out, ws_bytes ? (char *)scratch + seg_bytes : nullptr, ws_bytes, B, Cin,
+                                    Cout, N, n, P, dtype, KST_PATH_AUTO, stream);
     if (hipFreeAsync(scratch, stream) != hipSuccess && st == KST_OK) st = KST_ERR_HIP;
     return st;
 }

@@ -161,7 +161,6 @@ struct RowsParams {
     unsigned off[4];
 };
 
-constexpr int R_ITEMS = 8;    // (row, group) pairs per lane
 constexpr int R_PAD = 4;      // slack floats left of each staged row (and at least as many right)
 
 // One aligned group of row parity r whose first output has column parity `par`.
@@ -210,13 +209,6 @@ __device__ __forceinline__ void rows_geometry(const RowsParams &p, int fl, unsig
     g.rows_out = min(p.R, p.M - g.y0);
     g.rows_in = min(p.R / 2 + fl, p.N - g.i0);
     g.plane_base = (size_t)g.plane * p.M * p.M;
-}
-
-// Workgroups are dealt round-robin to the 8 XCDs.  With xcd_remap each XCD gets one
-// contiguous eighth of the strips, so that neighbouring strips share halo rows in its L2.
-__device__ __forceinline__ unsigned rows_logical_chunk(const RowsParams &p)
-{
-    return p.xcd_remap ? (blockIdx.x & 7u) * p.xcd_slots + (blockIdx.x >> 3) : blockIdx.x;
 }
 
 // Stage input rows i0 .. i0+rows_in-1 of (b, ci): one contiguous run of the input.
@@ -402,64 +394,6 @@ __global__ void __launch_bounds__(256) direct_rows1_kernel(const T *__restrict__
     }
 }
 
-// Several input channels: per-lane accumulators for R_ITEMS (row, group) pairs persist
-// across the channel loop.  GL = log2(groups per lane per row); R = R_ITEMS >> GL rows.
-template <int n, typename T, int GL>
-__global__ void __launch_bounds__(256) direct_rows_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
-                                                            float *__restrict__ out, RowsParams p)
-{
-    extern __shared__ __attribute__((aligned(16))) float Xs[];   // [R/2 + fl][xs_stride]
-    RowsGeom g;
-    const unsigned logical = rows_logical_chunk(p);
-    if (logical >= p.nchunks) return;
-    rows_geometry(p, n / 2, logical, g);
-    const int tid = threadIdx.x;
-    const int shift0 = (int)((g.plane_base + (size_t)g.y0 * p.M) & 3);
-    const int mstep = p.M & 3;
-
-    float4 acc[R_ITEMS];
-#pragma unroll
-    for (int it = 0; it < R_ITEMS; ++it) acc[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-
-    for (int ci = 0; ci < p.Cin; ++ci) {
-        if (ci) __syncthreads();
-        rows_stage<T>(Xs, in, p, g, ci);
-        float wk[2][2][((n + 1) / 2) * ((n + 1) / 2)];
-        rows_weights<n, T>(wk, w_seg, p, ci, g.co);
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < R_ITEMS; ++it) {
-            constexpr int gmask = (1 << GL) - 1;
-            const int row = it >> GL;
-            if (row >= g.rows_out) continue;                     // uniform
-            const int shift = (shift0 + row * mstep) & 3;
-            const int x0 = 4 * (((it & gmask) << 8) + tid) - shift;
-            if (x0 >= p.M) continue;
-            const float *rowp = Xs + ((row >> 1) + (row & 1)) * p.xs_stride + R_PAD;
-            if (shift & 1) {
-                const int cbase = ((x0 - 1) >> 1) + 1;
-                if (row & 1) rows_group<n, 1, 1>(acc[it], rowp, p.xs_stride, cbase, wk);
-                else rows_group<n, 0, 1>(acc[it], rowp, p.xs_stride, cbase, wk);
-            } else {
-                const int cbase = x0 >> 1;
-                if (row & 1) rows_group<n, 1, 0>(acc[it], rowp, p.xs_stride, cbase, wk);
-                else rows_group<n, 0, 0>(acc[it], rowp, p.xs_stride, cbase, wk);
-            }
-        }
-    }
-
-#pragma unroll
-    for (int it = 0; it < R_ITEMS; ++it) {
-        constexpr int gmask = (1 << GL) - 1;
-        const int row = it >> GL;
-        if (row >= g.rows_out) continue;
-        const int shift = (shift0 + row * mstep) & 3;
-        const int x0 = 4 * (((it & gmask) << 8) + tid) - shift;
-        if (x0 >= p.M) continue;
-        rows_store(out + g.plane_base + (size_t)(g.y0 + row) * p.M + x0, acc[it], x0, p.M);
-    }
-}
-
 // Any kernel size: one lane per quad, operands read straight from global memory.
 template <typename T>
 __global__ void __launch_bounds__(256) direct_generic_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
@@ -499,64 +433,40 @@ static void launch_tiled(const T *in, const T *w_seg, float *out, const DirectPa
 
 constexpr size_t kRowsLdsLimit = 64 * 1024;
 
-// Strip plan: R output rows per workgroup and 2^gl groups per lane per row with
-// R << gl == R_ITEMS, so that 256 lanes x 2^gl aligned groups cover a row of M (+3) floats.
+// Strip plan of the single-channel rows kernel (several input channels are the multi-channel
+// kernel's job): R output rows per strip.
 template <int n, typename T>
 static bool try_rows(const T *in, const T *w_seg, float *out, const Shape &s, kst_dtype dt, hipStream_t stream)
 {
+    if (s.Cin != 1) return false;
     RowsParams p;
-    const int groups = (s.M + 3 + 3) / 4;                      // aligned groups that can touch one row
-    int gl = 0;
-    while ((256 << gl) < groups) ++gl;
     p.xs_stride = ((s.N + 3) & ~3) + 2 * R_PAD;
-    p.prefetch = 0;
-    size_t lds;
-    unsigned grid;
-    if (s.Cin == 1) {
-        // Tallest strip (up to 16 rows) whose input fits the prefetch registers and 20 KB of LDS.
-        int R = 8;
-        const bool vec = sizeof(T) == 4 && (s.N & 3) == 0;
-        while (R > 2 && ((size_t)(R / 2 + s.fl) * p.xs_stride * sizeof(float) > 20 * 1024 ||
-                         (vec && (size_t)(R / 2 + s.fl) * s.N > (size_t)256 * R_NLD * 4)))
-            R -= 2;
-        p.R = R;
-        p.xs_buf = (R / 2 + s.fl) * p.xs_stride;
-        p.prefetch = vec && (size_t)(R / 2 + s.fl) * s.N <= (size_t)256 * R_NLD * 4;
-        lds = (size_t)2 * p.xs_buf * sizeof(float);
-        if (lds > kRowsLdsLimit) return false;
-    } else {
-        if ((R_ITEMS >> gl) < 2) return false;                 // rows wider than 4 * 256 * 4 floats
-        p.R = R_ITEMS >> gl;
-        p.xs_buf = (p.R / 2 + s.fl) * p.xs_stride;
-        lds = (size_t)p.xs_buf * sizeof(float);
-        if (lds > kRowsLdsLimit) return false;
-    }
+    // Tallest strip (up to 16 rows) whose input fits the prefetch registers and 20 KB of LDS.
+    int R = 8;
+    const bool vec = sizeof(T) == 4 && (s.N & 3) == 0;
+    while (R > 2 && ((size_t)(R / 2 + s.fl) * p.xs_stride * sizeof(float) > 20 * 1024 ||
+                     (vec && (size_t)(R / 2 + s.fl) * s.N > (size_t)256 * R_NLD * 4)))
+        R -= 2;
+    p.R = R;
+    p.xs_buf = (R / 2 + s.fl) * p.xs_stride;
+    p.prefetch = vec && (size_t)(R / 2 + s.fl) * s.N <= (size_t)256 * R_NLD * 4;
+    const size_t lds = (size_t)2 * p.xs_buf * sizeof(float);
+    if (lds > kRowsLdsLimit) return false;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M;
     p.chunks_per_plane = (s.M + p.R - 1) / p.R;
     const size_t nchunks = (size_t)s.B * s.Cout * p.chunks_per_plane;
     if (nchunks >= 0x7ffffff0u) return false;
     p.nchunks = (unsigned)nchunks;
     p.xcd_slots = (p.nchunks + 7) / 8;
-    // Single channel: plain interleaving measured faster than XCD-contiguous ranges (one stream
-    // over the chip keeps HBM pages hot); several channels: neighbours share halo rows in L2.
-    p.xcd_remap = s.Cin == 1 ? 0 : 1;
+    // Plain interleaving measured faster than XCD-contiguous ranges (one stream over the chip
+    // keeps HBM pages hot).
+    p.xcd_remap = 0;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
-    const dim3 block(256);
-    if (s.Cin == 1) {
-        // Persistent: a few workgroups per CU, each walking over its share of the strips.
-        grid = 1024;
-        if (grid > p.xcd_slots * 8) grid = p.xcd_slots * 8;
-        grid = grid < 8 ? 8 : (grid & ~7u);                    // whole multiples of the 8 XCDs
-        hipLaunchKernelGGL((direct_rows1_kernel<n, T>), dim3(grid), block, lds, stream, in, w_seg, out, p);
-        return true;
-    }
-    grid = p.xcd_slots * 8;
-    if (gl == 0)
-        hipLaunchKernelGGL((direct_rows_kernel<n, T, 0>), dim3(grid), block, lds, stream, in, w_seg, out, p);
-    else if (gl == 1)
-        hipLaunchKernelGGL((direct_rows_kernel<n, T, 1>), dim3(grid), block, lds, stream, in, w_seg, out, p);
-    else
-        hipLaunchKernelGGL((direct_rows_kernel<n, T, 2>), dim3(grid), block, lds, stream, in, w_seg, out, p);
+    // Persistent: a few workgroups per CU, each walking over its share of the strips.
+    unsigned grid = 1024;
+    if (grid > p.xcd_slots * 8) grid = p.xcd_slots * 8;
+    grid = grid < 8 ? 8 : (grid & ~7u);                        // whole multiples of the 8 XCDs
+    hipLaunchKernelGGL((direct_rows1_kernel<n, T>), dim3(grid), dim3(256), lds, stream, in, w_seg, out, p);
     return true;
 }
 
@@ -604,14 +514,29 @@ static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, k
     return hipGetLastError();
 }
 
+bool direct_takes_virtual_frame(const Shape &s, kst_dtype dt)
+{
+    FlatParams fp;
+    unsigned grid;
+    size_t lds;
+    Shape dense = s;
+    dense.frame = 0;
+    return !direct_flat_plan(dense, dt, fp, grid, lds) && direct_multi_supported(dense);
+}
+
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream)
 {
     FlatParams fp;
     unsigned grid;
     size_t lds;
+    if (s.frame != 0) {
+        if (!direct_takes_virtual_frame(s, dt)) return hipErrorInvalidValue;
+        return launch_direct_multi(in, w_seg, out, s, dt, stream);
+    }
     if (direct_flat_plan(s, dt, fp, grid, lds))
         return launch_direct_flat((const float *)in, (const float *)w_seg, out, s, fp, grid, lds, stream);
+    if (direct_multi_supported(s)) return launch_direct_multi(in, w_seg, out, s, dt, stream);
     if (dt == KST_BF16) return run<uint16_t>((const uint16_t *)in, (const uint16_t *)w_seg, out, s, dt, stream);
     return run<float>((const float *)in, (const float *)w_seg, out, s, dt, stream);
 }

@@ -52,11 +52,13 @@ struct Shape {
     int E;    // quad rows/columns: ceil(M / 2)
     int fl;   // floor(n / 2): halo of the input window of one quad
     int Ns;   // elements between consecutive rows of `in` (N unless the caller framed it with a wider stride)
+    int frame; // > 0: `in` is the dense [B][Cin][N - 2 frame][N - 2 frame] tensor and the kernel supplies the
+               // zero frame of that width itself (only kernels for which *_takes_virtual_frame says so)
 };
 
 inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
 {
-    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N};
+    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N, 0};
     return s;
 }
 
@@ -102,6 +104,13 @@ size_t backward_weight_igemm_workspace_bytes(const Shape &s);
 hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *dw, void *ws, const Shape &s,
                                         hipStream_t stream);
 // Direct path: any shape.
+// Direct kernel for several input channels (one lane per quad and output channel, input staged
+// in LDS by channel chunks); dense rows only.
+bool direct_multi_supported(const Shape &s);
+// True when the direct path on this shape reads a padded layer's input in place (Shape::frame).
+bool direct_takes_virtual_frame(const Shape &s, kst_dtype dt);
+hipError_t launch_direct_multi(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
+                               hipStream_t stream);
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                          hipStream_t stream);
 // Matrix-core path: whether the kernels can run the shape, scratch they need, launch.

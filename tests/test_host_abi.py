@@ -111,10 +111,17 @@ def test_argument_errors_are_statuses_not_crashes():
     assert l.kst_forward_seg_padded(one, one, one, one, 1 << 20, 1, 1, 1, 1, 9, 2, 0, 0, None) == 2
     assert l.kst_forward_padded(one, one, one, 1, 1, 1, 1, 9, 2, 0, None) == 2
     assert l.kst_forward_seg_padded(one, None, one, one, 1 << 20, 1, 1, 1, 4, 3, 2, 0, 0, None) == 1
-    need = kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 2, kst.KST_F32)
-    assert need >= 2 * 3 * 10 * 10 * 4
-    assert l.kst_forward_seg_padded(one, one, one, None, 0, 2, 3, 4, 8, 3, 2, 0, 0, None) == 4
-    assert l.kst_forward_seg_padded(one, one, one, one, need - 1, 2, 3, 4, 8, 3, 2, 0, 0, None) == 4
+    # (a single-channel layer is served through a framed copy of the input)
+    need = kst.kst_workspace_bytes_padded(2, 1, 4, 8, 3, 2, kst.KST_F32)
+    assert need >= 2 * 1 * 10 * 10 * 4
+    assert l.kst_forward_seg_padded(one, one, one, None, 0, 2, 1, 4, 8, 3, 2, 0, 0, None) == 4
+    assert l.kst_forward_seg_padded(one, one, one, one, need - 1, 2, 1, 4, 8, 3, 2, 0, 0, None) == 4
     assert kst.kst_workspace_bytes_padded(1, 1, 1, 1, 9, 2, 0) == 0
     # odd P also holds the wider output
-    assert kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 3, kst.KST_F32) >= 2 * 3 * 12 * 12 * 4 + 2 * 4 * 21 * 21 * 4
+    assert kst.kst_workspace_bytes_padded(2, 1, 4, 8, 3, 3, kst.KST_F32) >= 2 * 1 * 12 * 12 * 4 + 2 * 4 * 21 * 21 * 4
+    # several input channels on the direct path: the kernel supplies the zero frame itself, so an
+    # even P needs no workspace at all and an odd P only the wider output
+    assert kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 2, kst.KST_F32) == 0
+    need = kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 3, kst.KST_F32)
+    assert 2 * 4 * 21 * 21 * 4 <= need < 2 * 4 * 21 * 21 * 4 + 2 * 3 * 12 * 12 * 4
+    assert l.kst_forward_seg_padded(one, one, one, None, 0, 2, 3, 4, 8, 3, 3, 0, 0, None) == 4
