@@ -56,11 +56,19 @@ typedef enum {
 } kst_status;
 
 /* Which kernel family kst_forward_seg uses.  AUTO picks DIRECT for small
- * channel counts (bandwidth-bound) and IGEMM (matrix cores) otherwise. */
+ * channel counts (bandwidth-bound) and IGEMM (matrix cores) otherwise.
+ * IGEMM_EVEN (for tests and tuning) is IGEMM with one of its launch forms
+ * forced: the (tile, channel chunk) list of the layer cut into equal ranges
+ * over persistent workgroups, which IGEMM itself takes only where its cost
+ * model says it pays.  It exists for KST_F32 layers with Cin, Cout and the
+ * input row stride multiples of 4 whose tile fits the kernel; any other
+ * layer gets KST_ERR_PATH.  Its workspace differs from IGEMM's: ask
+ * kst_workspace_bytes with the same path. */
 typedef enum {
     KST_PATH_AUTO = 0,
     KST_PATH_DIRECT = 1,
-    KST_PATH_IGEMM = 2
+    KST_PATH_IGEMM = 2,
+    KST_PATH_IGEMM_EVEN = 3
 } kst_path;
 
 int kst_version(void);

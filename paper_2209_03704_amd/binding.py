@@ -13,7 +13,7 @@ import os
 import torch
 
 KST_F32, KST_BF16 = 0, 1
-KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM = 0, 1, 2
+KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN = 0, 1, 2, 3
 KST_OK = 0
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

@@ -51,13 +51,20 @@ kst_status resolve_path(const Shape &s, kst_dtype dt, int path, kst_path *out)
         *out = KST_PATH_IGEMM;
         return KST_OK;
     }
+    if (path == KST_PATH_IGEMM_EVEN) {
+        if (dt != KST_F32 || !igemm_f32_supported(s) || !igemm_f32_even_shares_possible(s)) return KST_ERR_PATH;
+        *out = KST_PATH_IGEMM_EVEN;
+        return KST_OK;
+    }
     return KST_ERR_PATH;
 }
 
+bool on_matrix_cores(kst_path path) { return path == KST_PATH_IGEMM || path == KST_PATH_IGEMM_EVEN; }
+
 size_t workspace_for(const Shape &s, kst_dtype dt, kst_path path)
 {
-    if (path != KST_PATH_IGEMM) return 0;
-    return dt == KST_BF16 ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s);
+    if (!on_matrix_cores(path)) return 0;
+    return dt == KST_BF16 ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s, path == KST_PATH_IGEMM_EVEN);
 }
 
 // The segregated forward pass on a validated shape (s.Ns may exceed s.N only where
@@ -74,7 +81,7 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
     }
-    if (s.Ns != s.N && !(chosen == KST_PATH_IGEMM && dtype == KST_F32 && igemm_f32_takes_row_stride(s)))
+    if (s.Ns != s.N && !(on_matrix_cores(chosen) && dtype == KST_F32 && igemm_f32_takes_row_stride(s)))
         return KST_ERR_SHAPE;
     hipError_t e;
     if (chosen == KST_PATH_DIRECT)
@@ -82,7 +89,8 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
     else if (dtype == KST_BF16)
         e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, stream);
     else
-        e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s, stream);
+        e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s,
+                             chosen == KST_PATH_IGEMM_EVEN, stream);
     return e == hipSuccess ? KST_OK : KST_ERR_HIP;
 }
 
@@ -208,7 +216,7 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     if (st != KST_OK) return st;
     // The pipelined fp32 matrix-core kernel wants rows of whole 16-byte groups: give the framed
     // copy a row stride rounded up to 4 elements when that is the kernel that will run.
-    if (f->chosen == KST_PATH_IGEMM && dt == KST_F32 && (f->Nq & 3) != 0) {
+    if (on_matrix_cores(f->chosen) && dt == KST_F32 && (f->Nq & 3) != 0) {
         Shape wide = f->s;
         wide.Ns = (f->Nq + 3) & ~3;
         if (igemm_f32_takes_row_stride(wide)) f->s = wide;

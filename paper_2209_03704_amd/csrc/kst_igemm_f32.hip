@@ -574,7 +574,7 @@ struct SkPlan {
     StreamK k;
 };
 
-static SkPlan streamk_plan(const Shape &s, const IgemmParams &p)
+static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
 {
     SkPlan r;
     r.use = false;
@@ -582,8 +582,13 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p)
     const unsigned long long tiles = (unsigned long long)p.tiles_m * p.tiles_co;
     r.k.units = tiles * (unsigned)r.k.chunks;
     r.k.grid = r.k.units < (unsigned long long)SK_GRID ? (int)r.k.units : SK_GRID;
+    if (!pipe_ok(p) || tiles > (1u << 22)) return r;
+    if (force) {
+        r.use = true;
+        return r;
+    }
     // Beyond 16 rounds of whole tiles the last, part-filled round costs less than the threshold.
-    if (!pipe_ok(p) || tiles % SK_GRID == 0 || tiles > 16u * SK_GRID) return r;
+    if (tiles % SK_GRID == 0 || tiles > 16u * SK_GRID) return r;
     unsigned long long partial = 0;                       // pieces that go through a slot
     for (int g = 0; g < r.k.grid; ++g) {
         unsigned long long u = (unsigned long long)g * r.k.units / (unsigned)r.k.grid;
@@ -603,10 +608,15 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p)
     return r;
 }
 
-size_t igemm_f32_workspace_bytes(const Shape &s)
+bool igemm_f32_even_shares_possible(const Shape &s)
+{
+    return streamk_plan(s, plan(s), true).use;
+}
+
+size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even)
 {
     const IgemmParams p = plan(s);
-    const SkPlan sk = streamk_plan(s, p);
+    const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) return (size_t)2 * sk.k.grid * SK_SLOT_FLOATS * sizeof(float);
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
 }
@@ -676,10 +686,10 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
 }
 
 hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
-                            hipStream_t stream)
+                            bool force_even, hipStream_t stream)
 {
     const IgemmParams p = plan(s);
-    const SkPlan sk = streamk_plan(s, p);
+    const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) {
         float *slots = (float *)ws;
         switch (s.n) {

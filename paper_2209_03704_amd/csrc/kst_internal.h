@@ -123,10 +123,12 @@ bool igemm_bf16_ring_supported(const Shape &s);    // LDS-ring variant (n = 2, 3
 hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
 bool igemm_bf16_wide_supported(const Shape &s);    // persistent wide-tile variant (same shapes, at least ~one tile per CU)
 hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
-size_t igemm_f32_workspace_bytes(const Shape &s);
+// force_even: take the even-share launch whenever igemm_f32_even_shares_possible, whatever the cost model says.
+bool igemm_f32_even_shares_possible(const Shape &s);
+size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even = false);
 size_t igemm_bf16_workspace_bytes(const Shape &s);
 hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
-                            hipStream_t stream);
+                            bool force_even, hipStream_t stream);
 hipError_t launch_igemm_bf16(const void *in, const void *w_seg, float *out, void *ws, const Shape &s,
                              hipStream_t stream);
 

@@ -151,6 +151,45 @@ def test_direct_multi_tile(B, Cin, Cout, N, n, dtype):
     check_layer(layer, paths=("direct", "forward"), seed=N + n)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (2, 3, 1, 70, 3),       # Table 1's channel counts: one output channel, chunks of 4 channels
+    (2, 3, 1, 70, 4),
+    (1, 3, 1, 45, 5),
+    (2, 20, 3, 32, 4),      # the last generator layer's shape (-> RGB): three chunks, the last ragged
+    (1, 9, 2, 37, 5),       # two channels per lane, odd M, a tile one quad wide
+    (1, 4, 4, 33, 6),       # exactly one chunk of 4 (fp32) / half a chunk of 8 (bf16)
+    (2, 5, 5, 19, 3),       # Cout = 5: one channel per lane
+    (1, 17, 6, 21, 7),      # Cout = 6: lanes take 3 channels each; largest kernel
+    (1, 8, 8, 18, 2),       # Cout = 8: groups of 4
+    (3, 2, 7, 12, 1),       # n = 1: three empty sub-kernels
+    (1, 33, 12, 70, 4),     # several tiles in both directions, groups of 4 of 12 channels
+])
+def test_direct_several_input_channels(B, Cin, Cout, N, n, dtype):
+    """Direct path with Cin >= 2: the kernel that keeps a quad of up to four output channels per lane."""
+    layer = wl.Layer("multi", B, Cin, Cout, N, n, dtype, "normal", w_std=0.3)
+    check_layer(layer, paths=("direct",), seed=31 * N + 7 * n + Cin)
+
+
+def test_direct_several_input_channels_is_exact_on_integers_and_stays_inside_out():
+    for (B, Cin, Cout, N, n, P) in [(2, 20, 3, 32, 4, 0), (1, 9, 2, 37, 5, 0), (2, 3, 1, 30, 3, 2), (1, 6, 4, 11, 4, 3),
+                                    (1, 5, 3, 2, 5, 2)]:
+        layer = wl.Layer("multi_int", B, Cin, Cout, N, n, "f32", "integer")
+        x, w = wl.make_tensors(layer, 100 + N)
+        xd, wd = x.to(DEV), w.to(DEV)
+        M = kst.kst_out_size_padded(N, n, P)
+        numel = B * Cout * M * M
+        guard = 2048
+        buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+        out = buf[guard:guard + numel].view(B, Cout, M, M)
+        kst.kst_forward_seg_padded(xd, kst.kst_segregate_weights(wd), Cout, n, P, out=out, path=kst.KST_PATH_DIRECT)
+        torch.cuda.synchronize()
+        host = buf.cpu()
+        assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+        want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+        assert np.array_equal(host[guard:guard + numel].view(out.shape).numpy().astype(np.float64), want), (N, n, P)
+
+
 @pytest.mark.parametrize("B,Cout,N,n", [
     (2, 3, 100, 5),     # M = 195: planes end off 16-byte boundaries, several output channels
     (3, 2, 64, 4),      # even kernel
@@ -266,6 +305,56 @@ def test_igemm_bf16_wide_kernel_is_exact_on_integers_and_stays_inside_out():
     assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
     want = oracle.forward(wl.to_f64(x), wl.to_f64(w))
     assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (32, 64, 768, 16, 4),    # 294 tiles x 16 chunks over 256 workgroups: whole tiles and partial pieces per range
+    (8, 256, 128, 16, 4),    # 13 tiles x 64 chunks: every tile shared by about 20 workgroups
+    (3, 100, 132, 12, 5),    # 6 tiles (ragged both ways) x 25 chunks: one chunk per workgroup
+    (20, 32, 384, 12, 3),    # 264 tiles x 8 chunks, odd M
+])
+def test_igemm_f32_even_shares_sampled_planes(B, Cin, Cout, N, n):
+    """fp32 matrix-core path where the (tile, chunk) list is cut into equal ranges: pieces that
+    are whole tiles, pieces that go through the partial slots, and their sum in a second pass."""
+    layer = wl.Layer("shares", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
+    x, w = wl.make_tensors(layer, 900 + Cin + N)
+    xd, wd = x.to(DEV), w.to(DEV)
+    # two partial-tile slots of 128 x 128 x 4 floats per workgroup, one workgroup per CU or per unit
+    M = 2 * N - n
+    E = (M + 1) // 2
+    units = ((B * E * E + 127) // 128) * ((Cout + 127) // 128) * (Cin // 4)
+    assert kst.kst_workspace_bytes(B, Cin, Cout, N, n, kst.KST_F32, kst.KST_PATH_IGEMM_EVEN) == \
+        2 * min(256, units) * 128 * 128 * 4 * 4
+    out = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM_EVEN)
+    again = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM_EVEN)
+    whole = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    assert rel_err(out.cpu().numpy(), whole.cpu().numpy().astype(np.float64)) <= TOL["f32"]
+    assert torch.isfinite(out).all()
+    assert torch.equal(out, again)                     # fixed summing order: bit-reproducible
+    b_idx, co_idx = sample_planes(layer, 48, Cin)
+    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx)
+    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
+    e = rel_err(got, want)
+    assert e <= TOL["f32"], "rel err %.3e" % e
+
+
+def test_igemm_f32_even_shares_are_exact_on_integers_and_stay_inside_out():
+    layer = wl.Layer("shares_int", 8, 256, 128, 16, 4, "f32", "integer")
+    x, w = wl.make_tensors(layer, 12)
+    xd, wd = x.to(DEV), w.to(DEV)
+    numel = int(np.prod(layer.out_shape))
+    guard = 4096
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    out = buf[guard:guard + numel].view(layer.out_shape)
+    kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, out=out, path=kst.KST_PATH_IGEMM_EVEN)
+    torch.cuda.synchronize()
+    host = buf.cpu()
+    assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+    b_idx, co_idx = sample_planes(layer, 32, 5)
+    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx)
+    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, want)
 
 
 # ----------------------------------------------------------------------------

@@ -94,6 +94,12 @@ def test_argument_errors_are_statuses_not_crashes():
     # unknown path; matrix-core path asked for a kernel size it does not cover
     assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 3, 0, 9, None) == 6
     assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 9, 0, 2, None) == 6
+    # the forced even-share launch exists for fp32 layers with Cin and Cout multiples of 4 only
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 3, 1, 3, None) == 6      # bf16
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 10, 16, 8, 3, 0, 3, None) == 6     # Cin = 10
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 18, 8, 3, 0, 3, None) == 6      # Cout = 18
+    assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 3, 0, 3, None) == 4      # fine, but no workspace
+    assert kst.kst_workspace_bytes(1, 8, 16, 8, 3, kst.KST_F32, kst.KST_PATH_IGEMM_EVEN) == 2 * 2 * 128 * 128 * 4 * 4
     # alignment
     odd = ctypes.c_void_p(20)
     assert l.kst_forward(odd, one, one, 1, 1, 1, 4, 3, 0, None) == 7
