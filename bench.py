@@ -30,10 +30,10 @@ if ROOT not in sys.path:
 # profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
 # kernels, quoted next to the live timing; None for a layer that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_1ch_bandwidth": 339391020,
-    "cfg3_gan_n4": 411742780,
-    "cfg4_deep_n5": 628984245 + 126872425,   # matrix-core kernel + split-reduction pass
-    "cfg5_late_bf16": 352737007,
+    "cfg2_1ch_bandwidth": 339373728,
+    "cfg3_gan_n4": 682990720 + 197908170,   # matrix-core kernel + pass summing the partial tiles
+    "cfg4_deep_n5": 577022863 + 100620772,  # the same two kernels
+    "cfg5_late_bf16": 352824969,
 }
 
 

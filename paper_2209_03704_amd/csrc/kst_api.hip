@@ -212,6 +212,7 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     f->Mq = 2 * f->Nq - n;
     if (f->M < 1) return KST_ERR_SHAPE;
     f->s = make_shape(B, Cin, Cout, f->Nq, n);
+    if (path == KST_PATH_IGEMM_EVEN) f->s.Ns = (f->Nq + 3) & ~3;     // the stride that launch form wants
     st = resolve_path(f->s, dt, path, &f->chosen);
     if (st != KST_OK) return st;
     // The pipelined fp32 matrix-core kernel wants rows of whole 16-byte groups: give the framed
