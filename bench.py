@@ -96,6 +96,22 @@ def roofline_for(layer, ms, metrics):
             "frac": round(a / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name)}
 
 
+def paper_roofline(layer, fwd_ms, din_ms, dw_ms, metrics):
+    """Roofline fractions of a paper-shaped layer's three passes.  Many-channel layers are priced
+    against the fp32 matrix-core peak (each gradient does the forward's useful MACs once), the
+    few-channel ones against HBM (the forward by its algorithmic bytes; the gradients read `g` and
+    the other operand and write the gradient: the same byte count)."""
+    macs = metrics.useful_macs(layer)
+    many = layer.Cin >= 8 and layer.Cout >= 16
+    out = {"bound": "mfma" if many else "hbm"}
+    for name, ms in (("forward", fwd_ms), ("backward_input", din_ms), ("backward_weight", dw_ms)):
+        if many:
+            out[name + "_frac"] = round(2.0 * macs / (ms * 1e-3) / 1e12 / metrics.MFMA_PEAK_TFLOPS["f32"], 4)
+        else:
+            out[name + "_frac"] = round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4)
+    return out
+
+
 def cpu_baseline(layer, host, metrics, wl, budget_s=12.0):
     """The fp64 zero-insert oracle on the host cores, on a bounded sample of batch items."""
     import oracle
@@ -293,6 +309,7 @@ def main():
                 "algorithmic_mac_ratio": round(metrics.conventional_macs(layer) / metrics.useful_macs(layer), 3),
                 "backward_input_us": round(bi_ms * 1e3, 1),
                 "backward_weight_us": round(bw_ms * 1e3, 1),
+                "roofline": paper_roofline(layer, ms, bi_ms, bw_ms, metrics),
             })
             del xd, outs, ws
             torch.cuda.empty_cache()

@@ -85,9 +85,354 @@ __global__ void __launch_bounds__(256) backward_weight_generic_kernel(const T *_
     }
 }
 
+// Kernel sizes up to 7, any channel counts: the same sums with register blocking.
+//
+// Kernel gradient: a workgroup owns one input channel, CO output channels (n*n*CO <= 64) and a
+// slice of the positions; a lane keeps all n*n*CO partial sums in registers, so an input value is
+// loaded once for n*n*CO products and nothing is re-read per kernel element.  The partial sums
+// are added across the lanes with wave shuffles, across the four waves through LDS.
+template <int n, int CO, typename T>
+__global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__restrict__ in, const float *__restrict__ g,
+                                                                    float *__restrict__ dst, int B, int Cin, int Cout,
+                                                                    int N, int M, int per_slice)
+{
+    constexpr int NN = n * n;
+    __shared__ float red[4][NN * CO];
+    const int groups = Cout / CO;                                 // CO divides Cout
+    unsigned id = blockIdx.x;
+    const int ci = (int)(id % (unsigned)Cin);
+    id /= (unsigned)Cin;
+    const int co0 = (int)(id % (unsigned)groups) * CO;
+    const int slice = (int)(id / (unsigned)groups);
+    const int tid = threadIdx.x;
+    const int per_item = N * N;
+    const int total = B * per_item;
+    const int e_begin = slice * per_slice, e_end = min(total, e_begin + per_slice);
+
+    float acc[CO][NN];
+#pragma unroll
+    for (int k = 0; k < CO; ++k)
+#pragma unroll
+        for (int t = 0; t < NN; ++t) acc[k][t] = 0.0f;
+
+    for (int e = e_begin + tid; e < e_end; e += 256) {
+        const int b = e / per_item, rem = e - b * per_item;
+        const int a = rem / N, c = rem - a * N;
+        const float xin = to_f32(in[(((size_t)b * Cin + ci) * N + a) * N + c]);
+        const float *gp = g + ((size_t)b * Cout + co0) * M * M;
+#pragma unroll
+        for (int u = 0; u < n; ++u) {
+            const int y = 2 * a - u;
+            if (y < 0 || y >= M) continue;
+#pragma unroll
+            for (int v = 0; v < n; ++v) {
+                const int x = 2 * c - v;
+                if (x < 0 || x >= M) continue;
+#pragma unroll
+                for (int k = 0; k < CO; ++k)
+                    acc[k][u * n + v] = fmaf(xin, gp[((size_t)k * M + y) * M + x], acc[k][u * n + v]);
+            }
+        }
+    }
+
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int k = 0; k < CO; ++k)
+#pragma unroll
+        for (int t = 0; t < NN; ++t) {
+            float v = acc[k][t];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+            if (lane == 0) red[wave][k * NN + t] = v;
+        }
+    __syncthreads();
+    if (tid < NN * CO) {
+        const int k = tid / NN, t = tid - k * NN;
+        const float sum = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        dst[(size_t)slice * Cout * Cin * NN + ((size_t)(co0 + k) * Cin + ci) * NN + t] = sum;
+    }
+}
+
+// Kernel gradient for layers with many input channels (and any, typically few, output channels):
+// a workgroup is one wave whose lanes are 64 input channels; it walks a slice of the positions.
+// At a position every lane loads its channel's input value, and the n*n*CO values of g the
+// position meets are loaded once by the first n*n*CO lanes (one predicated load, bounds per lane)
+// and handed to all lanes with lane reads, so a product costs no load of its own and g is not
+// fetched again for every input channel.  Positions are taken eight at a time so that their
+// loads are in flight together.  A lane ends with the n*n*CO sums of its own channel: no
+// reduction across lanes; every wave writes one partial result, added up by a second pass.
+constexpr int L_BATCH = 8;
+
+template <int n, int CO, typename T>
+__global__ void __launch_bounds__(64) backward_weight_lanes_kernel(const T *__restrict__ in, const float *__restrict__ g,
+                                                                    float *__restrict__ dst, int B, int Cin, int Cout,
+                                                                    int N, int M, int per_slice)
+{
+    constexpr int NN = n * n;
+    constexpr int W = NN * CO;                                    // window values per position (<= 64)
+    const int cgroups = (Cin + 63) / 64, groups = Cout / CO;      // CO divides Cout
+    unsigned id = blockIdx.x;
+    const int cg = (int)(id % (unsigned)cgroups);
+    id /= (unsigned)cgroups;
+    const int co0 = (int)(id % (unsigned)groups) * CO;
+    const int slice = (int)(id / (unsigned)groups);
+    const int lane = threadIdx.x;
+    const int ci = cg * 64 + lane;
+    const bool ci_ok = ci < Cin;
+    const int per_item = N * N;
+    const int total = B * per_item;
+    const int e_begin = slice * per_slice, e_end = min(total, e_begin + per_slice);
+    // this lane's window element: output channel k, kernel element (u, v)
+    const int wk = lane / NN, wuv = lane - wk * NN;
+    const int wu = wuv / n, wv = wuv - wu * n;
+    const bool w_ok = lane < W;
+
+    float acc[W];
+#pragma unroll
+    for (int t = 0; t < W; ++t) acc[t] = 0.0f;
+
+    for (int e0 = e_begin; e0 < e_end; e0 += L_BATCH) {
+        float xin[L_BATCH], gv[L_BATCH];
+#pragma unroll
+        for (int j = 0; j < L_BATCH; ++j) {
+            const int e = e0 + j;                                 // wave-uniform
+            xin[j] = 0.0f;
+            gv[j] = 0.0f;
+            if (e < e_end) {
+                const int b = e / per_item, rem = e - b * per_item;
+                const int a = rem / N, c = rem - a * N;
+                if (ci_ok) xin[j] = to_f32(in[(((size_t)b * Cin + ci) * N + a) * N + c]);
+                const int y = 2 * a - wu, x = 2 * c - wv;
+                if (w_ok && y >= 0 && y < M && x >= 0 && x < M)
+                    gv[j] = g[(((size_t)b * Cout + co0 + wk) * M + y) * M + x];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < L_BATCH; ++j)
+#pragma unroll
+            for (int t = 0; t < W; ++t)
+                acc[t] = fmaf(xin[j], __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gv[j]), t)),
+                              acc[t]);
+    }
+    if (!ci_ok) return;
+    float *o = dst + (size_t)slice * Cout * Cin * NN;
+#pragma unroll
+    for (int t = 0; t < W; ++t) {
+        const int k = t / NN, uv = t - k * NN;
+        o[((size_t)(co0 + k) * Cin + ci) * NN + uv] = acc[t];
+    }
+}
+
+// Input gradient: a lane owns one position (a, c) of one batch item for a group of D_CIG input
+// channels.  Per pass over CG output channels (n*n*CG <= 64) it loads the n x n window of g it
+// needs once into registers and multiplies it with the kernels of its D_CIG channels, which the
+// workgroup has staged in LDS (the same values for every lane: 16-byte reads at one address).
+constexpr int D_CIG = 8;
+
+template <int n, int CG, typename T>
+__global__ void __launch_bounds__(256) backward_input_regs_kernel(const float *__restrict__ g, const T *__restrict__ w,
+                                                                   float *__restrict__ din, int B, int Cin, int Cout,
+                                                                   int N, int M)
+{
+    constexpr int NN = n * n;
+    constexpr int WPC = (NN * CG + 3) & ~3;                       // staged weights per input channel, padded
+    __shared__ __attribute__((aligned(16))) float Wl[D_CIG * WPC];
+    const int tiles = (N * N + 255) / 256;
+    const int cigs = (Cin + D_CIG - 1) / D_CIG;
+    unsigned id = blockIdx.x;
+    const int tile = (int)(id % (unsigned)tiles);
+    id /= (unsigned)tiles;
+    const int ci0 = (int)(id % (unsigned)cigs) * D_CIG;
+    const int b = (int)(id / (unsigned)cigs);
+    const int tid = threadIdx.x;
+    const int pos = tile * 256 + tid;
+    const bool live = pos < N * N;
+    const int a = live ? pos / N : 0, c = live ? pos - (pos / N) * N : 0;
+
+    float acc[D_CIG];
+#pragma unroll
+    for (int q = 0; q < D_CIG; ++q) acc[q] = 0.0f;
+
+    for (int co0 = 0; co0 < Cout; co0 += CG) {
+        // This pass's kernels -> LDS: [channel of the group][output channel of the pass][u][v].
+        __syncthreads();                                          // the previous pass has read its weights
+        for (int e = tid; e < D_CIG * WPC; e += 256) {
+            const int q = e / WPC, rem = e - q * WPC;
+            const int k = rem / NN, t = rem - k * NN;
+            float v = 0.0f;
+            if (k < CG && co0 + k < Cout && ci0 + q < Cin) v = to_f32(w[((size_t)(co0 + k) * Cin + ci0 + q) * NN + t]);
+            Wl[e] = v;
+        }
+        // The window of g this position meets (zero outside the map and past the last channel).
+        float gw[CG][NN];
+#pragma unroll
+        for (int k = 0; k < CG; ++k) {
+            const bool k_ok = live && co0 + k < Cout;
+            const float *gp = g + ((size_t)b * Cout + min(co0 + k, Cout - 1)) * M * M;
+#pragma unroll
+            for (int u = 0; u < n; ++u)
+#pragma unroll
+                for (int v = 0; v < n; ++v) {
+                    const int y = 2 * a - u, x = 2 * c - v;
+                    const bool ok = k_ok && y >= 0 && y < M && x >= 0 && x < M;
+                    gw[k][u * n + v] = ok ? gp[(size_t)y * M + x] : 0.0f;
+                }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < D_CIG; ++q) {
+            float wv[WPC];
+#pragma unroll
+            for (int g4 = 0; g4 < WPC / 4; ++g4) {
+                const float4 v = *reinterpret_cast<const float4 *>(&Wl[q * WPC + 4 * g4]);
+                wv[4 * g4] = v.x;
+                wv[4 * g4 + 1] = v.y;
+                wv[4 * g4 + 2] = v.z;
+                wv[4 * g4 + 3] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < CG; ++k)
+#pragma unroll
+                for (int t = 0; t < NN; ++t) acc[q] = fmaf(gw[k][t], wv[k * NN + t], acc[q]);
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int q = 0; q < D_CIG; ++q)
+        if (ci0 + q < Cin) din[(((size_t)b * Cin + ci0 + q) * N + a) * N + c] = acc[q];
+}
+
+// Output channels per workgroup (kernel gradient) or per pass (input gradient): the largest of
+// 4, 3, 2, 1 with n*n*k <= 64 (and, for the kernel gradient, dividing Cout).
+constexpr int regs_fit(int n) { return 64 / (n * n) < 4 ? 64 / (n * n) : 4; }
+
+inline int weight_co(int n, int Cout)
+{
+    for (int k = regs_fit(n); k > 1; --k)
+        if (Cout % k == 0) return k;
+    return 1;
+}
+
+template <int n, int CO, typename T>
+void launch_weight_regs_co(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                           hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)s.Cin * (unsigned)(s.Cout / CO) * (unsigned)slices;
+    hipLaunchKernelGGL((backward_weight_regs_kernel<n, CO, T>), dim3(blocks), dim3(256), 0, stream, in, g, dst, s.B,
+                       s.Cin, s.Cout, s.N, s.M, per_slice);
+}
+
+template <int n, typename T>
+void launch_weight_regs_n(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                          hipStream_t stream)
+{
+    const int co = weight_co(n, s.Cout);
+    if constexpr (regs_fit(n) >= 4)
+        if (co == 4) return launch_weight_regs_co<n, 4, T>(in, g, dst, s, slices, per_slice, stream);
+    if constexpr (regs_fit(n) >= 3)
+        if (co == 3) return launch_weight_regs_co<n, 3, T>(in, g, dst, s, slices, per_slice, stream);
+    if constexpr (regs_fit(n) >= 2)
+        if (co == 2) return launch_weight_regs_co<n, 2, T>(in, g, dst, s, slices, per_slice, stream);
+    launch_weight_regs_co<n, 1, T>(in, g, dst, s, slices, per_slice, stream);
+}
+
+template <typename T>
+bool launch_weight_regs(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                        hipStream_t stream)
+{
+    switch (s.n) {
+        case 1: launch_weight_regs_n<1, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 2: launch_weight_regs_n<2, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 3: launch_weight_regs_n<3, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 4: launch_weight_regs_n<4, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 5: launch_weight_regs_n<5, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 6: launch_weight_regs_n<6, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        case 7: launch_weight_regs_n<7, T>(in, g, dst, s, slices, per_slice, stream); return true;
+        default: return false;
+    }
+}
+
+template <int n, typename T>
+void launch_input_regs_n(const float *g, const T *w, float *din, const Shape &s, hipStream_t stream)
+{
+    constexpr int CG = regs_fit(n);
+    const unsigned tiles = (unsigned)((s.N * s.N + 255) / 256), cigs = (unsigned)((s.Cin + D_CIG - 1) / D_CIG);
+    hipLaunchKernelGGL((backward_input_regs_kernel<n, CG, T>), dim3(tiles * cigs * (unsigned)s.B), dim3(256), 0, stream,
+                       g, w, din, s.B, s.Cin, s.Cout, s.N, s.M);
+}
+
+template <typename T>
+bool launch_input_regs(const float *g, const T *w, float *din, const Shape &s, hipStream_t stream)
+{
+    const size_t blocks = (size_t)((s.N * s.N + 255) / 256) * ((s.Cin + D_CIG - 1) / D_CIG) * s.B;
+    if (blocks >= 0x7fffffffu) return false;
+    switch (s.n) {
+        case 1: launch_input_regs_n<1, T>(g, w, din, s, stream); return true;
+        case 2: launch_input_regs_n<2, T>(g, w, din, s, stream); return true;
+        case 3: launch_input_regs_n<3, T>(g, w, din, s, stream); return true;
+        case 4: launch_input_regs_n<4, T>(g, w, din, s, stream); return true;
+        case 5: launch_input_regs_n<5, T>(g, w, din, s, stream); return true;
+        case 6: launch_input_regs_n<6, T>(g, w, din, s, stream); return true;
+        case 7: launch_input_regs_n<7, T>(g, w, din, s, stream); return true;
+        default: return false;
+    }
+}
+
+template <int n, int CO, typename T>
+void launch_weight_lanes_co(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                            hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((s.Cin + 63) / 64) * (unsigned)(s.Cout / CO) * (unsigned)slices;
+    hipLaunchKernelGGL((backward_weight_lanes_kernel<n, CO, T>), dim3(blocks), dim3(64), 0, stream, in, g, dst, s.B,
+                       s.Cin, s.Cout, s.N, s.M, per_slice);
+}
+
+template <int n, typename T>
+void launch_weight_lanes_n(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                           hipStream_t stream)
+{
+    const int co = weight_co(n, s.Cout);
+    if constexpr (regs_fit(n) >= 4)
+        if (co == 4) return launch_weight_lanes_co<n, 4, T>(in, g, dst, s, slices, per_slice, stream);
+    if constexpr (regs_fit(n) >= 3)
+        if (co == 3) return launch_weight_lanes_co<n, 3, T>(in, g, dst, s, slices, per_slice, stream);
+    if constexpr (regs_fit(n) >= 2)
+        if (co == 2) return launch_weight_lanes_co<n, 2, T>(in, g, dst, s, slices, per_slice, stream);
+    launch_weight_lanes_co<n, 1, T>(in, g, dst, s, slices, per_slice, stream);
+}
+
+template <typename T>
+void launch_weight_lanes(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                         hipStream_t stream)
+{
+    switch (s.n) {
+        case 1: return launch_weight_lanes_n<1, T>(in, g, dst, s, slices, per_slice, stream);
+        case 2: return launch_weight_lanes_n<2, T>(in, g, dst, s, slices, per_slice, stream);
+        case 3: return launch_weight_lanes_n<3, T>(in, g, dst, s, slices, per_slice, stream);
+        case 4: return launch_weight_lanes_n<4, T>(in, g, dst, s, slices, per_slice, stream);
+        case 5: return launch_weight_lanes_n<5, T>(in, g, dst, s, slices, per_slice, stream);
+        case 6: return launch_weight_lanes_n<6, T>(in, g, dst, s, slices, per_slice, stream);
+        default: return launch_weight_lanes_n<7, T>(in, g, dst, s, slices, per_slice, stream);
+    }
+}
+
+// Lanes over input channels pay once a wave's lanes are mostly busy.
+bool weight_lanes_apply(const Shape &s) { return s.n <= 7 && s.Cin >= 48; }
+
+// Slices of the position range for that kernel: about 2048 waves, at least 64 positions each.
+int weight_lane_slices(const Shape &s)
+{
+    const long long waves_per_slice = (long long)((s.Cin + 63) / 64) * (s.Cout / weight_co(s.n, s.Cout));
+    const long long total = (long long)s.B * s.N * s.N;
+    long long slices = (2048 + waves_per_slice - 1) / waves_per_slice;
+    if (slices > (total + 63) / 64) slices = (total + 63) / 64;
+    return slices < 1 ? 1 : (int)slices;
+}
+
 // Slices of the position range: few (co, ci) pairs alone cannot fill the chip.
 int weight_slices(const Shape &s)
 {
+    if (weight_lanes_apply(s)) return weight_lane_slices(s);
     const long long pairs = (long long)s.Cout * s.Cin;
     const long long total = (long long)s.B * s.N * s.N;
     long long slices = (1024 + pairs - 1) / pairs;
@@ -101,6 +446,9 @@ int weight_slices(const Shape &s)
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream)
 {
+    if (dt == KST_BF16 ? launch_input_regs<uint16_t>(g, (const uint16_t *)w, din, s, stream)
+                       : launch_input_regs<float>(g, (const float *)w, din, s, stream))
+        return hipGetLastError();
     const size_t total = (size_t)s.B * s.Cin * s.N * s.N;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == KST_BF16)
@@ -126,12 +474,24 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
     const int per_slice = (total + slices - 1) / slices;
     const unsigned blocks = (unsigned)s.Cout * (unsigned)s.Cin * (unsigned)slices;
     float *dst = slices > 1 ? (float *)ws : dw;
-    if (dt == KST_BF16)
+    bool regs = false;
+    if (weight_lanes_apply(s)) {
+        if (dt == KST_BF16) launch_weight_lanes<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream);
+        else launch_weight_lanes<float>((const float *)in, g, dst, s, slices, per_slice, stream);
+        regs = true;
+    } else {
+        regs = dt == KST_BF16 ? launch_weight_regs<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream)
+                              : launch_weight_regs<float>((const float *)in, g, dst, s, slices, per_slice, stream);
+    }
+    if (regs) {
+        // the register-blocked kernel has run
+    } else if (dt == KST_BF16) {
         hipLaunchKernelGGL(backward_weight_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
                            (const uint16_t *)in, g, dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
-    else
+    } else {
         hipLaunchKernelGGL(backward_weight_generic_kernel<float>, dim3(blocks), dim3(256), 0, stream, (const float *)in, g,
                            dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
     return launch_splitk_reduce((const float *)ws, dw, (size_t)s.Cout * s.Cin * s.n * s.n, slices, stream);

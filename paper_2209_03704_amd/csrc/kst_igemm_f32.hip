@@ -722,8 +722,33 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
     return e;
 }
 
+// The same sum for many partial results of a small tensor: 16 elements x 16 strided shares of the
+// partial results per workgroup, the shares added through LDS in a fixed order.
+__global__ void __launch_bounds__(256) splitk_reduce_shares_kernel(const float *__restrict__ ws, float *__restrict__ out,
+                                                                     size_t elems, int splits)
+{
+    __shared__ float red[16][17];
+    const int el = threadIdx.x & 15, share = threadIdx.x >> 4;
+    const size_t e = (size_t)blockIdx.x * 16u + el;
+    float a = 0.0f;
+    if (e < elems)
+        for (int s = share; s < splits; s += 16) a += ws[(size_t)s * elems + e];
+    red[share][el] = a;
+    __syncthreads();
+    if (share == 0 && e < elems) {
+        float t = red[0][el];
+        for (int k = 1; k < 16; ++k) t += red[k][el];
+        out[e] = t;
+    }
+}
+
 hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream)
 {
+    if (splits >= 64) {
+        hipLaunchKernelGGL(splitk_reduce_shares_kernel, dim3((unsigned)((elems + 15) / 16)), dim3(256), 0, stream, ws, out,
+                           elems, splits);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
                        ws, out, elems, splits);
     return hipGetLastError();

@@ -594,6 +594,12 @@ def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     (4, 3, 1, 40, 5, 2),       # few channels, many positions: the kernel gradient slices the positions
     (2, 3, 2, 63, 3, 0),
     (16, 1, 1, 33, 4, 1),
+    (2, 128, 3, 8, 4, 2),      # many input, few output channels (a generator's last layer): lanes are channels
+    (1, 70, 5, 6, 3, 0),       # a ragged second group of 64 channels, one output channel per wave
+    (2, 64, 2, 5, 5, 1),       # 5 x 5: two output channels per wave; odd padding factor
+    (1, 48, 4, 4, 7, 0),       # 7 x 7: one output channel per wave
+    (3, 9, 12, 11, 4, 3),      # input gradient in several passes of 4 output channels, ragged channel group
+    (1, 20, 6, 9, 6, 0),
 ])
 def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
     layer = wl.Layer("grad_few", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
@@ -636,13 +642,28 @@ def test_gradients_on_the_matrix_cores_are_exact_on_integers_and_stay_inside_the
     assert np.array_equal(whost[guard:guard + wn].view(16, 24, 5, 5).numpy().astype(np.float64), want_dw)
 
 
-def test_gradients_are_exact_on_integers():
-    layer = wl.Layer("grad_int", 2, 3, 4, 9, 5, "f32", "integer", P=2)
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (2, 3, 4, 9, 5, 2),        # lanes are positions (kernel gradient), one pass of output channels (input gradient)
+    (2, 80, 3, 7, 4, 2),       # lanes are input channels
+    (1, 10, 9, 6, 3, 1),
+])
+def test_gradients_are_exact_on_integers(B, Cin, Cout, N, n, P):
+    layer = wl.Layer("grad_int", B, Cin, Cout, N, n, "f32", "integer", P=P)
     x, w = wl.make_tensors(layer, 99)
     M = kst.kst_out_size_padded(layer.N, layer.n, layer.P)
     gen = torch.Generator().manual_seed(5)
-    g = torch.randint(-3, 4, (2, 4, M, M), generator=gen).to(torch.float32)
-    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P).cpu().numpy().astype(np.float64)
-    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), layer.n, layer.P).cpu().numpy().astype(np.float64)
-    assert np.array_equal(din, oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P))
-    assert np.array_equal(dw, oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P))
+    g = torch.randint(-3, 4, (B, Cout, M, M), generator=gen).to(torch.float32)
+    guard = 512
+    din_buf = torch.full((B * Cin * N * N + 2 * guard,), float("nan"), device=DEV)
+    dw_buf = torch.full((Cout * Cin * n * n + 2 * guard,), float("nan"), device=DEV)
+    din = din_buf[guard:-guard].view(B, Cin, N, N)
+    dw = dw_buf[guard:-guard].view(Cout, Cin, n, n)
+    kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P, din=din)
+    kst.kst_backward_weight(x.to(DEV), g.to(DEV), layer.n, layer.P, dw=dw)
+    torch.cuda.synchronize()
+    for buf in (din_buf.cpu(), dw_buf.cpu()):
+        assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[-guard:]).all()
+    assert np.array_equal(din.cpu().numpy().astype(np.float64),
+                          oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P))
+    assert np.array_equal(dw.cpu().numpy().astype(np.float64),
+                          oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P))
