@@ -311,6 +311,8 @@ struct GradPlan {
     Shape s;                          // the unframed problem the kernels see
     size_t g_bytes, din_bytes, in_bytes;
     size_t split_bytes, wsplit_bytes; // input / kernel gradient on the matrix cores: partial sums
+    size_t gw_bytes;                  // kernel gradient on the matrix cores: its framed copy of g (replaces g_bytes)
+    int gw_frame, gw_stride;          // frame on the caller's g and row stride of that copy
 };
 
 kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
@@ -330,6 +332,16 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->split_bytes = backward_input_igemm_supported(f->s, dt) ? backward_input_igemm_workspace_bytes(f->s) : 0;
     f->wsplit_bytes = backward_weight_igemm_supported(f->s, dt) ? backward_weight_igemm_workspace_bytes(f->s)
                                                                : backward_weight_generic_workspace_bytes(f->s);
+    f->gw_bytes = 0;
+    f->gw_frame = f->gw_stride = 0;
+    if (backward_weight_igemm_supported(f->s, dt)) {
+        int frame, stride;
+        backward_weight_igemm_g_copy(f->s, &frame, &stride);
+        f->gw_frame = frame + (P & 1);                 // on top of the odd padding factor's one-pixel frame
+        f->gw_stride = stride;
+        const size_t rows = (size_t)f->M + 2 * (size_t)f->gw_frame;
+        f->gw_bytes = ((size_t)B * Cout * rows * stride * sizeof(float) + 255) & ~(size_t)255;
+    }
     return KST_OK;
 }
 
@@ -346,7 +358,7 @@ size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int 
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return f.in_bytes + f.g_bytes + f.wsplit_bytes;
+    return f.in_bytes + (backward_weight_igemm_supported(f.s, dtype) ? f.gw_bytes : f.g_bytes) + f.wsplit_bytes;
 }
 
 kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
@@ -390,7 +402,9 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(g) || !aligned16(dw)) return KST_ERR_ALIGN;
-    const size_t need = f.in_bytes + f.g_bytes + f.wsplit_bytes;
+    const bool cores = backward_weight_igemm_supported(f.s, dtype);
+    const size_t g_copy = cores ? f.gw_bytes : f.g_bytes;
+    const size_t need = f.in_bytes + g_copy + f.wsplit_bytes;
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
@@ -401,19 +415,22 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
         if (launch_frame_input(in, ws, B, Cin, N, f.q, f.Nq, dtype, stream) != hipSuccess) return KST_ERR_HIP;
         x_in = ws;
     }
-    if (f.g_bytes) {
-        void *gw = (char *)ws + f.in_bytes;
-        if (launch_frame_input(g, gw, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
-        g_in = (const float *)gw;
-    }
-    if (backward_weight_igemm_supported(f.s, dtype)) {
-        void *split_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + f.g_bytes : nullptr;
-        return launch_backward_weight_igemm((const float *)x_in, g_in, (float *)dw, split_ws, f.s, stream) == hipSuccess
+    void *gw = (char *)ws + f.in_bytes;
+    void *partial_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + g_copy : nullptr;
+    if (cores) {
+        // g framed once for the odd padding factor and for the kernel's own bounds-free reads
+        if (launch_frame_input(g, gw, B, Cout, f.M, f.gw_frame, f.gw_stride, KST_F32, stream) != hipSuccess)
+            return KST_ERR_HIP;
+        return launch_backward_weight_igemm((const float *)x_in, (const float *)gw, (float *)dw, partial_ws, f.s, stream) ==
+                       hipSuccess
                    ? KST_OK
                    : KST_ERR_HIP;
     }
-    void *slice_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + f.g_bytes : nullptr;
-    return launch_backward_weight_generic(x_in, g_in, (float *)dw, slice_ws, f.s, dtype, stream) == hipSuccess
+    if (f.g_bytes) {
+        if (launch_frame_input(g, gw, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
+        g_in = (const float *)gw;
+    }
+    return launch_backward_weight_generic(x_in, g_in, (float *)dw, partial_ws, f.s, dtype, stream) == hipSuccess
                ? KST_OK
                : KST_ERR_HIP;
 }

@@ -296,23 +296,28 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 // operand: rows = output channels co (A gathered from g at stride 2, shifted by the tap),
 // columns = input channels ci, reduction over the positions (b, a, c).
 //
+// The kernel reads g from a copy framed by n - 1 zeros on every side (made by the caller of the
+// launch function), so every tap of every position reads inside that copy and no g load needs a
+// bounds check.
+//
 // Tile: 32 co x 32 ci x all n * n taps per 256-thread workgroup; the taps are dealt over the
 // four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4) accumulators.
 // The reduction walks chunks of up to 16 consecutive positions of one input row; per chunk
-// the workgroup stages the 32 x CW inputs and, zero-framed so that every tap reads inside the
-// image, the n rows x (2 CW + n - 2) columns of g the chunk's taps touch for its 32 output
-// channels, fetched into registers while the previous chunk is multiplied.  The position
-// range is split over workgroups; the partial sums are added by the
-// forward path's reduction pass (fixed order).
+// the workgroup stages the 32 x cw inputs and the n rows x (2 cw + n - 2) columns of g the
+// chunk's taps touch for its 32 output channels.  Staging is branch-free (every lane has a fixed
+// list of elements: offset from the chunk's base address and LDS cell) and runs two chunks ahead
+// through registers into the LDS stage that is not being multiplied; one barrier per chunk.
+// The position range is split over workgroups; the partial sums are added by the forward path's
+// reduction pass (fixed order).
 namespace {
 
 constexpr int W_T = 32;          // output channels = input channels per workgroup
 constexpr int W_THREADS = 256;
 constexpr int W_CW = 16;         // positions per chunk at most
-constexpr int W_PE = 26;         // elements a lane stages per chunk at most
 
 struct BwdWParams {
     int B, Cin, Cout, N, M, n;
+    int Mf, Mfs;           // framed copy of g: rows M + 2 (n - 1), elements between its rows (>= Mf)
     int cw;                // positions per chunk (even), column chunks per row
     int ccs;
     int is, gl, gs;        // LDS: floats per staged input channel, columns and floats per staged g channel
@@ -321,16 +326,20 @@ struct BwdWParams {
     size_t out_elems;
 };
 
-template <int n>
+// KS: half the positions per chunk (an MFMA takes two); all chunk geometry is a constant expression.
+template <int n, int KS>
 __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const float *__restrict__ in,
-                                                                         const float *__restrict__ g,
+                                                                         const float *__restrict__ gf,
                                                                          float *__restrict__ dst, BwdWParams p)
 {
     constexpr int NN = n * n;
     constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
+    constexpr int CW = 2 * KS;                                   // positions per chunk
+    constexpr int IS = CW + 1;                                   // odd strides: lanes of different channels hit different banks
+    constexpr int GL = 2 * CW + n - 2;
+    constexpr int GS = n * GL + ((n * GL) % 2 == 0 ? 1 : 0);
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    float *Is = lds;                                             // [W_T][is]
-    float *Gs = lds + W_T * p.is;                                // [W_T][n][gl] (channel stride gs)
+    constexpr int stage = W_T * IS + W_T * GS;                   // floats per stage: [W_T][IS] then [W_T][n][GL]
 
     unsigned id = blockIdx.x;
     const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
@@ -343,34 +352,33 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kk = lane >> 5;
 
-    // ---- staging plan: element e of a chunk, the same for every chunk --------------------------
-    // e < W_T * cw: input (ci, cc).  Then g: (co, lr, lc) with row y = 2a - (n - 1) + lr and column
-    // x = 2 c0 - (n - 1) + lc.
-    const int n_in = W_T * p.cw, n_all = n_in + W_T * n * p.gl;
-    int e_lds[W_PE], e_y[W_PE], e_x[W_PE];         // LDS float index; row / column offset; e_y = -1: input element
-    unsigned e_ch[W_PE];                           // channel's element offset in its tensor
+    // ---- staging plan, the same for every chunk ----------------------------------------------------
+    // Input element (ci, cc): offset ci * N * N + cc from the chunk's first input position; it is
+    // dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc): row 2a + lr and
+    // column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel past the tensor,
+    // repeats channel 0: what it stages is read by no stored output.
+    constexpr int n_in = W_T * CW, n_g = W_T * n * GL;
+    constexpr int NI = (n_in + W_THREADS - 1) / W_THREADS, NG = (n_g + W_THREADS - 1) / W_THREADS;
+    unsigned i_off[NI], g_off[NG];
+    int i_lds[NI], i_cc[NI], g_lds[NG];
 #pragma unroll
-    for (int k = 0; k < W_PE; ++k) {
+    for (int k = 0; k < NI; ++k) {
         const int e = tid + k * W_THREADS;
-        if (e < n_in) {
-            const int ci = e / p.cw, cc = e - ci * p.cw;
-            e_lds[k] = ci * p.is + cc;
-            e_y[k] = -1;
-            e_x[k] = cc;
-            e_ch[k] = ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0xffffffffu;
-        } else if (e < n_all) {
-            const int r = e - n_in;
-            const int co = r / (n * p.gl);
-            const int rem = r - co * (n * p.gl);
-            const int lr = rem / p.gl, lc = rem - lr * p.gl;
-            e_lds[k] = W_T * p.is + co * p.gs + lr * p.gl + lc;
-            e_y[k] = lr;
-            e_x[k] = lc;
-            e_ch[k] = co0 + co < p.Cout ? (unsigned)(co0 + co) * p.M * p.M : 0xffffffffu;
-        } else {
-            e_lds[k] = -1;
-            e_y[k] = 0; e_x[k] = 0; e_ch[k] = 0xffffffffu;
-        }
+        const int ci = e / CW, cc = e - ci * CW;
+        const bool ok = e < n_in;
+        i_off[k] = (ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? cc : 0);
+        i_cc[k] = ok ? cc : (1 << 20);
+        i_lds[k] = ok ? ci * IS + cc : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+        const int e = tid + k * W_THREADS;
+        const int co = e / (n * GL);
+        const int rem = e - co * (n * GL);
+        const int lr = rem / GL, lc = rem - lr * GL;
+        const bool ok = e < n_g;
+        g_off[k] = ok ? (co0 + co < p.Cout ? (unsigned)(co0 + co) * p.Mf * p.Mfs : 0u) + (unsigned)lr * p.Mfs + lc : 0u;
+        g_lds[k] = ok ? W_T * IS + co * GS + lr * GL + lc : -1;
     }
 
     floatx16 acc[TW];
@@ -381,52 +389,78 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
-    const int ibase = l32 * p.is + kk;                           // B operand: input channel l32, position 2 k2 + kk
-    const int gbase = W_T * p.is + l32 * p.gs + 2 * kk + (n - 1);   // A operand: output channel l32, tap (0, 0)
+    const int ibase = l32 * IS + kk;                             // B operand: input channel l32, position 2 k + kk
+    // A operand: output channel l32, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
+    int abase[TW];
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
+        const int u = uv / n, v = uv - u * n;
+        abase[t] = W_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
+    }
 
-    // The elements of chunk ch + 1 are fetched into registers while chunk ch is multiplied.
-    float e_reg[W_PE];
-    auto fetch = [&](int ch) {
+    float i_reg[NI], g_reg[NG];
+    // Registers <- chunk ch (a chunk past the end repeats the last one: valid addresses, unused data).
+    auto fetch = [&](int ch_any) {
+        const int ch = min(ch_any, p.nchunks - 1);
         const int row = ch / p.ccs, cchunk = ch - row * p.ccs;
         const int b = row / p.N, a = row - b * p.N;
-        const int c0 = cchunk * p.cw;
-        const unsigned in_row = ((unsigned)b * p.Cin * p.N + a) * p.N + c0;       // + channel * N * N + cc
-        const int y0 = 2 * a - (n - 1), x0 = 2 * c0 - (n - 1);
-        const unsigned g_img = (unsigned)b * p.Cout * p.M * p.M;
+        const int c0 = cchunk * CW;
+        const float *ip = in + (((size_t)b * p.Cin * p.N + a) * p.N + c0);
+        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * a) * p.Mfs + 2 * c0);
 #pragma unroll
-        for (int k = 0; k < W_PE; ++k) {
-            float v = 0.0f;
-            if (e_lds[k] >= 0 && e_ch[k] != 0xffffffffu) {
-                if (e_y[k] < 0) {
-                    if (c0 + e_x[k] < p.N) v = in[in_row + e_ch[k] + e_x[k]];
-                } else {
-                    const int y = y0 + e_y[k], x = x0 + e_x[k];
-                    if (y >= 0 && y < p.M && x >= 0 && x < p.M) v = g[g_img + e_ch[k] + (unsigned)y * p.M + x];
-                }
-            }
-            e_reg[k] = v;
+        for (int k = 0; k < NI; ++k) {
+            const bool inside = c0 + i_cc[k] < p.N;
+            const float v = ip[inside ? i_off[k] : 0u];
+            i_reg[k] = inside ? v : 0.0f;
         }
+#pragma unroll
+        for (int k = 0; k < NG; ++k) g_reg[k] = gp[g_off[k]];
     };
-    if (chunk_begin < chunk_end) fetch(chunk_begin);
+    auto stage_write = [&](int at) {
+#pragma unroll
+        for (int k = 0; k < NI; ++k)
+            if (i_lds[k] >= 0) lds[at + i_lds[k]] = i_reg[k];
+#pragma unroll
+        for (int k = 0; k < NG; ++k)
+            if (g_lds[k] >= 0) lds[at + g_lds[k]] = g_reg[k];
+    };
+
+    if (chunk_begin < chunk_end) {
+        fetch(chunk_begin);
+        stage_write(0);
+        fetch(chunk_begin + 1);
+    }
+    __syncthreads();
+    int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
-        __syncthreads();                                         // every wave is done with the previous chunk
+        const float *S = lds + cur;
+        float bf[KS], af[2][KS];                   // the A values of tap t + 1 are read before tap t is multiplied
 #pragma unroll
-        for (int k = 0; k < W_PE; ++k)
-            if (e_lds[k] >= 0) lds[e_lds[k]] = e_reg[k];
-        __syncthreads();
-        if (ch + 1 < chunk_end) fetch(ch + 1);
-        for (int k2 = 0; k2 < p.cw; k2 += 2) {
-            const float bf = Is[ibase + k2];
+        for (int k = 0; k < KS; ++k) bf[k] = S[ibase + 2 * k];
 #pragma unroll
-            for (int t = 0; t < TW; ++t) {
-                const int uv = wave + 4 * t;                     // wave-uniform
-                if (uv < NN) {
-                    const int u = uv / n, v = uv - u * n;
-                    const float af = Gs[gbase - W_T * p.is + (n - 1 - u) * p.gl + 2 * k2 - v];
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc[t], 0, 0, 0);
-                }
+        for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 4 * k];
+#pragma unroll
+        for (int t = 0; t < TW; ++t) {
+            if (t + 1 < TW) {
+#pragma unroll
+                for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 4 * k];
             }
+            if (t == (TW - 1) / 2) {
+                // chunk ch + 1 goes to the other stage (last read before the previous barrier) and
+                // its registers are refilled with chunk ch + 2
+                stage_write(stage - cur);
+                fetch(ch + 2);
+            }
+            // every wave has taps 0 .. TW - 2; the last one only while wave + 4 (TW - 1) < NN
+            if (t == TW - 1 && wave + 4 * t >= NN) break;
+#pragma unroll
+            for (int k = 0; k < KS; ++k)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[k], acc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        __syncthreads();
+        cur = stage - cur;
     }
 
     // acc[t][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + l32, tap wave + 4 t
@@ -448,10 +482,14 @@ BwdWParams plan_w(const Shape &s)
 {
     BwdWParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.n = s.n;
-    const int npad = (s.N + 1) & ~1;
-    p.cw = npad < W_CW ? npad : W_CW;
-    p.ccs = (s.N + p.cw - 1) / p.cw;
-    p.is = p.cw + 1;                                   // odd strides: lanes of different channels hit different banks
+    p.Mf = s.M + 2 * (s.n - 1);
+    // Equal chunks of an even number of positions, 16 at most: a row of 18 is cut 10 + 8, not 16 + 2.
+    p.ccs = (s.N + W_CW - 1) / W_CW;
+    p.cw = (((s.N + p.ccs - 1) / p.ccs) + 1) & ~1;
+    // The last chunk of a row may run past it by ccs * cw - N positions: their input values are
+    // dropped, and the g columns they would meet are zeros of the framed copy's wider rows.
+    p.Mfs = p.Mf + 2 * (p.ccs * p.cw - s.N);
+    p.is = p.cw + 1;                                   // (the kernel derives the same LDS geometry from cw)
     p.gl = 2 * p.cw + s.n - 2;
     p.gs = s.n * p.gl + ((s.n * p.gl) % 2 == 0 ? 1 : 0);
     p.nchunks = s.B * s.N * p.ccs;
@@ -469,14 +507,31 @@ BwdWParams plan_w(const Shape &s)
     return p;
 }
 
-size_t lds_bytes_w(const BwdWParams &p) { return ((size_t)W_T * p.is + (size_t)W_T * p.gs) * sizeof(float); }
+size_t lds_bytes_w(const BwdWParams &p) { return 2 * ((size_t)W_T * p.is + (size_t)W_T * p.gs) * sizeof(float); }
+
+template <int n, int KS>
+hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
+    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS>), dim3(blocks), dim3(W_THREADS), lds_bytes_w(p), stream, in, g,
+                       dst, p);
+    return hipGetLastError();
+}
 
 template <int n>
 hipError_t launch_w(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
-    hipLaunchKernelGGL(backward_weight_f32_kernel<n>, dim3(blocks), dim3(W_THREADS), lds_bytes_w(p), stream, in, g, dst, p);
-    return hipGetLastError();
+    switch (p.cw / 2) {
+        case 1: return launch_w_ks<n, 1>(in, g, dst, p, stream);
+        case 2: return launch_w_ks<n, 2>(in, g, dst, p, stream);
+        case 3: return launch_w_ks<n, 3>(in, g, dst, p, stream);
+        case 4: return launch_w_ks<n, 4>(in, g, dst, p, stream);
+        case 5: return launch_w_ks<n, 5>(in, g, dst, p, stream);
+        case 6: return launch_w_ks<n, 6>(in, g, dst, p, stream);
+        case 7: return launch_w_ks<n, 7>(in, g, dst, p, stream);
+        case 8: return launch_w_ks<n, 8>(in, g, dst, p, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
@@ -488,10 +543,16 @@ bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt)
     if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
     if (s.Cin < 8 || s.Cout < 8) return false;
     const BwdWParams p = plan_w(s);
-    if (W_T * p.cw + W_T * s.n * p.gl > W_THREADS * W_PE) return false;
     if (lds_bytes_w(p) > 64 * 1024) return false;
     if ((size_t)p.tiles_ci * p.tiles_co * p.splits >= 0x7fffffffu) return false;
     return true;
+}
+
+void backward_weight_igemm_g_copy(const Shape &s, int *frame, int *row_stride)
+{
+    const BwdWParams p = plan_w(s);
+    *frame = s.n - 1;
+    *row_stride = p.Mfs;
 }
 
 size_t backward_weight_igemm_workspace_bytes(const Shape &s)
@@ -500,9 +561,10 @@ size_t backward_weight_igemm_workspace_bytes(const Shape &s)
     return p.splits > 1 ? (((size_t)p.splits * p.out_elems * sizeof(float) + 255) & ~(size_t)255) : 0;
 }
 
-hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *dw, void *ws, const Shape &s,
+hipError_t launch_backward_weight_igemm(const float *in, const float *g_framed, float *dw, void *ws, const Shape &s,
                                         hipStream_t stream)
 {
+    const float *g = g_framed;
     if (!backward_weight_igemm_supported(s, KST_F32)) return hipErrorInvalidValue;
     const BwdWParams p = plan_w(s);
     float *dst = p.splits > 1 ? (float *)ws : dw;

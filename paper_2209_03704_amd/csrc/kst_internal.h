@@ -101,6 +101,9 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
                                        hipStream_t stream);
 bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt);
 size_t backward_weight_igemm_workspace_bytes(const Shape &s);
+// The copy of g that launch_backward_weight_igemm reads: g (edge s.M) framed by *frame zeros on
+// every side, its rows *row_stride elements apart (zeros past the frame).
+void backward_weight_igemm_g_copy(const Shape &s, int *frame, int *row_stride);
 hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *dw, void *ws, const Shape &s,
                                         hipStream_t stream);
 // Direct path: any shape.
