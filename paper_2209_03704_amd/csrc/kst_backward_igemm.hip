@@ -191,6 +191,189 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_f32_kernel(const flo
         }
 }
 
+// The same tile with 16-byte staging, for layers whose rows of g and runs of w are whole float4
+// (M, Cin and Cout multiples of 4).  The chunk's weights are copied as they lie in memory
+// ([co][ci][u v], one run of 128 n*n floats per output channel) and read back at stride n*n
+// (for n = 4 the four float4 of a channel are rotated by ci / 4 so that the 32 channels of an
+// MFMA operand do not fall into four banks); the image of g has a frame of 4 columns on the left
+// (>= n - 1) and rows of whole float4, so a float4 of g goes to LDS as it is.  All loads are
+// free of branches: a lane's list of float4 is fixed, a float4 outside the tensors re-reads
+// element 0 and is written as zeros (g) or feeds channels that are never stored (w).
+constexpr int V_XF = 4;          // columns of zeros left of the image of g
+
+template <int n>
+__global__ void __launch_bounds__(B_THREADS) backward_input_vec_kernel(const float *__restrict__ g,
+                                                                        const float *__restrict__ w,
+                                                                        float *__restrict__ dst, BwdParams p)
+{
+    constexpr int NN = n * n;
+    constexpr int WSZ = B_TCI * NN;                               // floats per staged output channel
+    constexpr int WV = B_KC * WSZ / 4;                            // weight float4 per chunk
+    constexpr int NWV = (WV + B_THREADS - 1) / B_THREADS;         // ... per lane
+    constexpr int NXV = B_PX / 4;                                 // g float4 per lane per chunk at most
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int xplane = p.lrows * p.Wl;                            // floats per staged channel (Wl a multiple of 4)
+    float *Xs = lds;                                              // [B_KC][lrows][Wl]
+    float *Ws = lds + B_KC * xplane;                              // [B_KC][B_TCI * NN]
+
+    unsigned id = blockIdx.x;
+    const int tile_m = (int)(id % (unsigned)p.tiles_m);
+    id /= (unsigned)p.tiles_m;
+    const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
+    const int split = (int)(id / (unsigned)p.tiles_ci);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kk = lane >> 5;
+    const int wci = wave & 1, wpos = wave >> 1;
+
+    const int NNp = p.N * p.N;
+    const int m0 = tile_m * B_TM;
+    const int ci0 = tile_ci * B_TCI;
+    const int b0 = m0 / NNp;
+    const int a0 = (m0 - b0 * NNp) / p.N;
+    const int VR0 = b0 * p.Hv + 2 * a0;
+
+    int m = m0 + wpos * 32 + l32;
+    const bool m_valid = m < p.Mtot;
+    if (!m_valid) m = p.Mtot - 1;
+    const int mb = m / NNp;
+    const int mrem = m - mb * NNp;
+    const int ma = mrem / p.N, mc = mrem - ma * p.N;
+    // LDS offset of this lane's tap (u, v) = (0, 0): row 2a + n - 1, column 2c + V_XF
+    const int xbase = (mb * p.Hv + 2 * ma + (n - 1) - VR0) * p.Wl + 2 * mc + V_XF + kk * xplane;
+    // weights of this lane's two channels (h = 0, 1): float offset of element (ci, u v = 0) of
+    // output channel kk of a channel pair; for n = 4, one offset per float4 of the channel
+    int wrow[2][n == 4 ? 4 : 1];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int ci = wci * 64 + h * 32 + l32;
+        if constexpr (n == 4) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wrow[h][q] = kk * WSZ + ci * NN + 4 * ((q + (ci >> 2)) & 3);
+        } else {
+            wrow[h][0] = kk * WSZ + ci * NN;
+        }
+    }
+
+    const int co_begin = split * p.co_per_split;
+    const int co_end = min(p.Cout, co_begin + p.co_per_split);
+
+    // ---- staging plan -------------------------------------------------------------------------
+    unsigned w_off[NWV], w_step[NWV];
+    int w_lds[NWV];                                 // float index in Ws, or -1
+    const int w_valid4 = (min(B_TCI, p.Cin - ci0) * NN) / 4;     // float4 of one output channel's run inside the tensor
+#pragma unroll
+    for (int k = 0; k < NWV; ++k) {
+        const int e4 = tid + k * B_THREADS;
+        const int c = e4 / (WSZ / 4), r = e4 - c * (WSZ / 4);
+        const bool in_list = e4 < WV;
+        const bool ok = in_list && r < w_valid4;
+        w_off[k] = ok ? (((unsigned)(co_begin + c) * p.Cin + ci0) * NN + 4 * r) : 0u;
+        w_step[k] = ok ? (unsigned)B_KC * p.Cin * NN : 0u;
+        int cell = 4 * r;
+        if constexpr (n == 4) {
+            const int ci = r >> 2, q = r & 3;
+            cell = ci * NN + 4 * ((q + (ci >> 2)) & 3);
+        }
+        w_lds[k] = in_list ? c * WSZ + cell : -1;
+    }
+    unsigned x_off[NXV];
+    int x_ok[NXV];                                  // 1: inside g, 0: a zero cell of the image, -1: past the image
+    const int wl4 = p.Wl >> 2, xp4 = xplane >> 2;
+#pragma unroll
+    for (int k = 0; k < NXV; ++k) {
+        const int e4 = tid + k * B_THREADS;
+        const int c = e4 / xp4;
+        const int rem = e4 - c * xp4;
+        const int lr = rem / wl4, x4 = rem - lr * wl4;
+        const int VR = VR0 + lr;
+        const int bb = VR / p.Hv;
+        const int y = VR - bb * p.Hv - (n - 1), x = 4 * x4 - V_XF;
+        const bool in_list = e4 < B_KC * xp4;
+        const bool ok = in_list && bb < p.B && y >= 0 && y < p.M && x >= 0 && x < p.M;
+        x_off[k] = ok ? ((((unsigned)bb * p.Cout + co_begin + c) * p.M + y) * p.M + x) : 0u;
+        x_ok[k] = ok ? 1 : in_list ? 0 : -1;
+    }
+    const unsigned x_inc = (unsigned)B_KC * p.M * p.M;
+
+    floatx16 acc[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[h][v] = 0.0f;
+
+    float4 w_reg[NWV], x_reg[NXV];
+    // Registers <- the chunk at output channel co_first (whole chunks: Cout is a multiple of 4; a
+    // chunk past the end re-reads element 0 and is never multiplied); offsets move on afterwards.
+    auto load_chunk = [&](int co_first) {
+        const bool live = co_first < co_end;                      // wave-uniform
+#pragma unroll
+        for (int k = 0; k < NWV; ++k) {
+            w_reg[k] = *reinterpret_cast<const float4 *>(w + (live ? w_off[k] : 0u));
+            w_off[k] += w_step[k];
+        }
+#pragma unroll
+        for (int k = 0; k < NXV; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(g + (live ? x_off[k] : 0u));
+            x_reg[k] = x_ok[k] == 1 ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+            x_off[k] += x_ok[k] == 1 ? x_inc : 0u;
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int k = 0; k < NWV; ++k) {
+            const float4 v = make_float4(w_reg[k].x, w_reg[k].y, w_reg[k].z, w_reg[k].w);
+            if (w_lds[k] >= 0) *reinterpret_cast<float4 *>(Ws + w_lds[k]) = v;
+        }
+#pragma unroll
+        for (int k = 0; k < NXV; ++k) {
+            const float4 v = make_float4(x_reg[k].x, x_reg[k].y, x_reg[k].z, x_reg[k].w);
+            if (x_ok[k] >= 0) reinterpret_cast<float4 *>(Xs)[tid + k * B_THREADS] = v;
+        }
+    };
+
+    load_chunk(co_begin);
+    store_chunk();
+    __syncthreads();
+
+    for (int co0 = co_begin; co0 < co_end; co0 += B_KC) {
+        const int cn = co0 + B_KC;
+        load_chunk(cn);
+#pragma unroll
+        for (int c2 = 0; c2 < B_KC; c2 += 2) {
+#pragma unroll
+            for (int u = 0; u < n; ++u)
+#pragma unroll
+                for (int v = 0; v < n; ++v) {
+                    const float xf = Xs[c2 * xplane + xbase - u * p.Wl - v];
+                    const int uv = u * n + v;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        float wf;
+                        if constexpr (n == 4) wf = Ws[c2 * WSZ + wrow[h][uv >> 2] + (uv & 3)];
+                        else wf = Ws[c2 * WSZ + wrow[h][0] + uv];
+                        acc[h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, xf, acc[h], 0, 0, 0);
+                    }
+                }
+        }
+        if (cn >= co_end) break;
+        __syncthreads();                                         // every wave is done reading this chunk
+        store_chunk();
+        __syncthreads();
+    }
+
+    if (!m_valid) return;
+    float *o = dst + (size_t)split * p.out_elems;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int ci = ci0 + wci * 64 + h * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            if (ci < p.Cin) o[(((size_t)mb * p.Cin + ci) * p.N + ma) * p.N + mc] = acc[h][v];
+        }
+}
+
 BwdParams plan(const Shape &s)
 {
     BwdParams p;
@@ -226,6 +409,29 @@ BwdParams plan(const Shape &s)
     return p;
 }
 
+// Geometry of the 16-byte variant: the image of g has V_XF columns of frame on the left and rows
+// of whole float4 (largest column read: 2 (N - 1) + V_XF).
+BwdParams plan_vec(const Shape &s)
+{
+    BwdParams p = plan(s);
+    p.Wl = (2 * s.N + V_XF - 1 + 3) & ~3;
+    return p;
+}
+
+size_t lds_bytes_vec(const BwdParams &p)
+{
+    return ((size_t)B_KC * p.lrows * p.Wl + (size_t)B_KC * B_TCI * p.n * p.n) * sizeof(float);
+}
+
+bool vec_applies(const Shape &s)
+{
+    if ((s.M & 3) || (s.Cin & 3) || (s.Cout & 3)) return false;
+    const BwdParams p = plan_vec(s);
+    if ((size_t)B_KC * p.lrows * p.Wl / 4 > (size_t)B_THREADS * (B_PX / 4)) return false;
+    if (lds_bytes_vec(p) > 160 * 1024) return false;
+    return (size_t)s.B * p.Hv < 0x7fffffffu / (size_t)p.Wl;
+}
+
 size_t lds_bytes(const BwdParams &p)
 {
     return ((size_t)B_KC * p.lrows * p.Wl + (size_t)B_KC * p.n * p.n * B_WST) * sizeof(float);
@@ -242,6 +448,20 @@ hipError_t launch_n(const float *g, const float *w, float *dst, const BwdParams 
     }
     const unsigned blocks = (unsigned)p.tiles_m * p.tiles_ci * p.splits;
     hipLaunchKernelGGL(backward_input_f32_kernel<n>, dim3(blocks), dim3(B_THREADS), lds, stream, g, w, dst, p);
+    return hipGetLastError();
+}
+
+template <int n>
+hipError_t launch_vec_n(const float *g, const float *w, float *dst, const BwdParams &p, hipStream_t stream)
+{
+    const size_t lds = lds_bytes_vec(p);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_input_vec_kernel<n>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const unsigned blocks = (unsigned)p.tiles_m * p.tiles_ci * p.splits;
+    hipLaunchKernelGGL(backward_input_vec_kernel<n>, dim3(blocks), dim3(B_THREADS), lds, stream, g, w, dst, p);
     return hipGetLastError();
 }
 
@@ -271,16 +491,28 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
                                        hipStream_t stream)
 {
     if (!backward_input_igemm_supported(s, KST_F32)) return hipErrorInvalidValue;
-    const BwdParams p = plan(s);
+    const bool vec = vec_applies(s);
+    const BwdParams p = vec ? plan_vec(s) : plan(s);
     float *dst = p.splits > 1 ? (float *)ws : din;
     hipError_t e;
-    switch (s.n) {
-        case 1: e = launch_n<1>(g, w, dst, p, stream); break;
-        case 2: e = launch_n<2>(g, w, dst, p, stream); break;
-        case 3: e = launch_n<3>(g, w, dst, p, stream); break;
-        case 4: e = launch_n<4>(g, w, dst, p, stream); break;
-        case 5: e = launch_n<5>(g, w, dst, p, stream); break;
-        default: return hipErrorInvalidValue;
+    if (vec) {
+        switch (s.n) {
+            case 1: e = launch_vec_n<1>(g, w, dst, p, stream); break;
+            case 2: e = launch_vec_n<2>(g, w, dst, p, stream); break;
+            case 3: e = launch_vec_n<3>(g, w, dst, p, stream); break;
+            case 4: e = launch_vec_n<4>(g, w, dst, p, stream); break;
+            case 5: e = launch_vec_n<5>(g, w, dst, p, stream); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (s.n) {
+            case 1: e = launch_n<1>(g, w, dst, p, stream); break;
+            case 2: e = launch_n<2>(g, w, dst, p, stream); break;
+            case 3: e = launch_n<3>(g, w, dst, p, stream); break;
+            case 4: e = launch_n<4>(g, w, dst, p, stream); break;
+            case 5: e = launch_n<5>(g, w, dst, p, stream); break;
+            default: return hipErrorInvalidValue;
+        }
     }
     if (e != hipSuccess) return e;
     if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, din, p.out_elems, p.splits, stream);
