@@ -47,7 +47,8 @@ struct WideGeom {
     static constexpr int M = 2 * N - n;
     static constexpr int E = (M + 1) / 2;
     static constexpr int CB = (E + 31) / 32;             // 32-column position blocks per quad row
-    static constexpr int QW = 4 / CB;                    // quad rows per wave
+    static constexpr int QH = 1;                         // workgroups per CU
+    static constexpr int QW = 4 / CB / QH;               // quad rows per wave
     static constexpr int TI = 2 * QW;                    // quad rows per tile
     static constexpr int XR = QW + fl;                   // input rows a wave reads
     static constexpr int STRIPS = (E + TI - 1) / TI;
@@ -77,7 +78,7 @@ struct WideGeom {
     // The image starts 64 bytes in; the last channel's sweeps may read past its run.
     static constexpr int EPI_B = (16 + 31 * ESTRIDE + 4 * 64 * ITS) * 4;
     static constexpr int LDS_B = STAGES * STAGE_B > EPI_B ? STAGES * STAGE_B : EPI_B;
-    static_assert(LDS_B <= 160 * 1024, "one workgroup per CU");
+    static_assert(LDS_B <= 160 * 1024 / QH, "workgroups per CU");
     static_assert(STAGES * KMAX < 64, "the vector-memory counter holds the whole ring");
 };
 
@@ -128,7 +129,8 @@ __device__ __forceinline__ void wait_loads_and_meet(int chunks)
 template <int n>
 struct TapOrder {
     int T[n * n], cls[n * n], dy[n * n], dx[n * n], n0;
-    constexpr TapOrder() : T(), cls(), dy(), dx(), n0(0)
+    bool first[n * n];            // no earlier tap in this order belongs to the same class
+    constexpr TapOrder() : T(), cls(), dy(), dx(), n0(0), first()
     {
         int m = 0;
         for (int want = 0; want < 2; ++want) {
@@ -145,11 +147,16 @@ struct TapOrder {
             }
             if (want == 0) n0 = m;
         }
+        for (int a = 0; a < n * n; ++a) {
+            first[a] = true;
+            for (int b = 0; b < a; ++b)
+                if (cls[b] == cls[a]) first[a] = false;
+        }
     }
 };
 
 template <int n, int N>
-__global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uint16_t *__restrict__ in,
+__global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wide_kernel(const uint16_t *__restrict__ in,
                                                                       const uint16_t *__restrict__ w_seg,
                                                                       float *__restrict__ out, WideParams p)
 {
@@ -293,15 +300,10 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
             for (int m = G::NN - LATE; m < G::NN; ++m) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w[m]) :: "memory");
         };
 
+        // The accumulators are not cleared: in a tile's first chunk the first tap of every class
+        // multiplies into zeros (the MFMA's addend is the constant 0).
         floatx16 acc[G::QW][4][G::CB];
-#pragma unroll
-        for (int q = 0; q < G::QW; ++q)
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int cb = 0; cb < G::CB; ++cb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[q][c][cb][v] = 0.0f;
+        constexpr floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
         // Chunk c, multiplied out of the stage at LDS address `cur`, while chunk c + 1 is read
         // from the stage at `nxt`.  The wave is alone on its SIMD and issues in order, so
@@ -318,9 +320,10 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
         //     slot's MFMA and the load issued behind it;
         //   at the first MFMA of each tap: the weight fragment of the tap before, for chunk c + 1.
         // more: a chunk follows; issue: chunk c + STAGES exists.
-        auto chunk = [&](int c, unsigned cur, unsigned nxt, auto more_tag, auto issue_tag) {
+        auto chunk = [&](int c, unsigned cur, unsigned nxt, auto more_tag, auto issue_tag, auto first_tag) {
             constexpr bool more = decltype(more_tag)::value;
             constexpr bool issue = decltype(issue_tag)::value;
+            constexpr bool first_chunk = decltype(first_tag)::value;
             constexpr int TAP_MFMA = G::QW * G::CB;
             constexpr int S1 = (G::NN - ord.n0) * TAP_MFMA;
             constexpr int NT = G::XR * G::CB;                  // window reads (pairs)
@@ -364,7 +367,7 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
                     for (int cb = 0; cb < G::CB; ++cb)
                         acc[q][ord.cls[m]][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                             __builtin_bit_cast(bf16x8, w[m]), __builtin_bit_cast(bf16x8, x[q + ord.dy[m]][cb]),
-                            acc[q][ord.cls[m]][cb], 0, 0, 0);
+                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb], 0, 0, 0);
 #pragma unroll
                 for (int r = m * RPT; r < (m + 1) * RPT && r < G::XR; ++r) shift_row(r);
 #pragma unroll
@@ -399,7 +402,7 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
                             if (k1 > k0) { aim_one(k0, cur); __builtin_amdgcn_sched_barrier(0); }
                         acc[q][ord.cls[m]][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                             __builtin_bit_cast(bf16x8, w[m]), __builtin_bit_cast(bf16x8, xs[q + ord.dy[m]][cb]),
-                            acc[q][ord.cls[m]][cb], 0, 0, 0);
+                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb], 0, 0, 0);
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (more) {
                             if (q == 0 && cb == 0) read_w(nxt, m - 1);
@@ -449,20 +452,27 @@ __global__ void __launch_bounds__(W_THREADS, 1) igemm_bf16_wide_kernel(const uin
             constexpr unsigned RING_B = (unsigned)G::STAGES * G::STAGE_B;
             unsigned cur = lds_base;                               // stage of chunk c
             auto next_of = [&](unsigned a) { return a + G::STAGE_B == lds_base + RING_B ? lds_base : a + G::STAGE_B; };
-            int c = 0;
+            // (the launcher takes layers with more than STAGES chunks only: the first chunk always
+            // has a successor and a chunk to issue loads for)
+            {
+                const unsigned nxt = next_of(cur);
+                chunk(0, cur, nxt, std::true_type{}, std::true_type{}, std::true_type{});
+                cur = nxt;
+            }
+            int c = 1;
 #pragma unroll 1
             for (; c + G::STAGES < nchunks; ++c) {
                 const unsigned nxt = next_of(cur);
-                chunk(c, cur, nxt, std::true_type{}, std::true_type{});
+                chunk(c, cur, nxt, std::true_type{}, std::true_type{}, std::false_type{});
                 cur = nxt;
             }
 #pragma unroll 1
             for (; c + 1 < nchunks; ++c) {
                 const unsigned nxt = next_of(cur);
-                chunk(c, cur, nxt, std::true_type{}, std::false_type{});
+                chunk(c, cur, nxt, std::true_type{}, std::false_type{}, std::false_type{});
                 cur = nxt;
             }
-            chunk(c, cur, cur, std::false_type{}, std::false_type{});
+            chunk(c, cur, cur, std::false_type{}, std::false_type{}, std::false_type{});
         }
 
         // ---- epilogue ----------------------------------------------------------------------------
@@ -569,7 +579,7 @@ hipError_t launch_wide(const uint16_t *in, const uint16_t *w_seg, float *out, co
     int dev = 0, cus = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    const unsigned blocks = (unsigned)min(p.ntiles, cus > 0 ? cus : 256);
+    const unsigned blocks = (unsigned)min(p.ntiles, (cus > 0 ? cus : 256) * G::QH);
     hipLaunchKernelGGL((igemm_bf16_wide_kernel<n, N>), dim3(blocks), dim3(W_THREADS), G::LDS_B, stream, in, w_seg, out, p);
     return hipGetLastError();
 }
@@ -596,6 +606,7 @@ bool igemm_bf16_wide_supported(const Shape &s)
     if (s.n != 2 && s.n != 3) return false;
     if (s.N != 32 && s.N != 64) return false;
     if (s.Cin % W_KC != 0 || s.Cout % W_TCO != 0) return false;
+    if (s.Cin / W_KC <= 3) return false;            // more chunks than ring stages (3 for every geometry)
     const size_t tiles = (size_t)s.B * (s.Cout / W_TCO) * strips_of(s);
     return tiles >= 224 && tiles < 0x7fffffffu;
 }
