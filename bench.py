@@ -82,6 +82,22 @@ def time_launches(torch, fn, iters, warmup):
     return start.elapsed_time(stop) / iters
 
 
+def launch_spread(torch, fn, iters, warmup):
+    """(median, min) milliseconds of single calls of fn(i): one event between every two calls on
+    the current stream (the events add a little to each call; the mean of time_launches has none)."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    ev[0].record()
+    for i in range(iters):
+        fn(i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+    return d[len(d) // 2], d[0]
+
+
 def roofline_for(layer, ms, metrics):
     """Roofline entry of the forward kernel of `layer` given its launch time."""
     direct = layer.Cout < 16 or layer.Cin < 8
@@ -246,6 +262,7 @@ def main():
             kst.kst_segregate_weights(r.w, r.w_seg)
             iters = max(5, min(args.steps, 30))
             ms = time_launches(torch, fwd_seg(r), iters, 3)
+            med_ms, min_ms = launch_spread(torch, fwd_seg(r), 50, 5)
             seg_ms = time_launches(torch, lambda i: kst.kst_segregate_weights(r.w, r.w_seg), 10, 2)
             U = torch.empty((layer.B, layer.Cin, 2 * layer.N - 1, 2 * layer.N - 1), dtype=r.w.dtype, device="cuda")
             zi_ms = time_launches(
@@ -259,6 +276,8 @@ def main():
                 "shape": {"B": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n,
                           "dtype": layer.dtype},
                 "forward_us": round(ms * 1e3, 2),
+                "forward_us_median_of_50": round(med_ms * 1e3, 2),
+                "forward_us_min_of_50": round(min_ms * 1e3, 2),
                 "segregate_us": round(seg_ms * 1e3, 2),
                 "forward_unsegregated_w_us": round(unseg_ms * 1e3, 2),
                 "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
