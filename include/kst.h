@@ -153,12 +153,14 @@ kst_status kst_forward(const void *in, const void *w, void *out,
  * frame to the ORIGINAL input with the reduced factor floor(P / 2); for odd P the
  * four sub-kernels swap roles (K4, K3, K2, K1).  Here: the input is copied into
  * the workspace framed by ceil(P / 2) zeros and the unframed kernels run on the
- * copy; for odd P they run into a second workspace buffer one pixel wider on
+ * copy (the direct kernel for several input channels reads the frame as zeros
+ * without a copy); for odd P they run into a second workspace buffer one pixel wider on
  * every side, whose interior is then copied to `out` (one extra pass over the
  * output).  Layouts, dtypes, alignment, stream and error behaviour are those of
  * kst_forward_seg / kst_forward; `out` is [B][Cout][2N+2P-n][2N+2P-n] fp32.
- * kst_workspace_bytes_padded returns 0 for an illegal shape or unsupported path
- * (a legal call always needs a workspace when P > 0).
+ * kst_workspace_bytes_padded returns 0 for an illegal shape or unsupported path,
+ * and for layers whose kernel supplies the zero frame itself (the direct path
+ * with several input channels at an even P): then ws may be NULL.
  */
 int kst_out_size_padded(int N, int n, int P);
 size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path);
@@ -179,9 +181,11 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
  * [Cout][Cin][n][n]) and in are of type `dtype`.  din [B][Cin][N][N] and dw
  * [Cout][Cin][n][n] are fully overwritten.  ws / ws_bytes: scratch of at least
  * kst_backward_*_workspace_bytes(...), used for framed copies as in
- * kst_forward_seg_padded and, by the matrix-core input-gradient kernel (fp32
- * weights, n <= 5, at least 8 channels on either side), for the partial sums of
- * a split reduction; it may be 0 (then ws may be NULL).  The byte count depends
+ * kst_forward_seg_padded, for the zero-framed copy of g the matrix-core
+ * kernel-gradient kernel reads, and for the partial sums of split reductions
+ * (the matrix-core kernels: fp32 operands, n <= 5, at least 8 channels on either
+ * side; the other kernel-gradient kernels when they slice the positions); it
+ * may be 0 (then ws may be NULL).  The byte count depends
  * on the shape only, never on the pointers, as in
  * kst_forward_seg_padded.  Pointers, alignment, stream and statuses as above.
  */
