@@ -82,6 +82,18 @@ def time_launches(torch, fn, iters, warmup):
     return start.elapsed_time(stop) / iters
 
 
+def settle(torch, fn, seconds):
+    """Untimed launches for about `seconds`: the first tens of milliseconds of work after an idle
+    period run several per cent slower than the steady state, whatever the kernel."""
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(5):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def launch_spread(torch, fn, iters, warmup):
     """(median, min) milliseconds of single calls of fn(i): one event between every two calls on
     the current stream (the events add a little to each call; the mean of time_launches has none)."""
@@ -261,6 +273,7 @@ def main():
             r = Resident(layer, 3, torch, kst, wl)
             kst.kst_segregate_weights(r.w, r.w_seg)
             iters = max(5, min(args.steps, 30))
+            settle(torch, fwd_seg(r), 0.05)
             ms = time_launches(torch, fwd_seg(r), iters, 3)
             med_ms, min_ms = launch_spread(torch, fwd_seg(r), 50, 5)
             seg_ms = time_launches(torch, lambda i: kst.kst_segregate_weights(r.w, r.w_seg), 10, 2)

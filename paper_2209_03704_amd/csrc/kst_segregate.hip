@@ -38,6 +38,44 @@ __global__ void __launch_bounds__(256) segregate_kernel(const T *__restrict__ w,
     w_seg[e] = val;
 }
 
+// fp32 weights of many-channel layers: the permutation is a transpose (w has the output channel
+// slowest, the segregated layout has it fastest), done through LDS so that both sides are
+// coalesced.  A workgroup takes 64 output channels x a run of S_RUN consecutive floats of
+// w[co][.] (whole input channels' kernels are not required: a run element is decoded on its own),
+// reads each channel's run as it lies in memory and writes, for every run element, the 64
+// output channels side by side.
+constexpr int S_CO = 64;
+constexpr int S_RUN = 128;
+
+__global__ void __launch_bounds__(256) segregate_tiled_f32_kernel(const float *__restrict__ w, float *__restrict__ w_seg,
+                                                                  SegGeom g)
+{
+    __shared__ float tile[S_CO][S_RUN + 1];
+    const unsigned per_co = (unsigned)g.Cin * g.n * g.n;          // floats of one output channel in w
+    const unsigned runs = (per_co + S_RUN - 1) / S_RUN;
+    const unsigned run = blockIdx.x % runs, co0 = (blockIdx.x / runs) * S_CO;
+    const unsigned r0 = run * S_RUN;
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < S_CO * S_RUN; idx += 256) {
+        const unsigned co_l = idx / S_RUN, r = idx % S_RUN;
+        float v = 0.0f;
+        if (co0 + co_l < (unsigned)g.Cout && r0 + r < per_co) v = w[(size_t)(co0 + co_l) * per_co + r0 + r];
+        tile[co_l][r] = v;
+    }
+    __syncthreads();
+    const unsigned nn = (unsigned)g.n * g.n;
+    for (int idx = tid; idx < S_CO * S_RUN; idx += 256) {
+        const unsigned r = idx / S_CO, co_l = idx % S_CO;
+        const unsigned e = r0 + r;                                    // element (ci, u, v) of a channel's kernels
+        if (co0 + co_l >= (unsigned)g.Cout || e >= per_co) continue;
+        const unsigned ci = e / nn, uv = e - ci * nn;
+        const unsigned u = uv / g.n, v = uv - u * g.n;
+        const int p = (int)((u & 1u) * 2u + (v & 1u));
+        const unsigned t = (u >> 1) * g.Tb[p] + (v >> 1);
+        w_seg[g.off[p] + ((size_t)ci * g.T[p] + t) * g.Cout + co0 + co_l] = tile[co_l][r];
+    }
+}
+
 hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n, kst_dtype dt,
                             hipStream_t stream)
 {
@@ -54,6 +92,15 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
     }
     g.off[4] = (unsigned)seg_elems(Cin, Cout, n, dt);
     const unsigned blocks = (g.off[4] + 255u) / 256u;
+    if (dt == KST_F32 && Cout >= 32 && (size_t)Cin * n * n >= 64) {
+        const size_t runs = ((size_t)Cin * n * n + S_RUN - 1) / S_RUN;
+        const size_t tiles = runs * ((Cout + S_CO - 1) / S_CO);
+        if (tiles < 0x7fffffffu) {
+            hipLaunchKernelGGL(segregate_tiled_f32_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, (const float *)w,
+                               (float *)w_seg, g);
+            return hipGetLastError();
+        }
+    }
     if (dt == KST_BF16)
         hipLaunchKernelGGL(segregate_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
                            (const uint16_t *)w, (uint16_t *)w_seg, g);

@@ -87,7 +87,7 @@ def expected_segregation(w: torch.Tensor) -> torch.Tensor:
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("Cin,Cout,n", [(1, 1, 3), (3, 2, 5), (5, 7, 4), (16, 33, 1), (9, 4, 2), (13, 3, 7),
-                                          (40, 70, 6)])
+                                          (40, 70, 6), (100, 96, 5), (64, 128, 4), (33, 40, 3), (130, 32, 2)])
 def test_segregate_weights_is_the_documented_permutation(dtype, Cin, Cout, n):
     g = torch.Generator().manual_seed(Cin * 100 + Cout * 10 + n)
     w = torch.randn((Cout, Cin, n, n), generator=g)
