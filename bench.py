@@ -314,9 +314,10 @@ def main():
             w_seg = kst.kst_segregate_weights(w.cuda())
             need = kst.kst_workspace_bytes_padded(layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, kst.KST_F32)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
-            ms = time_launches(
-                torch, lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P,
-                                                            out=outs[i % 3], ws=ws), 30, 5)
+            fwd_p = lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P,
+                                                         out=outs[i % 3], ws=ws)
+            settle(torch, fwd_p, 0.03)
+            ms = time_launches(torch, fwd_p, 30, 5)
             # gradients of the same layer: g = d(loss)/d(out)
             g = torch.randn(layer.out_shape, dtype=torch.float32, device="cuda")
             wd = w.cuda()
@@ -327,8 +328,12 @@ def main():
                 layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
             ws_bw = torch.empty(max(kst.kst_backward_weight_workspace_bytes(
                 layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt_code), 16), dtype=torch.uint8, device="cuda")
-            bi_ms = time_launches(torch, lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws_bi), 10, 2)
-            bw_ms = time_launches(torch, lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws_bw), 10, 2)
+            bi = lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws_bi)
+            bw = lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws_bw)
+            settle(torch, bi, 0.03)
+            bi_ms = time_launches(torch, bi, 10, 2)
+            settle(torch, bw, 0.03)
+            bw_ms = time_launches(torch, bw, 10, 2)
             del g, din, dw, ws_bi, ws_bw
             paper_table.append({
                 "layer": layer.name,
