@@ -544,7 +544,6 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 namespace {
 
 constexpr int W_T = 32;          // output channels = input channels per workgroup
-constexpr int W_THREADS = 256;
 constexpr int W_CW = 16;         // positions per chunk at most
 
 struct BwdWParams {
@@ -559,43 +558,50 @@ struct BwdWParams {
 };
 
 // KS: half the positions per chunk (an MFMA takes two); all chunk geometry is a constant expression.
+// (A tile of 128 input channels on eight waves, four times the MFMAs for 1.3 times the staging,
+// was measured slower: 502 against 393 us on the 8 -> 16 generator layer, one workgroup per CU
+// instead of three.)
 template <int n, int KS>
-__global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const float *__restrict__ in,
-                                                                         const float *__restrict__ gf,
-                                                                         float *__restrict__ dst, BwdWParams p)
+__global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *__restrict__ in,
+                                                                  const float *__restrict__ gf,
+                                                                  float *__restrict__ dst, BwdWParams p)
 {
     constexpr int NN = n * n;
     constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
+    constexpr int THREADS = 256;
+    constexpr int BPW = 1;                                       // input-channel blocks per wave
+    constexpr int CI_T = W_T;                                    // input channels per workgroup
     constexpr int CW = 2 * KS;                                   // positions per chunk
     constexpr int IS = CW + 1;                                   // odd strides: lanes of different channels hit different banks
     constexpr int GL = 2 * CW + n - 2;
     constexpr int GS = n * GL + ((n * GL) % 2 == 0 ? 1 : 0);
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int stage = W_T * IS + W_T * GS;                   // floats per stage: [W_T][IS] then [W_T][n][GL]
+    constexpr int stage = CI_T * IS + W_T * GS;                  // floats per stage: [CI_T][IS] then [W_T][n][GL]
 
     unsigned id = blockIdx.x;
     const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
     id /= (unsigned)p.tiles_ci;
     const int tile_co = (int)(id % (unsigned)p.tiles_co);
     const int split = (int)(id / (unsigned)p.tiles_co);
-    const int co0 = tile_co * W_T, ci0 = tile_ci * W_T;
+    const int co0 = tile_co * W_T, ci0 = tile_ci * CI_T;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kk = lane >> 5;
+    const int tg = wave, blk0 = 0;                               // this wave's taps tg + 4 t; its channel block
 
     // ---- staging plan, the same for every chunk ----------------------------------------------------
     // Input element (ci, cc): offset ci * N * N + cc from the chunk's first input position; it is
     // dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc): row 2a + lr and
     // column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel past the tensor,
     // repeats channel 0: what it stages is read by no stored output.
-    constexpr int n_in = W_T * CW, n_g = W_T * n * GL;
-    constexpr int NI = (n_in + W_THREADS - 1) / W_THREADS, NG = (n_g + W_THREADS - 1) / W_THREADS;
+    constexpr int n_in = CI_T * CW, n_g = W_T * n * GL;
+    constexpr int NI = (n_in + THREADS - 1) / THREADS, NG = (n_g + THREADS - 1) / THREADS;
     unsigned i_off[NI], g_off[NG];
     int i_lds[NI], i_cc[NI], g_lds[NG];
 #pragma unroll
     for (int k = 0; k < NI; ++k) {
-        const int e = tid + k * W_THREADS;
+        const int e = tid + k * THREADS;
         const int ci = e / CW, cc = e - ci * CW;
         const bool ok = e < n_in;
         i_off[k] = (ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? cc : 0);
@@ -604,31 +610,33 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
     }
 #pragma unroll
     for (int k = 0; k < NG; ++k) {
-        const int e = tid + k * W_THREADS;
+        const int e = tid + k * THREADS;
         const int co = e / (n * GL);
         const int rem = e - co * (n * GL);
         const int lr = rem / GL, lc = rem - lr * GL;
         const bool ok = e < n_g;
         g_off[k] = ok ? (co0 + co < p.Cout ? (unsigned)(co0 + co) * p.Mf * p.Mfs : 0u) + (unsigned)lr * p.Mfs + lc : 0u;
-        g_lds[k] = ok ? W_T * IS + co * GS + lr * GL + lc : -1;
+        g_lds[k] = ok ? CI_T * IS + co * GS + lr * GL + lc : -1;
     }
 
-    floatx16 acc[TW];
+    floatx16 acc[TW][BPW];
 #pragma unroll
     for (int t = 0; t < TW; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+        for (int q = 0; q < BPW; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][q][v] = 0.0f;
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
-    const int ibase = l32 * IS + kk;                             // B operand: input channel l32, position 2 k + kk
-    // A operand: output channel l32, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
+    const int ibase = (blk0 * 32 + l32) * IS + kk;               // B operand: first block's channel l32, position 2 k + kk
+    // A operand: output channel l32, position 2 k + kk, tap t of this wave (tg + 4 t): its cell at k = 0
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
+        const int uv = min(tg + 4 * t, NN - 1);                  // (a tap past the last is not multiplied)
         const int u = uv / n, v = uv - u * n;
-        abase[t] = W_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
+        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
     }
 
     float i_reg[NI], g_reg[NG];
@@ -667,9 +675,11 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
         const float *S = lds + cur;
-        float bf[KS], af[2][KS];                   // the A values of tap t + 1 are read before tap t is multiplied
+        float bf[BPW][KS], af[2][KS];              // the A values of tap t + 1 are read before tap t is multiplied
 #pragma unroll
-        for (int k = 0; k < KS; ++k) bf[k] = S[ibase + 2 * k];
+        for (int q = 0; q < BPW; ++q)
+#pragma unroll
+            for (int k = 0; k < KS; ++k) bf[q][k] = S[ibase + q * 32 * IS + 2 * k];
 #pragma unroll
         for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 4 * k];
 #pragma unroll
@@ -684,28 +694,33 @@ __global__ void __launch_bounds__(W_THREADS) backward_weight_f32_kernel(const fl
                 stage_write(stage - cur);
                 fetch(ch + 2);
             }
-            // every wave has taps 0 .. TW - 2; the last one only while wave + 4 (TW - 1) < NN
-            if (t == TW - 1 && wave + 4 * t >= NN) break;
+            // every wave has taps 0 .. TW - 2; the last one only while tg + 4 (TW - 1) < NN
+            if (t == TW - 1 && tg + 4 * t >= NN) break;
 #pragma unroll
-            for (int k = 0; k < KS; ++k)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[k], acc[t], 0, 0, 0);
+            for (int q = 0; q < BPW; ++q)
+#pragma unroll
+                for (int k = 0; k < KS; ++k)
+                    acc[t][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[q][k], acc[t][q], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         cur = stage - cur;
     }
 
-    // acc[t][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + l32, tap wave + 4 t
+    // acc[t][q][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel of block blk0 + q, tap tg + 4 t
     float *o = dst + (size_t)split * p.out_elems;
-    const int ci = ci0 + l32;
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        const int uv = wave + 4 * t;
-        if (uv >= NN || ci >= p.Cin) continue;
+        const int uv = tg + 4 * t;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
-            if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][v];
+        for (int q = 0; q < BPW; ++q) {
+            const int ci = ci0 + (blk0 + q) * 32 + l32;
+            if (uv >= NN || ci >= p.Cin) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
+                if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][q][v];
+            }
         }
     }
 }
@@ -728,12 +743,20 @@ BwdWParams plan_w(const Shape &s)
     p.tiles_co = (s.Cout + W_T - 1) / W_T;
     p.tiles_ci = (s.Cin + W_T - 1) / W_T;
     p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
-    // About four workgroups per CU, as long as every split keeps a few chunks.
+    // Split count: the workgroups a CU holds at a time (by their registers) times 256 run together;
+    // cost = rounds x chunks per split x the time of a chunk, plus the traffic of the partial sums.
     const int tiles = p.tiles_co * p.tiles_ci;
-    int splits = (1024 + tiles - 1) / tiles;
-    if (splits > p.nchunks / 4) splits = p.nchunks / 4;
-    if (splits > 64) splits = 64;
-    if (splits < 1) splits = 1;
+    const int per_cu = s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
+    const int taps_per_wave = (s.n * s.n + 3) / 4;
+    const double chunk_s = (double)per_cu * (p.cw / 2) * taps_per_wave * 64.0 / 2.1e9 / 0.45;
+    const double out_b = (double)p.out_elems * 4.0;
+    int splits = 1;
+    double best = 1e30;
+    for (int c = 1; c <= 64 && c <= (p.nchunks + 3) / 4; ++c) {
+        const double rounds = (double)(((size_t)tiles * c + 256 * per_cu - 1) / (256 * per_cu));
+        const double t = rounds * ((p.nchunks + c - 1) / c) * chunk_s + (c > 1 ? (c + 1) * out_b / 4.0e12 : 0.0);
+        if (t < best) { best = t; splits = c; }
+    }
     p.chunks_per_split = (p.nchunks + splits - 1) / splits;
     p.splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
     return p;
@@ -745,8 +768,7 @@ template <int n, int KS>
 hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
-    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS>), dim3(blocks), dim3(W_THREADS), lds_bytes_w(p), stream, in, g,
-                       dst, p);
+    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in, g, dst, p);
     return hipGetLastError();
 }
 
