@@ -395,9 +395,10 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
 }
 
 // ---------------------------------------------------------------------------
-// Even shares ("stream-K"): the (tile, channel chunk) pairs of the whole layer, tile-major, are
-// one list cut into SK_GRID equal ranges, one per persistent workgroup (one workgroup fits a
-// CU), so every CU multiplies for the same time whatever the tile count.  A range is a run of
+// Even shares ("stream-K"): every persistent workgroup (one fits a CU) first does whole tiles,
+// one per round of SK_GRID, as long as full rounds last; the (tile, channel chunk) pairs of the
+// remaining tiles, tile-major, are one list cut into SK_GRID equal ranges, one per workgroup,
+// so every CU multiplies for the same time whatever the tile count.  A range is a run of
 // pieces, each a span of chunks of one tile.  A piece that covers its tile's whole reduction is
 // stored straight to the output; any other is written raw (the accumulator registers, lane by
 // lane) to one of the workgroup's two slots: slot 2g for the first piece of workgroup g's range,
@@ -409,8 +410,9 @@ constexpr size_t SK_SLOT_FLOATS = (size_t)G_TM * G_TCO * 4;   // one tile's accu
 
 struct StreamK {
     int chunks;                // channel chunks per tile
-    int grid;                  // workgroups (<= SK_GRID, <= units)
-    unsigned long long units;  // tiles * chunks
+    int grid;                  // workgroups (<= SK_GRID)
+    int whole;                 // tiles 0 .. whole - 1 (a multiple of grid) are done whole, one workgroup each
+    unsigned long long units;  // (tiles - whole) * chunks: the list that is cut into grid ranges
 };
 
 __device__ __forceinline__ unsigned long long sk_begin(const StreamK &k, int g)
@@ -427,16 +429,30 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int g = blockIdx.x;
     const int tid = threadIdx.x;
+    // The pieces of this workgroup: whole tiles g, g + grid, ... below k.whole, then its range of
+    // the shared list (unit u of it is chunk u % chunks of tile k.whole + u / chunks).
+    int whole_tile = g;
     unsigned long long u = sk_begin(k, g);
     const unsigned long long u_end = sk_begin(k, g + 1);
-    bool first = true;
-    while (u < u_end) {
-        const int tile = (int)(u / (unsigned)k.chunks);
-        const int c0 = (int)(u - (unsigned long long)tile * k.chunks);
-        const unsigned long long left = u_end - u;
-        const int c1 = left < (unsigned long long)(k.chunks - c0) ? c0 + (int)left : k.chunks;
+    bool first = true, started = false;              // first: first piece of the shared range
+    while (whole_tile < k.whole || u < u_end) {
+        int tile, c0, c1;
+        const bool is_whole = whole_tile < k.whole;
+        if (is_whole) {
+            tile = whole_tile;
+            c0 = 0;
+            c1 = k.chunks;
+            whole_tile += k.grid;
+        } else {
+            const int rel = (int)(u / (unsigned)k.chunks);
+            tile = k.whole + rel;
+            c0 = (int)(u - (unsigned long long)rel * k.chunks);
+            const unsigned long long left = u_end - u;
+            c1 = left < (unsigned long long)(k.chunks - c0) ? c0 + (int)left : k.chunks;
+        }
         const int tile_m = tile % p.tiles_m, tile_co = tile / p.tiles_m;
-        if (!first) __syncthreads();                 // the previous piece's last LDS reads are done
+        if (started) __syncthreads();                // the previous piece's last LDS reads are done
+        started = true;
         // A fresh copy of the lane number the compiler cannot see through: the staging plan is then
         // worked out anew for every piece instead of being kept in registers across the pieces.
         int tid_p = tid;
@@ -460,19 +476,22 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
                         d[((c * 2 + h) * 4 + q) * G_THREADS + tid] =
                             make_float4(acc[c][h][4 * q], acc[c][h][4 * q + 1], acc[c][h][4 * q + 2], acc[c][h][4 * q + 3]);
         }
-        first = false;
-        u += (unsigned)(c1 - c0);
+        if (!is_whole) {
+            first = false;
+            u += (unsigned)(c1 - c0);
+        }
     }
 }
 
-// Two workgroups per tile (one per 32-channel half of every wave's block): nothing to do when a
-// single workgroup produced the tile; otherwise the sum of its contributors' slots, in workgroup
+// Two workgroups per tile of the shared list (one per 32-channel half of every wave's block):
+// nothing to do when a single workgroup produced the tile; otherwise the sum of its contributors' slots, in workgroup
 // order, goes to the output.
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const float *__restrict__ ws,
                                                                             float *__restrict__ out, IgemmParams p, StreamK k)
 {
-    const int tile = blockIdx.x >> 1, h = blockIdx.x & 1, tid = threadIdx.x;
-    const unsigned long long u0 = (unsigned long long)tile * k.chunks, u1 = u0 + k.chunks - 1;
+    const int rel = blockIdx.x >> 1, h = blockIdx.x & 1, tid = threadIdx.x;   // tile k.whole + rel of the shared list
+    const int tile = k.whole + rel;
+    const unsigned long long u0 = (unsigned long long)rel * k.chunks, u1 = u0 + k.chunks - 1;
     auto owner = [&](unsigned long long unit) {
         int g = (int)(unit * (unsigned)k.grid / k.units);
         while (g + 1 < k.grid && sk_begin(k, g + 1) <= unit) ++g;
@@ -487,6 +506,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const 
 #pragma unroll
         for (int q = 0; q < 4; ++q) a[c][q] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int g = g0; g <= g1; ++g) {
+        if (sk_begin(k, g) == sk_begin(k, g + 1)) continue;      // an empty range (fewer units than workgroups)
         const int slot = 2 * g + (sk_begin(k, g) < u0 ? 1 : 0);
         const float4 *d = reinterpret_cast<const float4 *>(ws + (size_t)slot * SK_SLOT_FLOATS);
         float4 v[4][4];
@@ -580,8 +600,10 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
     r.use = false;
     r.k.chunks = (s.Cin + G_KC - 1) / G_KC;
     const unsigned long long tiles = (unsigned long long)p.tiles_m * p.tiles_co;
-    r.k.units = tiles * (unsigned)r.k.chunks;
-    r.k.grid = r.k.units < (unsigned long long)SK_GRID ? (int)r.k.units : SK_GRID;
+    const unsigned long long all_units = tiles * (unsigned)r.k.chunks;
+    r.k.grid = all_units < (unsigned long long)SK_GRID ? (int)all_units : SK_GRID;
+    r.k.whole = (int)(tiles / SK_GRID) * SK_GRID;             // (0 unless grid == SK_GRID)
+    r.k.units = (tiles - r.k.whole) * (unsigned)r.k.chunks;
     if (!pipe_ok(p) || tiles > (1u << 22)) return r;
     if (force) {
         r.use = true;
@@ -604,7 +626,7 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
     // The slots are written while other workgroups still multiply; what shows is about half of
     // their traffic (measured on 64 x 1024 x 512 x 8 x 8, n = 5: 483 us against 514 us for seven splits).
     const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / 2.0e11;
-    const double longest = (double)((r.k.units + r.k.grid - 1) / r.k.grid);
+    const double longest = (double)(r.k.whole / r.k.grid) * r.k.chunks + (double)((r.k.units + r.k.grid - 1) / r.k.grid);
     const double t = longest * tile_s / r.k.chunks + (double)partial * SK_SLOT_FLOATS * 4.0 * 2.0 / 8.0e12 + 5.0e-6;
     r.use = t < 0.99 * p.est_s;
     return r;
@@ -637,8 +659,9 @@ static hipError_t launch_streamk_db(const float *in, const float *w_seg, float *
                        w_seg, out, ws, p, k);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3(2u * (unsigned)(p.tiles_m * p.tiles_co)), dim3(G_THREADS), 0,
-                       stream, ws, out, p, k);
+    const unsigned shared_tiles = (unsigned)(p.tiles_m * p.tiles_co - k.whole);
+    if (shared_tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3(2u * shared_tiles), dim3(G_THREADS), 0, stream, ws, out, p, k);
     return hipGetLastError();
 }
 

@@ -311,7 +311,10 @@ def test_igemm_bf16_wide_kernel_is_exact_on_integers_and_stays_inside_out():
     (32, 64, 768, 16, 4),    # 294 tiles x 16 chunks over 256 workgroups: whole tiles and partial pieces per range
     (8, 256, 128, 16, 4),    # 13 tiles x 64 chunks: every tile shared by about 20 workgroups
     (3, 100, 132, 12, 5),    # 6 tiles (ragged both ways) x 25 chunks: one chunk per workgroup
-    (20, 32, 384, 12, 3),    # 264 tiles x 8 chunks, odd M
+    (20, 32, 384, 12, 3),    # 264 tiles x 8 chunks, odd M: a round of whole tiles, then 8 tiles shared by 256 workgroups
+    (84, 8, 256, 16, 4),     # 258 tiles x 2 chunks: a round of whole tiles, then 4 shared units for 256 workgroups
+    (83, 8, 256, 16, 4),     # 256 tiles: whole tiles only, nothing shared and no second pass
+    (16, 16, 256, 16, 4),    # 50 tiles x 4 chunks: fewer units than workgroups
 ])
 def test_igemm_f32_even_shares_sampled_planes(B, Cin, Cout, N, n):
     """fp32 matrix-core path where the (tile, chunk) list is cut into equal ranges: pieces that
