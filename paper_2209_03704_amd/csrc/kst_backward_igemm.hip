@@ -549,19 +549,22 @@ constexpr int W_CW = 16;         // positions per chunk at most
 struct BwdWParams {
     int B, Cin, Cout, N, M, n;
     int Mf, Mfs;           // framed copy of g: rows M + 2 (n - 1), elements between its rows (>= Mf)
-    int cw;                // positions per chunk (even), column chunks per row
-    int ccs;
+    int cw;                // positions per chunk and row (even), column chunks per row, rows per chunk
+    int ccs, rows;
     int is, gl, gs;        // LDS: floats per staged input channel, columns and floats per staged g channel
     int nchunks, chunks_per_split, splits;
     int tiles_co, tiles_ci;
     size_t out_elems;
 };
 
-// KS: half the positions per chunk (an MFMA takes two); all chunk geometry is a constant expression.
+// KS: half the positions a chunk takes of one input row (an MFMA takes two); R: consecutive input
+// rows of one batch item per chunk (they share all but two of their n rows of g each, and a chunk
+// of several rows has that many more MFMAs per barrier: what small maps need).  All chunk
+// geometry is a constant expression.
 // (A tile of 128 input channels on eight waves, four times the MFMAs for 1.3 times the staging,
 // was measured slower: 502 against 393 us on the 8 -> 16 generator layer, one workgroup per CU
 // instead of three.)
-template <int n, int KS>
+template <int n, int KS, int R>
 __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ gf,
                                                                   float *__restrict__ dst, BwdWParams p)
@@ -569,85 +572,83 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     constexpr int NN = n * n;
     constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
     constexpr int THREADS = 256;
-    constexpr int BPW = 1;                                       // input-channel blocks per wave
-    constexpr int CI_T = W_T;                                    // input channels per workgroup
-    constexpr int CW = 2 * KS;                                   // positions per chunk
-    constexpr int IS = CW + 1;                                   // odd strides: lanes of different channels hit different banks
+    constexpr int CW = 2 * KS;                                   // positions per chunk and row
+    constexpr int IS = R * CW + 1;                               // odd strides: lanes of different channels hit different banks
+    constexpr int GR = n + 2 * (R - 1);                          // rows of g a chunk meets
     constexpr int GL = 2 * CW + n - 2;
-    constexpr int GS = n * GL + ((n * GL) % 2 == 0 ? 1 : 0);
+    constexpr int GS = GR * GL + ((GR * GL) % 2 == 0 ? 1 : 0);
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int stage = CI_T * IS + W_T * GS;                  // floats per stage: [CI_T][IS] then [W_T][n][GL]
+    constexpr int stage = W_T * IS + W_T * GS;                   // floats per stage: [W_T][R][CW] then [W_T][GR][GL]
 
     unsigned id = blockIdx.x;
     const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
     id /= (unsigned)p.tiles_ci;
     const int tile_co = (int)(id % (unsigned)p.tiles_co);
     const int split = (int)(id / (unsigned)p.tiles_co);
-    const int co0 = tile_co * W_T, ci0 = tile_ci * CI_T;
+    const int co0 = tile_co * W_T, ci0 = tile_ci * W_T;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kk = lane >> 5;
-    const int tg = wave, blk0 = 0;                               // this wave's taps tg + 4 t; its channel block
 
     // ---- staging plan, the same for every chunk ----------------------------------------------------
-    // Input element (ci, cc): offset ci * N * N + cc from the chunk's first input position; it is
-    // dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc): row 2a + lr and
-    // column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel past the tensor,
-    // repeats channel 0: what it stages is read by no stored output.
-    constexpr int n_in = CI_T * CW, n_g = W_T * n * GL;
+    // Input element (ci, r, cc): offset ci * N * N + r * N + cc from the chunk's first input
+    // position; it is dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc):
+    // row 2 a0 + lr and column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel
+    // past the tensor, repeats channel 0: what it stages is read by no stored output.
+    constexpr int n_in = W_T * R * CW, n_g = W_T * GR * GL;
     constexpr int NI = (n_in + THREADS - 1) / THREADS, NG = (n_g + THREADS - 1) / THREADS;
     unsigned i_off[NI], g_off[NG];
     int i_lds[NI], i_cc[NI], g_lds[NG];
 #pragma unroll
     for (int k = 0; k < NI; ++k) {
         const int e = tid + k * THREADS;
-        const int ci = e / CW, cc = e - ci * CW;
+        const int ci = e / (R * CW), rem = e - ci * (R * CW);
+        const int r = rem / CW, cc = rem - r * CW;
         const bool ok = e < n_in;
-        i_off[k] = (ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? cc : 0);
+        i_off[k] = (ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? r * p.N + cc : 0);
         i_cc[k] = ok ? cc : (1 << 20);
-        i_lds[k] = ok ? ci * IS + cc : -1;
+        i_lds[k] = ok ? ci * IS + rem : -1;
     }
 #pragma unroll
     for (int k = 0; k < NG; ++k) {
         const int e = tid + k * THREADS;
-        const int co = e / (n * GL);
-        const int rem = e - co * (n * GL);
+        const int co = e / (GR * GL);
+        const int rem = e - co * (GR * GL);
         const int lr = rem / GL, lc = rem - lr * GL;
         const bool ok = e < n_g;
         g_off[k] = ok ? (co0 + co < p.Cout ? (unsigned)(co0 + co) * p.Mf * p.Mfs : 0u) + (unsigned)lr * p.Mfs + lc : 0u;
-        g_lds[k] = ok ? CI_T * IS + co * GS + lr * GL + lc : -1;
+        g_lds[k] = ok ? W_T * IS + co * GS + rem : -1;
     }
 
-    floatx16 acc[TW][BPW];
+    floatx16 acc[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t)
 #pragma unroll
-        for (int q = 0; q < BPW; ++q)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[t][q][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
-    const int ibase = (blk0 * 32 + l32) * IS + kk;               // B operand: first block's channel l32, position 2 k + kk
-    // A operand: output channel l32, position 2 k + kk, tap t of this wave (tg + 4 t): its cell at k = 0
+    const int ibase = l32 * IS + kk;                             // B operand: input channel l32, row 0, position 2 k + kk
+    // A operand: output channel l32, row 0, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        const int uv = min(tg + 4 * t, NN - 1);                  // (a tap past the last is not multiplied)
+        const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
         const int u = uv / n, v = uv - u * n;
-        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
+        abase[t] = W_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
     }
 
     float i_reg[NI], g_reg[NG];
     // Registers <- chunk ch (a chunk past the end repeats the last one: valid addresses, unused data).
+    const int groups = p.N / R;                                  // row groups per batch item (R divides N)
     auto fetch = [&](int ch_any) {
         const int ch = min(ch_any, p.nchunks - 1);
-        const int row = ch / p.ccs, cchunk = ch - row * p.ccs;
-        const int b = row / p.N, a = row - b * p.N;
+        const int rg = ch / p.ccs, cchunk = ch - rg * p.ccs;
+        const int b = rg / groups, a0 = (rg - b * groups) * R;
         const int c0 = cchunk * CW;
-        const float *ip = in + (((size_t)b * p.Cin * p.N + a) * p.N + c0);
-        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * a) * p.Mfs + 2 * c0);
+        const float *ip = in + (((size_t)b * p.Cin * p.N + a0) * p.N + c0);
+        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * a0) * p.Mfs + 2 * c0);
 #pragma unroll
         for (int k = 0; k < NI; ++k) {
             const bool inside = c0 + i_cc[k] < p.N;
@@ -675,54 +676,64 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
         const float *S = lds + cur;
-        float bf[BPW][KS], af[2][KS];              // the A values of tap t + 1 are read before tap t is multiplied
 #pragma unroll
-        for (int q = 0; q < BPW; ++q)
+        for (int r = 0; r < R; ++r) {
+            float bf[KS], af[2][KS];               // the A values of tap t + 1 are read before tap t is multiplied
 #pragma unroll
-            for (int k = 0; k < KS; ++k) bf[q][k] = S[ibase + q * 32 * IS + 2 * k];
+            for (int k = 0; k < KS; ++k) bf[k] = S[ibase + r * CW + 2 * k];
 #pragma unroll
-        for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 4 * k];
+            for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 2 * r * GL + 4 * k];
 #pragma unroll
-        for (int t = 0; t < TW; ++t) {
-            if (t + 1 < TW) {
+            for (int t = 0; t < TW; ++t) {
+                if (t + 1 < TW) {
 #pragma unroll
-                for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 4 * k];
-            }
-            if (t == (TW - 1) / 2) {
-                // chunk ch + 1 goes to the other stage (last read before the previous barrier) and
-                // its registers are refilled with chunk ch + 2
-                stage_write(stage - cur);
-                fetch(ch + 2);
-            }
-            // every wave has taps 0 .. TW - 2; the last one only while tg + 4 (TW - 1) < NN
-            if (t == TW - 1 && tg + 4 * t >= NN) break;
-#pragma unroll
-            for (int q = 0; q < BPW; ++q)
+                    for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 2 * r * GL + 4 * k];
+                }
+                if (r == R / 2 && t == (TW - 1) / 2) {
+                    // chunk ch + 1 goes to the other stage (last read before the previous barrier)
+                    // and its registers are refilled with chunk ch + 2
+                    stage_write(stage - cur);
+                    fetch(ch + 2);
+                }
+                // every wave has taps 0 .. TW - 2; the last one only while wave + 4 (TW - 1) < NN
+                if (t == TW - 1 && wave + 4 * t >= NN) break;
 #pragma unroll
                 for (int k = 0; k < KS; ++k)
-                    acc[t][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[q][k], acc[t][q], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[k], acc[t], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         __syncthreads();
         cur = stage - cur;
     }
 
-    // acc[t][q][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel of block blk0 + q, tap tg + 4 t
+    // acc[t][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + l32, tap wave + 4 t
     float *o = dst + (size_t)split * p.out_elems;
+    const int ci = ci0 + l32;
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        const int uv = tg + 4 * t;
+        const int uv = wave + 4 * t;
+        if (uv >= NN || ci >= p.Cin) continue;
 #pragma unroll
-        for (int q = 0; q < BPW; ++q) {
-            const int ci = ci0 + (blk0 + q) * 32 + l32;
-            if (uv >= NN || ci >= p.Cin) continue;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
-                if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][q][v];
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][v];
         }
     }
+}
+
+// Rows per chunk: the largest of 6, 3, 2, 1 that divides N and keeps a chunk within 18 MFMA steps
+// per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one row).
+int weight_rows(int n, int N, int cw)
+{
+    if (n < 3 || cw > 10) return 1;
+    const int cands[3] = {6, 3, 2};
+    for (int c : cands) {
+        const int gr = n + 2 * (c - 1), gl = 2 * cw + n - 2;
+        const size_t lds = 2 * ((size_t)W_T * (c * cw + 1) + (size_t)W_T * (gr * gl + 1)) * sizeof(float);
+        if (N % c == 0 && c * (cw / 2) <= 18 && lds <= 64 * 1024) return c;
+    }
+    return 1;
 }
 
 BwdWParams plan_w(const Shape &s)
@@ -736,10 +747,12 @@ BwdWParams plan_w(const Shape &s)
     // The last chunk of a row may run past it by ccs * cw - N positions: their input values are
     // dropped, and the g columns they would meet are zeros of the framed copy's wider rows.
     p.Mfs = p.Mf + 2 * (p.ccs * p.cw - s.N);
-    p.is = p.cw + 1;                                   // (the kernel derives the same LDS geometry from cw)
+    p.rows = weight_rows(s.n, s.N, p.cw);
+    const int gr = s.n + 2 * (p.rows - 1);
+    p.is = p.rows * p.cw + 1;                          // (the kernel derives the same LDS geometry from cw and rows)
     p.gl = 2 * p.cw + s.n - 2;
-    p.gs = s.n * p.gl + ((s.n * p.gl) % 2 == 0 ? 1 : 0);
-    p.nchunks = s.B * s.N * p.ccs;
+    p.gs = gr * p.gl + ((gr * p.gl) % 2 == 0 ? 1 : 0);
+    p.nchunks = s.B * (s.N / p.rows) * p.ccs;
     p.tiles_co = (s.Cout + W_T - 1) / W_T;
     p.tiles_ci = (s.Cin + W_T - 1) / W_T;
     p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
@@ -748,7 +761,7 @@ BwdWParams plan_w(const Shape &s)
     const int tiles = p.tiles_co * p.tiles_ci;
     const int per_cu = s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
     const int taps_per_wave = (s.n * s.n + 3) / 4;
-    const double chunk_s = (double)per_cu * (p.cw / 2) * taps_per_wave * 64.0 / 2.1e9 / 0.45;
+    const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * taps_per_wave * 64.0 / 2.1e9 / 0.45;
     const double out_b = (double)p.out_elems * 4.0;
     int splits = 1;
     double best = 1e30;
@@ -764,12 +777,27 @@ BwdWParams plan_w(const Shape &s)
 
 size_t lds_bytes_w(const BwdWParams &p) { return 2 * ((size_t)W_T * p.is + (size_t)W_T * p.gs) * sizeof(float); }
 
+template <int n, int KS, int R>
+hipError_t launch_w_r(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
+    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in, g, dst,
+                       p);
+    return hipGetLastError();
+}
+
 template <int n, int KS>
 hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
-    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in, g, dst, p);
-    return hipGetLastError();
+    if constexpr (n >= 3 && KS <= 5) {               // the shapes weight_rows gives several rows
+        if (p.rows == 6) {
+            if constexpr (6 * KS <= 18) return launch_w_r<n, KS, 6>(in, g, dst, p, stream);
+        }
+        if (p.rows == 3) return launch_w_r<n, KS, 3>(in, g, dst, p, stream);
+        if (p.rows == 2) return launch_w_r<n, KS, 2>(in, g, dst, p, stream);
+    }
+    if (p.rows != 1) return hipErrorInvalidValue;
+    return launch_w_r<n, KS, 1>(in, g, dst, p, stream);
 }
 
 template <int n>

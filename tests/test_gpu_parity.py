@@ -573,6 +573,8 @@ def test_gradients(B, Cin, Cout, N, n, P, dtype):
     (2, 8, 8, 20, 2, 0),
     (2, 9, 11, 12, 1, 0),
     (1, 128, 128, 64, 4, 2),   # one row pair per tile
+    (8, 40, 48, 4, 4, 2),      # 4 x 4 maps (a generator's first layers): the kernel gradient takes a whole framed map per chunk
+    (3, 16, 24, 6, 5, 0),      # 5 x 5 kernel on 6 x 6 maps: three rows per chunk
 ])
 def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     """fp32 layers with at least 8 channels on either side take the MFMA gradient kernels."""
