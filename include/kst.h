@@ -181,7 +181,9 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
  * [Cout][Cin][n][n]) and in are of type `dtype`.  din [B][Cin][N][N] and dw
  * [Cout][Cin][n][n] are fully overwritten.  ws / ws_bytes: scratch of at least
  * kst_backward_*_workspace_bytes(...), used for framed copies as in
- * kst_forward_seg_padded, for the zero-framed copy of g the matrix-core
+ * kst_forward_seg_padded (the matrix-core kernels need none of `in` and no
+ * framed result: they visit the unframed positions only), for the zero-framed
+ * copy of g the matrix-core
  * kernel-gradient kernel reads, and for the partial sums of split reductions
  * (the matrix-core kernels: fp32 operands, n <= 5, at least 8 channels on either
  * side; the other kernel-gradient kernels when they slice the positions); it

@@ -308,7 +308,9 @@ namespace {
 //   kernel gradient: [input framed by q] [g framed by one zero (odd P)] [partial sums, as above]
 struct GradPlan {
     int q, Nq, M, Mq;
-    Shape s;                          // the unframed problem the kernels see
+    Shape s;                          // the problem on the framed input map (what the plain kernels see)
+    Shape si;                         // the same with frame = q: the matrix-core kernels work on the unframed
+                                      // positions only (din without the frame; in read as it lies in memory)
     size_t g_bytes, din_bytes, in_bytes;
     size_t split_bytes, wsplit_bytes; // input / kernel gradient on the matrix cores: partial sums
     size_t gw_bytes;                  // kernel gradient on the matrix cores: its framed copy of g (replaces g_bytes)
@@ -329,14 +331,20 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->g_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->din_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * sizeof(float) + 255) & ~(size_t)255) : 0;
     f->in_bytes = P ? (((size_t)B * Cin * f->Nq * f->Nq * elt_bytes(dt) + 255) & ~(size_t)255) : 0;
-    f->split_bytes = backward_input_igemm_supported(f->s, dt) ? backward_input_igemm_workspace_bytes(f->s) : 0;
-    f->wsplit_bytes = backward_weight_igemm_supported(f->s, dt) ? backward_weight_igemm_workspace_bytes(f->s)
-                                                               : backward_weight_generic_workspace_bytes(f->s);
+    f->si = f->s;
+    f->si.frame = f->q;
+    f->split_bytes = 0;
+    if (backward_input_igemm_supported(f->si, dt)) {
+        f->split_bytes = backward_input_igemm_workspace_bytes(f->si);
+        f->din_bytes = 0;                              // written in place, frame never computed
+    }
+    f->wsplit_bytes = backward_weight_igemm_supported(f->si, dt) ? backward_weight_igemm_workspace_bytes(f->si)
+                                                                : backward_weight_generic_workspace_bytes(f->s);
     f->gw_bytes = 0;
     f->gw_frame = f->gw_stride = 0;
-    if (backward_weight_igemm_supported(f->s, dt)) {
+    if (backward_weight_igemm_supported(f->si, dt)) {
         int frame, stride;
-        backward_weight_igemm_g_copy(f->s, &frame, &stride);
+        backward_weight_igemm_g_copy(f->si, &frame, &stride);
         f->gw_frame = frame + (P & 1);                 // on top of the odd padding factor's one-pixel frame
         f->gw_stride = stride;
         const size_t rows = (size_t)f->M + 2 * (size_t)f->gw_frame;
@@ -358,7 +366,8 @@ size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int 
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return f.in_bytes + (backward_weight_igemm_supported(f.s, dtype) ? f.gw_bytes : f.g_bytes) + f.wsplit_bytes;
+    return backward_weight_igemm_supported(f.si, dtype) ? f.gw_bytes + f.wsplit_bytes
+                                                         : f.in_bytes + f.g_bytes + f.wsplit_bytes;
 }
 
 kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
@@ -381,14 +390,15 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
         if (launch_frame_input(g, ws, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
         g_in = (const float *)ws;
     }
-    if (P) d_out = (float *)((char *)ws + f.g_bytes);
-    if (backward_input_igemm_supported(f.s, dtype)) {
-        void *split_ws = f.split_bytes ? (char *)ws + f.g_bytes + f.din_bytes : nullptr;
-        if (launch_backward_input_igemm(g_in, (const float *)w, d_out, split_ws, f.s, stream) != hipSuccess)
-            return KST_ERR_HIP;
-    } else if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) {
-        return KST_ERR_HIP;
+    if (backward_input_igemm_supported(f.si, dtype)) {
+        // the matrix-core kernels compute the unframed positions only, straight into din
+        void *split_ws = f.split_bytes ? (char *)ws + f.g_bytes : nullptr;
+        return launch_backward_input_igemm(g_in, (const float *)w, (float *)din, split_ws, f.si, stream) == hipSuccess
+                   ? KST_OK
+                   : KST_ERR_HIP;
     }
+    if (P) d_out = (float *)((char *)ws + f.g_bytes);
+    if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) return KST_ERR_HIP;
     if (P && launch_crop(d_out, (float *)din, B, Cin, N, f.q, stream) != hipSuccess) return KST_ERR_HIP;
     return KST_OK;
 }
@@ -402,26 +412,27 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(g) || !aligned16(dw)) return KST_ERR_ALIGN;
-    const bool cores = backward_weight_igemm_supported(f.s, dtype);
+    const bool cores = backward_weight_igemm_supported(f.si, dtype);
     const size_t g_copy = cores ? f.gw_bytes : f.g_bytes;
-    const size_t need = f.in_bytes + g_copy + f.wsplit_bytes;
+    const size_t in_copy = cores ? 0 : f.in_bytes;     // the matrix-core kernel reads `in` as it lies in memory
+    const size_t need = in_copy + g_copy + f.wsplit_bytes;
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
     }
     const void *x_in = in;
     const float *g_in = (const float *)g;
-    if (P) {
+    if (P && !cores) {
         if (launch_frame_input(in, ws, B, Cin, N, f.q, f.Nq, dtype, stream) != hipSuccess) return KST_ERR_HIP;
         x_in = ws;
     }
-    void *gw = (char *)ws + f.in_bytes;
-    void *partial_ws = f.wsplit_bytes ? (char *)ws + f.in_bytes + g_copy : nullptr;
+    void *gw = (char *)ws + in_copy;
+    void *partial_ws = f.wsplit_bytes ? (char *)ws + in_copy + g_copy : nullptr;
     if (cores) {
         // g framed once for the odd padding factor and for the kernel's own bounds-free reads
         if (launch_frame_input(g, gw, B, Cout, f.M, f.gw_frame, f.gw_stride, KST_F32, stream) != hipSuccess)
             return KST_ERR_HIP;
-        return launch_backward_weight_igemm((const float *)x_in, (const float *)gw, (float *)dw, partial_ws, f.s, stream) ==
+        return launch_backward_weight_igemm((const float *)x_in, (const float *)gw, (float *)dw, partial_ws, f.si, stream) ==
                        hipSuccess
                    ? KST_OK
                    : KST_ERR_HIP;

@@ -36,7 +36,9 @@ constexpr int B_WST = B_TCI + 1; // LDS row stride of the staged weights (odd: t
 constexpr int B_PX = 16;         // g elements a lane stages per chunk at most
 
 struct BwdParams {
-    int B, Cin, Cout, N, M, n;
+    int B, Cin, Cout, M, n;
+    int N, q;              // positions per row and column; zero frame of the input map around them (its
+                           // gradient is not wanted): position (a, c) meets g rows 2 (a + q) - u
     int Hv, Wl;            // virtual rows per batch item, LDS columns per row
     int lrows;             // virtual rows staged per channel
     int Mtot;              // B * N * N positions
@@ -75,7 +77,7 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_f32_kernel(const flo
     // first virtual row the tile can touch: position m0's taps u = n - 1 .. 0 read rows 2a .. 2a + n - 1
     const int b0 = m0 / NNp;
     const int a0 = (m0 - b0 * NNp) / p.N;
-    const int VR0 = b0 * p.Hv + 2 * a0;
+    const int VR0 = b0 * p.Hv + 2 * (a0 + p.q);
 
     int m = m0 + wpos * 32 + l32;
     const bool m_valid = m < p.Mtot;
@@ -84,7 +86,7 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_f32_kernel(const flo
     const int mrem = m - mb * NNp;
     const int ma = mrem / p.N, mc = mrem - ma * p.N;
     // LDS offset of this lane's tap (u, v) = (0, 0): row 2a + n - 1, column 2c + n - 1
-    const int xbase = (mb * p.Hv + 2 * ma + (n - 1) - VR0) * p.Wl + 2 * mc + (n - 1) + kk * xplane;
+    const int xbase = (mb * p.Hv + 2 * (ma + p.q) + (n - 1) - VR0) * p.Wl + 2 * (mc + p.q) + (n - 1) + kk * xplane;
     const int wbase = kk * (NN * B_WST) + wci * 64 + l32;
 
     const int co_begin = split * p.co_per_split;
@@ -232,7 +234,7 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_vec_kernel(const flo
     const int ci0 = tile_ci * B_TCI;
     const int b0 = m0 / NNp;
     const int a0 = (m0 - b0 * NNp) / p.N;
-    const int VR0 = b0 * p.Hv + 2 * a0;
+    const int VR0 = b0 * p.Hv + 2 * (a0 + p.q);
 
     int m = m0 + wpos * 32 + l32;
     const bool m_valid = m < p.Mtot;
@@ -241,7 +243,7 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_vec_kernel(const flo
     const int mrem = m - mb * NNp;
     const int ma = mrem / p.N, mc = mrem - ma * p.N;
     // LDS offset of this lane's tap (u, v) = (0, 0): row 2a + n - 1, column 2c + V_XF
-    const int xbase = (mb * p.Hv + 2 * ma + (n - 1) - VR0) * p.Wl + 2 * mc + V_XF + kk * xplane;
+    const int xbase = (mb * p.Hv + 2 * (ma + p.q) + (n - 1) - VR0) * p.Wl + 2 * (mc + p.q) + V_XF + kk * xplane;
     // weights of this lane's two channels (h = 0, 1): float offset of element (ci, u v = 0) of
     // output channel kk of a channel pair; for n = 4, one offset per float4 of the channel
     int wrow[2][n == 4 ? 4 : 1];
@@ -377,19 +379,27 @@ __global__ void __launch_bounds__(B_THREADS) backward_input_vec_kernel(const flo
 BwdParams plan(const Shape &s)
 {
     BwdParams p;
-    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.n = s.n;
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.M = s.M; p.n = s.n;
+    p.q = s.frame;
+    p.N = s.N - 2 * s.frame;
     p.Hv = 2 * s.N + s.n - 2;
     p.Wl = 2 * s.N + s.n - 2;
-    // Virtual rows 128 consecutive positions can touch: two per row of positions, n across a
-    // batch-item boundary, and the n rows of the last position's taps.
-    const int dr = (B_TM - 2) / s.N + 1;
-    p.lrows = dr * (s.n > 2 ? s.n : 2) + s.n;
-    p.Mtot = s.B * s.N * s.N;
+    p.Mtot = s.B * p.N * p.N;
     p.tiles_m = (p.Mtot + B_TM - 1) / B_TM;
+    // Virtual rows the positions of one tile can touch: from the first position's top tap row to
+    // the last position's bottom one; the largest over the tiles.
+    p.lrows = 0;
+    for (int t = 0; t < p.tiles_m; ++t) {
+        const int m0 = t * B_TM, m1 = (m0 + B_TM < p.Mtot ? m0 + B_TM : p.Mtot) - 1;
+        const int b0 = m0 / (p.N * p.N), a0 = (m0 - b0 * p.N * p.N) / p.N;
+        const int b1 = m1 / (p.N * p.N), a1 = (m1 - b1 * p.N * p.N) / p.N;
+        const int rows = (b1 * p.Hv + 2 * (a1 + p.q) + s.n - 1) - (b0 * p.Hv + 2 * (a0 + p.q)) + 1;
+        if (rows > p.lrows) p.lrows = rows;
+    }
     p.tiles_ci = (s.Cin + B_TCI - 1) / B_TCI;
     const int tiles = p.tiles_m * p.tiles_ci;
     const int chunks = (s.Cout + B_KC - 1) / B_KC;
-    p.out_elems = (size_t)s.B * s.Cin * s.N * s.N;
+    p.out_elems = (size_t)s.B * s.Cin * p.N * p.N;
     // Split count: launch rounds on 256 CUs times a tile's share of the reduction, plus the
     // summing pass; a split has to beat the unsplit launch by a tenth to be worth its workspace.
     int splits = 1;
@@ -547,7 +557,9 @@ constexpr int W_T = 32;          // output channels = input channels per workgro
 constexpr int W_CW = 16;         // positions per chunk at most
 
 struct BwdWParams {
-    int B, Cin, Cout, N, M, n;
+    int B, Cin, Cout, M, n;
+    int N, q;              // edge of `in` as it lies in memory; zero frame the forward put around it
+                           // (its products are zeros and are skipped): position (a, c) meets g rows 2 (a + q) - u
     int Mf, Mfs;           // framed copy of g: rows M + 2 (n - 1), elements between its rows (>= Mf)
     int cw;                // positions per chunk and row (even), column chunks per row, rows per chunk
     int ccs, rows;
@@ -648,7 +660,7 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
         const int b = rg / groups, a0 = (rg - b * groups) * R;
         const int c0 = cchunk * CW;
         const float *ip = in + (((size_t)b * p.Cin * p.N + a0) * p.N + c0);
-        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * a0) * p.Mfs + 2 * c0);
+        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * (a0 + p.q)) * p.Mfs + 2 * (c0 + p.q));
 #pragma unroll
         for (int k = 0; k < NI; ++k) {
             const bool inside = c0 + i_cc[k] < p.N;
@@ -739,20 +751,23 @@ int weight_rows(int n, int N, int cw)
 BwdWParams plan_w(const Shape &s)
 {
     BwdWParams p;
-    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.n = s.n;
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.M = s.M; p.n = s.n;
+    p.q = s.frame;
+    p.N = s.N - 2 * s.frame;
     p.Mf = s.M + 2 * (s.n - 1);
     // Equal chunks of an even number of positions, 16 at most: a row of 18 is cut 10 + 8, not 16 + 2.
-    p.ccs = (s.N + W_CW - 1) / W_CW;
-    p.cw = (((s.N + p.ccs - 1) / p.ccs) + 1) & ~1;
-    // The last chunk of a row may run past it by ccs * cw - N positions: their input values are
-    // dropped, and the g columns they would meet are zeros of the framed copy's wider rows.
-    p.Mfs = p.Mf + 2 * (p.ccs * p.cw - s.N);
-    p.rows = weight_rows(s.n, s.N, p.cw);
+    p.ccs = (p.N + W_CW - 1) / W_CW;
+    p.cw = (((p.N + p.ccs - 1) / p.ccs) + 1) & ~1;
+    // The last chunk of a row may run past it: the input values of those positions are dropped,
+    // and the g columns they would meet (up to 2 ccs cw + 2 q + n - 3) are zeros of the framed
+    // copy's wider rows.
+    p.Mfs = p.Mf > 2 * p.ccs * p.cw + 2 * p.q + s.n - 2 ? p.Mf : 2 * p.ccs * p.cw + 2 * p.q + s.n - 2;
+    p.rows = weight_rows(s.n, p.N, p.cw);
     const int gr = s.n + 2 * (p.rows - 1);
     p.is = p.rows * p.cw + 1;                          // (the kernel derives the same LDS geometry from cw and rows)
     p.gl = 2 * p.cw + s.n - 2;
     p.gs = gr * p.gl + ((gr * p.gl) % 2 == 0 ? 1 : 0);
-    p.nchunks = s.B * (s.N / p.rows) * p.ccs;
+    p.nchunks = s.B * (p.N / p.rows) * p.ccs;
     p.tiles_co = (s.Cout + W_T - 1) / W_T;
     p.tiles_ci = (s.Cin + W_T - 1) / W_T;
     p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
