@@ -542,8 +542,9 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 // launch function), so every tap of every position reads inside that copy and no g load needs a
 // bounds check.
 //
-// Tile: 32 co x 32 ci x all n * n taps per 256-thread workgroup; the taps are dealt over the
-// four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4) accumulators.
+// Tile: 32 co x 32 or 64 ci x all n * n taps per 256-thread workgroup; the taps are dealt over the
+// four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4) accumulators per
+// block of 32 input channels.
 // The reduction walks chunks of up to 16 consecutive positions of one input row; per chunk
 // the workgroup stages the 32 x cw inputs and the n rows x (2 cw + n - 2) columns of g the
 // chunk's taps touch for its 32 output channels.  Staging is branch-free (every lane has a fixed
@@ -553,8 +554,9 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 // reduction pass (fixed order).
 namespace {
 
-constexpr int W_T = 32;          // output channels = input channels per workgroup
+constexpr int W_T = 32;          // output channels per workgroup; input channels: W_T per block, 1 or 2 blocks
 constexpr int W_CW = 16;         // positions per chunk at most
+constexpr int W_DUMP = 32;       // floats at the end of an LDS stage that nothing reads
 
 struct BwdWParams {
     int B, Cin, Cout, M, n;
@@ -566,6 +568,7 @@ struct BwdWParams {
     int is, gl, gs;        // LDS: floats per staged input channel, columns and floats per staged g channel
     int nchunks, chunks_per_split, splits;
     int tiles_co, tiles_ci;
+    int cb;                // blocks of 32 input channels per workgroup
     size_t out_elems;
 };
 
@@ -573,10 +576,12 @@ struct BwdWParams {
 // rows of one batch item per chunk (they share all but two of their n rows of g each, and a chunk
 // of several rows has that many more MFMAs per barrier: what small maps need).  All chunk
 // geometry is a constant expression.
-// (A tile of 128 input channels on eight waves, four times the MFMAs for 1.3 times the staging,
-// was measured slower: 502 against 393 us on the 8 -> 16 generator layer, one workgroup per CU
-// instead of three.)
-template <int n, int KS, int R>
+// CB: blocks of 32 input channels per workgroup.  With two, every staged value of g and every A
+// fragment read from LDS feeds two MFMAs (4 -> 8 generator layer of 4 x 4 kernels, batch 64:
+// 318 -> 252 us; 16 -> 32: 269 -> 240 us), for twice the accumulators and so fewer waves per CU.
+// (A tile of 128 input channels on eight waves was measured slower than one of 32: 502 against
+// 393 us on the 8 -> 16 generator layer, one workgroup per CU.)
+template <int n, int KS, int R, int CB>
 __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ gf,
                                                                   float *__restrict__ dst, BwdWParams p)
@@ -590,14 +595,15 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     constexpr int GL = 2 * CW + n - 2;
     constexpr int GS = GR * GL + ((GR * GL) % 2 == 0 ? 1 : 0);
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int stage = W_T * IS + W_T * GS;                   // floats per stage: [W_T][R][CW] then [W_T][GR][GL]
+    constexpr int CI_T = W_T * CB;                               // input channels per workgroup
+    constexpr int stage = CI_T * IS + W_T * GS + W_DUMP;         // floats per stage: [CI_T][R][CW], [W_T][GR][GL], dump cells
 
     unsigned id = blockIdx.x;
     const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
     id /= (unsigned)p.tiles_ci;
     const int tile_co = (int)(id % (unsigned)p.tiles_co);
     const int split = (int)(id / (unsigned)p.tiles_co);
-    const int co0 = tile_co * W_T, ci0 = tile_ci * W_T;
+    const int co0 = tile_co * W_T, ci0 = tile_ci * CI_T;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -608,19 +614,21 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     // position; it is dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc):
     // row 2 a0 + lr and column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel
     // past the tensor, repeats channel 0: what it stages is read by no stored output.
-    constexpr int n_in = W_T * R * CW, n_g = W_T * GR * GL;
+    constexpr int n_in = CI_T * R * CW, n_g = W_T * GR * GL;
     constexpr int NI = (n_in + THREADS - 1) / THREADS, NG = (n_g + THREADS - 1) / THREADS;
-    unsigned i_off[NI], g_off[NG];
+    constexpr int ITEMS = NI + NG;
+    unsigned i_off[NI], g_off[NG];                               // byte offsets
     int i_lds[NI], i_cc[NI], g_lds[NG];
+    const int dump = stage - W_DUMP + (tid & (W_DUMP - 1));      // where a lane past the lists writes
 #pragma unroll
     for (int k = 0; k < NI; ++k) {
         const int e = tid + k * THREADS;
         const int ci = e / (R * CW), rem = e - ci * (R * CW);
         const int r = rem / CW, cc = rem - r * CW;
         const bool ok = e < n_in;
-        i_off[k] = (ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? r * p.N + cc : 0);
+        i_off[k] = 4u * ((ok && ci0 + ci < p.Cin ? (unsigned)(ci0 + ci) * p.N * p.N : 0u) + (ok ? r * p.N + cc : 0));
         i_cc[k] = ok ? cc : (1 << 20);
-        i_lds[k] = ok ? ci * IS + rem : -1;
+        i_lds[k] = ok ? ci * IS + rem : dump;
     }
 #pragma unroll
     for (int k = 0; k < NG; ++k) {
@@ -629,120 +637,164 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
         const int rem = e - co * (GR * GL);
         const int lr = rem / GL, lc = rem - lr * GL;
         const bool ok = e < n_g;
-        g_off[k] = ok ? (co0 + co < p.Cout ? (unsigned)(co0 + co) * p.Mf * p.Mfs : 0u) + (unsigned)lr * p.Mfs + lc : 0u;
-        g_lds[k] = ok ? W_T * IS + co * GS + rem : -1;
+        g_off[k] = ok ? 4u * ((co0 + co < p.Cout ? (unsigned)(co0 + co) * p.Mf * p.Mfs : 0u) + (unsigned)lr * p.Mfs + lc) : 0u;
+        g_lds[k] = ok ? CI_T * IS + co * GS + rem : dump;
     }
 
-    floatx16 acc[TW];
+    floatx16 acc[TW][CB];
 #pragma unroll
     for (int t = 0; t < TW; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
-    const int ibase = l32 * IS + kk;                             // B operand: input channel l32, row 0, position 2 k + kk
+    const int ibase = l32 * IS + kk;                             // B operand: input channel l32 of block 0, row 0, position 2 k + kk
     // A operand: output channel l32, row 0, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
         const int u = uv / n, v = uv - u * n;
-        abase[t] = W_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
+        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
     }
 
+    // Staging runs through registers, two chunks ahead: while chunk ch is multiplied the registers
+    // hold chunk ch + 1; item j of the lists writes its register to the stage that is not being
+    // read and reloads it with chunk ch + 2.  The cursor below names the chunk being loaded (past
+    // the last chunk it stays on the last one: valid addresses, unused data).
     float i_reg[NI], g_reg[NG];
-    // Registers <- chunk ch (a chunk past the end repeats the last one: valid addresses, unused data).
     const int groups = p.N / R;                                  // row groups per batch item (R divides N)
-    auto fetch = [&](int ch_any) {
-        const int ch = min(ch_any, p.nchunks - 1);
-        const int rg = ch / p.ccs, cchunk = ch - rg * p.ccs;
-        const int b = rg / groups, a0 = (rg - b * groups) * R;
-        const int c0 = cchunk * CW;
-        const float *ip = in + (((size_t)b * p.Cin * p.N + a0) * p.N + c0);
-        const float *gp = gf + ((size_t)b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * (a0 + p.q)) * p.Mfs + 2 * (c0 + p.q));
-#pragma unroll
-        for (int k = 0; k < NI; ++k) {
-            const bool inside = c0 + i_cc[k] < p.N;
-            const float v = ip[inside ? i_off[k] : 0u];
-            i_reg[k] = inside ? v : 0.0f;
+    int f_ch = min(chunk_begin, p.nchunks - 1);
+    int f_cc, f_g, f_b;
+    {
+        const int rg = f_ch / p.ccs;
+        f_cc = f_ch - rg * p.ccs;
+        f_b = rg / groups;
+        f_g = rg - f_b * groups;
+    }
+    auto advance = [&]() {
+        if (f_ch + 1 < p.nchunks) {
+            ++f_ch;
+            if (++f_cc == p.ccs) {
+                f_cc = 0;
+                if (++f_g == groups) { f_g = 0; ++f_b; }
+            }
         }
-#pragma unroll
-        for (int k = 0; k < NG; ++k) g_reg[k] = gp[g_off[k]];
     };
-    auto stage_write = [&](int at) {
-#pragma unroll
-        for (int k = 0; k < NI; ++k)
-            if (i_lds[k] >= 0) lds[at + i_lds[k]] = i_reg[k];
-#pragma unroll
-        for (int k = 0; k < NG; ++k)
-            if (g_lds[k] >= 0) lds[at + g_lds[k]] = g_reg[k];
+    const char *ip, *gp;
+    int f_c0, h_c0 = 0;                                           // first column of the chunk being loaded / held in registers
+    auto aim = [&]() {
+        const int a0 = f_g * R;
+        f_c0 = f_cc * CW;
+        ip = reinterpret_cast<const char *>(in + (((size_t)f_b * p.Cin * p.N + a0) * p.N + f_c0));
+        gp = reinterpret_cast<const char *>(gf + ((size_t)f_b * p.Cout * p.Mf * p.Mfs + (size_t)(2 * (a0 + p.q)) * p.Mfs +
+                                                  2 * (f_c0 + p.q)));
+    };
+    // An input position past its row is staged as zero (the chunk's last columns may be).
+    auto put = [&](int j, int at) {
+        if (j < NI)
+            lds[at + i_lds[j]] = h_c0 + i_cc[j] < p.N ? i_reg[j] : 0.0f;
+        else
+            lds[at + g_lds[j - NI]] = g_reg[j - NI];
+    };
+    auto get = [&](int j) {
+        if (j < NI)
+            i_reg[j] = *reinterpret_cast<const float *>(ip + (f_c0 + i_cc[j] < p.N ? i_off[j] : 0u));
+        else
+            g_reg[j - NI] = *reinterpret_cast<const float *>(gp + g_off[j - NI]);
     };
 
     if (chunk_begin < chunk_end) {
-        fetch(chunk_begin);
-        stage_write(0);
-        fetch(chunk_begin + 1);
+        aim();
+        static_for<ITEMS>([&](auto jc) { get(decltype(jc)::value); });
+        h_c0 = f_c0;
+        advance();
+        aim();
+        static_for<ITEMS>([&](auto jc) { put(decltype(jc)::value, 0); get(decltype(jc)::value); });
+        h_c0 = f_c0;
+        advance();
     }
     __syncthreads();
+
+    // The wave issues in order, so whatever stands between two MFMAs delays the second one by all
+    // it takes beyond the first one's run time: the items are dealt out over the MFMAs of the taps
+    // every wave has (the last tap may belong to fewer waves).  1 x 1 kernels have no such tap
+    // (one wave multiplies): there the items go in one block.
+    constexpr int TS = NN % 4 == 0 ? TW : TW - 1;
+    constexpr int SLOTS = TS > 0 ? R * TS * KS * CB : 1;
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
         const float *S = lds + cur;
+        const int other = stage - cur;
+        aim();
+        __builtin_amdgcn_sched_barrier(0);
+        float bf[CB][KS], af[2][KS];               // the A values of tap t + 1 are read before tap t is multiplied
+        static_for<R * TW>([&](auto qc) {
+            constexpr int r = decltype(qc)::value / TW, t = decltype(qc)::value % TW;
+            if constexpr (t == 0) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            float bf[KS], af[2][KS];               // the A values of tap t + 1 are read before tap t is multiplied
+                for (int c = 0; c < CB; ++c)
 #pragma unroll
-            for (int k = 0; k < KS; ++k) bf[k] = S[ibase + r * CW + 2 * k];
+                    for (int k = 0; k < KS; ++k) bf[c][k] = S[ibase + c * W_T * IS + r * CW + 2 * k];
 #pragma unroll
-            for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 2 * r * GL + 4 * k];
-#pragma unroll
-            for (int t = 0; t < TW; ++t) {
-                if (t + 1 < TW) {
-#pragma unroll
-                    for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 2 * r * GL + 4 * k];
-                }
-                if (r == R / 2 && t == (TW - 1) / 2) {
-                    // chunk ch + 1 goes to the other stage (last read before the previous barrier)
-                    // and its registers are refilled with chunk ch + 2
-                    stage_write(stage - cur);
-                    fetch(ch + 2);
-                }
-                // every wave has taps 0 .. TW - 2; the last one only while wave + 4 (TW - 1) < NN
-                if (t == TW - 1 && wave + 4 * t >= NN) break;
-#pragma unroll
-                for (int k = 0; k < KS; ++k)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[k], acc[t], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int k = 0; k < KS; ++k) af[0][k] = S[abase[0] + 2 * r * GL + 4 * k];
             }
-        }
+            if constexpr (t + 1 < TW) {
+#pragma unroll
+                for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 2 * r * GL + 4 * k];
+            }
+            if constexpr (TS == 0 && r == R / 2 && t == 0)
+                static_for<ITEMS>([&](auto jc) { put(decltype(jc)::value, other); get(decltype(jc)::value); });
+            // every wave has taps 0 .. TS - 1; the last one only while wave + 4 (TW - 1) < NN
+            if (t < TS || wave + 4 * t < NN) {
+                static_for<KS * CB>([&](auto mc) {
+                    constexpr int k = decltype(mc)::value / CB, c = decltype(mc)::value % CB;
+                    acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[c][k], acc[t][c], 0, 0, 0);
+                    if constexpr (t < TS) {
+                        constexpr int slot = ((r * TS + t) * KS + k) * CB + c;
+                        constexpr int j0 = slot * ITEMS / SLOTS, j1 = (slot + 1) * ITEMS / SLOTS;
+                        static_for<j1 - j0>([&](auto jc) { put(j0 + decltype(jc)::value, other); get(j0 + decltype(jc)::value); });
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            }
+        });
+        h_c0 = f_c0;
+        advance();
         __syncthreads();
-        cur = stage - cur;
+        cur = other;
     }
 
-    // acc[t][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + l32, tap wave + 4 t
+    // acc[t][c][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + 32 c + l32, tap wave + 4 t
     float *o = dst + (size_t)split * p.out_elems;
-    const int ci = ci0 + l32;
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         const int uv = wave + 4 * t;
-        if (uv >= NN || ci >= p.Cin) continue;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
-            if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][v];
+        for (int c = 0; c < CB; ++c) {
+            const int ci = ci0 + c * W_T + l32;
+            if (uv >= NN || ci >= p.Cin) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
+                if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][c][v];
+            }
         }
     }
 }
 
 // Rows per chunk: the largest of 6, 3, 2, 1 that divides N and keeps a chunk within 18 MFMA steps
 // per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one row).
-int weight_rows(int n, int N, int cw)
+int weight_rows(int n, int N, int cw, int cb)
 {
     if (n < 3 || cw > 10) return 1;
     const int cands[3] = {6, 3, 2};
     for (int c : cands) {
         const int gr = n + 2 * (c - 1), gl = 2 * cw + n - 2;
-        const size_t lds = 2 * ((size_t)W_T * (c * cw + 1) + (size_t)W_T * (gr * gl + 1)) * sizeof(float);
+        const size_t lds = 2 * ((size_t)W_T * cb * (c * cw + 1) + (size_t)W_T * (gr * gl + 1) + W_DUMP) * sizeof(float);
         if (N % c == 0 && c * (cw / 2) <= 18 && lds <= 64 * 1024) return c;
     }
     return 1;
@@ -762,21 +814,23 @@ BwdWParams plan_w(const Shape &s)
     // and the g columns they would meet (up to 2 ccs cw + 2 q + n - 3) are zeros of the framed
     // copy's wider rows.
     p.Mfs = p.Mf > 2 * p.ccs * p.cw + 2 * p.q + s.n - 2 ? p.Mf : 2 * p.ccs * p.cw + 2 * p.q + s.n - 2;
-    p.rows = weight_rows(s.n, p.N, p.cw);
+    p.cb = s.Cin > W_T ? 2 : 1;
+    p.rows = weight_rows(s.n, p.N, p.cw, p.cb);
     const int gr = s.n + 2 * (p.rows - 1);
     p.is = p.rows * p.cw + 1;                          // (the kernel derives the same LDS geometry from cw and rows)
     p.gl = 2 * p.cw + s.n - 2;
     p.gs = gr * p.gl + ((gr * p.gl) % 2 == 0 ? 1 : 0);
     p.nchunks = s.B * (p.N / p.rows) * p.ccs;
     p.tiles_co = (s.Cout + W_T - 1) / W_T;
-    p.tiles_ci = (s.Cin + W_T - 1) / W_T;
+    p.tiles_ci = (s.Cin + W_T * p.cb - 1) / (W_T * p.cb);
     p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
     // Split count: the workgroups a CU holds at a time (by their registers) times 256 run together;
     // cost = rounds x chunks per split x the time of a chunk, plus the traffic of the partial sums.
     const int tiles = p.tiles_co * p.tiles_ci;
-    const int per_cu = s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
+    // (two-block tiles: counted as one per CU, the setting that measured best)
+    const int per_cu = p.cb == 2 ? 1 : s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
     const int taps_per_wave = (s.n * s.n + 3) / 4;
-    const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * taps_per_wave * 64.0 / 2.1e9 / 0.45;
+    const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * taps_per_wave * p.cb * 64.0 / 2.1e9 / 0.45;
     const double out_b = (double)p.out_elems * 4.0;
     int splits = 1;
     double best = 1e30;
@@ -790,14 +844,21 @@ BwdWParams plan_w(const Shape &s)
     return p;
 }
 
-size_t lds_bytes_w(const BwdWParams &p) { return 2 * ((size_t)W_T * p.is + (size_t)W_T * p.gs) * sizeof(float); }
+size_t lds_bytes_w(const BwdWParams &p)
+{
+    return 2 * ((size_t)W_T * p.cb * p.is + (size_t)W_T * p.gs + W_DUMP) * sizeof(float);
+}
 
 template <int n, int KS, int R>
 hipError_t launch_w_r(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
-    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in, g, dst,
-                       p);
+    if (p.cb == 2)
+        hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, 2>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in,
+                           g, dst, p);
+    else
+        hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, 1>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in,
+                           g, dst, p);
     return hipGetLastError();
 }
 
@@ -840,6 +901,9 @@ bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt)
     if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
     if (s.Cin < 8 || s.Cout < 8) return false;
     const BwdWParams p = plan_w(s);
+    // (the staging lists hold byte offsets inside one batch item in 32 bits)
+    if ((size_t)s.Cout * p.Mf * p.Mfs * sizeof(float) >= 0xffffffffu) return false;
+    if ((size_t)s.Cin * s.N * s.N * sizeof(float) >= 0xffffffffu) return false;
     if (lds_bytes_w(p) > 64 * 1024) return false;
     if ((size_t)p.tiles_ci * p.tiles_co * p.splits >= 0x7fffffffu) return false;
     return true;

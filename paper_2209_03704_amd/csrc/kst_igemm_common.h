@@ -3,9 +3,25 @@
 #pragma once
 #include "kst_internal.h"
 
+#include <utility>
+
 namespace kst {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
+// constant expression inside the body, so register arrays are only ever indexed by constants.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_each(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_each(f, std::make_integer_sequence<int, N>{});
+}
+
 
 constexpr int G_TM = 128;        // positions per workgroup (4 MFMA column blocks)
 constexpr int G_TCO = 128;       // output channels per workgroup (4 MFMA row blocks)

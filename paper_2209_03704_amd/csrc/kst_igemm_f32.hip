@@ -147,19 +147,6 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__res
 // ---------------------------------------------------------------------------
 constexpr int P_NX4 = 2;         // input float4 per lane per chunk at most
 
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
-// constant expression inside the body, so register arrays are only ever indexed by constants.
-template <class F, int... I>
-__device__ __forceinline__ void static_for_each(F &&f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_each(f, std::make_integer_sequence<int, N>{});
-}
-
 // What a lane needs to know about its column of the tile when the accumulators are stored.
 struct PipeLane {
     int mb, mi, mj;      // batch item and quad of this lane's position

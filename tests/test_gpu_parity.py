@@ -621,30 +621,35 @@ def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
 
 
-def test_gradients_on_the_matrix_cores_are_exact_on_integers_and_stay_inside_their_outputs():
-    layer = wl.Layer("grad_mfma_int", 3, 24, 16, 10, 5, "f32", "integer", P=2)
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (3, 24, 16, 10, 5, 2),     # one block of input channels per workgroup
+    (2, 72, 40, 6, 3, 1),      # two blocks, the second tile's second block empty; three rows per chunk
+    (2, 40, 9, 9, 4, 0),       # two blocks, the second ragged; ragged output channels
+])
+def test_gradients_on_the_matrix_cores_are_exact_on_integers_and_stay_inside_their_outputs(B, Cin, Cout, N, n, P):
+    layer = wl.Layer("grad_mfma_int", B, Cin, Cout, N, n, "f32", "integer", P=P)
     x, w = wl.make_tensors(layer, 98)
-    M = kst.kst_out_size_padded(layer.N, layer.n, layer.P)
+    M = kst.kst_out_size_padded(N, n, P)
     gen = torch.Generator().manual_seed(6)
-    g = torch.randint(-3, 4, (3, 16, M, M), generator=gen).to(torch.float32)
-    numel = 3 * 24 * 10 * 10
+    g = torch.randint(-3, 4, (B, Cout, M, M), generator=gen).to(torch.float32)
+    numel = B * Cin * N * N
     guard = 1024
     buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
-    din = buf[guard:guard + numel].view(3, 24, 10, 10)
-    kst.kst_backward_input(g.to(DEV), w.to(DEV), layer.N, layer.P, din=din)
-    wn = 16 * 24 * 25
+    din = buf[guard:guard + numel].view(B, Cin, N, N)
+    kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P, din=din)
+    wn = Cout * Cin * n * n
     wbuf = torch.full((wn + 2 * guard,), float("nan"), device=DEV)
-    dw = wbuf[guard:guard + wn].view(16, 24, 5, 5)
-    kst.kst_backward_weight(x.to(DEV), g.to(DEV), layer.n, layer.P, dw=dw)
+    dw = wbuf[guard:guard + wn].view(Cout, Cin, n, n)
+    kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P, dw=dw)
     torch.cuda.synchronize()
     host = buf.cpu()
     assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
-    want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P)
-    assert np.array_equal(host[guard:guard + numel].view(3, 24, 10, 10).numpy().astype(np.float64), want)
+    want = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    assert np.array_equal(host[guard:guard + numel].view(B, Cin, N, N).numpy().astype(np.float64), want)
     whost = wbuf.cpu()
     assert torch.isnan(whost[:guard]).all() and torch.isnan(whost[guard + wn:]).all()
-    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P)
-    assert np.array_equal(whost[guard:guard + wn].view(16, 24, 5, 5).numpy().astype(np.float64), want_dw)
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert np.array_equal(whost[guard:guard + wn].view(Cout, Cin, n, n).numpy().astype(np.float64), want_dw)
 
 
 @pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
