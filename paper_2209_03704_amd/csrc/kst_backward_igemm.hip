@@ -569,6 +569,7 @@ struct BwdWParams {
     int nchunks, chunks_per_split, splits;
     int tiles_co, tiles_ci;
     int cb;                // blocks of 32 input channels per workgroup
+    int halves;            // wave quartets per workgroup
     size_t out_elems;
 };
 
@@ -581,14 +582,19 @@ struct BwdWParams {
 // 318 -> 252 us; 16 -> 32: 269 -> 240 us), for twice the accumulators and so fewer waves per CU.
 // (A tile of 128 input channels on eight waves was measured slower than one of 32: 502 against
 // 393 us on the 8 -> 16 generator layer, one workgroup per CU.)
-template <int n, int KS, int R, int CB>
-__global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *__restrict__ in,
+// H: wave quartets per workgroup.  With two, each takes half of a chunk's R rows for all taps
+// (two waves per SIMD: one multiplies while the other stages or waits), and the second quartet's
+// sums are added to the first's through LDS at the end.
+template <int n, int KS, int R, int CB, int H>
+__global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ gf,
                                                                   float *__restrict__ dst, BwdWParams p)
 {
     constexpr int NN = n * n;
     constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
-    constexpr int THREADS = 256;
+    constexpr int THREADS = 256 * H;
+    constexpr int RH = R / H;                                    // rows per quartet
+    static_assert(R % H == 0, "rows split evenly");
     constexpr int CW = 2 * KS;                                   // positions per chunk and row
     constexpr int IS = R * CW + 1;                               // odd strides: lanes of different channels hit different banks
     constexpr int GR = n + 2 * (R - 1);                          // rows of g a chunk meets
@@ -606,7 +612,9 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     const int co0 = tile_co * W_T, ci0 = tile_ci * CI_T;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6) & 3;      // owner of taps wave, wave + 4, ...
+    const int half = __builtin_amdgcn_readfirstlane(tid >> 8);         // quartet
     const int l32 = lane & 31, kk = lane >> 5;
 
     // ---- staging plan, the same for every chunk ----------------------------------------------------
@@ -651,14 +659,15 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
-    const int ibase = l32 * IS + kk;                             // B operand: input channel l32 of block 0, row 0, position 2 k + kk
+    // B operand: input channel l32 of block 0, this quartet's first row, position 2 k + kk
+    const int ibase = l32 * IS + kk + half * RH * CW;
     // A operand: output channel l32, row 0, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
         const int u = uv / n, v = uv - u * n;
-        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v;
+        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
     }
 
     // Staging runs through registers, two chunks ahead: while chunk ch is multiplied the registers
@@ -724,7 +733,7 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
     // every wave has (the last tap may belong to fewer waves).  1 x 1 kernels have no such tap
     // (one wave multiplies): there the items go in one block.
     constexpr int TS = NN % 4 == 0 ? TW : TW - 1;
-    constexpr int SLOTS = TS > 0 ? R * TS * KS * CB : 1;
+    constexpr int SLOTS = TS > 0 ? RH * TS * KS * CB : 1;
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
         const float *S = lds + cur;
@@ -732,7 +741,7 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
         aim();
         __builtin_amdgcn_sched_barrier(0);
         float bf[CB][KS], af[2][KS];               // the A values of tap t + 1 are read before tap t is multiplied
-        static_for<R * TW>([&](auto qc) {
+        static_for<RH * TW>([&](auto qc) {
             constexpr int r = decltype(qc)::value / TW, t = decltype(qc)::value % TW;
             if constexpr (t == 0) {
 #pragma unroll
@@ -746,7 +755,7 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
 #pragma unroll
                 for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 2 * r * GL + 4 * k];
             }
-            if constexpr (TS == 0 && r == R / 2 && t == 0)
+            if constexpr (TS == 0 && r == RH / 2 && t == 0)
                 static_for<ITEMS>([&](auto jc) { put(decltype(jc)::value, other); get(decltype(jc)::value); });
             // every wave has taps 0 .. TS - 1; the last one only while wave + 4 (TW - 1) < NN
             if (t < TS || wave + 4 * t < NN) {
@@ -768,36 +777,63 @@ __global__ void __launch_bounds__(256) backward_weight_f32_kernel(const float *_
         cur = other;
     }
 
-    // acc[t][c][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + 32 c + l32, tap wave + 4 t
+    // ---- epilogue -------------------------------------------------------------------------------
+    // acc[t][c][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + 32 c + l32,
+    // tap wave + 4 t.  In dw the taps of one (co, ci) lie side by side and the input channels of
+    // one co follow each other, so a tile's part of one output channel is ONE run of
+    // (channels of the tile) * n * n floats.  Eight output channels at a time go through LDS
+    // (the loop's last barrier has passed: nobody reads a stage any more) and leave as whole
+    // runs, consecutive lanes writing consecutive floats.  (Straight from the registers a lane's
+    // stores lie n * n floats apart: 35-45 us of the 4 x 4 generator layers' 210-220 us.)
+    // With two quartets the second one writes its sums first and the first adds its own.
+    constexpr int NP = NN | 1;                                   // odd stride between a channel's taps in LDS
     float *o = dst + (size_t)split * p.out_elems;
-#pragma unroll
-    for (int t = 0; t < TW; ++t) {
-        const int uv = wave + 4 * t;
-#pragma unroll
-        for (int c = 0; c < CB; ++c) {
-            const int ci = ci0 + c * W_T + l32;
-            if (uv >= NN || ci >= p.Cin) continue;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
-                if (co < p.Cout) o[((size_t)co * p.Cin + ci) * NN + uv] = acc[t][c][v];
-            }
+    const int run = min(CI_T, p.Cin - ci0) * NN;                 // floats of one output channel's run
+    static_for<4>([&](auto vqc) {
+        constexpr int vq = decltype(vqc)::value;
+        auto cell = [&](int t, int c, int j) { return ((4 * kk + j) * CI_T + c * W_T + l32) * NP + wave + 4 * t; };
+        if (H == 1 || half == 1) {
+            static_for<TW * CB * 4>([&](auto ec) {
+                constexpr int t = decltype(ec)::value / (CB * 4), c = (decltype(ec)::value / 4) % CB, j = decltype(ec)::value % 4;
+                if (wave + 4 * t < NN) lds[cell(t, c, j)] = acc[t][c][4 * vq + j];
+            });
         }
-    }
+        __syncthreads();
+        if constexpr (H == 2) {
+            if (half == 0) {
+                static_for<TW * CB * 4>([&](auto ec) {
+                    constexpr int t = decltype(ec)::value / (CB * 4), c = (decltype(ec)::value / 4) % CB, j = decltype(ec)::value % 4;
+                    if (wave + 4 * t < NN) lds[cell(t, c, j)] += acc[t][c][4 * vq + j];
+                });
+            }
+            __syncthreads();
+        }
+        for (int i = tid; i < 8 * CI_T * NN; i += THREADS) {
+            const int co8 = i / (CI_T * NN), e = i - co8 * (CI_T * NN);
+            const int ci_l = e / NN, uv = e - ci_l * NN;
+            const int co = co0 + 8 * vq + co8;
+            if (co < p.Cout && e < run) o[((size_t)co * p.Cin + ci0) * NN + e] = lds[(co8 * CI_T + ci_l) * NP + uv];
+        }
+        if constexpr (vq < 3) __syncthreads();
+    });
 }
 
 // Rows per chunk: the largest of 6, 3, 2, 1 that divides N and keeps a chunk within 18 MFMA steps
 // per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one row).
-int weight_rows(int n, int N, int cw, int cb)
+constexpr size_t W_LDS_MAX = 96 * 1024;
+
+int weight_rows(int n, int N, int cw, int cb, int halves)
 {
-    if (n < 3 || cw > 10) return 1;
-    const int cands[3] = {6, 3, 2};
+    if (halves == 1 && (n < 3 || cw > 10)) return 1;
+    const int cands[4] = {6, 4, 3, 2};
     for (int c : cands) {
+        if (c % halves != 0 || (c == 4 && halves == 1)) continue;
         const int gr = n + 2 * (c - 1), gl = 2 * cw + n - 2;
         const size_t lds = 2 * ((size_t)W_T * cb * (c * cw + 1) + (size_t)W_T * (gr * gl + 1) + W_DUMP) * sizeof(float);
-        if (N % c == 0 && c * (cw / 2) <= 18 && lds <= 64 * 1024) return c;
+        if (N % c == 0 && (c / halves) * (cw / 2) <= (halves == 2 ? 8 : 18) && lds <= (halves == 2 ? W_LDS_MAX : 64 * 1024))
+            return c;
     }
-    return 1;
+    return halves == 2 ? 0 : 1;
 }
 
 BwdWParams plan_w(const Shape &s)
@@ -815,7 +851,14 @@ BwdWParams plan_w(const Shape &s)
     // copy's wider rows.
     p.Mfs = p.Mf > 2 * p.ccs * p.cw + 2 * p.q + s.n - 2 ? p.Mf : 2 * p.ccs * p.cw + 2 * p.q + s.n - 2;
     p.cb = s.Cin > W_T ? 2 : 1;
-    p.rows = weight_rows(s.n, p.N, p.cw, p.cb);
+    // Two quartets where the tile has two channel blocks, an even number of rows fits a chunk and
+    // two waves' accumulators fit a SIMD's registers (kernels up to 4 x 4: 128 of 256 each).
+    p.halves = p.cb == 2 && s.n >= 2 && s.n <= 4 ? 2 : 1;
+    p.rows = weight_rows(s.n, p.N, p.cw, p.cb, p.halves);
+    if (p.rows == 0) {
+        p.halves = 1;
+        p.rows = weight_rows(s.n, p.N, p.cw, p.cb, 1);
+    }
     const int gr = s.n + 2 * (p.rows - 1);
     p.is = p.rows * p.cw + 1;                          // (the kernel derives the same LDS geometry from cw and rows)
     p.gl = 2 * p.cw + s.n - 2;
@@ -846,34 +889,54 @@ BwdWParams plan_w(const Shape &s)
 
 size_t lds_bytes_w(const BwdWParams &p)
 {
-    return 2 * ((size_t)W_T * p.cb * p.is + (size_t)W_T * p.gs + W_DUMP) * sizeof(float);
+    const size_t stages = 2 * ((size_t)W_T * p.cb * p.is + (size_t)W_T * p.gs + W_DUMP) * sizeof(float);
+    const size_t epilogue = (size_t)8 * W_T * p.cb * ((p.n * p.n) | 1) * sizeof(float);      // eight output channels of the tile
+    return stages > epilogue ? stages : epilogue;
 }
 
-template <int n, int KS, int R>
-hipError_t launch_w_r(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
+template <int n, int KS, int R, int CB, int H>
+hipError_t launch_w_k(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
-    if (p.cb == 2)
-        hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, 2>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in,
-                           g, dst, p);
-    else
-        hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, 1>), dim3(blocks), dim3(256), lds_bytes_w(p), stream, in,
-                           g, dst, p);
+    const size_t lds = lds_bytes_w(p);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_weight_f32_kernel<n, KS, R, CB, H>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, CB, H>), dim3(blocks), dim3(256 * H), lds, stream, in, g, dst,
+                       p);
     return hipGetLastError();
 }
 
+// The instantiations weight_rows can ask for: one quartet with 1, 2, 3 or 6 rows (several rows
+// only for 3 x 3 and larger kernels with at most 10 positions per row), two quartets (two channel
+// blocks) with 2, 4 or 6 rows.
 template <int n, int KS>
 hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
-    if constexpr (n >= 3 && KS <= 5) {               // the shapes weight_rows gives several rows
-        if (p.rows == 6) {
-            if constexpr (6 * KS <= 18) return launch_w_r<n, KS, 6>(in, g, dst, p, stream);
+    if (p.halves == 2) {
+        if constexpr (n >= 2 && n <= 4) {
+            if (p.cb != 2) return hipErrorInvalidValue;
+            if constexpr (3 * KS <= 8)
+                if (p.rows == 6) return launch_w_k<n, KS, 6, 2, 2>(in, g, dst, p, stream);
+            if constexpr (2 * KS <= 8)
+                if (p.rows == 4) return launch_w_k<n, KS, 4, 2, 2>(in, g, dst, p, stream);
+            if (p.rows == 2) return launch_w_k<n, KS, 2, 2, 2>(in, g, dst, p, stream);
         }
-        if (p.rows == 3) return launch_w_r<n, KS, 3>(in, g, dst, p, stream);
-        if (p.rows == 2) return launch_w_r<n, KS, 2>(in, g, dst, p, stream);
+        return hipErrorInvalidValue;
+    }
+    if constexpr (n >= 3 && KS <= 5) {
+        if constexpr (6 * KS <= 18)
+            if (p.rows == 6)
+                return p.cb == 2 ? launch_w_k<n, KS, 6, 2, 1>(in, g, dst, p, stream) : launch_w_k<n, KS, 6, 1, 1>(in, g, dst, p, stream);
+        if (p.rows == 3)
+            return p.cb == 2 ? launch_w_k<n, KS, 3, 2, 1>(in, g, dst, p, stream) : launch_w_k<n, KS, 3, 1, 1>(in, g, dst, p, stream);
+        if (p.rows == 2)
+            return p.cb == 2 ? launch_w_k<n, KS, 2, 2, 1>(in, g, dst, p, stream) : launch_w_k<n, KS, 2, 1, 1>(in, g, dst, p, stream);
     }
     if (p.rows != 1) return hipErrorInvalidValue;
-    return launch_w_r<n, KS, 1>(in, g, dst, p, stream);
+    return p.cb == 2 ? launch_w_k<n, KS, 1, 2, 1>(in, g, dst, p, stream) : launch_w_k<n, KS, 1, 1, 1>(in, g, dst, p, stream);
 }
 
 template <int n>
@@ -904,7 +967,7 @@ bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt)
     // (the staging lists hold byte offsets inside one batch item in 32 bits)
     if ((size_t)s.Cout * p.Mf * p.Mfs * sizeof(float) >= 0xffffffffu) return false;
     if ((size_t)s.Cin * s.N * s.N * sizeof(float) >= 0xffffffffu) return false;
-    if (lds_bytes_w(p) > 64 * 1024) return false;
+    if (lds_bytes_w(p) > W_LDS_MAX) return false;
     if ((size_t)p.tiles_ci * p.tiles_co * p.splits >= 0x7fffffffu) return false;
     return true;
 }
