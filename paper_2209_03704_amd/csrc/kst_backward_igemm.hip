@@ -482,7 +482,9 @@ hipError_t launch_vec_n(const float *g, const float *w, float *dst, const BwdPar
 bool backward_input_igemm_supported(const Shape &s, kst_dtype dt)
 {
     if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
-    if (s.Cin < 8 || s.Cout < 8) return false;
+    // at least 8 channels on either side, or a wide input with a few output channels (a
+    // generator's last layer: the reduction is short, the tile of 128 input channels is full)
+    if (s.Cin < 8 || (s.Cout < 8 && !(s.Cin >= 64 && s.Cout >= 2))) return false;
     const BwdParams p = plan(s);
     if ((size_t)B_KC * p.lrows * p.Wl > (size_t)B_THREADS * B_PX) return false;
     if (lds_bytes(p) > 160 * 1024) return false;
@@ -557,6 +559,7 @@ namespace {
 constexpr int W_T = 32;          // output channels per workgroup; input channels: W_T per block, 1 or 2 blocks
 constexpr int W_CW = 16;         // positions per chunk at most
 constexpr int W_DUMP = 32;       // floats at the end of an LDS stage that nothing reads
+constexpr int W_FOLD_CO = 8;     // output channels at most where (channel, kernel element) pairs are the GEMM's rows
 
 struct BwdWParams {
     int B, Cin, Cout, M, n;
@@ -570,6 +573,9 @@ struct BwdWParams {
     int tiles_co, tiles_ci;
     int cb;                // blocks of 32 input channels per workgroup
     int halves;            // wave quartets per workgroup
+    int co_fast;           // the output-channel tile index runs faster than the input-channel one
+    int fold, gc;          // rows are (channel, kernel element) pairs; channels of g staged per chunk
+    int slices;            // partial results written (1: the result itself)
     size_t out_elems;
 };
 
@@ -585,13 +591,19 @@ struct BwdWParams {
 // H: wave quartets per workgroup.  With two, each takes half of a chunk's R rows for all taps
 // (two waves per SIMD: one multiplies while the other stages or waits), and the second quartet's
 // sums are added to the first's through LDS at the end.
-template <int n, int KS, int R, int CB, int H>
+// FOLD: layers with few output channels (Cout * n * n <= 128).  The GEMM's rows are the pairs
+// (output channel, kernel element) instead of the output channels with one GEMM per kernel
+// element: row block w (32 rows) belongs to wave w, a lane's A operand comes from its own channel
+// and tap of the staged g, W_FOLD_CO channels of g are staged, every quartet writes a partial
+// result of its own (slot split * H + quartet), straight from the registers (dw is small).
+template <int n, int KS, int R, int CB, int H, bool FOLD>
 __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ gf,
                                                                   float *__restrict__ dst, BwdWParams p)
 {
     constexpr int NN = n * n;
-    constexpr int TW = (NN + 3) / 4;                             // taps per wave at most
+    constexpr int TW = FOLD ? 1 : (NN + 3) / 4;                  // taps (row blocks) per wave at most
+    constexpr int GC = FOLD ? W_FOLD_CO : W_T;                   // channels of g staged per chunk
     constexpr int THREADS = 256 * H;
     constexpr int RH = R / H;                                    // rows per quartet
     static_assert(R % H == 0, "rows split evenly");
@@ -602,13 +614,17 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     constexpr int GS = GR * GL + ((GR * GL) % 2 == 0 ? 1 : 0);
     extern __shared__ __attribute__((aligned(16))) float lds[];
     constexpr int CI_T = W_T * CB;                               // input channels per workgroup
-    constexpr int stage = CI_T * IS + W_T * GS + W_DUMP;         // floats per stage: [CI_T][R][CW], [W_T][GR][GL], dump cells
+    constexpr int stage = CI_T * IS + GC * GS + W_DUMP;          // floats per stage: [CI_T][R][CW], [GC][GR][GL], dump cells
 
+    // Consecutive workgroups go to consecutive XCDs, each with an L2 of its own.  The split index
+    // runs fastest (different splits read different positions of both operands), then the tile
+    // index of the larger operand: what one XCD reads of it, the others do not.
     unsigned id = blockIdx.x;
-    const int tile_ci = (int)(id % (unsigned)p.tiles_ci);
-    id /= (unsigned)p.tiles_ci;
-    const int tile_co = (int)(id % (unsigned)p.tiles_co);
-    const int split = (int)(id / (unsigned)p.tiles_co);
+    const int split = (int)(id % (unsigned)p.splits);
+    id /= (unsigned)p.splits;
+    const unsigned fast = p.co_fast ? p.tiles_co : p.tiles_ci;
+    const int t_fast = (int)(id % fast), t_slow = (int)(id / fast);
+    const int tile_co = p.co_fast ? t_fast : t_slow, tile_ci = p.co_fast ? t_slow : t_fast;
     const int co0 = tile_co * W_T, ci0 = tile_ci * CI_T;
 
     const int tid = threadIdx.x;
@@ -622,7 +638,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     // position; it is dropped (zero) when column c0 + cc is past the row.  g element (co, lr, lc):
     // row 2 a0 + lr and column 2 c0 + lc of the framed copy.  A lane past the lists, or a channel
     // past the tensor, repeats channel 0: what it stages is read by no stored output.
-    constexpr int n_in = CI_T * R * CW, n_g = W_T * GR * GL;
+    constexpr int n_in = CI_T * R * CW, n_g = GC * GR * GL;
     constexpr int NI = (n_in + THREADS - 1) / THREADS, NG = (n_g + THREADS - 1) / THREADS;
     constexpr int ITEMS = NI + NG;
     unsigned i_off[NI], g_off[NG];                               // byte offsets
@@ -665,9 +681,16 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        const int uv = min(wave + 4 * t, NN - 1);                // (a tap past the last is not multiplied)
-        const int u = uv / n, v = uv - u * n;
-        abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
+        if constexpr (FOLD) {
+            const int j = min(32 * wave + l32, p.Cout * NN - 1);  // (a row past the last repeats it and is not stored)
+            const int co = j / NN, uv = j - co * NN;
+            const int u = uv / n, v = uv - u * n;
+            abase[t] = CI_T * IS + co * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
+        } else {
+            const int uv = min(wave + 4 * t, NN - 1);            // (a tap past the last is not multiplied)
+            const int u = uv / n, v = uv - u * n;
+            abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
+        }
     }
 
     // Staging runs through registers, two chunks ahead: while chunk ch is multiplied the registers
@@ -732,7 +755,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     // it takes beyond the first one's run time: the items are dealt out over the MFMAs of the taps
     // every wave has (the last tap may belong to fewer waves).  1 x 1 kernels have no such tap
     // (one wave multiplies): there the items go in one block.
-    constexpr int TS = NN % 4 == 0 ? TW : TW - 1;
+    constexpr int TS = FOLD ? 0 : NN % 4 == 0 ? TW : TW - 1;
     constexpr int SLOTS = TS > 0 ? RH * TS * KS * CB : 1;
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
@@ -758,7 +781,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
             if constexpr (TS == 0 && r == RH / 2 && t == 0)
                 static_for<ITEMS>([&](auto jc) { put(decltype(jc)::value, other); get(decltype(jc)::value); });
             // every wave has taps 0 .. TS - 1; the last one only while wave + 4 (TW - 1) < NN
-            if (t < TS || wave + 4 * t < NN) {
+            if (FOLD ? 32 * wave < p.Cout * NN : (t < TS || wave + 4 * t < NN)) {
                 static_for<KS * CB>([&](auto mc) {
                     constexpr int k = decltype(mc)::value / CB, c = decltype(mc)::value % CB;
                     acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[c][k], acc[t][c], 0, 0, 0);
@@ -786,6 +809,21 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     // runs, consecutive lanes writing consecutive floats.  (Straight from the registers a lane's
     // stores lie n * n floats apart: 35-45 us of the 4 x 4 generator layers' 210-220 us.)
     // With two quartets the second one writes its sums first and the first adds its own.
+    if constexpr (FOLD) {
+        // acc[0][c][v]: row 32 wave + 8 (v / 4) + 4 kk + v % 4 = (co, kernel element), input channel ci0 + 32 c + l32
+        float *of = dst + (size_t)(split * H + half) * p.out_elems;
+#pragma unroll
+        for (int c = 0; c < CB; ++c) {
+            const int ci = ci0 + c * W_T + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int j = 32 * wave + 8 * (v >> 2) + 4 * kk + (v & 3);
+                const int co = j / NN, uv = j - co * NN;
+                if (j < p.Cout * NN && ci < p.Cin) of[((size_t)co * p.Cin + ci) * NN + uv] = acc[0][c][v];
+            }
+        }
+        return;
+    }
     constexpr int NP = NN | 1;                                   // odd stride between a channel's taps in LDS
     float *o = dst + (size_t)split * p.out_elems;
     const int run = min(CI_T, p.Cin - ci0) * NN;                 // floats of one output channel's run
@@ -822,14 +860,17 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
 // per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one row).
 constexpr size_t W_LDS_MAX = 96 * 1024;
 
-int weight_rows(int n, int N, int cw, int cb, int halves)
+// Few output channels, many input channels (a generator's last layer).
+bool weight_folds(const Shape &s) { return s.Cout < 8 && s.Cout * s.n * s.n <= 128 && s.Cin >= 64; }
+
+int weight_rows(int n, int N, int cw, int cb, int halves, int gc)
 {
     if (halves == 1 && (n < 3 || cw > 10)) return 1;
     const int cands[4] = {6, 4, 3, 2};
     for (int c : cands) {
         if (c % halves != 0 || (c == 4 && halves == 1)) continue;
         const int gr = n + 2 * (c - 1), gl = 2 * cw + n - 2;
-        const size_t lds = 2 * ((size_t)W_T * cb * (c * cw + 1) + (size_t)W_T * (gr * gl + 1) + W_DUMP) * sizeof(float);
+        const size_t lds = 2 * ((size_t)W_T * cb * (c * cw + 1) + (size_t)gc * (gr * gl + 1) + W_DUMP) * sizeof(float);
         if (N % c == 0 && (c / halves) * (cw / 2) <= (halves == 2 ? 8 : 18) && lds <= (halves == 2 ? W_LDS_MAX : 64 * 1024))
             return c;
     }
@@ -854,58 +895,64 @@ BwdWParams plan_w(const Shape &s)
     // Two quartets where the tile has two channel blocks, an even number of rows fits a chunk and
     // two waves' accumulators fit a SIMD's registers (kernels up to 4 x 4: 128 of 256 each).
     p.halves = p.cb == 2 && s.n >= 2 && s.n <= 4 ? 2 : 1;
-    p.rows = weight_rows(s.n, p.N, p.cw, p.cb, p.halves);
+    p.fold = weight_folds(s) ? 1 : 0;
+    p.gc = p.fold ? W_FOLD_CO : W_T;
+    p.rows = weight_rows(s.n, p.N, p.cw, p.cb, p.halves, p.gc);
     if (p.rows == 0) {
         p.halves = 1;
-        p.rows = weight_rows(s.n, p.N, p.cw, p.cb, 1);
+        p.rows = p.fold ? 1 : weight_rows(s.n, p.N, p.cw, p.cb, 1, p.gc);
+    } else if (p.fold && p.halves == 1) {
+        p.rows = 1;
     }
     const int gr = s.n + 2 * (p.rows - 1);
     p.is = p.rows * p.cw + 1;                          // (the kernel derives the same LDS geometry from cw and rows)
     p.gl = 2 * p.cw + s.n - 2;
     p.gs = gr * p.gl + ((gr * p.gl) % 2 == 0 ? 1 : 0);
     p.nchunks = s.B * (p.N / p.rows) * p.ccs;
-    p.tiles_co = (s.Cout + W_T - 1) / W_T;
+    p.tiles_co = p.fold ? 1 : (s.Cout + W_T - 1) / W_T;
     p.tiles_ci = (s.Cin + W_T * p.cb - 1) / (W_T * p.cb);
     p.out_elems = (size_t)s.Cout * s.Cin * s.n * s.n;
+    p.co_fast = (double)s.Cout * p.Mf * p.Mfs >= (double)s.Cin * p.N * p.N ? 1 : 0;
     // Split count: the workgroups a CU holds at a time (by their registers) times 256 run together;
     // cost = rounds x chunks per split x the time of a chunk, plus the traffic of the partial sums.
     const int tiles = p.tiles_co * p.tiles_ci;
     // (two-block tiles: counted as one per CU, the setting that measured best)
     const int per_cu = p.cb == 2 ? 1 : s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
-    const int taps_per_wave = (s.n * s.n + 3) / 4;
+    const int taps_per_wave = p.fold ? 1 : (s.n * s.n + 3) / 4;
     const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * taps_per_wave * p.cb * 64.0 / 2.1e9 / 0.45;
     const double out_b = (double)p.out_elems * 4.0;
     int splits = 1;
     double best = 1e30;
-    for (int c = 1; c <= 64 && c <= (p.nchunks + 3) / 4; ++c) {
+    for (int c = 1; c <= (p.fold ? 1024 : 64) && c <= (p.nchunks + 3) / 4; ++c) {
         const double rounds = (double)(((size_t)tiles * c + 256 * per_cu - 1) / (256 * per_cu));
         const double t = rounds * ((p.nchunks + c - 1) / c) * chunk_s + (c > 1 ? (c + 1) * out_b / 4.0e12 : 0.0);
         if (t < best) { best = t; splits = c; }
     }
     p.chunks_per_split = (p.nchunks + splits - 1) / splits;
     p.splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    p.slices = p.splits * (p.fold ? p.halves : 1);
     return p;
 }
 
 size_t lds_bytes_w(const BwdWParams &p)
 {
-    const size_t stages = 2 * ((size_t)W_T * p.cb * p.is + (size_t)W_T * p.gs + W_DUMP) * sizeof(float);
-    const size_t epilogue = (size_t)8 * W_T * p.cb * ((p.n * p.n) | 1) * sizeof(float);      // eight output channels of the tile
+    const size_t stages = 2 * ((size_t)W_T * p.cb * p.is + (size_t)p.gc * p.gs + W_DUMP) * sizeof(float);
+    const size_t epilogue = p.fold ? 0 : (size_t)8 * W_T * p.cb * ((p.n * p.n) | 1) * sizeof(float);      // eight output channels of the tile
     return stages > epilogue ? stages : epilogue;
 }
 
-template <int n, int KS, int R, int CB, int H>
+template <int n, int KS, int R, int CB, int H, bool FOLD = false>
 hipError_t launch_w_k(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)p.tiles_ci * p.tiles_co * p.splits;
     const size_t lds = lds_bytes_w(p);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_weight_f32_kernel<n, KS, R, CB, H>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_weight_f32_kernel<n, KS, R, CB, H, FOLD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, CB, H>), dim3(blocks), dim3(256 * H), lds, stream, in, g, dst,
-                       p);
+    hipLaunchKernelGGL((backward_weight_f32_kernel<n, KS, R, CB, H, FOLD>), dim3(blocks), dim3(256 * H), lds, stream, in, g,
+                       dst, p);
     return hipGetLastError();
 }
 
@@ -915,6 +962,21 @@ hipError_t launch_w_k(const float *in, const float *g, float *dst, const BwdWPar
 template <int n, int KS>
 hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
+    if (p.fold) {                                    // two channel blocks; two quartets, or one with one row
+        if (p.cb != 2) return hipErrorInvalidValue;
+        if (p.halves == 2) {
+            if constexpr (n >= 2 && n <= 4) {
+                if constexpr (3 * KS <= 8)
+                    if (p.rows == 6) return launch_w_k<n, KS, 6, 2, 2, true>(in, g, dst, p, stream);
+                if constexpr (2 * KS <= 8)
+                    if (p.rows == 4) return launch_w_k<n, KS, 4, 2, 2, true>(in, g, dst, p, stream);
+                if (p.rows == 2) return launch_w_k<n, KS, 2, 2, 2, true>(in, g, dst, p, stream);
+            }
+            return hipErrorInvalidValue;
+        }
+        if (p.rows != 1) return hipErrorInvalidValue;
+        return launch_w_k<n, KS, 1, 2, 1, true>(in, g, dst, p, stream);
+    }
     if (p.halves == 2) {
         if constexpr (n >= 2 && n <= 4) {
             if (p.cb != 2) return hipErrorInvalidValue;
@@ -962,7 +1024,7 @@ hipError_t launch_w(const float *in, const float *g, float *dst, const BwdWParam
 bool backward_weight_igemm_supported(const Shape &s, kst_dtype dt)
 {
     if (dt != KST_F32 || s.n < 1 || s.n > 5) return false;
-    if (s.Cin < 8 || s.Cout < 8) return false;
+    if ((s.Cin < 8 || s.Cout < 8) && !weight_folds(s)) return false;
     const BwdWParams p = plan_w(s);
     // (the staging lists hold byte offsets inside one batch item in 32 bits)
     if ((size_t)s.Cout * p.Mf * p.Mfs * sizeof(float) >= 0xffffffffu) return false;
@@ -982,7 +1044,7 @@ void backward_weight_igemm_g_copy(const Shape &s, int *frame, int *row_stride)
 size_t backward_weight_igemm_workspace_bytes(const Shape &s)
 {
     const BwdWParams p = plan_w(s);
-    return p.splits > 1 ? (((size_t)p.splits * p.out_elems * sizeof(float) + 255) & ~(size_t)255) : 0;
+    return p.slices > 1 ? (((size_t)p.slices * p.out_elems * sizeof(float) + 255) & ~(size_t)255) : 0;
 }
 
 hipError_t launch_backward_weight_igemm(const float *in, const float *g_framed, float *dw, void *ws, const Shape &s,
@@ -991,7 +1053,7 @@ hipError_t launch_backward_weight_igemm(const float *in, const float *g_framed, 
     const float *g = g_framed;
     if (!backward_weight_igemm_supported(s, KST_F32)) return hipErrorInvalidValue;
     const BwdWParams p = plan_w(s);
-    float *dst = p.splits > 1 ? (float *)ws : dw;
+    float *dst = p.slices > 1 ? (float *)ws : dw;
     hipError_t e;
     switch (s.n) {
         case 1: e = launch_w<1>(in, g, dst, p, stream); break;
@@ -1002,7 +1064,7 @@ hipError_t launch_backward_weight_igemm(const float *in, const float *g_framed, 
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, dw, p.out_elems, p.splits, stream);
+    if (p.slices > 1) e = launch_splitk_reduce((const float *)ws, dw, p.out_elems, p.slices, stream);
     return e;
 }
 

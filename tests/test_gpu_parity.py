@@ -605,6 +605,9 @@ def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     (1, 48, 4, 4, 7, 0),       # 7 x 7: one output channel per wave
     (3, 9, 12, 11, 4, 3),      # input gradient in several passes of 4 output channels, ragged channel group
     (1, 20, 6, 9, 6, 0),
+    (3, 100, 7, 9, 2, 1),      # matrix cores with (channel, kernel element) rows: odd map, one row per chunk
+    (2, 96, 3, 12, 3, 2),      # ... two quartets, six rows per chunk
+    (2, 64, 6, 16, 4, 0),      # ... 96 rows in three waves
 ])
 def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
     layer = wl.Layer("grad_few", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
