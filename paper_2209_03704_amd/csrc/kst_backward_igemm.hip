@@ -868,7 +868,8 @@ int weight_rows(int n, int N, int cw, int cb, int halves, int gc)
     if (halves == 1 && (n < 3 || cw > 10)) return 1;
     const int cands[4] = {6, 4, 3, 2};
     for (int c : cands) {
-        if (c % halves != 0 || (c == 4 && halves == 1)) continue;
+        // (6 rows on two quartets would need rows of at most 4 positions, which 6 does not divide)
+        if (c % halves != 0 || (c == 4 && halves == 1) || (c == 6 && halves == 2)) continue;
         const int gr = n + 2 * (c - 1), gl = 2 * cw + n - 2;
         const size_t lds = 2 * ((size_t)W_T * cb * (c * cw + 1) + (size_t)gc * (gr * gl + 1) + W_DUMP) * sizeof(float);
         if (N % c == 0 && (c / halves) * (cw / 2) <= (halves == 2 ? 8 : 18) && lds <= (halves == 2 ? W_LDS_MAX : 64 * 1024))
@@ -958,16 +959,14 @@ hipError_t launch_w_k(const float *in, const float *g, float *dst, const BwdWPar
 
 // The instantiations weight_rows can ask for: one quartet with 1, 2, 3 or 6 rows (several rows
 // only for 3 x 3 and larger kernels with at most 10 positions per row), two quartets (two channel
-// blocks) with 2, 4 or 6 rows.
+// blocks) with 2 or 4 rows.
 template <int n, int KS>
 hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWParams &p, hipStream_t stream)
 {
-    if (p.fold) {                                    // two channel blocks; two quartets, or one with one row
+    if (p.fold) {                                    // two channel blocks; two quartets (2 or 4 rows), or one with one row
         if (p.cb != 2) return hipErrorInvalidValue;
         if (p.halves == 2) {
             if constexpr (n >= 2 && n <= 4) {
-                if constexpr (3 * KS <= 8)
-                    if (p.rows == 6) return launch_w_k<n, KS, 6, 2, 2, true>(in, g, dst, p, stream);
                 if constexpr (2 * KS <= 8)
                     if (p.rows == 4) return launch_w_k<n, KS, 4, 2, 2, true>(in, g, dst, p, stream);
                 if (p.rows == 2) return launch_w_k<n, KS, 2, 2, 2, true>(in, g, dst, p, stream);
@@ -980,8 +979,6 @@ hipError_t launch_w_ks(const float *in, const float *g, float *dst, const BwdWPa
     if (p.halves == 2) {
         if constexpr (n >= 2 && n <= 4) {
             if (p.cb != 2) return hipErrorInvalidValue;
-            if constexpr (3 * KS <= 8)
-                if (p.rows == 6) return launch_w_k<n, KS, 6, 2, 2>(in, g, dst, p, stream);
             if constexpr (2 * KS <= 8)
                 if (p.rows == 4) return launch_w_k<n, KS, 4, 2, 2>(in, g, dst, p, stream);
             if (p.rows == 2) return launch_w_k<n, KS, 2, 2, 2>(in, g, dst, p, stream);

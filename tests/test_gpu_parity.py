@@ -575,6 +575,8 @@ def test_gradients(B, Cin, Cout, N, n, P, dtype):
     (1, 128, 128, 64, 4, 2),   # one row pair per tile
     (8, 40, 48, 4, 4, 2),      # 4 x 4 maps (a generator's first layers): the kernel gradient takes a whole framed map per chunk
     (3, 16, 24, 6, 5, 0),      # 5 x 5 kernel on 6 x 6 maps: three rows per chunk
+    (2, 48, 16, 8, 3, 0),      # two channel blocks, two wave quartets, four rows of 8 per chunk
+    (2, 80, 9, 18, 2, 1),      # ... rows of 18 cut 10 + 8, two rows per chunk, odd padding factor
 ])
 def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     """fp32 layers with at least 8 channels on either side take the MFMA gradient kernels."""
@@ -606,8 +608,9 @@ def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     (3, 9, 12, 11, 4, 3),      # input gradient in several passes of 4 output channels, ragged channel group
     (1, 20, 6, 9, 6, 0),
     (3, 100, 7, 9, 2, 1),      # matrix cores with (channel, kernel element) rows: odd map, one row per chunk
-    (2, 96, 3, 12, 3, 2),      # ... two quartets, six rows per chunk
+    (2, 96, 3, 12, 3, 2),      # ... two quartets, two rows of 12 per chunk
     (2, 64, 6, 16, 4, 0),      # ... 96 rows in three waves
+    (2, 64, 3, 6, 1, 0),       # ... 1 x 1 kernels: the rows are the output channels
 ])
 def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
     layer = wl.Layer("grad_few", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
