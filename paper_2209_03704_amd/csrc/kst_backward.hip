@@ -87,21 +87,24 @@ __global__ void __launch_bounds__(256) backward_weight_generic_kernel(const T *_
 
 // Kernel sizes up to 7, any channel counts: the same sums with register blocking.
 //
-// Kernel gradient: a workgroup owns one input channel, CO output channels (n*n*CO <= 64) and a
-// slice of the positions; a lane keeps all n*n*CO partial sums in registers, so an input value is
-// loaded once for n*n*CO products and nothing is re-read per kernel element.  The partial sums
-// are added across the lanes with wave shuffles, across the four waves through LDS.
-template <int n, int CO, typename T>
+// Kernel gradient: a workgroup owns CI input channels, CO output channels (n*n*CO <= 64; more than
+// one input channel only with CO = 1, n*n*CI <= 100) and a slice of the positions; a lane keeps
+// all n*n*CO*CI partial sums in registers, so an input value is loaded once for n*n*CO products, a
+// value of g once for CI, and nothing is re-read per kernel element.  The partial sums are added
+// across the lanes with wave shuffles, across the four waves through LDS.
+template <int n, int CO, int CI, typename T>
 __global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__restrict__ in, const float *__restrict__ g,
                                                                     float *__restrict__ dst, int B, int Cin, int Cout,
                                                                     int N, int M, int per_slice)
 {
     constexpr int NN = n * n;
-    __shared__ float red[4][NN * CO];
+    constexpr int S = NN * CO * CI;                               // sums per lane
+    __shared__ float red[4][S];
     const int groups = Cout / CO;                                 // CO divides Cout
+    const int cigs = (Cin + CI - 1) / CI;
     unsigned id = blockIdx.x;
-    const int ci = (int)(id % (unsigned)Cin);
-    id /= (unsigned)Cin;
+    const int ci0 = (int)(id % (unsigned)cigs) * CI;
+    id /= (unsigned)cigs;
     const int co0 = (int)(id % (unsigned)groups) * CO;
     const int slice = (int)(id / (unsigned)groups);
     const int tid = threadIdx.x;
@@ -109,16 +112,21 @@ __global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__re
     const int total = B * per_item;
     const int e_begin = slice * per_slice, e_end = min(total, e_begin + per_slice);
 
-    float acc[CO][NN];
+    float acc[CI][CO][NN];
 #pragma unroll
-    for (int k = 0; k < CO; ++k)
+    for (int q = 0; q < CI; ++q)
 #pragma unroll
-        for (int t = 0; t < NN; ++t) acc[k][t] = 0.0f;
+        for (int k = 0; k < CO; ++k)
+#pragma unroll
+            for (int t = 0; t < NN; ++t) acc[q][k][t] = 0.0f;
 
     for (int e = e_begin + tid; e < e_end; e += 256) {
         const int b = e / per_item, rem = e - b * per_item;
         const int a = rem / N, c = rem - a * N;
-        const float xin = to_f32(in[(((size_t)b * Cin + ci) * N + a) * N + c]);
+        float xin[CI];
+#pragma unroll
+        for (int q = 0; q < CI; ++q)
+            xin[q] = ci0 + q < Cin ? to_f32(in[(((size_t)b * Cin + ci0 + q) * N + a) * N + c]) : 0.0f;
         const float *gp = g + ((size_t)b * Cout + co0) * M * M;
 #pragma unroll
         for (int u = 0; u < n; ++u) {
@@ -129,27 +137,33 @@ __global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__re
                 const int x = 2 * c - v;
                 if (x < 0 || x >= M) continue;
 #pragma unroll
-                for (int k = 0; k < CO; ++k)
-                    acc[k][u * n + v] = fmaf(xin, gp[((size_t)k * M + y) * M + x], acc[k][u * n + v]);
+                for (int k = 0; k < CO; ++k) {
+                    const float gv = gp[((size_t)k * M + y) * M + x];
+#pragma unroll
+                    for (int q = 0; q < CI; ++q) acc[q][k][u * n + v] = fmaf(xin[q], gv, acc[q][k][u * n + v]);
+                }
             }
         }
     }
 
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-    for (int k = 0; k < CO; ++k)
+    for (int q = 0; q < CI; ++q)
 #pragma unroll
-        for (int t = 0; t < NN; ++t) {
-            float v = acc[k][t];
+        for (int k = 0; k < CO; ++k)
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-            if (lane == 0) red[wave][k * NN + t] = v;
-        }
+            for (int t = 0; t < NN; ++t) {
+                float v = acc[q][k][t];
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+                if (lane == 0) red[wave][(q * CO + k) * NN + t] = v;
+            }
     __syncthreads();
-    if (tid < NN * CO) {
-        const int k = tid / NN, t = tid - k * NN;
-        const float sum = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-        dst[(size_t)slice * Cout * Cin * NN + ((size_t)(co0 + k) * Cin + ci) * NN + t] = sum;
+    for (int i = tid; i < S; i += 256) {
+        const int q = i / (CO * NN), r = i - q * (CO * NN);
+        const int k = r / NN, t = r - k * NN;
+        const float sum = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
+        if (ci0 + q < Cin) dst[(size_t)slice * Cout * Cin * NN + ((size_t)(co0 + k) * Cin + ci0 + q) * NN + t] = sum;
     }
 }
 
@@ -313,13 +327,38 @@ inline int weight_co(int n, int Cout)
     return 1;
 }
 
+// Input channels per workgroup of that kernel: more than one only with a single output channel.
+inline int weight_ci(int n, int co, int Cin)
+{
+    if (co != 1) return 1;
+    int k = Cin < 4 ? Cin : 4;
+    while (k > 1 && k * n * n > 100) --k;
+    return k;
+}
+
+template <int n, int CO, int CI, typename T>
+void launch_weight_regs_ci(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
+                           hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((s.Cin + CI - 1) / CI) * (unsigned)(s.Cout / CO) * (unsigned)slices;
+    hipLaunchKernelGGL((backward_weight_regs_kernel<n, CO, CI, T>), dim3(blocks), dim3(256), 0, stream, in, g, dst, s.B,
+                       s.Cin, s.Cout, s.N, s.M, per_slice);
+}
+
 template <int n, int CO, typename T>
 void launch_weight_regs_co(const T *in, const float *g, float *dst, const Shape &s, int slices, int per_slice,
                            hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)s.Cin * (unsigned)(s.Cout / CO) * (unsigned)slices;
-    hipLaunchKernelGGL((backward_weight_regs_kernel<n, CO, T>), dim3(blocks), dim3(256), 0, stream, in, g, dst, s.B,
-                       s.Cin, s.Cout, s.N, s.M, per_slice);
+    if constexpr (CO == 1) {
+        const int ci = weight_ci(n, 1, s.Cin);
+        if constexpr (4 * n * n <= 100)
+            if (ci == 4) return launch_weight_regs_ci<n, 1, 4, T>(in, g, dst, s, slices, per_slice, stream);
+        if constexpr (3 * n * n <= 100)
+            if (ci == 3) return launch_weight_regs_ci<n, 1, 3, T>(in, g, dst, s, slices, per_slice, stream);
+        if constexpr (2 * n * n <= 100)
+            if (ci == 2) return launch_weight_regs_ci<n, 1, 2, T>(in, g, dst, s, slices, per_slice, stream);
+    }
+    launch_weight_regs_ci<n, CO, 1, T>(in, g, dst, s, slices, per_slice, stream);
 }
 
 template <int n, typename T>
@@ -429,15 +468,19 @@ int weight_lane_slices(const Shape &s)
     return slices < 1 ? 1 : (int)slices;
 }
 
-// Slices of the position range: few (co, ci) pairs alone cannot fill the chip.
+// Slices of the position range: few (co, ci) pairs alone cannot fill the chip.  About 1024
+// workgroups, at least 1024 positions per slice.
 int weight_slices(const Shape &s)
 {
     if (weight_lanes_apply(s)) return weight_lane_slices(s);
-    const long long pairs = (long long)s.Cout * s.Cin;
+    long long wgs = (long long)s.Cout * s.Cin;                     // workgroups per slice
+    if (s.n <= 7) {
+        const int co = weight_co(s.n, s.Cout), ci = weight_ci(s.n, co, s.Cin);
+        wgs = (long long)(s.Cout / co) * ((s.Cin + ci - 1) / ci);
+    }
     const long long total = (long long)s.B * s.N * s.N;
-    long long slices = (1024 + pairs - 1) / pairs;
-    if (slices > 256) slices = 256;
-    if (slices > (total + 1023) / 1024) slices = (total + 1023) / 1024;   // at least 1024 positions per slice
+    long long slices = (1024 + wgs - 1) / wgs;
+    if (slices > (total + 1023) / 1024) slices = (total + 1023) / 1024;
     return slices < 1 ? 1 : (int)slices;
 }
 

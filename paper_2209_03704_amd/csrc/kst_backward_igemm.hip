@@ -544,14 +544,15 @@ hipError_t launch_backward_input_igemm(const float *g, const float *w, float *di
 // launch function), so every tap of every position reads inside that copy and no g load needs a
 // bounds check.
 //
-// Tile: 32 co x 32 or 64 ci x all n * n taps per 256-thread workgroup; the taps are dealt over the
-// four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4) accumulators per
-// block of 32 input channels.
-// The reduction walks chunks of up to 16 consecutive positions of one input row; per chunk
-// the workgroup stages the 32 x cw inputs and the n rows x (2 cw + n - 2) columns of g the
-// chunk's taps touch for its 32 output channels.  Staging is branch-free (every lane has a fixed
-// list of elements: offset from the chunk's base address and LDS cell) and runs two chunks ahead
-// through registers into the LDS stage that is not being multiplied; one barrier per chunk.
+// Tile: 32 co x 32 or 64 ci x all n * n taps per workgroup of four or eight waves; the taps are
+// dealt over four waves (tap t goes to wave t % 4), so a wave holds at most ceil(n * n / 4)
+// accumulators per block of 32 input channels.
+// The reduction walks chunks: up to 16 consecutive positions of 1, 2, 3, 4 or 6 consecutive input
+// rows of one batch item; per chunk the workgroup stages those inputs for its input channels and
+// the rows and columns of g the chunk's taps touch for its 32 output channels.  Staging is
+// branch-free (every lane has a fixed list of elements: byte offset from the chunk's base address
+// and LDS cell) and runs two chunks ahead through registers into the LDS stage that is not being
+// multiplied; one barrier per chunk.
 // The position range is split over workgroups; the partial sums are added by the forward path's
 // reduction pass (fixed order).
 namespace {
@@ -856,13 +857,15 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     });
 }
 
-// Rows per chunk: the largest of 6, 3, 2, 1 that divides N and keeps a chunk within 18 MFMA steps
-// per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one row).
-constexpr size_t W_LDS_MAX = 96 * 1024;
+constexpr size_t W_LDS_MAX = 96 * 1024;     // LDS a workgroup of two quartets may take (one runs per CU)
 
 // Few output channels, many input channels (a generator's last layer).
 bool weight_folds(const Shape &s) { return s.Cout < 8 && s.Cout * s.n * s.n <= 128 && s.Cin >= 64; }
 
+// Rows per chunk.  One quartet: the largest of 6, 3, 2, 1 that divides N and keeps a chunk within
+// 18 MFMA steps per tap (kernels of 3 x 3 and larger with at most 10 positions per row; else one
+// row).  Two quartets: 4 or 2 rows (an even number, at most 8 steps per tap and quartet), or 0
+// when N is odd (then one quartet does the work).
 int weight_rows(int n, int N, int cw, int cb, int halves, int gc)
 {
     if (halves == 1 && (n < 3 || cw > 10)) return 1;

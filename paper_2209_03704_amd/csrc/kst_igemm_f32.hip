@@ -732,30 +732,38 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
     return e;
 }
 
-// The same sum for many partial results of a small tensor: 16 elements x 16 strided shares of the
-// partial results per workgroup, the shares added through LDS in a fixed order.
+// The same sum for many partial results of a small tensor: 256 / SH elements x SH strided shares of
+// the partial results per workgroup, the shares added through LDS in a fixed order.
+template <int SH>
 __global__ void __launch_bounds__(256) splitk_reduce_shares_kernel(const float *__restrict__ ws, float *__restrict__ out,
                                                                      size_t elems, int splits)
 {
-    __shared__ float red[16][17];
-    const int el = threadIdx.x & 15, share = threadIdx.x >> 4;
-    const size_t e = (size_t)blockIdx.x * 16u + el;
+    constexpr int EL = 256 / SH;
+    __shared__ float red[SH][EL + 1];
+    const int el = threadIdx.x % EL, share = threadIdx.x / EL;
+    const size_t e = (size_t)blockIdx.x * EL + el;
     float a = 0.0f;
     if (e < elems)
-        for (int s = share; s < splits; s += 16) a += ws[(size_t)s * elems + e];
+        for (int s = share; s < splits; s += SH) a += ws[(size_t)s * elems + e];
     red[share][el] = a;
     __syncthreads();
     if (share == 0 && e < elems) {
         float t = red[0][el];
-        for (int k = 1; k < 16; ++k) t += red[k][el];
+        for (int k = 1; k < SH; ++k) t += red[k][el];
         out[e] = t;
     }
 }
 
+// 64 and more partial results: 16 shares; 512 and more: 64 shares.
 hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream)
 {
+    if (splits >= 512) {
+        hipLaunchKernelGGL(splitk_reduce_shares_kernel<64>, dim3((unsigned)((elems + 3) / 4)), dim3(256), 0, stream, ws, out,
+                           elems, splits);
+        return hipGetLastError();
+    }
     if (splits >= 64) {
-        hipLaunchKernelGGL(splitk_reduce_shares_kernel, dim3((unsigned)((elems + 15) / 16)), dim3(256), 0, stream, ws, out,
+        hipLaunchKernelGGL(splitk_reduce_shares_kernel<16>, dim3((unsigned)((elems + 15) / 16)), dim3(256), 0, stream, ws, out,
                            elems, splits);
         return hipGetLastError();
     }
