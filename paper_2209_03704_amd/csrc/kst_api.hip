@@ -315,6 +315,7 @@ struct GradPlan {
     size_t split_bytes, wsplit_bytes; // input / kernel gradient on the matrix cores: partial sums
     size_t gw_bytes;                  // kernel gradient on the matrix cores: its framed copy of g (replaces g_bytes)
     int gw_frame, gw_stride;          // frame on the caller's g and row stride of that copy
+    bool plain_unframed;              // the other kernels work on the unframed positions too (kernels up to 7 x 7)
 };
 
 kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
@@ -334,12 +335,17 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->si = f->s;
     f->si.frame = f->q;
     f->split_bytes = 0;
+    f->plain_unframed = backward_generic_takes_frame(f->si);
     if (backward_input_igemm_supported(f->si, dt)) {
         f->split_bytes = backward_input_igemm_workspace_bytes(f->si);
         f->din_bytes = 0;                              // written in place, frame never computed
+    } else if (f->plain_unframed) {
+        f->din_bytes = 0;
     }
-    f->wsplit_bytes = backward_weight_igemm_supported(f->si, dt) ? backward_weight_igemm_workspace_bytes(f->si)
-                                                                : backward_weight_generic_workspace_bytes(f->s);
+    if (f->plain_unframed) f->in_bytes = 0;            // `in` read as it lies in memory
+    f->wsplit_bytes = backward_weight_igemm_supported(f->si, dt)
+                          ? backward_weight_igemm_workspace_bytes(f->si)
+                          : backward_weight_generic_workspace_bytes(f->plain_unframed ? f->si : f->s);
     f->gw_bytes = 0;
     f->gw_frame = f->gw_stride = 0;
     if (backward_weight_igemm_supported(f->si, dt)) {
@@ -397,6 +403,8 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
                    ? KST_OK
                    : KST_ERR_HIP;
     }
+    if (f.plain_unframed)
+        return launch_backward_input_generic(g_in, w, d_out, f.si, dtype, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;
     if (P) d_out = (float *)((char *)ws + f.g_bytes);
     if (launch_backward_input_generic(g_in, w, d_out, f.s, dtype, stream) != hipSuccess) return KST_ERR_HIP;
     if (P && launch_crop(d_out, (float *)din, B, Cin, N, f.q, stream) != hipSuccess) return KST_ERR_HIP;
@@ -422,7 +430,7 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     }
     const void *x_in = in;
     const float *g_in = (const float *)g;
-    if (P && !cores) {
+    if (P && !cores && !f.plain_unframed) {
         if (launch_frame_input(in, ws, B, Cin, N, f.q, f.Nq, dtype, stream) != hipSuccess) return KST_ERR_HIP;
         x_in = ws;
     }
@@ -441,7 +449,8 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
         if (launch_frame_input(g, gw, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
         g_in = (const float *)gw;
     }
-    return launch_backward_weight_generic(x_in, g_in, (float *)dw, partial_ws, f.s, dtype, stream) == hipSuccess
+    return launch_backward_weight_generic(x_in, g_in, (float *)dw, partial_ws, f.plain_unframed ? f.si : f.s, dtype,
+                                          stream) == hipSuccess
                ? KST_OK
                : KST_ERR_HIP;
 }

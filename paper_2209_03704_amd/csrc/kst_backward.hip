@@ -95,8 +95,10 @@ __global__ void __launch_bounds__(256) backward_weight_generic_kernel(const T *_
 template <int n, int CO, int CI, typename T>
 __global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__restrict__ in, const float *__restrict__ g,
                                                                     float *__restrict__ dst, int B, int Cin, int Cout,
-                                                                    int N, int M, int per_slice)
+                                                                    int N, int M, int q, int per_slice)
 {
+    // N: edge of `in` as it lies in memory; q: zero frame the forward put around it (its products
+    // are zeros and are skipped): position (a, c) meets g rows 2 (a + q) - u.
     constexpr int NN = n * n;
     constexpr int S = NN * CO * CI;                               // sums per lane
     __shared__ float red[4][S];
@@ -130,11 +132,11 @@ __global__ void __launch_bounds__(256) backward_weight_regs_kernel(const T *__re
         const float *gp = g + ((size_t)b * Cout + co0) * M * M;
 #pragma unroll
         for (int u = 0; u < n; ++u) {
-            const int y = 2 * a - u;
+            const int y = 2 * (a + q) - u;
             if (y < 0 || y >= M) continue;
 #pragma unroll
             for (int v = 0; v < n; ++v) {
-                const int x = 2 * c - v;
+                const int x = 2 * (c + q) - v;
                 if (x < 0 || x >= M) continue;
 #pragma unroll
                 for (int k = 0; k < CO; ++k) {
@@ -180,8 +182,9 @@ constexpr int L_BATCH = 8;
 template <int n, int CO, typename T>
 __global__ void __launch_bounds__(64) backward_weight_lanes_kernel(const T *__restrict__ in, const float *__restrict__ g,
                                                                     float *__restrict__ dst, int B, int Cin, int Cout,
-                                                                    int N, int M, int per_slice)
+                                                                    int N, int M, int q, int per_slice)
 {
+    // (N, q: as in the kernel above)
     constexpr int NN = n * n;
     constexpr int W = NN * CO;                                    // window values per position (<= 64)
     const int cgroups = (Cin + 63) / 64, groups = Cout / CO;      // CO divides Cout
@@ -216,7 +219,7 @@ __global__ void __launch_bounds__(64) backward_weight_lanes_kernel(const T *__re
                 const int b = e / per_item, rem = e - b * per_item;
                 const int a = rem / N, c = rem - a * N;
                 if (ci_ok) xin[j] = to_f32(in[(((size_t)b * Cin + ci) * N + a) * N + c]);
-                const int y = 2 * a - wu, x = 2 * c - wv;
+                const int y = 2 * (a + q) - wu, x = 2 * (c + q) - wv;
                 if (w_ok && y >= 0 && y < M && x >= 0 && x < M)
                     gv[j] = g[(((size_t)b * Cout + co0 + wk) * M + y) * M + x];
             }
@@ -237,44 +240,45 @@ __global__ void __launch_bounds__(64) backward_weight_lanes_kernel(const T *__re
     }
 }
 
-// Input gradient: a lane owns one position (a, c) of one batch item for a group of D_CIG input
+// Input gradient: a lane owns one position (a, c) of one batch item for a group of Q input
 // channels.  Per pass over CG output channels (n*n*CG <= 64) it loads the n x n window of g it
-// needs once into registers and multiplies it with the kernels of its D_CIG channels, which the
+// needs once into registers and multiplies it with the kernels of its Q channels, which the
 // workgroup has staged in LDS (the same values for every lane: 16-byte reads at one address).
-constexpr int D_CIG = 8;
-
-template <int n, int CG, typename T>
+// CG: output channels per pass; Q: input channels per workgroup (8, or 4 for layers with at most 4).
+// N: edge of din as it lies in memory; q: zero frame the forward put around the input (its
+// gradient is not wanted): position (a, c) meets g rows 2 (a + q) - u.
+template <int n, int CG, int Q, typename T>
 __global__ void __launch_bounds__(256) backward_input_regs_kernel(const float *__restrict__ g, const T *__restrict__ w,
                                                                    float *__restrict__ din, int B, int Cin, int Cout,
-                                                                   int N, int M)
+                                                                   int N, int M, int q)
 {
     constexpr int NN = n * n;
     constexpr int WPC = (NN * CG + 3) & ~3;                       // staged weights per input channel, padded
-    __shared__ __attribute__((aligned(16))) float Wl[D_CIG * WPC];
+    __shared__ __attribute__((aligned(16))) float Wl[Q * WPC];
     const int tiles = (N * N + 255) / 256;
-    const int cigs = (Cin + D_CIG - 1) / D_CIG;
+    const int cigs = (Cin + Q - 1) / Q;
     unsigned id = blockIdx.x;
     const int tile = (int)(id % (unsigned)tiles);
     id /= (unsigned)tiles;
-    const int ci0 = (int)(id % (unsigned)cigs) * D_CIG;
+    const int ci0 = (int)(id % (unsigned)cigs) * Q;
     const int b = (int)(id / (unsigned)cigs);
     const int tid = threadIdx.x;
     const int pos = tile * 256 + tid;
     const bool live = pos < N * N;
     const int a = live ? pos / N : 0, c = live ? pos - (pos / N) * N : 0;
 
-    float acc[D_CIG];
+    float acc[Q];
 #pragma unroll
-    for (int q = 0; q < D_CIG; ++q) acc[q] = 0.0f;
+    for (int j = 0; j < Q; ++j) acc[j] = 0.0f;
 
     for (int co0 = 0; co0 < Cout; co0 += CG) {
         // This pass's kernels -> LDS: [channel of the group][output channel of the pass][u][v].
         __syncthreads();                                          // the previous pass has read its weights
-        for (int e = tid; e < D_CIG * WPC; e += 256) {
-            const int q = e / WPC, rem = e - q * WPC;
+        for (int e = tid; e < Q * WPC; e += 256) {
+            const int j = e / WPC, rem = e - j * WPC;
             const int k = rem / NN, t = rem - k * NN;
             float v = 0.0f;
-            if (k < CG && co0 + k < Cout && ci0 + q < Cin) v = to_f32(w[((size_t)(co0 + k) * Cin + ci0 + q) * NN + t]);
+            if (k < CG && co0 + k < Cout && ci0 + j < Cin) v = to_f32(w[((size_t)(co0 + k) * Cin + ci0 + j) * NN + t]);
             Wl[e] = v;
         }
         // The window of g this position meets (zero outside the map and past the last channel).
@@ -287,18 +291,18 @@ __global__ void __launch_bounds__(256) backward_input_regs_kernel(const float *_
             for (int u = 0; u < n; ++u)
 #pragma unroll
                 for (int v = 0; v < n; ++v) {
-                    const int y = 2 * a - u, x = 2 * c - v;
+                    const int y = 2 * (a + q) - u, x = 2 * (c + q) - v;
                     const bool ok = k_ok && y >= 0 && y < M && x >= 0 && x < M;
                     gw[k][u * n + v] = ok ? gp[(size_t)y * M + x] : 0.0f;
                 }
         }
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < D_CIG; ++q) {
+        for (int j = 0; j < Q; ++j) {
             float wv[WPC];
 #pragma unroll
             for (int g4 = 0; g4 < WPC / 4; ++g4) {
-                const float4 v = *reinterpret_cast<const float4 *>(&Wl[q * WPC + 4 * g4]);
+                const float4 v = *reinterpret_cast<const float4 *>(&Wl[j * WPC + 4 * g4]);
                 wv[4 * g4] = v.x;
                 wv[4 * g4 + 1] = v.y;
                 wv[4 * g4 + 2] = v.z;
@@ -307,13 +311,13 @@ __global__ void __launch_bounds__(256) backward_input_regs_kernel(const float *_
 #pragma unroll
             for (int k = 0; k < CG; ++k)
 #pragma unroll
-                for (int t = 0; t < NN; ++t) acc[q] = fmaf(gw[k][t], wv[k * NN + t], acc[q]);
+                for (int t = 0; t < NN; ++t) acc[j] = fmaf(gw[k][t], wv[k * NN + t], acc[j]);
         }
     }
     if (!live) return;
 #pragma unroll
-    for (int q = 0; q < D_CIG; ++q)
-        if (ci0 + q < Cin) din[(((size_t)b * Cin + ci0 + q) * N + a) * N + c] = acc[q];
+    for (int j = 0; j < Q; ++j)
+        if (ci0 + j < Cin) din[(((size_t)b * Cin + ci0 + j) * N + a) * N + c] = acc[j];
 }
 
 // Output channels per workgroup (kernel gradient) or per pass (input gradient): the largest of
@@ -342,7 +346,7 @@ void launch_weight_regs_ci(const T *in, const float *g, float *dst, const Shape 
 {
     const unsigned blocks = (unsigned)((s.Cin + CI - 1) / CI) * (unsigned)(s.Cout / CO) * (unsigned)slices;
     hipLaunchKernelGGL((backward_weight_regs_kernel<n, CO, CI, T>), dim3(blocks), dim3(256), 0, stream, in, g, dst, s.B,
-                       s.Cin, s.Cout, s.N, s.M, per_slice);
+                       s.Cin, s.Cout, s.N - 2 * s.frame, s.M, s.frame, per_slice);
 }
 
 template <int n, int CO, typename T>
@@ -391,19 +395,37 @@ bool launch_weight_regs(const T *in, const float *g, float *dst, const Shape &s,
     }
 }
 
+// Edge of the maps as they lie in memory: the shape's edge less its virtual frame.
+inline int unframed_edge(const Shape &s) { return s.N - 2 * s.frame; }
+
+template <int n, int CG, int Q, typename T>
+void launch_input_regs_q(const float *g, const T *w, float *din, const Shape &s, hipStream_t stream)
+{
+    const int N0 = unframed_edge(s);
+    const unsigned tiles = (unsigned)((N0 * N0 + 255) / 256), cigs = (unsigned)((s.Cin + Q - 1) / Q);
+    hipLaunchKernelGGL((backward_input_regs_kernel<n, CG, Q, T>), dim3(tiles * cigs * (unsigned)s.B), dim3(256), 0,
+                       stream, g, w, din, s.B, s.Cin, s.Cout, N0, s.M, s.frame);
+}
+
+// Output channels per pass: as many as fit the registers, or one for a single-channel output;
+// input channels per workgroup: 8, or 4 for layers with at most 4.
 template <int n, typename T>
 void launch_input_regs_n(const float *g, const T *w, float *din, const Shape &s, hipStream_t stream)
 {
     constexpr int CG = regs_fit(n);
-    const unsigned tiles = (unsigned)((s.N * s.N + 255) / 256), cigs = (unsigned)((s.Cin + D_CIG - 1) / D_CIG);
-    hipLaunchKernelGGL((backward_input_regs_kernel<n, CG, T>), dim3(tiles * cigs * (unsigned)s.B), dim3(256), 0, stream,
-                       g, w, din, s.B, s.Cin, s.Cout, s.N, s.M);
+    if (s.Cout == 1 && CG > 1) {
+        if (s.Cin <= 4) return launch_input_regs_q<n, 1, 4, T>(g, w, din, s, stream);
+        return launch_input_regs_q<n, 1, 8, T>(g, w, din, s, stream);
+    }
+    if (s.Cin <= 4) return launch_input_regs_q<n, CG, 4, T>(g, w, din, s, stream);
+    launch_input_regs_q<n, CG, 8, T>(g, w, din, s, stream);
 }
 
 template <typename T>
 bool launch_input_regs(const float *g, const T *w, float *din, const Shape &s, hipStream_t stream)
 {
-    const size_t blocks = (size_t)((s.N * s.N + 255) / 256) * ((s.Cin + D_CIG - 1) / D_CIG) * s.B;
+    const int N0 = unframed_edge(s);
+    const size_t blocks = (size_t)((N0 * N0 + 255) / 256) * ((s.Cin + 3) / 4) * s.B;
     if (blocks >= 0x7fffffffu) return false;
     switch (s.n) {
         case 1: launch_input_regs_n<1, T>(g, w, din, s, stream); return true;
@@ -423,7 +445,7 @@ void launch_weight_lanes_co(const T *in, const float *g, float *dst, const Shape
 {
     const unsigned blocks = (unsigned)((s.Cin + 63) / 64) * (unsigned)(s.Cout / CO) * (unsigned)slices;
     hipLaunchKernelGGL((backward_weight_lanes_kernel<n, CO, T>), dim3(blocks), dim3(64), 0, stream, in, g, dst, s.B,
-                       s.Cin, s.Cout, s.N, s.M, per_slice);
+                       s.Cin, s.Cout, unframed_edge(s), s.M, s.frame, per_slice);
 }
 
 template <int n, typename T>
@@ -462,7 +484,7 @@ bool weight_lanes_apply(const Shape &s) { return s.n <= 7 && s.Cin >= 48; }
 int weight_lane_slices(const Shape &s)
 {
     const long long waves_per_slice = (long long)((s.Cin + 63) / 64) * (s.Cout / weight_co(s.n, s.Cout));
-    const long long total = (long long)s.B * s.N * s.N;
+    const long long total = (long long)s.B * (s.N - 2 * s.frame) * (s.N - 2 * s.frame);
     long long slices = (2048 + waves_per_slice - 1) / waves_per_slice;
     if (slices > (total + 63) / 64) slices = (total + 63) / 64;
     return slices < 1 ? 1 : (int)slices;
@@ -478,7 +500,7 @@ int weight_slices(const Shape &s)
         const int co = weight_co(s.n, s.Cout), ci = weight_ci(s.n, co, s.Cin);
         wgs = (long long)(s.Cout / co) * ((s.Cin + ci - 1) / ci);
     }
-    const long long total = (long long)s.B * s.N * s.N;
+    const long long total = (long long)s.B * (s.N - 2 * s.frame) * (s.N - 2 * s.frame);
     long long slices = (1024 + wgs - 1) / wgs;
     if (slices > (total + 1023) / 1024) slices = (total + 1023) / 1024;
     return slices < 1 ? 1 : (int)slices;
@@ -486,12 +508,21 @@ int weight_slices(const Shape &s)
 
 }  // namespace
 
+// The register-blocked kernels (n <= 7) skip a virtual frame (Shape::frame); the plain ones take
+// the framed problem as it is.
+bool backward_generic_takes_frame(const Shape &s)
+{
+    const int N0 = s.N - 2 * s.frame;
+    return s.n <= 7 && (size_t)((N0 * N0 + 255) / 256) * ((s.Cin + 3) / 4) * s.B < 0x7fffffffu;
+}
+
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream)
 {
     if (dt == KST_BF16 ? launch_input_regs<uint16_t>(g, (const uint16_t *)w, din, s, stream)
                        : launch_input_regs<float>(g, (const float *)w, din, s, stream))
         return hipGetLastError();
+    if (s.frame) return hipErrorInvalidValue;                    // the plain kernel knows no virtual frame
     const size_t total = (size_t)s.B * s.Cin * s.N * s.N;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (dt == KST_BF16)
@@ -513,7 +544,7 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
                                           kst_dtype dt, hipStream_t stream)
 {
     const int slices = weight_slices(s);
-    const int total = s.B * s.N * s.N;
+    const int total = s.B * (s.N - 2 * s.frame) * (s.N - 2 * s.frame);
     const int per_slice = (total + slices - 1) / slices;
     const unsigned blocks = (unsigned)s.Cout * (unsigned)s.Cin * (unsigned)slices;
     float *dst = slices > 1 ? (float *)ws : dw;
@@ -528,6 +559,8 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
     }
     if (regs) {
         // the register-blocked kernel has run
+    } else if (s.frame) {
+        return hipErrorInvalidValue;                             // the plain kernel knows no virtual frame
     } else if (dt == KST_BF16) {
         hipLaunchKernelGGL(backward_weight_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
                            (const uint16_t *)in, g, dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);

@@ -88,6 +88,7 @@ hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, i
                               hipStream_t stream);
 hipError_t launch_crop(const float *wide, float *out, int planes_b, int planes_c, int M, int q, hipStream_t stream);
 // Gradients, P = 0, any shape (plain ALU kernels).  g, din and dw are fp32; w and in are of type dt.
+bool backward_generic_takes_frame(const Shape &s);     // these two skip Shape::frame themselves (else: frame must be 0)
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream);
 size_t backward_weight_generic_workspace_bytes(const Shape &s);    // partial sums when the positions are sliced
