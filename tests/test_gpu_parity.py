@@ -548,6 +548,8 @@ GRAD_TOL = {"f32": 2e-5, "bf16": 2e-5}     # operands are exact in both cases; t
     (3, 8, 24, 12, 3, 4),
     (1, 40, 72, 10, 5, 0),
     (1, 2, 2, 1, 5, 2),
+    (1, 2, 3, 7, 9, 3),      # 9 x 9: the plain kernels on a framed copy, result cropped; odd padding factor
+    (2, 2, 2, 6, 8, 2),
 ])
 def test_gradients(B, Cin, Cout, N, n, P, dtype):
     layer = wl.Layer("grad", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
