@@ -180,13 +180,14 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
  * forward pass that involve an original input pixel.  w (un-segregated,
  * [Cout][Cin][n][n]) and in are of type `dtype`.  din [B][Cin][N][N] and dw
  * [Cout][Cin][n][n] are fully overwritten.  ws / ws_bytes: scratch of at least
- * kst_backward_*_workspace_bytes(...), used for framed copies as in
- * kst_forward_seg_padded (the matrix-core kernels need none of `in` and no
- * framed result: they visit the unframed positions only), for the zero-framed
- * copy of g the matrix-core
- * kernel-gradient kernel reads, and for the partial sums of split reductions
- * (the matrix-core kernels: fp32 operands, n <= 5, at least 8 channels on either
- * side; the other kernel-gradient kernels when they slice the positions); it
+ * kst_backward_*_workspace_bytes(...): for framed copies as in
+ * kst_forward_seg_padded (kernels up to 7 x 7 need none of `in` and no framed
+ * result: they visit the unframed positions only; odd P frames g by one pixel),
+ * for the zero-framed copy of g the matrix-core kernel-gradient kernel reads,
+ * and for the partial sums of split reductions (the matrix-core kernels: fp32
+ * operands, n <= 5, at least 8 channels on either side, or at least 64 input
+ * channels with a few output channels; the other kernel-gradient kernels when
+ * they slice the positions); it
  * may be 0 (then ws may be NULL).  The byte count depends
  * on the shape only, never on the pointers, as in
  * kst_forward_seg_padded.  Pointers, alignment, stream and statuses as above.
