@@ -131,3 +131,28 @@ def test_argument_errors_are_statuses_not_crashes():
     need = kst.kst_workspace_bytes_padded(2, 3, 4, 8, 3, 3, kst.KST_F32)
     assert 2 * 4 * 21 * 21 * 4 <= need < 2 * 4 * 21 * 21 * 4 + 2 * 3 * 12 * 12 * 4
     assert l.kst_forward_seg_padded(one, one, one, None, 0, 2, 3, 4, 8, 3, 3, 0, 0, None) == 4
+
+
+def test_gradient_workspaces_follow_the_kernels_that_run():
+    """Byte counts depend on the shape only; what they hold is stated in the header."""
+    f32 = kst.KST_F32
+    # no padding factor, one workgroup's worth of positions: nothing to copy, nothing to add up
+    assert kst.kst_backward_input_workspace_bytes(1, 2, 2, 8, 3, 0, f32) == 0
+    # kernels up to 7 x 7 visit the unframed positions: an even P needs no copy for the input
+    # gradient, an odd P only the one-pixel frame around g
+    assert kst.kst_backward_input_workspace_bytes(2, 3, 1, 8, 3, 2, f32) == 0
+    M = kst.kst_out_size_padded(8, 3, 3)                 # 19; framed by one pixel: 21
+    need = kst.kst_backward_input_workspace_bytes(2, 3, 1, 8, 3, 3, f32)
+    assert 2 * 1 * (M + 2) * (M + 2) * 4 <= need < 2 * 1 * (M + 2) * (M + 2) * 4 + 256
+    # beyond 7 x 7 the plain kernels work on a framed problem: the framed result is held too
+    assert kst.kst_backward_input_workspace_bytes(1, 2, 2, 8, 9, 2, f32) >= 1 * 2 * 10 * 10 * 4
+    # kernel gradient, few channels, many positions: partial results of the sliced position range only
+    need = kst.kst_backward_weight_workspace_bytes(16, 3, 1, 224, 5, 2, f32)
+    assert 0 < need <= 1024 * 3 * 25 * 4 + 256
+    # matrix cores: the zero-framed copy of g plus partial sums
+    Mg = kst.kst_out_size_padded(16, 4, 2)               # 32; framed by n - 1 = 3
+    need = kst.kst_backward_weight_workspace_bytes(64, 256, 128, 16, 4, 2, f32)
+    assert need >= 64 * 128 * (Mg + 6) * (Mg + 6) * 4
+    # illegal shapes give 0
+    assert kst.kst_backward_weight_workspace_bytes(1, 1, 1, 1, 9, 0, f32) == 0
+    assert kst.kst_backward_input_workspace_bytes(0, 1, 1, 8, 3, 0, f32) == 0
