@@ -755,7 +755,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     // The wave issues in order, so whatever stands between two MFMAs delays the second one by all
     // it takes beyond the first one's run time: the items are dealt out over the MFMAs of the taps
     // every wave has (the last tap may belong to fewer waves).  1 x 1 kernels have no such tap
-    // (one wave multiplies): there the items go in one block.
+    // (one wave multiplies): there the items go in one block.  (Folded rows: over all MFMA slots.)
     constexpr int TS = FOLD ? 0 : NN % 4 == 0 ? TW : TW - 1;
     constexpr int SLOTS = TS > 0 ? RH * TS * KS * CB : 1;
     int cur = 0;
@@ -779,10 +779,22 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
 #pragma unroll
                 for (int k = 0; k < KS; ++k) af[(t + 1) & 1][k] = S[abase[t + 1] + 2 * r * GL + 4 * k];
             }
-            if constexpr (TS == 0 && r == RH / 2 && t == 0)
+            if constexpr (!FOLD && TS == 0 && r == RH / 2 && t == 0)
                 static_for<ITEMS>([&](auto jc) { put(decltype(jc)::value, other); get(decltype(jc)::value); });
+            if constexpr (FOLD) {
+                // a wave without a row block skips the MFMAs, not its share of the staging
+                const bool mine = 32 * wave < p.Cout * NN;
+                static_for<KS * CB>([&](auto mc) {
+                    constexpr int k = decltype(mc)::value / CB, c = decltype(mc)::value % CB;
+                    if (mine) acc[0][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[0][k], bf[c][k], acc[0][c], 0, 0, 0);
+                    constexpr int slot = (r * KS + k) * CB + c;
+                    constexpr int j0 = slot * ITEMS / (RH * KS * CB), j1 = (slot + 1) * ITEMS / (RH * KS * CB);
+                    static_for<j1 - j0>([&](auto jc) { put(j0 + decltype(jc)::value, other); get(j0 + decltype(jc)::value); });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            }
             // every wave has taps 0 .. TS - 1; the last one only while wave + 4 (TW - 1) < NN
-            if (FOLD ? 32 * wave < p.Cout * NN : (t < TS || wave + 4 * t < NN)) {
+            if (!FOLD && (t < TS || wave + 4 * t < NN)) {
                 static_for<KS * CB>([&](auto mc) {
                     constexpr int k = decltype(mc)::value / CB, c = decltype(mc)::value % CB;
                     acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[c][k], acc[t][c], 0, 0, 0);
