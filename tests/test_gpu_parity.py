@@ -579,6 +579,7 @@ def test_gradients(B, Cin, Cout, N, n, P, dtype):
     (3, 16, 24, 6, 5, 0),      # 5 x 5 kernel on 6 x 6 maps: three rows per chunk
     (2, 48, 16, 8, 3, 0),      # two channel blocks, two wave quartets, four rows of 8 per chunk
     (2, 80, 9, 18, 2, 1),      # ... rows of 18 cut 10 + 8, two rows per chunk, odd padding factor
+    (2, 40, 16, 7, 3, 1),      # two channel blocks on an odd map: one quartet, one row per chunk
 ])
 def test_gradients_on_the_matrix_cores(B, Cin, Cout, N, n, P):
     """fp32 layers with at least 8 channels on either side take the MFMA gradient kernels."""
