@@ -30,10 +30,10 @@ if ROOT not in sys.path:
 # profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
 # kernels, quoted next to the live timing; None for a layer that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_1ch_bandwidth": 339386100,
-    "cfg3_gan_n4": 513567433 + 137492694,   # matrix-core kernel + pass summing the partial tiles
-    "cfg4_deep_n5": 576978987 + 100629522,  # the same two kernels
-    "cfg5_late_bf16": 352324485,
+    "cfg2_1ch_bandwidth": 339392985,
+    "cfg3_gan_n4": 513564504 + 137493331,   # matrix-core kernel + pass summing the partial tiles
+    "cfg4_deep_n5": 576979972 + 100629585,  # the same two kernels
+    "cfg5_late_bf16": 352244829,
 }
 
 
