@@ -686,3 +686,78 @@ def test_gradients_are_exact_on_integers(B, Cin, Cout, N, n, P):
                           oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), layer.N, layer.P))
     assert np.array_equal(dw.cpu().numpy().astype(np.float64),
                           oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), layer.n, layer.P))
+
+
+def _seeded_gradient_shapes(count, seed):
+    """Small layers that between them reach every chunk size, row count, channel-block count and
+    row mode of the matrix-core gradient kernels (seeded: the same list on every run)."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        n = int(rng.integers(1, 6))
+        N = int(rng.choice([2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 18, 21, 24, 32, 33]))
+        P = int(rng.integers(0, 4))
+        if 2 * N + 2 * P - n < 1:
+            continue
+        Cin = int(rng.choice([8, 24, 33, 40, 64, 72, 100]))
+        Cout = int(rng.choice([2, 3, 5, 8, 9, 24, 40]))
+        if Cout < 8 and Cin < 64:
+            Cin = 64                                             # few output channels: the folded rows need 64 inputs
+        B = int(rng.integers(1, 4))
+        if B * Cin * Cout * N * N * n * n > 6e8:                 # keeps the oracle to a second or two per case
+            continue
+        shapes.append((B, Cin, Cout, N, n, P))
+    return shapes
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", _seeded_gradient_shapes(40, 20260511))
+def test_gradients_on_the_matrix_cores_seeded_shapes(B, Cin, Cout, N, n, P):
+    layer = wl.Layer("grad_seeded", B, Cin, Cout, N, n, "f32", "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 7000 + 31 * N + 7 * n + P + Cin)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(29 * N + n + P + Cout)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    torch.cuda.synchronize()
+    want_din = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL["f32"]
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL["f32"]
+
+
+def _seeded_few_channel_shapes(count, seed):
+    """Layers the register-blocked gradient kernels take: every kernel size up to 7, one to several
+    channels per workgroup, ragged channel groups, with and without a padding factor."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        n = int(rng.integers(1, 8))
+        N = int(rng.choice([1, 2, 3, 5, 8, 11, 17, 30, 45]))
+        P = int(rng.integers(0, 4))
+        if 2 * N + 2 * P - n < 1:
+            continue
+        Cin = int(rng.choice([1, 2, 3, 4, 5, 7, 9, 20, 50, 70]))
+        Cout = int(rng.choice([1, 2, 3, 4, 6, 7])) if Cin >= 8 else int(rng.choice([1, 2, 3, 4, 6, 12, 33]))
+        B = int(rng.integers(1, 5))
+        dtype = "bf16" if rng.integers(0, 3) == 0 else "f32"
+        if B * Cin * Cout * N * N * n * n > 3e8:
+            continue
+        shapes.append((B, Cin, Cout, N, n, P, dtype))
+    return shapes
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", _seeded_few_channel_shapes(36, 20260512))
+def test_gradients_of_few_channel_layers_seeded_shapes(B, Cin, Cout, N, n, P, dtype):
+    layer = wl.Layer("grad_few_seeded", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 8000 + 31 * N + 7 * n + P + Cin)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(37 * N + n + P + Cout)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    torch.cuda.synchronize()
+    want_din = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL[dtype]
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
