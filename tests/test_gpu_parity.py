@@ -761,3 +761,46 @@ def test_gradients_of_few_channel_layers_seeded_shapes(B, Cin, Cout, N, n, P, dt
     want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
     assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL[dtype]
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
+
+
+def _seeded_forward_shapes(count, seed):
+    """Forward layers over every kernel size up to 7, both operand types, padding factors 0-3 and
+    channel counts on both sides of every path's limits."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        n = int(rng.integers(1, 8))
+        N = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 17, 31, 40, 64]))
+        P = int(rng.integers(0, 4))
+        if 2 * N + 2 * P - n < 1:
+            continue
+        Cin = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 24, 40, 64, 136]))
+        Cout = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 32, 40, 132]))
+        B = int(rng.integers(1, 4))
+        dtype = "bf16" if rng.integers(0, 3) == 0 else "f32"
+        if B * Cin * Cout * N * N * n * n > 3e8:
+            continue
+        shapes.append((B, Cin, Cout, N, n, P, dtype))
+    return shapes
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", _seeded_forward_shapes(40, 20260513))
+def test_forward_seeded_shapes_on_every_path_that_takes_them(B, Cin, Cout, N, n, P, dtype):
+    layer = wl.Layer("fwd_seeded", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2)
+    x, w = wl.make_tensors(layer, 9000 + 31 * N + 7 * n + P + Cin)
+    xd, wd = x.to(DEV), w.to(DEV)
+    w_seg = kst.kst_segregate_weights(wd)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    ran = []
+    for name, code in (("auto", kst.KST_PATH_AUTO), ("direct", kst.KST_PATH_DIRECT), ("igemm", kst.KST_PATH_IGEMM),
+                       ("even", kst.KST_PATH_IGEMM_EVEN)):
+        try:
+            got = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=code)
+        except kst.KstError:
+            assert name in ("igemm", "even"), name               # only the matrix-core paths may refuse a layer
+            continue
+        torch.cuda.synchronize()
+        ran.append(name)
+        e = rel_err(got.cpu().numpy(), want)
+        assert e <= TOL[dtype], "%s: rel err %.3e" % (name, e)
+    assert "auto" in ran and "direct" in ran
