@@ -16,8 +16,10 @@
  *   - Dense row-major layouts: in[B][Cin][N][N], w[Cout][Cin][n][n],
  *     out[B][Cout][M][M].  out is always fp32 and is completely overwritten
  *     (no bias, no activation, no accumulation).  Buffers must not alias.
- *   - dtype describes in and w: KST_F32 (fp32 operands, fp32 arithmetic) or
- *     KST_BF16 (bfloat16 operands, fp32 accumulation, fp32 out).
+ *   - dtype describes in and w: KST_F32 (fp32 operands, fp32 arithmetic),
+ *     KST_BF16 (bfloat16 operands, fp32 accumulation, fp32 out) or KST_F16 (IEEE
+ *     half-precision operands, fp32 accumulation, fp32 out; not in the paper:
+ *     the same kernels as KST_BF16 with the other 16-bit multiply).
  *   - Work is enqueued on `stream` and the call returns without waiting for
  *     it.  Arguments are validated on the host before anything is launched;
  *     errors come back as a kst_status, nothing throws or aborts.
@@ -41,14 +43,15 @@ typedef struct ihipStream_t *hipStream_t;
 
 typedef enum {
     KST_F32 = 0,
-    KST_BF16 = 1
+    KST_BF16 = 1,
+    KST_F16 = 2
 } kst_dtype;
 
 typedef enum {
     KST_OK = 0,
     KST_ERR_NULL = 1,       /* a required pointer is NULL                              */
     KST_ERR_SHAPE = 2,      /* a size < 1, 2N - n < 1, or a tensor of 2^31+ elements   */
-    KST_ERR_DTYPE = 3,      /* dtype is neither KST_F32 nor KST_BF16                   */
+    KST_ERR_DTYPE = 3,      /* dtype is none of KST_F32, KST_BF16, KST_F16             */
     KST_ERR_WORKSPACE = 4,  /* workspace missing or smaller than kst_workspace_bytes  */
     KST_ERR_HIP = 5,        /* the HIP runtime refused an allocation or a launch      */
     KST_ERR_PATH = 6,       /* unknown kst_path, or a path that cannot run this shape */
@@ -95,7 +98,7 @@ kst_status kst_subkernel_shape(int n, int p, int *Ta, int *Tb);
  * W_p(co, ci, a, b) = w[co][ci][2a + r][2b + s]:
  *
  *   KST_F32 :  W_p laid out as [Cin][Ta*Tb][Cout]            (co fastest)
- *   KST_BF16:  W_p laid out as [ceil(Cin/8)][Ta*Tb][Cout][8] (ci mod 8 fastest),
+ *   KST_BF16, KST_F16:  W_p laid out as [ceil(Cin/8)][Ta*Tb][Cout][8] (ci mod 8 fastest),
  *              input channels padded with zeros to a multiple of 8.
  *
  * Both put the reduction index next to the output channel the way the matrix

@@ -12,7 +12,7 @@ import os
 
 import torch
 
-KST_F32, KST_BF16 = 0, 1
+KST_F32, KST_BF16, KST_F16 = 0, 1, 2
 KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN = 0, 1, 2, 3
 KST_OK = 0
 
@@ -78,7 +78,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return KST_F32
     if t.dtype == torch.bfloat16:
         return KST_BF16
-    raise TypeError("kst supports float32 and bfloat16 operands, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return KST_F16
+    raise TypeError("kst supports float32, bfloat16 and float16 operands, got %s" % t.dtype)
 
 
 def _dev(t: torch.Tensor, what: str) -> int:

@@ -7,8 +7,8 @@ namespace {
 
 constexpr size_t kMaxElems = (size_t)1 << 31;
 
-bool dtype_ok(int dt) { return dt == KST_F32 || dt == KST_BF16; }
-size_t elt_bytes(kst_dtype dt) { return dt == KST_BF16 ? 2 : 4; }
+bool dtype_ok(int dt) { return dt == KST_F32 || dt == KST_BF16 || dt == KST_F16; }
+size_t elt_bytes(kst_dtype dt) { return is16(dt) ? 2 : 4; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 kst_status check_weight_shape(int Cin, int Cout, int n)
@@ -36,7 +36,7 @@ kst_status check_shape(int B, int Cin, int Cout, int N, int n)
 // AUTO: the matrix cores pay off once both channel counts can fill MFMA blocks.
 kst_path choose_path(const Shape &s, kst_dtype dt)
 {
-    const bool ok = dt == KST_BF16 ? igemm_bf16_supported(s) : igemm_f32_supported(s);
+    const bool ok = is16(dt) ? igemm_bf16_supported(s) : igemm_f32_supported(s);
     if (ok && s.Cout >= 16 && s.Cin >= 8) return KST_PATH_IGEMM;
     return KST_PATH_DIRECT;
 }
@@ -46,7 +46,7 @@ kst_status resolve_path(const Shape &s, kst_dtype dt, int path, kst_path *out)
     if (path == KST_PATH_AUTO) { *out = choose_path(s, dt); return KST_OK; }
     if (path == KST_PATH_DIRECT) { *out = KST_PATH_DIRECT; return KST_OK; }
     if (path == KST_PATH_IGEMM) {
-        const bool ok = dt == KST_BF16 ? igemm_bf16_supported(s) : igemm_f32_supported(s);
+        const bool ok = is16(dt) ? igemm_bf16_supported(s) : igemm_f32_supported(s);
         if (!ok) return KST_ERR_PATH;
         *out = KST_PATH_IGEMM;
         return KST_OK;
@@ -64,7 +64,7 @@ bool on_matrix_cores(kst_path path) { return path == KST_PATH_IGEMM || path == K
 size_t workspace_for(const Shape &s, kst_dtype dt, kst_path path)
 {
     if (!on_matrix_cores(path)) return 0;
-    return dt == KST_BF16 ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s, path == KST_PATH_IGEMM_EVEN);
+    return is16(dt) ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s, path == KST_PATH_IGEMM_EVEN);
 }
 
 // The segregated forward pass on a validated shape (s.Ns may exceed s.N only where
@@ -86,8 +86,8 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
     hipError_t e;
     if (chosen == KST_PATH_DIRECT)
         e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
-    else if (dtype == KST_BF16)
-        e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, stream);
+    else if (is16(dtype))
+        e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, dtype == KST_F16, stream);
     else
         e = launch_igemm_f32((const float *)in, (const float *)w_seg, (float *)out, ws, s,
                              chosen == KST_PATH_IGEMM_EVEN, stream);
@@ -471,14 +471,14 @@ size_t kst_yardstick_mfma_sink_elems(void) { return yardstick_mfma_sink_elems();
 
 double kst_yardstick_mfma_flops(kst_dtype dtype, int iters)
 {
-    if (!dtype_ok(dtype) || iters < 1) return 0.0;
+    if ((dtype != KST_F32 && dtype != KST_BF16) || iters < 1) return 0.0;
     return yardstick_mfma_flops(dtype, iters);
 }
 
 kst_status kst_yardstick_mfma(kst_dtype dtype, int iters, float *sink, size_t sink_elems, hipStream_t stream)
 {
     if (!sink) return KST_ERR_NULL;
-    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    if (dtype != KST_F32 && dtype != KST_BF16) return KST_ERR_DTYPE;
     if (iters < 1 || iters > (1 << 22)) return KST_ERR_SHAPE;
     if (sink_elems < yardstick_mfma_sink_elems()) return KST_ERR_WORKSPACE;
     return launch_yardstick_mfma(dtype, iters, sink, stream) == hipSuccess ? KST_OK : KST_ERR_HIP;

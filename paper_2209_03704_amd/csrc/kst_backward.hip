@@ -519,8 +519,9 @@ bool backward_generic_takes_frame(const Shape &s)
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream)
 {
-    if (dt == KST_BF16 ? launch_input_regs<uint16_t>(g, (const uint16_t *)w, din, s, stream)
-                       : launch_input_regs<float>(g, (const float *)w, din, s, stream))
+    if (dt == KST_BF16   ? launch_input_regs<uint16_t>(g, (const uint16_t *)w, din, s, stream)
+        : dt == KST_F16 ? launch_input_regs<half_bits>(g, (const half_bits *)w, din, s, stream)
+                        : launch_input_regs<float>(g, (const float *)w, din, s, stream))
         return hipGetLastError();
     if (s.frame) return hipErrorInvalidValue;                    // the plain kernel knows no virtual frame
     const size_t total = (size_t)s.B * s.Cin * s.N * s.N;
@@ -528,6 +529,9 @@ hipError_t launch_backward_input_generic(const float *g, const void *w, float *d
     if (dt == KST_BF16)
         hipLaunchKernelGGL(backward_input_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream, g,
                            (const uint16_t *)w, din, s.B, s.Cin, s.Cout, s.N, s.M, s.n);
+    else if (dt == KST_F16)
+        hipLaunchKernelGGL(backward_input_generic_kernel<half_bits>, dim3(blocks), dim3(256), 0, stream, g,
+                           (const half_bits *)w, din, s.B, s.Cin, s.Cout, s.N, s.M, s.n);
     else
         hipLaunchKernelGGL(backward_input_generic_kernel<float>, dim3(blocks), dim3(256), 0, stream, g, (const float *)w,
                            din, s.B, s.Cin, s.Cout, s.N, s.M, s.n);
@@ -551,11 +555,13 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
     bool regs = false;
     if (weight_lanes_apply(s)) {
         if (dt == KST_BF16) launch_weight_lanes<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream);
+        else if (dt == KST_F16) launch_weight_lanes<half_bits>((const half_bits *)in, g, dst, s, slices, per_slice, stream);
         else launch_weight_lanes<float>((const float *)in, g, dst, s, slices, per_slice, stream);
         regs = true;
     } else {
-        regs = dt == KST_BF16 ? launch_weight_regs<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream)
-                              : launch_weight_regs<float>((const float *)in, g, dst, s, slices, per_slice, stream);
+        regs = dt == KST_BF16   ? launch_weight_regs<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream)
+               : dt == KST_F16 ? launch_weight_regs<half_bits>((const half_bits *)in, g, dst, s, slices, per_slice, stream)
+                               : launch_weight_regs<float>((const float *)in, g, dst, s, slices, per_slice, stream);
     }
     if (regs) {
         // the register-blocked kernel has run
@@ -564,6 +570,9 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
     } else if (dt == KST_BF16) {
         hipLaunchKernelGGL(backward_weight_generic_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
                            (const uint16_t *)in, g, dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
+    } else if (dt == KST_F16) {
+        hipLaunchKernelGGL(backward_weight_generic_kernel<half_bits>, dim3(blocks), dim3(256), 0, stream,
+                           (const half_bits *)in, g, dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);
     } else {
         hipLaunchKernelGGL(backward_weight_generic_kernel<float>, dim3(blocks), dim3(256), 0, stream, (const float *)in, g,
                            dst, s.B, s.Cin, s.Cout, s.N, s.M, s.n, per_slice);

@@ -538,6 +538,7 @@ hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Sh
         return launch_direct_flat((const float *)in, (const float *)w_seg, out, s, fp, grid, lds, stream);
     if (direct_multi_supported(s)) return launch_direct_multi(in, w_seg, out, s, dt, stream);
     if (dt == KST_BF16) return run<uint16_t>((const uint16_t *)in, (const uint16_t *)w_seg, out, s, dt, stream);
+    if (dt == KST_F16) return run<half_bits>((const half_bits *)in, (const half_bits *)w_seg, out, s, dt, stream);
     return run<float>((const float *)in, (const float *)w_seg, out, s, dt, stream);
 }
 

@@ -284,6 +284,7 @@ hipError_t launch_direct_multi(const void *in, const void *w_seg, float *out, co
 {
     if (!direct_multi_supported(s)) return hipErrorInvalidValue;
     if (dt == KST_BF16) return launch_t<uint16_t>((const uint16_t *)in, (const uint16_t *)w_seg, out, s, dt, stream);
+    if (dt == KST_F16) return launch_t<half_bits>((const half_bits *)in, (const half_bits *)w_seg, out, s, dt, stream);
     return launch_t<float>((const float *)in, (const float *)w_seg, out, s, dt, stream);
 }
 

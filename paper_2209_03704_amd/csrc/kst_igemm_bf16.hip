@@ -11,12 +11,11 @@
 
 namespace kst {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int H_KC = 16;               // input channels staged per step = one MFMA reduction step
 constexpr int H_XS = H_KC + 8;         // LDS pixel stride in bf16: 48 bytes, conflict-free 16-byte reads
 
-template <int n>
+template <int n, bool F16>
 __global__ void __launch_bounds__(G_THREADS) igemm_bf16_kernel(const uint16_t *__restrict__ in,
                                                                  const uint16_t *__restrict__ w_seg,
                                                                  float *__restrict__ dst, IgemmParams p)
@@ -119,7 +118,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_bf16_kernel(const uint16_t *_
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const bf16x8 wf = *reinterpret_cast<const bf16x8 *>(&Ws[T * OCT * G_TCO + wbase + h * 32]);
-                        acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[r + a][s + bq], acc[cls][h], 0, 0, 0);
+                        acc[cls][h] = mfma16<F16>(wf, xf[r + a][s + bq], acc[cls][h]);
                     }
                 }
         }
@@ -151,44 +150,52 @@ size_t igemm_bf16_workspace_bytes(const Shape &s)
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
 }
 
-template <int n>
+template <int n, bool F16>
 static hipError_t launch_n(const uint16_t *in, const uint16_t *w_seg, float *dst, const IgemmParams &p,
                            hipStream_t stream)
 {
     const size_t lds = lds_bytes(p, n);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_kernel<n>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_kernel<n, F16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)p.tiles_m * p.tiles_co * p.splits;
-    hipLaunchKernelGGL(igemm_bf16_kernel<n>, dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    hipLaunchKernelGGL((igemm_bf16_kernel<n, F16>), dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
     return hipGetLastError();
 }
 
-hipError_t launch_igemm_bf16(const void *in_v, const void *w_seg_v, float *out, void *ws, const Shape &s,
-                             hipStream_t stream)
+template <bool F16>
+static hipError_t launch_plain(const void *in_v, const void *w_seg_v, float *out, void *ws, const Shape &s,
+                               hipStream_t stream)
 {
-    if (igemm_bf16_wide_supported(s)) return launch_igemm_bf16_wide(in_v, w_seg_v, out, s, stream);
-    if (igemm_bf16_ring_supported(s)) return launch_igemm_bf16_ring(in_v, w_seg_v, out, s, stream);
-    if (igemm_bf16_strip_supported(s)) return launch_igemm_bf16_strip(in_v, w_seg_v, out, s, stream);
     const uint16_t *in = (const uint16_t *)in_v, *w_seg = (const uint16_t *)w_seg_v;
     const IgemmParams p = plan(s);
     float *dst = p.splits > 1 ? (float *)ws : out;
     hipError_t e;
     switch (s.n) {
-        case 1: e = launch_n<1>(in, w_seg, dst, p, stream); break;
-        case 2: e = launch_n<2>(in, w_seg, dst, p, stream); break;
-        case 3: e = launch_n<3>(in, w_seg, dst, p, stream); break;
-        case 4: e = launch_n<4>(in, w_seg, dst, p, stream); break;
-        case 5: e = launch_n<5>(in, w_seg, dst, p, stream); break;
-        case 6: e = launch_n<6>(in, w_seg, dst, p, stream); break;
-        case 7: e = launch_n<7>(in, w_seg, dst, p, stream); break;
+        case 1: e = launch_n<1, F16>(in, w_seg, dst, p, stream); break;
+        case 2: e = launch_n<2, F16>(in, w_seg, dst, p, stream); break;
+        case 3: e = launch_n<3, F16>(in, w_seg, dst, p, stream); break;
+        case 4: e = launch_n<4, F16>(in, w_seg, dst, p, stream); break;
+        case 5: e = launch_n<5, F16>(in, w_seg, dst, p, stream); break;
+        case 6: e = launch_n<6, F16>(in, w_seg, dst, p, stream); break;
+        case 7: e = launch_n<7, F16>(in, w_seg, dst, p, stream); break;
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
     if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream);
     return e;
+}
+
+// f16: half-precision operands (else bfloat16).
+hipError_t launch_igemm_bf16(const void *in_v, const void *w_seg_v, float *out, void *ws, const Shape &s, bool f16,
+                             hipStream_t stream)
+{
+    if (igemm_bf16_wide_supported(s)) return launch_igemm_bf16_wide(in_v, w_seg_v, out, s, f16, stream);
+    if (igemm_bf16_ring_supported(s)) return launch_igemm_bf16_ring(in_v, w_seg_v, out, s, f16, stream);
+    if (igemm_bf16_strip_supported(s)) return launch_igemm_bf16_strip(in_v, w_seg_v, out, s, f16, stream);
+    return f16 ? launch_plain<true>(in_v, w_seg_v, out, ws, s, stream) : launch_plain<false>(in_v, w_seg_v, out, ws, s, stream);
 }
 
 }  // namespace kst

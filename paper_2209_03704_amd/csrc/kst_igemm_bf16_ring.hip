@@ -30,7 +30,6 @@
 
 namespace kst {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
@@ -91,7 +90,7 @@ __device__ __forceinline__ void lds_barrier()
 #define KST_LDS(T) T __attribute__((address_space(3)))
 #define KST_GLB(T) T __attribute__((address_space(1)))
 
-template <int n, int N>
+template <int n, int N, bool F16>
 __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uint16_t *__restrict__ in,
                                                                       const uint16_t *__restrict__ w_seg,
                                                                       float *__restrict__ out, RingParams p)
@@ -266,8 +265,8 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
         for (int m = 0; m < ord.n0; ++m)
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb)
-                acc[ord.cls[m]][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb], 0, 0, 0);
+                acc[ord.cls[m]][pb] = mfma16<F16>(
+                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb]);
         __builtin_amdgcn_sched_barrier(0);
         if (refill) issue_direct(refill_stage);
         // Window column 1 = column 0 of the next quad = the next lane's value.  With both blocks
@@ -294,8 +293,8 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
         for (int m = ord.n0; m < G::NN; ++m)
 #pragma unroll
             for (int pb = 0; pb < 2; ++pb)
-                acc[ord.cls[m]][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb], 0, 0, 0);
+                acc[ord.cls[m]][pb] = mfma16<F16>(
+                    wv[m], __builtin_bit_cast(bf16x8, x[pb][ord.dy[m]]), acc[ord.cls[m]][pb]);
     };
 
     // ---- reduction over the input channels ------------------------------------------------------
@@ -380,18 +379,18 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
     }
 }
 
-template <int n, int N>
+template <int n, int N, bool F16>
 hipError_t launch_ring(const uint16_t *in, const uint16_t *w_seg, float *out, const RingParams &p, hipStream_t stream)
 {
     using G = RingGeom<n, N>;
     static_assert(G::LDS_B <= 80 * 1024, "two workgroups per CU");
     if (G::LDS_B > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_ring_kernel<n, N>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_ring_kernel<n, N, F16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_B);
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)p.B * p.tiles_co * G::STRIPS;
-    hipLaunchKernelGGL((igemm_bf16_ring_kernel<n, N>), dim3(blocks), dim3(R_THREADS), G::LDS_B, stream, in, w_seg, out, p);
+    hipLaunchKernelGGL((igemm_bf16_ring_kernel<n, N, F16>), dim3(blocks), dim3(R_THREADS), G::LDS_B, stream, in, w_seg, out, p);
     return hipGetLastError();
 }
 
@@ -406,7 +405,8 @@ bool igemm_bf16_ring_supported(const Shape &s)
     return (size_t)s.B * (s.Cout / R_TCO) * strips < 0x7fffffffu;
 }
 
-hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream)
+hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                  hipStream_t stream)
 {
     if (!igemm_bf16_ring_supported(s)) return hipErrorInvalidValue;
     RingParams p;
@@ -414,10 +414,10 @@ hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out,
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
     const uint16_t *i16 = (const uint16_t *)in, *w16 = (const uint16_t *)w_seg;
     switch (s.n * 1000 + s.N) {
-        case 2032: return launch_ring<2, 32>(i16, w16, out, p, stream);
-        case 2064: return launch_ring<2, 64>(i16, w16, out, p, stream);
-        case 3032: return launch_ring<3, 32>(i16, w16, out, p, stream);
-        case 3064: return launch_ring<3, 64>(i16, w16, out, p, stream);
+        case 2032: return f16 ? launch_ring<2, 32, true>(i16, w16, out, p, stream) : launch_ring<2, 32, false>(i16, w16, out, p, stream);
+        case 2064: return f16 ? launch_ring<2, 64, true>(i16, w16, out, p, stream) : launch_ring<2, 64, false>(i16, w16, out, p, stream);
+        case 3032: return f16 ? launch_ring<3, 32, true>(i16, w16, out, p, stream) : launch_ring<3, 32, false>(i16, w16, out, p, stream);
+        case 3064: return f16 ? launch_ring<3, 64, true>(i16, w16, out, p, stream) : launch_ring<3, 64, false>(i16, w16, out, p, stream);
         default: return hipErrorInvalidValue;
     }
 }

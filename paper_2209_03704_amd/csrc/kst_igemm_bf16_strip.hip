@@ -18,7 +18,6 @@
 
 namespace kst {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -38,7 +37,7 @@ struct StripParams {
     unsigned off[4];
 };
 
-template <int n>
+template <int n, bool F16>
 __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const uint16_t *__restrict__ in,
                                                                        const uint16_t *__restrict__ w_seg,
                                                                        float *__restrict__ out, StripParams p)
@@ -193,8 +192,8 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
                     const bf16x8 wf = *reinterpret_cast<const bf16x8 *>(&Ws[T * 2 * S_TCO + wbase]);
 #pragma unroll
                     for (int pb = 0; pb < 2; ++pb)
-                        acc[cls][pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[pb][r + a][s + bq],
-                                                                                acc[cls][pb], 0, 0, 0);
+                        acc[cls][pb] = mfma16<F16>(wf, xf[pb][r + a][s + bq],
+                                                                                acc[cls][pb]);
                 }
         }
         if (cn >= p.Cin) break;
@@ -284,17 +283,17 @@ bool strip_plan(const Shape &s, StripParams &p, size_t &lds)
     return lds <= 160 * 1024 && (size_t)s.B * p.tiles_co * p.strips < 0x7fffffffu;
 }
 
-template <int n>
+template <int n, bool F16>
 hipError_t launch_n(const uint16_t *in, const uint16_t *w_seg, float *out, const StripParams &p, size_t lds,
                     hipStream_t stream)
 {
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_strip_kernel<n>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_strip_kernel<n, F16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     const unsigned blocks = (unsigned)p.B * p.tiles_co * p.strips;
-    hipLaunchKernelGGL(igemm_bf16_strip_kernel<n>, dim3(blocks), dim3(S_THREADS), lds, stream, in, w_seg, out, p);
+    hipLaunchKernelGGL((igemm_bf16_strip_kernel<n, F16>), dim3(blocks), dim3(S_THREADS), lds, stream, in, w_seg, out, p);
     return hipGetLastError();
 }
 
@@ -307,17 +306,18 @@ bool igemm_bf16_strip_supported(const Shape &s)
     return strip_plan(s, p, lds);
 }
 
-hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream)
+hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                   hipStream_t stream)
 {
     StripParams p;
     size_t lds;
     if (!strip_plan(s, p, lds)) return hipErrorInvalidValue;
     const uint16_t *i16 = (const uint16_t *)in, *w16 = (const uint16_t *)w_seg;
     switch (s.n) {
-        case 1: return launch_n<1>(i16, w16, out, p, lds, stream);
-        case 2: return launch_n<2>(i16, w16, out, p, lds, stream);
-        case 3: return launch_n<3>(i16, w16, out, p, lds, stream);
-        case 4: return launch_n<4>(i16, w16, out, p, lds, stream);
+        case 1: return f16 ? launch_n<1, true>(i16, w16, out, p, lds, stream) : launch_n<1, false>(i16, w16, out, p, lds, stream);
+        case 2: return f16 ? launch_n<2, true>(i16, w16, out, p, lds, stream) : launch_n<2, false>(i16, w16, out, p, lds, stream);
+        case 3: return f16 ? launch_n<3, true>(i16, w16, out, p, lds, stream) : launch_n<3, false>(i16, w16, out, p, lds, stream);
+        case 4: return f16 ? launch_n<4, true>(i16, w16, out, p, lds, stream) : launch_n<4, false>(i16, w16, out, p, lds, stream);
         default: return hipErrorInvalidValue;
     }
 }

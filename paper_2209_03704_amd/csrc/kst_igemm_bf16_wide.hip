@@ -28,7 +28,6 @@
 
 namespace kst {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
@@ -155,7 +154,7 @@ struct TapOrder {
     }
 };
 
-template <int n, int N>
+template <int n, int N, bool F16>
 __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wide_kernel(const uint16_t *__restrict__ in,
                                                                       const uint16_t *__restrict__ w_seg,
                                                                       float *__restrict__ out, WideParams p)
@@ -365,9 +364,9 @@ __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wi
                 for (int q = 0; q < G::QW; ++q)
 #pragma unroll
                     for (int cb = 0; cb < G::CB; ++cb)
-                        acc[q][ord.cls[m]][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        acc[q][ord.cls[m]][cb] = mfma16<F16>(
                             __builtin_bit_cast(bf16x8, w[m]), __builtin_bit_cast(bf16x8, x[q + ord.dy[m]][cb]),
-                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb], 0, 0, 0);
+                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb]);
 #pragma unroll
                 for (int r = m * RPT; r < (m + 1) * RPT && r < G::XR; ++r) shift_row(r);
 #pragma unroll
@@ -400,9 +399,9 @@ __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wi
                         const int k0 = s2 >= 0 ? s2 * G::KMAX / SL : 0, k1 = s2 >= 0 ? (s2 + 1) * G::KMAX / SL : 0;
                         if constexpr (issue)
                             if (k1 > k0) { aim_one(k0, cur); __builtin_amdgcn_sched_barrier(0); }
-                        acc[q][ord.cls[m]][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        acc[q][ord.cls[m]][cb] = mfma16<F16>(
                             __builtin_bit_cast(bf16x8, w[m]), __builtin_bit_cast(bf16x8, xs[q + ord.dy[m]][cb]),
-                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb], 0, 0, 0);
+                            first_chunk && ord.first[m] ? zero16 : acc[q][ord.cls[m]][cb]);
                         __builtin_amdgcn_sched_barrier(0);
                         if constexpr (more) {
                             if (q == 0 && cb == 0) read_w(nxt, m - 1);
@@ -569,18 +568,18 @@ __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wi
     }
 }
 
-template <int n, int N>
+template <int n, int N, bool F16>
 hipError_t launch_wide(const uint16_t *in, const uint16_t *w_seg, float *out, const WideParams &p, hipStream_t stream)
 {
     using G = WideGeom<n, N>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_wide_kernel<n, N>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_wide_kernel<n, N, F16>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_B);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     const unsigned blocks = (unsigned)min(p.ntiles, (cus > 0 ? cus : 256) * G::QH);
-    hipLaunchKernelGGL((igemm_bf16_wide_kernel<n, N>), dim3(blocks), dim3(W_THREADS), G::LDS_B, stream, in, w_seg, out, p);
+    hipLaunchKernelGGL((igemm_bf16_wide_kernel<n, N, F16>), dim3(blocks), dim3(W_THREADS), G::LDS_B, stream, in, w_seg, out, p);
     return hipGetLastError();
 }
 
@@ -611,7 +610,8 @@ bool igemm_bf16_wide_supported(const Shape &s)
     return tiles >= 224 && tiles < 0x7fffffffu;
 }
 
-hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream)
+hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                  hipStream_t stream)
 {
     if (!igemm_bf16_wide_supported(s)) return hipErrorInvalidValue;
     WideParams p;
@@ -620,10 +620,10 @@ hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out,
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
     const uint16_t *i16 = (const uint16_t *)in, *w16 = (const uint16_t *)w_seg;
     switch (s.n * 1000 + s.N) {
-        case 2032: return launch_wide<2, 32>(i16, w16, out, p, stream);
-        case 2064: return launch_wide<2, 64>(i16, w16, out, p, stream);
-        case 3032: return launch_wide<3, 32>(i16, w16, out, p, stream);
-        case 3064: return launch_wide<3, 64>(i16, w16, out, p, stream);
+        case 2032: return f16 ? launch_wide<2, 32, true>(i16, w16, out, p, stream) : launch_wide<2, 32, false>(i16, w16, out, p, stream);
+        case 2064: return f16 ? launch_wide<2, 64, true>(i16, w16, out, p, stream) : launch_wide<2, 64, false>(i16, w16, out, p, stream);
+        case 3032: return f16 ? launch_wide<3, 32, true>(i16, w16, out, p, stream) : launch_wide<3, 32, false>(i16, w16, out, p, stream);
+        case 3064: return f16 ? launch_wide<3, 64, true>(i16, w16, out, p, stream) : launch_wide<3, 64, false>(i16, w16, out, p, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -8,6 +8,19 @@
 namespace kst {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
+// One 32x32x16 MFMA on eight 16-bit values per lane and operand: bfloat16, or half precision
+// (the operands travel through the kernels as bit patterns; only the multiply tells them apart).
+template <bool F16>
+__device__ __forceinline__ floatx16 mfma16(bf16x8 a, bf16x8 b, floatx16 c)
+{
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
 // constant expression inside the body, so register arrays are only ever indexed by constants.
@@ -64,7 +77,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     int splits = 1;
     double est;
     {
-        const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt == KST_BF16 ? 1.0e12 : 2.0e11);
+        const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt != KST_F32 ? 1.0e12 : 2.0e11);
         const double out_b = (double)s.B * s.Cout * s.M * s.M * 4.0;
         double best = (double)((tiles + 255) / 256) * tile_s;
         const double unsplit = best;

@@ -32,9 +32,19 @@ __host__ __device__ constexpr int tap_class(int n, int T)
     return c;
 }
 
-// Operand element -> fp32.  bfloat16 operands travel as raw 16-bit patterns.
+// Operand element -> fp32.  bfloat16 operands travel as raw 16-bit patterns (uint16_t), half
+// precision ones as half_bits.
+struct half_bits {
+    uint16_t v;
+    half_bits() = default;
+    __host__ __device__ explicit half_bits(int bits) : v((uint16_t)bits) {}
+};
 __device__ inline float to_f32(float v) { return v; }
 __device__ inline float to_f32(uint16_t v) { return __uint_as_float((unsigned)v << 16); }
+__device__ inline float to_f32(half_bits h) { return (float)__builtin_bit_cast(_Float16, h.v); }
+
+// The two 16-bit operand types share layouts, sizes and kernels.
+inline bool is16(kst_dtype dt) { return dt == KST_BF16 || dt == KST_F16; }
 
 // 16-byte aligned streaming store: output lines are written once and never read back by
 // the kernel that writes them, so they need not stay in L2 (measured: a map-sized output
@@ -63,7 +73,7 @@ inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
 }
 
 // Element offset of W_p inside the segregated buffer, and the total size.
-inline size_t seg_cin_padded(int Cin, kst_dtype dt) { return dt == KST_BF16 ? (size_t)((Cin + 7) / 8) * 8 : (size_t)Cin; }
+inline size_t seg_cin_padded(int Cin, kst_dtype dt) { return dt != KST_F32 ? (size_t)((Cin + 7) / 8) * 8 : (size_t)Cin; }
 inline size_t seg_offset(int Cin, int Cout, int n, int p, kst_dtype dt)
 {
     return seg_cin_padded(Cin, dt) * (size_t)Cout * (size_t)class_tap_base(n, p);
@@ -122,18 +132,21 @@ bool igemm_f32_supported(const Shape &s);
 bool igemm_f32_takes_row_stride(const Shape &s);   // s.Ns != s.N is only read by the pipelined fp32 kernel
 bool igemm_bf16_supported(const Shape &s);
 bool igemm_bf16_strip_supported(const Shape &s);   // row-strip variant (quad rows of at most 128 quads)
-hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
+hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                   hipStream_t stream);   // f16: half-precision operands (else bfloat16), here and below
 bool igemm_bf16_ring_supported(const Shape &s);    // LDS-ring variant (n = 2, 3; N = 32, 64, 128; whole channel tiles)
-hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
+hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                  hipStream_t stream);
 bool igemm_bf16_wide_supported(const Shape &s);    // persistent wide-tile variant (same shapes, at least ~one tile per CU)
-hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, hipStream_t stream);
+hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                  hipStream_t stream);
 // force_even: take the even-share launch whenever igemm_f32_even_shares_possible, whatever the cost model says.
 bool igemm_f32_even_shares_possible(const Shape &s);
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even = false);
 size_t igemm_bf16_workspace_bytes(const Shape &s);
 hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
                             bool force_even, hipStream_t stream);
-hipError_t launch_igemm_bf16(const void *in, const void *w_seg, float *out, void *ws, const Shape &s,
+hipError_t launch_igemm_bf16(const void *in, const void *w_seg, float *out, void *ws, const Shape &s, bool f16,
                              hipStream_t stream);
 
 }  // namespace kst

@@ -60,7 +60,7 @@ hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, i
 {
     const unsigned planes = (unsigned)B * (unsigned)Cin;
     const size_t total = (size_t)planes * (N + 2 * q) * Ns;
-    if (dt == KST_BF16)
+    if (is16(dt))
         hipLaunchKernelGGL(frame_input_kernel<uint16_t>, dim3(grid_for(total)), dim3(256), 0, stream,
                            (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q, Ns);
     else

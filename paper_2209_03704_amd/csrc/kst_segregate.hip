@@ -83,7 +83,7 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
     g.Cin = Cin;
     g.Cout = Cout;
     g.n = n;
-    g.group = dt == KST_BF16 ? 8 : 1;
+    g.group = is16(dt) ? 8 : 1;
     g.cin_pad = (int)seg_cin_padded(Cin, dt);
     for (int p = 0; p < 4; ++p) {
         g.off[p] = (unsigned)seg_offset(Cin, Cout, n, p, dt);
@@ -101,7 +101,7 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
             return hipGetLastError();
         }
     }
-    if (dt == KST_BF16)
+    if (is16(dt))
         hipLaunchKernelGGL(segregate_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
                            (const uint16_t *)w, (uint16_t *)w_seg, g);
     else

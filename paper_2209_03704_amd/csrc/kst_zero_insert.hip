@@ -68,6 +68,8 @@ hipError_t launch_zero_insert(const void *in, const void *w, void *U, float *out
 {
     if (dt == KST_BF16)
         return run<uint16_t>((const uint16_t *)in, (const uint16_t *)w, (uint16_t *)U, out, s, stream);
+    if (dt == KST_F16)
+        return run<half_bits>((const half_bits *)in, (const half_bits *)w, (half_bits *)U, out, s, stream);
     return run<float>((const float *)in, (const float *)w, (float *)U, out, s, stream);
 }
 

@@ -16,7 +16,7 @@ from __future__ import annotations
 from .workloads import Layer
 
 HBM_PEAK_GBS = 8000.0
-MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 
 
 def useful_macs(layer: Layer) -> int:
@@ -33,7 +33,7 @@ def conventional_macs(layer: Layer) -> int:
 
 
 def algorithmic_bytes(layer: Layer) -> int:
-    eb = 2 if layer.dtype == "bf16" else 4
+    eb = 2 if layer.dtype in ("bf16", "f16") else 4
     n_in = layer.B * layer.Cin * layer.N ** 2
     n_w = layer.Cout * layer.Cin * layer.n ** 2
     n_out = layer.B * layer.Cout * layer.M ** 2
@@ -42,5 +42,5 @@ def algorithmic_bytes(layer: Layer) -> int:
 
 def upsampled_bytes(layer: Layer) -> int:
     """The (2N-1)^2 buffer the conventional method writes and re-reads."""
-    eb = 2 if layer.dtype == "bf16" else 4
+    eb = 2 if layer.dtype in ("bf16", "f16") else 4
     return eb * layer.B * layer.Cin * (2 * layer.N - 1) ** 2

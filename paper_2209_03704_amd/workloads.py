@@ -25,7 +25,7 @@ class Layer:
     Cout: int
     N: int          # input map edge
     n: int          # kernel edge
-    dtype: str      # "f32" | "bf16" (bf16 operands, fp32 accumulate and output)
+    dtype: str      # "f32" | "bf16" | "f16" (16-bit operands, fp32 accumulate and output)
     in_dist: str    # "uniform" | "normal" | "relu_normal"
     w_std: float = 0.02
     P: int = 0      # padding factor on the up-sampled map
@@ -115,6 +115,9 @@ def make_tensors(layer: Layer, seed: int | None = None):
     if layer.dtype == "bf16":
         x = x.to(torch.bfloat16)
         w = w.to(torch.bfloat16)
+    elif layer.dtype == "f16":
+        x = x.to(torch.float16)
+        w = w.to(torch.float16)
     elif layer.dtype != "f32":
         raise ValueError(layer.dtype)
     return x.contiguous(), w.contiguous()

@@ -14,7 +14,7 @@ from paper_2209_03704_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 2e-5, "bf16": 1e-2}
+TOL = {"f32": 2e-5, "bf16": 1e-2, "f16": 2e-5}     # f16: exact products, fp32 sums, as for fp32 operands
 DEV = "cuda:0"
 
 
@@ -85,19 +85,20 @@ def expected_segregation(w: torch.Tensor) -> torch.Tensor:
     return torch.cat(parts)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("Cin,Cout,n", [(1, 1, 3), (3, 2, 5), (5, 7, 4), (16, 33, 1), (9, 4, 2), (13, 3, 7),
                                           (40, 70, 6), (100, 96, 5), (64, 128, 4), (33, 40, 3), (130, 32, 2)])
 def test_segregate_weights_is_the_documented_permutation(dtype, Cin, Cout, n):
     g = torch.Generator().manual_seed(Cin * 100 + Cout * 10 + n)
     w = torch.randn((Cout, Cin, n, n), generator=g)
-    if dtype == "bf16":
-        w = w.to(torch.bfloat16)
+    if dtype != "f32":
+        w = w.to(torch.bfloat16 if dtype == "bf16" else torch.float16)
     got = kst.kst_segregate_weights(w.to(DEV)).cpu()
     want = expected_segregation(w)
-    assert got.numel() == want.numel() == kst.kst_segregated_elems(Cin, Cout, n, 0 if dtype == "f32" else 1)
-    assert torch.equal(got.view(torch.int16 if dtype == "bf16" else torch.int32),
-                       want.contiguous().view(torch.int16 if dtype == "bf16" else torch.int32))
+    code = {"f32": kst.KST_F32, "bf16": kst.KST_BF16, "f16": kst.KST_F16}[dtype]
+    assert got.numel() == want.numel() == kst.kst_segregated_elems(Cin, Cout, n, code)
+    assert torch.equal(got.view(torch.int32 if dtype == "f32" else torch.int16),
+                       want.contiguous().view(torch.int32 if dtype == "f32" else torch.int16))
 
 
 # ----------------------------------------------------------------------------
@@ -532,7 +533,7 @@ def test_padded_forward_full_size_sampled_planes(B, Cin, Cout, N, n, P, dtype):
 # ----------------------------------------------------------------------------
 # Gradients (end of Section 3.3)
 # ----------------------------------------------------------------------------
-GRAD_TOL = {"f32": 2e-5, "bf16": 2e-5}     # operands are exact in both cases; the sums are fp32
+GRAD_TOL = {"f32": 2e-5, "bf16": 2e-5, "f16": 2e-5}     # operands are exact in both cases; the sums are fp32
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -804,3 +805,42 @@ def test_forward_seeded_shapes_on_every_path_that_takes_them(B, Cin, Cout, N, n,
         e = rel_err(got.cpu().numpy(), want)
         assert e <= TOL[dtype], "%s: rel err %.3e" % (name, e)
     assert "auto" in ran and "direct" in ran
+
+
+# ----------------------------------------------------------------------------
+# Half-precision operands: the 16-bit kernels with the other multiply
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("B,Cin,Cout,N,n,paths", [
+    (2, 48, 32, 22, 3, ("igemm", "forward", "direct")),      # row-strip kernel
+    (1, 17, 33, 50, 1, ("igemm", "forward", "direct")),      # ... n = 1, ragged channels
+    (2, 48, 64, 32, 2, ("igemm", "forward", "direct")),      # LDS-ring kernel
+    (1, 64, 64, 64, 3, ("igemm", "forward", "direct")),      # ... the ring wraps
+    (4, 32, 256, 64, 3, ("igemm", "forward")),               # persistent wide-tile kernel
+    (29, 112, 128, 32, 2, ("igemm", "forward")),             # ... seven chunks
+    (2, 24, 40, 9, 5, ("igemm", "forward", "direct")),       # the plain 16-bit matrix-core kernel
+    (1, 3, 2, 20, 4, ("direct", "forward", "zero_insert")),  # few channels
+    (2, 1, 1, 33, 5, ("direct", "forward", "zero_insert")),  # one channel
+])
+def test_half_precision_forward(B, Cin, Cout, N, n, paths):
+    layer = wl.Layer("f16", B, Cin, Cout, N, n, "f16", "relu_normal", w_std=0.1)
+    check_layer(layer, paths=paths, seed=N * 11 + n)
+
+
+def test_half_precision_wide_kernel_is_exact_on_integers():
+    """Small integers are exact in half precision and in the fp32 accumulators."""
+    layer = wl.Layer("wide_int_f16", 5, 32, 256, 64, 3, "f16", "integer")
+    x, w = wl.make_tensors(layer, 14)
+    out = kst.kst_forward_seg(x.to(DEV), kst.kst_segregate_weights(w.to(DEV)), layer.Cout, layer.n, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.forward(wl.to_f64(x), wl.to_f64(w)))
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", [s[:6] + ("f16",) for s in _seeded_forward_shapes(16, 20260514)])
+def test_half_precision_forward_seeded_shapes(B, Cin, Cout, N, n, P, dtype):
+    test_forward_seeded_shapes_on_every_path_that_takes_them(B, Cin, Cout, N, n, P, dtype)
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", [s[:6] + ("f16",) for s in _seeded_few_channel_shapes(12, 20260515)] +
+                         [(2, 64, 32, 8, 4, 2, "f16"), (1, 128, 3, 8, 4, 2, "f16")])
+def test_half_precision_gradients(B, Cin, Cout, N, n, P, dtype):
+    test_gradients_of_few_channel_layers_seeded_shapes(B, Cin, Cout, N, n, P, dtype)

@@ -84,7 +84,7 @@ def test_argument_errors_are_statuses_not_crashes():
     assert l.kst_forward_zero_insert(one, one, None, one, 1, 1, 1, 4, 3, 0, None) == 1
     # dtype
     assert l.kst_forward(one, one, one, 1, 1, 1, 4, 3, 7, None) == 3
-    assert l.kst_segregate_weights(one, one, 1, 1, 3, 2, None) == 3
+    assert l.kst_segregate_weights(one, one, 1, 1, 3, 3, None) == 3
     # shapes: a size < 1, kernel larger than the up-sampled map, tensors of 2^31 elements
     assert l.kst_forward(one, one, one, 0, 1, 1, 4, 3, 0, None) == 2
     assert l.kst_forward(one, one, one, 1, 1, 1, 2, 5, 0, None) == 2
