@@ -187,10 +187,11 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out,
  * kst_forward_seg_padded (kernels up to 7 x 7 need none of `in` and no framed
  * result: they visit the unframed positions only; odd P frames g by one pixel),
  * for the zero-framed copy of g the matrix-core kernel-gradient kernel reads,
- * and for the partial sums of split reductions (the matrix-core kernels: fp32
- * operands, n <= 5, at least 8 channels on either side, or at least 64 input
- * channels with a few output channels; the other kernel-gradient kernels when
- * they slice the positions); it
+ * for the partial sums of split reductions (the matrix-core kernels: n <= 5,
+ * at least 8 channels on either side, or at least 64 input channels with a few
+ * output channels; the other kernel-gradient kernels when they slice the
+ * positions), and for the fp32 copy of w or in that the matrix-core kernels
+ * read when the operands are 16-bit (widening is exact); it
  * may be 0 (then ws may be NULL).  The byte count depends
  * on the shape only, never on the pointers, as in
  * kst_forward_seg_padded.  Pointers, alignment, stream and statuses as above.

@@ -316,6 +316,9 @@ struct GradPlan {
     size_t gw_bytes;                  // kernel gradient on the matrix cores: its framed copy of g (replaces g_bytes)
     int gw_frame, gw_stride;          // frame on the caller's g and row stride of that copy
     bool plain_unframed;              // the other kernels work on the unframed positions too (kernels up to 7 x 7)
+    bool din_cores, dw_cores;         // the gradient runs on the matrix cores (fp32 kernels; 16-bit operands are
+                                      // widened to fp32 first, which is exact)
+    size_t wconv_bytes, xconv_bytes;  // fp32 copies of w (input gradient) and of in (kernel gradient) for that
 };
 
 kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt, GradPlan *f)
@@ -336,19 +339,23 @@ kst_status grad_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dt
     f->si.frame = f->q;
     f->split_bytes = 0;
     f->plain_unframed = backward_generic_takes_frame(f->si);
-    if (backward_input_igemm_supported(f->si, dt)) {
+    f->din_cores = backward_input_igemm_supported(f->si, KST_F32);
+    f->dw_cores = backward_weight_igemm_supported(f->si, KST_F32);
+    f->wconv_bytes = is16(dt) && f->din_cores ? (((size_t)Cout * Cin * n * n * sizeof(float) + 255) & ~(size_t)255) : 0;
+    f->xconv_bytes = is16(dt) && f->dw_cores ? (((size_t)B * Cin * N * N * sizeof(float) + 255) & ~(size_t)255) : 0;
+    if (f->din_cores) {
         f->split_bytes = backward_input_igemm_workspace_bytes(f->si);
         f->din_bytes = 0;                              // written in place, frame never computed
     } else if (f->plain_unframed) {
         f->din_bytes = 0;
     }
     if (f->plain_unframed) f->in_bytes = 0;            // `in` read as it lies in memory
-    f->wsplit_bytes = backward_weight_igemm_supported(f->si, dt)
+    f->wsplit_bytes = f->dw_cores
                           ? backward_weight_igemm_workspace_bytes(f->si)
                           : backward_weight_generic_workspace_bytes(f->plain_unframed ? f->si : f->s);
     f->gw_bytes = 0;
     f->gw_frame = f->gw_stride = 0;
-    if (backward_weight_igemm_supported(f->si, dt)) {
+    if (f->dw_cores) {
         int frame, stride;
         backward_weight_igemm_g_copy(f->si, &frame, &stride);
         f->gw_frame = frame + (P & 1);                 // on top of the odd padding factor's one-pixel frame
@@ -365,15 +372,14 @@ size_t kst_backward_input_workspace_bytes(int B, int Cin, int Cout, int N, int n
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return f.g_bytes + f.din_bytes + f.split_bytes;
+    return f.g_bytes + f.din_bytes + f.split_bytes + f.wconv_bytes;
 }
 
 size_t kst_backward_weight_workspace_bytes(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype)
 {
     GradPlan f;
     if (!dtype_ok(dtype) || grad_plan(B, Cin, Cout, N, n, P, dtype, &f) != KST_OK) return 0;
-    return backward_weight_igemm_supported(f.si, dtype) ? f.gw_bytes + f.wsplit_bytes
-                                                         : f.in_bytes + f.g_bytes + f.wsplit_bytes;
+    return f.dw_cores ? f.gw_bytes + f.wsplit_bytes + f.xconv_bytes : f.in_bytes + f.g_bytes + f.wsplit_bytes;
 }
 
 kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws, size_t ws_bytes,
@@ -385,7 +391,7 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(g) || !aligned16(w) || !aligned16(din)) return KST_ERR_ALIGN;
-    const size_t need = f.g_bytes + f.din_bytes + f.split_bytes;
+    const size_t need = f.g_bytes + f.din_bytes + f.split_bytes + f.wconv_bytes;
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
@@ -396,10 +402,16 @@ kst_status kst_backward_input(const void *g, const void *w, void *din, void *ws,
         if (launch_frame_input(g, ws, B, Cout, f.M, 1, f.Mq, KST_F32, stream) != hipSuccess) return KST_ERR_HIP;
         g_in = (const float *)ws;
     }
-    if (backward_input_igemm_supported(f.si, dtype)) {
+    if (f.din_cores) {
         // the matrix-core kernels compute the unframed positions only, straight into din
         void *split_ws = f.split_bytes ? (char *)ws + f.g_bytes : nullptr;
-        return launch_backward_input_igemm(g_in, (const float *)w, (float *)din, split_ws, f.si, stream) == hipSuccess
+        const float *w32 = (const float *)w;
+        if (f.wconv_bytes) {
+            float *wc = (float *)((char *)ws + f.g_bytes + f.split_bytes);
+            if (launch_widen(w, wc, (size_t)Cout * Cin * n * n, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+            w32 = wc;
+        }
+        return launch_backward_input_igemm(g_in, w32, (float *)din, split_ws, f.si, stream) == hipSuccess
                    ? KST_OK
                    : KST_ERR_HIP;
     }
@@ -420,10 +432,10 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     kst_status st = grad_plan(B, Cin, Cout, N, n, P, dtype, &f);
     if (st != KST_OK) return st;
     if (!aligned16(in) || !aligned16(g) || !aligned16(dw)) return KST_ERR_ALIGN;
-    const bool cores = backward_weight_igemm_supported(f.si, dtype);
+    const bool cores = f.dw_cores;
     const size_t g_copy = cores ? f.gw_bytes : f.g_bytes;
     const size_t in_copy = cores ? 0 : f.in_bytes;     // the matrix-core kernel reads `in` as it lies in memory
-    const size_t need = in_copy + g_copy + f.wsplit_bytes;
+    const size_t need = in_copy + g_copy + f.wsplit_bytes + (cores ? f.xconv_bytes : 0);
     if (need) {
         if (!ws || ws_bytes < need) return KST_ERR_WORKSPACE;
         if (!aligned16(ws)) return KST_ERR_ALIGN;
@@ -437,6 +449,11 @@ kst_status kst_backward_weight(const void *in, const void *g, void *dw, void *ws
     void *gw = (char *)ws + in_copy;
     void *partial_ws = f.wsplit_bytes ? (char *)ws + in_copy + g_copy : nullptr;
     if (cores) {
+        if (f.xconv_bytes) {
+            float *xc = (float *)((char *)ws + in_copy + g_copy + f.wsplit_bytes);
+            if (launch_widen(in, xc, (size_t)B * Cin * N * N, dtype, stream) != hipSuccess) return KST_ERR_HIP;
+            x_in = xc;
+        }
         // g framed once for the odd padding factor and for the kernel's own bounds-free reads
         if (launch_frame_input(g, gw, B, Cout, f.M, f.gw_frame, f.gw_stride, KST_F32, stream) != hipSuccess)
             return KST_ERR_HIP;

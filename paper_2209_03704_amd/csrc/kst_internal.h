@@ -97,6 +97,8 @@ hipError_t launch_yardstick_copy(const void *src, void *dst, size_t bytes, hipSt
 hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, int N, int q, int Ns, kst_dtype dt,
                               hipStream_t stream);
 hipError_t launch_crop(const float *wide, float *out, int planes_b, int planes_c, int M, int q, hipStream_t stream);
+// dst (fp32) = src (16-bit operands of type dt), element by element.
+hipError_t launch_widen(const void *src, float *dst, size_t elems, kst_dtype dt, hipStream_t stream);
 // Gradients, P = 0, any shape (plain ALU kernels).  g, din and dw are fp32; w and in are of type dt.
 bool backward_generic_takes_frame(const Shape &s);     // these two skip Shape::frame themselves (else: frame must be 0)
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,

@@ -47,6 +47,13 @@ __global__ void __launch_bounds__(256) crop_kernel(const float *__restrict__ src
     }
 }
 
+// dst[i] = src[i] widened to fp32 (exact for both 16-bit types).
+template <typename T>
+__global__ void __launch_bounds__(256) widen_kernel(const T *__restrict__ src, float *__restrict__ dst, size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) dst[i] = to_f32(src[i]);
+}
+
 unsigned grid_for(size_t total)
 {
     const size_t blocks = (total + 255) / 256;
@@ -66,6 +73,19 @@ hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, i
     else
         hipLaunchKernelGGL(frame_input_kernel<float>, dim3(grid_for(total)), dim3(256), 0, stream, (const float *)in,
                            (float *)in_framed, planes, N, q, Ns);
+    return hipGetLastError();
+}
+
+hipError_t launch_widen(const void *src, float *dst, size_t elems, kst_dtype dt, hipStream_t stream)
+{
+    if (dt == KST_BF16)
+        hipLaunchKernelGGL(widen_kernel<uint16_t>, dim3(grid_for(elems)), dim3(256), 0, stream, (const uint16_t *)src, dst,
+                           elems);
+    else if (dt == KST_F16)
+        hipLaunchKernelGGL(widen_kernel<half_bits>, dim3(grid_for(elems)), dim3(256), 0, stream, (const half_bits *)src, dst,
+                           elems);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

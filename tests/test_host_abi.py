@@ -153,6 +153,13 @@ def test_gradient_workspaces_follow_the_kernels_that_run():
     Mg = kst.kst_out_size_padded(16, 4, 2)               # 32; framed by n - 1 = 3
     need = kst.kst_backward_weight_workspace_bytes(64, 256, 128, 16, 4, 2, f32)
     assert need >= 64 * 128 * (Mg + 6) * (Mg + 6) * 4
+    # 16-bit operands on the matrix cores: the fp32 kernels after an exact widening of w (input
+    # gradient) or in (kernel gradient) into the workspace
+    for dt in (kst.KST_BF16, kst.KST_F16):
+        assert (kst.kst_backward_input_workspace_bytes(64, 256, 128, 16, 4, 2, dt)
+                == kst.kst_backward_input_workspace_bytes(64, 256, 128, 16, 4, 2, f32) + 128 * 256 * 16 * 4)
+        assert (kst.kst_backward_weight_workspace_bytes(64, 256, 128, 16, 4, 2, dt)
+                == kst.kst_backward_weight_workspace_bytes(64, 256, 128, 16, 4, 2, f32) + 64 * 256 * 16 * 16 * 4)
     # illegal shapes give 0
     assert kst.kst_backward_weight_workspace_bytes(1, 1, 1, 1, 9, 0, f32) == 0
     assert kst.kst_backward_input_workspace_bytes(0, 1, 1, 8, 3, 0, f32) == 0
