@@ -14,20 +14,21 @@ namespace kst {
 namespace {
 
 // dst[b*c][Nq][Ns] = src[b*c][N][N] framed by q zeros, rows Ns >= Nq = N + 2q elements apart
-// (the elements past Nq are zeros too); one thread per element.
-template <typename T>
+// (the elements past Nq are zeros too); one thread per element.  I: index type (32 bits while the
+// copy has fewer than 2^32 elements: its two divisions per element are what the kernel costs).
+template <typename T, typename I>
 __global__ void __launch_bounds__(256) frame_input_kernel(const T *__restrict__ src, T *__restrict__ dst, unsigned planes,
                                                           int N, int q, int Ns)
 {
     const int Nq = N + 2 * q;
-    const size_t total = (size_t)planes * Nq * Ns;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const size_t row = i / (unsigned)Ns;
+    const I total = (I)planes * (I)Nq * (I)Ns;
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I row = i / (unsigned)Ns;
         const int x = (int)(i - row * (unsigned)Ns) - q;
-        const size_t plane = row / (unsigned)Nq;
+        const I plane = row / (unsigned)Nq;
         const int y = (int)(row - plane * (unsigned)Nq) - q;
         T v = (T)0;
-        if (x >= 0 && x < N && y >= 0 && y < N) v = src[(plane * N + y) * N + x];
+        if (x >= 0 && x < N && y >= 0 && y < N) v = src[((size_t)plane * N + y) * N + x];
         dst[i] = v;
     }
 }
@@ -67,12 +68,22 @@ hipError_t launch_frame_input(const void *in, void *in_framed, int B, int Cin, i
 {
     const unsigned planes = (unsigned)B * (unsigned)Cin;
     const size_t total = (size_t)planes * (N + 2 * q) * Ns;
-    if (is16(dt))
-        hipLaunchKernelGGL(frame_input_kernel<uint16_t>, dim3(grid_for(total)), dim3(256), 0, stream,
-                           (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q, Ns);
-    else
-        hipLaunchKernelGGL(frame_input_kernel<float>, dim3(grid_for(total)), dim3(256), 0, stream, (const float *)in,
-                           (float *)in_framed, planes, N, q, Ns);
+    const bool small = total + (size_t)8192 * 256 < 0xffffffffu;      // the grid-stride index stays inside 32 bits
+    if (is16(dt)) {
+        if (small)
+            hipLaunchKernelGGL((frame_input_kernel<uint16_t, unsigned>), dim3(grid_for(total)), dim3(256), 0, stream,
+                               (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q, Ns);
+        else
+            hipLaunchKernelGGL((frame_input_kernel<uint16_t, size_t>), dim3(grid_for(total)), dim3(256), 0, stream,
+                               (const uint16_t *)in, (uint16_t *)in_framed, planes, N, q, Ns);
+    } else {
+        if (small)
+            hipLaunchKernelGGL((frame_input_kernel<float, unsigned>), dim3(grid_for(total)), dim3(256), 0, stream,
+                               (const float *)in, (float *)in_framed, planes, N, q, Ns);
+        else
+            hipLaunchKernelGGL((frame_input_kernel<float, size_t>), dim3(grid_for(total)), dim3(256), 0, stream,
+                               (const float *)in, (float *)in_framed, planes, N, q, Ns);
+    }
     return hipGetLastError();
 }
 
