@@ -30,10 +30,10 @@ if ROOT not in sys.path:
 # profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
 # kernels, quoted next to the live timing; None for a layer that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_1ch_bandwidth": 339383366,
-    "cfg3_gan_n4": 513561477 + 137492555,   # matrix-core kernel + pass summing the partial tiles
-    "cfg4_deep_n5": 576974032 + 100628644,  # the same two kernels
-    "cfg5_late_bf16": 352496228,
+    "cfg2_1ch_bandwidth": 339385417,
+    "cfg3_gan_n4": 513565875 + 137499522,   # matrix-core kernel + pass summing the partial tiles
+    "cfg4_deep_n5": 576979908 + 100629937,  # the same two kernels
+    "cfg5_late_bf16": 352252164,
 }
 
 
