@@ -603,7 +603,13 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
                                                                   float *__restrict__ dst, BwdWParams p)
 {
     constexpr int NN = n * n;
-    constexpr int TW = FOLD ? 1 : (NN + 3) / 4;                  // taps (row blocks) per wave at most
+    // With two channel blocks and a tap count that four waves cannot share evenly (n odd), a wave
+    // takes one channel block and every second tap instead of both blocks and every fourth tap:
+    // 3 x 3 kernels then keep the waves busy 5 : 5 : 4 : 4 instead of 6 : 4 : 4 : 4.
+    constexpr bool PAIR = CB == 2 && !FOLD && NN % 4 != 0;
+    constexpr int TSTEP = PAIR ? 2 : 4;                          // taps tw0, tw0 + TSTEP, ... belong to a wave
+    constexpr int CBW = PAIR ? 1 : CB;                           // channel blocks a wave multiplies
+    constexpr int TW = FOLD ? 1 : PAIR ? (NN + 1) / 2 : (NN + 3) / 4;   // taps (row blocks) per wave at most
     constexpr int GC = FOLD ? W_FOLD_CO : W_T;                   // channels of g staged per chunk
     constexpr int THREADS = 256 * H;
     constexpr int RH = R / H;                                    // rows per quartet
@@ -630,7 +636,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6) & 3;      // owner of taps wave, wave + 4, ...
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6) & 3;      // owner of taps wave, wave + 4, ... (or see PAIR)
     const int half = __builtin_amdgcn_readfirstlane(tid >> 8);         // quartet
     const int l32 = lane & 31, kk = lane >> 5;
 
@@ -666,19 +672,21 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
         g_lds[k] = ok ? CI_T * IS + co * GS + rem : dump;
     }
 
-    floatx16 acc[TW][CB];
+    const int tw0 = PAIR ? wave >> 1 : wave;                     // this wave's first tap
+    const int cw0 = PAIR ? wave & 1 : 0;                         // ... and first channel block
+    floatx16 acc[TW][CBW];
 #pragma unroll
     for (int t = 0; t < TW; ++t)
 #pragma unroll
-        for (int c = 0; c < CB; ++c)
+        for (int c = 0; c < CBW; ++c)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][c][v] = 0.0f;
 
     const int chunk_begin = split * p.chunks_per_split;
     const int chunk_end = min(p.nchunks, chunk_begin + p.chunks_per_split);
     // B operand: input channel l32 of block 0, this quartet's first row, position 2 k + kk
-    const int ibase = l32 * IS + kk + half * RH * CW;
-    // A operand: output channel l32, row 0, position 2 k + kk, tap t of this wave (wave + 4 t): its cell at k = 0
+    const int ibase = l32 * IS + kk + half * RH * CW + cw0 * W_T * IS;
+    // A operand: output channel l32, row 0, position 2 k + kk, tap t of this wave (tw0 + TSTEP t): its cell at k = 0
     int abase[TW];
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
@@ -688,7 +696,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
             const int u = uv / n, v = uv - u * n;
             abase[t] = CI_T * IS + co * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
         } else {
-            const int uv = min(wave + 4 * t, NN - 1);            // (a tap past the last is not multiplied)
+            const int uv = min(tw0 + TSTEP * t, NN - 1);         // (a tap past the last is not multiplied)
             const int u = uv / n, v = uv - u * n;
             abase[t] = CI_T * IS + l32 * GS + 2 * kk + (n - 1) + (n - 1 - u) * GL - v + 2 * half * RH * GL;
         }
@@ -756,8 +764,8 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     // it takes beyond the first one's run time: the items are dealt out over the MFMAs of the taps
     // every wave has (the last tap may belong to fewer waves).  1 x 1 kernels have no such tap
     // (one wave multiplies): there the items go in one block.  (Folded rows: over all MFMA slots.)
-    constexpr int TS = FOLD ? 0 : NN % 4 == 0 ? TW : TW - 1;
-    constexpr int SLOTS = TS > 0 ? RH * TS * KS * CB : 1;
+    constexpr int TS = FOLD ? 0 : PAIR ? NN / 2 : NN % 4 == 0 ? TW : TW - 1;
+    constexpr int SLOTS = TS > 0 ? RH * TS * KS * CBW : 1;
     int cur = 0;
     for (int ch = chunk_begin; ch < chunk_end; ++ch) {
         const float *S = lds + cur;
@@ -765,11 +773,12 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
         aim();
         __builtin_amdgcn_sched_barrier(0);
         float bf[CB][KS], af[2][KS];               // the A values of tap t + 1 are read before tap t is multiplied
+        constexpr int CBL = FOLD ? CB : CBW;       // channel blocks whose B values this wave reads
         static_for<RH * TW>([&](auto qc) {
             constexpr int r = decltype(qc)::value / TW, t = decltype(qc)::value % TW;
             if constexpr (t == 0) {
 #pragma unroll
-                for (int c = 0; c < CB; ++c)
+                for (int c = 0; c < CBL; ++c)
 #pragma unroll
                     for (int k = 0; k < KS; ++k) bf[c][k] = S[ibase + c * W_T * IS + r * CW + 2 * k];
 #pragma unroll
@@ -793,13 +802,13 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
                     __builtin_amdgcn_sched_barrier(0);
                 });
             }
-            // every wave has taps 0 .. TS - 1; the last one only while wave + 4 (TW - 1) < NN
-            if (!FOLD && (t < TS || wave + 4 * t < NN)) {
-                static_for<KS * CB>([&](auto mc) {
-                    constexpr int k = decltype(mc)::value / CB, c = decltype(mc)::value % CB;
+            // every wave has its taps 0 .. TS - 1; the last one only while it lies inside the kernel
+            if (!FOLD && (t < TS || tw0 + TSTEP * t < NN)) {
+                static_for<KS * CBW>([&](auto mc) {
+                    constexpr int k = decltype(mc)::value / CBW, c = decltype(mc)::value % CBW;
                     acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][k], bf[c][k], acc[t][c], 0, 0, 0);
                     if constexpr (t < TS) {
-                        constexpr int slot = ((r * TS + t) * KS + k) * CB + c;
+                        constexpr int slot = ((r * TS + t) * KS + k) * CBW + c;
                         constexpr int j0 = slot * ITEMS / SLOTS, j1 = (slot + 1) * ITEMS / SLOTS;
                         static_for<j1 - j0>([&](auto jc) { put(j0 + decltype(jc)::value, other); get(j0 + decltype(jc)::value); });
                     }
@@ -815,7 +824,7 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
 
     // ---- epilogue -------------------------------------------------------------------------------
     // acc[t][c][v]: output channel co0 + 8 (v / 4) + 4 kk + v % 4, input channel ci0 + 32 c + l32,
-    // tap wave + 4 t.  In dw the taps of one (co, ci) lie side by side and the input channels of
+    // tap tw0 + TSTEP t (channel block cw0 + c).  In dw the taps of one (co, ci) lie side by side and the input channels of
     // one co follow each other, so a tile's part of one output channel is ONE run of
     // (channels of the tile) * n * n floats.  Eight output channels at a time go through LDS
     // (the loop's last barrier has passed: nobody reads a stage any more) and leave as whole
@@ -842,19 +851,19 @@ __global__ void __launch_bounds__(256 * H) backward_weight_f32_kernel(const floa
     const int run = min(CI_T, p.Cin - ci0) * NN;                 // floats of one output channel's run
     static_for<4>([&](auto vqc) {
         constexpr int vq = decltype(vqc)::value;
-        auto cell = [&](int t, int c, int j) { return ((4 * kk + j) * CI_T + c * W_T + l32) * NP + wave + 4 * t; };
+        auto cell = [&](int t, int c, int j) { return ((4 * kk + j) * CI_T + (cw0 + c) * W_T + l32) * NP + tw0 + TSTEP * t; };
         if (H == 1 || half == 1) {
-            static_for<TW * CB * 4>([&](auto ec) {
-                constexpr int t = decltype(ec)::value / (CB * 4), c = (decltype(ec)::value / 4) % CB, j = decltype(ec)::value % 4;
-                if (wave + 4 * t < NN) lds[cell(t, c, j)] = acc[t][c][4 * vq + j];
+            static_for<TW * CBW * 4>([&](auto ec) {
+                constexpr int t = decltype(ec)::value / (CBW * 4), c = (decltype(ec)::value / 4) % CBW, j = decltype(ec)::value % 4;
+                if (tw0 + TSTEP * t < NN) lds[cell(t, c, j)] = acc[t][c][4 * vq + j];
             });
         }
         __syncthreads();
         if constexpr (H == 2) {
             if (half == 0) {
-                static_for<TW * CB * 4>([&](auto ec) {
-                    constexpr int t = decltype(ec)::value / (CB * 4), c = (decltype(ec)::value / 4) % CB, j = decltype(ec)::value % 4;
-                    if (wave + 4 * t < NN) lds[cell(t, c, j)] += acc[t][c][4 * vq + j];
+                static_for<TW * CBW * 4>([&](auto ec) {
+                    constexpr int t = decltype(ec)::value / (CBW * 4), c = (decltype(ec)::value / 4) % CBW, j = decltype(ec)::value % 4;
+                    if (tw0 + TSTEP * t < NN) lds[cell(t, c, j)] += acc[t][c][4 * vq + j];
                 });
             }
             __syncthreads();
@@ -934,8 +943,10 @@ BwdWParams plan_w(const Shape &s)
     const int tiles = p.tiles_co * p.tiles_ci;
     // (two-block tiles: counted as one per CU, the setting that measured best)
     const int per_cu = p.cb == 2 ? 1 : s.n <= 3 ? 4 : s.n == 4 ? 3 : 2;
-    const int taps_per_wave = p.fold ? 1 : (s.n * s.n + 3) / 4;
-    const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * taps_per_wave * p.cb * 64.0 / 2.1e9 / 0.45;
+    // MFMA groups a wave runs per row and reduction step (see PAIR in the kernel)
+    const int nn = s.n * s.n;
+    const int groups_per_wave = p.fold ? p.cb : (p.cb == 2 && nn % 4 != 0) ? (nn + 1) / 2 : (nn + 3) / 4 * p.cb;
+    const double chunk_s = (double)per_cu * p.rows * (p.cw / 2) * groups_per_wave * 64.0 / 2.1e9 / 0.45;
     const double out_b = (double)p.out_elems * 4.0;
     int splits = 1;
     double best = 1e30;
