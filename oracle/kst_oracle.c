@@ -133,7 +133,11 @@ int kst_oracle_backward_input(const double *g, const double *w, double *din,
     for (int b = 0; b < B; ++b)
         for (int ci = 0; ci < Cin; ++ci) {
             double *dU = (double *)calloc((size_t)Sp * Sp, sizeof(double));
-            if (!dU) { fail = 1; continue; }
+            if (!dU) {
+#pragma omp atomic write
+                fail = 1;
+                continue;
+            }
             for (int co = 0; co < Cout; ++co) {
                 const double *gp = g + ((size_t)b * Cout + co) * M * M;
                 const double *wk = w + ((size_t)co * Cin + ci) * n * n;

@@ -1,6 +1,6 @@
 """Build libkst.so (HIP, gfx950 only) in-tree with hipcc.
 
-    python -m paper_2209_03704_amd.build
+    python -m paper_2209_03704_amd.build [--incremental]
 
 Every .hip file under csrc/ is compiled to an object (in parallel) and linked
 into paper_2209_03704_amd/libkst.so.  hipcc cross-compiles without a GPU.
@@ -30,8 +30,15 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
+def _headers_mtime() -> float:
+    hdrs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h")) + [__file__]
+    return max(os.path.getmtime(h) for h in hdrs)
+
+
+def _compile(src: str, force: bool = True) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), _headers_mtime()):
+        return obj
     r = subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -42,14 +49,16 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int | None = None) -> str:
+def build_library(jobs: int | None = None, force: bool = True) -> str:
+    """Compile and link.  force=False recompiles only sources newer than their objects (or older
+    than any header): for iterating; the default compiles everything."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     if not srcs:
         raise RuntimeError("no sources under " + CSRC)
     jobs = jobs or min(len(srcs), int(os.environ.get("MAX_JOBS", "8")))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, srcs))
+        objs = list(ex.map(lambda src: _compile(src, force), srcs))
     tmp = LIB + ".tmp.%d" % os.getpid()
     r = subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs],
                        capture_output=True, text=True)
@@ -60,4 +69,4 @@ def build_library(jobs: int | None = None) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(build_library(force="--incremental" not in sys.argv))

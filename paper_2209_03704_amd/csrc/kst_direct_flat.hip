@@ -44,10 +44,7 @@ namespace {
 __device__ __forceinline__ void store_streaming(float *dst, const float (&o)[4]) { store_streaming4(dst, o[0], o[1], o[2], o[3]); }
 
 constexpr int F_PAD = 4;      // slack floats left and right of each staged input row
-#ifndef KST_FLAT_THREADS
-#define KST_FLAT_THREADS 512
-#endif
-constexpr int F_THREADS = KST_FLAT_THREADS;
+constexpr int F_THREADS = 512;
 constexpr int F_NPRE = 1024 / F_THREADS;      // float4 loads in flight per lane (1024 per piece at most)
 constexpr int F_STEP = 4 * F_THREADS;         // floats the workgroup covers per iteration
 constexpr int F_STEP_LOG2 = F_THREADS == 512 ? 11 : 10;

@@ -136,7 +136,7 @@ bool igemm_bf16_supported(const Shape &s);
 bool igemm_bf16_strip_supported(const Shape &s);   // row-strip variant (quad rows of at most 128 quads)
 hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                    hipStream_t stream);   // f16: half-precision operands (else bfloat16), here and below
-bool igemm_bf16_ring_supported(const Shape &s);    // LDS-ring variant (n = 2, 3; N = 32, 64, 128; whole channel tiles)
+bool igemm_bf16_ring_supported(const Shape &s);    // LDS-ring variant (n = 2, 3; N = 32, 64; whole channel tiles)
 hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                   hipStream_t stream);
 bool igemm_bf16_wide_supported(const Shape &s);    // persistent wide-tile variant (same shapes, at least ~one tile per CU)

@@ -1,8 +1,8 @@
 """Parity of the HIP path (through the C ABI) against the CPU fp64 oracle.
 
-Tolerances are the ones the baseline fixes: max|gpu - oracle| <= 2e-5 * max|oracle|
-for fp32, <= 1e-2 * max|oracle| for bf16 operands with fp32 accumulation.  Both
-sides read the same seeded inputs (bf16 cases: the same rounded bits).
+Tolerance: max|gpu - oracle| <= 2e-5 * max|oracle|, the bound the baseline fixes for
+fp32, applied to 16-bit operands too (see TOL below).  Both sides read the same
+seeded inputs (16-bit cases: the same rounded bits).
 """
 import numpy as np
 import pytest
@@ -14,7 +14,12 @@ from paper_2209_03704_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 2e-5, "bf16": 1e-2, "f16": 2e-5}     # f16: exact products, fp32 sums, as for fp32 operands
+# The baseline's contractual bound for bf16 operands is 1e-2 * max|oracle|.  The tests hold them to
+# the fp32 bound instead: both sides read the same rounded operands, a product of two 16-bit
+# values is exact in fp32, and the sums are fp32 -- so only the accumulation order differs, as
+# for fp32 operands.  At 1e-2 a dropped tap among hundreds of terms could pass.
+CONTRACT_TOL = {"f32": 2e-5, "bf16": 1e-2, "f16": 1e-2}
+TOL = {"f32": 2e-5, "bf16": 2e-5, "f16": 2e-5}
 DEV = "cuda:0"
 
 
@@ -59,6 +64,26 @@ def check_layer(layer, paths=("direct", "igemm", "forward", "zero_insert"), seed
         assert np.isfinite(got).all(), name
         e = rel_err(got, want)
         assert e <= TOL[layer.dtype], "%s on %s: rel err %.3e" % (name, layer, e)
+
+
+def check_exact_with_guards(layer, path, seed, P=0):
+    """Small integers are exact in every operand type and in the fp32 sums, so whatever the
+    order of accumulation the result must equal the oracle bit for bit; words before and after
+    `out` must keep their NaN pattern and every element of `out` must be written."""
+    x, w = wl.make_tensors(layer, seed)
+    xd, wd = x.to(DEV), w.to(DEV)
+    M = kst.kst_out_size_padded(layer.N, layer.n, P)
+    shape = (layer.B, layer.Cout, M, M)
+    numel = int(np.prod(shape))
+    guard = 4096
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    out = buf[guard:guard + numel].view(shape)
+    kst.kst_forward_seg_padded(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, P, out=out, path=path)
+    torch.cuda.synchronize()
+    host = buf.cpu()
+    assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    assert np.array_equal(host[guard:guard + numel].view(shape).numpy().astype(np.float64), want)
 
 
 # ----------------------------------------------------------------------------
@@ -240,6 +265,32 @@ def test_igemm_bf16_row_strip_kernel(B, Cin, Cout, N, n):
     check_layer(layer, paths=("igemm", "forward", "direct"), seed=N * 5 + n)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (2, 24, 40, 34, 4),     # E = 32: four quad rows per strip, ragged channel tile, ragged last chunk
+    (1, 17, 33, 50, 1),     # n = 1: three empty sub-kernels whose zeros must be written
+    (2, 48, 32, 22, 3),     # E = 21: six quad rows per strip, last strip short, odd M
+    (1, 9, 16, 128, 3),     # E = 127: one quad row per strip
+])
+def test_igemm_bf16_row_strip_kernel_is_exact_on_integers_and_stays_inside_out(B, Cin, Cout, N, n, dtype):
+    check_exact_with_guards(wl.Layer("strip_int", B, Cin, Cout, N, n, dtype, "integer"), kst.KST_PATH_IGEMM, 21 + N)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n", [
+    (5, 20, 150, 12, 4),    # 2 channel tiles (ragged), tiles straddle batch items
+    (3, 37, 40, 17, 5),     # 5 x 5 kernel (the row-strip kernel stops at 4 x 4), odd Cin, odd M
+    (7, 64, 129, 8, 3),     # tiny maps: many batch items per tile, Cout one over a tile
+    (9, 130, 16, 6, 4),     # reduction split across workgroups (few tiles): partial sums and the summing pass
+    (2, 24, 40, 9, 5),
+    (3, 16, 16, 5, 2),
+])
+def test_igemm_bf16_plain_kernel_is_exact_on_integers_and_stays_inside_out(B, Cin, Cout, N, n, dtype):
+    """Maps with fewer than 16 quads per row, odd maps and kernels beyond 4 x 4 take the first
+    16-bit matrix-core kernel."""
+    check_exact_with_guards(wl.Layer("plain_int", B, Cin, Cout, N, n, dtype, "integer"), kst.KST_PATH_IGEMM, 31 + N)
+
+
 @pytest.mark.parametrize("B,Cin,Cout,N,n", [
     (2, 32, 64, 32, 3),     # E = 31: one column block, four quad rows per tile, last tile short
     (2, 48, 64, 32, 2),     # even kernel, three chunks
@@ -317,7 +368,7 @@ def test_igemm_bf16_wide_kernel_is_exact_on_integers_and_stays_inside_out():
     (83, 8, 256, 16, 4),     # 256 tiles: whole tiles only, nothing shared and no second pass
     (16, 16, 256, 16, 4),    # 50 tiles x 4 chunks: fewer units than workgroups
 ])
-def test_igemm_f32_even_shares_sampled_planes(B, Cin, Cout, N, n):
+def test_igemm_f32_even_shares(B, Cin, Cout, N, n):
     """fp32 matrix-core path where the (tile, chunk) list is cut into equal ranges: pieces that
     are whole tiles, pieces that go through the partial slots, and their sum in a second pass."""
     layer = wl.Layer("shares", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
@@ -336,11 +387,9 @@ def test_igemm_f32_even_shares_sampled_planes(B, Cin, Cout, N, n):
     assert rel_err(out.cpu().numpy(), whole.cpu().numpy().astype(np.float64)) <= TOL["f32"]
     assert torch.isfinite(out).all()
     assert torch.equal(out, again)                     # fixed summing order: bit-reproducible
-    b_idx, co_idx = sample_planes(layer, 48, Cin)
-    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx)
-    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
-    e = rel_err(got, want)
-    assert e <= TOL["f32"], "rel err %.3e" % e
+    b_idx, co_idx = covering_planes(B, Cout)
+    check_planes(out, x, w, b_idx, co_idx, TOL["f32"])
+    check_channel_projection(out, x, w, TOL["f32"], seed=Cin)
 
 
 def test_igemm_f32_even_shares_are_exact_on_integers_and_stay_inside_out():
@@ -355,10 +404,8 @@ def test_igemm_f32_even_shares_are_exact_on_integers_and_stay_inside_out():
     torch.cuda.synchronize()
     host = buf.cpu()
     assert torch.isnan(host[:guard]).all() and torch.isnan(host[guard + numel:]).all()
-    b_idx, co_idx = sample_planes(layer, 32, 5)
-    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx)
-    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy().astype(np.float64)
-    assert np.array_equal(got, want)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w))
+    assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
 
 
 # ----------------------------------------------------------------------------
@@ -402,13 +449,45 @@ def test_runs_on_a_side_stream():
 # ----------------------------------------------------------------------------
 # The five benchmark layers at full size, in the configuration bench.py times
 # ----------------------------------------------------------------------------
-def sample_planes(layer, count, seed):
-    rng = np.random.default_rng(seed)
-    pairs = {(0, 0), (layer.B - 1, layer.Cout - 1), (0, layer.Cout - 1), (layer.B - 1, 0)}
-    while len(pairs) < min(count, layer.B * layer.Cout):
-        pairs.add((int(rng.integers(layer.B)), int(rng.integers(layer.Cout))))
-    pairs = sorted(pairs)
-    return [p[0] for p in pairs], [p[1] for p in pairs]
+def covering_planes(B, Cout, group=32):
+    """Every batch item with one output channel of every `group` consecutive channels (the
+    matrix-core kernels store blocks of 32 channels of tiles of 64 or 128); the channel inside
+    the group moves with the batch item, so that over the batch every channel is visited."""
+    b_idx, co_idx = [], []
+    for b in range(B):
+        for g0 in range(0, Cout, group):
+            width = min(group, Cout - g0)
+            b_idx.append(b)
+            co_idx.append(g0 + (5 * b + 3 * (g0 // group)) % width)
+    return b_idx, co_idx
+
+
+def check_planes(out, x, w, b_idx, co_idx, tol, P=0, exact=False):
+    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx, P)
+    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
+    assert got.shape == want.shape
+    if exact:
+        assert np.array_equal(got.astype(np.float64), want)
+    e = rel_err(got, want)
+    assert e <= tol, "planes: rel err %.3e" % e
+
+
+def check_channel_projection(out, x, w, tol, P=0, seed=0, count=2):
+    """Every element of `out` against the oracle at the price of a one-channel layer: the
+    operation is linear in the kernel, so sum_co r[co] * out[b][co] is the oracle's result for
+    the single kernel sum_co r[co] * w[co].  Random normal r: a wrong, missing or misplaced
+    value anywhere in the tensor changes the projection (two draws)."""
+    rng = np.random.default_rng(77 + seed)
+    x64, w64 = wl.to_f64(x), wl.to_f64(w)
+    host = out.cpu().numpy()
+    for _ in range(count):
+        r = rng.standard_normal(w64.shape[0])
+        want = oracle.forward(x64, np.einsum("o,oiuv->iuv", r, w64)[None], P)[:, 0]
+        got = np.stack([np.einsum("o,oyx->yx", r, host[b].astype(np.float64)) for b in range(host.shape[0])])
+        # the fp32 rounding of the summed channels adds up like the projection itself
+        scale = np.abs(want).max()
+        e = float(np.abs(got - want).max() / scale)
+        assert e <= tol, "channel projection: rel err %.3e" % e
 
 
 @pytest.mark.parametrize("idx", [0, 1])
@@ -418,9 +497,11 @@ def test_benchmark_layers_full_output(idx):
 
 
 @pytest.mark.parametrize("idx", [2, 3, 4])
-def test_benchmark_layers_sampled_planes(idx):
-    """Complete output planes (b, co), corners of the (b, co) grid plus random ones, each
-    computed by the oracle from the definition; the GPU computes the whole tensor."""
+def test_benchmark_layers_full_size(idx):
+    """The many-channel benchmark layers at full size, in the launch configuration the bench
+    times.  The whole output is held to the oracle twice: complete output planes for every batch
+    item and every block of 32 output channels (computed from the definition), and every element
+    through random projections over the output channels."""
     layer = wl.LAYERS[idx]
     x, w = wl.make_tensors(layer)
     xd, wd = x.to(DEV), w.to(DEV)
@@ -430,12 +511,9 @@ def test_benchmark_layers_sampled_planes(idx):
     torch.cuda.synchronize()
     assert torch.equal(out_seg, out_fwd)
     assert torch.isfinite(out_seg).all()
-    b_idx, co_idx = sample_planes(layer, 64, idx)
-    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx)
-    got = out_seg[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
-    assert got.shape == want.shape
-    e = rel_err(got, want)
-    assert e <= TOL[layer.dtype], "%s: rel err %.3e" % (layer.name, e)
+    b_idx, co_idx = covering_planes(layer.B, layer.Cout)
+    check_planes(out_seg, x, w, b_idx, co_idx, TOL[layer.dtype])
+    check_channel_projection(out_seg, x, w, TOL[layer.dtype], seed=idx)
 
 
 def test_zero_insert_reference_on_a_benchmark_layer():
@@ -510,24 +588,18 @@ def test_padded_forward_is_exact_on_integers_and_stays_inside_out():
     (4, 64, 128, 60, 3, 4, "bf16"),      # framed to 64 x 64: takes the LDS-ring kernel
     (16, 3, 1, 224, 5, 2, "f32"),        # Table 1's shape: 224 x 224 x 3 -> 447 x 447 x 1
     (8, 3, 1, 224, 4, 3, "f32"),         # the same with an odd padding factor
+    (16, 3, 1, 224, 3, 2, "f32"),        # Table 1's 3 x 3 kernel: 449 x 449 x 1
 ])
-def test_padded_forward_full_size_sampled_planes(B, Cin, Cout, N, n, P, dtype):
+def test_padded_forward_full_size(B, Cin, Cout, N, n, P, dtype):
     layer = wl.Layer("padded_full", B, Cin, Cout, N, n, dtype, "relu_normal")
     x, w = wl.make_tensors(layer, 4242 + N + P)
     xd, wd = x.to(DEV), w.to(DEV)
     out = kst.kst_forward_padded(xd, wd, P)
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
-    rng = np.random.default_rng(N * 10 + P)
-    pairs = set()
-    while len(pairs) < min(32, B * Cout):
-        pairs.add((int(rng.integers(B)), int(rng.integers(Cout))))
-    b_idx, co_idx = [p[0] for p in sorted(pairs)], [p[1] for p in sorted(pairs)]
-    want = oracle.forward_planes(wl.to_f64(x), wl.to_f64(w), b_idx, co_idx, P)
-    got = out[torch.tensor(b_idx), torch.tensor(co_idx)].cpu().numpy()
-    assert got.shape == want.shape
-    e = rel_err(got, want)
-    assert e <= TOL[dtype], "rel err %.3e" % e
+    b_idx, co_idx = covering_planes(B, Cout)
+    check_planes(out, x, w, b_idx, co_idx, TOL[dtype], P=P)
+    check_channel_projection(out, x, w, TOL[dtype], P=P, seed=N + P)
 
 
 # ----------------------------------------------------------------------------

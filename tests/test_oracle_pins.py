@@ -365,15 +365,36 @@ def test_table4_conventional_counts():
     assert oracle.conventional_ops(64, 64, 128, 4, 2) == (4_294_967_296, 4_290_772_992)
 
 
-def test_forward_planes_equals_forward():
-    rng = np.random.default_rng(9)
+@pytest.mark.parametrize("P", [0, 1, 2, 3])
+def test_forward_planes_equals_forward(P):
+    """The plane-wise entry is the checker of the full-size GPU tests, with and without a
+    padding factor: it must reproduce the pinned full forward bit for bit, plane by plane."""
+    rng = np.random.default_rng(9 + P)
     x, w = rand_case(rng, 3, 2, 4, 6, 5)
-    full = oracle.forward(x, w)
-    b = [2, 0, 1, 2]
-    co = [3, 0, 2, 1]
-    pl = oracle.forward_planes(x, w, b, co)
-    for k in range(4):
+    full = oracle.forward(x, w, P)
+    b = [2, 0, 1, 2, 1]
+    co = [3, 0, 2, 1, 2]
+    pl = oracle.forward_planes(x, w, b, co, P)
+    assert pl.shape == (5,) + full.shape[2:]
+    for k in range(5):
         assert np.array_equal(pl[k], full[b[k], co[k]])
+
+
+@pytest.mark.parametrize("N,n,P", [(4, 5, 2), (4, 5, 3), (7, 4, 1), (5, 3, 3)])
+def test_forward_planes_with_padding_factor_matches_library_conv(N, n, P):
+    """Independent of `forward`: fp64 library correlation on an explicitly zero-embedded map
+    with a zero frame of P (Section 3.3, Figs. 5-7)."""
+    rng = np.random.default_rng(90 + N + n + P)
+    x, w = rand_case(rng, 2, 3, 3, N, n)
+    S = 2 * N - 1
+    U = torch.zeros(2, 3, S, S, dtype=torch.float64)
+    U[:, :, ::2, ::2] = torch.from_numpy(x)
+    want = torch.nn.functional.conv2d(U, torch.from_numpy(w), padding=P).numpy()
+    b = [1, 0, 1]
+    co = [2, 1, 0]
+    pl = oracle.forward_planes(x, w, b, co, P)
+    for k in range(3):
+        assert np.abs(pl[k] - want[b[k], co[k]]).max() <= 1e-12 * np.abs(want).max()
 
 
 def test_rejects_illegal_shapes():
