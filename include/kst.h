@@ -130,12 +130,30 @@ size_t kst_workspace_bytes(int B, int Cin, int Cout, int N, int n, kst_dtype dty
  *   out[b][co][2i+r][2j+s] = sum_ci sum_a sum_b' in[b][ci][i+r+a][j+s+b'] * W_p(co,ci,a,b')
  * for every (i, j, r, s) with 2i+r < M and 2j+s < M; the extra row and column
  * the quad sweep would produce for odd M are never written.  ws/ws_bytes:
- * scratch of at least kst_workspace_bytes(...) bytes, 256-byte aligned (may
+ * scratch of at least kst_workspace_bytes(...) bytes, 16-byte aligned (may
  * be NULL/0 when that is 0).  Its contents are undefined afterwards.
  */
 kst_status kst_forward_seg(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
                            int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path,
                            hipStream_t stream);
+
+/*
+ * For callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc.
+ * kst_forward_seg with the same kernels, results and statuses, its workspace taken from an
+ * array of KST_STATIC_SCRATCH_BYTES that is part of the library's device code (each GPU the
+ * library runs on holds one until the process ends) instead of from the caller.  It calls no
+ * hipMalloc, hipFree or other allocating routine; the first call on a device looks the array's
+ * address up (hipGetSymbolAddress), later calls only launch.  A layer whose path needs more
+ * workspace than the array holds gets KST_ERR_WORKSPACE and nothing is launched
+ * (kst_workspace_bytes tells beforehand).  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (different streams, different threads) race on it; calls on
+ * one stream are ordered and safe.  The array's contents are undefined between calls.
+ */
+#define KST_STATIC_SCRATCH_BYTES (64u << 20)
+kst_status kst_forward_seg_static(const void *in, const void *w_seg, void *out,
+                                  int B, int Cin, int Cout, int N, int n, kst_dtype dtype, kst_path path,
+                                  hipStream_t stream);
 
 /*
  * Whole path from un-segregated weights: segregates w into scratch, then runs

@@ -15,6 +15,7 @@ import torch
 KST_F32, KST_BF16, KST_F16 = 0, 1, 2
 KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN = 0, 1, 2, 3
 KST_OK = 0
+KST_STATIC_SCRATCH_BYTES = 64 << 20
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libkst.so")
@@ -34,6 +35,7 @@ SIGNATURES = {
     "kst_workspace_bytes": (_c_size_t, [_c_int] * 7),
     "kst_forward_seg": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 7 + [_c_void_p]),
     "kst_forward": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 6 + [_c_void_p]),
+    "kst_forward_seg_static": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 7 + [_c_void_p]),
     "kst_forward_zero_insert": (_c_int, [_c_void_p] * 4 + [_c_int] * 6 + [_c_void_p]),
     "kst_out_size_padded": (_c_int, [_c_int] * 3),
     "kst_workspace_bytes_padded": (_c_size_t, [_c_int] * 8),
@@ -173,6 +175,21 @@ def kst_forward_seg(x: torch.Tensor, w_seg: torch.Tensor, Cout: int, n: int, out
                                B, Cin, Cout, N, n, dt, path, _stream())
     if st != KST_OK:
         raise KstError(st, "kst_forward_seg")
+    return out
+
+
+def kst_forward_seg_static(x: torch.Tensor, w_seg: torch.Tensor, Cout: int, n: int, out: torch.Tensor,
+                           path: int = KST_PATH_AUTO) -> torch.Tensor:
+    """kst_forward_seg with the library's own fixed workspace; `out` is the caller's (nothing is allocated)."""
+    B, Cin, Cout, N, n = _dims(x, n, Cout)
+    if w_seg.dtype != x.dtype:
+        raise TypeError("x and w_seg must share a dtype")
+    if out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    st = lib().kst_forward_seg_static(_dev(x, "x"), _dev(w_seg, "w_seg"), _dev(out, "out"), B, Cin, Cout, N, n,
+                                      _dtype_code(x), path, _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_forward_seg_static")
     return out
 
 

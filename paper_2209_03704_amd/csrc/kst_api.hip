@@ -1,6 +1,8 @@
 // C ABI of libkst.so: argument validation, path choice, launches.
 #include "kst_internal.h"
 
+#include <mutex>
+
 using namespace kst;
 
 namespace {
@@ -167,6 +169,67 @@ kst_status kst_forward_seg(const void *in, const void *w_seg, void *out, void *w
     kst_status st = check_shape(B, Cin, Cout, N, n);
     if (st != KST_OK) return st;
     return run_forward_seg(in, w_seg, out, ws, ws_bytes, make_shape(B, Cin, Cout, N, n), dtype, path, stream);
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------------
+}  // extern "C"
+
+// Workspace of kst_forward_seg_static: one array per GPU, part of the loaded code object, held
+// until the process ends.  In host code `scratch` is only a handle for hipGetSymbolAddress; the
+// kernels get the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[KST_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, looked up once
+
+// The current device's copy of `scratch`, or nullptr (with *st set) when it cannot be had.
+void *static_scratch(kst_status *st)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *st = KST_ERR_HIP;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            *st = KST_ERR_HIP;
+            return nullptr;
+        }
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" {
+
+kst_status kst_forward_seg_static(const void *in, const void *w_seg, void *out, int B, int Cin, int Cout, int N, int n,
+                                  kst_dtype dtype, kst_path path, hipStream_t stream)
+{
+    if (!in || !w_seg || !out) return KST_ERR_NULL;
+    if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    kst_status st = check_shape(B, Cin, Cout, N, n);
+    if (st != KST_OK) return st;
+    const Shape s = make_shape(B, Cin, Cout, N, n);
+    kst_path chosen;
+    st = resolve_path(s, dtype, path, &chosen);
+    if (st != KST_OK) return st;
+    const size_t need = workspace_for(s, dtype, chosen);
+    if (need > (size_t)KST_STATIC_SCRATCH_BYTES) return KST_ERR_WORKSPACE;     // larger than the array: refuse
+    void *ws = nullptr;
+    if (need) {
+        ws = static_scratch(&st);
+        if (!ws) return st;
+    }
+    // The kernels write every workspace word before they read it: nothing has to be cleared
+    // between calls, whatever the previous call left there.
+    return run_forward_seg(in, w_seg, out, ws, need, s, dtype, chosen, stream);
 }
 
 kst_status kst_forward(const void *in, const void *w, void *out, int B, int Cin, int Cout, int N, int n,
