@@ -281,7 +281,8 @@ def main():
             zi_ms = time_launches(
                 torch, lambda i: kst.kst_forward_zero_insert(r.x[0], r.w, U=U, out=r.out[0]), 2, 1)
             unseg_ms = time_launches(torch, lambda i: kst.kst_forward(r.x[i % r.sets], r.w, out=r.out[i % r.sets]),
-                                     min(iters, 10), 2)
+                                     iters, 5)
+            parts_ms = time_launches(torch, whole_path(r), iters, 5)
             roof_l = roofline_for(layer, ms, metrics)
             roof_l["frac_of_measured_yardstick"] = of_measured(layer, roof_l)
             table.append({
@@ -292,7 +293,8 @@ def main():
                 "forward_us_median_of_50": round(med_ms * 1e3, 2),
                 "forward_us_min_of_50": round(min_ms * 1e3, 2),
                 "segregate_us": round(seg_ms * 1e3, 2),
-                "forward_unsegregated_w_us": round(unseg_ms * 1e3, 2),
+                "forward_unsegregated_w_us": round(unseg_ms * 1e3, 2),              # kst_forward
+                "segregate_then_forward_us": round(parts_ms * 1e3, 2),              # its two parts, caller's buffers
                 "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
                 "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
                 "hbm_frac": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),

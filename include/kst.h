@@ -159,9 +159,11 @@ kst_status kst_forward_seg_static(const void *in, const void *w_seg, void *out,
  * Whole path from un-segregated weights: segregates w into scratch, then runs
  * the segregated forward pass with path AUTO.  Same result as
  * kst_segregate_weights + kst_forward_seg.  The scratch (segregated weights
- * and workspace) is taken from and returned to the device's stream-ordered
- * memory pool on `stream` (hipMallocAsync / hipFreeAsync): no host
- * synchronisation, but not usable under stream capture.
+ * and workspace) is taken from and returned to a stream-ordered memory pool
+ * that the library keeps per device (hipMallocFromPoolAsync / hipFreeAsync on
+ * `stream`): no host synchronisation, but not usable under stream capture.
+ * The pool keeps freed blocks for the next call (at most the largest scratch
+ * any call has needed, up to about 0.2 GB) until the process ends.
  */
 kst_status kst_forward(const void *in, const void *w, void *out,
                        int B, int Cin, int Cout, int N, int n, kst_dtype dtype, hipStream_t stream);

@@ -30,16 +30,23 @@ FLAGS = [
 ]
 
 
-def _headers_mtime() -> float:
-    hdrs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h")) + [__file__]
-    return max(os.path.getmtime(h) for h in hdrs)
+def _up_to_date(src: str, obj: str) -> bool:
+    """True when obj is newer than src, this script and every project header the compiler read
+    for it last time (the .d file written beside the object)."""
+    dep = obj + ".d"
+    if not (os.path.exists(obj) and os.path.exists(dep)):
+        return False
+    t = os.path.getmtime(obj)
+    names = open(dep).read().replace("\\\n", " ").split()
+    deps = [n for n in names[1:] if n.endswith((".h", ".hip")) and not n.startswith("/opt/")] + [src, __file__]
+    return all(os.path.exists(d) and os.path.getmtime(d) < t for d in deps)
 
 
 def _compile(src: str, force: bool = True) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), _headers_mtime()):
+    if not force and _up_to_date(src, obj):
         return obj
-    r = subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, "-MD", "-MF", obj + ".d", "-c", src, "-o", obj], capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:
@@ -50,8 +57,8 @@ def _compile(src: str, force: bool = True) -> str:
 
 
 def build_library(jobs: int | None = None, force: bool = True) -> str:
-    """Compile and link.  force=False recompiles only sources newer than their objects (or older
-    than any header): for iterating; the default compiles everything."""
+    """Compile and link.  force=False recompiles only sources whose object is older than the source or one of
+    the headers it includes: for iterating; the default compiles everything."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     if not srcs:

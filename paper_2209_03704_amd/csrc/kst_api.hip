@@ -96,11 +96,50 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
     return e == hipSuccess ? KST_OK : KST_ERR_HIP;
 }
 
+// Scratch of the entry points that take un-segregated weights (kst_forward, kst_forward_padded):
+// a stream-ordered memory pool of the library's own per device, which keeps what is freed
+// (release threshold: never) so that call after call re-uses one block instead of mapping and
+// unmapping it every time -- with the runtime's default pool a 128 MiB workspace cost about
+// 100 us per call.  The pool holds at most the largest scratch any call has asked for.
+constexpr int kMaxPoolDevices = 64;
+std::mutex pool_mutex;
+hipMemPool_t pools[kMaxPoolDevices];
+bool pool_tried[kMaxPoolDevices];
+
+hipError_t scratch_alloc(void **ptr, size_t bytes, hipStream_t stream)
+{
+    int dev = -1;
+    hipMemPool_t pool = nullptr;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxPoolDevices) {
+        std::lock_guard<std::mutex> lock(pool_mutex);
+        if (!pool_tried[dev]) {
+            pool_tried[dev] = true;
+            hipMemPoolProps props = {};
+            props.allocType = hipMemAllocationTypePinned;
+            props.handleTypes = hipMemHandleTypeNone;
+            props.location.type = hipMemLocationTypeDevice;
+            props.location.id = dev;
+            hipMemPool_t made = nullptr;
+            if (hipMemPoolCreate(&made, &props) == hipSuccess) {
+                uint64_t keep = UINT64_MAX;
+                if (hipMemPoolSetAttribute(made, hipMemPoolAttrReleaseThreshold, &keep) == hipSuccess)
+                    pools[dev] = made;
+                else
+                    (void)hipMemPoolDestroy(made);
+            }
+            (void)hipGetLastError();       // a refused pool is no error of the call: the default pool serves
+        }
+        pool = pools[dev];
+    }
+    if (pool) return hipMallocFromPoolAsync(ptr, bytes, pool, stream);
+    return hipMallocAsync(ptr, bytes, stream);
+}
+
 }  // namespace
 
 extern "C" {
 
-int kst_version(void) { return 100; }
+int kst_version(void) { return 101; }
 
 const char *kst_status_string(int status)
 {
@@ -245,7 +284,7 @@ kst_status kst_forward(const void *in, const void *w, void *out, int B, int Cin,
     const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;
     const size_t ws_bytes = workspace_for(s, dtype, chosen);
     void *scratch = nullptr;
-    if (hipMallocAsync(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
+    if (scratch_alloc(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
     void *ws = ws_bytes ? (void *)((char *)scratch + seg_bytes) : nullptr;
     st = kst_segregate_weights(w, scratch, Cin, Cout, n, dtype, stream);
     if (st == KST_OK)
@@ -353,7 +392,7 @@ kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, i
     const size_t seg_bytes = (seg_elems(Cin, Cout, n, dtype) * elt_bytes(dtype) + 255) & ~(size_t)255;
     const size_t ws_bytes = f.in_bytes + f.wide_bytes + workspace_for(f.s, dtype, f.chosen);   // may be 0
     void *scratch = nullptr;
-    if (hipMallocAsync(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
+    if (scratch_alloc(&scratch, seg_bytes + ws_bytes, stream) != hipSuccess) return KST_ERR_HIP;
     st = kst_segregate_weights(w, scratch, Cin, Cout, n, dtype, stream);
     if (st == KST_OK)
         st = kst_forward_seg_padded(in, scratch, out, ws_bytes ? (char *)scratch + seg_bytes : nullptr, ws_bytes, B, Cin,
