@@ -66,12 +66,20 @@ typedef enum {
  * model says it pays.  It exists for KST_F32 layers with Cin, Cout and the
  * input row stride multiples of 4 whose tile fits the kernel; any other
  * layer gets KST_ERR_PATH.  Its workspace differs from IGEMM's: ask
- * kst_workspace_bytes with the same path. */
+ * kst_workspace_bytes with the same path.
+ * IGEMM_PASSES (for tests and measurement) forces a second 16-bit matrix-core
+ * kernel: a tile's even and odd output rows in two passes, one pass's rows
+ * leaving for memory while the other multiplies.  It exists for 3 x 3 kernels
+ * on 64 x 64 maps with 256 input channels, output channels a multiple of 64 and
+ * at least 224 tiles of 64 channels x 4 quad rows; any other layer gets
+ * KST_ERR_PATH.  AUTO and IGEMM never take it (it measures slower than the
+ * kernel they take).  No workspace. */
 typedef enum {
     KST_PATH_AUTO = 0,
     KST_PATH_DIRECT = 1,
     KST_PATH_IGEMM = 2,
-    KST_PATH_IGEMM_EVEN = 3
+    KST_PATH_IGEMM_EVEN = 3,
+    KST_PATH_IGEMM_PASSES = 4
 } kst_path;
 
 int kst_version(void);

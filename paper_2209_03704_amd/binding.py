@@ -13,7 +13,7 @@ import os
 import torch
 
 KST_F32, KST_BF16, KST_F16 = 0, 1, 2
-KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN = 0, 1, 2, 3
+KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN, KST_PATH_IGEMM_PASSES = 0, 1, 2, 3, 4
 KST_OK = 0
 KST_STATIC_SCRATCH_BYTES = 64 << 20
 

@@ -53,6 +53,11 @@ kst_status resolve_path(const Shape &s, kst_dtype dt, int path, kst_path *out)
         *out = KST_PATH_IGEMM;
         return KST_OK;
     }
+    if (path == KST_PATH_IGEMM_PASSES) {
+        if (!is16(dt) || !igemm_bf16_pp_supported(s)) return KST_ERR_PATH;
+        *out = KST_PATH_IGEMM_PASSES;
+        return KST_OK;
+    }
     if (path == KST_PATH_IGEMM_EVEN) {
         if (dt != KST_F32 || !igemm_f32_supported(s) || !igemm_f32_even_shares_possible(s)) return KST_ERR_PATH;
         *out = KST_PATH_IGEMM_EVEN;
@@ -61,11 +66,14 @@ kst_status resolve_path(const Shape &s, kst_dtype dt, int path, kst_path *out)
     return KST_ERR_PATH;
 }
 
-bool on_matrix_cores(kst_path path) { return path == KST_PATH_IGEMM || path == KST_PATH_IGEMM_EVEN; }
+bool on_matrix_cores(kst_path path)
+{
+    return path == KST_PATH_IGEMM || path == KST_PATH_IGEMM_EVEN || path == KST_PATH_IGEMM_PASSES;
+}
 
 size_t workspace_for(const Shape &s, kst_dtype dt, kst_path path)
 {
-    if (!on_matrix_cores(path)) return 0;
+    if (!on_matrix_cores(path) || path == KST_PATH_IGEMM_PASSES) return 0;
     return is16(dt) ? igemm_bf16_workspace_bytes(s) : igemm_f32_workspace_bytes(s, path == KST_PATH_IGEMM_EVEN);
 }
 
@@ -88,6 +96,8 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
     hipError_t e;
     if (chosen == KST_PATH_DIRECT)
         e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
+    else if (chosen == KST_PATH_IGEMM_PASSES)
+        e = launch_igemm_bf16_pp(in, w_seg, (float *)out, s, dtype == KST_F16, stream);
     else if (is16(dtype))
         e = launch_igemm_bf16(in, w_seg, (float *)out, ws, s, dtype == KST_F16, stream);
     else

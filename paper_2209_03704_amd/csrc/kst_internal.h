@@ -142,6 +142,9 @@ hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out,
 bool igemm_bf16_wide_supported(const Shape &s);    // persistent wide-tile variant (same shapes, at least ~one tile per CU)
 hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                   hipStream_t stream);
+bool igemm_bf16_pp_supported(const Shape &s);      // row-parity passes: 3 x 3 kernels, 64 x 64 maps, 256 input channels
+hipError_t launch_igemm_bf16_pp(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
+                                hipStream_t stream);
 // force_even: take the even-share launch whenever igemm_f32_even_shares_possible, whatever the cost model says.
 bool igemm_f32_even_shares_possible(const Shape &s);
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even = false);

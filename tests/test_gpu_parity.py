@@ -359,6 +359,46 @@ def test_igemm_bf16_wide_kernel_is_exact_on_integers_and_stays_inside_out():
     assert np.array_equal(host[guard:guard + numel].view(layer.out_shape).numpy().astype(np.float64), want)
 
 
+@pytest.mark.parametrize("B,Cout,dtype,dist", [
+    (7, 128, "bf16", "relu_normal"),     # 224 tiles: one per workgroup (first tile = last tile)
+    (9, 128, "bf16", "relu_normal"),     # 288 tiles: some workgroups walk over two
+    (5, 192, "f16", "relu_normal"),      # three channel tiles, half-precision multiply
+    (7, 128, "bf16", "integer"),         # exact: must equal the oracle bit for bit
+    (20, 64, "f16", "integer"),          # 320 tiles, one channel tile
+])
+def test_igemm_bf16_row_parity_passes_kernel(B, Cout, dtype, dist):
+    """The forced path IGEMM_PASSES: the kernel that works a tile's even and odd output rows in two
+    passes and drains one pass's rows while the other multiplies (3 x 3 kernels, 64 x 64 maps, 256
+    input channels; not taken by AUTO: it measures slower than the wide-tile kernel).  Every
+    batch item and every block of 32 channels is held to the oracle plane by plane, the whole tensor
+    through channel projections; guard words around `out` must survive."""
+    layer = wl.Layer("pp", B, 256, Cout, 64, 3, dtype, dist, w_std=0.1)
+    x, w = wl.make_tensors(layer, 40 + B + Cout)
+    xd, wd = x.to(DEV), w.to(DEV)
+    numel = int(np.prod(layer.out_shape))
+    guard = 4096
+    buf = torch.full((numel + 2 * guard,), float("nan"), device=DEV)
+    out = buf[guard:guard + numel].view(layer.out_shape)
+    kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, 3, out=out, path=kst.KST_PATH_IGEMM_PASSES)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + numel:]).all()
+    assert torch.isfinite(out).all()
+    again = torch.empty_like(out)
+    kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, 3, out=again, path=kst.KST_PATH_IGEMM_PASSES)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)                     # fixed order everywhere: bit-reproducible
+    b_idx, co_idx = covering_planes(B, Cout)
+    check_planes(out, x, w, b_idx, co_idx, TOL[dtype], exact=(dist == "integer"))
+    check_channel_projection(out, x, w, TOL[dtype], seed=B)
+    # the kernel AUTO takes for the same layer agrees with it (both hold fp32 sums of exact products)
+    auto = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, 3, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    assert rel_err(out.cpu().numpy(), auto.cpu().numpy().astype(np.float64)) <= TOL[dtype]
+    with pytest.raises(kst.KstError):                  # any other shape is refused
+        kst.kst_forward_seg(xd[:, :128].contiguous(), kst.kst_segregate_weights(wd[:, :128].contiguous()), Cout, 3,
+                            path=kst.KST_PATH_IGEMM_PASSES)
+
+
 @pytest.mark.parametrize("B,Cin,Cout,N,n", [
     (32, 64, 768, 16, 4),    # 294 tiles x 16 chunks over 256 workgroups: whole tiles and partial pieces per range
     (8, 256, 128, 16, 4),    # 13 tiles x 64 chunks: every tile shared by about 20 workgroups
