@@ -9,8 +9,9 @@ segregated forward pass with its edge masking, through the C ABI, inputs
 resident in HBM.  Prints ONE JSON line: whole-job useful GMAC/s, the roofline
 of the dominant kernel (measured live with events on the launch stream), the
 CPU oracle as a baseline, a per-layer table for the five benchmark layers (time, useful
-GMAC/s, roofline fraction, speed-up over the zero-insert path), and a table for the paper's
-own shapes with padding factor 2 (Tables 1 and 3).
+GMAC/s, roofline fraction, speed-up over the zero-insert path), a table for the paper's
+own shapes with padding factor 2 (Tables 1 and 3) at a batch that fills the chip, and Table 3's
+four generator families on one input sample with the seconds the paper prints beside them.
 """
 from __future__ import annotations
 
@@ -353,6 +354,45 @@ def main():
             del xd, outs, ws
             torch.cuda.empty_cache()
 
+    # ---- Table 3's generator layers on one input sample, as the paper times them ---------------
+    one_sample = []
+    if args.layers == "all":
+        for model in wl.TABLE3_GENERATORS:
+            rows, tot_seg, tot_whole, tot_paper = [], 0.0, 0.0, 0.0
+            for layer, paper_s in wl.table3_layers(model, 1):
+                x, w = wl.make_tensors(layer)
+                xd, wd = x.cuda(), w.cuda()
+                out = torch.empty(layer.out_shape, dtype=torch.float32, device="cuda")
+                w_seg = kst.kst_segregate_weights(wd)
+                need = kst.kst_workspace_bytes_padded(1, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, kst.KST_F32)
+                ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+                f_seg = lambda i: kst.kst_forward_seg_padded(xd, w_seg, layer.Cout, layer.n, layer.P, out=out, ws=ws)
+                f_all = lambda i: kst.kst_forward_padded(xd, wd, layer.P, out=out)
+                settle(torch, f_seg, 0.02)
+                seg_ms = time_launches(torch, f_seg, 30, 5)
+                whole_ms = time_launches(torch, f_all, 30, 5)
+                # a sample reads every weight once: weights + maps are the bytes that must move
+                bytes_min = 4 * (layer.Cin * layer.Cout * 16 + layer.Cin * layer.N ** 2 + layer.Cout * layer.M ** 2)
+                rows.append({
+                    "layer": layer.name,
+                    "shape": {"Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "M": layer.M},
+                    "forward_seg_us": round(seg_ms * 1e3, 2),
+                    "forward_unsegregated_w_us": round(whole_ms * 1e3, 2),
+                    "hbm_frac": round(bytes_min / (seg_ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),
+                    "paper_rtx2070_proposed_us": round(paper_s[1] * 1e6, 1),
+                    "paper_rtx2070_conventional_us": round(paper_s[0] * 1e6, 1),
+                    "paper_xeon_proposed_us": round(paper_s[3] * 1e6, 1),
+                })
+                tot_seg += seg_ms
+                tot_whole += whole_ms
+                tot_paper += paper_s[1]
+                del xd, wd, out, w_seg, ws
+            torch.cuda.empty_cache()
+            one_sample.append({"model": model, "layers": rows,
+                               "total_forward_seg_us": round(tot_seg * 1e3, 1),
+                               "total_forward_unsegregated_w_us": round(tot_whole * 1e3, 1),
+                               "paper_rtx2070_proposed_total_us": round(tot_paper * 1e6, 1)})
+
     line = {
         "metric": "useful GMAC/s (segregated transpose convolution, whole path)",
         "value": round(value, 1),
@@ -374,6 +414,7 @@ def main():
         "yardsticks": yard,
         "layers": table,
         "paper_shaped_layers": paper_table,
+        "table3_one_sample": one_sample,
         "paper_context": "paper reports 3.7x (Xeon CPU) / 3.4x (RTX 2070) average speed-up over zero-insert; ideal 4x",
     }
     print(json.dumps(line))

@@ -81,7 +81,10 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
         const double out_b = (double)s.B * s.Cout * s.M * s.M * 4.0;
         double best = (double)((tiles + 255) / 256) * tile_s;
         const double unsplit = best;
-        for (int c = 2; c <= 16 && c <= chunks; ++c) {
+        // A layer with very few tiles (one sample of a small map) may split further, up to one
+        // workgroup per CU: its reduction is a stream of weights that only many CUs can pull.
+        const int c_max = tiles * 16 < 256 ? 256 / tiles : 16;
+        for (int c = 2; c <= c_max && c <= chunks; ++c) {
             const double t = (double)(((size_t)tiles * c + 255) / 256) * tile_s / c + (c + 1) * out_b / 4.0e12;
             if (t < best && t < 0.9 * unsplit) { best = t; splits = c; }
         }

@@ -614,7 +614,13 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
     // their traffic (measured on 64 x 1024 x 512 x 8 x 8, n = 5: 483 us against 514 us for seven splits).
     const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / 2.0e11;
     const double longest = (double)(r.k.whole / r.k.grid) * r.k.chunks + (double)((r.k.units + r.k.grid - 1) / r.k.grid);
-    const double t = longest * tile_s / r.k.chunks + (double)partial * SK_SLOT_FLOATS * 4.0 * 2.0 / 8.0e12 + 5.0e-6;
+    // The summing pass walks a tile's contributors one after the other (about 2.5 us each, measured
+    // on one-sample layers with 64 and 128 contributors per tile); up to four hide in its launch.
+    const unsigned long long shared_tiles = tiles - (unsigned)r.k.whole;
+    const double per_tile = shared_tiles ? (double)partial / (double)shared_tiles : 0.0;
+    const double serial_sum = per_tile > 4.0 ? (per_tile - 4.0) * 2.5e-6 : 0.0;
+    const double t = longest * tile_s / r.k.chunks + (double)partial * SK_SLOT_FLOATS * 4.0 * 2.0 / 8.0e12 + 5.0e-6 +
+                     serial_sum;
     r.use = t < 0.99 * p.est_s;
     return r;
 }

@@ -72,6 +72,52 @@ PAPER_LAYERS = (
 )
 
 
+# Table 3's transpose-convolution layers of four generator families, one input sample each
+# (the paper times the forward pass of a single sample): 4 x 4 kernels, padding factor 2, so every
+# layer doubles its map (N -> 2N).  Entries: (layer number, N, Cin, Cout).  The second tuple holds
+# the seconds Table 3 prints for that layer, as context beside this library's figures and never as
+# a target: (conventional on the GPU, proposed on the GPU, conventional on the CPU, proposed on the
+# CPU), measured by the authors on an RTX 2070 and a Xeon.
+TABLE3_GENERATORS = {
+    "dcgan_discogan": (
+        ((2, 4, 1024, 512), (0.046753, 0.011541, 3.023, 0.727)),
+        ((3, 8, 512, 256), (0.046085, 0.011381, 3.101, 0.6863)),
+        ((4, 16, 256, 128), (0.043747, 0.011296, 2.90, 0.6598)),
+        ((5, 32, 128, 3), (0.003049, 0.001551, 0.1363, 0.0371)),
+    ),
+    "art_gan": (
+        ((2, 4, 512, 256), (0.011886, 0.005768, 0.7114, 0.1782)),
+        ((3, 8, 256, 128), (0.011726, 0.002971, 0.7219, 0.1652)),
+        ((4, 16, 128, 128), (0.021727, 0.00568, 1.3879, 0.316)),
+        ((6, 32, 128, 3), (0.001582, 0.001532, 0.0359, 0.0075)),
+    ),
+    "gp_gan": (
+        ((2, 4, 512, 256), (0.011847, 0.005787, 0.7114, 0.1782)),
+        ((3, 8, 256, 128), (0.01171, 0.002952, 0.7219, 0.1652)),
+        ((4, 16, 128, 64), (0.01167, 0.002895, 0.6995, 0.1611)),
+        ((5, 32, 64, 3), (0.001574, 0.000852, 0.0659, 0.016)),
+    ),
+    "eb_gan": (
+        ((2, 4, 2048, 1024), (0.188821, 0.046078, 16.0994, 3.598)),
+        ((3, 8, 1024, 512), (0.176702, 0.045508, 14.193, 2.919)),
+        ((4, 16, 512, 256), (0.172839, 0.045071, 16.587, 2.950)),
+        ((5, 32, 256, 128), (0.172694, 0.042322, 12.197, 2.866)),
+        ((6, 64, 128, 64), (0.175486, 0.041105, 11.745, 2.774)),
+        ((7, 128, 64, 64), (0.349605, 0.082192, 22.398, 5.233)),
+    ),
+}
+
+
+def table3_layers(model: str, B: int = 1):
+    """Table 3's layers of one generator family as Layer records at batch B, with the seconds the
+    table prints for each: a list of (Layer, (conv_gpu_s, prop_gpu_s, conv_cpu_s, prop_cpu_s))."""
+    out = []
+    for (num, N, Cin, Cout), paper_s in TABLE3_GENERATORS[model]:
+        name = "table3_%s_l%d_%dto%d_b%d" % (model, num, N, 2 * N, B)
+        out.append((Layer(name, B, Cin, Cout, N, 4, "f32", "relu_normal", P=2), paper_s))
+    return out
+
+
 def layer_by_name(name: str) -> Layer:
     for i, l in enumerate(LAYERS):
         if l.name == name or name in ("cfg%d" % (i + 1), str(i + 1)):

@@ -642,6 +642,30 @@ def test_padded_forward_full_size(B, Cin, Cout, N, n, P, dtype):
     check_channel_projection(out, x, w, TOL[dtype], P=P, seed=N + P)
 
 
+TABLE3_CASES = [(m, i) for m in wl.TABLE3_GENERATORS for i in range(len(wl.TABLE3_GENERATORS[m]))]
+
+
+@pytest.mark.parametrize("model,index", TABLE3_CASES, ids=["%s-%d" % c for c in TABLE3_CASES])
+def test_table3_generator_layers_one_sample(model, index):
+    """Every transpose-convolution layer Table 3 lists (four generator families), on one input
+    sample as the paper times them, through the entry point that takes unsegregated weights."""
+    layer, _ = wl.table3_layers(model, 1)[index]
+    x, w = wl.make_tensors(layer, 9000 + 31 * index + len(model))
+    out = kst.kst_forward_padded(x.to(DEV), w.to(DEV), layer.P)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == layer.out_shape and layer.M == 2 * layer.N
+    assert torch.isfinite(out).all()
+    if layer.Cin * layer.Cout * layer.M * layer.M * 16 <= 600_000_000:
+        want = oracle.forward(wl.to_f64(x), wl.to_f64(w), layer.P)
+        e = rel_err(out.cpu().numpy(), want)
+        assert e <= TOL["f32"], "%s: rel err %.3e" % (layer.name, e)
+    else:
+        # one plane of every block of 8 output channels, and two projections over all of them
+        b_idx, co_idx = covering_planes(1, layer.Cout, group=8)
+        check_planes(out, x, w, b_idx, co_idx, TOL["f32"], P=layer.P)
+        check_channel_projection(out, x, w, TOL["f32"], P=layer.P, seed=index)
+
+
 # ----------------------------------------------------------------------------
 # Gradients (end of Section 3.3)
 # ----------------------------------------------------------------------------

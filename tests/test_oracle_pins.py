@@ -365,6 +365,40 @@ def test_table4_conventional_counts():
     assert oracle.conventional_ops(64, 64, 128, 4, 2) == (4_294_967_296, 4_290_772_992)
 
 
+# Table 4, columns "multiplications (original)" and "additions (original)", row by row for the four
+# generator families of Table 3 (one input sample).
+TABLE4_ORIGINAL = {
+    "dcgan_discogan": [(536_870_912, 536_838_144), (536_870_912, 536_805_376),
+                       (536_870_912, 536_739_840), (25_165_824, 25_153_536)],
+    "art_gan": [(134_217_728, 134_201_344), (134_217_728, 134_184_960),
+                (268_435_456, 268_304_384), (25_165_824, 25_153_536)],
+    "gp_gan": [(134_217_728, 134_201_344), (134_217_728, 134_184_960),
+               (134_217_728, 134_152_192), (12_582_912, 12_570_624)],
+    "eb_gan": [(2_147_483_648, 2_147_418_112), (2_147_483_648, 2_147_352_576),
+               (2_147_483_648, 2_147_221_504), (2_147_483_648, 2_146_959_360),
+               (2_147_483_648, 2_146_435_072), (4_294_967_296, 4_290_772_992)],
+}
+TABLE4_ORIGINAL_TOTAL_MULTS = {"dcgan_discogan": 1_635_778_560, "art_gan": 562_036_736,
+                               "gp_gan": 415_236_096, "eb_gan": 15_032_385_536}
+
+
+@pytest.mark.parametrize("model", sorted(TABLE4_ORIGINAL))
+def test_table3_layer_lists_reproduce_table4(model):
+    """The layer lists the workloads module holds for Table 3 are the shapes Table 4 counts: the
+    oracle's operation counts on them equal the table's "original" columns, row by row, and the
+    multiplications sum to the table's total."""
+    from paper_2209_03704_amd import workloads as wl
+    layers = wl.table3_layers(model, 1)
+    assert len(layers) == len(TABLE4_ORIGINAL[model])
+    total = 0
+    for (layer, _), want in zip(layers, TABLE4_ORIGINAL[model]):
+        assert (layer.B, layer.n, layer.P, layer.M) == (1, 4, 2, 2 * layer.N)
+        got = oracle.conventional_ops(layer.Cin, layer.Cout, layer.N, layer.n, layer.P)
+        assert got == want, layer.name
+        total += got[0]
+    assert total == TABLE4_ORIGINAL_TOTAL_MULTS[model]
+
+
 @pytest.mark.parametrize("P", [0, 1, 2, 3])
 def test_forward_planes_equals_forward(P):
     """The plane-wise entry is the checker of the full-size GPU tests, with and without a

@@ -32,10 +32,10 @@ def run_both(layer, seed, path):
 
 
 def test_static_workspace_entry_point_two_calls_in_a_row():
-    # 1: one tile x 128 channel chunks in even shares over 128 workgroups: the whole 64 MiB array
+    # 1: one tile x 128 channel chunks in even shares over 128 workgroups (forced): the whole 64 MiB array
     # 2: a smaller layer whose reduction is split over workgroups (partial sums + summing pass)
     # 3: 16-bit operands, split reduction; 4: a direct-path layer that needs no workspace at all
-    cases = [(wl.Layer("static_1", 2, 512, 128, 8, 4, "f32", "relu_normal", w_std=0.1), kst.KST_PATH_AUTO),
+    cases = [(wl.Layer("static_1", 2, 512, 128, 8, 4, "f32", "relu_normal", w_std=0.1), kst.KST_PATH_IGEMM_EVEN),
              (wl.Layer("static_2", 3, 100, 132, 12, 5, "f32", "relu_normal", w_std=0.1), kst.KST_PATH_AUTO),
              (wl.Layer("static_3", 9, 130, 16, 6, 4, "bf16", "relu_normal", w_std=0.1), kst.KST_PATH_IGEMM),
              (wl.Layer("static_4", 2, 3, 2, 33, 3, "f32", "normal", w_std=0.2), kst.KST_PATH_AUTO)]
@@ -53,12 +53,13 @@ def test_static_workspace_entry_point_two_calls_in_a_row():
 
 def test_static_workspace_entry_point_refuses_what_does_not_fit():
     layer = wl.Layer("static_big", 4, 1024, 512, 4, 4, "f32", "relu_normal")
-    assert kst.kst_workspace_bytes(4, 1024, 512, 4, 4, kst.KST_F32, kst.KST_PATH_AUTO) > kst.KST_STATIC_SCRATCH_BYTES
+    path = kst.KST_PATH_IGEMM_EVEN                   # even shares of this layer want 128 MiB of slots
+    assert kst.kst_workspace_bytes(4, 1024, 512, 4, 4, kst.KST_F32, path) > kst.KST_STATIC_SCRATCH_BYTES
     x, w = wl.make_tensors(layer, 1)
     xd, wd = x.to(DEV), w.to(DEV)
     out = torch.full(layer.out_shape, float("nan"), dtype=torch.float32, device=DEV)
     with pytest.raises(kst.KstError) as e:
-        kst.kst_forward_seg_static(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, out)
+        kst.kst_forward_seg_static(xd, kst.kst_segregate_weights(wd), layer.Cout, layer.n, out, path=path)
     assert e.value.status == 4                       # KST_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.isnan(out).all()                    # nothing was launched
