@@ -132,10 +132,18 @@ def paper_roofline(layer, fwd_ms, din_ms, dw_ms, metrics):
     the other operand and write the gradient: the same byte count)."""
     macs = metrics.useful_macs(layer)
     many = layer.Cin >= 8 and layer.Cout >= 16
-    out = {"bound": "mfma" if many else "hbm"}
+    # Few output channels fed by many input channels (the 128 -> 3 output layer of the generators):
+    # 2 * useful MACs / algorithmic bytes = 22 flop/B, past the ridge of the vector ALUs
+    # (157.3 TFLOP/s / 8 TB/s = 19.7 flop/B), and too narrow for the matrix cores (3 of 32 columns):
+    # priced against the fp32 vector peak, the HBM fraction beside it.
+    alu = not many and 2.0 * macs / metrics.algorithmic_bytes(layer) > metrics.VALU_PEAK_TFLOPS * 1e12 / (metrics.HBM_PEAK_GBS * 1e9)
+    out = {"bound": "mfma" if many else "alu" if alu else "hbm"}
     for name, ms in (("forward", fwd_ms), ("backward_input", din_ms), ("backward_weight", dw_ms)):
         if many:
             out[name + "_frac"] = round(2.0 * macs / (ms * 1e-3) / 1e12 / metrics.MFMA_PEAK_TFLOPS["f32"], 4)
+        elif alu:
+            out[name + "_frac"] = round(2.0 * macs / (ms * 1e-3) / 1e12 / metrics.VALU_PEAK_TFLOPS, 4)
+            out[name + "_hbm_frac"] = round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4)
         else:
             out[name + "_frac"] = round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4)
     return out

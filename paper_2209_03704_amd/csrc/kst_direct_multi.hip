@@ -11,6 +11,13 @@
 // LDS as whole 16-byte groups (scalar loads were tried first: the n*n*CO values of a channel do not
 // fit the scalar registers together with the next channel's, and with one or two waves per SIMD
 // every channel then waited for several scalar-load round trips).
+//
+// Layers with many input channels and few tiles (the 128 -> 3 and 64 -> 3 output layers of the
+// generators: one tile per CU at a batch of 64, four tiles in all for one sample) are bound by the
+// latency of one chunk's loads per workgroup.  For them a workgroup is KS groups of M_THREADS
+// lanes on the same tile: group g takes chunks g, g + KS, ... with staging buffers of its own, so
+// that KS chunks are in flight per workgroup, and the groups' accumulators are added through LDS
+// in group order at the end (a fixed order: results do not depend on timing).
 #include "kst_internal.h"
 
 namespace kst {
@@ -36,10 +43,11 @@ __device__ __forceinline__ size_t wseg_at(size_t off_p, int Tp, int Cout, int ci
         return off_p + ((size_t)ci * Tp + t) * Cout + co;
 }
 
-// M_KC: input channels per chunk (8, or 4 for layers with at most 4 input channels).
-template <int n, int CO, int M_KC, typename T>
-__global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
-                                                                  float *__restrict__ out, MultiParams p)
+// M_KC: input channels per chunk (8, or 4 for layers with at most 4 input channels); KS: groups of
+// lanes that share the reduction of a tile.
+template <int n, int CO, int M_KC, int KS, typename T>
+__global__ void __launch_bounds__(M_THREADS * KS) direct_multi_kernel(const T *__restrict__ in, const T *__restrict__ w_seg,
+                                                                       float *__restrict__ out, MultiParams p)
 {
     constexpr int fl = n / 2;
     constexpr int XH = M_TI + fl, XW = M_TJ + fl;              // staged rows and columns per channel
@@ -51,8 +59,13 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
     constexpr int WPC = (NN * CO + 3) & ~3;                    // staged weights per channel: [tap][k], padded
     constexpr int WCHUNK = M_KC * WPC;
     constexpr int NWL = (WCHUNK + M_THREADS - 1) / M_THREADS;  // ... per lane
-    __shared__ float Xs[2][CHUNK];
-    __shared__ __attribute__((aligned(16))) float Wsh[2][WCHUNK];
+    static_assert(CHUNK % 4 == 0 && WCHUNK % 4 == 0, "stages keep 16-byte alignment");
+    constexpr int GROUP_FLOATS = 2 * (CHUNK + WCHUNK);         // one group's two stages
+    static_assert(KS == 1 || 4 * CO * M_THREADS <= GROUP_FLOATS, "a group's accumulators fit its stages");
+    extern __shared__ __attribute__((aligned(16))) float multi_lds[];
+    const int grp = KS == 1 ? 0 : (int)threadIdx.x / M_THREADS;       // uniform over a wave
+    float(*Xs)[CHUNK] = reinterpret_cast<float(*)[CHUNK]>(multi_lds + grp * GROUP_FLOATS);
+    float(*Wsh)[WCHUNK] = reinterpret_cast<float(*)[WCHUNK]>(multi_lds + grp * GROUP_FLOATS + 2 * CHUNK);
 
     unsigned id = blockIdx.x;
     const int co_groups = p.Cout / CO;              // CO divides Cout
@@ -63,7 +76,7 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
     const int ty = (int)(id % (unsigned)p.tiles_y);
     const int b = (int)(id / (unsigned)p.tiles_y);
 
-    const int tid = threadIdx.x;
+    const int tid = KS == 1 ? (int)threadIdx.x : (int)threadIdx.x - grp * M_THREADS;   // lane within its group
     const int ti = tid / M_TJ, tj = tid - ti * M_TJ;
     const int i0 = ty * M_TI, j0 = tx * M_TJ;
     const int i = i0 + ti, j = j0 + tj;
@@ -82,10 +95,10 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
         const int row = rem / XW, col = rem - row * XW;
         const int y = i0 + row - p.q, xx = j0 + col - p.q;     // in the tensor as it lies in memory
         const bool ok = e < CHUNK && y >= 0 && y < p.N0 && xx >= 0 && xx < p.N0;
-        ld_off[k] = ok ? (((unsigned)b * p.Cin + c) * p.N0 + y) * p.N0 + xx : ~0u;
+        ld_off[k] = ok ? (((unsigned)b * p.Cin + grp * M_KC + c) * p.N0 + y) * p.N0 + xx : ~0u;
         ld_c[k] = c;
     }
-    const unsigned ld_inc = (unsigned)M_KC * p.N0 * p.N0;
+    const unsigned ld_inc = (unsigned)(M_KC * KS) * p.N0 * p.N0;
 
     // Weights: element e of a chunk is (channel c, tap t in class-major order, output channel k).
     unsigned w_off[NWL], w_inc[NWL];
@@ -103,8 +116,8 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
             if (t >= class_tap_base(n, q) && class_taps(n, q) > 0) cls = q;
         const int Tp = cls == 0 ? class_taps(n, 0) : cls == 1 ? class_taps(n, 1) : cls == 2 ? class_taps(n, 2) : class_taps(n, 3);
         const int tb = cls == 0 ? 0 : cls == 1 ? class_tap_base(n, 1) : cls == 2 ? class_tap_base(n, 2) : class_tap_base(n, 3);
-        w_off[k] = ok ? (unsigned)wseg_at<T>(p.off[cls], Tp, p.Cout, c, t - tb, co0 + kk) : ~0u;
-        w_inc[k] = (unsigned)M_KC * Tp * p.Cout;
+        w_off[k] = ok ? (unsigned)wseg_at<T>(p.off[cls], Tp, p.Cout, grp * M_KC + c, t - tb, co0 + kk) : ~0u;
+        w_inc[k] = (unsigned)(M_KC * KS) * Tp * p.Cout;
         w_c[k] = c;
     }
 
@@ -145,13 +158,17 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
         for (int r = 0; r < 2; ++r)
 #pragma unroll
             for (int s = 0; s < 2; ++s) acc[k][r][s] = 0.f;
-    fetch(0);
+    // Every group makes the same number of rounds (and meets the same barriers); a group whose
+    // chunk lies past the last channel stages zeros and multiplies nothing.
+    const int rounds = (p.Cin + M_KC * KS - 1) / (M_KC * KS);
+    fetch(grp * M_KC);
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int ci0 = 0; ci0 < p.Cin; ci0 += M_KC) {
-        const bool more = ci0 + M_KC < p.Cin;                   // uniform
-        if (more) fetch(ci0 + M_KC);
+    for (int round = 0; round < rounds; ++round) {
+        const int ci0 = (round * KS + grp) * M_KC;
+        const bool more = round + 1 < rounds;                   // uniform over the workgroup
+        if (more) fetch(ci0 + M_KC * KS);
         const float *X = &Xs[buf][ti * XW + tj];
 #pragma unroll
         for (int c = 0; c < M_KC; ++c) {
@@ -193,6 +210,31 @@ __global__ void __launch_bounds__(M_THREADS) direct_multi_kernel(const T *__rest
         buf ^= 1;
     }
 
+    if constexpr (KS > 1) {
+        // Add the groups' accumulators in group order: group g leaves its 4 * CO values per lane
+        // in its own (now idle) stages, group 0 collects.
+        __syncthreads();                                        // the last stage has been read by all
+        float *mine = multi_lds + grp * GROUP_FLOATS;
+        if (grp != 0) {
+#pragma unroll
+            for (int k = 0; k < CO; ++k)
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) mine[((k * 2 + r) * 2 + s2) * M_THREADS + tid] = acc[k][r][s2];
+        }
+        __syncthreads();
+        if (grp != 0) return;
+#pragma unroll
+        for (int g = 1; g < KS; ++g)
+#pragma unroll
+            for (int k = 0; k < CO; ++k)
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2)
+                        acc[k][r][s2] += multi_lds[g * GROUP_FLOATS + ((k * 2 + r) * 2 + s2) * M_THREADS + tid];
+    }
     if (i >= p.E || j >= p.E) return;
     const bool x1 = 2 * j + 1 < p.M;
 #pragma unroll
@@ -225,16 +267,48 @@ inline int co_per_lane(int Cout)
     return Cout % 4 == 0 ? 4 : Cout % 3 == 0 ? 3 : Cout % 2 == 0 ? 2 : 1;
 }
 
+// Lane groups per workgroup: several when the tiles alone leave most of the chip's load slots
+// empty and there are enough chunks to share (kernels up to 5 x 5: the larger ones need the
+// registers a 1024-lane workgroup does not have).
+inline int lane_groups(int n, size_t blocks, int Cin)
+{
+    if (n > 5 || blocks >= 1024) return 1;
+    if (Cin >= 64) return 4;
+    return Cin >= 32 ? 2 : 1;
+}
+
+template <int n, int CO, int M_KC, int KS, typename T>
+hipError_t launch_ks(const T *in, const T *w_seg, float *out, const MultiParams &p, unsigned blocks, hipStream_t stream)
+{
+    constexpr int fl = n / 2;
+    constexpr size_t lds = (size_t)KS * 2 * ((size_t)M_KC * (M_TI + fl) * (M_TJ + fl) + (size_t)M_KC * ((n * n * CO + 3) & ~3)) *
+                           sizeof(float);
+    static_assert(lds <= 160 * 1024, "stages fit the LDS of a CU");
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_multi_kernel<n, CO, M_KC, KS, T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((direct_multi_kernel<n, CO, M_KC, KS, T>), dim3(blocks), dim3(M_THREADS * KS), lds, stream, in,
+                       w_seg, out, p);
+    return hipGetLastError();
+}
+
 template <int n, int CO, typename T>
 hipError_t launch_co(const T *in, const T *w_seg, float *out, const MultiParams &p, hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)((size_t)p.B * (p.Cout / CO) * p.tiles_x * p.tiles_y);
+    const size_t blocks_l = (size_t)p.B * (p.Cout / CO) * p.tiles_x * p.tiles_y;
+    const unsigned blocks = (unsigned)blocks_l;
     // (bf16 weights are stored in groups of 8 input channels: chunks of 8 only.)
-    if (p.Cin <= 4 && sizeof(T) == 4)
-        hipLaunchKernelGGL((direct_multi_kernel<n, CO, 4, T>), dim3(blocks), dim3(M_THREADS), 0, stream, in, w_seg, out, p);
-    else
-        hipLaunchKernelGGL((direct_multi_kernel<n, CO, 8, T>), dim3(blocks), dim3(M_THREADS), 0, stream, in, w_seg, out, p);
-    return hipGetLastError();
+    if (p.Cin <= 4 && sizeof(T) == 4) return launch_ks<n, CO, 4, 1, T>(in, w_seg, out, p, blocks, stream);
+    if constexpr (n <= 5) {
+        const int ks = lane_groups(n, blocks_l, p.Cin);
+        // Four groups are 1024 lanes with 128 registers each: enough for up to 50 weights per channel.
+        if constexpr (n * n * CO <= 50)
+            if (ks == 4) return launch_ks<n, CO, 8, 4, T>(in, w_seg, out, p, blocks, stream);
+        if (ks >= 2) return launch_ks<n, CO, 8, 2, T>(in, w_seg, out, p, blocks, stream);
+    }
+    return launch_ks<n, CO, 8, 1, T>(in, w_seg, out, p, blocks, stream);
 }
 
 template <int n, typename T>

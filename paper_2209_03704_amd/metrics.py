@@ -17,6 +17,9 @@ from .workloads import Layer
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
+# fp32 on the vector ALUs: 256 CUs x 4 SIMDs x 32 multiply-adds per clock (packed pairs) x 2.4 GHz.
+# Built without packed fp32 instructions (as this library is) a SIMD retires 16 per clock: half of it.
+VALU_PEAK_TFLOPS = 157.3
 
 
 def useful_macs(layer: Layer) -> int:

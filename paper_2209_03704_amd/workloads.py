@@ -65,6 +65,9 @@ PAPER_LAYERS = (
     Layer("table1_224x224x3_n3_p2", 16, 3, 1, 224, 3, "f32", "uniform", P=2),
     Layer("table1_224x224x3_n4_p2", 16, 3, 1, 224, 4, "f32", "uniform", P=2),
     Layer("table1_224x224x3_n5_p2", 16, 3, 1, 224, 5, "f32", "uniform", P=2),
+    # the same image layers at a batch that fills the chip (about 3700 tiles at 16 images are two rounds of workgroups)
+    Layer("table1_224x224x3_n3_p2_b256", 256, 3, 1, 224, 3, "f32", "uniform", P=2),
+    Layer("table1_224x224x3_n5_p2_b256", 256, 3, 1, 224, 5, "f32", "uniform", P=2),
     Layer("table3_dcgan_l2_4to8", 64, 1024, 512, 4, 4, "f32", "relu_normal", P=2),
     Layer("table3_dcgan_l3_8to16", 64, 512, 256, 8, 4, "f32", "relu_normal", P=2),
     Layer("table3_dcgan_l4_16to32", 64, 256, 128, 16, 4, "f32", "relu_normal", P=2),

@@ -197,6 +197,35 @@ def test_direct_several_input_channels(B, Cin, Cout, N, n, dtype):
     check_layer(layer, paths=("direct",), seed=31 * N + 7 * n + Cin)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (1, 128, 3, 32, 4, 2),    # Table 3's 128 -> 3 output layer on one sample: four lane groups, four rounds
+    (2, 64, 3, 32, 4, 2),     # the 64 -> 3 one: two rounds
+    (1, 72, 3, 20, 4, 0),     # nine chunks over four groups: three groups idle in the last round
+    (1, 40, 2, 37, 5, 0),     # two groups, five chunks; odd M, two channels per lane
+    (2, 100, 4, 18, 3, 1),    # ragged last chunk (100 = 12 * 8 + 4), four channels per lane, odd padding factor
+    (1, 64, 4, 16, 4, 2),     # 4 x 4 with four channels per lane: two groups (registers)
+    (1, 96, 1, 40, 5, 2),     # one channel per lane, 5 x 5
+    (3, 33, 6, 21, 2, 0),     # Cout = 6: lanes take 3 channels; a chunk with one channel in it
+    (1, 256, 3, 9, 1, 0),     # n = 1: three empty sub-kernels, 32 chunks
+])
+def test_direct_many_input_channels_in_lane_groups(B, Cin, Cout, N, n, P, dtype):
+    """Few tiles and many input channels: the workgroup's lane groups share the reduction of a tile
+    and their sums are added in a fixed order (bit-reproducible)."""
+    layer = wl.Layer("multi_groups", B, Cin, Cout, N, n, dtype, "normal", w_std=0.3)
+    x, w = wl.make_tensors(layer, 500 + Cin + 3 * n)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    got = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_DIRECT)
+    again = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_DIRECT)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    e = rel_err(got.cpu().numpy(), want)
+    assert e <= TOL[dtype], "rel err %.3e" % e
+    int_layer = wl.Layer("multi_groups_int", B, Cin, Cout, N, n, dtype, "integer")
+    check_exact_with_guards(int_layer, kst.KST_PATH_DIRECT, 600 + Cin, P=P)
+
+
 def test_direct_several_input_channels_is_exact_on_integers_and_stays_inside_out():
     for (B, Cin, Cout, N, n, P) in [(2, 20, 3, 32, 4, 0), (1, 9, 2, 37, 5, 0), (2, 3, 1, 30, 3, 2), (1, 6, 4, 11, 4, 3),
                                     (1, 5, 3, 2, 5, 2)]:
