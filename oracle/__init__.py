@@ -51,6 +51,8 @@ def _load():
             for fn in (lib.kst_oracle_backward_input, lib.kst_oracle_backward_weight):
                 fn.argtypes = [dp, dp, dp] + [ctypes.c_int] * 6
                 fn.restype = ctypes.c_int
+            lib.kst_oracle_forward_epilogue.argtypes = [dp, dp, dp, dp] + [ctypes.c_int] * 7
+            lib.kst_oracle_forward_epilogue.restype = ctypes.c_int
             lib.kst_oracle_forward_planes.argtypes = (
                 [dp, dp, dp, ip, ip, ctypes.c_int] + [ctypes.c_int] * 6)
             lib.kst_oracle_forward_planes.restype = ctypes.c_int
@@ -102,6 +104,31 @@ def forward(x, w, P: int = 0) -> np.ndarray:
     rc = lib.kst_oracle_forward(_dptr(x), _dptr(w), _dptr(out), B, Cin, Cout, N, n, P)
     if rc != 0:
         raise RuntimeError("kst_oracle_forward failed (%d)" % rc)
+    return out
+
+
+ACT_NONE, ACT_RELU, ACT_TANH = 0, 1, 2
+
+
+def forward_epilogue(x, w, bias=None, act: int = ACT_NONE, P: int = 0) -> np.ndarray:
+    """act(forward(x, w, P) + bias[co]) in fp64; bias: Cout values or None."""
+    x = _f64(x, 4)
+    w = _f64(w, 4)
+    B, Cin, Cout, N, n = _dims(x, w)
+    lib = _load()
+    M = lib.kst_oracle_out_size(N, n, P)
+    if M < 1:
+        raise ValueError("kernel larger than the up-sampled map")
+    bp = None
+    if bias is not None:
+        bias = _f64(bias, 1)
+        if bias.shape != (Cout,):
+            raise ValueError("bias must hold Cout values")
+        bp = _dptr(bias)
+    out = np.empty((B, Cout, M, M), dtype=np.float64)
+    rc = lib.kst_oracle_forward_epilogue(_dptr(x), _dptr(w), bp, _dptr(out), B, Cin, Cout, N, n, P, int(act))
+    if rc != 0:
+        raise RuntimeError("kst_oracle_forward_epilogue failed (%d)" % rc)
     return out
 
 

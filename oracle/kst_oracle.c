@@ -29,8 +29,11 @@
  * the scatter (adjoint) form, linearity, the adjoint identity with a strided
  * correlation, library conv routines on fp64, and the operation counts of
  * Table 4; the gradients by the inner-product identities that define an adjoint and
- * by a library autograd of the forward in fp64.
+ * by a library autograd of the forward in fp64; the bias + activation form by constant maps
+ * (zero kernel), printed values of tanh, the order of bias and activation on a one-pixel
+ * layer, the hand-worked example shifted and clipped, and a library layer in fp64.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -103,6 +106,35 @@ int kst_oracle_forward(const double *in, const double *w, double *out,
                             out + ((size_t)b * Cout + co) * M * M, Cin, Sp, n, M);
     }
     free(Upad);
+    return 0;
+}
+
+/*
+ * The layer as a generator uses it: the transpose convolution above, then a bias per output
+ * channel, then an activation.  The paper leaves both out (its layers are timed bare; Table 3
+ * only lists the generators they come from); this is the usual definition of such a layer,
+ * written out on top of kst_oracle_forward:
+ *     out[b][co][y][x] = act( T[b][co][y][x] + bias[co] ),   T = kst_oracle_forward(in, w)
+ * act: 0 identity, 1 max(v, 0), 2 tanh(v).  bias may be NULL (no bias).  fp64, libm's tanh.
+ * Returns 0, or 1 for an illegal shape, an unknown act or a failed allocation.
+ */
+int kst_oracle_forward_epilogue(const double *in, const double *w, const double *bias, double *out,
+                                int B, int Cin, int Cout, int N, int n, int P, int act)
+{
+    if (act < 0 || act > 2) return 1;
+    if (kst_oracle_forward(in, w, out, B, Cin, Cout, N, n, P) != 0) return 1;
+    const int M = kst_oracle_out_size(N, n, P);
+    for (int b = 0; b < B; ++b)
+        for (int co = 0; co < Cout; ++co) {
+            double *plane = out + ((size_t)b * Cout + co) * M * M;
+            for (size_t e = 0; e < (size_t)M * M; ++e) {
+                double v = plane[e];
+                if (bias) v += bias[co];
+                if (act == 1) v = v > 0.0 ? v : 0.0;
+                else if (act == 2) v = tanh(v);
+                plane[e] = v;
+            }
+        }
     return 0;
 }
 

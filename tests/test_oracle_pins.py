@@ -504,3 +504,92 @@ def test_input_gradient_is_a_stride_two_correlation_with_the_rotated_kernel():
                     if 0 <= y < M and 0 <= xx < M:
                         want[0, :, a, c] += np.einsum("o,oi->i", g[0, :, y, xx], w[:, :, u, v])
     assert np.array_equal(oracle.backward_input(g, w, N, 0), want)
+
+
+# ----------------------------------------------------------------------------
+# 11. Bias and activation on top of the layer (not in the paper: the usual form of the
+# generator layers its Table 3 takes its shapes from)
+# ----------------------------------------------------------------------------
+# tanh at a few arguments, from a table of the function (15 digits)
+TANH_TABLE = {-1.5: -0.905148253644866, -0.25: -0.244918662403709, 0.0: 0.0, 0.5: 0.462117157260010,
+              1.0: 0.761594155955765, 2.0: 0.964027580075817}
+
+
+def test_epilogue_without_bias_and_activation_is_the_layer_itself():
+    rng = np.random.default_rng(1101)
+    x, w = rand_case(rng, 2, 3, 4, 6, 3)
+    assert np.array_equal(oracle.forward_epilogue(x, w), oracle.forward(x, w))
+    assert np.array_equal(oracle.forward_epilogue(x, w, None, oracle.ACT_NONE, 2), oracle.forward(x, w, 2))
+
+
+def test_epilogue_on_a_zero_kernel_is_a_constant_map_per_channel():
+    # a wrong channel index for the bias, or a bias added once per batch item or row, shows here
+    bias = np.array(sorted(TANH_TABLE), dtype=np.float64)
+    Cout = bias.size
+    x = np.random.default_rng(5).normal(size=(3, 2, 5, 5))
+    w = np.zeros((Cout, 2, 4, 4))
+    for P in (0, 1, 2):
+        M = oracle.out_size(5, 4, P)
+        got = oracle.forward_epilogue(x, w, bias, oracle.ACT_NONE, P)
+        assert got.shape == (3, Cout, M, M)
+        assert np.array_equal(got, np.broadcast_to(bias[None, :, None, None], got.shape))
+        got = oracle.forward_epilogue(x, w, bias, oracle.ACT_RELU, P)
+        assert np.array_equal(got, np.broadcast_to(np.maximum(bias, 0.0)[None, :, None, None], got.shape))
+        got = oracle.forward_epilogue(x, w, bias, oracle.ACT_TANH, P)
+        want = np.array([TANH_TABLE[b] for b in bias])
+        assert np.abs(got - want[None, :, None, None]).max() <= 1e-14
+
+
+def test_epilogue_adds_the_bias_before_the_activation():
+    # 1 x 1 input, 1 x 1 kernel: T = in * w = -1.  With bias 2: relu(-1 + 2) = 1, not relu(-1) + 2 = 2;
+    # with bias -2: relu(-3) = 0, not relu(-1) - 2 = -2; tanh(-1 + 2) = tanh(1).
+    x = np.full((1, 1, 1, 1), -1.0)
+    w = np.ones((1, 1, 1, 1))
+    assert oracle.forward(x, w)[0, 0, 0, 0] == -1.0
+    assert oracle.forward_epilogue(x, w, [2.0], oracle.ACT_RELU)[0, 0, 0, 0] == 1.0
+    assert oracle.forward_epilogue(x, w, [-2.0], oracle.ACT_RELU)[0, 0, 0, 0] == 0.0
+    assert oracle.forward_epilogue(x, w, [-2.0], oracle.ACT_NONE)[0, 0, 0, 0] == -3.0
+    assert abs(oracle.forward_epilogue(x, w, [2.0], oracle.ACT_TANH)[0, 0, 0, 0] - TANH_TABLE[1.0]) <= 1e-15
+    assert oracle.forward_epilogue(x, w, None, oracle.ACT_RELU)[0, 0, 0, 0] == 0.0
+
+
+@pytest.mark.parametrize("n", [3, 5])
+def test_epilogue_on_the_hand_worked_example(n):
+    # the hand-worked maps of Fig. 2's and Figs. 5-6's shapes, shifted down by a bias that
+    # sends part of them below zero, then clipped
+    want_t = read_golden()[n]
+    x = (np.arange(16, dtype=np.float64) + 1).reshape(1, 1, 4, 4)
+    w = (np.arange(n * n, dtype=np.float64) + 1).reshape(1, 1, n, n)
+    bias = -float(np.median(want_t))
+    assert (want_t + bias < 0).any() and (want_t + bias > 0).any()
+    got = oracle.forward_epilogue(x, w, [bias], oracle.ACT_RELU)
+    assert np.array_equal(got[0, 0], np.maximum(want_t + bias, 0.0))
+    got = oracle.forward_epilogue(x, w, [bias], oracle.ACT_NONE)
+    assert np.array_equal(got[0, 0], want_t + bias)
+
+
+@pytest.mark.parametrize("act", ["none", "relu", "tanh"])
+@pytest.mark.parametrize("N,n,P", [(5, 4, 2), (6, 3, 0), (4, 5, 2), (7, 4, 1)])
+def test_epilogue_against_a_library_layer(N, n, P, act):
+    """A library transpose-convolution layer with bias (stride 2, the kernel rotated by 180 degrees,
+    channel axes swapped, padding n-1-P) followed by the library's activation, all in fp64."""
+    rng = np.random.default_rng(1200 + 10 * N + n + P)
+    x, w = rand_case(rng, 2, 3, 5, N, n)
+    bias = rng.normal(size=5)
+    code = {"none": oracle.ACT_NONE, "relu": oracle.ACT_RELU, "tanh": oracle.ACT_TANH}[act]
+    got = oracle.forward_epilogue(x, w, bias, code, P)
+    w_t = torch.flip(torch.from_numpy(w), dims=(2, 3)).permute(1, 0, 2, 3).contiguous()
+    ref = torch.nn.functional.conv_transpose2d(torch.from_numpy(x), w_t, bias=torch.from_numpy(bias), stride=2,
+                                               padding=n - 1 - P)
+    ref = {"none": lambda t: t, "relu": torch.relu, "tanh": torch.tanh}[act](ref).numpy()
+    assert ref.shape == got.shape
+    assert np.abs(got - ref).max() <= 1e-12 * max(1.0, np.abs(ref).max())
+
+
+def test_epilogue_rejects_an_unknown_activation_and_a_wrong_bias_length():
+    x = np.ones((1, 1, 3, 3))
+    w = np.ones((2, 1, 3, 3))
+    with pytest.raises(RuntimeError):
+        oracle.forward_epilogue(x, w, None, 3)
+    with pytest.raises(ValueError):
+        oracle.forward_epilogue(x, w, [1.0], oracle.ACT_RELU)
