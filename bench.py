@@ -292,6 +292,11 @@ def main():
             unseg_ms = time_launches(torch, lambda i: kst.kst_forward(r.x[i % r.sets], r.w, out=r.out[i % r.sets]),
                                      iters, 5)
             parts_ms = time_launches(torch, whole_path(r), iters, 5)
+            # the same layer with a bias and a ReLU applied at the stores
+            bias = torch.zeros(layer.Cout, dtype=torch.float32, device="cuda")
+            epi_ms = time_launches(torch, lambda i: kst.kst_forward_seg_epilogue(
+                r.x[i % r.sets], r.w_seg, layer.Cout, layer.n, bias, kst.KST_ACT_RELU, 0, out=r.out[i % r.sets],
+                ws=r.ws), iters, 3)
             roof_l = roofline_for(layer, ms, metrics)
             roof_l["frac_of_measured_yardstick"] = of_measured(layer, roof_l)
             table.append({
@@ -304,6 +309,7 @@ def main():
                 "segregate_us": round(seg_ms * 1e3, 2),
                 "forward_unsegregated_w_us": round(unseg_ms * 1e3, 2),              # kst_forward
                 "segregate_then_forward_us": round(parts_ms * 1e3, 2),              # its two parts, caller's buffers
+                "forward_bias_relu_us": round(epi_ms * 1e3, 2),                     # kst_forward_seg_epilogue
                 "useful_GMAC_per_s": round(metrics.useful_macs(layer) / (ms * 1e-3) / 1e9, 1),
                 "algorithmic_GB_per_s": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9, 1),
                 "hbm_frac": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),

@@ -55,7 +55,8 @@ typedef enum {
     KST_ERR_WORKSPACE = 4,  /* workspace missing or smaller than kst_workspace_bytes  */
     KST_ERR_HIP = 5,        /* the HIP runtime refused an allocation or a launch      */
     KST_ERR_PATH = 6,       /* unknown kst_path, or a path that cannot run this shape */
-    KST_ERR_ALIGN = 7       /* a data pointer is not 16-byte aligned                  */
+    KST_ERR_ALIGN = 7,      /* a data pointer is not 16-byte aligned                  */
+    KST_ERR_ACT = 8         /* activation is none of KST_ACT_NONE, _RELU, _TANH       */
 } kst_status;
 
 /* Which kernel family kst_forward_seg uses.  AUTO picks DIRECT for small
@@ -81,6 +82,13 @@ typedef enum {
     KST_PATH_IGEMM_EVEN = 3,
     KST_PATH_IGEMM_PASSES = 4
 } kst_path;
+
+/* What kst_forward_seg_epilogue applies to every output element after the bias. */
+typedef enum {
+    KST_ACT_NONE = 0,       /* v            */
+    KST_ACT_RELU = 1,       /* max(v, 0)    */
+    KST_ACT_TANH = 2        /* tanh(v)      */
+} kst_activation;
 
 int kst_version(void);
 const char *kst_status_string(int status);
@@ -200,6 +208,26 @@ kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, 
                                   hipStream_t stream);
 kst_status kst_forward_padded(const void *in, const void *w, void *out,
                               int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, hipStream_t stream);
+
+/*
+ * The layer as a generator uses it (not part of the paper's method, whose
+ * layers are timed bare; the generators of its Table 3 follow each of them
+ * with a bias and a ReLU or, on the last layer, a tanh):
+ *     out[b][co][y][x] = act( T[b][co][y][x] + bias[co] )
+ * with T the result of kst_forward_seg_padded on the same arguments.  The bias
+ * and the activation are applied in fp32 where a kernel stores the final value
+ * of an element (for split reductions: in the pass that sums the partial
+ * results), so the layer costs no extra pass over `out`.  bias: Cout fp32
+ * values in device memory, 4-byte aligned, or NULL for none.  act: see
+ * kst_activation (KST_ERR_ACT for anything else).  Everything else -- layouts,
+ * P, workspace (kst_workspace_bytes_padded), paths, stream, statuses -- is as
+ * for kst_forward_seg_padded; KST_PATH_IGEMM_PASSES takes no epilogue
+ * (KST_ERR_PATH).  With bias = NULL and KST_ACT_NONE the call is
+ * kst_forward_seg_padded.
+ */
+kst_status kst_forward_seg_epilogue(const void *in, const void *w_seg, const float *bias, void *out, void *ws,
+                                    size_t ws_bytes, int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype,
+                                    kst_activation act, kst_path path, hipStream_t stream);
 
 /*
  * Gradients (end of Section 3.3: the segregated method also gives the input and

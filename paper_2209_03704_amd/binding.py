@@ -14,6 +14,7 @@ import torch
 
 KST_F32, KST_BF16, KST_F16 = 0, 1, 2
 KST_PATH_AUTO, KST_PATH_DIRECT, KST_PATH_IGEMM, KST_PATH_IGEMM_EVEN, KST_PATH_IGEMM_PASSES = 0, 1, 2, 3, 4
+KST_ACT_NONE, KST_ACT_RELU, KST_ACT_TANH = 0, 1, 2
 KST_OK = 0
 KST_STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -40,6 +41,8 @@ SIGNATURES = {
     "kst_out_size_padded": (_c_int, [_c_int] * 3),
     "kst_workspace_bytes_padded": (_c_size_t, [_c_int] * 8),
     "kst_forward_seg_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 8 + [_c_void_p]),
+    "kst_forward_seg_epilogue": (_c_int, [_c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_void_p, _c_size_t] + [_c_int] * 9
+                                 + [_c_void_p]),
     "kst_forward_padded": (_c_int, [_c_void_p, _c_void_p, _c_void_p] + [_c_int] * 7 + [_c_void_p]),
     "kst_backward_input_workspace_bytes": (_c_size_t, [_c_int] * 7),
     "kst_backward_weight_workspace_bytes": (_c_size_t, [_c_int] * 7),
@@ -255,6 +258,34 @@ def kst_forward_seg_padded(x: torch.Tensor, w_seg: torch.Tensor, Cout: int, n: i
                                       B, Cin, Cout, N, n, P, dt, path, _stream())
     if st != KST_OK:
         raise KstError(st, "kst_forward_seg_padded")
+    return out
+
+
+def kst_forward_seg_epilogue(x: torch.Tensor, w_seg: torch.Tensor, Cout: int, n: int, bias: torch.Tensor | None = None,
+                             act: int = KST_ACT_NONE, P: int = 0, out: torch.Tensor | None = None,
+                             ws: torch.Tensor | None = None, path: int = KST_PATH_AUTO) -> torch.Tensor:
+    """act(transpose convolution + bias[co]); bias: Cout float32 values on the device, or None."""
+    B, Cin, Cout, N, n = _dims(x, n, Cout)
+    dt = _dtype_code(x)
+    if w_seg.dtype != x.dtype:
+        raise TypeError("x and w_seg must share a dtype")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != Cout or not bias.is_contiguous()):
+        raise TypeError("bias must hold Cout contiguous float32 values")
+    M = 2 * N + 2 * P - n
+    if out is None:
+        out = torch.empty((B, Cout, max(M, 0), max(M, 0)), dtype=torch.float32, device=x.device)
+    elif out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    need = kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, dt, path)
+    if ws is None and need:
+        ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_ptr = _dev(ws, "ws") if ws is not None else None
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    st = lib().kst_forward_seg_epilogue(_dev(x, "x"), _dev(w_seg, "w_seg"), _dev(bias, "bias") if bias is not None else None,
+                                        _dev(out, "out"), ws_ptr, ws_bytes, B, Cin, Cout, N, n, P, dt, act, path,
+                                        _stream())
+    if st != KST_OK:
+        raise KstError(st, "kst_forward_seg_epilogue")
     return out
 
 

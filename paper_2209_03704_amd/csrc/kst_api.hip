@@ -93,6 +93,7 @@ kst_status run_forward_seg(const void *in, const void *w_seg, void *out, void *w
     }
     if (s.Ns != s.N && !(on_matrix_cores(chosen) && dtype == KST_F32 && igemm_f32_takes_row_stride(s)))
         return KST_ERR_SHAPE;
+    if (chosen == KST_PATH_IGEMM_PASSES && epi_on(s.epi)) return KST_ERR_PATH;    // that kernel stores bare sums only
     hipError_t e;
     if (chosen == KST_PATH_DIRECT)
         e = launch_direct(in, w_seg, (float *)out, s, dtype, stream);
@@ -149,7 +150,7 @@ hipError_t scratch_alloc(void **ptr, size_t bytes, hipStream_t stream)
 
 extern "C" {
 
-int kst_version(void) { return 101; }
+int kst_version(void) { return 102; }
 
 const char *kst_status_string(int status)
 {
@@ -162,6 +163,7 @@ const char *kst_status_string(int status)
         case KST_ERR_HIP: return "HIP runtime error";
         case KST_ERR_PATH: return "unknown or unsupported path";
         case KST_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case KST_ERR_ACT: return "unknown activation";
         default: return "unknown status";
     }
 }
@@ -357,16 +359,29 @@ size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P,
     return f.in_bytes + f.wide_bytes + workspace_for(f.s, dtype, f.chosen);
 }
 
-kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
-                                  int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path,
-                                  hipStream_t stream)
+}  // extern "C"
+
+namespace {
+
+// The segregated forward pass for any padding factor, with an optional epilogue at the stores
+// that write final values (the copy that crops an odd padding factor's wider map moves them on unchanged).
+kst_status forward_seg_padded_impl(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes, int B, int Cin,
+                                   int Cout, int N, int n, int P, kst_dtype dtype, int path, const Epilogue &epi,
+                                   hipStream_t stream)
 {
-    if (P == 0) return kst_forward_seg(in, w_seg, out, ws, ws_bytes, B, Cin, Cout, N, n, dtype, path, stream);
     if (!in || !w_seg || !out) return KST_ERR_NULL;
     if (!dtype_ok(dtype)) return KST_ERR_DTYPE;
+    if (P == 0) {
+        kst_status st0 = check_shape(B, Cin, Cout, N, n);
+        if (st0 != KST_OK) return st0;
+        Shape s0 = make_shape(B, Cin, Cout, N, n);
+        s0.epi = epi;
+        return run_forward_seg(in, w_seg, out, ws, ws_bytes, s0, dtype, path, stream);
+    }
     Framed f;
     kst_status st = framed_plan(B, Cin, Cout, N, n, P, dtype, path, &f);
     if (st != KST_OK) return st;
+    f.s.epi = epi;
     if (!aligned16(in) || !aligned16(w_seg) || !aligned16(out)) return KST_ERR_ALIGN;
     const size_t inner = workspace_for(f.s, dtype, f.chosen);
     const size_t need = f.in_bytes + f.wide_bytes + inner;
@@ -387,6 +402,28 @@ kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, 
     if (st != KST_OK) return st;
     if (wide && launch_crop(wide, (float *)out, B, Cout, f.M, 1, stream) != hipSuccess) return KST_ERR_HIP;
     return KST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+kst_status kst_forward_seg_padded(const void *in, const void *w_seg, void *out, void *ws, size_t ws_bytes,
+                                  int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path,
+                                  hipStream_t stream)
+{
+    const Epilogue none = {nullptr, KST_ACT_NONE};
+    return forward_seg_padded_impl(in, w_seg, out, ws, ws_bytes, B, Cin, Cout, N, n, P, dtype, path, none, stream);
+}
+
+kst_status kst_forward_seg_epilogue(const void *in, const void *w_seg, const float *bias, void *out, void *ws,
+                                    size_t ws_bytes, int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype,
+                                    kst_activation act, kst_path path, hipStream_t stream)
+{
+    if (act != KST_ACT_NONE && act != KST_ACT_RELU && act != KST_ACT_TANH) return KST_ERR_ACT;
+    if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u) != 0) return KST_ERR_ALIGN;
+    const Epilogue epi = {bias, (int)act};
+    return forward_seg_padded_impl(in, w_seg, out, ws, ws_bytes, B, Cin, Cout, N, n, P, dtype, path, epi, stream);
 }
 
 kst_status kst_forward_padded(const void *in, const void *w, void *out, int B, int Cin, int Cout, int N, int n, int P,

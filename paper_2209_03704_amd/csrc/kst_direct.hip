@@ -27,6 +27,7 @@ struct DirectParams {
     int B, Cin, Cout, N, M, E;
     int tiles_x, tiles_y;
     unsigned off[4];   // element offset of W_p in the segregated buffer
+    Epilogue epi;
 };
 
 constexpr int D_TJ = 64;                 // quad columns per tile = lanes of a wave
@@ -109,6 +110,15 @@ __global__ void __launch_bounds__(256) direct_kernel(const T *__restrict__ in, c
     const int gj = j0 + lane;
     const int x = 2 * gj;
     if (x >= p.M) return;
+    if (epi_on(p.epi)) {                                     // uniform
+        const float bias = epi_bias(p.epi, co);
+#pragma unroll
+        for (int q = 0; q < D_RPT; ++q)
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[q][r][s2] = epi_apply(acc[q][r][s2], bias, p.epi.act);
+    }
 #pragma unroll
     for (int q = 0; q < D_RPT; ++q)
 #pragma unroll
@@ -159,6 +169,7 @@ struct RowsParams {
     int xs_buf;               // floats per LDS input buffer
     int xs_stride;            // floats per staged row: N rounded up to 4, plus 8
     unsigned off[4];
+    Epilogue epi;
 };
 
 constexpr int R_PAD = 4;      // slack floats left of each staged row (and at least as many right)
@@ -294,11 +305,14 @@ __device__ __forceinline__ void rows_emit(float *__restrict__ out, const float *
     const int y = g.y0 + row;
     const float *rowp = Xs + ((row >> 1) + r) * p.xs_stride + R_PAD;
     float *orow = out + g.plane_base + (size_t)y * p.M;
+    const bool epi = epi_on(p.epi);                          // uniform
+    const float bias = epi ? epi_bias(p.epi, g.co) : 0.0f;
     for (int t = threadIdx.x; 4 * t - shift < p.M; t += 256) {
         const int x0 = 4 * t - shift;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (shift & 1) rows_group<n, r, 1>(acc, rowp, p.xs_stride, ((x0 - 1) >> 1) + 1, wk);
         else rows_group<n, r, 0>(acc, rowp, p.xs_stride, x0 >> 1, wk);
+        if (epi) epi_apply4(acc.x, acc.y, acc.z, acc.w, bias, p.epi.act);
         rows_store(orow + x0, acc, x0, p.M);
     }
 }
@@ -420,6 +434,7 @@ __global__ void __launch_bounds__(256) direct_generic_kernel(const T *__restrict
                         a = fmaf(to_f32(src[(size_t)u * p.N + v]),
                                  to_f32(w_seg[wseg_index<T>(p.off[2 * r + s], Ta * Tb, p.Cout, ci, u * Tb + v, co)]), a);
             }
+            if (epi_on(p.epi)) a = epi_apply(a, epi_bias(p.epi, co), p.epi.act);
             out[((size_t)plane * p.M + y) * p.M + x] = a;
         }
 }
@@ -462,6 +477,7 @@ static bool try_rows(const T *in, const T *w_seg, float *out, const Shape &s, ks
     // keeps HBM pages hot).
     p.xcd_remap = 0;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
+    p.epi = s.epi;
     // Persistent: a few workgroups per CU, each walking over its share of the strips.
     unsigned grid = 1024;
     if (grid > p.xcd_slots * 8) grid = p.xcd_slots * 8;
@@ -494,6 +510,7 @@ static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, k
     p.tiles_x = (s.E + D_TJ - 1) / D_TJ;
     p.tiles_y = (s.E + D_TI - 1) / D_TI;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
+    p.epi = s.epi;
     const size_t blocks = (size_t)s.B * s.Cout * p.tiles_x * p.tiles_y;
     if (s.n <= 7 && blocks < 0x7fffffffu) {
         const unsigned nb = (unsigned)blocks;

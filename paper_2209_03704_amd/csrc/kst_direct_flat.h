@@ -19,6 +19,7 @@ struct FlatParams {
     int max_rows;           // input rows one piece can need
     int xs_stride, xs_buf;  // floats per staged row / per LDS buffer
     unsigned off[4];        // element offset of W_p in the segregated weights
+    Epilogue epi;
 };
 
 // False when the shape is outside what the kernel covers (then the caller uses another path).

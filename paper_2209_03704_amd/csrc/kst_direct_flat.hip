@@ -42,6 +42,11 @@ namespace {
 
 // 16-byte aligned streaming store of four outputs.
 __device__ __forceinline__ void store_streaming(float *dst, const float (&o)[4]) { store_streaming4(dst, o[0], o[1], o[2], o[3]); }
+// on: whether an epilogue is active (uniform over the workgroup).
+__device__ __forceinline__ void flat_epilogue(float (&o)[4], bool on, float bias, int act)
+{
+    if (on) epi_apply4(o[0], o[1], o[2], o[3], bias, act);
+}
 
 constexpr int F_PAD = 4;      // slack floats left and right of each staged input row
 constexpr int F_THREADS = 512;
@@ -250,6 +255,8 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
 
     float wk[2][2][Ta0 * Ta0];
     int cur_co = -1;
+    const bool epi = epi_on(p.epi);
+    float bias = 0.0f;
     int buf = 0;
     while (true) {
         // ---- the next piece and its loads --------------------------------------------------------
@@ -291,6 +298,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     for (int t = 0; t < Ta * Tb; ++t)
                         wk[r][s][t] = w_seg[p.off[2 * r + s] + (unsigned)(t * p.Cout + co)];   // Cin == 1
                 }
+            if (epi) bias = epi_bias(p.epi, co);
             cur_co = co;
         }
 
@@ -320,6 +328,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                 } else {
                     cross_segment<n>(o, Xs, p, pc.ia, y, xs, lane, wk);
                 }
+                flat_epilogue(o, epi, bias, p.epi.act);
                 store_streaming(out + fw + 4 * lane, o);
                 fw += F_STEP;
                 xs += p.s_x;
@@ -354,6 +363,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                             if (xx + k >= p.M) o[k] = o2[k];
                     }
                     float *dst = out + f0;                       // 16-byte aligned
+                    flat_epilogue(o, epi, bias, p.epi.act);
                     if (f0 >= pc.fa && f0 + 3 < pc.fb) {
                         store_streaming(dst, o);
                     } else {
@@ -414,6 +424,7 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     lds = (size_t)2 * p.xs_buf * sizeof(float);
     if (lds > 64 * 1024) return false;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(1, s.Cout, s.n, c, KST_F32);
+    p.epi = s.epi;
     // One resident round: three 512-lane workgroups per CU on 256 CUs.
     const int wgs = 768;
     grid = (unsigned)wgs;

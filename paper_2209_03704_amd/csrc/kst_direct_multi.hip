@@ -32,6 +32,7 @@ struct MultiParams {
     int N0, q;                           // edge of the tensor in memory; zero frame around it (virtual)
     int tiles_x, tiles_y;
     unsigned off[4];                     // element offset of W_p in the segregated buffer
+    Epilogue epi;
 };
 
 template <typename T>
@@ -236,6 +237,16 @@ __global__ void __launch_bounds__(M_THREADS * KS) direct_multi_kernel(const T *_
                         acc[k][r][s2] += multi_lds[g * GROUP_FLOATS + ((k * 2 + r) * 2 + s2) * M_THREADS + tid];
     }
     if (i >= p.E || j >= p.E) return;
+    if (epi_on(p.epi)) {                                        // uniform
+#pragma unroll
+        for (int k = 0; k < CO; ++k) {
+            const float bias = epi_bias(p.epi, co0 + k);
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[k][r][s2] = epi_apply(acc[k][r][s2], bias, p.epi.act);
+        }
+    }
     const bool x1 = 2 * j + 1 < p.M;
 #pragma unroll
     for (int k = 0; k < CO; ++k) {
@@ -332,6 +343,7 @@ hipError_t launch_t(const T *in, const T *w_seg, float *out, const Shape &s, kst
     p.tiles_x = (s.E + M_TJ - 1) / M_TJ;
     p.tiles_y = (s.E + M_TI - 1) / M_TI;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
+    p.epi = s.epi;
     switch (s.n) {
         case 1: return launch_n<1, T>(in, w_seg, out, p, stream);
         case 2: return launch_n<2, T>(in, w_seg, out, p, stream);

@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_bf16_kernel(const uint16_t *_
     }
 
     if (!m_valid) return;
-    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj, p.splits == 1);
 }
 
 static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_BF16, H_KC); }
@@ -184,7 +184,8 @@ static hipError_t launch_plain(const void *in_v, const void *w_seg_v, float *out
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream);
+    if (p.splits > 1)
+        e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream, p.epi, (size_t)p.M * p.M, p.Cout);
     return e;
 }
 

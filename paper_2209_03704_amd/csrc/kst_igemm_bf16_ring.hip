@@ -76,6 +76,7 @@ struct RingGeom {
 struct RingParams {
     int B, Cin, Cout, tiles_co;
     unsigned off[4];
+    Epilogue epi;
 };
 
 // Workgroup barrier that orders LDS traffic only (LDS-direct loads included): global
@@ -362,17 +363,21 @@ __global__ void __launch_bounds__(R_THREADS, 2) igemm_bf16_ring_kernel(const uin
             const int a16 = (int)(g_co & 15u);                          // run start inside its 64-byte segment
             const float *erun = Es + cl * G::ESTRIDE - (int)(g_co & 12u);   // group t of the run is at erun + 4t
             float *orun = out + (g_co & ~15u);
+            const bool epi = epi_on(p.epi);                             // uniform
+            const float bias = epi ? epi_bias(p.epi, co0 + pass * 32 + cl) : 0.0f;
 #pragma unroll
             for (int it = 0; it < (G::TG + 63) / 64; ++it) {
                 const int t = lane + 64 * it;
                 const int rel = 4 * t - a16;                           // first float of the group, relative to the run
                 if (rel >= 0 && rel + 3 < L) {
-                    const float4 v4 = *reinterpret_cast<const float4 *>(erun + 4 * t);
+                    float4 v4 = *reinterpret_cast<const float4 *>(erun + 4 * t);
+                    if (epi) epi_apply4(v4.x, v4.y, v4.z, v4.w, bias, p.epi.act);
                     store_streaming4(orun + 4 * t, v4.x, v4.y, v4.z, v4.w);
                 } else if (rel + 3 >= 0 && rel < L) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        if (rel + k >= 0 && rel + k < L) orun[4 * t + k] = erun[4 * t + k];
+                        if (rel + k >= 0 && rel + k < L)
+                            orun[4 * t + k] = epi ? epi_apply(erun[4 * t + k], bias, p.epi.act) : erun[4 * t + k];
                 }
             }
         }
@@ -412,6 +417,7 @@ hipError_t launch_igemm_bf16_ring(const void *in, const void *w_seg, float *out,
     RingParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.tiles_co = s.Cout / R_TCO;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
+    p.epi = s.epi;
     const uint16_t *i16 = (const uint16_t *)in, *w16 = (const uint16_t *)w_seg;
     switch (s.n * 1000 + s.N) {
         case 2032: return f16 ? launch_ring<2, 32, true>(i16, w16, out, p, stream) : launch_ring<2, 32, false>(i16, w16, out, p, stream);

@@ -35,6 +35,7 @@ struct StripParams {
     int estride;            // floats per channel in the epilogue's LDS image (multiple of 4)
     int tg;                 // 16-byte groups per channel run, upper bound
     unsigned off[4];
+    Epilogue epi;
 };
 
 template <int n, bool F16>
@@ -243,6 +244,8 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
             const unsigned g_co = g_first + (unsigned)(pass * 32 + cl) * MM;
             const unsigned base64 = g_co & ~15u;
             const float *erow = Es + cl * p.estride + (int)(g_co & 3u);
+            const bool epi = epi_on(p.epi);                             // uniform
+            const float bias = epi ? epi_bias(p.epi, co0 + pass * 32 + cl) : 0.0f;
             for (int t = lane; t < p.tg; t += 64) {
                 const unsigned f0 = base64 + 4u * t;
                 const int rel = (int)(f0 - g_co);
@@ -250,12 +253,13 @@ __global__ void __launch_bounds__(S_THREADS, 2) igemm_bf16_strip_kernel(const ui
                 const float *src = erow + rel;                       // 16-byte aligned
                 float *dst = out + f0;
                 if (rel >= 0 && rel + 3 < L) {
-                    const float4 v4 = *reinterpret_cast<const float4 *>(src);
+                    float4 v4 = *reinterpret_cast<const float4 *>(src);
+                    if (epi) epi_apply4(v4.x, v4.y, v4.z, v4.w, bias, p.epi.act);
                     store_streaming4(dst, v4.x, v4.y, v4.z, v4.w);
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        if (rel + k >= 0 && rel + k < L) dst[k] = src[k];
+                        if (rel + k >= 0 && rel + k < L) dst[k] = epi ? epi_apply(src[k], bias, p.epi.act) : src[k];
                 }
             }
         }
@@ -274,6 +278,7 @@ bool strip_plan(const Shape &s, StripParams &p, size_t &lds)
     if (p.npix > S_NXU * S_THREADS) return false;             // (npix / 2 pairs) * 2 octets units
     p.cin_oct = (s.Cin + 7) / 8;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
+    p.epi = s.epi;
     const int Lmax = 2 * p.TI * s.M;
     p.estride = (Lmax + 3 + 3) & ~3;
     p.tg = (15 + Lmax - 1) / 4 + 1;

@@ -84,6 +84,7 @@ struct WideGeom {
 struct WideParams {
     int B, Cin, Cout, tiles_co, ntiles;
     unsigned off[4];
+    Epilogue epi;
 };
 
 #define KST_LDS(T) T __attribute__((address_space(3)))
@@ -154,7 +155,9 @@ struct TapOrder {
     }
 };
 
-template <int n, int N, bool F16>
+// EPI: an instantiation of its own for layers with an epilogue (bias, activation), so that the
+// store loop of the bare layer stays exactly as it is scheduled without one.
+template <int n, int N, bool F16, bool EPI>
 __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wide_kernel(const uint16_t *__restrict__ in,
                                                                       const uint16_t *__restrict__ w_seg,
                                                                       float *__restrict__ out, WideParams p)
@@ -547,6 +550,11 @@ __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wi
                 float4 v[ITS];
 #pragma unroll
                 for (int it = 0; it < ITS; ++it) v[it] = *reinterpret_cast<const float4 *>(erun + 4 * (lane_e + 64 * it));
+                if constexpr (EPI) {
+                    const float bias = epi_bias(p.epi, co0 + ch);
+#pragma unroll
+                    for (int it = 0; it < ITS; ++it) epi_apply4(v[it].x, v[it].y, v[it].z, v[it].w, bias, p.epi.act);
+                }
 #pragma unroll
                 for (int it = 0; it < ITS; ++it) {
                     const int tt = lane_e + 64 * it;
@@ -568,19 +576,26 @@ __global__ void __launch_bounds__(W_THREADS, (WideGeom<n, N>::QH)) igemm_bf16_wi
     }
 }
 
-template <int n, int N, bool F16>
-hipError_t launch_wide(const uint16_t *in, const uint16_t *w_seg, float *out, const WideParams &p, hipStream_t stream)
+template <int n, int N, bool F16, bool EPI>
+hipError_t launch_wide_epi(const uint16_t *in, const uint16_t *w_seg, float *out, const WideParams &p, hipStream_t stream)
 {
     using G = WideGeom<n, N>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_wide_kernel<n, N, F16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_bf16_wide_kernel<n, N, F16, EPI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_B);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     const unsigned blocks = (unsigned)min(p.ntiles, (cus > 0 ? cus : 256) * G::QH);
-    hipLaunchKernelGGL((igemm_bf16_wide_kernel<n, N, F16>), dim3(blocks), dim3(W_THREADS), G::LDS_B, stream, in, w_seg, out, p);
+    hipLaunchKernelGGL((igemm_bf16_wide_kernel<n, N, F16, EPI>), dim3(blocks), dim3(W_THREADS), G::LDS_B, stream, in, w_seg, out, p);
     return hipGetLastError();
+}
+
+template <int n, int N, bool F16>
+hipError_t launch_wide(const uint16_t *in, const uint16_t *w_seg, float *out, const WideParams &p, hipStream_t stream)
+{
+    if (epi_on(p.epi)) return launch_wide_epi<n, N, F16, true>(in, w_seg, out, p, stream);
+    return launch_wide_epi<n, N, F16, false>(in, w_seg, out, p, stream);
 }
 
 template <int n, int N>
@@ -618,6 +633,7 @@ hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out,
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.tiles_co = s.Cout / W_TCO;
     p.ntiles = s.B * p.tiles_co * strips_of(s);
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_BF16);
+    p.epi = s.epi;
     const uint16_t *i16 = (const uint16_t *)in, *w16 = (const uint16_t *)w_seg;
     switch (s.n * 1000 + s.N) {
         case 2032: return f16 ? launch_wide<2, 32, true>(i16, w16, out, p, stream) : launch_wide<2, 32, false>(i16, w16, out, p, stream);

@@ -50,6 +50,7 @@ struct IgemmParams {
     unsigned off[4];       // element offset of W_p
     size_t out_elems;
     double est_s;          // the cost model's time for the launch chosen here (seconds)
+    Epilogue epi;          // applied by the stores that write final values (not by those of partial sums)
 };
 
 // kc: input channels staged per step.
@@ -96,27 +97,35 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     p.splits = (chunks + cps - 1) / cps;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
     p.out_elems = (size_t)s.B * s.Cout * s.M * s.M;
+    p.epi = s.epi;
     return p;
 }
 
 // Store 32 output channels of one wave's accumulators.  acc[cls] is the 32 x 32 block of class
 // cls (rows: output channels co_base + 8(v/4) + 4kk + v%4; column: this lane's quad).  The
 // s = 0 / s = 1 classes of a row parity sit side by side in memory.
+// final: these are the element's final values (the epilogue applies), not partial sums.
 __device__ __forceinline__ void igemm_store_block(float *__restrict__ o, const floatx16 &a0, const floatx16 &a1,
                                                   const floatx16 &a2, const floatx16 &a3, const IgemmParams &p,
-                                                  int co_base, int kk, int mb, int mi, int mj)
+                                                  int co_base, int kk, int mb, int mi, int mj, bool final = true)
 {
     const bool x1_ok = 2 * mj + 1 < p.M;
+    const bool epi = final && epi_on(p.epi);            // uniform
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = co_base + 8 * (v >> 2) + 4 * kk + (v & 3);
         if (co >= p.Cout) continue;
+        const float bias = epi ? epi_bias(p.epi, co) : 0.0f;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int y = 2 * mi + r;
             if (y >= p.M) continue;
             float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
-            const float v0 = r ? a2[v] : a0[v], v1 = r ? a3[v] : a1[v];
+            float v0 = r ? a2[v] : a0[v], v1 = r ? a3[v] : a1[v];
+            if (epi) {
+                v0 = epi_apply(v0, bias, p.epi.act);
+                v1 = epi_apply(v1, bias, p.epi.act);
+            }
             if (x1_ok) {
                 if ((reinterpret_cast<uintptr_t>(q) & 7u) == 0) {
                     *reinterpret_cast<float2 *>(q) = make_float2(v0, v1);
@@ -133,14 +142,16 @@ __device__ __forceinline__ void igemm_store_block(float *__restrict__ o, const f
 
 // Store one wave's accumulators: acc[cls][h] covers output channels co_base + 32h .. + 31.
 __device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][2], const IgemmParams &p,
-                                            int co_base, int kk, int mb, int mi, int mj)
+                                            int co_base, int kk, int mb, int mi, int mj, bool final = true)
 {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
-        igemm_store_block(o, acc[0][h], acc[1][h], acc[2][h], acc[3][h], p, co_base + h * 32, kk, mb, mi, mj);
+        igemm_store_block(o, acc[0][h], acc[1][h], acc[2][h], acc[3][h], p, co_base + h * 32, kk, mb, mi, mj, final);
 }
 
-// out[e] = sum over splits of ws[split][e], in split order (deterministic).
-hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream);
+// out[e] = sum over splits of ws[split][e], in split order (deterministic), then the epilogue if
+// one is active (element e belongs to output channel (e / plane_elems) % Cout).
+hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream,
+                                Epilogue epi = {nullptr, KST_ACT_NONE}, size_t plane_elems = 1, int Cout = 1);
 
 }  // namespace kst

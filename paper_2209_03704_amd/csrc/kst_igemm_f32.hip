@@ -136,7 +136,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_kernel(const float *__res
 
     // Epilogue: interleave the four classes; lanes l32 = consecutive quads of a row.
     if (!m_valid) return;
-    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj);
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, co0 + wco * 64, kk, mb, mi, mj, p.splits == 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -378,7 +378,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     pipe_accumulate<n, DB>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
     if (!L.m_valid) return;
     const int wave = threadIdx.x >> 6, kk = (threadIdx.x & 63) >> 5;
-    igemm_store(dst + (size_t)split * p.out_elems, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
+    igemm_store(dst + (size_t)split * p.out_elems, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj, p.splits == 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -531,12 +531,14 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const 
 
 // Sum the per-split partial outputs (fixed order: deterministic).
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restrict__ ws, float *__restrict__ out,
-                                                              size_t elems, int splits)
+                                                              size_t elems, int splits, Epilogue epi, size_t plane_elems,
+                                                              int Cout)
 {
     const size_t e = (size_t)blockIdx.x * 256u + threadIdx.x;
     if (e >= elems) return;
     float a = ws[e];
     for (int s = 1; s < splits; ++s) a += ws[(size_t)s * elems + e];
+    if (epi_on(epi)) a = epi_apply(a, epi_bias(epi, (int)((e / plane_elems) % (size_t)Cout)), epi.act);
     out[e] = a;
 }
 
@@ -734,7 +736,8 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    if (p.splits > 1) e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream);
+    if (p.splits > 1)
+        e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream, p.epi, (size_t)p.M * p.M, p.Cout);
     return e;
 }
 
@@ -742,7 +745,8 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
 // the partial results per workgroup, the shares added through LDS in a fixed order.
 template <int SH>
 __global__ void __launch_bounds__(256) splitk_reduce_shares_kernel(const float *__restrict__ ws, float *__restrict__ out,
-                                                                     size_t elems, int splits)
+                                                                     size_t elems, int splits, Epilogue epi,
+                                                                     size_t plane_elems, int Cout)
 {
     constexpr int EL = 256 / SH;
     __shared__ float red[SH][EL + 1];
@@ -756,25 +760,27 @@ __global__ void __launch_bounds__(256) splitk_reduce_shares_kernel(const float *
     if (share == 0 && e < elems) {
         float t = red[0][el];
         for (int k = 1; k < SH; ++k) t += red[k][el];
+        if (epi_on(epi)) t = epi_apply(t, epi_bias(epi, (int)((e / plane_elems) % (size_t)Cout)), epi.act);
         out[e] = t;
     }
 }
 
 // 64 and more partial results: 16 shares; 512 and more: 64 shares.
-hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream)
+hipError_t launch_splitk_reduce(const float *ws, float *out, size_t elems, int splits, hipStream_t stream, Epilogue epi,
+                                size_t plane_elems, int Cout)
 {
     if (splits >= 512) {
         hipLaunchKernelGGL(splitk_reduce_shares_kernel<64>, dim3((unsigned)((elems + 3) / 4)), dim3(256), 0, stream, ws, out,
-                           elems, splits);
+                           elems, splits, epi, plane_elems, Cout);
         return hipGetLastError();
     }
     if (splits >= 64) {
         hipLaunchKernelGGL(splitk_reduce_shares_kernel<16>, dim3((unsigned)((elems + 15) / 16)), dim3(256), 0, stream, ws, out,
-                           elems, splits);
+                           elems, splits, epi, plane_elems, Cout);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
-                       ws, out, elems, splits);
+                       ws, out, elems, splits, epi, plane_elems, Cout);
     return hipGetLastError();
 }
 

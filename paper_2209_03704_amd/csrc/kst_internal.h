@@ -56,6 +56,39 @@ __device__ __forceinline__ void store_streaming4(float *dst, float a, float b, f
     __builtin_nontemporal_store(v, reinterpret_cast<kst_floatx4 *>(dst));
 }
 
+// Optional epilogue on the store path (not part of the paper's method; the layers of the GAN
+// generators its Table 3 lists are followed by a bias and a ReLU or tanh):
+// out = act(out + bias[co]).  bias: Cout fp32 values in device memory, or nullptr for none.
+struct Epilogue {
+    const float *bias;
+    int act;             // kst_activation
+};
+__host__ __device__ inline bool epi_on(const Epilogue &e) { return e.bias != nullptr || e.act != KST_ACT_NONE; }
+__device__ __forceinline__ float epi_bias(const Epilogue &e, int co) { return e.bias ? e.bias[co] : 0.0f; }
+// One uniform branch (tanh or not); identity and ReLU share a branch-free form: max(v + b, floor)
+// with floor = 0 or -infinity.
+__device__ __forceinline__ float epi_floor(int act) { return act == KST_ACT_RELU ? 0.0f : -__builtin_inff(); }
+__device__ __forceinline__ float epi_apply(float v, float b, int act)
+{
+    if (act == KST_ACT_TANH) return tanhf(v + b);
+    return fmaxf(v + b, epi_floor(act));
+}
+__device__ __forceinline__ void epi_apply4(float &a, float &b, float &c, float &d, float bias, int act)
+{
+    if (act == KST_ACT_TANH) {
+        a = tanhf(a + bias);
+        b = tanhf(b + bias);
+        c = tanhf(c + bias);
+        d = tanhf(d + bias);
+    } else {
+        const float lo = epi_floor(act);
+        a = fmaxf(a + bias, lo);
+        b = fmaxf(b + bias, lo);
+        c = fmaxf(c + bias, lo);
+        d = fmaxf(d + bias, lo);
+    }
+}
+
 struct Shape {
     int B, Cin, Cout, N, n;
     int M;    // output edge 2N - n
@@ -64,11 +97,13 @@ struct Shape {
     int Ns;   // elements between consecutive rows of `in` (N unless the caller framed it with a wider stride)
     int frame; // > 0: `in` is the dense [B][Cin][N - 2 frame][N - 2 frame] tensor and the kernel supplies the
                // zero frame of that width itself (only kernels for which *_takes_virtual_frame says so)
+    Epilogue epi;  // applied where the final value of an element is stored (every forward kernel but the
+                   // row-parity-passes one, which must be given an inactive one)
 };
 
 inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
 {
-    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N, 0};
+    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N, 0, {nullptr, KST_ACT_NONE}};
     return s;
 }
 
