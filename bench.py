@@ -25,17 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of each layer's forward kernel, measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE in separate runs, each scaled by what the same counter reads
-# for `--only copy`, a plain copy of known size: 2.0 and 1.0).  Figures and commands:
-# profiles/hbm_traffic_pmc.txt.  They are measurements of an earlier run of these same
-# kernels, quoted next to the live timing; None for a layer that was not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_1ch_bandwidth": 339385417,
-    "cfg3_gan_n4": 513565875 + 137499522,   # matrix-core kernel + pass summing the partial tiles
-    "cfg4_deep_n5": 576979908 + 100629937,  # the same two kernels
-    "cfg5_late_bf16": 352252164,
-}
+MEASURED_TRAFFIC_BYTES = {}      # filled by measured_traffic() from profiles/hbm_traffic_pmc.txt
 
 
 def parse_args():
@@ -46,7 +36,10 @@ def parse_args():
     ap.add_argument("--layers", default="all", choices=["all", "none"],
                     help="also time each of the five benchmark layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default=None, help="time just this layer's kernel (profiling aid), e.g. cfg3")
+    ap.add_argument("--only", default=None,
+                    help="time just one pass of one layer (profiling aid): cfg1..cfg5, a paper-shaped layer's name, or copy")
+    ap.add_argument("--what", default="forward", choices=["forward", "backward_input", "backward_weight"],
+                    help="with --only: which pass of the layer")
     return ap.parse_args()
 
 
@@ -109,6 +102,48 @@ def launch_spread(torch, fn, iters, warmup):
     torch.cuda.synchronize()
     d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
     return d[len(d) // 2], d[0]
+
+
+def one_pass(layer, what, torch, kst, wl):
+    """A launcher fn(i) for one pass of `layer` (pre-segregated weights, caller's workspace, three
+    rotating buffer sets for the forward pass) and the buffers it needs, kept alive by the closure."""
+    dt = {"f32": kst.KST_F32, "bf16": kst.KST_BF16, "f16": kst.KST_F16}[layer.dtype]
+    x, w = wl.make_tensors(layer)
+    xd = [x.cuda().clone() for _ in range(3)]
+    wd = w.cuda()
+    if what == "forward":
+        outs = [torch.empty(layer.out_shape, dtype=torch.float32, device="cuda") for _ in range(3)]
+        w_seg = kst.kst_segregate_weights(wd)
+        need = kst.kst_workspace_bytes_padded(layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        return lambda i: kst.kst_forward_seg_padded(xd[i % 3], w_seg, layer.Cout, layer.n, layer.P, out=outs[i % 3], ws=ws)
+    g = torch.randn(layer.out_shape, dtype=torch.float32, device="cuda")
+    if what == "backward_input":
+        din = torch.empty(layer.in_shape, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(kst.kst_backward_input_workspace_bytes(
+            layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt), 16), dtype=torch.uint8, device="cuda")
+        return lambda i: kst.kst_backward_input(g, wd, layer.N, layer.P, din=din, ws=ws)
+    dw = torch.empty(layer.w_shape, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(kst.kst_backward_weight_workspace_bytes(
+        layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, dt), 16), dtype=torch.uint8, device="cuda")
+    return lambda i: kst.kst_backward_weight(xd[0], g, layer.n, layer.P, dw=dw, ws=ws)
+
+
+def measured_traffic():
+    """HBM bytes per forward launch of each layer, read from the committed counter summary
+    (profiles/hbm_traffic_pmc.txt: table rows `layer | kernel | ... | HBM bytes | ...`; a layer's
+    kernels add up).  Measurements of an earlier run of these kernels, quoted beside the live timing."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) >= 6 and cells[0].startswith(("cfg", "table")) and cells[4].isdigit():
+                    out[cells[0]] = out.get(cells[0], 0) + int(cells[4])
+    except OSError:
+        pass
+    return out
 
 
 def roofline_for(layer, ms, metrics):
@@ -181,6 +216,7 @@ def main():
         sys.exit("bench.py needs a GPU")
     kst.lib()   # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    MEASURED_TRAFFIC_BYTES.update(measured_traffic())
 
     def fwd_seg(r):
         L = r.layer
@@ -206,10 +242,13 @@ def main():
         return
     if args.only:
         layer = wl.layer_by_name(args.only)
-        r = Resident(layer, 3, torch, kst, wl)
-        kst.kst_segregate_weights(r.w, r.w_seg)
-        ms = time_launches(torch, fwd_seg(r), args.steps, args.warmup)
-        print(json.dumps({"layer": layer.name, "kernel_ms": ms, "roofline": roofline_for(layer, ms, metrics)}))
+        fn = one_pass(layer, args.what, torch, kst, wl)
+        settle(torch, fn, 0.05)
+        ms = time_launches(torch, fn, args.steps, args.warmup)
+        line = {"layer": layer.name, "pass": args.what, "kernel_ms": ms}
+        if args.what == "forward" and layer.P == 0:
+            line["roofline"] = roofline_for(layer, ms, metrics)
+        print(json.dumps(line))
         return
 
     # ---- headline: whole path on the bandwidth-bound single-channel layer ----------------

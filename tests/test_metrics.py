@@ -59,3 +59,24 @@ def test_workloads_are_seeded_and_bf16_is_rounded_once():
     x64 = wl.to_f64(x1)
     assert x64.dtype == np.float64
     assert np.array_equal(x64.astype(np.float32).astype(np.float64), x64)
+
+
+def test_bench_reads_traffic_from_the_committed_counter_summary():
+    """bench.py's roofline.traffic comes from profiles/hbm_traffic_pmc.txt, not from constants in
+    the script: the four benchmark layers with a counter measurement are found there, and each
+    figure lies between the layer's algorithmic bytes and ten times that."""
+    import bench
+    from paper_2209_03704_amd import metrics, workloads as wl
+    traffic = bench.measured_traffic()
+    for name in ("cfg2_1ch_bandwidth", "cfg3_gan_n4", "cfg4_deep_n5", "cfg5_late_bf16"):
+        alg = metrics.algorithmic_bytes(wl.layer_by_name(name))
+        assert alg <= traffic[name] <= 10 * alg, name
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
