@@ -338,7 +338,7 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     }
     f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
     // The multi-channel direct kernel supplies the zero frame itself: no framed copy at all.
-    if (f->chosen == KST_PATH_DIRECT && direct_takes_virtual_frame(f->s, dt)) {
+    if (f->chosen == KST_PATH_DIRECT && direct_takes_virtual_frame(f->s, f->q, dt)) {
         f->s.frame = f->q;
         f->in_bytes = 0;
     }

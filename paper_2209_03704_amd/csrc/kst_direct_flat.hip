@@ -34,6 +34,13 @@
 // host-computed steps with carries instead of divisions, and a wave whose 256
 // floats lie in one row, or cross exactly one row end, runs code specialised
 // by scalar (r, par) with LDS addresses of the form scalar base + 2 * lane.
+//
+// The same kernel serves the three-channel image layers of Tables 1-2 (CI = 3 input channels, one
+// output channel or a few) and padded layers (FRAME): a piece then stages its rows of every
+// input channel, a lane adds the channels' contributions to its four outputs, and the zero
+// frame of a padded layer exists in LDS only -- frame columns are cells that are cleared once
+// and never written, frame rows are cleared when a piece at the top or bottom of a plane needs
+// them -- so no framed copy of the input is made.
 #include "kst_direct_flat.h"
 
 namespace kst {
@@ -50,10 +57,11 @@ __device__ __forceinline__ void flat_epilogue(float (&o)[4], bool on, float bias
 
 constexpr int F_PAD = 4;      // slack floats left and right of each staged input row
 constexpr int F_THREADS = 512;
-constexpr int F_NPRE = 1024 / F_THREADS;      // float4 loads in flight per lane (1024 per piece at most)
+// float4 loads in flight per lane: a piece's input is at most 1024 float4 with one input channel,
+// 3072 with several.
+__host__ __device__ constexpr int flat_npre(int CI) { return CI == 1 ? 2 : 6; }
 constexpr int F_STEP = 4 * F_THREADS;         // floats the workgroup covers per iteration
-constexpr int F_STEP_LOG2 = F_THREADS == 512 ? 11 : 10;
-static_assert(F_THREADS == 256 || F_THREADS == 512, "two or four float4 per lane");
+constexpr int F_STEP_LOG2 = 11;
 
 // Flat output indices fit 32 bits: the ABI keeps every tensor below 2^31 elements.
 struct Piece {
@@ -63,10 +71,12 @@ struct Piece {
     int plane;
     int ya, xa;               // row / column of fa inside the plane
     int yb;                   // last output row touched
-    int ia;                   // first input row staged
+    int ia;                   // first input row staged (a row of the framed map, if there is a frame)
     int rows_in;              // input rows staged
+    int top;                  // of those, frame rows above the first row that exists in memory
+    int rows_real;            // rows that exist in memory
     int full;                 // covers its whole block: fa = j*CH, fb = fa + CH
-    const float *src;         // in + first staged row
+    const float *src;         // channel 0 of the batch item, first staged row that exists in memory
 };
 
 // Position (plane, row, column) of the first float of block j.
@@ -75,6 +85,7 @@ struct BlockPos {
     int plane, y, x;
 };
 
+template <bool FRAME>
 __device__ __forceinline__ void finish_piece(const FlatParams &p, const float *__restrict__ in, Piece &pc)
 {
     const unsigned block_end = min((pc.j + 1) * p.CH, p.total);
@@ -89,11 +100,25 @@ __device__ __forceinline__ void finish_piece(const FlatParams &p, const float *_
     pc.ia = pc.ya >> 1;
     const int ib = min(p.N - 1, (pc.yb >> 1) + p.fl);
     pc.rows_in = ib - pc.ia + 1;
-    // Cin == 1: plane -> batch item.  32-bit offsets: the input has fewer than 2^31 elements.
+    // plane -> batch item.  32-bit offsets: the input has fewer than 2^31 elements.
     const unsigned b = p.Cout == 1 ? (unsigned)pc.plane : (unsigned)pc.plane / (unsigned)p.Cout;
-    pc.src = in + (b * (unsigned)p.N + (unsigned)pc.ia) * (unsigned)p.N;
+    if constexpr (FRAME) {
+        // The staged rows in the coordinates of the tensor in memory: lo .. hi, of which only
+        // those inside 0 .. N0 - 1 exist (possibly none, for a piece inside the frame).
+        const int lo = pc.ia - p.q, hi = ib - p.q;
+        const int first = max(lo, 0), last = min(hi, p.N0 - 1);
+        pc.top = min(pc.rows_in, max(-lo, 0));
+        pc.rows_real = max(last - first + 1, 0);
+        const int ra = min(first, p.N0 - 1);                     // a row that exists, whatever the piece
+        pc.src = in + (b * (unsigned)p.Cin * (unsigned)p.N0 + (unsigned)ra) * (unsigned)p.N0;
+    } else {
+        pc.top = 0;
+        pc.rows_real = pc.rows_in;
+        pc.src = in + (b * (unsigned)p.Cin * (unsigned)p.N + (unsigned)pc.ia) * (unsigned)p.N;
+    }
 }
 
+template <bool FRAME>
 __device__ __forceinline__ void first_piece(const FlatParams &p, const float *__restrict__ in, const BlockPos &bp, Piece &pc)
 {
     pc.j = bp.j;
@@ -101,11 +126,12 @@ __device__ __forceinline__ void first_piece(const FlatParams &p, const float *__
     pc.plane = bp.plane;
     pc.ya = bp.y;
     pc.xa = bp.x;
-    finish_piece(p, in, pc);
+    finish_piece<FRAME>(p, in, pc);
 }
 
 // One aligned group in output row parity r whose first column has parity par.
-template <int n, int r, int par>
+// ADD: add to o instead of setting it (the second and further input channels).
+template <int n, int r, int par, bool ADD = false>
 __device__ __forceinline__ void flat_group(float (&o)[4], const float *__restrict__ rowp, int xs_stride, int cbase,
                                            const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
 {
@@ -122,7 +148,7 @@ __device__ __forceinline__ void flat_group(float (&o)[4], const float *__restric
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int Tb = s_k[k] ? Tb1 : Tb0;
-        float acc = 0.0f;
+        float acc = ADD ? o[k] : 0.0f;
 #pragma unroll
         for (int a = 0; a < Ta; ++a)
 #pragma unroll
@@ -131,77 +157,104 @@ __device__ __forceinline__ void flat_group(float (&o)[4], const float *__restric
     }
 }
 
-// Outputs of the group at (row y, first column x0), x0 in [-3, M).
-template <int n>
-__device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int ia,
-                                               int y, int x0,
-                                               const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
+// The same group summed over the CI staged input channels (chan: floats between two channels' rows in LDS).
+template <int n, int r, int par, int CI>
+__device__ __forceinline__ void flat_group_ci(float (&o)[4], const float *__restrict__ rowp, int xs_stride, int chan,
+                                              int cbase, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
 {
-    const int r = y & 1;
-    const float *rowp = Xs + ((y >> 1) - ia + r) * p.xs_stride + F_PAD;
+    flat_group<n, r, par, false>(o, rowp, xs_stride, cbase, wk[0]);
+#pragma unroll
+    for (int c = 1; c < CI; ++c) flat_group<n, r, par, true>(o, rowp + c * chan, xs_stride, cbase, wk[c]);
+}
+
+// (r, par) selected at run time; rowp points at the group's first tap row, column 0 of the map.
+template <int n, int CI>
+__device__ __forceinline__ void flat_group_rp(float (&o)[4], const float *__restrict__ rowp, const FlatParams &p, int r,
+                                              int x0, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
+{
     if (x0 & 1) {
         const int cbase = ((x0 - 1) >> 1) + 1;
-        if (r) flat_group<n, 1, 1>(o, rowp, p.xs_stride, cbase, wk);
-        else flat_group<n, 0, 1>(o, rowp, p.xs_stride, cbase, wk);
+        if (r) flat_group_ci<n, 1, 1, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
+        else flat_group_ci<n, 0, 1, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
     } else {
         const int cbase = x0 >> 1;
-        if (r) flat_group<n, 1, 0>(o, rowp, p.xs_stride, cbase, wk);
-        else flat_group<n, 0, 0>(o, rowp, p.xs_stride, cbase, wk);
+        if (r) flat_group_ci<n, 1, 0, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
+        else flat_group_ci<n, 0, 0, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
     }
+}
+
+// Outputs of the group at (row y, first column x0), x0 in [-3, M).  pad0: LDS column of the map's column 0.
+template <int n, int CI>
+__device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
+                                               int ia, int y, int x0,
+                                               const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
+{
+    const int r = y & 1;
+    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0, p, r, x0, wk);
 }
 
 // Segment = the 256 consecutive floats one wave covers in one iteration; it starts at
 // (row y, column xs) and crosses exactly one row end.  Lanes left of the row end compute
 // their group in row y, lanes right of it in row y + 1, the lane on it both.
-template <int n>
-__device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int ia,
-                                              int y, int xs, int lane,
-                                              const float (&wk)[2][2][((n + 1) / 2) * ((n + 1) / 2)])
+template <int n, int CI>
+__device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
+                                              int ia, int y, int xs, int lane,
+                                              const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
 {
     const int x0 = xs + 4 * lane;
     float oa[4] = {0.f, 0.f, 0.f, 0.f}, ob[4] = {0.f, 0.f, 0.f, 0.f};
     if (x0 < p.M) {
         const int r = y & 1;
-        const float *rowp = Xs + ((y >> 1) - ia + r) * p.xs_stride + F_PAD + 2 * lane;
-        if (xs & 1) {
-            const int cbase = ((xs - 1) >> 1) + 1;
-            if (r) flat_group<n, 1, 1>(oa, rowp, p.xs_stride, cbase, wk);
-            else flat_group<n, 0, 1>(oa, rowp, p.xs_stride, cbase, wk);
-        } else {
-            const int cbase = xs >> 1;
-            if (r) flat_group<n, 1, 0>(oa, rowp, p.xs_stride, cbase, wk);
-            else flat_group<n, 0, 0>(oa, rowp, p.xs_stride, cbase, wk);
-        }
+        flat_group_rp<n, CI>(oa, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs, wk);
     }
     if (x0 + 3 >= p.M) {
         const int y1 = y + 1, xs1 = xs - p.M;                        // negative column: head of the next row
         const int r = y1 & 1;
-        const float *rowp = Xs + ((y1 >> 1) - ia + r) * p.xs_stride + F_PAD + 2 * lane;
-        if (xs1 & 1) {
-            const int cbase = ((xs1 - 1) >> 1) + 1;
-            if (r) flat_group<n, 1, 1>(ob, rowp, p.xs_stride, cbase, wk);
-            else flat_group<n, 0, 1>(ob, rowp, p.xs_stride, cbase, wk);
-        } else {
-            const int cbase = xs1 >> 1;
-            if (r) flat_group<n, 1, 0>(ob, rowp, p.xs_stride, cbase, wk);
-            else flat_group<n, 0, 0>(ob, rowp, p.xs_stride, cbase, wk);
-        }
+        flat_group_rp<n, CI>(ob, Xs + ((y1 >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs1, wk);
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) o[k] = x0 + k < p.M ? oa[k] : ob[k];
 }
 
-template <int n>
+// Sub-kernel (r, s) of input channel c and output channel co, from the segregated weights [class][Cin][tap][Cout].
+template <int n, int r, int s>
+__device__ __forceinline__ void flat_load_class(float (&w)[((n + 1) / 2) * ((n + 1) / 2)], const float *__restrict__ w_seg,
+                                                unsigned off, int c, int co, int Cout)
+{
+    constexpr int T = (r ? n / 2 : (n + 1) / 2) * (s ? n / 2 : (n + 1) / 2);
+#pragma unroll
+    for (int t = 0; t < T; ++t) w[t] = w_seg[off + (unsigned)((c * T + t) * Cout + co)];
+}
+
+// Rows of the zero frame above or below the rows a piece finds in memory (pieces at the top and
+// bottom of a plane only): cleared over the map's width in every channel.
+template <int CI>
+__device__ __forceinline__ void clear_frame_rows(float *X, const FlatParams &p, int pad0, int tid, int top, int rows_real,
+                                                 int rows_in)
+{
+    const int nz = rows_in - rows_real;                          // top + below
+    if (nz == 0) return;                                         // uniform
+    for (int e = tid; e < CI * nz * p.N; e += F_THREADS) {
+        const int rc = e / p.N, col = e - rc * p.N;
+        const int c = rc / nz, z = rc - c * nz;
+        const int row = z < top ? z : rows_real + z;             // below the real rows: top + rows_real + (z - top)
+        X[c * p.chan_lds + row * p.xs_stride + pad0 + col] = 0.0f;
+    }
+}
+
+template <int n, int CI, bool FRAME>
 __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ w_seg,
                                                                   float *__restrict__ out, FlatParams p)
 {
     constexpr int Ta0 = (n + 1) / 2, Ta1 = n / 2;
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 x [max_rows][xs_stride]
+    constexpr int NPRE = flat_npre(CI);
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 x [CI][max_rows][xs_stride]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n4 = p.N >> 2;
+    const int n4 = (FRAME ? p.N0 : p.N) >> 2;                     // float4 per row of the tensor in memory
+    const int pad0 = FRAME ? p.pad0 : F_PAD;                      // LDS column of the (framed) map's column 0
 
     // This workgroup's blocks: blockIdx.x, + gridDim.x, ...  The position of the first one costs
     // the only divisions of the common path; later ones are reached by adding the grid step.
@@ -227,33 +280,51 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     // Row / column offset of this wave's 256 floats inside an iteration.
     const int w_y = (wave * 256) / p.M, w_x = wave * 256 - w_y * p.M;
 
-    // Where float4 number k * threads + tid of a staged run lands in an LDS buffer (same for every piece).
-    int lds_off[F_NPRE];
+    // float4 number e = k * threads + tid of a staged piece is (row rr, channel c, group x4) with
+    // e = (rr * CI + c) * n4 + x4, the same for every piece: where it comes from, relative to the
+    // piece's first row of channel 0, and where it lands in an LDS buffer.
+    int lds_off[NPRE], src_off[NPRE], row_of[NPRE];
 #pragma unroll
-    for (int k = 0; k < F_NPRE; ++k) {
+    for (int k = 0; k < NPRE; ++k) {
         const int e = k * F_THREADS + tid;
-        const int rr = e / n4, x4 = e - rr * n4;
-        lds_off[k] = rr * p.xs_stride + F_PAD + 4 * x4;
+        const int rc = e / n4, x4 = e - rc * n4;
+        const int rr = rc / CI, c = rc - rr * CI;
+        row_of[k] = rr;
+        lds_off[k] = c * p.chan_lds + rr * p.xs_stride + pad0 + (FRAME ? p.q : 0) + 4 * x4;
+        src_off[k] = c * (int)p.chan_in + rr * (FRAME ? p.N0 : p.N) + 4 * x4;
+    }
+
+    if constexpr (FRAME) {
+        // The frame columns and the slack of every staged row are cells nobody writes: clear them
+        // (and everything else) once.
+        for (int e = tid; e < 2 * p.xs_buf; e += F_THREADS) lds[e] = 0.0f;
+        __syncthreads();
     }
 
     Piece pc;
-    first_piece(p, in, bp, pc);
+    first_piece<FRAME>(p, in, bp, pc);
     // First piece: plain staging (all loads issued before the first LDS write).
     {
-        const float4 *s4 = reinterpret_cast<const float4 *>(pc.src);
-        const int count4 = pc.rows_in * n4;
-        const float4 t0 = s4[min(tid, count4 - 1)];
-        const float4 t1 = s4[min(F_THREADS + tid, count4 - 1)];
-        const float4 t2 = F_NPRE > 2 ? s4[min(2 * F_THREADS + tid, count4 - 1)] : t0;
-        const float4 t3 = F_NPRE > 2 ? s4[min(3 * F_THREADS + tid, count4 - 1)] : t0;
-        const float4 t[4] = {t0, t1, t2, t3};
+        // (named values, gathered into an array only where they are consumed: an array that lives
+        // across the loads is kept in memory by the compiler)
+        auto fetch = [&](int k) {                                // k < NPRE, constant after inlining
+            return *reinterpret_cast<const float4 *>(pc.src + (row_of[k] < pc.rows_real ? src_off[k] : 0));
+        };
+        const float4 t0 = fetch(0), t1 = fetch(1);
+        const float4 t2 = NPRE > 2 ? fetch(NPRE > 2 ? 2 : 0) : t0, t3 = NPRE > 3 ? fetch(NPRE > 3 ? 3 : 0) : t0;
+        const float4 t4 = NPRE > 4 ? fetch(NPRE > 4 ? 4 : 0) : t0, t5 = NPRE > 5 ? fetch(NPRE > 5 ? 5 : 0) : t0;
+        const float4 t[6] = {t0, t1, t2, t3, t4, t5};
+        if constexpr (FRAME) clear_frame_rows<CI>(lds, p, pad0, tid, pc.top, pc.rows_real, pc.rows_in);
 #pragma unroll
-        for (int k = 0; k < F_NPRE; ++k)
-            if (k * F_THREADS + tid < count4) *reinterpret_cast<float4 *>(lds + lds_off[k]) = t[k];
+        for (int k = 0; k < NPRE; ++k)
+            if (row_of[k] < pc.rows_real) {
+                float *d = lds + lds_off[k] + (FRAME ? pc.top * p.xs_stride : 0);
+                *reinterpret_cast<float4 *>(d) = t[k];          // pad0 + q is a multiple of 4: 16-byte aligned
+            }
     }
     __syncthreads();
 
-    float wk[2][2][Ta0 * Ta0];
+    float wk[CI][2][2][Ta0 * Ta0];
     int cur_co = -1;
     const bool epi = epi_on(p.epi);
     float bias = 0.0f;
@@ -268,7 +339,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
             pn.plane = pc.plane + 1;
             pn.ya = 0;
             pn.xa = 0;
-            finish_piece(p, in, pn);
+            finish_piece<FRAME>(p, in, pn);
         } else {
             bp.j += gridDim.x;
             bp.plane += p.g_plane;
@@ -276,28 +347,26 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
             bp.x += p.g_x;
             if (bp.x >= p.M) { bp.x -= p.M; ++bp.y; }
             if (bp.y >= p.M) { bp.y -= p.M; ++bp.plane; }
-            if (bp.j < p.nblocks) first_piece(p, in, bp, pn);
+            if (bp.j < p.nblocks) first_piece<FRAME>(p, in, bp, pn);
             else more = false;
         }
-        const int count4n = pn.rows_in * n4;
-        const float4 *s4 = reinterpret_cast<const float4 *>(pn.src);
-        const float4 pre0 = s4[min(tid, count4n - 1)];
-        const float4 pre1 = s4[min(F_THREADS + tid, count4n - 1)];
-        const float4 pre2 = F_NPRE > 2 ? s4[min(2 * F_THREADS + tid, count4n - 1)] : pre0;
-        const float4 pre3 = F_NPRE > 2 ? s4[min(3 * F_THREADS + tid, count4n - 1)] : pre0;
+        auto fetch = [&](int k) {                                // k < NPRE, constant after inlining
+            return *reinterpret_cast<const float4 *>(pn.src + (row_of[k] < pn.rows_real ? src_off[k] : 0));
+        };
+        const float4 pre0 = fetch(0), pre1 = fetch(1);
+        const float4 pre2 = NPRE > 2 ? fetch(NPRE > 2 ? 2 : 0) : pre0, pre3 = NPRE > 3 ? fetch(NPRE > 3 ? 3 : 0) : pre0;
+        const float4 pre4 = NPRE > 4 ? fetch(NPRE > 4 ? 4 : 0) : pre0, pre5 = NPRE > 5 ? fetch(NPRE > 5 ? 5 : 0) : pre0;
 
         // ---- weights of this plane's output channel (scalar registers) ----------------------
         const int co = p.Cout == 1 ? 0 : (int)((unsigned)pc.plane % (unsigned)p.Cout);
         if (co != cur_co) {
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int Ta = r ? Ta1 : Ta0, Tb = s ? Ta1 : Ta0;
-#pragma unroll
-                    for (int t = 0; t < Ta * Tb; ++t)
-                        wk[r][s][t] = w_seg[p.off[2 * r + s] + (unsigned)(t * p.Cout + co)];   // Cin == 1
-                }
+            for (int c = 0; c < CI; ++c) {
+                flat_load_class<n, 0, 0>(wk[c][0][0], w_seg, p.off[0], c, co, p.Cout);
+                flat_load_class<n, 0, 1>(wk[c][0][1], w_seg, p.off[1], c, co, p.Cout);
+                flat_load_class<n, 1, 0>(wk[c][1][0], w_seg, p.off[2], c, co, p.Cout);
+                flat_load_class<n, 1, 1>(wk[c][1][1], w_seg, p.off[3], c, co, p.Cout);
+            }
             if (epi) bias = epi_bias(p.epi, co);
             cur_co = co;
         }
@@ -315,18 +384,9 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                 float o[4];
                 if (xs + 255 < p.M) {
                     const int r = y & 1;
-                    const float *rowp = Xs + ((y >> 1) - pc.ia + r) * p.xs_stride + F_PAD + 2 * lane;
-                    if (xs & 1) {
-                        const int cbase = ((xs - 1) >> 1) + 1;
-                        if (r) flat_group<n, 1, 1>(o, rowp, p.xs_stride, cbase, wk);
-                        else flat_group<n, 0, 1>(o, rowp, p.xs_stride, cbase, wk);
-                    } else {
-                        const int cbase = xs >> 1;
-                        if (r) flat_group<n, 1, 0>(o, rowp, p.xs_stride, cbase, wk);
-                        else flat_group<n, 0, 0>(o, rowp, p.xs_stride, cbase, wk);
-                    }
+                    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - pc.ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs, wk);
                 } else {
-                    cross_segment<n>(o, Xs, p, pc.ia, y, xs, lane, wk);
+                    cross_segment<n, CI>(o, Xs, p, pad0, pc.ia, y, xs, lane, wk);
                 }
                 flat_epilogue(o, epi, bias, p.epi.act);
                 store_streaming(out + fw + 4 * lane, o);
@@ -354,10 +414,10 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     // A group hanging over the start of the plane is the head of row 0 (negative column).
                     const int yy = y < 0 ? 0 : y, xx = y < 0 ? x0 - p.M : x0;
                     float o[4];
-                    flat_row_group<n>(o, Xs, p, pc.ia, yy, xx, wk);
+                    flat_row_group<n, CI>(o, Xs, p, pad0, pc.ia, yy, xx, wk);
                     if (xx + 3 >= p.M && yy + 1 <= pc.yb) {      // straddles a row end: head of the next row
                         float o2[4];
-                        flat_row_group<n>(o2, Xs, p, pc.ia, yy + 1, xx - p.M, wk);
+                        flat_row_group<n, CI>(o2, Xs, p, pad0, pc.ia, yy + 1, xx - p.M, wk);
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             if (xx + k >= p.M) o[k] = o2[k];
@@ -382,51 +442,97 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
 
         // ---- land the prefetched rows in the other buffer -----------------------------------
         float *Xn = lds + (buf ^ 1) * p.xs_buf;
-        const float4 pre[4] = {pre0, pre1, pre2, pre3};
+        if constexpr (FRAME) clear_frame_rows<CI>(Xn, p, pad0, tid, pn.top, pn.rows_real, pn.rows_in);
+        const float4 pre[6] = {pre0, pre1, pre2, pre3, pre4, pre5};
 #pragma unroll
-        for (int k = 0; k < F_NPRE; ++k)
-            if (k * F_THREADS + tid < count4n) *reinterpret_cast<float4 *>(Xn + lds_off[k]) = pre[k];
+        for (int k = 0; k < NPRE; ++k)
+            if (row_of[k] < pn.rows_real) {
+                float *d = Xn + lds_off[k] + (FRAME ? pn.top * p.xs_stride : 0);
+                *reinterpret_cast<float4 *>(d) = pre[k];
+            }
         __syncthreads();
         pc = pn;
         buf ^= 1;
     }
 }
 
+template <int n, int CI, bool FRAME>
+hipError_t launch_kernel(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
+                         hipStream_t stream)
+{
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_flat_kernel<n, CI, FRAME>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((direct_flat_kernel<n, CI, FRAME>), dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
+    return hipGetLastError();
+}
+
+// One input channel with or without a frame, three (the image layers of Tables 1-2) likewise.
 template <int n>
 hipError_t launch_n(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
                     hipStream_t stream)
 {
-    hipLaunchKernelGGL(direct_flat_kernel<n>, dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
-    return hipGetLastError();
+    if (p.q == 0) {
+        if (p.Cin == 1) return launch_kernel<n, 1, false>(in, w_seg, out, p, grid, lds, stream);
+        if (p.Cin == 3) return launch_kernel<n, 3, false>(in, w_seg, out, p, grid, lds, stream);
+    } else if constexpr (n >= 2) {
+        if (p.Cin == 1) return launch_kernel<n, 1, true>(in, w_seg, out, p, grid, lds, stream);
+        if (p.Cin == 3) return launch_kernel<n, 3, true>(in, w_seg, out, p, grid, lds, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
 
+// s.N is the edge of the map the kernel sees (with the frame, if s.frame > 0); s.frame > 0 means
+// the tensor in memory is the dense unframed one and the kernel supplies the frame.
 bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &grid, size_t &lds)
 {
-    if (dt != KST_F32 || s.Cin != 1 || s.n > 7 || (s.N & 3) != 0) return false;
-    const unsigned CH = 8192;
+    const int q = s.frame, N0 = s.N - 2 * q;
+    if (dt != KST_F32 || (s.Cin != 1 && s.Cin != 3) || s.n > 7 || N0 < 4 || (N0 & 3) != 0 || s.Ns != s.N) return false;
+    if (q < 0 || q > 4 || (q > 0 && s.n < 2)) return false;
+    const int npre = flat_npre(s.Cin);
     const long long MM = (long long)s.M * s.M;
+    // Blocks of 8192 outputs; of 4096 where three channels' rows for 8192 do not fit the prefetch
+    // registers and two workgroups' LDS buffers (narrow blocks re-read more halo rows).
+    unsigned CH = 8192;
+    if (s.Cin > 1) {
+        const int rows = (int)((CH - 1 + s.M - 1) / s.M) / 2 + 1 + s.fl + 1;
+        const size_t stride = (size_t)((8 + s.N + F_PAD + 3) & ~3);
+        if ((size_t)s.Cin * rows * N0 > (size_t)F_THREADS * npre * 4 || 2 * 2 * s.Cin * rows * stride * sizeof(float) > 160 * 1024)
+            CH = 4096;
+    }
     if (MM < CH || s.M < 8) return false;                       // a block may touch at most two planes
-    p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.fl = s.fl;
+    p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.fl = s.fl;
+    p.q = q; p.N0 = N0;
+    p.pad0 = q > 0 ? 8 - q : F_PAD;                             // the tensor's column 0 lands on LDS column 8 (or 4)
     p.CH = CH;
     p.MM = (unsigned)MM;
     p.total = (unsigned)((long long)s.B * s.Cout * MM);
     p.nblocks = (p.total + CH - 1) / CH;
+    // Three channels: only where every workgroup walks over several blocks.  Below that the many small
+    // workgroups of the multi-channel kernel finish sooner (16 images of 224 x 224: 10 us against 12).
+    if (s.Cin > 1 && p.nblocks < 1024) return false;
     p.fast = s.M >= 256;
     // Input rows one piece can need: the rows its output span maps to, plus halo.
     const int span = (int)((CH - 1 + s.M - 1) / s.M);           // yb - ya at most
     p.max_rows = span / 2 + 1 + s.fl + 1;
     if (p.max_rows > s.N) p.max_rows = s.N;
-    if ((size_t)p.max_rows * s.N > (size_t)F_THREADS * F_NPRE * 4) return false;   // prefetch registers
-    p.xs_stride = s.N + 2 * F_PAD;
-    p.xs_buf = p.max_rows * p.xs_stride;
+    if ((size_t)s.Cin * p.max_rows * N0 > (size_t)F_THREADS * npre * 4) return false;   // prefetch registers
+    p.xs_stride = (p.pad0 + s.N + F_PAD + 3) & ~3;
+    p.chan_lds = p.max_rows * p.xs_stride;
+    p.chan_in = (unsigned)N0 * (unsigned)N0;
+    p.xs_buf = s.Cin * p.chan_lds;
     lds = (size_t)2 * p.xs_buf * sizeof(float);
-    if (lds > 64 * 1024) return false;
-    for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(1, s.Cout, s.n, c, KST_F32);
+    for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_F32);
     p.epi = s.epi;
-    // One resident round: three 512-lane workgroups per CU on 256 CUs.
-    const int wgs = 768;
+    // One resident round on 256 CUs: three 512-lane workgroups per CU with one input channel, two
+    // with three (their prefetch registers and LDS buffers are twice as large).
+    const int per_cu = s.Cin == 1 ? 3 : 2;
+    if (lds * per_cu > 160 * 1024) return false;
+    const int wgs = 256 * per_cu;
     grid = (unsigned)wgs;
     if (grid > p.nblocks) grid = p.nblocks;
     p.run = grid % 64 == 0 ? 8 : 1;                             // 1: plain blockIdx order

@@ -158,8 +158,9 @@ hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *
 // Direct kernel for several input channels (one lane per quad and output channel, input staged
 // in LDS by channel chunks); dense rows only.
 bool direct_multi_supported(const Shape &s);
-// True when the direct path on this shape reads a padded layer's input in place (Shape::frame).
-bool direct_takes_virtual_frame(const Shape &s, kst_dtype dt);
+// True when the direct path reads a padded layer's input in place: s is the framed problem (s.N
+// includes the frame of q zeros per side), the kernel is then given Shape::frame = q and the dense tensor.
+bool direct_takes_virtual_frame(const Shape &s, int q, kst_dtype dt);
 hipError_t launch_direct_multi(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                                hipStream_t stream);
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,

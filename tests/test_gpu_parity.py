@@ -265,6 +265,42 @@ def test_direct_single_channel_flat_kernel(B, Cout, N, n):
     assert np.array_equal(res["direct"].astype(np.float64), want)
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    # (three channels take this kernel from 1024 blocks of 8192 outputs on: hence the batch sizes)
+    (520, 3, 1, 64, 3, 2),    # Table 1's channel counts at a small map: frame of one, M = 129
+    (61, 3, 2, 132, 5, 2),    # M = 263: the path for maps wider than a wave's 256 floats; two output channels
+    (42, 3, 1, 224, 4, 2),    # Table 1's map, even kernel
+    (1000, 3, 1, 48, 3, 0),   # three channels without a frame; M * M just above one block
+    (253, 3, 2, 64, 7, 4),    # frame of two, largest kernel
+    (380, 3, 1, 72, 2, 3),    # odd padding factor: frame of two, interior copied out
+    (2, 3, 1, 64, 3, 2),      # too few blocks: the multi-channel kernel
+    (2, 1, 2, 64, 5, 2),      # one input channel with a frame (no framed copy of the input any more)
+    (1, 1, 1, 512, 5, 2),     # the headline layer's map with a frame
+    (2, 1, 3, 100, 3, 8),     # frame of four (the widest the kernel supplies)
+    (1, 1, 1, 60, 6, 3),
+    (1, 3, 1, 40, 5, 6),      # frame of three: pieces that lie entirely inside the frame rows
+    (2, 3, 1, 32, 3, 10),     # frame of five: beyond the flat kernel, the multi-channel kernel takes it
+])
+def test_direct_flat_kernel_with_channels_and_frame(B, Cin, Cout, N, n, P):
+    """The flat-output kernel on three input channels (the image layers of Tables 1-2) and on padded
+    layers, whose zero frame it keeps in LDS: against the oracle, bit for bit on integers, with guard
+    words around `out`, and reproducibly."""
+    layer = wl.Layer("flat_ci", B, Cin, Cout, N, n, "f32", "normal", w_std=0.3)
+    x, w = wl.make_tensors(layer, 800 + N + 7 * n + P)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    got = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_DIRECT)
+    again = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_DIRECT)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    e = rel_err(got.cpu().numpy(), want)
+    assert e <= TOL["f32"], "rel err %.3e" % e
+    check_exact_with_guards(wl.Layer("flat_ci_int", B, Cin, Cout, N, n, "f32", "integer"), kst.KST_PATH_DIRECT,
+                            900 + N + n, P=P)
+    if P % 2 == 0 and P // 2 <= 4:
+        assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_DIRECT) == 0
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Cin,Cout,N,n", [
     (5, 20, 150, 12, 4),    # 2 channel tiles (ragged), tiles straddle batch items
