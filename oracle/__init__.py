@@ -35,6 +35,16 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitize_check(exe_path: str, sanitize: bool = True) -> str:
+    """Compile sanitize_check.c together with the oracle into an executable: with the address and
+    undefined-behaviour sanitizers (the test-suite runs that one), or plainly (the build check)."""
+    flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+             "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+    subprocess.run(["gcc", "-std=c11", "-fopenmp", "-Wall", "-Wextra"] + flags +
+                   ["-o", exe_path, os.path.join(_HERE, "sanitize_check.c"), _SRC, "-lm"], check=True)
+    return exe_path
+
+
 def _load():
     global _lib
     with _lock:

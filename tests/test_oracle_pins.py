@@ -593,3 +593,17 @@ def test_epilogue_rejects_an_unknown_activation_and_a_wrong_bias_length():
         oracle.forward_epilogue(x, w, None, 3)
     with pytest.raises(ValueError):
         oracle.forward_epilogue(x, w, [1.0], oracle.ACT_RELU)
+
+
+# ----------------------------------------------------------------------------
+# 12. The oracle under the address and undefined-behaviour sanitizers
+# ----------------------------------------------------------------------------
+def test_oracle_is_clean_under_sanitizers(tmp_path):
+    """oracle/sanitize_check.c drives every oracle function over ordinary and edge shapes; built
+    with -fsanitize=address,undefined any index outside a buffer or any undefined arithmetic
+    ends the run with a report instead of "ok"."""
+    import subprocess
+    exe = oracle.build_sanitize_check(str(tmp_path / "oracle_san"))
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=0", OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", r.stdout + r.stderr
