@@ -190,16 +190,19 @@ kst_status kst_forward(const void *in, const void *w, void *out,
  * the output edge is kst_out_size_padded(N, n, P) = 2N + 2P - n (it must be
  * >= 1; P = 0 is the unframed operation above).  The segregated method moves the
  * frame to the ORIGINAL input with the reduced factor floor(P / 2); for odd P the
- * four sub-kernels swap roles (K4, K3, K2, K1).  Here: the input is copied into
- * the workspace framed by ceil(P / 2) zeros and the unframed kernels run on the
- * copy (the direct kernel for several input channels reads the frame as zeros
- * without a copy); for odd P they run into a second workspace buffer one pixel wider on
- * every side, whose interior is then copied to `out` (one extra pass over the
- * output).  Layouts, dtypes, alignment, stream and error behaviour are those of
- * kst_forward_seg / kst_forward; `out` is [B][Cout][2N+2P-n][2N+2P-n] fp32.
- * kst_workspace_bytes_padded returns 0 for an illegal shape or unsupported path,
- * and for layers whose kernel supplies the zero frame itself (the direct path
- * with several input channels at an even P): then ws may be NULL.
+ * four sub-kernels swap roles (K4, K3, K2, K1).  Here the frame is ceil(P / 2)
+ * zeros.  The direct kernels supply it themselves (in LDS, or by predicated
+ * loads) and for odd P write output (y, x) as element (y + 1, x + 1) of the
+ * map the framed input defines, which is that swap of roles: no workspace.
+ * The matrix-core kernels run on a framed copy of the input made in the
+ * workspace; for odd P they run into a second workspace buffer one pixel wider
+ * on every side, whose interior is then copied to `out` (one extra pass over
+ * the output).  Layouts, dtypes, alignment, stream and error behaviour are
+ * those of kst_forward_seg / kst_forward; `out` is [B][Cout][2N+2P-n][2N+2P-n]
+ * fp32.  kst_workspace_bytes_padded returns 0 for an illegal shape or
+ * unsupported path, and for layers whose kernel needs neither copy (the direct
+ * path, frames of up to 4 with one or three input channels, any frame with
+ * several): then ws may be NULL.
  */
 int kst_out_size_padded(int N, int n, int P);
 size_t kst_workspace_bytes_padded(int B, int Cin, int Cout, int N, int n, int P, kst_dtype dtype, kst_path path);

@@ -337,12 +337,22 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
         if (igemm_f32_takes_row_stride(wide)) f->s = wide;
     }
     f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
-    // The multi-channel direct kernel supplies the zero frame itself: no framed copy at all.
-    if (f->chosen == KST_PATH_DIRECT && direct_takes_virtual_frame(f->s, f->q, dt)) {
-        f->s.frame = f->q;
-        f->in_bytes = 0;
-    }
     f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
+    // The direct kernels supply the zero frame themselves: no framed copy at all; and for an odd
+    // padding factor the flat-output kernel writes the interior of the wider map straight to
+    // `out` (output row y is row y + 1 of that map: the row parities, hence the sub-kernels,
+    // swap roles as in Fig. 7): no wider buffer and no copy of its interior either.
+    if (f->chosen == KST_PATH_DIRECT) {
+        if ((P & 1) && direct_takes_virtual_frame(f->s, f->q, 1, dt)) {
+            f->s.frame = f->q;
+            f->s.crop = 1;
+            f->in_bytes = 0;
+            f->wide_bytes = 0;
+        } else if (direct_takes_virtual_frame(f->s, f->q, 0, dt)) {
+            f->s.frame = f->q;
+            f->in_bytes = 0;
+        }
+    }
     return KST_OK;
 }
 

@@ -531,13 +531,14 @@ static hipError_t run(const T *in, const T *w_seg, float *out, const Shape &s, k
     return hipGetLastError();
 }
 
-bool direct_takes_virtual_frame(const Shape &s, int q, kst_dtype dt)
+bool direct_takes_virtual_frame(const Shape &s, int q, int crop, kst_dtype dt)
 {
     FlatParams fp;
     unsigned grid;
     size_t lds;
     Shape framed = s;
     framed.frame = q;
+    framed.crop = crop;
     if (direct_flat_plan(framed, dt, fp, grid, lds)) return true;       // the flat kernel keeps the frame in LDS
     Shape dense = s;
     dense.frame = 0;
@@ -553,7 +554,7 @@ hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Sh
     if (s.frame != 0) {
         if (direct_flat_plan(s, dt, fp, grid, lds))
             return launch_direct_flat((const float *)in, (const float *)w_seg, out, s, fp, grid, lds, stream);
-        if (!direct_takes_virtual_frame(s, s.frame, dt)) return hipErrorInvalidValue;
+        if (!direct_takes_virtual_frame(s, s.frame, s.crop, dt)) return hipErrorInvalidValue;
         return launch_direct_multi(in, w_seg, out, s, dt, stream);
     }
     if (direct_flat_plan(s, dt, fp, grid, lds))

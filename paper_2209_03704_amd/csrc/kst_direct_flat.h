@@ -8,6 +8,7 @@ struct FlatParams {
     int Cin, Cout, N, M, fl;   // N: edge of the map the kernel sees (frame included)
     int q, N0;              // zero frame the kernel supplies, edge of the tensor in memory (N - 2q)
     int pad0;               // LDS column of the map's column 0
+    int sh;                 // 1: output (y, x) is element (y + 1, x + 1) of the map the framed input defines (odd padding factor)
     int chan_lds;           // floats per input channel in an LDS buffer
     unsigned chan_in;       // floats per input channel in memory
     unsigned CH;            // floats per block: workgroups own 1 KB-aligned blocks of the flat output

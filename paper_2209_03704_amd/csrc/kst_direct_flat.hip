@@ -97,8 +97,11 @@ __device__ __forceinline__ void finish_piece(const FlatParams &p, const float *_
     } else {
         pc.yb = (int)((pc.fb - 1 - pc.p0) / (unsigned)p.M);          // rare: blocks at a plane end
     }
-    pc.ia = pc.ya >> 1;
-    const int ib = min(p.N - 1, (pc.yb >> 1) + p.fl);
+    // (sh: with an odd padding factor output row y is row y + 1 of the map one ring wider that the
+    // framed input defines; the same for columns)
+    const int sh = FRAME ? p.sh : 0;
+    pc.ia = (pc.ya + sh) >> 1;
+    const int ib = min(p.N - 1, ((pc.yb + sh) >> 1) + p.fl);
     pc.rows_in = ib - pc.ia + 1;
     // plane -> batch item.  32-bit offsets: the input has fewer than 2^31 elements.
     const unsigned b = p.Cout == 1 ? (unsigned)pc.plane : (unsigned)pc.plane / (unsigned)p.Cout;
@@ -187,10 +190,11 @@ __device__ __forceinline__ void flat_group_rp(float (&o)[4], const float *__rest
 template <int n, int CI>
 __device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
                                                int ia, int y, int x0,
-                                               const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
+                                               const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)], int sh = 0)
 {
+    y += sh;
     const int r = y & 1;
-    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0, p, r, x0, wk);
+    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0, p, r, x0 + sh, wk);
 }
 
 // Segment = the 256 consecutive floats one wave covers in one iteration; it starts at
@@ -199,16 +203,16 @@ __device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__res
 template <int n, int CI>
 __device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
                                               int ia, int y, int xs, int lane,
-                                              const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
+                                              const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)], int sh = 0)
 {
     const int x0 = xs + 4 * lane;
     float oa[4] = {0.f, 0.f, 0.f, 0.f}, ob[4] = {0.f, 0.f, 0.f, 0.f};
     if (x0 < p.M) {
-        const int r = y & 1;
-        flat_group_rp<n, CI>(oa, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs, wk);
+        const int ys = y + sh, r = ys & 1;
+        flat_group_rp<n, CI>(oa, Xs + ((ys >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk);
     }
     if (x0 + 3 >= p.M) {
-        const int y1 = y + 1, xs1 = xs - p.M;                        // negative column: head of the next row
+        const int y1 = y + 1 + sh, xs1 = xs - p.M + sh;              // negative column: head of the next row
         const int r = y1 & 1;
         flat_group_rp<n, CI>(ob, Xs + ((y1 >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs1, wk);
     }
@@ -255,6 +259,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n4 = (FRAME ? p.N0 : p.N) >> 2;                     // float4 per row of the tensor in memory
     const int pad0 = FRAME ? p.pad0 : F_PAD;                      // LDS column of the (framed) map's column 0
+    const int sh = FRAME ? p.sh : 0;                              // odd padding factor: output (y, x) is (y + 1, x + 1) of the framed input's map
 
     // This workgroup's blocks: blockIdx.x, + gridDim.x, ...  The position of the first one costs
     // the only divisions of the common path; later ones are reached by adding the grid step.
@@ -383,10 +388,10 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
             for (int it = 0; it < (int)(p.CH / F_STEP); ++it) {
                 float o[4];
                 if (xs + 255 < p.M) {
-                    const int r = y & 1;
-                    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - pc.ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs, wk);
+                    const int ys = y + sh, r = ys & 1;
+                    flat_group_rp<n, CI>(o, Xs + ((ys >> 1) - pc.ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk);
                 } else {
-                    cross_segment<n, CI>(o, Xs, p, pad0, pc.ia, y, xs, lane, wk);
+                    cross_segment<n, CI>(o, Xs, p, pad0, pc.ia, y, xs, lane, wk, sh);
                 }
                 flat_epilogue(o, epi, bias, p.epi.act);
                 store_streaming(out + fw + 4 * lane, o);
@@ -414,10 +419,10 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                     // A group hanging over the start of the plane is the head of row 0 (negative column).
                     const int yy = y < 0 ? 0 : y, xx = y < 0 ? x0 - p.M : x0;
                     float o[4];
-                    flat_row_group<n, CI>(o, Xs, p, pad0, pc.ia, yy, xx, wk);
+                    flat_row_group<n, CI>(o, Xs, p, pad0, pc.ia, yy, xx, wk, sh);
                     if (xx + 3 >= p.M && yy + 1 <= pc.yb) {      // straddles a row end: head of the next row
                         float o2[4];
-                        flat_row_group<n, CI>(o2, Xs, p, pad0, pc.ia, yy + 1, xx - p.M, wk);
+                        flat_row_group<n, CI>(o2, Xs, p, pad0, pc.ia, yy + 1, xx - p.M, wk, sh);
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             if (xx + k >= p.M) o[k] = o2[k];
@@ -493,19 +498,23 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     const int q = s.frame, N0 = s.N - 2 * q;
     if (dt != KST_F32 || (s.Cin != 1 && s.Cin != 3) || s.n > 7 || N0 < 4 || (N0 & 3) != 0 || s.Ns != s.N) return false;
     if (q < 0 || q > 4 || (q > 0 && s.n < 2)) return false;
+    if (s.crop != 0 && (s.crop != 1 || q == 0)) return false;
     const int npre = flat_npre(s.Cin);
-    const long long MM = (long long)s.M * s.M;
+    const int M = s.M - 2 * s.crop;                             // edge of the planes that are written
+    if (M < 1) return false;
+    const long long MM = (long long)M * M;
     // Blocks of 8192 outputs; of 4096 where three channels' rows for 8192 do not fit the prefetch
     // registers and two workgroups' LDS buffers (narrow blocks re-read more halo rows).
     unsigned CH = 8192;
     if (s.Cin > 1) {
-        const int rows = (int)((CH - 1 + s.M - 1) / s.M) / 2 + 1 + s.fl + 1;
+        const int rows = (int)((CH - 1 + M - 1) / M) / 2 + 1 + s.fl + 1;
         const size_t stride = (size_t)((8 + s.N + F_PAD + 3) & ~3);
         if ((size_t)s.Cin * rows * N0 > (size_t)F_THREADS * npre * 4 || 2 * 2 * s.Cin * rows * stride * sizeof(float) > 160 * 1024)
             CH = 4096;
     }
-    if (MM < CH || s.M < 8) return false;                       // a block may touch at most two planes
-    p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.fl = s.fl;
+    if (MM < CH || M < 8) return false;                       // a block may touch at most two planes
+    p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = M; p.fl = s.fl;
+    p.sh = s.crop;
     p.q = q; p.N0 = N0;
     p.pad0 = q > 0 ? 8 - q : F_PAD;                             // the tensor's column 0 lands on LDS column 8 (or 4)
     p.CH = CH;
@@ -515,9 +524,9 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     // Three channels: only where every workgroup walks over several blocks.  Below that the many small
     // workgroups of the multi-channel kernel finish sooner (16 images of 224 x 224: 10 us against 12).
     if (s.Cin > 1 && p.nblocks < 1024) return false;
-    p.fast = s.M >= 256;
+    p.fast = M >= 256;
     // Input rows one piece can need: the rows its output span maps to, plus halo.
-    const int span = (int)((CH - 1 + s.M - 1) / s.M);           // yb - ya at most
+    const int span = (int)((CH - 1 + M - 1) / M);           // yb - ya at most
     p.max_rows = span / 2 + 1 + s.fl + 1;
     if (p.max_rows > s.N) p.max_rows = s.N;
     if ((size_t)s.Cin * p.max_rows * N0 > (size_t)F_THREADS * npre * 4) return false;   // prefetch registers
@@ -539,12 +548,12 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     const unsigned long long gstep = (unsigned long long)grid * CH;
     p.g_plane = (int)(gstep / (unsigned long long)MM);
     const unsigned grem = (unsigned)(gstep % (unsigned long long)MM);
-    p.g_y = (int)(grem / (unsigned)s.M);
-    p.g_x = (int)(grem % (unsigned)s.M);
-    p.s_y = F_STEP / s.M;
-    p.s_x = F_STEP % s.M;
-    p.c_y = (int)((CH - 1) / (unsigned)s.M);
-    p.c_x = (int)((CH - 1) % (unsigned)s.M);
+    p.g_y = (int)(grem / (unsigned)M);
+    p.g_x = (int)(grem % (unsigned)M);
+    p.s_y = F_STEP / M;
+    p.s_x = F_STEP % M;
+    p.c_y = (int)((CH - 1) / (unsigned)M);
+    p.c_x = (int)((CH - 1) % (unsigned)M);
     return true;
 }
 

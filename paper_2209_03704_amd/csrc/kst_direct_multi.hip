@@ -30,6 +30,7 @@ constexpr int M_THREADS = M_TI * M_TJ;
 struct MultiParams {
     int B, Cin, Cout, M, E;
     int N0, q;                           // edge of the tensor in memory; zero frame around it (virtual)
+    int crop;                            // 1: `out` is the interior of the M x M map (edge M - 2)
     int tiles_x, tiles_y;
     unsigned off[4];                     // element offset of W_p in the segregated buffer
     Epilogue epi;
@@ -247,6 +248,25 @@ __global__ void __launch_bounds__(M_THREADS * KS) direct_multi_kernel(const T *_
                 for (int s2 = 0; s2 < 2; ++s2) acc[k][r][s2] = epi_apply(acc[k][r][s2], bias, p.epi.act);
         }
     }
+    if (p.crop) {
+        // Odd padding factor: only the interior of the map is wanted, and `out` holds just that:
+        // element (y, x) of the map is element (y - 1, x - 1) of `out` (edge M - 2).  Seen from `out`
+        // the quads start on odd rows and columns: its even rows take the sub-kernels of the odd
+        // row parity and the other way round (Fig. 7's swap of roles).
+        const int Mo = p.M - 2;
+#pragma unroll
+        for (int k = 0; k < CO; ++k) {
+            float *plane = out + ((size_t)b * p.Cout + co0 + k) * Mo * Mo;
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const int y = 2 * i + r - 1, x = 2 * j + s2 - 1;
+                    if (y >= 0 && y < Mo && x >= 0 && x < Mo) plane[(size_t)y * Mo + x] = acc[k][r][s2];
+                }
+        }
+        return;
+    }
     const bool x1 = 2 * j + 1 < p.M;
 #pragma unroll
     for (int k = 0; k < CO; ++k) {
@@ -339,6 +359,7 @@ hipError_t launch_t(const T *in, const T *w_seg, float *out, const Shape &s, kst
     MultiParams p;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.M = s.M; p.E = s.E;
     p.q = s.frame;
+    p.crop = s.crop;
     p.N0 = s.N - 2 * s.frame;
     p.tiles_x = (s.E + M_TJ - 1) / M_TJ;
     p.tiles_y = (s.E + M_TI - 1) / M_TI;

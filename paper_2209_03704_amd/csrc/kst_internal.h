@@ -97,13 +97,16 @@ struct Shape {
     int Ns;   // elements between consecutive rows of `in` (N unless the caller framed it with a wider stride)
     int frame; // > 0: `in` is the dense [B][Cin][N - 2 frame][N - 2 frame] tensor and the kernel supplies the
                // zero frame of that width itself (only kernels for which *_takes_virtual_frame says so)
+    int crop;  // 1: only the interior of the M x M map is wanted -- `out` is the dense [B][Cout][M - 2][M - 2] tensor
+               // whose element (y, x) is element (y + 1, x + 1) of the map (an odd padding factor; only kernels for
+               // which *_takes_virtual_frame says so)
     Epilogue epi;  // applied where the final value of an element is stored (every forward kernel but the
                    // row-parity-passes one, which must be given an inactive one)
 };
 
 inline Shape make_shape(int B, int Cin, int Cout, int N, int n)
 {
-    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N, 0, {nullptr, KST_ACT_NONE}};
+    Shape s{B, Cin, Cout, N, n, 2 * N - n, (2 * N - n + 1) / 2, n / 2, N, 0, 0, {nullptr, KST_ACT_NONE}};
     return s;
 }
 
@@ -160,7 +163,8 @@ hipError_t launch_backward_weight_igemm(const float *in, const float *g, float *
 bool direct_multi_supported(const Shape &s);
 // True when the direct path reads a padded layer's input in place: s is the framed problem (s.N
 // includes the frame of q zeros per side), the kernel is then given Shape::frame = q and the dense tensor.
-bool direct_takes_virtual_frame(const Shape &s, int q, kst_dtype dt);
+// crop = 1: and writes only the interior of the map, straight into the caller's tensor (Shape::crop).
+bool direct_takes_virtual_frame(const Shape &s, int q, int crop, kst_dtype dt);
 hipError_t launch_direct_multi(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,
                                hipStream_t stream);
 hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Shape &s, kst_dtype dt,

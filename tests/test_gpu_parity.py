@@ -272,12 +272,15 @@ def test_direct_single_channel_flat_kernel(B, Cout, N, n):
     (42, 3, 1, 224, 4, 2),    # Table 1's map, even kernel
     (1000, 3, 1, 48, 3, 0),   # three channels without a frame; M * M just above one block
     (253, 3, 2, 64, 7, 4),    # frame of two, largest kernel
-    (380, 3, 1, 72, 2, 3),    # odd padding factor: frame of two, interior copied out
+    (400, 3, 1, 72, 2, 3),    # odd padding factor: frame of two, rows and columns shifted by one (sub-kernel roles swapped)
+    (70, 3, 2, 132, 5, 1),    # odd padding factor on wide maps (M = 261)
     (2, 3, 1, 64, 3, 2),      # too few blocks: the multi-channel kernel
     (2, 1, 2, 64, 5, 2),      # one input channel with a frame (no framed copy of the input any more)
     (1, 1, 1, 512, 5, 2),     # the headline layer's map with a frame
     (2, 1, 3, 100, 3, 8),     # frame of four (the widest the kernel supplies)
-    (1, 1, 1, 60, 6, 3),
+    (1, 1, 1, 60, 6, 3),      # one channel, odd padding factor
+    (2, 1, 2, 128, 5, 5),     # one channel, odd padding factor, M = 261
+    (1, 1, 1, 64, 3, 7),      # frame of four with the shift
     (1, 3, 1, 40, 5, 6),      # frame of three: pieces that lie entirely inside the frame rows
     (2, 3, 1, 32, 3, 10),     # frame of five: beyond the flat kernel, the multi-channel kernel takes it
 ])
@@ -297,8 +300,9 @@ def test_direct_flat_kernel_with_channels_and_frame(B, Cin, Cout, N, n, P):
     assert e <= TOL["f32"], "rel err %.3e" % e
     check_exact_with_guards(wl.Layer("flat_ci_int", B, Cin, Cout, N, n, "f32", "integer"), kst.KST_PATH_DIRECT,
                             900 + N + n, P=P)
-    if P % 2 == 0 and P // 2 <= 4:
-        assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_DIRECT) == 0
+    # no framed copy of the input, and for an odd padding factor no wider result to copy the interior of
+    # (the two small three-channel cases go to the multi-channel kernel, which supplies the frame too)
+    assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_DIRECT) == 0
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
