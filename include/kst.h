@@ -195,9 +195,10 @@ kst_status kst_forward(const void *in, const void *w, void *out,
  * loads) and for odd P write output (y, x) as element (y + 1, x + 1) of the
  * map the framed input defines, which is that swap of roles: no workspace.
  * The matrix-core kernels run on a framed copy of the input made in the
- * workspace; for odd P they run into a second workspace buffer one pixel wider
- * on every side, whose interior is then copied to `out` (one extra pass over
- * the output).  Layouts, dtypes, alignment, stream and error behaviour are
+ * workspace and shift their stores in the same way for odd P, except three
+ * 16-bit kernels (maps of 16 to 128 quads a row), which for odd P run into a
+ * second workspace buffer one pixel wider on every side, whose interior is
+ * then copied to `out` (one extra pass over the output).  Layouts, dtypes, alignment, stream and error behaviour are
  * those of kst_forward_seg / kst_forward; `out` is [B][Cout][2N+2P-n][2N+2P-n]
  * fp32.  kst_workspace_bytes_padded returns 0 for an illegal shape or
  * unsupported path, and for layers whose kernel needs neither copy (the direct

@@ -342,6 +342,15 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     // padding factor the flat-output kernel writes the interior of the wider map straight to
     // `out` (output row y is row y + 1 of that map: the row parities, hence the sub-kernels,
     // swap roles as in Fig. 7): no wider buffer and no copy of its interior either.
+    // The matrix-core kernels whose accumulators go straight to memory (all fp32 ones, the first
+    // 16-bit one) store the interior of the wider map directly as well; those that leave through
+    // an LDS image of whole rows keep the wider buffer and the copy.
+    if ((P & 1) && on_matrix_cores(f->chosen) && f->chosen != KST_PATH_IGEMM_PASSES &&
+        (!is16(dt) || !(igemm_bf16_wide_supported(f->s) || igemm_bf16_ring_supported(f->s) ||
+                        igemm_bf16_strip_supported(f->s)))) {
+        f->s.crop = 1;
+        f->wide_bytes = 0;
+    }
     if (f->chosen == KST_PATH_DIRECT) {
         if ((P & 1) && direct_takes_virtual_frame(f->s, f->q, 1, dt)) {
             f->s.frame = f->q;

@@ -51,13 +51,17 @@ struct IgemmParams {
     size_t out_elems;
     double est_s;          // the cost model's time for the launch chosen here (seconds)
     Epilogue epi;          // applied by the stores that write final values (not by those of partial sums)
+    int crop;              // 1: quad members land one row and one column earlier (odd padding factor)
 };
 
 // kc: input channels staged per step.
 inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
 {
     IgemmParams p;
-    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M; p.E = s.E;
+    // M: edge of the planes that are written -- with Shape::crop the interior of the map only, whose
+    // element (y, x) is the map's (y + 1, x + 1); positions and tiles are those of the whole map.
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M - 2 * s.crop; p.E = s.E;
+    p.crop = s.crop;
     p.Ns = s.Ns;
     p.EE = s.E * s.E;
     p.Mtot = s.B * p.EE;
@@ -79,7 +83,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     double est;
     {
         const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt != KST_F32 ? 1.0e12 : 2.0e11);
-        const double out_b = (double)s.B * s.Cout * s.M * s.M * 4.0;
+        const double out_b = (double)s.B * s.Cout * p.M * p.M * 4.0;
         double best = (double)((tiles + 255) / 256) * tile_s;
         const double unsplit = best;
         // A layer with very few tiles (one sample of a small map) may split further, up to one
@@ -96,7 +100,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     p.ci_per_split = cps * kc;
     p.splits = (chunks + cps - 1) / cps;
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, dt);
-    p.out_elems = (size_t)s.B * s.Cout * s.M * s.M;
+    p.out_elems = (size_t)s.B * s.Cout * p.M * p.M;
     p.epi = s.epi;
     return p;
 }
@@ -118,14 +122,22 @@ __device__ __forceinline__ void igemm_store_block(float *__restrict__ o, const f
         const float bias = epi ? epi_bias(p.epi, co) : 0.0f;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const int y = 2 * mi + r;
-            if (y >= p.M) continue;
-            float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
             float v0 = r ? a2[v] : a0[v], v1 = r ? a3[v] : a1[v];
             if (epi) {
                 v0 = epi_apply(v0, bias, p.epi.act);
                 v1 = epi_apply(v1, bias, p.epi.act);
             }
+            if (p.crop) {                               // uniform: members at (2 mi + r - 1, 2 mj + s - 1)
+                const int yc = 2 * mi + r - 1, xc = 2 * mj - 1;
+                if (yc < 0 || yc >= p.M) continue;
+                float *qc = o + (((size_t)mb * p.Cout + co) * p.M + yc) * p.M + xc;
+                if (xc >= 0 && xc < p.M) qc[0] = v0;
+                if (xc + 1 < p.M) qc[1] = v1;
+                continue;
+            }
+            const int y = 2 * mi + r;
+            if (y >= p.M) continue;
+            float *q = o + (((size_t)mb * p.Cout + co) * p.M + y) * p.M + 2 * mj;
             if (x1_ok) {
                 if ((reinterpret_cast<uintptr_t>(q) & 7u) == 0) {
                     *reinterpret_cast<float2 *>(q) = make_float2(v0, v1);

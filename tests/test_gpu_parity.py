@@ -711,6 +711,41 @@ def test_padded_forward_full_size(B, Cin, Cout, N, n, P, dtype):
     check_channel_projection(out, x, w, TOL[dtype], P=P, seed=N + P)
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype,path", [
+    (16, 32, 128, 16, 4, 1, "f32", kst.KST_PATH_IGEMM),        # pipelined fp32 kernel, whole tiles
+    (2, 64, 128, 8, 4, 3, "f32", kst.KST_PATH_IGEMM),          # split reduction + summing pass
+    (1, 512, 128, 4, 4, 1, "f32", kst.KST_PATH_IGEMM),         # one sample: 64+ splits
+    (2, 512, 128, 8, 4, 1, "f32", kst.KST_PATH_IGEMM_EVEN),    # even shares: slots + slot-summing pass
+    (2, 18, 40, 9, 3, 3, "f32", kst.KST_PATH_IGEMM),           # first fp32 kernel (ragged channels), odd map
+    (3, 24, 150, 12, 5, 1, "f32", kst.KST_PATH_IGEMM),         # 5 x 5, ragged channel tile
+    (9, 130, 16, 6, 4, 1, "bf16", kst.KST_PATH_IGEMM),         # first 16-bit kernel, split reduction
+    (3, 37, 40, 17, 5, 3, "f16", kst.KST_PATH_IGEMM),          # first 16-bit kernel, whole tiles
+    (2, 48, 64, 30, 2, 1, "bf16", kst.KST_PATH_IGEMM),         # LDS-ring kernel: keeps the wider buffer and the copy
+])
+def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, path):
+    """Odd padding factors (Fig. 7): the kernels whose accumulators go straight to memory write the
+    interior of the wider map directly (no wider workspace buffer, no copy); against the oracle,
+    bit for bit on integers, with guard words around `out`."""
+    layer = wl.Layer("odd_p", B, Cin, Cout, N, n, dtype, "relu_normal", w_std=0.1)
+    x, w = wl.make_tensors(layer, 1300 + N + n + P)
+    code = {"f32": kst.KST_F32, "bf16": kst.KST_BF16, "f16": kst.KST_F16}[dtype]
+    got = kst.kst_forward_seg_padded(x.to(DEV), kst.kst_segregate_weights(w.to(DEV)), Cout, n, P, path=path)
+    torch.cuda.synchronize()
+    want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+    assert got.shape == want.shape
+    e = rel_err(got.cpu().numpy(), want)
+    assert e <= TOL[dtype], "rel err %.3e" % e
+    check_exact_with_guards(wl.Layer("odd_p_int", B, Cin, Cout, N, n, dtype, "integer"), path, 1400 + N, P=P)
+    M = kst.kst_out_size_padded(N, n, P)
+    wider = B * Cout * (M + 2) * (M + 2) * 4
+    need = kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, code, path)
+    even = kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P + 1, code, path)
+    if N == 30:
+        assert need >= wider                      # that kernel leaves through an LDS image of whole rows
+    else:
+        assert need <= even + 4096                # nothing beyond what the even padding factor above it needs
+
+
 TABLE3_CASES = [(m, i) for m in wl.TABLE3_GENERATORS for i in range(len(wl.TABLE3_GENERATORS[m]))]
 
 
