@@ -326,17 +326,29 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     f->Mq = 2 * f->Nq - n;
     if (f->M < 1) return KST_ERR_SHAPE;
     f->s = make_shape(B, Cin, Cout, f->Nq, n);
-    if (path == KST_PATH_IGEMM_EVEN) f->s.Ns = (f->Nq + 3) & ~3;     // the stride that launch form wants
+    // The pipelined fp32 matrix-core kernel supplies the frame itself while it stages its input
+    // rows (tensor rows of whole 16-byte groups): no framed copy.
+    Shape in_place = f->s;
+    in_place.frame = f->q;
+    const bool frame_in_kernel = dt == KST_F32 && igemm_f32_takes_virtual_frame(in_place);
+    if (path == KST_PATH_IGEMM_EVEN) {
+        if (frame_in_kernel) f->s = in_place;
+        else f->s.Ns = (f->Nq + 3) & ~3;                            // the stride that launch form wants of a copy
+    }
     st = resolve_path(f->s, dt, path, &f->chosen);
     if (st != KST_OK) return st;
-    // The pipelined fp32 matrix-core kernel wants rows of whole 16-byte groups: give the framed
-    // copy a row stride rounded up to 4 elements when that is the kernel that will run.
-    if (on_matrix_cores(f->chosen) && dt == KST_F32 && (f->Nq & 3) != 0) {
-        Shape wide = f->s;
-        wide.Ns = (f->Nq + 3) & ~3;
-        if (igemm_f32_takes_row_stride(wide)) f->s = wide;
+    if (on_matrix_cores(f->chosen) && dt == KST_F32) {
+        if (frame_in_kernel) {
+            f->s = in_place;
+        } else if ((f->Nq & 3) != 0) {
+            // Otherwise that kernel wants rows of whole 16-byte groups: give the framed copy a row
+            // stride rounded up to 4 elements when that is the kernel that will run.
+            Shape wide = f->s;
+            wide.Ns = (f->Nq + 3) & ~3;
+            if (igemm_f32_takes_row_stride(wide)) f->s = wide;
+        }
     }
-    f->in_bytes = ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
+    f->in_bytes = f->s.frame > 0 ? 0 : ((size_t)B * Cin * f->Nq * f->s.Ns * elt_bytes(dt) + 255) & ~(size_t)255;
     f->wide_bytes = (P & 1) ? (((size_t)B * Cout * f->Mq * f->Mq * sizeof(float) + 255) & ~(size_t)255) : 0;
     // The direct kernels supply the zero frame themselves: no framed copy at all; and for an odd
     // padding factor the flat-output kernel writes the interior of the wider map straight to

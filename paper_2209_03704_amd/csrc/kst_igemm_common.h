@@ -42,7 +42,10 @@ constexpr int G_THREADS = 512;   // 8 waves: 2 (channel halves) x 4 (position bl
 
 struct IgemmParams {
     int B, Cin, Cout, N, M, E, EE;
-    int Ns;                // row stride of the input in elements (>= N)
+    int Ns;                // row stride of the input in elements (>= N); with a frame supplied by the kernel
+                           // (q > 0): row stride of the staged, framed rows in LDS
+    int q, N0, pad;        // zero frame the kernel supplies; edge of the tensor in memory (N - 2q); LDS column
+                           // of the framed map's column 0 (pad + q is a multiple of 4)
     int Mtot;              // B * E * E
     int tiles_m, tiles_co, splits;
     int ci_per_split;      // multiple of the kernel's channel step
@@ -62,7 +65,10 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     // element (y, x) is the map's (y + 1, x + 1); positions and tiles are those of the whole map.
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M - 2 * s.crop; p.E = s.E;
     p.crop = s.crop;
-    p.Ns = s.Ns;
+    p.q = s.frame;
+    p.N0 = s.N - 2 * s.frame;
+    p.pad = (4 - (s.frame & 3)) & 3;
+    p.Ns = s.frame > 0 ? (p.pad + s.N + 3) & ~3 : s.Ns;
     p.EE = s.E * s.E;
     p.Mtot = s.B * p.EE;
     p.tiles_m = (p.Mtot + G_TM - 1) / G_TM;

@@ -194,7 +194,7 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     const int i0 = (m0 - b0 * p.EE) / p.E;
     const int R0 = b0 * p.N + i0;
 
-    const int xbase = ((L.mb * p.N + L.mi) - R0) * p.Ns + L.mj + kk * xplane;
+    const int xbase = ((L.mb * p.N + L.mi) - R0) * p.Ns + p.pad + L.mj + kk * xplane;
     const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
 
     // ---- staging plan: where each of this lane's float4 comes from and goes to -------------
@@ -220,8 +220,14 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
         w_off[k] = ok ? p.off[cls] + ((unsigned)(ci_begin + c) * Tp + (T - tb)) * p.Cout + co0 + 4 * tco4 : 0u;
         w_inc[k] = ok ? (unsigned)G_KC * Tp * p.Cout : 0u;
     }
+    // With a frame supplied here (p.q > 0) the staged rows are rows of the framed map, the tensor
+    // in memory is the dense unframed one, and an item is either 16 bytes of a row that exists or
+    // four cells of the frame (or of the slack beside it): those are cleared once, below, and
+    // never written again, in either stage.
     const int xp4 = xplane >> 2, n4 = p.Ns >> 2;
+    const int g_first = (p.pad + p.q) >> 2, g_count = p.N0 >> 2;   // 16-byte groups of a staged row that hold tensor data
     unsigned x_off[P_NX4], x_inc[P_NX4];
+    bool x_keep[P_NX4];                                           // (frame only) the item's cells keep their zeros
 #pragma unroll
     for (int k = 0; k < P_NX4; ++k) {
         const int e4 = tid + k * G_THREADS;
@@ -230,9 +236,18 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
         const int lr = rem / n4, x4 = rem - lr * n4;
         const int R = R0 + lr;
         const int bb = R / p.N, y = R - bb * p.N;
-        const bool ok = e4 < G_KC * xp4 && bb < p.B;
-        x_off[k] = ok ? (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.Ns + 4 * x4 : 0u;
-        x_inc[k] = ok ? (unsigned)G_KC * p.N * p.Ns : 0u;
+        bool ok = e4 < G_KC * xp4 && bb < p.B;
+        x_keep[k] = false;
+        if (p.q > 0) {                                            // uniform
+            const bool real = y >= p.q && y < p.N - p.q && x4 >= g_first && x4 < g_first + g_count;
+            x_keep[k] = e4 < G_KC * xp4 && !real;
+            ok = ok && real;
+            x_off[k] = ok ? (((unsigned)bb * p.Cin + ci_begin + c) * p.N0 + (y - p.q)) * p.N0 + 4 * (x4 - g_first) : 0u;
+            x_inc[k] = ok ? (unsigned)G_KC * p.N0 * p.N0 : 0u;
+        } else {
+            x_off[k] = ok ? (((unsigned)bb * p.Cin + ci_begin + c) * p.N + y) * p.Ns + 4 * x4 : 0u;
+            x_inc[k] = ok ? (unsigned)G_KC * p.N * p.Ns : 0u;
+        }
     }
 
 #pragma unroll
@@ -267,7 +282,7 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
         } else {
             constexpr int k = j - NW4;
             const float4 v = make_float4(x_reg[k].x, x_reg[k].y, x_reg[k].z, x_reg[k].w);
-            if (tid + k * G_THREADS < G_KC * xp4) reinterpret_cast<float4 *>(Xs + at)[tid + k * G_THREADS] = v;
+            if (tid + k * G_THREADS < G_KC * xp4 && !x_keep[k]) reinterpret_cast<float4 *>(Xs + at)[tid + k * G_THREADS] = v;
         }
     };
     auto fetch_item = [&](auto jc, int c0) {
@@ -286,6 +301,15 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     // multiplied.  From then on an item is written to LDS late in a chunk and its register
     // refilled at once with the chunk after the next, so a load has a whole chunk's MFMAs to arrive.
     static_for<ITEMS>([&](auto jc) { fetch_item(jc, ci_begin); });
+    if (p.q > 0) {                                                // uniform: the frame's cells, in every stage
+#pragma unroll
+        for (int k = 0; k < P_NX4; ++k)
+            if (x_keep[k]) {
+                reinterpret_cast<float4 *>(Xs)[tid + k * G_THREADS] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if constexpr (DB)
+                    reinterpret_cast<float4 *>(Xs + stage_floats)[tid + k * G_THREADS] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+    }
     static_for<ITEMS>([&](auto jc) {
         write_item(jc, 0);
         fetch_item(jc, ci_begin + G_KC);
@@ -548,6 +572,7 @@ static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_F32, G_KC); }
 // P_NX4 loads per lane.
 static bool pipe_ok(const IgemmParams &p)
 {
+    if (p.q > 0 && ((p.N0 & 3) != 0 || p.N0 < 4)) return false;     // a frame supplied by the kernel: whole 16-byte groups of tensor rows
     return (p.Ns & 3) == 0 && (p.Cout & 3) == 0 && p.Cin % G_KC == 0 &&
            (size_t)G_KC * p.lrows * p.Ns / 4 <= (size_t)P_NX4 * G_THREADS;
 }
@@ -573,6 +598,11 @@ bool igemm_f32_supported(const Shape &s)
 bool igemm_f32_takes_row_stride(const Shape &s)
 {
     return igemm_f32_supported(s) && pipe_ok(plan(s));
+}
+
+bool igemm_f32_takes_virtual_frame(const Shape &s)
+{
+    return s.frame > 0 && s.Ns == s.N && igemm_f32_supported(s) && pipe_ok(plan(s));
 }
 
 // Even shares or whole tiles?  Even shares when the pipelined kernel applies and the model says
@@ -694,7 +724,7 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
     }
     const unsigned blocks = (unsigned)p.tiles_m * p.tiles_co * p.splits;
     const bool pipe = pipe_ok(p);
-    if (!pipe && p.Ns != p.N) return hipErrorInvalidValue;
+    if (!pipe && (p.Ns != p.N || p.q > 0)) return hipErrorInvalidValue;
     if (pipe) {
         if constexpr (n <= 5)
             if (two_stages(p, n)) return launch_pipe_db<n, true>(in, w_seg, dst, p, blocks, stream);

@@ -172,6 +172,7 @@ hipError_t launch_direct(const void *in, const void *w_seg, float *out, const Sh
 // Matrix-core path: whether the kernels can run the shape, scratch they need, launch.
 bool igemm_f32_supported(const Shape &s);
 bool igemm_f32_takes_row_stride(const Shape &s);   // s.Ns != s.N is only read by the pipelined fp32 kernel
+bool igemm_f32_takes_virtual_frame(const Shape &s); // s.frame > 0: that kernel supplies the zero frame while it stages (dense unframed tensor)
 bool igemm_bf16_supported(const Shape &s);
 bool igemm_bf16_strip_supported(const Shape &s);   // row-strip variant (quad rows of at most 128 quads)
 hipError_t launch_igemm_bf16_strip(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
