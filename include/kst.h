@@ -194,8 +194,10 @@ kst_status kst_forward(const void *in, const void *w, void *out,
  * zeros.  The direct kernels supply it themselves (in LDS, or by predicated
  * loads) and for odd P write output (y, x) as element (y + 1, x + 1) of the
  * map the framed input defines, which is that swap of roles: no workspace.
- * The matrix-core kernels run on a framed copy of the input made in the
- * workspace and shift their stores in the same way for odd P, except three
+ * The fp32 matrix-core kernel for channel counts that are multiples of 4
+ * supplies the frame while it stages its input; the other matrix-core kernels
+ * run on a framed copy of the input made in the workspace.  They shift their
+ * stores in the same way for odd P, except three
  * 16-bit kernels (maps of 16 to 128 quads a row), which for odd P run into a
  * second workspace buffer one pixel wider on every side, whose interior is
  * then copied to `out` (one extra pass over the output).  Layouts, dtypes, alignment, stream and error behaviour are
