@@ -589,20 +589,27 @@ static bool two_stages(const IgemmParams &p, int n)
     return n <= 5 && 2 * lds_bytes(p, n) <= 160 * 1024;
 }
 
-bool igemm_f32_supported(const Shape &s)
+// The kernels for ordinary layers (tiles of 128 positions); layers with very few positions have a kernel of their own.
+static bool tiles_supported(const Shape &s)
 {
     if (s.n > 7) return false;
     return lds_bytes(plan(s), s.n) <= 160 * 1024;
 }
 
+bool igemm_f32_supported(const Shape &s)
+{
+    return igemm_f32_small_supported(s) || tiles_supported(s);
+}
+
 bool igemm_f32_takes_row_stride(const Shape &s)
 {
-    return igemm_f32_supported(s) && pipe_ok(plan(s));
+    return tiles_supported(s) && pipe_ok(plan(s));
 }
 
 bool igemm_f32_takes_virtual_frame(const Shape &s)
 {
-    return s.frame > 0 && s.Ns == s.N && igemm_f32_supported(s) && pipe_ok(plan(s));
+    if (s.frame <= 0 || s.Ns != s.N) return false;
+    return igemm_f32_small_supported(s) || (tiles_supported(s) && pipe_ok(plan(s)));
 }
 
 // Even shares or whole tiles?  Even shares when the pipelined kernel applies and the model says
@@ -623,7 +630,7 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
     r.k.grid = all_units < (unsigned long long)SK_GRID ? (int)all_units : SK_GRID;
     r.k.whole = (int)(tiles / SK_GRID) * SK_GRID;             // (0 unless grid == SK_GRID)
     r.k.units = (tiles - r.k.whole) * (unsigned)r.k.chunks;
-    if (!pipe_ok(p) || tiles > (1u << 22)) return r;
+    if (!tiles_supported(s) || !pipe_ok(p) || tiles > (1u << 22)) return r;
     if (force) {
         r.use = true;
         return r;
@@ -664,6 +671,7 @@ bool igemm_f32_even_shares_possible(const Shape &s)
 
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even)
 {
+    if (!force_even && igemm_f32_small_supported(s)) return igemm_f32_small_workspace_bytes(s);
     const IgemmParams p = plan(s);
     const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) return (size_t)2 * sk.k.grid * SK_SLOT_FLOATS * sizeof(float);
@@ -738,6 +746,7 @@ static hipError_t launch_n(const float *in, const float *w_seg, float *dst, cons
 hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
                             bool force_even, hipStream_t stream)
 {
+    if (!force_even && igemm_f32_small_supported(s)) return launch_igemm_f32_small(in, w_seg, out, ws, s, stream);
     const IgemmParams p = plan(s);
     const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) {

@@ -1,0 +1,245 @@
+// Matrix-core segregated forward pass for fp32 layers with very few positions: one sample (or a
+// few) of a small map -- the way Table 3 times the generator layers -- where a layer is a stream
+// of weights over 16 or 64 quad positions (Section 3.3, Eqs. 7-10 as four implicit GEMMs).
+//
+// The kernel for ordinary layers multiplies tiles of 128 positions: with 16 positions seven
+// eighths of its matrix-core work and of its partial sums are padding.  Here the position block
+// is the 16 columns of v_mfma_f32_16x16x4f32, so nothing is padded beyond the last block:
+//   * one wave = one workgroup owns 16 positions x 64 output channels (four MFMA row blocks) x the
+//     four parity classes: 64 accumulator registers;
+//   * the reduction over input channels is cut into `splits` ranges, one workgroup each, so that
+//     the layer's weights -- each read exactly once, straight from memory into the A operands, 16
+//     bytes per lane and 256 consecutive bytes per 16 lanes: a lane's four values are its row of
+//     the four row blocks, so row i of block j is output channel 4 i + j of the wave's 64 -- are
+//     pulled by a few waves on every SIMD of the chip; the partial outputs are added by the
+//     strided-share pass (fixed order: reproducible);
+//   * the B operand is the lane's own position and channel: its (fl+1) x (fl+1) window is loaded
+//     from the input tensor as it lies in memory, the zero frame of a padded layer by predicate
+//     (no framed copy), once per chunk of four channels for all taps;
+//   * the loads of chunk c + 1 are issued before the MFMAs of chunk c.
+#include "kst_igemm_common.h"
+
+namespace kst {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int SM_TCO = 64;            // output channels per wave: four row blocks of 16
+constexpr int SM_POS = 16;            // positions per wave: the MFMA's columns
+constexpr int SM_KC = 4;              // input channels per MFMA
+
+struct SmallParams {
+    int B, Cin, Cout, N0, q, E, EE, Mtot;
+    int M, crop;                      // edge of the planes that are written; 1: quad members land one row / column earlier
+    int pos_blocks, co_blocks, splits, chunks_per_split, chunks;
+    unsigned off[4];                  // element offset of W_p in the segregated weights
+    size_t out_elems;
+    Epilogue epi;
+};
+
+template <int n>
+__global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__restrict__ in, const float *__restrict__ w_seg,
+                                                               float *__restrict__ dst, SmallParams p)
+{
+    constexpr int fl = n / 2;
+    constexpr int NN = n * n;
+    const int lane = threadIdx.x;
+    const int m = lane & 15, k = lane >> 4;          // column / row-in-block of the operands; channel of the chunk
+    unsigned id = blockIdx.x;
+    const int co_block = (int)(id % (unsigned)p.co_blocks);
+    id /= (unsigned)p.co_blocks;
+    const int pos_block = (int)(id % (unsigned)p.pos_blocks);
+    const int split = (int)(id / (unsigned)p.pos_blocks);
+    const int co0 = co_block * SM_TCO;
+
+    // This lane's position (B operand column m): batch item and quad, clamped past the end.
+    int pos = pos_block * SM_POS + m;
+    const bool pos_valid = pos < p.Mtot;
+    if (!pos_valid) pos = p.Mtot - 1;
+    const int mb = pos / p.EE;
+    const int prem = pos - mb * p.EE;
+    const int mi = prem / p.E, mj = prem - mi * p.E;
+
+    // Window of the position in the tensor as it lies in memory: rows mi - q .. mi - q + fl, the
+    // same for columns; cells outside the tensor belong to the zero frame.
+    unsigned x_off[fl + 1][fl + 1];
+    bool x_ok[fl + 1][fl + 1];
+#pragma unroll
+    for (int dy = 0; dy <= fl; ++dy)
+#pragma unroll
+        for (int dx = 0; dx <= fl; ++dx) {
+            const int y = mi + dy - p.q, x = mj + dx - p.q;
+            x_ok[dy][dx] = y >= 0 && y < p.N0 && x >= 0 && x < p.N0;
+            x_off[dy][dx] = x_ok[dy][dx] ? (((unsigned)mb * p.Cin + k) * p.N0 + y) * p.N0 + x : 0u;
+        }
+    const unsigned x_step = (unsigned)SM_KC * p.N0 * p.N0;
+
+    // A operands: lane (m, k) loads the weights of output channels co0 + 4 m .. + 3, input channel
+    // ci0 + k, as one 16-byte group; value j is its row (m) of row block j.  Groups past Cout (the
+    // last block of a ragged layer; Cout is a multiple of 4) read the last group again: their
+    // accumulator rows are never stored.
+    const unsigned w_col = (unsigned)min(co0 + 4 * m, p.Cout - 4);
+
+    const int c_begin = split * p.chunks_per_split;
+    const int c_end = min(p.chunks, c_begin + p.chunks_per_split);
+
+    floatx4 acc[4][4];                               // [class][row block]
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) acc[c][blk] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    float xf[2][fl + 1][fl + 1];
+    float4 wf[2][NN];
+    auto fetch = [&](auto bufc, int chunk) {
+        constexpr int buf = decltype(bufc)::value;
+        const unsigned ci = (unsigned)(chunk * SM_KC + k);
+#pragma unroll
+        for (int dy = 0; dy <= fl; ++dy)
+#pragma unroll
+            for (int dx = 0; dx <= fl; ++dx) {
+                const float v = in[x_off[dy][dx] + (unsigned)chunk * x_step];   // (frame cells read element 0 of the channel block: valid, unused)
+                xf[buf][dy][dx] = x_ok[dy][dx] ? v : 0.0f;
+            }
+#pragma unroll
+        for (int T = 0; T < NN; ++T) {
+            constexpr int dummy = 0;
+            (void)dummy;
+            const int cls = tap_class(n, T);
+            const unsigned Tp = (unsigned)class_taps(n, cls);
+            const unsigned t = (unsigned)(T - class_tap_base(n, cls));
+            const unsigned row = p.off[cls] + (ci * Tp + t) * (unsigned)p.Cout;
+            wf[buf][T] = *reinterpret_cast<const float4 *>(w_seg + row + w_col);     // 16-byte aligned: offsets are multiples of 4
+        }
+    };
+    auto multiply = [&](auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        static_for<NN>([&](auto Tc) {
+            constexpr int T = decltype(Tc)::value;
+            constexpr int cls = tap_class(n, T);
+            constexpr int r = cls >> 1, sp = cls & 1;
+            constexpr int local = T - class_tap_base(n, cls);
+            constexpr int Tb = taps_for_parity(n, sp);
+            constexpr int a = local / Tb, bq = local - a * Tb;
+            const float x = xf[buf][r + a][sp + bq];
+            acc[cls][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[buf][T].x, x, acc[cls][0], 0, 0, 0);
+            acc[cls][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[buf][T].y, x, acc[cls][1], 0, 0, 0);
+            acc[cls][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[buf][T].z, x, acc[cls][2], 0, 0, 0);
+            acc[cls][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[buf][T].w, x, acc[cls][3], 0, 0, 0);
+        });
+    };
+
+    if (c_begin < c_end) {
+        fetch(std::integral_constant<int, 0>{}, c_begin);
+        int c = c_begin;
+        while (true) {
+            if (c + 1 < c_end) fetch(std::integral_constant<int, 1>{}, c + 1);
+            multiply(std::integral_constant<int, 0>{});
+            if (++c >= c_end) break;
+            if (c + 1 < c_end) fetch(std::integral_constant<int, 0>{}, c + 1);
+            multiply(std::integral_constant<int, 1>{});
+            if (++c >= c_end) break;
+        }
+    }
+
+    // D layout: lane (m, k) holds rows 4 k + v (v = 0..3) of column m; row i of block blk is output
+    // channel co0 + 4 i + blk, at this lane's position.  The four classes are the quad's members.
+    if (!pos_valid) return;
+    const bool final = p.splits == 1;
+    const bool epi = final && epi_on(p.epi);
+    float *o = dst + (size_t)split * p.out_elems;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int co = co0 + 4 * (4 * k + v) + blk;
+            if (co >= p.Cout) continue;
+            const float bias = epi ? epi_bias(p.epi, co) : 0.0f;
+            float *plane = o + ((size_t)mb * p.Cout + co) * p.M * p.M;
+#pragma unroll
+            for (int cls = 0; cls < 4; ++cls) {
+                const int y = 2 * mi + (cls >> 1) - p.crop, x = 2 * mj + (cls & 1) - p.crop;
+                if (y < 0 || y >= p.M || x < 0 || x >= p.M) continue;
+                float val = acc[cls][blk][v];
+                if (epi) val = epi_apply(val, bias, p.epi.act);
+                plane[(size_t)y * p.M + x] = val;
+            }
+        }
+}
+
+bool small_plan(const Shape &s, SmallParams &p)
+{
+    if (s.n < 1 || s.n > 5 || s.Ns != s.N) return false;
+    if (s.Cin % SM_KC != 0 || s.Cin < 64 || s.Cout < 16 || (s.Cout & 3) != 0) return false;
+    const long long Mtot = (long long)s.B * s.E * s.E;
+    if (Mtot > 64) return false;                       // beyond that the tiles of 128 positions are filled well enough
+    p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout;
+    p.q = s.frame;
+    p.N0 = s.N - 2 * s.frame;
+    if (p.N0 < 1) return false;
+    p.E = s.E; p.EE = s.E * s.E; p.Mtot = (int)Mtot;
+    p.crop = s.crop;
+    p.M = s.M - 2 * s.crop;
+    if (p.M < 1) return false;
+    p.pos_blocks = (p.Mtot + SM_POS - 1) / SM_POS;
+    p.co_blocks = (s.Cout + SM_TCO - 1) / SM_TCO;
+    p.chunks = s.Cin / SM_KC;
+    // About two waves per SIMD over the chip, but at least four chunks per workgroup (so that the
+    // partial outputs stay well below the weights in bytes).
+    const int want = (2048 + p.pos_blocks * p.co_blocks - 1) / (p.pos_blocks * p.co_blocks);
+    int splits = p.chunks / 2 < want ? p.chunks / 2 : want;
+    if (splits < 1) splits = 1;
+    p.chunks_per_split = (p.chunks + splits - 1) / splits;
+    p.splits = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_F32);
+    p.out_elems = (size_t)s.B * s.Cout * p.M * p.M;
+    p.epi = s.epi;
+    return (size_t)p.pos_blocks * p.co_blocks * p.splits < 0x7fffffffu;
+}
+
+template <int n>
+hipError_t launch_small_n(const float *in, const float *w_seg, float *dst, const SmallParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)(p.pos_blocks * p.co_blocks * p.splits);
+    hipLaunchKernelGGL(igemm_f32_small_kernel<n>, dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool igemm_f32_small_supported(const Shape &s)
+{
+    SmallParams p;
+    return small_plan(s, p);
+}
+
+size_t igemm_f32_small_workspace_bytes(const Shape &s)
+{
+    SmallParams p;
+    if (!small_plan(s, p)) return 0;
+    return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+}
+
+hipError_t launch_igemm_f32_small(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
+                                  hipStream_t stream)
+{
+    SmallParams p;
+    if (!small_plan(s, p)) return hipErrorInvalidValue;
+    float *dst = p.splits > 1 ? (float *)ws : out;
+    hipError_t e;
+    switch (s.n) {
+        case 1: e = launch_small_n<1>(in, w_seg, dst, p, stream); break;
+        case 2: e = launch_small_n<2>(in, w_seg, dst, p, stream); break;
+        case 3: e = launch_small_n<3>(in, w_seg, dst, p, stream); break;
+        case 4: e = launch_small_n<4>(in, w_seg, dst, p, stream); break;
+        case 5: e = launch_small_n<5>(in, w_seg, dst, p, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    if (p.splits > 1)
+        e = launch_splitk_reduce((const float *)ws, out, p.out_elems, p.splits, stream, p.epi, (size_t)p.M * p.M, p.Cout);
+    return e;
+}
+
+}  // namespace kst

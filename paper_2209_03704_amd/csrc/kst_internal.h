@@ -186,6 +186,11 @@ hipError_t launch_igemm_bf16_wide(const void *in, const void *w_seg, float *out,
 bool igemm_bf16_pp_supported(const Shape &s);      // row-parity passes: 3 x 3 kernels, 64 x 64 maps, 256 input channels
 hipError_t launch_igemm_bf16_pp(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                 hipStream_t stream);
+// Layers with at most 64 quad positions in all (one sample of a small map): position blocks of 16.
+bool igemm_f32_small_supported(const Shape &s);
+size_t igemm_f32_small_workspace_bytes(const Shape &s);
+hipError_t launch_igemm_f32_small(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,
+                                  hipStream_t stream);
 // force_even: take the even-share launch whenever igemm_f32_even_shares_possible, whatever the cost model says.
 bool igemm_f32_even_shares_possible(const Shape &s);
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even = false);

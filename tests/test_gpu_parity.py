@@ -746,6 +746,39 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
         assert need <= even + 4096                # nothing beyond what the even padding factor above it needs
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
+    (1, 1024, 512, 4, 4, 2),    # Table 3, DCGAN layer 2 on one sample: 16 positions, one block
+    (1, 512, 256, 8, 4, 2),     # ... layer 3: 64 positions, four blocks
+    (1, 256, 128, 4, 4, 0),     # no padding: E = 2, four positions of a block's sixteen
+    (3, 128, 80, 3, 3, 2),      # three samples, 3 x 3 kernel, odd map, ragged channel block (80 = 64 + 16)
+    (2, 64, 16, 4, 5, 3),       # odd padding factor (stores shifted by one), 5 x 5 kernel, smallest channel counts
+    (1, 132, 72, 6, 2, 1),      # 2 x 2 kernel, odd padding factor, channel counts that are no powers of two
+    (4, 96, 64, 3, 1, 0),       # n = 1: three empty classes whose zeros must be written
+    (1, 2048, 1024, 4, 4, 2),   # Table 3, EB-GAN layer 2: 134 MB of weights
+])
+def test_matrix_cores_on_very_few_positions(B, Cin, Cout, N, n, P):
+    """Layers with at most 64 quad positions in all take position blocks of 16 on the matrix cores,
+    their reduction split over the chip: against the oracle, reproducible, bit for bit on
+    integers with guard words around `out`."""
+    layer = wl.Layer("small", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.05)
+    x, w = wl.make_tensors(layer, 1500 + Cin + n + P)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    got = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_IGEMM)
+    again = kst.kst_forward_seg_padded(xd, w_seg, Cout, n, P, path=kst.KST_PATH_IGEMM)
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)
+    if Cin * Cout > 600_000:
+        b_idx, co_idx = covering_planes(B, Cout, group=8)
+        check_planes(got, x, w, b_idx, co_idx, TOL["f32"], P=P)
+        check_channel_projection(got, x, w, TOL["f32"], P=P, seed=Cin)
+    else:
+        want = oracle.forward(wl.to_f64(x), wl.to_f64(w), P)
+        e = rel_err(got.cpu().numpy(), want)
+        assert e <= TOL["f32"], "rel err %.3e" % e
+        check_exact_with_guards(wl.Layer("small_int", B, Cin, Cout, N, n, "f32", "integer"), kst.KST_PATH_IGEMM,
+                                1600 + Cin, P=P)
+
+
 TABLE3_CASES = [(m, i) for m in wl.TABLE3_GENERATORS for i in range(len(wl.TABLE3_GENERATORS[m]))]
 
 
