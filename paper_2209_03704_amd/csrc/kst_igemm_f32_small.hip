@@ -144,28 +144,40 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
     }
 
     // D layout: lane (m, k) holds rows 4 k + v (v = 0..3) of column m; row i of block blk is output
-    // channel co0 + 4 i + blk, at this lane's position.  The four classes are the quad's members.
-    if (!pos_valid) return;
-    const bool final = p.splits == 1;
-    const bool epi = final && epi_on(p.epi);
-    float *o = dst + (size_t)split * p.out_elems;
+    // channel co0 + 4 i + blk, at this lane's position.  Stored from there a lane's 64 values
+    // would go to 64 different planes, 64 scattered 4-byte writes per instruction (measured: most of
+    // the kernel's time).  They go through an LDS image [channel][position][class] instead, and
+    // leave one channel per instruction with the lanes running along the output rows: lane
+    // (r, position, s) writes member (r, s) of its quad, so neighbouring lanes write neighbouring
+    // columns.
+    __shared__ float img[SM_TCO * SM_POS * 4];
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int co = co0 + 4 * (4 * k + v) + blk;
-            if (co >= p.Cout) continue;
-            const float bias = epi ? epi_bias(p.epi, co) : 0.0f;
-            float *plane = o + ((size_t)mb * p.Cout + co) * p.M * p.M;
-#pragma unroll
-            for (int cls = 0; cls < 4; ++cls) {
-                const int y = 2 * mi + (cls >> 1) - p.crop, x = 2 * mj + (cls & 1) - p.crop;
-                if (y < 0 || y >= p.M || x < 0 || x >= p.M) continue;
-                float val = acc[cls][blk][v];
-                if (epi) val = epi_apply(val, bias, p.epi.act);
-                plane[(size_t)y * p.M + x] = val;
-            }
+            const int col = 4 * (4 * k + v) + blk;               // channel of the wave's 64
+            *reinterpret_cast<float4 *>(&img[(col * SM_POS + m) * 4]) =
+                make_float4(acc[0][blk][v], acc[1][blk][v], acc[2][blk][v], acc[3][blk][v]);
         }
+    __syncthreads();                                             // (one wave: orders the LDS writes before the reads)
+    const int r2 = lane >> 5, m2 = (lane >> 1) & 15, s2 = lane & 1;
+    const int pos2 = pos_block * SM_POS + m2;
+    if (pos2 >= p.Mtot) return;
+    const int mb2 = pos2 / p.EE;
+    const int prem2 = pos2 - mb2 * p.EE;
+    const int mi2 = prem2 / p.E, mj2 = prem2 - mi2 * p.E;
+    const int y = 2 * mi2 + r2 - p.crop, x = 2 * mj2 + s2 - p.crop;
+    if (y < 0 || y >= p.M || x < 0 || x >= p.M) return;
+    const bool final = p.splits == 1;
+    const bool epi = final && epi_on(p.epi);
+    float *o = dst + (size_t)split * p.out_elems + ((size_t)mb2 * p.Cout + co0) * p.M * p.M + (size_t)y * p.M + x;
+    const size_t plane = (size_t)p.M * p.M;
+    const int ncol = min(SM_TCO, p.Cout - co0);
+    for (int col = 0; col < ncol; ++col) {
+        float val = img[(col * SM_POS + m2) * 4 + 2 * r2 + s2];
+        if (epi) val = epi_apply(val, epi_bias(p.epi, co0 + col), p.epi.act);
+        o[(size_t)col * plane] = val;
+    }
 }
 
 bool small_plan(const Shape &s, SmallParams &p)
