@@ -185,7 +185,11 @@ bool small_plan(const Shape &s, SmallParams &p)
     if (s.n < 1 || s.n > 5 || s.Ns != s.N) return false;
     if (s.Cin % SM_KC != 0 || s.Cin < 64 || s.Cout < 16 || (s.Cout & 3) != 0) return false;
     const long long Mtot = (long long)s.B * s.E * s.E;
-    if (Mtot > 64) return false;                       // beyond that the tiles of 128 positions are filled well enough
+    // Every block of 16 positions streams the layer's weights once (through L2): worth it while the
+    // positions are few, or the weights small.  Beyond that the tiles of 128 positions, which stage a
+    // weight once for all of them, are the better kernel.
+    const double w_bytes = (double)s.Cin * s.Cout * s.n * s.n * 4.0;
+    if (Mtot > 1024 || (Mtot > 256 && (double)((Mtot + 15) / 16) * w_bytes > 256.0e6)) return false;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout;
     p.q = s.frame;
     p.N0 = s.N - 2 * s.frame;

@@ -755,9 +755,12 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
     (1, 132, 72, 6, 2, 1),      # 2 x 2 kernel, odd padding factor, channel counts that are no powers of two
     (4, 96, 64, 3, 1, 0),       # n = 1: three empty classes whose zeros must be written
     (1, 2048, 1024, 4, 4, 2),   # Table 3, EB-GAN layer 2: 134 MB of weights
+    (1, 256, 128, 16, 4, 2),    # Table 3, DCGAN layer 4 on one sample: 256 positions
+    (1, 256, 128, 32, 4, 2),    # Table 3, EB-GAN layer 5: 1024 positions, small weights
+    (5, 64, 48, 13, 3, 1),      # 5 x 14 x 14 = 980 positions, ragged last block, odd padding factor
 ])
 def test_matrix_cores_on_very_few_positions(B, Cin, Cout, N, n, P):
-    """Layers with at most 64 quad positions in all take position blocks of 16 on the matrix cores,
+    """Layers with few quad positions in all (or small weights) take position blocks of 16 on the matrix cores,
     their reduction split over the chip: against the oracle, reproducible, bit for bit on
     integers with guard words around `out`."""
     layer = wl.Layer("small", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.05)
