@@ -186,10 +186,13 @@ bool small_plan(const Shape &s, SmallParams &p)
     if (s.Cin % SM_KC != 0 || s.Cin < 64 || s.Cout < 16 || (s.Cout & 3) != 0) return false;
     const long long Mtot = (long long)s.B * s.E * s.E;
     // Every block of 16 positions streams the layer's weights once (through L2): worth it while the
-    // positions are few, or the weights small.  Beyond that the tiles of 128 positions, which stage a
-    // weight once for all of them, are the better kernel.
+    // positions are few, or the weights small.  Beyond that the tiles of 128 positions x 128
+    // channels, which stage a weight once for all their positions, are the better kernel
+    // (measured crossover: about 512 MB of weight reads; twice that for layers of at most 64
+    // output channels, which fill only half of such a tile).
     const double w_bytes = (double)s.Cin * s.Cout * s.n * s.n * 4.0;
-    if (Mtot > 1024 || (Mtot > 256 && (double)((Mtot + 15) / 16) * w_bytes > 256.0e6)) return false;
+    const double budget = s.Cout <= 64 ? 1024.0e6 : 512.0e6;
+    if (Mtot > (1 << 20) || (Mtot > 256 && (double)((Mtot + 15) / 16) * w_bytes > budget)) return false;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout;
     p.q = s.frame;
     p.N0 = s.N - 2 * s.frame;

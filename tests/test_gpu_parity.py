@@ -758,6 +758,8 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
     (1, 256, 128, 16, 4, 2),    # Table 3, DCGAN layer 4 on one sample: 256 positions
     (1, 256, 128, 32, 4, 2),    # Table 3, EB-GAN layer 5: 1024 positions, small weights
     (5, 64, 48, 13, 3, 1),      # 5 x 14 x 14 = 980 positions, ragged last block, odd padding factor
+    (1, 128, 64, 64, 4, 2),     # Table 3, EB-GAN layer 6: 4096 positions, half a megabyte of weights
+    (8, 64, 64, 32, 4, 2),      # a small batch of such a layer: 8192 positions
 ])
 def test_matrix_cores_on_very_few_positions(B, Cin, Cout, N, n, P):
     """Layers with few quad positions in all (or small weights) take position blocks of 16 on the matrix cores,
