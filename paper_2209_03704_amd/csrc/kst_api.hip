@@ -1,5 +1,6 @@
 // C ABI of libkst.so: argument validation, path choice, launches.
 #include "kst_internal.h"
+#include "kst_yardstick.h"
 
 #include <mutex>
 
