@@ -45,8 +45,11 @@ __global__ void __launch_bounds__(256) segregate_kernel(const T *__restrict__ w,
 // reads each channel's run as it lies in memory and writes, for every run element, the 64
 // output channels side by side.
 constexpr int S_CO = 64;
-constexpr int S_RUN = 128;
+constexpr int S_RUN = 64;
 
+// VEC: a channel's floats in w are a multiple of 4, so runs are read as 16-byte groups (all of a
+// lane's loads in flight at once).
+template <bool VEC>
 __global__ void __launch_bounds__(256) segregate_tiled_f32_kernel(const float *__restrict__ w, float *__restrict__ w_seg,
                                                                   SegGeom g)
 {
@@ -56,11 +59,33 @@ __global__ void __launch_bounds__(256) segregate_tiled_f32_kernel(const float *_
     const unsigned run = blockIdx.x % runs, co0 = (blockIdx.x / runs) * S_CO;
     const unsigned r0 = run * S_RUN;
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < S_CO * S_RUN; idx += 256) {
-        const unsigned co_l = idx / S_RUN, r = idx % S_RUN;
-        float v = 0.0f;
-        if (co0 + co_l < (unsigned)g.Cout && r0 + r < per_co) v = w[(size_t)(co0 + co_l) * per_co + r0 + r];
-        tile[co_l][r] = v;
+    if constexpr (VEC) {
+        constexpr int G = S_RUN / 4, PER = S_CO * G / 256;        // 16-byte groups per row / per lane
+        float4 v[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int idx = tid + k * 256;
+            const unsigned co_l = idx / G, r = 4 * (idx % G);
+            v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (co0 + co_l < (unsigned)g.Cout && r0 + r < per_co)
+                v[k] = *reinterpret_cast<const float4 *>(w + (size_t)(co0 + co_l) * per_co + r0 + r);
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int idx = tid + k * 256;
+            const unsigned co_l = idx / G, r = 4 * (idx % G);
+            tile[co_l][r] = v[k].x;
+            tile[co_l][r + 1] = v[k].y;
+            tile[co_l][r + 2] = v[k].z;
+            tile[co_l][r + 3] = v[k].w;
+        }
+    } else {
+        for (int idx = tid; idx < S_CO * S_RUN; idx += 256) {
+            const unsigned co_l = idx / S_RUN, r = idx % S_RUN;
+            float v = 0.0f;
+            if (co0 + co_l < (unsigned)g.Cout && r0 + r < per_co) v = w[(size_t)(co0 + co_l) * per_co + r0 + r];
+            tile[co_l][r] = v;
+        }
     }
     __syncthreads();
     const unsigned nn = (unsigned)g.n * g.n;
@@ -96,8 +121,12 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
         const size_t runs = ((size_t)Cin * n * n + S_RUN - 1) / S_RUN;
         const size_t tiles = runs * ((Cout + S_CO - 1) / S_CO);
         if (tiles < 0x7fffffffu) {
-            hipLaunchKernelGGL(segregate_tiled_f32_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, (const float *)w,
-                               (float *)w_seg, g);
+            if (((size_t)Cin * n * n) % 4 == 0)
+                hipLaunchKernelGGL(segregate_tiled_f32_kernel<true>, dim3((unsigned)tiles), dim3(256), 0, stream,
+                                   (const float *)w, (float *)w_seg, g);
+            else
+                hipLaunchKernelGGL(segregate_tiled_f32_kernel<false>, dim3((unsigned)tiles), dim3(256), 0, stream,
+                                   (const float *)w, (float *)w_seg, g);
             return hipGetLastError();
         }
     }
