@@ -41,6 +41,9 @@ kst_path choose_path(const Shape &s, kst_dtype dt)
 {
     const bool ok = is16(dt) ? igemm_bf16_supported(s) : igemm_f32_supported(s);
     if (ok && s.Cout >= 16 && s.Cin >= 8) return KST_PATH_IGEMM;
+    // One sample of a generator's output layer (many input channels, three output channels): the
+    // position-block kernel splits its reduction over the chip, the direct kernel has four tiles.
+    if (dt == KST_F32 && s.Cout < 16 && igemm_f32_small_supported(s)) return KST_PATH_IGEMM;
     return KST_PATH_DIRECT;
 }
 

@@ -38,7 +38,9 @@ struct SmallParams {
     Epilogue epi;
 };
 
-template <int n>
+// V4: Cout is a multiple of 4 and the weights are read as 16-byte groups; otherwise (the 128 -> 3
+// output layer of a generator) one value at a time, rows past Cout reading the last channel again.
+template <int n, bool V4>
 __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__restrict__ in, const float *__restrict__ w_seg,
                                                                float *__restrict__ dst, SmallParams p)
 {
@@ -79,7 +81,10 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
     // ci0 + k, as one 16-byte group; value j is its row (m) of row block j.  Groups past Cout (the
     // last block of a ragged layer; Cout is a multiple of 4) read the last group again: their
     // accumulator rows are never stored.
-    const unsigned w_col = (unsigned)min(co0 + 4 * m, p.Cout - 4);
+    const unsigned w_col = V4 ? (unsigned)min(co0 + 4 * m, p.Cout - 4) : 0u;
+    unsigned w_cols[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w_cols[j] = (unsigned)min(co0 + 4 * m + j, p.Cout - 1);
 
     const int c_begin = split * p.chunks_per_split;
     const int c_end = min(p.chunks, c_begin + p.chunks_per_split);
@@ -110,7 +115,11 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
             const unsigned Tp = (unsigned)class_taps(n, cls);
             const unsigned t = (unsigned)(T - class_tap_base(n, cls));
             const unsigned row = p.off[cls] + (ci * Tp + t) * (unsigned)p.Cout;
-            wf[buf][T] = *reinterpret_cast<const float4 *>(w_seg + row + w_col);     // 16-byte aligned: offsets are multiples of 4
+            if constexpr (V4)
+                wf[buf][T] = *reinterpret_cast<const float4 *>(w_seg + row + w_col);     // 16-byte aligned: offsets are multiples of 4
+            else
+                wf[buf][T] = make_float4(w_seg[row + w_cols[0]], w_seg[row + w_cols[1]], w_seg[row + w_cols[2]],
+                                         w_seg[row + w_cols[3]]);
         }
     };
     auto multiply = [&](auto bufc) {
@@ -183,7 +192,7 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
 bool small_plan(const Shape &s, SmallParams &p)
 {
     if (s.n < 1 || s.n > 5 || s.Ns != s.N) return false;
-    if (s.Cin % SM_KC != 0 || s.Cin < 64 || s.Cout < 16 || (s.Cout & 3) != 0) return false;
+    if (s.Cin % SM_KC != 0 || s.Cin < 64) return false;
     const long long Mtot = (long long)s.B * s.E * s.E;
     // Every block of 16 positions streams the layer's weights once (through L2): worth it while the
     // positions are few, or the weights small.  Beyond that the tiles of 128 positions x 128
@@ -193,6 +202,9 @@ bool small_plan(const Shape &s, SmallParams &p)
     const double w_bytes = (double)s.Cin * s.Cout * s.n * s.n * 4.0;
     const double budget = s.Cout <= 64 ? 1024.0e6 : 512.0e6;
     if (Mtot > (1 << 20) || (Mtot > 256 && (double)((Mtot + 15) / 16) * w_bytes > budget)) return false;
+    // Fewer than 16 output channels leave most of a 64-row block empty: only where the padded
+    // multiply-adds are still next to nothing for the chip (about 5 us of matrix-core work).
+    if (s.Cout < 16 && (double)((Mtot + 15) / 16) * 16.0 * 64.0 * s.Cin * s.n * s.n > 4.0e8) return false;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout;
     p.q = s.frame;
     p.N0 = s.N - 2 * s.frame;
@@ -221,7 +233,10 @@ template <int n>
 hipError_t launch_small_n(const float *in, const float *w_seg, float *dst, const SmallParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)(p.pos_blocks * p.co_blocks * p.splits);
-    hipLaunchKernelGGL(igemm_f32_small_kernel<n>, dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+    if ((p.Cout & 3) == 0)
+        hipLaunchKernelGGL((igemm_f32_small_kernel<n, true>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+    else
+        hipLaunchKernelGGL((igemm_f32_small_kernel<n, false>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
     return hipGetLastError();
 }
 

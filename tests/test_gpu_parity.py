@@ -763,6 +763,8 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
     (1, 256, 128, 16, 4, 2),    # Table 3, DCGAN layer 4 on one sample: 256 positions
     (1, 256, 128, 32, 4, 2),    # Table 3, EB-GAN layer 5: 1024 positions, small weights
     (5, 64, 48, 13, 3, 1),      # 5 x 14 x 14 = 980 positions, ragged last block, odd padding factor
+    (1, 128, 3, 32, 4, 2),      # Table 3, the generators' output layer on one sample: three of a block's 64 channels
+    (1, 64, 5, 16, 3, 1),       # five output channels (weights read one value at a time), odd padding factor
     (1, 128, 64, 64, 4, 2),     # Table 3, EB-GAN layer 6: 4096 positions, half a megabyte of weights
     (8, 64, 64, 32, 4, 2),      # a small batch of such a layer: 8192 positions
 ])
