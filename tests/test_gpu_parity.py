@@ -1092,6 +1092,67 @@ def test_forward_seeded_shapes_on_every_path_that_takes_them(B, Cin, Cout, N, n,
     assert "auto" in ran and "direct" in ran
 
 
+def _seeded_frame_and_epilogue_shapes(count, seed):
+    """fp32 layers aimed at the kernels that supply the zero frame themselves and shift their
+    stores for odd padding factors -- the flat-output kernel (one or three input channels, maps
+    that are multiples of 4), the multi-channel direct kernel, the pipelined matrix-core kernel
+    (channel counts that are multiples of 4), the position-block kernel (64 and more input
+    channels, few positions) -- each with a random bias and activation."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        kind = int(rng.integers(0, 4))
+        n = int(rng.integers(2, 6))
+        P = int(rng.integers(0, 6))
+        act = int(rng.integers(0, 3))
+        bias = bool(rng.integers(0, 2))
+        if kind == 0:        # flat-output kernel
+            Cin, Cout = int(rng.choice([1, 3])), int(rng.choice([1, 2, 3]))
+            N = int(rng.choice([48, 52, 64, 100, 132]))
+            B = int(rng.integers(1, 4)) if Cin == 1 else int(rng.choice([260, 300]))
+            if Cin == 3 and N > 64:
+                continue
+        elif kind == 1:      # multi-channel direct kernel
+            Cin, Cout = int(rng.choice([2, 5, 20, 33, 64, 100])), int(rng.choice([1, 2, 3, 4, 6]))
+            N, B = int(rng.choice([5, 9, 16, 30, 37])), int(rng.integers(1, 4))
+        elif kind == 2:      # pipelined matrix-core kernel
+            Cin, Cout = int(rng.choice([8, 16, 32, 48])), int(rng.choice([16, 32, 64, 132]))
+            N, B = int(rng.choice([4, 8, 12, 16, 20])), int(rng.choice([4, 8, 16]))
+        else:                # position blocks of 16
+            Cin, Cout = int(rng.choice([64, 96, 128, 256])), int(rng.choice([3, 16, 48, 64, 100]))
+            N, B = int(rng.choice([2, 3, 4, 6, 8, 12])), int(rng.integers(1, 4))
+        if 2 * N + 2 * P - n < 1 or B * Cin * Cout * (2 * N + 2 * P) ** 2 * n * n > 2.5e9:
+            continue
+        shapes.append((B, Cin, Cout, N, n, P, act, bias))
+    return shapes
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,act,bias", _seeded_frame_and_epilogue_shapes(48, 20261128))
+def test_seeded_padded_layers_with_bias_and_activation(B, Cin, Cout, N, n, P, act, bias):
+    layer = wl.Layer("frame_seeded", B, Cin, Cout, N, n, "f32", "normal", w_std=0.2)
+    x, w = wl.make_tensors(layer, 9500 + 31 * N + 7 * n + P + Cin)
+    gen = torch.Generator().manual_seed(N + n + P + Cout)
+    bvec = torch.randn((Cout,), generator=gen, dtype=torch.float32) if bias else None
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    want = oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), None if bvec is None else bvec.numpy().astype(np.float64),
+                                   act, P)
+    scale = max(1.0, np.abs(oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w),
+                                                    None if bvec is None else bvec.numpy().astype(np.float64), 0, P)).max())
+    ran = []
+    for name, code in (("auto", kst.KST_PATH_AUTO), ("direct", kst.KST_PATH_DIRECT), ("igemm", kst.KST_PATH_IGEMM)):
+        try:
+            got = kst.kst_forward_seg_epilogue(xd, w_seg, Cout, n, None if bvec is None else bvec.to(DEV), act, P, path=code)
+        except kst.KstError:
+            assert name == "igemm", name
+            continue
+        torch.cuda.synchronize()
+        ran.append(name)
+        assert got.shape == want.shape
+        err = np.abs(got.cpu().numpy() - want).max()
+        assert err <= 2e-5 * scale, "%s: abs err %.3e (scale %.3g)" % (name, err, scale)
+    assert "auto" in ran and "direct" in ran
+
+
 # ----------------------------------------------------------------------------
 # Half-precision operands: the 16-bit kernels with the other multiply
 # ----------------------------------------------------------------------------
