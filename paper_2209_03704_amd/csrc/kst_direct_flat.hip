@@ -160,74 +160,100 @@ __device__ __forceinline__ void flat_group(float (&o)[4], const float *__restric
     }
 }
 
-// The same group summed over the CI staged input channels (chan: floats between two channels' rows in LDS).
-template <int n, int r, int par, int CI>
-__device__ __forceinline__ void flat_group_ci(float (&o)[4], const float *__restrict__ rowp, int xs_stride, int chan,
-                                              int cbase, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
-{
-    flat_group<n, r, par, false>(o, rowp, xs_stride, cbase, wk[0]);
-#pragma unroll
-    for (int c = 1; c < CI; ++c) flat_group<n, r, par, true>(o, rowp + c * chan, xs_stride, cbase, wk[c]);
-}
-
-// (r, par) selected at run time; rowp points at the group's first tap row, column 0 of the map.
-template <int n, int CI>
-__device__ __forceinline__ void flat_group_rp(float (&o)[4], const float *__restrict__ rowp, const FlatParams &p, int r,
-                                              int x0, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)])
-{
-    if (x0 & 1) {
-        const int cbase = ((x0 - 1) >> 1) + 1;
-        if (r) flat_group_ci<n, 1, 1, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
-        else flat_group_ci<n, 0, 1, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
-    } else {
-        const int cbase = x0 >> 1;
-        if (r) flat_group_ci<n, 1, 0, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
-        else flat_group_ci<n, 0, 0, CI>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk);
-    }
-}
-
-// Outputs of the group at (row y, first column x0), x0 in [-3, M).  pad0: LDS column of the map's column 0.
-template <int n, int CI>
-__device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
-                                               int ia, int y, int x0,
-                                               const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)], int sh = 0)
-{
-    y += sh;
-    const int r = y & 1;
-    flat_group_rp<n, CI>(o, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0, p, r, x0 + sh, wk);
-}
-
-// Segment = the 256 consecutive floats one wave covers in one iteration; it starts at
-// (row y, column xs) and crosses exactly one row end.  Lanes left of the row end compute
-// their group in row y, lanes right of it in row y + 1, the lane on it both.
-template <int n, int CI>
-__device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
-                                              int ia, int y, int xs, int lane,
-                                              const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)], int sh = 0)
-{
-    const int x0 = xs + 4 * lane;
-    float oa[4] = {0.f, 0.f, 0.f, 0.f}, ob[4] = {0.f, 0.f, 0.f, 0.f};
-    if (x0 < p.M) {
-        const int ys = y + sh, r = ys & 1;
-        flat_group_rp<n, CI>(oa, Xs + ((ys >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk);
-    }
-    if (x0 + 3 >= p.M) {
-        const int y1 = y + 1 + sh, xs1 = xs - p.M + sh;              // negative column: head of the next row
-        const int r = y1 & 1;
-        flat_group_rp<n, CI>(ob, Xs + ((y1 >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs1, wk);
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) o[k] = x0 + k < p.M ? oa[k] : ob[k];
-}
-
 // Sub-kernel (r, s) of input channel c and output channel co, from the segregated weights [class][Cin][tap][Cout].
 template <int n, int r, int s>
 __device__ __forceinline__ void flat_load_class(float (&w)[((n + 1) / 2) * ((n + 1) / 2)], const float *__restrict__ w_seg,
                                                 unsigned off, int c, int co, int Cout)
 {
     constexpr int T = (r ? n / 2 : (n + 1) / 2) * (s ? n / 2 : (n + 1) / 2);
+    const float *base = w_seg + off;
 #pragma unroll
-    for (int t = 0; t < T; ++t) w[t] = w_seg[off + (unsigned)((c * T + t) * Cout + co)];
+    for (int t = 0; t < T; ++t) w[t] = base[(c * T + t) * Cout + co];
+}
+
+// Where the sub-kernels of all input channels do not fit the scalar registers (three channels of a
+// 5 x 5 kernel are 75 values; kept resident they spill into vector-register lanes, and every
+// multiply-add then pays a lane read first), a group fetches the two sub-kernels of its row parity
+// from memory when it needs them: scalar loads that the scalar cache serves.  One output channel only
+// (then a channel's taps are consecutive in the segregated layout and load as wide scalar loads).
+struct WeightSource {
+    const float *w_seg;
+    unsigned off[4];
+};
+
+// The same group summed over the CI staged input channels (chan: floats between two channels' rows in LDS).
+template <int n, int r, int par, int CI, bool WMEM>
+__device__ __forceinline__ void flat_group_ci(float (&o)[4], const float *__restrict__ rowp, int xs_stride, int chan,
+                                              int cbase, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)],
+                                              const WeightSource &ws)
+{
+    if constexpr (WMEM) {
+#pragma unroll
+        for (int c = 0; c < CI; ++c) {
+            float w[2][2][((n + 1) / 2) * ((n + 1) / 2)];
+            flat_load_class<n, r, 0>(w[r][0], ws.w_seg, ws.off[2 * r], c, 0, 1);
+            flat_load_class<n, r, 1>(w[r][1], ws.w_seg, ws.off[2 * r + 1], c, 0, 1);
+            if (c == 0) flat_group<n, r, par, false>(o, rowp, xs_stride, cbase, w);
+            else flat_group<n, r, par, true>(o, rowp + c * chan, xs_stride, cbase, w);
+        }
+    } else {
+        flat_group<n, r, par, false>(o, rowp, xs_stride, cbase, wk[0]);
+#pragma unroll
+        for (int c = 1; c < CI; ++c) flat_group<n, r, par, true>(o, rowp + c * chan, xs_stride, cbase, wk[c]);
+    }
+}
+
+// (r, par) selected at run time; rowp points at the group's first tap row, column 0 of the map.
+template <int n, int CI, bool WMEM>
+__device__ __forceinline__ void flat_group_rp(float (&o)[4], const float *__restrict__ rowp, const FlatParams &p, int r,
+                                              int x0, const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)],
+                                              const WeightSource &ws)
+{
+    if (x0 & 1) {
+        const int cbase = ((x0 - 1) >> 1) + 1;
+        if (r) flat_group_ci<n, 1, 1, CI, WMEM>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk, ws);
+        else flat_group_ci<n, 0, 1, CI, WMEM>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk, ws);
+    } else {
+        const int cbase = x0 >> 1;
+        if (r) flat_group_ci<n, 1, 0, CI, WMEM>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk, ws);
+        else flat_group_ci<n, 0, 0, CI, WMEM>(o, rowp, p.xs_stride, p.chan_lds, cbase, wk, ws);
+    }
+}
+
+// Outputs of the group at (row y, first column x0), x0 in [-3, M).  pad0: LDS column of the map's column 0.
+template <int n, int CI, bool WMEM>
+__device__ __forceinline__ void flat_row_group(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
+                                               int ia, int y, int x0,
+                                               const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)],
+                                               const WeightSource &ws, int sh = 0)
+{
+    y += sh;
+    const int r = y & 1;
+    flat_group_rp<n, CI, WMEM>(o, Xs + ((y >> 1) - ia + r) * p.xs_stride + pad0, p, r, x0 + sh, wk, ws);
+}
+
+// Segment = the 256 consecutive floats one wave covers in one iteration; it starts at
+// (row y, column xs) and crosses exactly one row end.  Lanes left of the row end compute
+// their group in row y, lanes right of it in row y + 1, the lane on it both.
+template <int n, int CI, bool WMEM>
+__device__ __forceinline__ void cross_segment(float (&o)[4], const float *__restrict__ Xs, const FlatParams &p, int pad0,
+                                              int ia, int y, int xs, int lane,
+                                              const float (&wk)[CI][2][2][((n + 1) / 2) * ((n + 1) / 2)],
+                                              const WeightSource &ws, int sh = 0)
+{
+    const int x0 = xs + 4 * lane;
+    float oa[4] = {0.f, 0.f, 0.f, 0.f}, ob[4] = {0.f, 0.f, 0.f, 0.f};
+    if (x0 < p.M) {
+        const int ys = y + sh, r = ys & 1;
+        flat_group_rp<n, CI, WMEM>(oa, Xs + ((ys >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk, ws);
+    }
+    if (x0 + 3 >= p.M) {
+        const int y1 = y + 1 + sh, xs1 = xs - p.M + sh;              // negative column: head of the next row
+        const int r = y1 & 1;
+        flat_group_rp<n, CI, WMEM>(ob, Xs + ((y1 >> 1) - ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs1, wk, ws);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = x0 + k < p.M ? oa[k] : ob[k];
 }
 
 // Rows of the zero frame above or below the rows a piece finds in memory (pieces at the top and
@@ -246,7 +272,7 @@ __device__ __forceinline__ void clear_frame_rows(float *X, const FlatParams &p, 
     }
 }
 
-template <int n, int CI, bool FRAME>
+template <int n, int CI, bool FRAME, bool WMEM>
 __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ w_seg,
                                                                   float *__restrict__ out, FlatParams p)
@@ -329,7 +355,8 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     }
     __syncthreads();
 
-    float wk[CI][2][2][Ta0 * Ta0];
+    float wk[CI][2][2][Ta0 * Ta0];                           // WMEM: unused
+    WeightSource ws = {w_seg, {p.off[0], p.off[1], p.off[2], p.off[3]}};
     int cur_co = -1;
     const bool epi = epi_on(p.epi);
     float bias = 0.0f;
@@ -366,7 +393,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
         const int co = p.Cout == 1 ? 0 : (int)((unsigned)pc.plane % (unsigned)p.Cout);
         if (co != cur_co) {
 #pragma unroll
-            for (int c = 0; c < CI; ++c) {
+            for (int c = 0; c < (WMEM ? 0 : CI); ++c) {
                 flat_load_class<n, 0, 0>(wk[c][0][0], w_seg, p.off[0], c, co, p.Cout);
                 flat_load_class<n, 0, 1>(wk[c][0][1], w_seg, p.off[1], c, co, p.Cout);
                 flat_load_class<n, 1, 0>(wk[c][1][0], w_seg, p.off[2], c, co, p.Cout);
@@ -387,11 +414,14 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
 #pragma unroll 1
             for (int it = 0; it < (int)(p.CH / F_STEP); ++it) {
                 float o[4];
+                // (the offsets pass through an empty statement the compiler cannot see through, or it
+                // would move the weight loads out of the loop and keep every value resident again)
+                if constexpr (WMEM) asm volatile("" : "+s"(ws.off[0]), "+s"(ws.off[1]), "+s"(ws.off[2]), "+s"(ws.off[3]));
                 if (xs + 255 < p.M) {
                     const int ys = y + sh, r = ys & 1;
-                    flat_group_rp<n, CI>(o, Xs + ((ys >> 1) - pc.ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk);
+                    flat_group_rp<n, CI, WMEM>(o, Xs + ((ys >> 1) - pc.ia + r) * p.xs_stride + pad0 + 2 * lane, p, r, xs + sh, wk, ws);
                 } else {
-                    cross_segment<n, CI>(o, Xs, p, pad0, pc.ia, y, xs, lane, wk, sh);
+                    cross_segment<n, CI, WMEM>(o, Xs, p, pad0, pc.ia, y, xs, lane, wk, ws, sh);
                 }
                 flat_epilogue(o, epi, bias, p.epi.act);
                 store_streaming(out + fw + 4 * lane, o);
@@ -415,14 +445,15 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                 x0 = (int)(relp - q * (unsigned)p.M);
             }
             for (int it = it0; it <= it1; ++it) {
+                if constexpr (WMEM) asm volatile("" : "+s"(ws.off[0]), "+s"(ws.off[1]), "+s"(ws.off[2]), "+s"(ws.off[3]));
                 if (f0 + 3 >= pc.fa && f0 < pc.fb) {
                     // A group hanging over the start of the plane is the head of row 0 (negative column).
                     const int yy = y < 0 ? 0 : y, xx = y < 0 ? x0 - p.M : x0;
                     float o[4];
-                    flat_row_group<n, CI>(o, Xs, p, pad0, pc.ia, yy, xx, wk, sh);
+                    flat_row_group<n, CI, WMEM>(o, Xs, p, pad0, pc.ia, yy, xx, wk, ws, sh);
                     if (xx + 3 >= p.M && yy + 1 <= pc.yb) {      // straddles a row end: head of the next row
                         float o2[4];
-                        flat_row_group<n, CI>(o2, Xs, p, pad0, pc.ia, yy + 1, xx - p.M, wk, sh);
+                        flat_row_group<n, CI, WMEM>(o2, Xs, p, pad0, pc.ia, yy + 1, xx - p.M, wk, ws, sh);
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
                             if (xx + k >= p.M) o[k] = o2[k];
@@ -461,17 +492,27 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     }
 }
 
+template <int n, int CI, bool FRAME, bool WMEM>
+hipError_t launch_variant(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
+                          hipStream_t stream)
+{
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_flat_kernel<n, CI, FRAME, WMEM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((direct_flat_kernel<n, CI, FRAME, WMEM>), dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
+    return hipGetLastError();
+}
+
 template <int n, int CI, bool FRAME>
 hipError_t launch_kernel(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
                          hipStream_t stream)
 {
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_flat_kernel<n, CI, FRAME>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((direct_flat_kernel<n, CI, FRAME>), dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
-    return hipGetLastError();
+    // More sub-kernel values than the scalar registers hold beside the kernel's bookkeeping: fetched per group.
+    if constexpr (CI * n * n > 40)
+        if (p.Cout == 1) return launch_variant<n, CI, FRAME, true>(in, w_seg, out, p, grid, lds, stream);
+    return launch_variant<n, CI, FRAME, false>(in, w_seg, out, p, grid, lds, stream);
 }
 
 // One input channel with or without a frame, three (the image layers of Tables 1-2) likewise.
