@@ -22,6 +22,7 @@ struct FlatParams {
     unsigned run;           // consecutive blocks handed to one XCD (1: plain blockIdx order)
     int fast;               // M >= 256: a wave's 256 floats cross at most one row end
     int max_rows;           // input rows one piece can need
+    int npre;               // 16-byte loads a lane keeps in flight for the next piece
     int xs_stride, xs_buf;  // floats per staged row / per LDS buffer
     unsigned off[4];        // element offset of W_p in the segregated weights
     Epilogue epi;

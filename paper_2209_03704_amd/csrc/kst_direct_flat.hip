@@ -272,13 +272,12 @@ __device__ __forceinline__ void clear_frame_rows(float *X, const FlatParams &p, 
     }
 }
 
-template <int n, int CI, bool FRAME, bool WMEM>
+template <int n, int CI, bool FRAME, bool WMEM, int NPRE>
 __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__restrict__ in,
                                                                   const float *__restrict__ w_seg,
                                                                   float *__restrict__ out, FlatParams p)
 {
     constexpr int Ta0 = (n + 1) / 2, Ta1 = n / 2;
-    constexpr int NPRE = flat_npre(CI);
     extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 x [CI][max_rows][xs_stride]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -492,27 +491,39 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
     }
 }
 
-template <int n, int CI, bool FRAME, bool WMEM>
+template <int n, int CI, bool FRAME, bool WMEM, int NPRE>
 hipError_t launch_variant(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
                           hipStream_t stream)
 {
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_flat_kernel<n, CI, FRAME, WMEM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&direct_flat_kernel<n, CI, FRAME, WMEM, NPRE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((direct_flat_kernel<n, CI, FRAME, WMEM>), dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
+    hipLaunchKernelGGL((direct_flat_kernel<n, CI, FRAME, WMEM, NPRE>), dim3(grid), dim3(F_THREADS), lds, stream, in, w_seg, out, p);
     return hipGetLastError();
+}
+
+template <int n, int CI, bool FRAME, int NPRE>
+hipError_t launch_npre(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
+                       hipStream_t stream)
+{
+    // More sub-kernel values than the scalar registers hold beside the kernel's bookkeeping: fetched per group.
+    if constexpr (CI * n * n > 40)
+        if (p.Cout == 1) return launch_variant<n, CI, FRAME, true, NPRE>(in, w_seg, out, p, grid, lds, stream);
+    return launch_variant<n, CI, FRAME, false, NPRE>(in, w_seg, out, p, grid, lds, stream);
 }
 
 template <int n, int CI, bool FRAME>
 hipError_t launch_kernel(const float *in, const float *w_seg, float *out, const FlatParams &p, unsigned grid, size_t lds,
                          hipStream_t stream)
 {
-    // More sub-kernel values than the scalar registers hold beside the kernel's bookkeeping: fetched per group.
-    if constexpr (CI * n * n > 40)
-        if (p.Cout == 1) return launch_variant<n, CI, FRAME, true>(in, w_seg, out, p, grid, lds, stream);
-    return launch_variant<n, CI, FRAME, false>(in, w_seg, out, p, grid, lds, stream);
+    if constexpr (CI == 1) {
+        return launch_npre<n, CI, FRAME, 2>(in, w_seg, out, p, grid, lds, stream);
+    } else {
+        if (p.npre == 3) return launch_npre<n, CI, FRAME, 3>(in, w_seg, out, p, grid, lds, stream);
+        return launch_npre<n, CI, FRAME, 6>(in, w_seg, out, p, grid, lds, stream);
+    }
 }
 
 // One input channel with or without a frame, three (the image layers of Tables 1-2) likewise.
@@ -540,18 +551,29 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     if (dt != KST_F32 || (s.Cin != 1 && s.Cin != 3) || s.n > 7 || N0 < 4 || (N0 & 3) != 0 || s.Ns != s.N) return false;
     if (q < 0 || q > 4 || (q > 0 && s.n < 2)) return false;
     if (s.crop != 0 && (s.crop != 1 || q == 0)) return false;
-    const int npre = flat_npre(s.Cin);
+    int npre = flat_npre(s.Cin);
     const int M = s.M - 2 * s.crop;                             // edge of the planes that are written
     if (M < 1) return false;
     const long long MM = (long long)M * M;
-    // Blocks of 8192 outputs; of 4096 where three channels' rows for 8192 do not fit the prefetch
-    // registers and two workgroups' LDS buffers (narrow blocks re-read more halo rows).
+    // One input channel: blocks of 8192 outputs, three workgroups per CU.  Three channels: blocks of
+    // 4096 where their rows fit three prefetch loads per lane and a third of the LDS, again three
+    // workgroups per CU (measured against blocks of 8192 at two per CU, whose prefetch registers
+    // leave room for four waves per SIMD only: Table 1's 5 x 5 kernel at a batch of 256 119 -> 107 us,
+    // the 3 x 3 kernel unchanged; the narrow blocks re-read more halo rows, from L2); otherwise
+    // 8192 at two per CU, or 4096 at two per CU where the rows for 8192 fit neither.
     unsigned CH = 8192;
+    int per_cu = s.Cin == 1 ? 3 : 2;
     if (s.Cin > 1) {
-        const int rows = (int)((CH - 1 + M - 1) / M) / 2 + 1 + s.fl + 1;
         const size_t stride = (size_t)((8 + s.N + F_PAD + 3) & ~3);
-        if ((size_t)s.Cin * rows * N0 > (size_t)F_THREADS * npre * 4 || 2 * 2 * s.Cin * rows * stride * sizeof(float) > 160 * 1024)
+        const int rows = (int)((CH - 1 + M - 1) / M) / 2 + 1 + s.fl + 1;
+        const int rows_half = (int)((CH / 2 - 1 + M - 1) / M) / 2 + 1 + s.fl + 1;
+        if ((size_t)s.Cin * rows_half * N0 <= (size_t)F_THREADS * 3 * 4 &&
+            3 * 2 * s.Cin * rows_half * stride * sizeof(float) <= 160 * 1024) {
+            CH = 4096; npre = 3; per_cu = 3;
+        } else if ((size_t)s.Cin * rows * N0 > (size_t)F_THREADS * npre * 4 ||
+                   2 * 2 * s.Cin * rows * stride * sizeof(float) > 160 * 1024) {
             CH = 4096;
+        }
     }
     if (MM < CH || M < 8) return false;                       // a block may touch at most two planes
     p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = M; p.fl = s.fl;
@@ -559,12 +581,13 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     p.q = q; p.N0 = N0;
     p.pad0 = q > 0 ? 8 - q : F_PAD;                             // the tensor's column 0 lands on LDS column 8 (or 4)
     p.CH = CH;
+    p.npre = npre;
     p.MM = (unsigned)MM;
     p.total = (unsigned)((long long)s.B * s.Cout * MM);
     p.nblocks = (p.total + CH - 1) / CH;
     // Three channels: only where every workgroup walks over several blocks.  Below that the many small
     // workgroups of the multi-channel kernel finish sooner (16 images of 224 x 224: 10 us against 12).
-    if (s.Cin > 1 && p.nblocks < 1024) return false;
+    if (s.Cin > 1 && p.total / 8192 < 1024) return false;
     p.fast = M >= 256;
     // Input rows one piece can need: the rows its output span maps to, plus halo.
     const int span = (int)((CH - 1 + M - 1) / M);           // yb - ya at most
@@ -578,9 +601,7 @@ bool direct_flat_plan(const Shape &s, kst_dtype dt, FlatParams &p, unsigned &gri
     lds = (size_t)2 * p.xs_buf * sizeof(float);
     for (int c = 0; c < 4; ++c) p.off[c] = (unsigned)seg_offset(s.Cin, s.Cout, s.n, c, KST_F32);
     p.epi = s.epi;
-    // One resident round on 256 CUs: three 512-lane workgroups per CU with one input channel, two
-    // with three (their prefetch registers and LDS buffers are twice as large).
-    const int per_cu = s.Cin == 1 ? 3 : 2;
+    // One resident round on 256 CUs.
     if (lds * per_cu > 160 * 1024) return false;
     const int wgs = 256 * per_cu;
     grid = (unsigned)wgs;

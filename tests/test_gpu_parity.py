@@ -274,6 +274,8 @@ def test_direct_single_channel_flat_kernel(B, Cout, N, n):
     (253, 3, 2, 64, 7, 4),    # frame of two, largest kernel
     (400, 3, 1, 72, 2, 3),    # odd padding factor: frame of two, rows and columns shifted by one (sub-kernel roles swapped)
     (70, 3, 2, 132, 5, 1),    # odd padding factor on wide maps (M = 261)
+    (15, 3, 1, 384, 3, 0),    # three channels on maps too wide for the half-size blocks: blocks of 8192, two workgroups per CU
+    (8, 3, 1, 512, 5, 2),     # ... and too wide for those as well: half-size blocks at two per CU
     (2, 3, 1, 64, 3, 2),      # too few blocks: the multi-channel kernel
     (2, 1, 2, 64, 5, 2),      # one input channel with a frame (no framed copy of the input any more)
     (1, 1, 1, 512, 5, 2),     # the headline layer's map with a frame
