@@ -47,6 +47,7 @@ struct IgemmParams {
     int q, N0, pad;        // zero frame the kernel supplies; edge of the tensor in memory (N - 2q); LDS column
                            // of the framed map's column 0 (pad + q is a multiple of 4)
     int Mtot;              // B * E * E
+    int tco;               // output channels per workgroup tile: G_TCO, or half of it in the fp32 pipelined kernels
     int tiles_m, tiles_co, splits;
     int ci_per_split;      // multiple of the kernel's channel step
     int lrows;             // input rows (stacked over batch items) held per channel
@@ -57,10 +58,11 @@ struct IgemmParams {
     int crop;              // 1: quad members land one row and one column earlier (odd padding factor)
 };
 
-// kc: input channels staged per step.
-inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
+// kc: input channels staged per step; tco: output channels per workgroup tile.
+inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc, int tco = G_TCO)
 {
     IgemmParams p;
+    p.tco = tco;
     // M: edge of the planes that are written -- with Shape::crop the interior of the map only, whose
     // element (y, x) is the map's (y + 1, x + 1); positions and tiles are those of the whole map.
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N = s.N; p.M = s.M - 2 * s.crop; p.E = s.E;
@@ -72,7 +74,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     p.EE = s.E * s.E;
     p.Mtot = s.B * p.EE;
     p.tiles_m = (p.Mtot + G_TM - 1) / G_TM;
-    p.tiles_co = (s.Cout + G_TCO - 1) / G_TCO;
+    p.tiles_co = (s.Cout + tco - 1) / tco;
     // Rows of one channel that G_TM consecutive positions can touch: the quad rows
     // spanned, the rows skipped at each batch-item boundary, and the window halo.
     const int dg = (G_TM - 2) / s.E + 1;
@@ -88,7 +90,7 @@ inline IgemmParams igemm_plan(const Shape &s, kst_dtype dt, int kc)
     int splits = 1;
     double est;
     {
-        const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / (dt != KST_F32 ? 1.0e12 : 2.0e11);
+        const double tile_s = (double)G_TM * tco * s.Cin * s.n * s.n / (dt != KST_F32 ? 1.0e12 : 2.0e11);
         const double out_b = (double)s.B * s.Cout * p.M * p.M * 4.0;
         double best = (double)((tiles + 255) / 256) * tile_s;
         const double unsplit = best;
@@ -159,11 +161,12 @@ __device__ __forceinline__ void igemm_store_block(float *__restrict__ o, const f
 }
 
 // Store one wave's accumulators: acc[cls][h] covers output channels co_base + 32h .. + 31.
-__device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][2], const IgemmParams &p,
+template <int H>
+__device__ __forceinline__ void igemm_store(float *__restrict__ o, const floatx16 (&acc)[4][H], const IgemmParams &p,
                                             int co_base, int kk, int mb, int mi, int mj, bool final = true)
 {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < H; ++h)
         igemm_store_block(o, acc[0][h], acc[1][h], acc[2][h], acc[3][h], p, co_base + h * 32, kk, mb, mi, mj, final);
 }
 

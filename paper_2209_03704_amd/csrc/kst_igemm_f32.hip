@@ -170,32 +170,34 @@ __device__ __forceinline__ PipeLane pipe_lane(const IgemmParams &p, int tile_m, 
 
 // acc = the tile's sums over input channels [ci_begin, ci_end).  Every thread of the workgroup
 // calls it; LDS is free to be overwritten once all of them have passed a barrier afterwards.
-template <int n, bool DB>
+// H: 32-channel blocks per wave (the workgroup's tile is TCO = 64 H output channels wide).
+template <int n, bool DB, int H>
 __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, const float *__restrict__ w_seg,
                                                 const IgemmParams &p, float *lds, int tile_m, int tile_co,
                                                 int ci_begin, int ci_end, const PipeLane &L, int tid,
-                                                floatx16 (&acc)[4][2])
+                                                floatx16 (&acc)[4][H])
 {
     constexpr int fl = n / 2;
     constexpr int NN = n * n;
-    constexpr int W4 = G_KC * NN * (G_TCO / 4);                  // weight float4 per chunk
+    constexpr int TCO = 64 * H;
+    constexpr int W4 = G_KC * NN * (TCO / 4);                  // weight float4 per chunk
     constexpr int NW4 = (W4 + G_THREADS - 1) / G_THREADS;        // ... per lane
     const int xplane = p.lrows * p.Ns;                           // floats per staged channel (multiple of 4)
     float *Xs = lds;                                             // [G_KC][xplane]
-    float *Ws = lds + G_KC * xplane;                             // [G_KC][NN][G_TCO]
+    float *Ws = lds + G_KC * xplane;                             // [G_KC][NN][TCO]
 
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, kk = lane >> 5;
     const int wco = wave & 1;
 
     const int m0 = tile_m * G_TM;
-    const int co0 = tile_co * G_TCO;
+    const int co0 = tile_co * TCO;
     const int b0 = m0 / p.EE;
     const int i0 = (m0 - b0 * p.EE) / p.E;
     const int R0 = b0 * p.N + i0;
 
     const int xbase = ((L.mb * p.N + L.mi) - R0) * p.Ns + p.pad + L.mj + kk * xplane;
-    const int wbase = kk * (NN * G_TCO) + wco * 64 + l32;
+    const int wbase = kk * (NN * TCO) + wco * (32 * H) + l32;
 
     // ---- staging plan: where each of this lane's float4 comes from and goes to -------------
     // Cin is a multiple of G_KC here, so a chunk is either whole or past the end.  A lane with
@@ -207,8 +209,8 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
 #pragma unroll
     for (int k = 0; k < NW4; ++k) {
         const int e4 = tid + k * G_THREADS;
-        const int tco4 = e4 & (G_TCO / 4 - 1);
-        const int rest = e4 / (G_TCO / 4);
+        const int tco4 = e4 & (TCO / 4 - 1);
+        const int rest = e4 / (TCO / 4);
         const int T = rest % NN, c = rest / NN;
         int cls = 0;
 #pragma unroll
@@ -253,14 +255,14 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < H; ++h)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[c][h][v] = 0.0f;
 
     // With two LDS stages (DB) chunk k + 1 is written into the other stage while chunk k is
     // multiplied, and one barrier per chunk is enough; with one stage the writes wait between
     // two barriers at the end of the chunk.
-    const int stage_floats = DB ? G_KC * (xplane + NN * G_TCO) : 0;
+    const int stage_floats = DB ? G_KC * (xplane + NN * TCO) : 0;
     int cur = 0;                                    // float offset of the stage being multiplied
     // A lane stages NW4 + P_NX4 float4 per chunk ("items": weights first, then input), each
     // through a register of its own: item -> LDS at float offset `at`, and item <- global memory
@@ -320,7 +322,7 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     // DB: item j goes to LDS (and is refilled) behind tap Q_WRITE + j, so that the staging
     // instructions are spread over the MFMAs instead of holding them up in one block.
     constexpr int Q_WRITE = STEPS * NN > ITEMS + 1 ? STEPS * NN - ITEMS - 1 : 0;
-    float xf[2][fl + 1][fl + 1], wf[2][2];
+    float xf[2][fl + 1][fl + 1], wf[2][H];
     auto read_x = [&](auto stc) {
         constexpr int st = decltype(stc)::value;
 #pragma unroll
@@ -331,8 +333,8 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     };
     auto read_w = [&](auto qc) {                    // the two weight values of tap q of the chunk
         constexpr int q = decltype(qc)::value;
-        wf[q & 1][0] = Ws[cur + (2 * (q / NN) * NN + q % NN) * G_TCO + wbase];
-        wf[q & 1][1] = Ws[cur + (2 * (q / NN) * NN + q % NN) * G_TCO + wbase + 32];
+#pragma unroll
+        for (int h = 0; h < H; ++h) wf[q & 1][h] = Ws[cur + (2 * (q / NN) * NN + q % NN) * TCO + wbase + 32 * h];
     };
 
     for (int ci0 = ci_begin; ci0 < ci_end; ci0 += G_KC) {
@@ -354,7 +356,7 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
             constexpr int Tb = taps_for_parity(n, sp);
             constexpr int a = local / Tb, bq = local - a * Tb;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < H; ++h)
                 acc[cls][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[q & 1][h], xf[st & 1][r + a][sp + bq],
                                                                    acc[cls][h], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -383,7 +385,7 @@ __device__ __forceinline__ void pipe_accumulate(const float *__restrict__ in, co
     }
 }
 
-template <int n, bool DB>
+template <int n, bool DB, int H>
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *__restrict__ in,
                                                                      const float *__restrict__ w_seg,
                                                                      float *__restrict__ dst, IgemmParams p)
@@ -398,11 +400,12 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
     const int ci_end = min(p.Cin, ci_begin + p.ci_per_split);
 
     const PipeLane L = pipe_lane(p, tile_m, threadIdx.x);
-    floatx16 acc[4][2];
-    pipe_accumulate<n, DB>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
+    floatx16 acc[4][H];
+    pipe_accumulate<n, DB, H>(in, w_seg, p, lds, tile_m, tile_co, ci_begin, ci_end, L, (int)threadIdx.x, acc);
     if (!L.m_valid) return;
     const int wave = threadIdx.x >> 6, kk = (threadIdx.x & 63) >> 5;
-    igemm_store(dst + (size_t)split * p.out_elems, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj, p.splits == 1);
+    igemm_store<H>(dst + (size_t)split * p.out_elems, acc, p, (tile_co * 2 + (wave & 1)) * (32 * H), kk, L.mb, L.mi, L.mj,
+                   p.splits == 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -417,7 +420,8 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_pipe_kernel(const float *
 // every tile that has more than one contributor in workgroup order (deterministic) and stores.
 // ---------------------------------------------------------------------------
 constexpr int SK_GRID = 256;                                  // CUs of the chip
-constexpr size_t SK_SLOT_FLOATS = (size_t)G_TM * G_TCO * 4;   // one tile's accumulators
+// One tile's accumulators.
+__host__ __device__ constexpr size_t sk_slot_floats(int tco) { return (size_t)G_TM * (size_t)tco * 4; }
 
 struct StreamK {
     int chunks;                // channel chunks per tile
@@ -431,7 +435,7 @@ __device__ __forceinline__ unsigned long long sk_begin(const StreamK &k, int g)
     return (unsigned long long)g * k.units / (unsigned)k.grid;
 }
 
-template <int n, bool DB>
+template <int n, bool DB, int H>
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const float *__restrict__ in,
                                                                         const float *__restrict__ w_seg,
                                                                         float *__restrict__ out, float *__restrict__ ws,
@@ -469,22 +473,22 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
         int tid_p = tid;
         asm volatile("" : "+v"(tid_p));
         const PipeLane L = pipe_lane(p, tile_m, tid_p);
-        floatx16 acc[4][2];
-        pipe_accumulate<n, DB>(in, w_seg, p, lds, tile_m, tile_co, c0 * G_KC, min(p.Cin, c1 * G_KC), L, tid_p, acc);
+        floatx16 acc[4][H];
+        pipe_accumulate<n, DB, H>(in, w_seg, p, lds, tile_m, tile_co, c0 * G_KC, min(p.Cin, c1 * G_KC), L, tid_p, acc);
         if (c0 == 0 && c1 == k.chunks) {
             if (L.m_valid) {
                 const int wave = tid >> 6, kk = (tid & 63) >> 5;
-                igemm_store(out, acc, p, tile_co * G_TCO + (wave & 1) * 64, kk, L.mb, L.mi, L.mj);
+                igemm_store<H>(out, acc, p, (tile_co * 2 + (wave & 1)) * (32 * H), kk, L.mb, L.mi, L.mj);
             }
         } else {
-            float4 *d = reinterpret_cast<float4 *>(ws + (size_t)(2 * g + (first ? 0 : 1)) * SK_SLOT_FLOATS);
+            float4 *d = reinterpret_cast<float4 *>(ws + (size_t)(2 * g + (first ? 0 : 1)) * sk_slot_floats(64 * H));
 #pragma unroll
             for (int c = 0; c < 4; ++c)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < H; ++h)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        d[((c * 2 + h) * 4 + q) * G_THREADS + tid] =
+                        d[((c * H + h) * 4 + q) * G_THREADS + tid] =
                             make_float4(acc[c][h][4 * q], acc[c][h][4 * q + 1], acc[c][h][4 * q + 2], acc[c][h][4 * q + 3]);
         }
         if (!is_whole) {
@@ -494,13 +498,14 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_kernel(const floa
     }
 }
 
-// Two workgroups per tile of the shared list (one per 32-channel half of every wave's block):
+// H workgroups per tile of the shared list (one per 32-channel block of every wave's share, H = tile width / 64):
 // nothing to do when a single workgroup produced the tile; otherwise the sum of its contributors' slots, in workgroup
 // order, goes to the output.
 __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const float *__restrict__ ws,
                                                                             float *__restrict__ out, IgemmParams p, StreamK k)
 {
-    const int rel = blockIdx.x >> 1, h = blockIdx.x & 1, tid = threadIdx.x;   // tile k.whole + rel of the shared list
+    const int H = p.tco >> 6;
+    const int rel = blockIdx.x / H, h = blockIdx.x - rel * H, tid = threadIdx.x;   // tile k.whole + rel of the shared list
     const int tile = k.whole + rel;
     const unsigned long long u0 = (unsigned long long)rel * k.chunks, u1 = u0 + k.chunks - 1;
     auto owner = [&](unsigned long long unit) {
@@ -519,12 +524,12 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const 
     for (int g = g0; g <= g1; ++g) {
         if (sk_begin(k, g) == sk_begin(k, g + 1)) continue;      // an empty range (fewer units than workgroups)
         const int slot = 2 * g + (sk_begin(k, g) < u0 ? 1 : 0);
-        const float4 *d = reinterpret_cast<const float4 *>(ws + (size_t)slot * SK_SLOT_FLOATS);
+        const float4 *d = reinterpret_cast<const float4 *>(ws + (size_t)slot * sk_slot_floats(p.tco));
         float4 v[4][4];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[c][q] = d[((c * 2 + h) * 4 + q) * G_THREADS + tid];
+            for (int q = 0; q < 4; ++q) v[c][q] = d[((c * H + h) * 4 + q) * G_THREADS + tid];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -549,7 +554,7 @@ __global__ void __launch_bounds__(G_THREADS) igemm_f32_streamk_sum_kernel(const 
             acc[c][4 * q + 3] = a[c][q].w;
         }
     const int wave = tid >> 6, kk = (tid & 63) >> 5;
-    igemm_store_block(out, acc[0], acc[1], acc[2], acc[3], p, tile_co * G_TCO + (wave & 1) * 64 + h * 32, kk,
+    igemm_store_block(out, acc[0], acc[1], acc[2], acc[3], p, (tile_co * 2 + (wave & 1)) * (32 * H) + h * 32, kk,
                       L.mb, L.mi, L.mj);
 }
 
@@ -566,7 +571,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *__restr
     out[e] = a;
 }
 
-static IgemmParams plan(const Shape &s) { return igemm_plan(s, KST_F32, G_KC); }
+static IgemmParams plan(const Shape &s, bool force_even = false);
 
 // The pipelined kernels want 16-byte rows, whole channel chunks, and an input chunk that fits
 // P_NX4 loads per lane.
@@ -579,7 +584,7 @@ static bool pipe_ok(const IgemmParams &p)
 
 static size_t lds_bytes(const IgemmParams &p, int n)
 {
-    return (size_t)G_KC * ((size_t)p.lrows * p.Ns + (size_t)n * n * G_TCO) * sizeof(float);
+    return (size_t)G_KC * ((size_t)p.lrows * p.Ns + (size_t)n * n * p.tco) * sizeof(float);
 }
 
 // The pipelined kernels keep two stages in LDS when they fit (n <= 5: the larger kernels have no
@@ -590,10 +595,14 @@ static bool two_stages(const IgemmParams &p, int n)
 }
 
 // The kernels for ordinary layers (tiles of 128 positions); layers with very few positions have a kernel of their own.
+static bool tiles_fit(const IgemmParams &p, int n)
+{
+    return n <= 7 && lds_bytes(p, n) <= 160 * 1024;
+}
+
 static bool tiles_supported(const Shape &s)
 {
-    if (s.n > 7) return false;
-    return lds_bytes(plan(s), s.n) <= 160 * 1024;
+    return tiles_fit(plan(s), s.n);
 }
 
 bool igemm_f32_supported(const Shape &s)
@@ -618,19 +627,21 @@ bool igemm_f32_takes_virtual_frame(const Shape &s)
 struct SkPlan {
     bool use;
     StreamK k;
+    double t;          // the model's time for even shares (seconds), where it was worked out
 };
 
 static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
 {
     SkPlan r;
     r.use = false;
+    r.t = 0.0;
     r.k.chunks = (s.Cin + G_KC - 1) / G_KC;
     const unsigned long long tiles = (unsigned long long)p.tiles_m * p.tiles_co;
     const unsigned long long all_units = tiles * (unsigned)r.k.chunks;
     r.k.grid = all_units < (unsigned long long)SK_GRID ? (int)all_units : SK_GRID;
     r.k.whole = (int)(tiles / SK_GRID) * SK_GRID;             // (0 unless grid == SK_GRID)
     r.k.units = (tiles - r.k.whole) * (unsigned)r.k.chunks;
-    if (!tiles_supported(s) || !pipe_ok(p) || tiles > (1u << 22)) return r;
+    if (!tiles_fit(p, s.n) || !pipe_ok(p) || tiles > (1u << 22)) return r;
     if (force) {
         r.use = true;
         return r;
@@ -651,51 +662,79 @@ static SkPlan streamk_plan(const Shape &s, const IgemmParams &p, bool force)
     }
     // The slots are written while other workgroups still multiply; what shows is about half of
     // their traffic (measured on 64 x 1024 x 512 x 8 x 8, n = 5: 483 us against 514 us for seven splits).
-    const double tile_s = (double)G_TM * G_TCO * s.Cin * s.n * s.n / 2.0e11;
+    const double tile_s = (double)G_TM * p.tco * s.Cin * s.n * s.n / 2.0e11;
     const double longest = (double)(r.k.whole / r.k.grid) * r.k.chunks + (double)((r.k.units + r.k.grid - 1) / r.k.grid);
     // The summing pass walks a tile's contributors one after the other (about 2.5 us each, measured
     // on one-sample layers with 64 and 128 contributors per tile); up to four hide in its launch.
     const unsigned long long shared_tiles = tiles - (unsigned)r.k.whole;
     const double per_tile = shared_tiles ? (double)partial / (double)shared_tiles : 0.0;
     const double serial_sum = per_tile > 4.0 ? (per_tile - 4.0) * 2.5e-6 : 0.0;
-    const double t = longest * tile_s / r.k.chunks + (double)partial * SK_SLOT_FLOATS * 4.0 * 2.0 / 8.0e12 + 5.0e-6 +
+    const double t = longest * tile_s / r.k.chunks + (double)partial * sk_slot_floats(p.tco) * 4.0 * 2.0 / 8.0e12 + 5.0e-6 +
                      serial_sum;
+    r.t = t;
     r.use = t < 0.99 * p.est_s;
     return r;
 }
 
+// Tiles of 128 or of 64 output channels (pipelined kernels only).  Half-width tiles are twice as many, which
+// saves a split of the reduction, or half the work where a layer has 64 output channels; a wave then
+// multiplies every window value it reads into one 32-channel block instead of two.
+static IgemmParams plan(const Shape &s, bool force_even)
+{
+    const IgemmParams wide = igemm_plan(s, KST_F32, G_KC);
+    if (!pipe_ok(wide) || !tiles_fit(wide, s.n)) return wide;
+    const IgemmParams narrow = igemm_plan(s, KST_F32, G_KC, 64);
+    if (s.Cout <= 64) return narrow;
+    if (force_even) return wide;                     // a forced launch does not depend on the cost model
+    // Measured: with tiles to spare the half-width tile costs 5 % (cfg3 844 -> 885 us); where the wide tiles
+    // are fewer than the CUs it wins by halving the split of the reduction (64 x 256 x 128 x 16 x 16, n = 4:
+    // 163 -> 145 us; 64 x 512 x 256 x 8 x 8: 163 -> 156 us).
+    const SkPlan a = streamk_plan(s, wide, false), b = streamk_plan(s, narrow, false);
+    const double ta = a.use ? a.t : wide.est_s, tb = b.use ? b.t : narrow.est_s;
+    const double handicap = wide.tiles_m * wide.tiles_co < SK_GRID ? 1.0 : 1.05;
+    return handicap * tb <= ta ? narrow : wide;
+}
+
 bool igemm_f32_even_shares_possible(const Shape &s)
 {
-    return streamk_plan(s, plan(s), true).use;
+    return streamk_plan(s, plan(s, true), true).use;
 }
 
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even)
 {
     if (!force_even && igemm_f32_small_supported(s)) return igemm_f32_small_workspace_bytes(s);
-    const IgemmParams p = plan(s);
+    const IgemmParams p = plan(s, force_even);
     const SkPlan sk = streamk_plan(s, p, force_even);
-    if (sk.use) return (size_t)2 * sk.k.grid * SK_SLOT_FLOATS * sizeof(float);
+    if (sk.use) return (size_t)2 * sk.k.grid * sk_slot_floats(p.tco) * sizeof(float);
     return p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+}
+
+template <int n, bool DB, int H>
+static hipError_t launch_streamk_h(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
+                                   const StreamK &k, hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_streamk_kernel<n, DB, H>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((igemm_f32_streamk_kernel<n, DB, H>), dim3((unsigned)k.grid), dim3(G_THREADS), lds, stream, in,
+                       w_seg, out, ws, p, k);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const unsigned shared_tiles = (unsigned)(p.tiles_m * p.tiles_co - k.whole);
+    if (shared_tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3((unsigned)H * shared_tiles), dim3(G_THREADS), 0, stream, ws, out, p, k);
+    return hipGetLastError();
 }
 
 template <int n, bool DB>
 static hipError_t launch_streamk_db(const float *in, const float *w_seg, float *out, float *ws, const IgemmParams &p,
                                     const StreamK &k, hipStream_t stream)
 {
-    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_streamk_kernel<n, DB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((igemm_f32_streamk_kernel<n, DB>), dim3((unsigned)k.grid), dim3(G_THREADS), lds, stream, in,
-                       w_seg, out, ws, p, k);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const unsigned shared_tiles = (unsigned)(p.tiles_m * p.tiles_co - k.whole);
-    if (shared_tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(igemm_f32_streamk_sum_kernel, dim3(2u * shared_tiles), dim3(G_THREADS), 0, stream, ws, out, p, k);
-    return hipGetLastError();
+    if (p.tco == 64) return launch_streamk_h<n, DB, 1>(in, w_seg, out, ws, p, k, stream);
+    return launch_streamk_h<n, DB, 2>(in, w_seg, out, ws, p, k, stream);
 }
 
 template <int n>
@@ -707,18 +746,26 @@ static hipError_t launch_streamk_n(const float *in, const float *w_seg, float *o
     return launch_streamk_db<n, false>(in, w_seg, out, ws, p, k, stream);
 }
 
+template <int n, bool DB, int H>
+static hipError_t launch_pipe_h(const float *in, const float *w_seg, float *dst, const IgemmParams &p, unsigned blocks,
+                                hipStream_t stream)
+{
+    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n, DB, H>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((igemm_f32_pipe_kernel<n, DB, H>), dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
+    return hipGetLastError();
+}
+
 template <int n, bool DB>
 static hipError_t launch_pipe_db(const float *in, const float *w_seg, float *dst, const IgemmParams &p, unsigned blocks,
                                  hipStream_t stream)
 {
-    const size_t lds = lds_bytes(p, n) * (DB ? 2 : 1);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&igemm_f32_pipe_kernel<n, DB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((igemm_f32_pipe_kernel<n, DB>), dim3(blocks), dim3(G_THREADS), lds, stream, in, w_seg, dst, p);
-    return hipGetLastError();
+    if (p.tco == 64) return launch_pipe_h<n, DB, 1>(in, w_seg, dst, p, blocks, stream);
+    return launch_pipe_h<n, DB, 2>(in, w_seg, dst, p, blocks, stream);
 }
 
 template <int n>
@@ -747,7 +794,7 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
                             bool force_even, hipStream_t stream)
 {
     if (!force_even && igemm_f32_small_supported(s)) return launch_igemm_f32_small(in, w_seg, out, ws, s, stream);
-    const IgemmParams p = plan(s);
+    const IgemmParams p = plan(s, force_even);
     const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) {
         float *slots = (float *)ws;

@@ -195,12 +195,13 @@ bool small_plan(const Shape &s, SmallParams &p)
     if (s.Cin % SM_KC != 0 || s.Cin < 64) return false;
     const long long Mtot = (long long)s.B * s.E * s.E;
     // Every block of 16 positions streams the layer's weights once (through L2): worth it while the
-    // positions are few, or the weights small.  Beyond that the tiles of 128 positions x 128
+    // positions are few, or the weights small.  Beyond that the tiles of 128 positions x 128 (or 64)
     // channels, which stage a weight once for all their positions, are the better kernel
-    // (measured crossover: about 512 MB of weight reads; twice that for layers of at most 64
-    // output channels, which fill only half of such a tile).
+    // (measured on one sample of Table 3's generators: no layer loses with a limit of 128 MB of
+    // weight reads, and the widest maps gain: 64 x 64 channels on 128 x 128 positions 52.8 -> 40.8 us,
+    // 128 x 64 channels on 64 x 64 positions 37.8 -> 34.3 us).
     const double w_bytes = (double)s.Cin * s.Cout * s.n * s.n * 4.0;
-    const double budget = s.Cout <= 64 ? 1024.0e6 : 512.0e6;
+    const double budget = 128.0e6;
     if (Mtot > (1 << 20) || (Mtot > 256 && (double)((Mtot + 15) / 16) * w_bytes > budget)) return false;
     // Fewer than 16 output channels leave most of a 64-row block empty: only where the padded
     // multiply-adds are still next to nothing for the chip (about 5 us of matrix-core work).

@@ -128,6 +128,15 @@ def layer_by_name(name: str) -> Layer:
     for l in PAPER_LAYERS:
         if l.name == name:
             return l
+    # a generator layer of Table 3 at any batch: table3_<model>_l<k>_<N>to<2N>_b<B>
+    for model in TABLE3_GENERATORS:
+        prefix = "table3_%s_l" % model
+        if name.startswith(prefix) and "_b" in name:
+            tail = name.rsplit("_b", 1)[1]
+            if tail.isdigit():
+                for l, _ in table3_layers(model, int(tail)):
+                    if l.name == name:
+                        return l
     raise KeyError(name)
 
 

@@ -478,6 +478,9 @@ def test_igemm_bf16_row_parity_passes_kernel(B, Cout, dtype, dist):
     (84, 8, 256, 16, 4),     # 258 tiles x 2 chunks: a round of whole tiles, then 4 shared units for 256 workgroups
     (83, 8, 256, 16, 4),     # 256 tiles: whole tiles only, nothing shared and no second pass
     (16, 16, 256, 16, 4),    # 50 tiles x 4 chunks: fewer units than workgroups
+    (40, 64, 64, 16, 4),     # tiles of 64 output channels: 62 tiles x 16 chunks
+    (9, 40, 44, 12, 5),      # ... ragged in the channels (44 of 64), odd M: 8 tiles x 10 chunks
+    (70, 16, 64, 32, 3),     # ... 526 tiles x 4 chunks: two rounds of whole tiles, then 14 tiles shared
 ])
 def test_igemm_f32_even_shares(B, Cin, Cout, N, n):
     """fp32 matrix-core path where the (tile, chunk) list is cut into equal ranges: pieces that
@@ -485,12 +488,14 @@ def test_igemm_f32_even_shares(B, Cin, Cout, N, n):
     layer = wl.Layer("shares", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
     x, w = wl.make_tensors(layer, 900 + Cin + N)
     xd, wd = x.to(DEV), w.to(DEV)
-    # two partial-tile slots of 128 x 128 x 4 floats per workgroup, one workgroup per CU or per unit
+    # two partial-tile slots per workgroup, one workgroup per CU or per unit; a slot is one tile's accumulators:
+    # 128 positions x 4 classes x 128 output channels (64 for layers with up to 64 of them)
     M = 2 * N - n
     E = (M + 1) // 2
-    units = ((B * E * E + 127) // 128) * ((Cout + 127) // 128) * (Cin // 4)
+    tco = 64 if Cout <= 64 else 128
+    units = ((B * E * E + 127) // 128) * ((Cout + tco - 1) // tco) * (Cin // 4)
     assert kst.kst_workspace_bytes(B, Cin, Cout, N, n, kst.KST_F32, kst.KST_PATH_IGEMM_EVEN) == \
-        2 * min(256, units) * 128 * 128 * 4 * 4
+        2 * min(256, units) * 128 * tco * 4 * 4
     out = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM_EVEN)
     again = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM_EVEN)
     whole = kst.kst_forward_seg(xd, kst.kst_segregate_weights(wd), Cout, n, path=kst.KST_PATH_IGEMM)
@@ -763,12 +768,13 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
     (4, 96, 64, 3, 1, 0),       # n = 1: three empty classes whose zeros must be written
     (1, 2048, 1024, 4, 4, 2),   # Table 3, EB-GAN layer 2: 134 MB of weights
     (1, 256, 128, 16, 4, 2),    # Table 3, DCGAN layer 4 on one sample: 256 positions
-    (1, 256, 128, 32, 4, 2),    # Table 3, EB-GAN layer 5: 1024 positions, small weights
+    (1, 256, 128, 32, 4, 2),    # Table 3, EB-GAN layer 5: 1024 positions -- 64 blocks x 2 MB of weights, just past what the position-block kernel takes: tiles
     (5, 64, 48, 13, 3, 1),      # 5 x 14 x 14 = 980 positions, ragged last block, odd padding factor
     (1, 128, 3, 32, 4, 2),      # Table 3, the generators' output layer on one sample: three of a block's 64 channels
     (1, 64, 5, 16, 3, 1),       # five output channels (weights read one value at a time), odd padding factor
-    (1, 128, 64, 64, 4, 2),     # Table 3, EB-GAN layer 6: 4096 positions, half a megabyte of weights
-    (8, 64, 64, 32, 4, 2),      # a small batch of such a layer: 8192 positions
+    (1, 128, 64, 64, 4, 2),     # Table 3, EB-GAN layer 6: 4096 positions, half a megabyte of weights (tiles of 64 channels)
+    (8, 64, 64, 32, 4, 2),      # a small batch of such a layer: 8192 positions (tiles of 64 channels)
+    (2, 64, 32, 32, 3, 2),      # 2178 positions in 137 blocks, 74 KB of weights: position blocks, ragged last block, half a channel block
 ])
 def test_matrix_cores_on_very_few_positions(B, Cin, Cout, N, n, P):
     """Layers with few quad positions in all (or small weights) take position blocks of 16 on the matrix cores,

@@ -105,7 +105,9 @@ def test_argument_errors_are_statuses_not_crashes():
     assert l.kst_forward_seg(one, one, one, None, 0, 1, 10, 16, 8, 3, 0, 3, None) == 6     # Cin = 10
     assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 18, 8, 3, 0, 3, None) == 6      # Cout = 18
     assert l.kst_forward_seg(one, one, one, None, 0, 1, 8, 16, 8, 3, 0, 3, None) == 4      # fine, but no workspace
-    assert kst.kst_workspace_bytes(1, 8, 16, 8, 3, kst.KST_F32, kst.KST_PATH_IGEMM_EVEN) == 2 * 2 * 128 * 128 * 4 * 4
+    # (two workgroups, two slots each, of one tile's accumulators: 128 positions x 64 channels -- the half-width tile of
+    # layers with up to 64 output channels -- x 4 classes)
+    assert kst.kst_workspace_bytes(1, 8, 16, 8, 3, kst.KST_F32, kst.KST_PATH_IGEMM_EVEN) == 2 * 2 * 128 * 64 * 4 * 4
     # alignment
     odd = ctypes.c_void_p(20)
     assert l.kst_forward(odd, one, one, 1, 1, 1, 4, 3, 0, None) == 7
