@@ -169,10 +169,15 @@ def paper_roofline(layer, fwd_ms, din_ms, dw_ms, metrics):
     many = layer.Cin >= 8 and layer.Cout >= 16
     # Few output channels fed by many input channels (the 128 -> 3 output layer of the generators):
     # 2 * useful MACs / algorithmic bytes = 22 flop/B, past the ridge of the vector ALUs
-    # (157.3 TFLOP/s / 8 TB/s = 19.7 flop/B), and too narrow for the matrix cores (3 of 32 columns):
-    # priced against the fp32 vector peak, the HBM fraction beside it.
+    # (157.3 TFLOP/s / 8 TB/s = 19.7 flop/B), and too narrow for the matrix cores with the output
+    # channels down the MFMA rows (3 of 32): the gradients run on the vector ALUs and are priced
+    # against the fp32 vector peak; the forward pass of a batch runs on the matrix cores with the
+    # taps of all sub-kernels as rows (48 of 48), whose fp32 peak is the same 157.3 TFLOP/s.  The
+    # HBM fraction is given beside it.
     alu = not many and 2.0 * macs / metrics.algorithmic_bytes(layer) > metrics.VALU_PEAK_TFLOPS * 1e12 / (metrics.HBM_PEAK_GBS * 1e9)
     out = {"bound": "mfma" if many else "alu" if alu else "hbm"}
+    if alu:
+        out["forward_bound"] = "mfma"
     for name, ms in (("forward", fwd_ms), ("backward_input", din_ms), ("backward_weight", dw_ms)):
         if many:
             out[name + "_frac"] = round(2.0 * macs / (ms * 1e-3) / 1e12 / metrics.MFMA_PEAK_TFLOPS["f32"], 4)

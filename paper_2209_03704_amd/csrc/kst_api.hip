@@ -44,6 +44,8 @@ kst_path choose_path(const Shape &s, kst_dtype dt)
     // One sample of a generator's output layer (many input channels, three output channels): the
     // position-block kernel splits its reduction over the chip, the direct kernel has four tiles.
     if (dt == KST_F32 && s.Cout < 16 && igemm_f32_small_supported(s)) return KST_PATH_IGEMM;
+    // ... and a batch of them: the taps of all sub-kernels as the rows of one matrix product.
+    if (dt == KST_F32 && tapmajor_f32_supported(s)) return KST_PATH_IGEMM;
     return KST_PATH_DIRECT;
 }
 
@@ -341,6 +343,10 @@ kst_status framed_plan(int B, int Cin, int Cout, int N, int n, int P, kst_dtype 
     }
     st = resolve_path(f->s, dt, path, &f->chosen);
     if (st != KST_OK) return st;
+    // (the tap-major kernel of few-output-channel layers reads the tensor as it lies in memory and is
+    // planned on its edge, which only the in-place view carries)
+    if (path == KST_PATH_AUTO && dt == KST_F32 && f->chosen == KST_PATH_DIRECT && tapmajor_f32_supported(in_place))
+        f->chosen = KST_PATH_IGEMM;
     if (on_matrix_cores(f->chosen) && dt == KST_F32) {
         if (frame_in_kernel) {
             f->s = in_place;

@@ -607,7 +607,7 @@ static bool tiles_supported(const Shape &s)
 
 bool igemm_f32_supported(const Shape &s)
 {
-    return igemm_f32_small_supported(s) || tiles_supported(s);
+    return igemm_f32_small_supported(s) || tapmajor_f32_supported(s) || tiles_supported(s);
 }
 
 bool igemm_f32_takes_row_stride(const Shape &s)
@@ -618,7 +618,7 @@ bool igemm_f32_takes_row_stride(const Shape &s)
 bool igemm_f32_takes_virtual_frame(const Shape &s)
 {
     if (s.frame <= 0 || s.Ns != s.N) return false;
-    return igemm_f32_small_supported(s) || (tiles_supported(s) && pipe_ok(plan(s)));
+    return igemm_f32_small_supported(s) || tapmajor_f32_supported(s) || (tiles_supported(s) && pipe_ok(plan(s)));
 }
 
 // Even shares or whole tiles?  Even shares when the pipelined kernel applies and the model says
@@ -703,6 +703,7 @@ bool igemm_f32_even_shares_possible(const Shape &s)
 size_t igemm_f32_workspace_bytes(const Shape &s, bool force_even)
 {
     if (!force_even && igemm_f32_small_supported(s)) return igemm_f32_small_workspace_bytes(s);
+    if (!force_even && tapmajor_f32_supported(s)) return 0;
     const IgemmParams p = plan(s, force_even);
     const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) return (size_t)2 * sk.k.grid * sk_slot_floats(p.tco) * sizeof(float);
@@ -794,6 +795,7 @@ hipError_t launch_igemm_f32(const float *in, const float *w_seg, float *out, voi
                             bool force_even, hipStream_t stream)
 {
     if (!force_even && igemm_f32_small_supported(s)) return launch_igemm_f32_small(in, w_seg, out, ws, s, stream);
+    if (!force_even && tapmajor_f32_supported(s)) return launch_tapmajor_f32(in, w_seg, out, s, stream);
     const IgemmParams p = plan(s, force_even);
     const SkPlan sk = streamk_plan(s, p, force_even);
     if (sk.use) {

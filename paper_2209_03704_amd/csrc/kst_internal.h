@@ -187,6 +187,10 @@ bool igemm_bf16_pp_supported(const Shape &s);      // row-parity passes: 3 x 3 k
 hipError_t launch_igemm_bf16_pp(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                 hipStream_t stream);
 // Layers with at most 64 quad positions in all (one sample of a small map): position blocks of 16.
+// fp32 layers of many input and at most four output channels, batched: the taps of all sub-kernels as the rows of
+// one matrix product over the input channels (s.frame, s.crop as for the other kernels that take a virtual frame).
+bool tapmajor_f32_supported(const Shape &s);
+hipError_t launch_tapmajor_f32(const float *in, const float *w_seg, float *out, const Shape &s, hipStream_t stream);
 bool igemm_f32_small_supported(const Shape &s);
 size_t igemm_f32_small_workspace_bytes(const Shape &s);
 hipError_t launch_igemm_f32_small(const float *in, const float *w_seg, float *out, void *ws, const Shape &s,

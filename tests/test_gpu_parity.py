@@ -1162,6 +1162,44 @@ def test_seeded_padded_layers_with_bias_and_activation(B, Cin, Cout, N, n, P, ac
 
 
 # ----------------------------------------------------------------------------
+# Few output channels, many input channels, batched: the taps of all sub-kernels as the rows of
+# one matrix product over the input channels (the generators' output layer of Table 3)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,act,bias", [
+    (33, 64, 3, 32, 4, 2, 2, True),     # Table 3's output layer at half the channels: 48 rows, 16 output rows per workgroup, tanh
+    (32, 96, 4, 32, 4, 0, 0, False),    # no padding, 64 rows (all four row blocks), three chunks of channels, M = 60: ragged last block
+    (33, 64, 2, 32, 3, 1, 1, True),     # 3 x 3 kernel, odd padding factor, 18 rows, ReLU
+    (33, 64, 1, 32, 5, 3, 0, True),     # 5 x 5 kernel, one output channel, odd map (M = 65): five row blocks, the last of one row
+    (16, 64, 3, 64, 2, 2, 0, False),    # 2 x 2 kernel on the widest map the kernel takes: 8 output rows per workgroup
+    (128, 64, 3, 8, 4, 2, 2, False),    # small maps: one workgroup per batch item
+    (64, 64, 3, 16, 3, 9, 1, True),     # padding factor beyond the kernel: output rows that only the padding reaches (bias alone)
+    (35, 128, 3, 28, 4, 2, 0, False),   # a map edge that is no multiple of 16: column blocks straddle rows; four chunks
+])
+def test_tap_major_matrix_core_kernel(B, Cin, Cout, N, n, P, act, bias):
+    layer = wl.Layer("tap_major", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
+    x, w = wl.make_tensors(layer, 7300 + 13 * N + 5 * n + P + Cin)
+    gen = torch.Generator().manual_seed(N + n + P + Cout)
+    bvec = torch.randn((Cout,), generator=gen, dtype=torch.float32) if bias else None
+    b64 = None if bvec is None else bvec.numpy().astype(np.float64)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    want = oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, act, P)
+    scale = max(1.0, np.abs(oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, 0, P)).max())
+    # the matrix-core path of such a layer needs no workspace (the tile kernels would: this is how the test knows
+    # which kernel AUTO and the forced path run)
+    assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_IGEMM) == 0
+    assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_AUTO) == 0
+    got = {}
+    for name, code in (("auto", kst.KST_PATH_AUTO), ("igemm", kst.KST_PATH_IGEMM), ("direct", kst.KST_PATH_DIRECT)):
+        o = kst.kst_forward_seg_epilogue(xd, w_seg, Cout, n, None if bvec is None else bvec.to(DEV), act, P, path=code)
+        torch.cuda.synchronize()
+        assert o.shape == want.shape
+        err = np.abs(o.cpu().numpy() - want).max()
+        assert err <= 2e-5 * scale, "%s: abs err %.3e (scale %.3g)" % (name, err, scale)
+        got[name] = o
+    assert torch.equal(got["auto"], got["igemm"])          # AUTO takes the matrix-core kernel for these layers
+
+
+# ----------------------------------------------------------------------------
 # Half-precision operands: the 16-bit kernels with the other multiply
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("B,Cin,Cout,N,n,paths", [
