@@ -34,19 +34,19 @@ constexpr int TM_THREADS = 512;
 constexpr int TM_WAVES = 8;                     // two per SIMD: one's LDS and index work runs under the other's MFMAs
 constexpr int TM_POS = 320;                     // positions per workgroup at most: 20 column blocks of 16
 constexpr int TM_CT = (TM_POS / 16 + TM_WAVES - 1) / TM_WAVES;   // column blocks per wave: 3
-constexpr int TM_XS = 336;                      // floats per row of Y in LDS
 constexpr int TM_KC = 32;                       // input channels per block of the reduction
 
 struct TapMajorParams {
     int B, Cin, Cout, N0, M, n, P;   // N0: edge of the tensor in memory; M: edge of the planes written; P: padding factor
     int YB;                          // output rows per workgroup
+    int XS;                          // floats per row of Y in LDS
     int row_blocks;                  // ceil(M / YB)
     unsigned off[4];                 // element offset of W_p in the segregated weights
     Epilogue epi;
 };
 
-// RT: blocks of 16 rows of Y (n * n * Cout <= 16 RT).
-template <int RT>
+// RT: blocks of 16 rows of Y (n * n * Cout <= 16 RT); NK: the kernel edge n.
+template <int RT, int NK>
 __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *__restrict__ in,
                                                                     const float *__restrict__ w_seg,
                                                                     float *__restrict__ out, TapMajorParams p)
@@ -54,7 +54,7 @@ __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *_
     constexpr int R16 = 16 * RT;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Wl = lds;                                // [Cin][R16]
-    float *Ys = lds + p.Cin * R16;                  // Y: [R16][TM_XS]
+    float *Ys = lds + p.Cin * R16;                  // Y: [R16][p.XS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, kgrp = lane >> 4;
     const int b = blockIdx.x / p.row_blocks, rb = blockIdx.x - b * p.row_blocks;
@@ -172,7 +172,7 @@ __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *_
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) Ys[(16 * r + 4 * kgrp + v) * TM_XS + 16 * tile + col] = acc[t][r][v];
+                for (int v = 0; v < 4; ++v) Ys[(16 * r + 4 * kgrp + v) * p.XS + 16 * tile + col] = acc[t][r][v];
         }
     }
     __syncthreads();
@@ -185,15 +185,24 @@ __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *_
         const int co = rr / yrows, y = y0 + rr - co * yrows;    // uniform over the wave
         const float bias = epi ? epi_bias(p.epi, co) : 0.0f;
         float *orow = out + (((size_t)b * p.Cout + co) * p.M + y) * p.M;
+        // The row's tap rows: u = u0, u0 + 2, ... (2 i = y - P + u), at most (n + 1) / 2 of them.
+        const int u0 = (y - p.P) & 1;
         for (int x = lane; x < p.M; x += 64) {
+            const int v0 = (x - p.P) & 1;
             float sum = 0.0f;
-            for (int u = (y - p.P) & 1; u < p.n; u += 2) {      // 2 i = y - P + u
-                const int i = (y - p.P + u) >> 1;
-                if (i < 0 || i >= p.N0) continue;
-                const float *yr = Ys + (u * p.n * p.Cout + co) * TM_XS + (i - i_lo) * p.N0;
-                for (int v = (x - p.P) & 1; v < p.n; v += 2) {
-                    const int j = (x - p.P + v) >> 1;
-                    if (j >= 0 && j < p.N0) sum += yr[v * p.Cout * TM_XS + j];
+            // All loads of an output are issued together: a tap that does not exist, or whose input position lies
+            // outside the map, reads a valid cell and adds zero.
+#pragma unroll
+            for (int a = 0; a < (NK + 1) / 2; ++a) {
+                const int u = u0 + 2 * a, i = (y - p.P + u) >> 1;
+                const bool u_ok = u < NK && i >= 0 && i < p.N0;          // uniform over the wave
+                const float *yr = Ys + ((u_ok ? u : 0) * NK * p.Cout + co) * p.XS + (u_ok ? i - i_lo : 0) * p.N0;
+#pragma unroll
+                for (int bq = 0; bq < (NK + 1) / 2; ++bq) {
+                    const int v = v0 + 2 * bq, j = (x - p.P + v) >> 1;
+                    const bool ok = u_ok && v < NK && j >= 0 && j < p.N0;
+                    const float val = yr[(v < NK ? v : 0) * p.Cout * p.XS + (ok ? j : 0)];
+                    sum += ok ? val : 0.0f;
                 }
             }
             if (epi) sum = epi_apply(sum, bias, p.epi.act);
@@ -217,7 +226,8 @@ bool tapmajor_plan(const Shape &s, TapMajorParams &p, size_t &lds)
         if (((yb + s.n) / 2) * N0 <= TM_POS) { YB = yb; break; }
     if (YB == 0) return false;
     if ((long long)s.B * ((s.M + YB - 1) / YB) < 128) return false;      // too few workgroups for the chip
-    lds = ((size_t)s.Cin * 16 * rt + (size_t)16 * rt * TM_XS) * sizeof(float);
+    p.XS = ((YB + s.n) / 2) * N0 + 16;
+    lds = ((size_t)s.Cin * 16 * rt + (size_t)16 * rt * p.XS) * sizeof(float);
     if (lds > 150 * 1024) return false;
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.n = s.n;
     p.N0 = N0;
@@ -231,17 +241,33 @@ bool tapmajor_plan(const Shape &s, TapMajorParams &p, size_t &lds)
     return true;
 }
 
-template <int RT>
+template <int RT, int NK>
 hipError_t launch_rt(const float *in, const float *w_seg, float *out, const TapMajorParams &p, size_t lds, hipStream_t stream)
 {
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tapmajor_f32_kernel<RT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tapmajor_f32_kernel<RT, NK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((tapmajor_f32_kernel<RT>), dim3((unsigned)(p.B * p.row_blocks)), dim3(TM_THREADS), lds, stream, in,
+    hipLaunchKernelGGL((tapmajor_f32_kernel<RT, NK>), dim3((unsigned)(p.B * p.row_blocks)), dim3(TM_THREADS), lds, stream, in,
                        w_seg, out, p);
     return hipGetLastError();
+}
+
+// The row blocks a kernel edge can need with one to four output channels: ceil(n * n * Cout / 16) <= 4.
+template <int NK>
+hipError_t launch_n(const float *in, const float *w_seg, float *out, const TapMajorParams &p, size_t lds, hipStream_t stream)
+{
+    const int rt = (NK * NK * p.Cout + 15) / 16;
+    if constexpr (NK * NK <= 16)
+        if (rt == 1) return launch_rt<1, NK>(in, w_seg, out, p, lds, stream);
+    if constexpr (NK * NK <= 32 && NK * NK * 4 > 16)
+        if (rt == 2) return launch_rt<2, NK>(in, w_seg, out, p, lds, stream);
+    if constexpr (NK * NK <= 48 && NK * NK * 4 > 32)
+        if (rt == 3) return launch_rt<3, NK>(in, w_seg, out, p, lds, stream);
+    if constexpr (NK * NK * 4 > 48)
+        if (rt == 4) return launch_rt<4, NK>(in, w_seg, out, p, lds, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -258,11 +284,13 @@ hipError_t launch_tapmajor_f32(const float *in, const float *w_seg, float *out, 
     TapMajorParams p;
     size_t lds;
     if (!tapmajor_plan(s, p, lds)) return hipErrorInvalidValue;
-    switch ((s.n * s.n * s.Cout + 15) / 16) {
-        case 1: return launch_rt<1>(in, w_seg, out, p, lds, stream);
-        case 2: return launch_rt<2>(in, w_seg, out, p, lds, stream);
-        case 3: return launch_rt<3>(in, w_seg, out, p, lds, stream);
-        case 4: return launch_rt<4>(in, w_seg, out, p, lds, stream);
+    switch (s.n) {
+        case 2: return launch_n<2>(in, w_seg, out, p, lds, stream);
+        case 3: return launch_n<3>(in, w_seg, out, p, lds, stream);
+        case 4: return launch_n<4>(in, w_seg, out, p, lds, stream);
+        case 5: return launch_n<5>(in, w_seg, out, p, lds, stream);
+        case 6: return launch_n<6>(in, w_seg, out, p, lds, stream);
+        case 7: return launch_n<7>(in, w_seg, out, p, lds, stream);
         default: return hipErrorInvalidValue;
     }
 }
