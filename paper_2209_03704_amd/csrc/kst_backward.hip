@@ -494,6 +494,7 @@ int weight_lane_slices(const Shape &s)
 // workgroups, at least 1024 positions per slice.
 int weight_slices(const Shape &s)
 {
+    if (backward_weight_image_apply(s)) return backward_weight_image_slices(s);
     if (weight_lanes_apply(s)) return weight_lane_slices(s);
     long long wgs = (long long)s.Cout * s.Cin;                     // workgroups per slice
     if (s.n <= 7) {
@@ -553,6 +554,11 @@ hipError_t launch_backward_weight_generic(const void *in, const float *g, float 
     const unsigned blocks = (unsigned)s.Cout * (unsigned)s.Cin * (unsigned)slices;
     float *dst = slices > 1 ? (float *)ws : dw;
     bool regs = false;
+    if (backward_weight_image_apply(s)) {
+        hipError_t e = launch_backward_weight_image(in, g, dst, s, dt, stream);
+        if (e != hipSuccess || slices == 1) return e;
+        return launch_splitk_reduce((const float *)ws, dw, (size_t)s.Cout * s.Cin * s.n * s.n, slices, stream);
+    }
     if (weight_lanes_apply(s)) {
         if (dt == KST_BF16) launch_weight_lanes<uint16_t>((const uint16_t *)in, g, dst, s, slices, per_slice, stream);
         else if (dt == KST_F16) launch_weight_lanes<half_bits>((const half_bits *)in, g, dst, s, slices, per_slice, stream);

@@ -187,6 +187,12 @@ bool igemm_bf16_pp_supported(const Shape &s);      // row-parity passes: 3 x 3 k
 hipError_t launch_igemm_bf16_pp(const void *in, const void *w_seg, float *out, const Shape &s, bool f16,
                                 hipStream_t stream);
 // Layers with at most 64 quad positions in all (one sample of a small map): position blocks of 16.
+// Kernel gradient of layers with at most four input channels on large maps (rows of `in` and `g` staged through LDS,
+// one partial result per workgroup): whether it applies, how many partial results it writes, the launch.
+bool backward_weight_image_apply(const Shape &s);
+int backward_weight_image_slices(const Shape &s);
+hipError_t launch_backward_weight_image(const void *in, const float *g, float *dst, const Shape &s, kst_dtype dt,
+                                        hipStream_t stream);
 // fp32 layers of many input and at most four output channels, batched: the taps of all sub-kernels as the rows of
 // one matrix product over the input channels (s.frame, s.crop as for the other kernels that take a virtual frame).
 bool tapmajor_f32_supported(const Shape &s);

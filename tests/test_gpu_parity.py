@@ -924,6 +924,32 @@ def test_gradients_of_few_channel_layers(B, Cin, Cout, N, n, P, dtype):
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
 
 
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,dtype", [
+    (6, 3, 1, 224, 3, 2, "f32"),     # Table 1's layer: 28 strips of 8 rows per image, 168 persistent workgroups
+    (6, 3, 1, 224, 5, 2, "f32"),     # ... 5 x 5 kernel: 75 sums per lane
+    (6, 3, 1, 224, 4, 2, "bf16"),    # ... 16-bit input
+    (8, 3, 2, 192, 4, 1, "f32"),     # odd padding factor, two output channels
+    (5, 4, 1, 256, 3, 0, "f32"),     # no padding (margins of two zero columns), a map as wide as the workgroup
+    (3, 1, 1, 320, 7, 2, "f32"),     # 7 x 7 kernel, one channel, a map wider than the workgroup
+    (8, 2, 3, 200, 6, 4, "f32"),     # 6 x 6 kernel, padding factor 4, three output channels
+    (5, 3, 1, 228, 5, 0, "bf16"),    # last strip of four rows; taps beyond every edge of the map
+    (600, 3, 1, 64, 3, 2, "f32"),    # many small images: more strips than workgroups
+])
+def test_kernel_gradient_of_image_layers(B, Cin, Cout, N, n, P, dtype):
+    """Few channels on large maps: rows of `in` and `g` staged through LDS, one partial result per workgroup."""
+    layer = wl.Layer("grad_image", B, Cin, Cout, N, n, dtype, "normal", w_std=0.2, P=P)
+    x, w = wl.make_tensors(layer, 5100 + 3 * N + 7 * n + P)
+    M = kst.kst_out_size_padded(N, n, P)
+    gen = torch.Generator().manual_seed(29 * N + n + P)
+    g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
+    dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    again = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    torch.cuda.synchronize()
+    want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
+    assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
+    assert torch.equal(dw, again)                      # fixed summing order: bit-reproducible
+
+
 @pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
     (3, 24, 16, 10, 5, 2),     # one block of input channels per workgroup
     (2, 72, 40, 6, 3, 1),      # two blocks, the second tile's second block empty; three rows per chunk
