@@ -520,6 +520,7 @@ bool backward_generic_takes_frame(const Shape &s)
 hipError_t launch_backward_input_generic(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
                                          hipStream_t stream)
 {
+    if (backward_input_image_apply(s)) return launch_backward_input_image(g, w, din, s, dt, stream);
     if (dt == KST_BF16   ? launch_input_regs<uint16_t>(g, (const uint16_t *)w, din, s, stream)
         : dt == KST_F16 ? launch_input_regs<half_bits>(g, (const half_bits *)w, din, s, stream)
                         : launch_input_regs<float>(g, (const float *)w, din, s, stream))

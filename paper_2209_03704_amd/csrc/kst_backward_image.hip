@@ -61,10 +61,9 @@ constexpr int BI_XE = 8;                                         // input elemen
 template <int n>
 constexpr int bi_rows_per_wave() { return (2 * 8 + n - 1 + 3) / 4; }
 
-template <int n, int CI, typename T>
-__device__ __forceinline__ void strip_fetch(const ImageGradParams &p, const T *__restrict__ in, const float *__restrict__ g,
-                                            const Strip &st, int co, int tid, float (&gv)[bi_rows_per_wave<n>()][BI_XK],
-                                            float (&xv)[CI][BI_XE])
+template <int n>
+__device__ __forceinline__ void g_rows_fetch(const ImageGradParams &p, const float *__restrict__ g, const Strip &st, int co,
+                                             int tid, float (&gv)[bi_rows_per_wave<n>()][BI_XK])
 {
     const int lane = tid & 63, wave = tid >> 6;
     const float *gp = g + ((size_t)st.b * p.Cout + co) * ((size_t)p.M * p.M);
@@ -79,6 +78,33 @@ __device__ __forceinline__ void strip_fetch(const ImageGradParams &p, const T *_
             gv[k][m] = row_ok && x < p.M ? grow[x] : 0.0f;
         }
     }
+}
+
+template <int n>
+__device__ __forceinline__ void g_rows_land(const ImageGradParams &p, float *gs, const Strip &st, int tid,
+                                            const float (&gv)[bi_rows_per_wave<n>()][BI_XK])
+{
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int k = 0; k < bi_rows_per_wave<n>(); ++k) {
+        const int r = wave + 4 * k;
+        if (r < st.nrows) {
+            float *drow = gs + r * p.GS + p.padc;
+#pragma unroll
+            for (int m = 0; m < BI_XK; ++m) {
+                const int x = lane + 64 * m;
+                if (x < p.M) drow[x] = gv[k][m];
+            }
+        }
+    }
+}
+
+template <int n, int CI, typename T>
+__device__ __forceinline__ void strip_fetch(const ImageGradParams &p, const T *__restrict__ in, const float *__restrict__ g,
+                                            const Strip &st, int co, int tid, float (&gv)[bi_rows_per_wave<n>()][BI_XK],
+                                            float (&xv)[CI][BI_XE])
+{
+    g_rows_fetch<n>(p, g, st, co, tid, gv);
     const int cnt = st.rows * p.N0;
 #pragma unroll
     for (int c = 0; c < CI; ++c) {
@@ -105,19 +131,7 @@ template <int n, int CI, typename T>
 __device__ __forceinline__ void strip_land(const ImageGradParams &p, float *gs, float *xs, const Strip &st, int tid,
                                            const float (&gv)[bi_rows_per_wave<n>()][BI_XK], const float (&xv)[CI][BI_XE])
 {
-    const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-    for (int k = 0; k < bi_rows_per_wave<n>(); ++k) {
-        const int r = wave + 4 * k;
-        if (r < st.nrows) {
-            float *drow = gs + r * p.GS + p.padc;
-#pragma unroll
-            for (int m = 0; m < BI_XK; ++m) {
-                const int x = lane + 64 * m;
-                if (x < p.M) drow[x] = gv[k][m];
-            }
-        }
-    }
+    g_rows_land<n>(p, gs, st, tid, gv);
     const int cnt = st.rows * p.N0;
 #pragma unroll
     for (int c = 0; c < CI; ++c) {
@@ -265,6 +279,71 @@ __global__ void __launch_bounds__(BI_THREADS) backward_weight_image_kernel(const
     }
 }
 
+// Input gradient of the same layers with one output channel:
+//
+//   din[b][ci][i][j] = sum over u, v of g[b][0][2 i + P - u][2 j + P - v] * w[0][ci][u][v]
+//
+// The same strips and the same staged rows of g (the next strip's on their way while this one is
+// multiplied); a lane computes its positions for all input channels from one window of g and
+// stores them along the rows of din.  The kernels of all input channels sit in vector registers,
+// read once from LDS (as scalar values they would not fit beside the bookkeeping).
+template <int n, int CI, typename T>
+__global__ void __launch_bounds__(BI_THREADS) backward_input_image_kernel(const float *__restrict__ g,
+                                                                           const T *__restrict__ w, float *__restrict__ din,
+                                                                           ImageGradParams p)
+{
+    constexpr int NN = n * n;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int grows = 2 * p.RB + n - 1;
+    float *gs = lds;                                // [grows][GS]
+    __shared__ float wl[CI * NN];
+    const int tid = threadIdx.x;
+    const size_t in_plane = (size_t)p.N0 * p.N0;
+
+    for (int e = tid; e < grows * p.GS; e += BI_THREADS) gs[e] = 0.0f;
+    for (int e = tid; e < CI * NN; e += BI_THREADS) wl[e] = to_f32(w[e]);       // w[0][ci][u][v]
+    __syncthreads();
+    float wk[CI][NN];
+#pragma unroll
+    for (int c = 0; c < CI; ++c)
+#pragma unroll
+        for (int t = 0; t < NN; ++t) wk[c][t] = wl[c * NN + t];
+
+    const int i0 = tid / p.N0, j0 = tid - i0 * p.N0;
+    const int strips = p.B * p.strips_per_item;
+    const int w0 = blockIdx.x;
+    float gv[bi_rows_per_wave<n>()][BI_XK];
+    if (w0 < strips) g_rows_fetch<n>(p, g, strip_of<n>(p, w0), 0, tid, gv);
+    for (int strip = w0; strip < strips; strip += p.wgs) {
+        const Strip st = strip_of<n>(p, strip);
+        __syncthreads();                                        // the strip before is done with LDS
+        g_rows_land<n>(p, gs, st, tid, gv);
+        __syncthreads();
+        if (strip + p.wgs < strips) g_rows_fetch<n>(p, g, strip_of<n>(p, strip + p.wgs), 0, tid, gv);
+        float *dp = din + (size_t)st.b * p.Cin * in_plane + (size_t)st.i_lo * p.N0;
+        int ir = i0, j = j0;
+        while (ir < st.rows) {
+            float acc[CI];
+#pragma unroll
+            for (int c = 0; c < CI; ++c) acc[c] = 0.0f;
+            const float *gw = gs + (2 * ir + (n - 1)) * p.GS + p.padc + 2 * j + p.P;
+#pragma unroll
+            for (int u = 0; u < n; ++u)
+#pragma unroll
+                for (int v = 0; v < n; ++v) {
+                    const float gval = gw[-u * p.GS - v];
+#pragma unroll
+                    for (int c = 0; c < CI; ++c) acc[c] = fmaf(gval, wk[c][u * n + v], acc[c]);
+                }
+#pragma unroll
+            for (int c = 0; c < CI; ++c) dp[c * in_plane + (size_t)ir * p.N0 + j] = acc[c];
+            ir += p.step_i;
+            j += p.step_j;
+            if (j >= p.N0) { j -= p.N0; ++ir; }
+        }
+    }
+}
+
 bool image_plan(const Shape &s, ImageGradParams &p, size_t &lds)
 {
     const int N0 = s.N - 2 * s.frame;
@@ -344,6 +423,57 @@ hipError_t launch_t(const T *in, const float *g, float *dst, const ImageGradPara
     }
 }
 
+template <int n, int CI, typename T>
+hipError_t launch_din_ci(const float *g, const T *w, float *din, const ImageGradParams &p, hipStream_t stream)
+{
+    const size_t lds = (size_t)(2 * p.RB + n - 1) * p.GS * sizeof(float);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&backward_input_image_kernel<n, CI, T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((backward_input_image_kernel<n, CI, T>), dim3((unsigned)p.wgs), dim3(BI_THREADS), lds, stream, g, w, din, p);
+    return hipGetLastError();
+}
+
+template <int n, typename T>
+hipError_t launch_din_n(const float *g, const T *w, float *din, const ImageGradParams &p, hipStream_t stream)
+{
+    switch (p.Cin) {
+        case 1: return launch_din_ci<n, 1, T>(g, w, din, p, stream);
+        case 2: return launch_din_ci<n, 2, T>(g, w, din, p, stream);
+        case 3:
+            if constexpr (3 * n * n <= 100) return launch_din_ci<n, 3, T>(g, w, din, p, stream);
+            break;
+        case 4:
+            if constexpr (4 * n * n <= 100) return launch_din_ci<n, 4, T>(g, w, din, p, stream);
+            break;
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t launch_din_t(const float *g, const T *w, float *din, const ImageGradParams &p, hipStream_t stream)
+{
+    switch (p.n) {
+        case 1: return launch_din_n<1, T>(g, w, din, p, stream);
+        case 2: return launch_din_n<2, T>(g, w, din, p, stream);
+        case 3: return launch_din_n<3, T>(g, w, din, p, stream);
+        case 4: return launch_din_n<4, T>(g, w, din, p, stream);
+        case 5: return launch_din_n<5, T>(g, w, din, p, stream);
+        case 6: return launch_din_n<6, T>(g, w, din, p, stream);
+        case 7: return launch_din_n<7, T>(g, w, din, p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// The input gradient's kernel: one output channel, and a map whose rows of g fit a lane's registers.
+bool din_plan(const Shape &s, ImageGradParams &p)
+{
+    size_t lds;
+    return s.Cout == 1 && image_plan(s, p, lds) && p.pre;
+}
+
 }  // namespace
 
 bool backward_weight_image_apply(const Shape &s)
@@ -369,6 +499,22 @@ hipError_t launch_backward_weight_image(const void *in, const float *g, float *d
     if (dt == KST_BF16) return launch_t<uint16_t>((const uint16_t *)in, g, dst, p, lds, stream);
     if (dt == KST_F16) return launch_t<half_bits>((const half_bits *)in, g, dst, p, lds, stream);
     return launch_t<float>((const float *)in, g, dst, p, lds, stream);
+}
+
+bool backward_input_image_apply(const Shape &s)
+{
+    ImageGradParams p;
+    return din_plan(s, p);
+}
+
+hipError_t launch_backward_input_image(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
+                                       hipStream_t stream)
+{
+    ImageGradParams p;
+    if (!din_plan(s, p)) return hipErrorInvalidValue;
+    if (dt == KST_BF16) return launch_din_t<uint16_t>(g, (const uint16_t *)w, din, p, stream);
+    if (dt == KST_F16) return launch_din_t<half_bits>(g, (const half_bits *)w, din, p, stream);
+    return launch_din_t<float>(g, (const float *)w, din, p, stream);
 }
 
 }  // namespace kst

@@ -193,6 +193,10 @@ bool backward_weight_image_apply(const Shape &s);
 int backward_weight_image_slices(const Shape &s);
 hipError_t launch_backward_weight_image(const void *in, const float *g, float *dst, const Shape &s, kst_dtype dt,
                                         hipStream_t stream);
+// ... and the input gradient of such layers with one output channel (din is the unframed tensor).
+bool backward_input_image_apply(const Shape &s);
+hipError_t launch_backward_input_image(const float *g, const void *w, float *din, const Shape &s, kst_dtype dt,
+                                       hipStream_t stream);
 // fp32 layers of many input and at most four output channels, batched: the taps of all sub-kernels as the rows of
 // one matrix product over the input channels (s.frame, s.crop as for the other kernels that take a virtual frame).
 bool tapmajor_f32_supported(const Shape &s);

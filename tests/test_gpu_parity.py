@@ -944,10 +944,14 @@ def test_kernel_gradient_of_image_layers(B, Cin, Cout, N, n, P, dtype):
     g = torch.randn((B, Cout, M, M), generator=gen, dtype=torch.float32)
     dw = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
     again = kst.kst_backward_weight(x.to(DEV), g.to(DEV), n, P)
+    din = kst.kst_backward_input(g.to(DEV), w.to(DEV), N, P)    # (one output channel, maps up to 512 wide: the same strips)
     torch.cuda.synchronize()
     want_dw = oracle.backward_weight(wl.to_f64(x), g.numpy().astype(np.float64), n, P)
     assert rel_err(dw.cpu().numpy(), want_dw) <= GRAD_TOL[dtype]
     assert torch.equal(dw, again)                      # fixed summing order: bit-reproducible
+    want_din = oracle.backward_input(g.numpy().astype(np.float64), wl.to_f64(w), N, P)
+    assert din.shape == want_din.shape
+    assert rel_err(din.cpu().numpy(), want_din) <= GRAD_TOL[dtype]
 
 
 @pytest.mark.parametrize("B,Cin,Cout,N,n,P", [
