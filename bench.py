@@ -423,6 +423,34 @@ def main():
             del xd, outs, ws
             torch.cuda.empty_cache()
 
+    # ---- Table 1's first rows: a whole class of 769 images per launch ----------------------------
+    class_rows = []
+    if args.layers == "all":
+        for layer, paper_s in wl.table1_class_layers():
+            x, w = wl.make_tensors(layer)
+            xd = [x.cuda(), x.cuda().clone()]
+            outs = [torch.empty(layer.out_shape, dtype=torch.float32, device="cuda") for _ in range(2)]
+            w_seg = kst.kst_segregate_weights(w.cuda())
+            need = kst.kst_workspace_bytes_padded(layer.B, layer.Cin, layer.Cout, layer.N, layer.n, layer.P, kst.KST_F32)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            fwd_c = lambda i: kst.kst_forward_seg_padded(xd[i % 2], w_seg, layer.Cout, layer.n, layer.P,
+                                                         out=outs[i % 2], ws=ws)
+            settle(torch, fwd_c, 0.03)
+            ms = time_launches(torch, fwd_c, 20, 3)
+            class_rows.append({
+                "layer": layer.name,
+                "shape": {"images": layer.B, "Cin": layer.Cin, "Cout": layer.Cout, "N": layer.N, "n": layer.n, "P": layer.P,
+                          "M": layer.M},
+                "forward_us": round(ms * 1e3, 1),
+                "us_per_image": round(ms * 1e3 / layer.B, 3),
+                "hbm_frac": round(metrics.algorithmic_bytes(layer) / (ms * 1e-3) / 1e9 / metrics.HBM_PEAK_GBS, 4),
+                "paper_rtx2070_proposed_s": paper_s[1],
+                "paper_rtx2070_conventional_s": paper_s[0],
+                "paper_xeon_proposed_s": paper_s[3],
+            })
+            del xd, outs, ws, x
+            torch.cuda.empty_cache()
+
     # ---- Table 3's generator layers on one input sample, as the paper times them ---------------
     one_sample = []
     if args.layers == "all":
@@ -483,6 +511,7 @@ def main():
         "yardsticks": yard,
         "layers": table,
         "paper_shaped_layers": paper_table,
+        "table1_class_of_769_images": class_rows,
         "table3_one_sample": one_sample,
         "paper_context": "paper reports 3.7x (Xeon CPU) / 3.4x (RTX 2070) average speed-up over zero-insert; ideal 4x",
     }

@@ -75,6 +75,25 @@ PAPER_LAYERS = (
 )
 
 
+# Table 1's first row group: all 769 images of one class of the flower data set (224 x 224 x 3, one
+# output channel, padding factor 2) with 5 x 5, 4 x 4 and 3 x 3 kernels.  Here: 769 synthetic images
+# of that shape in one launch.  Entries: kernel edge -> the total seconds Table 1 prints for the
+# class (conventional on the GPU, proposed on the GPU, conventional on the CPU, proposed on the
+# CPU; RTX 2070 and Xeon), context beside this library's figures, never a target.
+TABLE1_CLASS_IMAGES = 769
+TABLE1_CLASS_SECONDS = {
+    5: (3.6233, 1.018, 61.388, 15.714),
+    4: (2.715, 0.741, 38.978, 10.331),
+    3: (1.7454, 0.4916, 22.491, 6.098),
+}
+
+
+def table1_class_layers():
+    """[(Layer, paper seconds)] for the three kernel sizes of Table 1 on a whole class of images."""
+    return [(Layer("table1_class769_n%d_p2" % n, TABLE1_CLASS_IMAGES, 3, 1, 224, n, "f32", "uniform", P=2), sec)
+            for n, sec in TABLE1_CLASS_SECONDS.items()]
+
+
 # Table 3's transpose-convolution layers of four generator families, one input sample each
 # (the paper times the forward pass of a single sample): 4 x 4 kernels, padding factor 2, so every
 # layer doubles its map (N -> 2N).  Entries: (layer number, N, Cin, Cout).  The second tuple holds
@@ -126,6 +145,9 @@ def layer_by_name(name: str) -> Layer:
         if l.name == name or name in ("cfg%d" % (i + 1), str(i + 1)):
             return l
     for l in PAPER_LAYERS:
+        if l.name == name:
+            return l
+    for l, _ in table1_class_layers():
         if l.name == name:
             return l
     # a generator layer of Table 3 at any batch: table3_<model>_l<k>_<N>to<2N>_b<B>
