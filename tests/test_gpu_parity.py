@@ -1192,6 +1192,36 @@ def test_seeded_padded_layers_with_bias_and_activation(B, Cin, Cout, N, n, P, ac
 
 
 # ----------------------------------------------------------------------------
+# Image layers with kernels of 4 x 4 and more at large batches (the flat-output kernel with three
+# input channels, the multi-channel kernel with two or four)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,act,bias", [
+    (90, 3, 1, 224, 5, 2, 1, True),      # Table 1's layer, 5 x 5 kernel, ReLU
+    (86, 3, 1, 224, 4, 1, 0, False),     # ... 4 x 4 kernel, odd padding factor (the sub-kernels' roles swapped)
+    (1024, 2, 2, 64, 4, 3, 2, True),     # small maps, two output channels, odd padding factor, tanh
+    (300, 4, 1, 120, 5, 0, 0, False),    # no padding: odd map (M = 235), four input channels
+    (70, 2, 3, 250, 7, 4, 0, True),      # 7 x 7 kernel, a map edge that is no multiple of 4, three output channels
+    (260, 2, 2, 128, 6, 5, 1, False),    # 6 x 6 kernel, padding factor 5
+])
+def test_forward_of_image_layers_at_large_batches(B, Cin, Cout, N, n, P, act, bias):
+    layer = wl.Layer("image_batches", B, Cin, Cout, N, n, "f32", "normal", w_std=0.2)
+    x, w = wl.make_tensors(layer, 8100 + 3 * N + 7 * n + P)
+    gen = torch.Generator().manual_seed(N + n + P + Cout)
+    bvec = torch.randn((Cout,), generator=gen, dtype=torch.float32) if bias else None
+    b64 = None if bvec is None else bvec.numpy().astype(np.float64)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    want = oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, act, P)
+    scale = max(1.0, np.abs(oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, 0, P)).max())
+    assert kst.kst_workspace_bytes_padded(B, Cin, Cout, N, n, P, kst.KST_F32, kst.KST_PATH_AUTO) == 0
+    for name, code in (("auto", kst.KST_PATH_AUTO), ("direct", kst.KST_PATH_DIRECT)):
+        o = torch.full(want.shape, float("nan"), dtype=torch.float32, device=DEV)
+        kst.kst_forward_seg_epilogue(xd, w_seg, Cout, n, None if bvec is None else bvec.to(DEV), act, P, out=o, path=code)
+        torch.cuda.synchronize()
+        err = np.abs(o.cpu().numpy() - want).max()                       # (NaN where nothing was written)
+        assert err <= 2e-5 * scale, "%s: abs err %.3e (scale %.3g)" % (name, err, scale)
+
+
+# ----------------------------------------------------------------------------
 # Few output channels, many input channels, batched: the taps of all sub-kernels as the rows of
 # one matrix product over the input channels (the generators' output layer of Table 3)
 # ----------------------------------------------------------------------------
