@@ -1130,6 +1130,69 @@ def test_forward_seeded_shapes_on_every_path_that_takes_them(B, Cin, Cout, N, n,
     assert "auto" in ran and "direct" in ran
 
 
+def _seeded_narrow_and_tap_major_shapes(count, seed):
+    """fp32 layers aimed at the matrix-core kernels' tile choices: 8 to 64 output channels (tiles of 64
+    channels), few wide tiles (a halved split), batches of layers with one to four output channels and
+    32 k input channels (taps as the rows of the product), weights around the limit between position
+    blocks and tiles -- every padding factor form, random bias and activation."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        kind = int(rng.integers(0, 3))
+        n = int(rng.integers(2, 6))
+        P = int(rng.integers(0, 5))
+        if kind == 0:                                   # tiles of 64 output channels
+            N = int(rng.choice([4, 8, 12, 16, 20, 32]))
+            Cin = int(rng.choice([8, 16, 32, 64, 128]))
+            Cout = int(rng.choice([8, 12, 16, 32, 48, 64]))
+            B = int(rng.integers(1, 40))
+        elif kind == 1:                                 # more than 64 output channels, few tiles
+            N = int(rng.choice([4, 8, 16]))
+            Cin = int(rng.choice([64, 128, 256]))
+            Cout = int(rng.choice([128, 192, 256]))
+            B = int(rng.integers(1, 24))
+        else:                                           # taps as rows: at least 128 workgroups
+            N = int(rng.choice([8, 16, 32, 48]))
+            Cin = int(rng.choice([64, 96, 128]))
+            Cout = int(rng.integers(1, 5))
+            if n * n * Cout > 64:
+                continue
+            M = 2 * N + 2 * P - n
+            B = int(rng.integers(1, 3)) * (128 // max(1, (M + 15) // 16) + 1)
+        if 2 * N - 1 + 2 * P < n:
+            continue
+        if B * Cin * Cout * (2 * N + 2 * P) ** 2 * n * n > 6e9:
+            continue
+        shapes.append((B, Cin, Cout, N, n, P, int(rng.integers(0, 3)), bool(rng.integers(0, 2))))
+    return shapes
+
+
+@pytest.mark.parametrize("B,Cin,Cout,N,n,P,act,bias", _seeded_narrow_and_tap_major_shapes(36, 20261129))
+def test_seeded_matrix_core_tile_choices_with_bias_and_activation(B, Cin, Cout, N, n, P, act, bias):
+    layer = wl.Layer("tiles_seeded", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
+    x, w = wl.make_tensors(layer, 9700 + 31 * N + 7 * n + P + Cin + Cout)
+    gen = torch.Generator().manual_seed(N + n + P + Cout)
+    bvec = torch.randn((Cout,), generator=gen, dtype=torch.float32) if bias else None
+    b64 = None if bvec is None else bvec.numpy().astype(np.float64)
+    xd, w_seg = x.to(DEV), kst.kst_segregate_weights(w.to(DEV))
+    want = oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, act, P)
+    scale = max(1.0, np.abs(oracle.forward_epilogue(wl.to_f64(x), wl.to_f64(w), b64, 0, P)).max())
+    ran = []
+    for name, code in (("auto", kst.KST_PATH_AUTO), ("direct", kst.KST_PATH_DIRECT), ("igemm", kst.KST_PATH_IGEMM),
+                       ("even", kst.KST_PATH_IGEMM_EVEN)):
+        o = torch.full(want.shape, float("nan"), dtype=torch.float32, device=DEV)
+        try:
+            kst.kst_forward_seg_epilogue(xd, w_seg, Cout, n, None if bvec is None else bvec.to(DEV), act, P, out=o, path=code)
+        except kst.KstError:
+            assert name in ("igemm", "even"), name
+            continue
+        torch.cuda.synchronize()
+        ran.append(name)
+        err = np.abs(o.cpu().numpy() - want).max()                       # (NaN where nothing was written)
+        assert err <= 2e-5 * scale, "%s: abs err %.3e (scale %.3g)" % (name, err, scale)
+    assert "auto" in ran and "direct" in ran and "igemm" in ran
+
+
 def _seeded_frame_and_epilogue_shapes(count, seed):
     """fp32 layers aimed at the kernels that supply the zero frame themselves and shift their
     stores for odd padding factors -- the flat-output kernel (one or three input channels, maps
