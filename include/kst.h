@@ -60,7 +60,11 @@ typedef enum {
 } kst_status;
 
 /* Which kernel family kst_forward_seg uses.  AUTO picks DIRECT for small
- * channel counts (bandwidth-bound) and IGEMM (matrix cores) otherwise.
+ * channel counts (bandwidth-bound) and IGEMM (matrix cores) otherwise; of
+ * the layers with fewer than 16 output channels it also gives IGEMM those
+ * with many input channels that the matrix cores can take with the
+ * sub-kernels' taps as rows (a batch of them) or with the reduction split
+ * over the chip (one sample).
  * IGEMM_EVEN (for tests and tuning) is IGEMM with one of its launch forms
  * forced: the (tile, channel chunk) list of the layer cut into equal ranges
  * over persistent workgroups, which IGEMM itself takes only where its cost

@@ -156,7 +156,7 @@ hipError_t scratch_alloc(void **ptr, size_t bytes, hipStream_t stream)
 
 extern "C" {
 
-int kst_version(void) { return 102; }
+int kst_version(void) { return 103; }
 
 const char *kst_status_string(int status)
 {
