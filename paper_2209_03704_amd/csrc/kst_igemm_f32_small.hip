@@ -33,6 +33,7 @@ struct SmallParams {
     int B, Cin, Cout, N0, q, E, EE, Mtot;
     int M, crop;                      // edge of the planes that are written; 1: quad members land one row / column earlier
     int pos_blocks, co_blocks, splits, chunks_per_split, chunks;
+    int waves;                        // waves per workgroup (1 or 4): a workgroup's range of chunks is shared out among them
     unsigned off[4];                  // element offset of W_p in the segregated weights
     size_t out_elems;
     Epilogue epi;
@@ -40,13 +41,17 @@ struct SmallParams {
 
 // V4: Cout is a multiple of 4 and the weights are read as 16-byte groups; otherwise (the 128 -> 3
 // output layer of a generator) one value at a time, rows past Cout reading the last channel again.
-template <int n, bool V4>
-__global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__restrict__ in, const float *__restrict__ w_seg,
+// WV: waves per workgroup.  With four, each takes a quarter of the workgroup's chunks and their sums are
+// added through LDS in wave order before anything is stored: a quarter of the partial outputs for
+// the same number of waves pulling weights (one sample of a 1024 -> 512 layer writes 16.7 MB of
+// partial outputs beside its 33.5 MB of weights with one wave per workgroup).
+template <int n, bool V4, int WV>
+__global__ void __launch_bounds__(64 * WV) igemm_f32_small_kernel(const float *__restrict__ in, const float *__restrict__ w_seg,
                                                                float *__restrict__ dst, SmallParams p)
 {
     constexpr int fl = n / 2;
     constexpr int NN = n * n;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, k = lane >> 4;          // column / row-in-block of the operands; channel of the chunk
     unsigned id = blockIdx.x;
     const int co_block = (int)(id % (unsigned)p.co_blocks);
@@ -86,8 +91,11 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
 #pragma unroll
     for (int j = 0; j < 4; ++j) w_cols[j] = (unsigned)min(co0 + 4 * m + j, p.Cout - 1);
 
-    const int c_begin = split * p.chunks_per_split;
-    const int c_end = min(p.chunks, c_begin + p.chunks_per_split);
+    const int wg_begin = split * p.chunks_per_split;
+    const int wg_end = min(p.chunks, wg_begin + p.chunks_per_split);
+    const int per_wave = (wg_end - wg_begin + WV - 1) / WV;
+    const int c_begin = wg_begin + wave * per_wave;
+    const int c_end = min(wg_end, c_begin + per_wave);
 
     floatx4 acc[4][4];                               // [class][row block]
 #pragma unroll
@@ -159,16 +167,41 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
     // leave one channel per instruction with the lanes running along the output rows: lane
     // (r, position, s) writes member (r, s) of its quad, so neighbouring lanes write neighbouring
     // columns.
-    __shared__ float img[SM_TCO * SM_POS * 4];
+    __shared__ float buf[(WV > 1 ? (WV - 1) * 64 : 64) * 64];    // the other waves' sums [wave - 1][register][lane]; then the image (64 x 64 floats)
+    float *img = buf;                                            // [SM_TCO][SM_POS][4]
+    if constexpr (WV > 1) {
+        if (wave > 0) {
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int col = 4 * (4 * k + v) + blk;               // channel of the wave's 64
-            *reinterpret_cast<float4 *>(&img[(col * SM_POS + m) * 4]) =
-                make_float4(acc[0][blk][v], acc[1][blk][v], acc[2][blk][v], acc[3][blk][v]);
+                for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) buf[((wave - 1) * 64 + (c * 4 + blk) * 4 + v) * 64 + lane] = acc[c][blk][v];
         }
-    __syncthreads();                                             // (one wave: orders the LDS writes before the reads)
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 1; w < WV; ++w)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[c][blk][v] += buf[((w - 1) * 64 + (c * 4 + blk) * 4 + v) * 64 + lane];
+        }
+        __syncthreads();                                         // every lane of wave 0 has read the sums: the image may overwrite them
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int col = 4 * (4 * k + v) + blk;           // channel of the workgroup's 64
+                *reinterpret_cast<float4 *>(&img[(col * SM_POS + m) * 4]) =
+                    make_float4(acc[0][blk][v], acc[1][blk][v], acc[2][blk][v], acc[3][blk][v]);
+            }
+    }
+    __syncthreads();
     const int r2 = lane >> 5, m2 = (lane >> 1) & 15, s2 = lane & 1;
     const int pos2 = pos_block * SM_POS + m2;
     if (pos2 >= p.Mtot) return;
@@ -182,7 +215,7 @@ __global__ void __launch_bounds__(64) igemm_f32_small_kernel(const float *__rest
     float *o = dst + (size_t)split * p.out_elems + ((size_t)mb2 * p.Cout + co0) * p.M * p.M + (size_t)y * p.M + x;
     const size_t plane = (size_t)p.M * p.M;
     const int ncol = min(SM_TCO, p.Cout - co0);
-    for (int col = 0; col < ncol; ++col) {
+    for (int col = wave; col < ncol; col += WV) {                // the waves share out the channels
         float val = img[(col * SM_POS + m2) * 4 + 2 * r2 + s2];
         if (epi) val = epi_apply(val, epi_bias(p.epi, co0 + col), p.epi.act);
         o[(size_t)col * plane] = val;
@@ -218,9 +251,17 @@ bool small_plan(const Shape &s, SmallParams &p)
     p.co_blocks = (s.Cout + SM_TCO - 1) / SM_TCO;
     p.chunks = s.Cin / SM_KC;
     // About two waves per SIMD over the chip, but at least four chunks per workgroup (so that the
-    // partial outputs stay well below the weights in bytes).
-    const int want = (2048 + p.pos_blocks * p.co_blocks - 1) / (p.pos_blocks * p.co_blocks);
-    int splits = p.chunks / 2 < want ? p.chunks / 2 : want;
+    // partial outputs stay well below the weights in bytes); with a long reduction (64 chunks and
+    // more) four waves per workgroup, two chunks each at least -- except where a single position
+    // block would then leave the weights to fewer than 512 workgroups (measured on one sample of
+    // Table 3's layers: 512 -> 256 on 4 x 4 positions 13.1 us with one wave, 15.3 with four;
+    // 1024 -> 512: 20.2 and 21.0; 2048 -> 1024: 46.4 and 42.1; with 64 and 256 positions four waves
+    // win throughout, 19.9 -> 16.1, 24.6 -> 14.3, 37.8 -> 31.2 us).
+    p.waves = p.chunks >= 64 && (p.pos_blocks > 1 || p.co_blocks * (p.chunks / 8) >= 512) ? 4 : 1;
+    const int wgs = 2048 / p.waves;
+    const int want = (wgs + p.pos_blocks * p.co_blocks - 1) / (p.pos_blocks * p.co_blocks);
+    const int most = p.chunks / (2 * p.waves);
+    int splits = most < want ? most : want;
     if (splits < 1) splits = 1;
     p.chunks_per_split = (p.chunks + splits - 1) / splits;
     p.splits = (p.chunks + p.chunks_per_split - 1) / p.chunks_per_split;
@@ -234,10 +275,18 @@ template <int n>
 hipError_t launch_small_n(const float *in, const float *w_seg, float *dst, const SmallParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)(p.pos_blocks * p.co_blocks * p.splits);
-    if ((p.Cout & 3) == 0)
-        hipLaunchKernelGGL((igemm_f32_small_kernel<n, true>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
-    else
-        hipLaunchKernelGGL((igemm_f32_small_kernel<n, false>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+    const bool v4 = (p.Cout & 3) == 0;
+    if (p.waves == 4) {
+        if (v4)
+            hipLaunchKernelGGL((igemm_f32_small_kernel<n, true, 4>), dim3(blocks), dim3(256), 0, stream, in, w_seg, dst, p);
+        else
+            hipLaunchKernelGGL((igemm_f32_small_kernel<n, false, 4>), dim3(blocks), dim3(256), 0, stream, in, w_seg, dst, p);
+    } else {
+        if (v4)
+            hipLaunchKernelGGL((igemm_f32_small_kernel<n, true, 1>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+        else
+            hipLaunchKernelGGL((igemm_f32_small_kernel<n, false, 1>), dim3(blocks), dim3(64), 0, stream, in, w_seg, dst, p);
+    }
     return hipGetLastError();
 }
 

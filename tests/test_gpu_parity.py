@@ -775,6 +775,9 @@ def test_odd_padding_factor_on_the_matrix_cores(B, Cin, Cout, N, n, P, dtype, pa
     (1, 128, 64, 64, 4, 2),     # Table 3, EB-GAN layer 6: 4096 positions, half a megabyte of weights (tiles of 64 channels)
     (8, 64, 64, 32, 4, 2),      # a small batch of such a layer: 8192 positions (tiles of 64 channels)
     (2, 64, 32, 32, 3, 2),      # 2178 positions in 137 blocks, 74 KB of weights: position blocks, ragged last block, half a channel block
+    (2, 256, 80, 6, 3, 3),      # four waves per workgroup (64 chunks): ragged channel block, ragged position block, odd padding factor
+    (1, 384, 5, 8, 4, 1),       # ... with five output channels (weights read one value at a time), 96 chunks in three splits
+    (1, 1100, 64, 8, 4, 2),     # ... a chunk count (275: nine per workgroup) that four waves cannot share evenly
 ])
 def test_matrix_cores_on_very_few_positions(B, Cin, Cout, N, n, P):
     """Layers with few quad positions in all (or small weights) take position blocks of 16 on the matrix cores,
