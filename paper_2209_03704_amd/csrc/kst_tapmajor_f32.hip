@@ -17,11 +17,11 @@
 //
 // A workgroup (8 waves) owns YB output rows of all channels of one batch item.  The input rows
 // that reach them (YB / 2 + a halo of (n - 1) / 2) times the map's width are at most 320
-// positions = 20 column blocks of 16, two or three per wave; the reduction runs in chunks of 32 channels
-// staged through LDS (16-byte loads in flight in registers during the chunk before), the
-// weights, regrouped as rows of Y, stay in LDS for the whole tile, and a wave's A operand is
-// shared by its column blocks.  The Y tile then goes to LDS, and the threads gather every
-// output's taps from it and store whole output rows.
+// positions = 20 column blocks of 16, two or three per wave.  The weights, regrouped as rows of
+// Y, stay in LDS for the whole tile, and a wave's A operand is shared by its column blocks; the
+// B operands come straight from memory, 32 channels at a time, the next 32 on their way while
+// these are multiplied, with no barrier inside the reduction.  The Y tile then goes to LDS, and
+// the waves gather every output's taps from it and store whole output rows.
 #include "kst_internal.h"
 
 namespace kst {
