@@ -16,6 +16,9 @@
 // channel in registers, reads an input value once for n * n products and a g value once for Cin;
 // at the end the sums are added across the lanes by wave shuffles, across the waves through LDS,
 // and every workgroup writes one partial result that the summing pass adds in a fixed order.
+// Where a strip's loads fit a lane's registers (maps up to 512 wide) the next strip is fetched
+// while this one is multiplied; wider maps stage strip after strip.  The input gradient of
+// such layers with one output channel (second kernel below) runs on the same strips of g.
 #include "kst_internal.h"
 
 namespace kst {

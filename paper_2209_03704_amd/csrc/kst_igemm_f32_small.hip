@@ -5,8 +5,9 @@
 // The kernel for ordinary layers multiplies tiles of 128 positions: with 16 positions seven
 // eighths of its matrix-core work and of its partial sums are padding.  Here the position block
 // is the 16 columns of v_mfma_f32_16x16x4f32, so nothing is padded beyond the last block:
-//   * one wave = one workgroup owns 16 positions x 64 output channels (four MFMA row blocks) x the
-//     four parity classes: 64 accumulator registers;
+//   * a wave owns 16 positions x 64 output channels (four MFMA row blocks) x the four parity
+//     classes: 64 accumulator registers; a workgroup is one such wave, or four that share out
+//     the workgroup's part of a long reduction and add their sums through LDS before storing;
 //   * the reduction over input channels is cut into `splits` ranges, one workgroup each, so that
 //     the layer's weights -- each read exactly once, straight from memory into the A operands, 16
 //     bytes per lane and 256 consecutive bytes per 16 lanes: a lane's four values are its row of
