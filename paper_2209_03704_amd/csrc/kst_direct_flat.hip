@@ -277,7 +277,7 @@ __global__ void __launch_bounds__(F_THREADS) direct_flat_kernel(const float *__r
                                                                   const float *__restrict__ w_seg,
                                                                   float *__restrict__ out, FlatParams p)
 {
-    constexpr int Ta0 = (n + 1) / 2, Ta1 = n / 2;
+    constexpr int Ta0 = (n + 1) / 2;
     extern __shared__ __attribute__((aligned(16))) float lds[];   // 2 x [CI][max_rows][xs_stride]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
