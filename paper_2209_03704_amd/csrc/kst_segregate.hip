@@ -88,16 +88,25 @@ __global__ void __launch_bounds__(256) segregate_tiled_f32_kernel(const float *_
         }
     }
     __syncthreads();
+    // A wave writes run element r = wave, wave + 4, ... for its 64 output channels (lane = channel).
+    // The element's (ci, u, v) follow from those of the one before by a step of four with carries: one
+    // division per wave, none per element (u = uv / n by a multiplication, exact for every uv < n * n with n <= 42).
     const unsigned nn = (unsigned)g.n * g.n;
-    for (int idx = tid; idx < S_CO * S_RUN; idx += 256) {
-        const unsigned r = idx / S_CO, co_l = idx % S_CO;
-        const unsigned e = r0 + r;                                    // element (ci, u, v) of a channel's kernels
-        if (co0 + co_l >= (unsigned)g.Cout || e >= per_co) continue;
-        const unsigned ci = e / nn, uv = e - ci * nn;
-        const unsigned u = uv / g.n, v = uv - u * g.n;
-        const int p = (int)((u & 1u) * 2u + (v & 1u));
-        const unsigned t = (u >> 1) * g.Tb[p] + (v >> 1);
-        w_seg[g.off[p] + ((size_t)ci * g.T[p] + t) * g.Cout + co0 + co_l] = tile[co_l][r];
+    const unsigned co_l = (unsigned)tid & 63u;
+    unsigned r = (unsigned)tid >> 6;
+    unsigned e = r0 + r;
+    unsigned ci = e / nn, uv = e - ci * nn;
+    const unsigned magic = (65536u + (unsigned)g.n - 1u) / (unsigned)g.n;
+    const bool co_ok = co0 + co_l < (unsigned)g.Cout;
+    for (; r < (unsigned)S_RUN; r += 4, e += 4) {
+        if (e < per_co && co_ok) {
+            const unsigned u = (uv * magic) >> 16, v = uv - u * g.n;
+            const int p = (int)((u & 1u) * 2u + (v & 1u));
+            const unsigned t = (u >> 1) * g.Tb[p] + (v >> 1);
+            w_seg[g.off[p] + ((size_t)ci * g.T[p] + t) * g.Cout + co0 + co_l] = tile[co_l][r];
+        }
+        uv += 4;
+        while (uv >= nn) { uv -= nn; ++ci; }
     }
 }
 
@@ -117,7 +126,7 @@ hipError_t launch_segregate(const void *w, void *w_seg, int Cin, int Cout, int n
     }
     g.off[4] = (unsigned)seg_elems(Cin, Cout, n, dt);
     const unsigned blocks = (g.off[4] + 255u) / 256u;
-    if (dt == KST_F32 && Cout >= 32 && (size_t)Cin * n * n >= 64) {
+    if (dt == KST_F32 && Cout >= 32 && n <= 32 && (size_t)Cin * n * n >= 64) {     // (n <= 32: the tiled kernel's division by n)
         const size_t runs = ((size_t)Cin * n * n + S_RUN - 1) / S_RUN;
         const size_t tiles = runs * ((Cout + S_CO - 1) / S_CO);
         if (tiles < 0x7fffffffu) {
