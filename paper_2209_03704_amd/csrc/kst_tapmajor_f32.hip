@@ -97,7 +97,7 @@ __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *_
 
     // ---- the weights as rows of Y: row (u n + v) Cout + co, zero beyond R ------------------
     // Where row rho of channel ci lies in the segregated buffer: first[rho] + ci * stride[rho], worked
-    // out once per row (the divisions), then eight values per lane in flight.
+    // out once per row (the divisions), then sixteen values per lane in flight.
     {
         int *first = reinterpret_cast<int *>(Ys);   // [R16], then stride[R16]: the place of Y is still free
         int *stride = first + R16;
@@ -117,17 +117,17 @@ __global__ void __launch_bounds__(TM_THREADS) tapmajor_f32_kernel(const float *_
         }
         __syncthreads();
         const int W = p.Cin * R16;
-        for (int e0 = 0; e0 < W; e0 += 8 * TM_THREADS) {
-            float val[8];
+        for (int e0 = 0; e0 < W; e0 += 16 * TM_THREADS) {
+            float val[16];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 16; ++k) {
                 const int e = e0 + k * TM_THREADS + tid;
                 const int ci = e / R16, rho = e - ci * R16;     // (a constant divisor)
                 const int fo = e < W ? first[rho] : -1;
                 val[k] = fo >= 0 ? w_seg[fo + ci * stride[rho]] : 0.0f;
             }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 16; ++k) {
                 const int e = e0 + k * TM_THREADS + tid;
                 if (e < W) Wl[e] = val[k];
             }
