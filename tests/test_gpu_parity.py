@@ -1300,6 +1300,7 @@ def test_forward_of_image_layers_at_large_batches(B, Cin, Cout, N, n, P, act, bi
     (128, 64, 3, 8, 4, 2, 2, False),    # small maps: one workgroup per batch item
     (64, 64, 3, 16, 3, 9, 1, True),     # padding factor beyond the kernel: output rows that only the padding reaches (bias alone)
     (35, 128, 3, 28, 4, 2, 0, False),   # a map edge that is no multiple of 16: column blocks straddle rows; four chunks
+    (32, 256, 4, 32, 4, 2, 1, True),    # the largest the kernel takes: 64 rows, 256 input channels (150 KB of LDS)
 ])
 def test_tap_major_matrix_core_kernel(B, Cin, Cout, N, n, P, act, bias):
     layer = wl.Layer("tap_major", B, Cin, Cout, N, n, "f32", "relu_normal", w_std=0.1)
