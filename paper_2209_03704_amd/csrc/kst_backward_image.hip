@@ -32,7 +32,8 @@ struct ImageGradParams {
     int RB;                 // input rows per strip
     int strips_per_item;    // ceil(N0 / RB)
     int wgs;                // workgroups per output channel (= partial results)
-    int GS;                 // floats per staged g row: the map's M between two margins of padc
+    int GS;                 // floats per staged g row: the map's M between two margins of padc, rounded up to even;
+                            // a row is stored as its even columns followed by its odd columns (see g_cell)
     int padc;               // max(0, n - 1 - P)
     int step_i, step_j;     // a lane's step through the positions: threads = step_i * N0 + step_j
     int pre;                // 1: a strip's loads fit a lane's registers (the prefetching variant)
@@ -64,6 +65,12 @@ constexpr int BI_XE = 8;                                         // input elemen
 template <int n>
 constexpr int bi_rows_per_wave() { return (2 * 8 + n - 1 + 3) / 4; }
 
+// Where column c (margin included) of a staged g row lies: the even columns first, then the odd
+// ones.  A lane reads column c0 - v + 2 j for its position j, so with the two parities apart
+// neighbouring lanes read neighbouring cells (in one interleaved row they would be two cells
+// apart and half of the LDS banks would serve the whole wave).
+__device__ __forceinline__ int g_cell(const ImageGradParams &p, int c) { return (c & 1) * (p.GS >> 1) + (c >> 1); }
+
 template <int n>
 __device__ __forceinline__ void g_rows_fetch(const ImageGradParams &p, const float *__restrict__ g, const Strip &st, int co,
                                              int tid, float (&gv)[bi_rows_per_wave<n>()][BI_XK])
@@ -92,11 +99,11 @@ __device__ __forceinline__ void g_rows_land(const ImageGradParams &p, float *gs,
     for (int k = 0; k < bi_rows_per_wave<n>(); ++k) {
         const int r = wave + 4 * k;
         if (r < st.nrows) {
-            float *drow = gs + r * p.GS + p.padc;
+            float *drow = gs + r * p.GS;
 #pragma unroll
             for (int m = 0; m < BI_XK; ++m) {
                 const int x = lane + 64 * m;
-                if (x < p.M) drow[x] = gv[k][m];
+                if (x < p.M) drow[g_cell(p, p.padc + x)] = gv[k][m];
             }
         }
     }
@@ -184,6 +191,10 @@ __global__ void __launch_bounds__(BI_THREADS) backward_weight_image_kernel(const
 
     // This lane's first position of a strip.
     const int i0 = tid / p.N0, j0 = tid - i0 * p.N0;
+    // Column c0 - v + 2 j of a g row, for tap column v: cell po[v] + j.
+    int po[n];
+#pragma unroll
+    for (int v = 0; v < n; ++v) po[v] = g_cell(p, p.padc + p.P - v);
 
     const int strips = p.B * p.strips_per_item;
     float gv[bi_rows_per_wave<n>()][BI_XK], xv[CI][BI_XE];       // PRE: the strip on its way
@@ -205,7 +216,7 @@ __global__ void __launch_bounds__(BI_THREADS) backward_weight_image_kernel(const
                 const int y = y_lo + r;
                 const bool row_ok = y >= 0 && y < p.M;              // uniform over the wave
                 const float *grow = gp + (size_t)(row_ok ? y : 0) * p.M;
-                float *drow = gs + r * p.GS + p.padc;
+                float *drow = gs + r * p.GS;
                 for (int x0 = lane; x0 < p.M; x0 += 256) {
                     float v[4];
 #pragma unroll
@@ -216,7 +227,7 @@ __global__ void __launch_bounds__(BI_THREADS) backward_weight_image_kernel(const
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const int x = x0 + 64 * k;
-                        if (x < p.M) drow[x] = v[k];
+                        if (x < p.M) drow[g_cell(p, p.padc + x)] = v[k];
                     }
                 }
             }
@@ -249,12 +260,12 @@ __global__ void __launch_bounds__(BI_THREADS) backward_weight_image_kernel(const
             float xin[CI];
 #pragma unroll
             for (int c = 0; c < CI; ++c) xin[c] = xs[c * p.RB * p.N0 + ir * p.N0 + j];
-            const float *gw = gs + (2 * ir + (n - 1)) * p.GS + p.padc + 2 * j + p.P;
+            const float *gw = gs + (2 * ir + (n - 1)) * p.GS + j;
 #pragma unroll
             for (int u = 0; u < n; ++u)
 #pragma unroll
                 for (int v = 0; v < n; ++v) {
-                    const float gval = gw[-u * p.GS - v];
+                    const float gval = gw[-u * p.GS + po[v]];
 #pragma unroll
                     for (int c = 0; c < CI; ++c) acc[c][u * n + v] = fmaf(xin[c], gval, acc[c][u * n + v]);
                 }
@@ -313,6 +324,10 @@ __global__ void __launch_bounds__(BI_THREADS) backward_input_image_kernel(const 
         for (int t = 0; t < NN; ++t) wk[c][t] = wl[c * NN + t];
 
     const int i0 = tid / p.N0, j0 = tid - i0 * p.N0;
+    // Column c0 - v + 2 j of a g row, for tap column v: cell po[v] + j.
+    int po[n];
+#pragma unroll
+    for (int v = 0; v < n; ++v) po[v] = g_cell(p, p.padc + p.P - v);
     const int strips = p.B * p.strips_per_item;
     const int w0 = blockIdx.x;
     float gv[bi_rows_per_wave<n>()][BI_XK];
@@ -329,12 +344,12 @@ __global__ void __launch_bounds__(BI_THREADS) backward_input_image_kernel(const 
             float acc[CI];
 #pragma unroll
             for (int c = 0; c < CI; ++c) acc[c] = 0.0f;
-            const float *gw = gs + (2 * ir + (n - 1)) * p.GS + p.padc + 2 * j + p.P;
+            const float *gw = gs + (2 * ir + (n - 1)) * p.GS + j;
 #pragma unroll
             for (int u = 0; u < n; ++u)
 #pragma unroll
                 for (int v = 0; v < n; ++v) {
-                    const float gval = gw[-u * p.GS - v];
+                    const float gval = gw[-u * p.GS + po[v]];
 #pragma unroll
                     for (int c = 0; c < CI; ++c) acc[c] = fmaf(gval, wk[c][u * n + v], acc[c]);
                 }
@@ -356,7 +371,7 @@ bool image_plan(const Shape &s, ImageGradParams &p, size_t &lds)
     p.B = s.B; p.Cin = s.Cin; p.Cout = s.Cout; p.N0 = N0; p.M = s.M; p.n = s.n;
     p.P = 2 * s.frame;
     p.padc = s.n - 1 - p.P > 0 ? s.n - 1 - p.P : 0;
-    p.GS = p.M + 2 * p.padc;
+    p.GS = (p.M + 2 * p.padc + 1) & ~1;
     p.RB = 0;
     // (Shorter strips for small batches, so that every workgroup has a second strip to fetch while it
     // multiplies, were measured and change nothing: 16 images 21 and 35 us either way.)
